@@ -1,0 +1,249 @@
+/*
+ * gmidrl.h -- C ABI of the MI355X-native PPO agent/trainer hot path of GMI-DRL.
+ *
+ * The paper's unit of execution is the GMI ("GPU multiplexing instance", Section 2): a
+ * resource-adjustable sub-GPU that hosts one or more of the three DRL roles of Section 3
+ * (environment simulator, agent, trainer) and talks to other GMIs by send/recv (Listing 1).
+ * Here a GMI is a HIP stream restricted to a set of compute units of one gfx950 device; all
+ * instances of a process share one address space, so "sending" experience or parameters to
+ * another instance is an ordering (event) plus, optionally, a device-to-device copy.
+ *
+ * Conventions
+ *  - Every function returns 0 (GMI_OK) or a negative gmi_status.  gmi_last_error() returns a
+ *    thread-local, human-readable message for the last failure on the calling thread.
+ *  - "dev" pointers are device memory owned by the caller (e.g. PyTorch tensors); they must stay
+ *    valid until the work that uses them has completed.  "host" pointers are ordinary host memory
+ *    read during the call.  The library allocates device memory only inside *_bind / gmi_create
+ *    and frees it in the matching *_destroy; no compute call allocates.
+ *  - Every compute call is asynchronous on its instance's stream.  Ordering between instances is
+ *    established only by gmi_transfer(); gmi_sync() blocks the host.
+ *  - All randomness is a pure function of (seed, stream id, step, env index, element) through
+ *    Philox4x32-10: counter = (env index, step, stream id, block), key = (seed low, seed high).
+ *    Stream ids: 0 action noise, 1 environment noise, 2 done draw, 3 reset state, 4 shuffle.
+ *    Element j of a per-env vector uses block j/4; words (0,1) of a block give normals 0,1 and
+ *    words (2,3) give normals 2,3 (Box-Muller, see gmi_noise_fill).
+ *  - Matrices are row-major.  Experience is time-major: [T, ld_envs] (scalars per step and env)
+ *    or [T, ld_envs, dim]; sample index of (t, env) in a batch is t * n_envs + env.
+ *  - Flat parameter vector (fp32 master): policy net W_0,b_0,...,W_L,b_L, value net the same,
+ *    then log_std[act_dim].  W_l is [out_l, in_l] row-major; L = n_hidden; the policy head has
+ *    act_dim outputs and the value head 1.  Both nets use ELU (alpha = 1) on hidden layers and a
+ *    linear head (policy shapes of the paper's Table 6 are "in:h1:...:out" in this notation).
+ */
+#ifndef GMIDRL_H
+#define GMIDRL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GMI_OK = 0,
+  GMI_ERR_INVALID_ARG = -1,
+  GMI_ERR_BAD_SHAPE = -2,
+  GMI_ERR_BAD_HANDLE = -3,
+  GMI_ERR_HIP = -4,
+  GMI_ERR_UNSUPPORTED = -5
+} gmi_status;
+
+typedef enum { GMI_DTYPE_F32 = 0, GMI_DTYPE_BF16 = 1 } gmi_dtype;
+
+#define GMI_MAX_HIDDEN 8
+
+typedef struct gmi_instance* gmi_t;
+typedef struct gmi_model* gmi_model_t;
+typedef struct gmi_env* gmi_env_t;
+typedef struct gmi_buffer* gmi_buffer_t;
+
+/* ------------------------------------------------------------------ instances --------------- */
+
+/* Creates an instance: a stream on `device` whose kernels run only on the compute units whose
+ * bit is set in cu_mask (bit i of word i/32 = CU i; the paper's GMI_manager.add_GMI + set_GPU of
+ * Listing 1, with the SM share of a GMI expressed as a CU set).  cu_mask == NULL or n_words == 0
+ * gives an unrestricted stream.  An all-zero mask is GMI_ERR_INVALID_ARG.  host: cu_mask. */
+int gmi_create(const uint32_t* cu_mask, uint32_t n_words, int device, gmi_t* out);
+int gmi_destroy(gmi_t gmi);
+/* The instance's hipStream_t (as void*), e.g. for torch.cuda.ExternalStream. NULL on bad handle. */
+void* gmi_stream(gmi_t gmi);
+/* Blocks the host until all work queued on the instance has finished. */
+int gmi_sync(gmi_t gmi);
+/* Number of compute units enabled for the instance (device CU count if unrestricted). */
+int gmi_cu_count(gmi_t gmi);
+const char* gmi_last_error(void);
+
+/* Hands data from instance `src` to instance `dst` (the paper's asynchronous send / synchronous
+ * recv of Listing 1, and the experience / parameter movements of Table 5, which on one device need
+ * no host bounce): work queued on dst after this call sees everything queued on src before it.
+ * If bytes > 0 and src_ptr != dst_ptr, a device-to-device copy of `bytes` is queued on src first.
+ * bytes == 0 or src_ptr == dst_ptr: ordering only.  src == dst is allowed (plain copy). dev ptrs. */
+int gmi_transfer(gmi_t src, gmi_t dst, const void* src_ptr, void* dst_ptr, size_t bytes);
+
+/* ------------------------------------------------------------------ model ------------------- */
+
+typedef struct {
+  int32_t obs_dim;
+  int32_t act_dim;
+  int32_t n_hidden;                 /* 1..GMI_MAX_HIDDEN */
+  int32_t hidden[GMI_MAX_HIDDEN];
+  int32_t dtype;                    /* gmi_dtype: arithmetic of the MLP products.
+                                       F32: fp32 FMA.  BF16: bf16 operands on MFMA, fp32 accumulate,
+                                       fp32 master parameters and optimizer state. */
+  int32_t max_rows;                 /* largest number of rows (envs of agent_act, samples of one
+                                       minibatch) any call through this binding will process */
+} gmi_model_desc;
+
+/* Number of fp32 elements of the flat parameter vector / bytes of the bf16 shadow for a desc
+ * (the shadow is needed for dtype BF16 only; returns 0 bytes for F32). */
+int64_t gmi_model_param_count(const gmi_model_desc* desc);
+int64_t gmi_model_shadow_bytes(const gmi_model_desc* desc);
+
+/* Binds a model to an instance and allocates that binding's activation workspace.
+ *  params  dev fp32 [P]   master parameters (read by F32 forward; read/written by ppo_update)
+ *  shadow  dev bytes      bf16 copies of the weights in MFMA-friendly padded layouts, plus fp32
+ *                         biases and log_std; opaque to the caller, gmi_model_shadow_bytes() long,
+ *                         256-byte aligned; written by gmi_model_refresh_shadow and ppo_update,
+ *                         read by agent_act / value.  Several bindings (agent instances and the
+ *                         trainer instance) may share one params/shadow pair.  NULL for F32.
+ *  adam_m, adam_v  dev fp32 [P]  Adam moments; NULL for an inference-only binding (ppo_update then
+ *                         fails with GMI_ERR_INVALID_ARG). */
+int gmi_model_bind(gmi_t gmi, const gmi_model_desc* desc, float* params, void* shadow,
+                   float* adam_m, float* adam_v, gmi_model_t* out);
+int gmi_model_destroy(gmi_model_t model);
+/* Rebuilds the shadow from the master parameters (after the caller initialised or replaced them). */
+int gmi_model_refresh_shadow(gmi_t gmi, gmi_model_t model);
+
+/* ------------------------------------------------------------------ environment ------------- */
+
+typedef struct {
+  int32_t n_envs;
+  int32_t obs_dim;
+  int32_t act_dim;
+  float noise_std;
+  float reward_scale;
+  uint32_t done_period;      /* > 0: done when (episode_step + 1) % done_period == 0 */
+  uint32_t done_threshold;   /* done_period == 0: done when the done-stream word < threshold */
+  uint64_t seed;
+  uint32_t env_offset;       /* index of this binding's env 0 in the Philox counter */
+} gmi_env_desc;
+
+/* The synthetic linear-Gaussian simulator that stands in for the paper's physics simulator role
+ * (Section 3, "DRL Environment Simulator"; co-located with the agent in one instance, Section 5.1).
+ *  a_mat dev fp32 [O,O], b_mat dev fp32 [O,A]: read at bind time (transposed copies are kept).
+ *  episode_step dev u32 [N]: per-env step counter, read and updated by env_step. */
+int gmi_env_bind(gmi_t gmi, const gmi_env_desc* desc, const float* a_mat, const float* b_mat,
+                 uint32_t* episode_step, gmi_env_t* out);
+int gmi_env_destroy(gmi_env_t env);
+
+/* One transition of all N envs:
+ *   next_obs = obs A^T + act B^T + noise_std * xi,  xi ~ N(0,1) (stream 1)
+ *   reward   = reward_scale * (-|obs|^2 - 0.01 |act|^2)
+ *   done     = periodic or Bernoulli (integer compare of the stream-2 word with done_threshold)
+ *   where done: next_obs = fresh N(0,1) state (stream 3), episode_step = 0; else episode_step += 1
+ * obs dev [N,O], act dev [N,A] in; next_obs dev [N,O] (must not alias obs), reward dev [N],
+ * done dev u8 [N] out.  step = global interaction index (iteration * horizon + t). */
+int env_step(gmi_t gmi, gmi_env_t env, const float* obs, const float* act, uint32_t step,
+             float* next_obs, float* reward, uint8_t* done);
+
+/* ------------------------------------------------------------------ agent ------------------- */
+
+/* Action decision of the agent role (Section 3, "DRL Agent") for n_rows envs:
+ *   mu = pi(obs), value = V(obs), eps ~ N(0,1) (stream 0, env index = env_offset + row)
+ *   act = mu + exp(log_std) * eps,  logp = sum_j [-eps_j^2/2 - log_std_j - ln(2 pi)/2]
+ * obs dev [n,O] in; act dev [n,A], logp dev [n], value dev [n] out; mu dev [n,A] out or NULL. */
+int agent_act(gmi_t gmi, gmi_model_t model, const float* obs, int32_t n_rows, uint64_t seed,
+              uint32_t step, uint32_t env_offset, float* act, float* logp, float* value, float* mu);
+
+/* value = V(obs) only: the bootstrap value of the state after the last collected step. */
+int agent_value(gmi_t gmi, gmi_model_t model, const float* obs, int32_t n_rows, float* value);
+
+/* ------------------------------------------------------------------ experience -------------- */
+
+typedef struct {
+  int32_t horizon;     /* T */
+  int32_t n_envs;      /* N: envs (columns) covered by this binding */
+  int32_t ld_envs;     /* column stride of the arrays (>= N); > N when the binding is a column
+                          slice of a wider buffer shared by several agent instances */
+  int32_t obs_dim;
+  int32_t act_dim;
+  float* obs;          /* dev [T, ld, O] */
+  float* act;          /* dev [T, ld, A] */
+  float* logp;         /* dev [T, ld]   */
+  float* val;          /* dev [T, ld]   */
+  float* rew;          /* dev [T, ld]   */
+  uint8_t* done;       /* dev [T, ld]   */
+  float* adv;          /* dev [T, ld]   written by gae_compute */
+  float* ret;          /* dev [T, ld]   written by gae_compute */
+} gmi_buffer_desc;
+
+/* Experience buffer: one array per type of data (the per-type "channels" of Section 4.2), time
+ * major so that one step's write is one contiguous slab per array. */
+int gmi_buffer_bind(gmi_t gmi, const gmi_buffer_desc* desc, gmi_buffer_t* out);
+int gmi_buffer_destroy(gmi_buffer_t buf);
+
+/* Stores step t's experience (state, action, log-prob, value, reward, done) of N envs into slot t
+ * (Section 3: the agent records experience vectors for the trainer).  All inputs dev, [N,...]. */
+int collect_experience(gmi_t gmi, gmi_buffer_t buf, int32_t t, const float* obs, const float* act,
+                       const float* logp, const float* value, const float* reward,
+                       const uint8_t* done);
+
+/* Generalized advantage estimation over the horizon, then returns, then optional normalisation:
+ *   delta_t = r_t + gamma v_{t+1} (1-d_t) - v_t (v_T = last_value),  A_t = delta_t + gamma lambda (1-d_t) A_{t+1}
+ *   ret = A + v;  normalize != 0: A <- (A - mean) / (std + 1e-8) over all T*N entries.
+ * last_value dev [N]. */
+int gae_compute(gmi_t gmi, gmi_buffer_t buf, const float* last_value, float gamma, float lambda,
+                int normalize);
+
+/* ------------------------------------------------------------------ trainer ----------------- */
+
+typedef struct {
+  float clip;          /* surrogate clip range */
+  float c_v;           /* value-loss coefficient */
+  float c_e;           /* entropy coefficient */
+  float lr, beta1, beta2, adam_eps;
+  int32_t epochs;
+  int32_t minibatch;   /* must divide T*N */
+  uint64_t seed;       /* shuffle seed */
+  uint32_t iteration;  /* shuffle counter: permutation is a function of (seed, iteration, epoch) */
+  uint32_t adam_step0; /* number of Adam steps taken before this call */
+} gmi_ppo_hparams;
+
+/* Model training stage of the trainer role (Section 3 "DRL Trainer"; stage (ii) of Section 5.1):
+ * for each epoch a seeded permutation of the T*N samples, consecutive `minibatch`-sized slices are
+ * the minibatches; each does forward of both nets, the clipped-surrogate + value + entropy loss,
+ * exact backward, and one Adam step on the fp32 master parameters (and refreshes the shadow).
+ * stats_out dev fp32 [epochs * (T*N/minibatch), 5] = per minibatch
+ *   {policy loss, value loss, entropy, mean(logp_old - logp), clip fraction}; may be NULL. */
+int ppo_update(gmi_t gmi, gmi_model_t model, gmi_buffer_t buf, const gmi_ppo_hparams* hp,
+               float* stats_out);
+
+/* Loss statistics of one minibatch given by explicit sample indices, without updating anything
+ * (forward + loss only).  idx dev i32 [n]; stats_out dev fp32 [5]. */
+int ppo_evaluate(gmi_t gmi, gmi_model_t model, gmi_buffer_t buf, const gmi_ppo_hparams* hp,
+                 const int32_t* idx, int32_t n, float* stats_out);
+
+/* Forward, loss and backward of one minibatch given by explicit sample indices: writes the flat
+ * gradient dL/dtheta (dev fp32 [P]) and the stats (dev fp32 [5]); updates nothing. */
+int ppo_gradient(gmi_t gmi, gmi_model_t model, gmi_buffer_t buf, const gmi_ppo_hparams* hp,
+                 const int32_t* idx, int32_t n, float* grad_out, float* stats_out);
+
+/* One Adam step on caller-supplied arrays (dev fp32 [n]): step = 1-based step index. */
+int adam_update(gmi_t gmi, float* params, float* adam_m, float* adam_v, const float* grad,
+                int64_t n, const gmi_ppo_hparams* hp, uint32_t step);
+
+/* ------------------------------------------------------------------ utilities --------------- */
+
+/* out[e, j] = standard normal of (seed, stream, step, env_offset + e, element j), dev fp32 [n,dim].
+ * Box-Muller on Philox words with integer-defined uniforms: u1 = (2 (w_a >> 9) + 1) / 2^24,
+ * quadrant = w_b >> 30, position in quadrant = (2 ((w_b >> 7) & 0x7FFFFF) + 1) / 2^24. */
+int gmi_noise_fill(gmi_t gmi, uint64_t seed, uint32_t stream, uint32_t step, uint32_t env_offset,
+                   int32_t n_envs, int32_t dim, float* out);
+/* out[i] = shuffle permutation of [0,n) for (seed, iteration, epoch), dev i32 [n]. */
+int gmi_permutation(gmi_t gmi, int32_t n, uint64_t seed, uint32_t iteration, uint32_t epoch,
+                    int32_t* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GMIDRL_H */

@@ -1,0 +1,306 @@
+"""Python binding of libgmidrl (the MI355X-native PPO agent/trainer hot path of GMI-DRL).
+
+Argument marshalling only: every function forwards to the C-ABI entry point of the same name
+declared in ``include/gmidrl.h``; tensors are PyTorch CUDA(ROCm) tensors used purely as device
+memory.  There is no fallback: if the HIP library is missing, importing this package fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgmidrl.so")
+
+GMI_MAX_HIDDEN = 8
+DTYPE_F32, DTYPE_BF16 = 0, 1
+OK, ERR_INVALID_ARG, ERR_BAD_SHAPE, ERR_BAD_HANDLE, ERR_HIP, ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5
+STREAM_ACTION, STREAM_ENV, STREAM_DONE, STREAM_RESET, STREAM_SHUFFLE = 0, 1, 2, 3, 4
+
+EXPORTS = [
+    "gmi_create", "gmi_destroy", "gmi_stream", "gmi_sync", "gmi_cu_count", "gmi_last_error",
+    "gmi_transfer", "gmi_model_param_count", "gmi_model_shadow_bytes", "gmi_model_bind",
+    "gmi_model_destroy", "gmi_model_refresh_shadow", "gmi_env_bind", "gmi_env_destroy", "env_step",
+    "agent_act", "agent_value", "gmi_buffer_bind", "gmi_buffer_destroy", "collect_experience",
+    "gae_compute", "ppo_update", "ppo_evaluate", "ppo_gradient", "adam_update", "gmi_noise_fill",
+    "gmi_permutation",
+]
+
+
+class GmiError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"gmidrl error {code}: {msg}")
+        self.code = code
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [("obs_dim", C.c_int32), ("act_dim", C.c_int32), ("n_hidden", C.c_int32),
+                ("hidden", C.c_int32 * GMI_MAX_HIDDEN), ("dtype", C.c_int32), ("max_rows", C.c_int32)]
+
+
+class EnvDesc(C.Structure):
+    _fields_ = [("n_envs", C.c_int32), ("obs_dim", C.c_int32), ("act_dim", C.c_int32),
+                ("noise_std", C.c_float), ("reward_scale", C.c_float), ("done_period", C.c_uint32),
+                ("done_threshold", C.c_uint32), ("seed", C.c_uint64), ("env_offset", C.c_uint32)]
+
+
+class BufferDesc(C.Structure):
+    _fields_ = [("horizon", C.c_int32), ("n_envs", C.c_int32), ("ld_envs", C.c_int32),
+                ("obs_dim", C.c_int32), ("act_dim", C.c_int32),
+                ("obs", C.c_void_p), ("act", C.c_void_p), ("logp", C.c_void_p), ("val", C.c_void_p),
+                ("rew", C.c_void_p), ("done", C.c_void_p), ("adv", C.c_void_p), ("ret", C.c_void_p)]
+
+
+class PPOHparams(C.Structure):
+    _fields_ = [("clip", C.c_float), ("c_v", C.c_float), ("c_e", C.c_float), ("lr", C.c_float),
+                ("beta1", C.c_float), ("beta2", C.c_float), ("adam_eps", C.c_float),
+                ("epochs", C.c_int32), ("minibatch", C.c_int32), ("seed", C.c_uint64),
+                ("iteration", C.c_uint32), ("adam_step0", C.c_uint32)]
+
+
+def load_library(path: str = LIB_PATH) -> C.CDLL:
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2206_08482_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(path)
+    vp, i32, u32, u64, f32, i64 = C.c_void_p, C.c_int32, C.c_uint32, C.c_uint64, C.c_float, C.c_int64
+    sig = {
+        "gmi_create": (C.c_int, [C.POINTER(C.c_uint32), u32, C.c_int, C.POINTER(vp)]),
+        "gmi_destroy": (C.c_int, [vp]),
+        "gmi_stream": (vp, [vp]),
+        "gmi_sync": (C.c_int, [vp]),
+        "gmi_cu_count": (C.c_int, [vp]),
+        "gmi_last_error": (C.c_char_p, []),
+        "gmi_transfer": (C.c_int, [vp, vp, vp, vp, C.c_size_t]),
+        "gmi_model_param_count": (i64, [C.POINTER(ModelDesc)]),
+        "gmi_model_shadow_bytes": (i64, [C.POINTER(ModelDesc)]),
+        "gmi_model_bind": (C.c_int, [vp, C.POINTER(ModelDesc), vp, vp, vp, vp, C.POINTER(vp)]),
+        "gmi_model_destroy": (C.c_int, [vp]),
+        "gmi_model_refresh_shadow": (C.c_int, [vp, vp]),
+        "gmi_env_bind": (C.c_int, [vp, C.POINTER(EnvDesc), vp, vp, vp, C.POINTER(vp)]),
+        "gmi_env_destroy": (C.c_int, [vp]),
+        "env_step": (C.c_int, [vp, vp, vp, vp, u32, vp, vp, vp]),
+        "agent_act": (C.c_int, [vp, vp, vp, i32, u64, u32, u32, vp, vp, vp, vp]),
+        "agent_value": (C.c_int, [vp, vp, vp, i32, vp]),
+        "gmi_buffer_bind": (C.c_int, [vp, C.POINTER(BufferDesc), C.POINTER(vp)]),
+        "gmi_buffer_destroy": (C.c_int, [vp]),
+        "collect_experience": (C.c_int, [vp, vp, i32, vp, vp, vp, vp, vp, vp]),
+        "gae_compute": (C.c_int, [vp, vp, vp, f32, f32, C.c_int]),
+        "ppo_update": (C.c_int, [vp, vp, vp, C.POINTER(PPOHparams), vp]),
+        "ppo_evaluate": (C.c_int, [vp, vp, vp, C.POINTER(PPOHparams), vp, i32, vp]),
+        "ppo_gradient": (C.c_int, [vp, vp, vp, C.POINTER(PPOHparams), vp, i32, vp, vp]),
+        "adam_update": (C.c_int, [vp, vp, vp, vp, vp, i64, C.POINTER(PPOHparams), u32]),
+        "gmi_noise_fill": (C.c_int, [vp, u64, u32, u32, u32, i32, i32, vp]),
+        "gmi_permutation": (C.c_int, [vp, i32, u64, u32, u32, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    return lib
+
+
+class _Lazy:
+    """Loads libgmidrl.so on first use (so that `python -m paper_2206_08482_amd.build` can import the
+    package before the library exists); a missing library raises ImportError at that point."""
+    _lib = None
+
+    def __getattr__(self, name):
+        if _Lazy._lib is None:
+            _Lazy._lib = load_library()
+        return getattr(_Lazy._lib, name)
+
+
+_lib = _Lazy()
+
+
+def last_error() -> str:
+    return _lib.gmi_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise GmiError(rc, last_error())
+
+
+def _ptr(t) -> Optional[int]:
+    """Device pointer of a tensor (None passes NULL); tensors must be contiguous CUDA tensors."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda:
+        raise TypeError("expected a device tensor")
+    if not t.is_contiguous():
+        raise TypeError("expected a contiguous tensor")
+    return t.data_ptr()
+
+
+# ---------------------------------------------------------------- instances
+def gmi_create(cu_mask: Optional[Sequence[int]] = None, device: int = 0) -> int:
+    out = C.c_void_p()
+    if cu_mask is None:
+        _check(_lib.gmi_create(None, 0, device, C.byref(out)))
+    else:
+        arr = (C.c_uint32 * len(cu_mask))(*cu_mask)
+        _check(_lib.gmi_create(arr, len(cu_mask), device, C.byref(out)))
+    return out.value
+
+
+def gmi_destroy(gmi: int) -> None:
+    _check(_lib.gmi_destroy(gmi))
+
+
+def gmi_stream(gmi: int) -> int:
+    return _lib.gmi_stream(gmi)
+
+
+def gmi_sync(gmi: int) -> None:
+    _check(_lib.gmi_sync(gmi))
+
+
+def gmi_cu_count(gmi: int) -> int:
+    rc = _lib.gmi_cu_count(gmi)
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
+def gmi_transfer(src: int, dst: int, src_t=None, dst_t=None, nbytes: int = 0) -> None:
+    _check(_lib.gmi_transfer(src, dst, _ptr(src_t), _ptr(dst_t), nbytes))
+
+
+# ---------------------------------------------------------------- model
+def model_desc(obs_dim: int, act_dim: int, hidden: Sequence[int], dtype: int, max_rows: int) -> ModelDesc:
+    d = ModelDesc()
+    d.obs_dim, d.act_dim, d.n_hidden, d.dtype, d.max_rows = obs_dim, act_dim, len(hidden), dtype, max_rows
+    for i, h in enumerate(hidden[:GMI_MAX_HIDDEN]):
+        d.hidden[i] = h
+    return d
+
+
+def gmi_model_param_count(desc: ModelDesc) -> int:
+    n = _lib.gmi_model_param_count(C.byref(desc))
+    if n < 0:
+        _check(int(n))
+    return n
+
+
+def gmi_model_shadow_bytes(desc: ModelDesc) -> int:
+    n = _lib.gmi_model_shadow_bytes(C.byref(desc))
+    if n < 0:
+        _check(int(n))
+    return n
+
+
+def gmi_model_bind(gmi: int, desc: ModelDesc, params, shadow=None, adam_m=None, adam_v=None) -> int:
+    out = C.c_void_p()
+    _check(_lib.gmi_model_bind(gmi, C.byref(desc), _ptr(params), _ptr(shadow), _ptr(adam_m),
+                               _ptr(adam_v), C.byref(out)))
+    return out.value
+
+
+def gmi_model_destroy(model: int) -> None:
+    _check(_lib.gmi_model_destroy(model))
+
+
+def gmi_model_refresh_shadow(gmi: int, model: int) -> None:
+    _check(_lib.gmi_model_refresh_shadow(gmi, model))
+
+
+# ---------------------------------------------------------------- environment
+def env_desc(n_envs, obs_dim, act_dim, noise_std, reward_scale, done_period, done_threshold, seed,
+             env_offset=0) -> EnvDesc:
+    d = EnvDesc()
+    d.n_envs, d.obs_dim, d.act_dim = n_envs, obs_dim, act_dim
+    d.noise_std, d.reward_scale = noise_std, reward_scale
+    d.done_period, d.done_threshold, d.seed, d.env_offset = done_period, done_threshold, seed, env_offset
+    return d
+
+
+def gmi_env_bind(gmi: int, desc: EnvDesc, a_mat, b_mat, episode_step) -> int:
+    out = C.c_void_p()
+    _check(_lib.gmi_env_bind(gmi, C.byref(desc), _ptr(a_mat), _ptr(b_mat), _ptr(episode_step), C.byref(out)))
+    return out.value
+
+
+def gmi_env_destroy(env: int) -> None:
+    _check(_lib.gmi_env_destroy(env))
+
+
+def env_step(gmi: int, env: int, obs, act, step: int, next_obs, reward, done) -> None:
+    _check(_lib.env_step(gmi, env, _ptr(obs), _ptr(act), step, _ptr(next_obs), _ptr(reward), _ptr(done)))
+
+
+# ---------------------------------------------------------------- agent
+def agent_act(gmi: int, model: int, obs, n_rows: int, seed: int, step: int, env_offset: int, act, logp,
+              value, mu=None) -> None:
+    _check(_lib.agent_act(gmi, model, _ptr(obs), n_rows, seed, step, env_offset, _ptr(act), _ptr(logp),
+                          _ptr(value), _ptr(mu)))
+
+
+def agent_value(gmi: int, model: int, obs, n_rows: int, value) -> None:
+    _check(_lib.agent_value(gmi, model, _ptr(obs), n_rows, _ptr(value)))
+
+
+# ---------------------------------------------------------------- experience
+def buffer_desc(horizon, n_envs, ld_envs, obs_dim, act_dim, obs, act, logp, val, rew, done, adv, ret) -> BufferDesc:
+    d = BufferDesc()
+    d.horizon, d.n_envs, d.ld_envs, d.obs_dim, d.act_dim = horizon, n_envs, ld_envs, obs_dim, act_dim
+    d.obs, d.act, d.logp, d.val = _ptr(obs), _ptr(act), _ptr(logp), _ptr(val)
+    d.rew, d.done, d.adv, d.ret = _ptr(rew), _ptr(done), _ptr(adv), _ptr(ret)
+    return d
+
+
+def gmi_buffer_bind(gmi: int, desc: BufferDesc) -> int:
+    out = C.c_void_p()
+    _check(_lib.gmi_buffer_bind(gmi, C.byref(desc), C.byref(out)))
+    return out.value
+
+
+def gmi_buffer_destroy(buf: int) -> None:
+    _check(_lib.gmi_buffer_destroy(buf))
+
+
+def collect_experience(gmi: int, buf: int, t: int, obs, act, logp, value, reward, done) -> None:
+    _check(_lib.collect_experience(gmi, buf, t, _ptr(obs), _ptr(act), _ptr(logp), _ptr(value),
+                                   _ptr(reward), _ptr(done)))
+
+
+def gae_compute(gmi: int, buf: int, last_value, gamma: float, lam: float, normalize: bool) -> None:
+    _check(_lib.gae_compute(gmi, buf, _ptr(last_value), gamma, lam, 1 if normalize else 0))
+
+
+# ---------------------------------------------------------------- trainer
+def ppo_hparams(clip=0.2, c_v=0.5, c_e=0.0, lr=3e-4, beta1=0.9, beta2=0.999, adam_eps=1e-8, epochs=1,
+                minibatch=256, seed=0, iteration=0, adam_step0=0) -> PPOHparams:
+    h = PPOHparams()
+    h.clip, h.c_v, h.c_e, h.lr, h.beta1, h.beta2, h.adam_eps = clip, c_v, c_e, lr, beta1, beta2, adam_eps
+    h.epochs, h.minibatch, h.seed, h.iteration, h.adam_step0 = epochs, minibatch, seed, iteration, adam_step0
+    return h
+
+
+def ppo_update(gmi: int, model: int, buf: int, hp: PPOHparams, stats_out=None) -> None:
+    _check(_lib.ppo_update(gmi, model, buf, C.byref(hp), _ptr(stats_out)))
+
+
+def ppo_evaluate(gmi: int, model: int, buf: int, hp: PPOHparams, idx, n: int, stats_out) -> None:
+    _check(_lib.ppo_evaluate(gmi, model, buf, C.byref(hp), _ptr(idx), n, _ptr(stats_out)))
+
+
+def ppo_gradient(gmi: int, model: int, buf: int, hp: PPOHparams, idx, n: int, grad_out, stats_out=None) -> None:
+    _check(_lib.ppo_gradient(gmi, model, buf, C.byref(hp), _ptr(idx), n, _ptr(grad_out), _ptr(stats_out)))
+
+
+def adam_update(gmi: int, params, adam_m, adam_v, grad, n: int, hp: PPOHparams, step: int) -> None:
+    _check(_lib.adam_update(gmi, _ptr(params), _ptr(adam_m), _ptr(adam_v), _ptr(grad), n, C.byref(hp), step))
+
+
+# ---------------------------------------------------------------- utilities
+def gmi_noise_fill(gmi: int, seed: int, stream: int, step: int, env_offset: int, n_envs: int, dim: int, out) -> None:
+    _check(_lib.gmi_noise_fill(gmi, seed, stream, step, env_offset, n_envs, dim, _ptr(out)))
+
+
+def gmi_permutation(gmi: int, n: int, seed: int, iteration: int, epoch: int, out) -> None:
+    _check(_lib.gmi_permutation(gmi, n, seed, iteration, epoch, _ptr(out)))

@@ -1,0 +1,166 @@
+// Instances (CU-masked streams), hand-off between instances, error reporting, RNG utilities.
+#include <stdarg.h>
+#include <string.h>
+
+#include "internal.h"
+#include "rng.cuh"
+
+namespace gmi {
+static thread_local char g_err[512] = "";
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+}  // namespace gmi
+
+extern "C" const char* gmi_last_error(void) { return gmi::g_err; }
+
+extern "C" int gmi_create(const uint32_t* cu_mask, uint32_t n_words, int device, gmi_t* out) {
+  if (!out) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_create: out is NULL");
+  *out = nullptr;
+  int n_dev = 0;
+  GMI_HIP(hipGetDeviceCount(&n_dev));
+  if (device < 0 || device >= n_dev)
+    GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_create: device %d out of range (have %d)", device, n_dev);
+  GMI_HIP(hipSetDevice(device));
+  hipDeviceProp_t prop;
+  GMI_HIP(hipGetDeviceProperties(&prop, device));
+  const int n_cu = prop.multiProcessorCount;
+  int cu_count = n_cu;
+  hipStream_t stream = nullptr;
+  if (cu_mask && n_words > 0) {
+    const uint32_t need_words = (uint32_t)((n_cu + 31) / 32);
+    std::vector<uint32_t> mask(need_words, 0u);
+    int bits = 0;
+    for (uint32_t w = 0; w < n_words; ++w) {
+      uint32_t v = cu_mask[w];
+      if (w >= need_words) {
+        if (v) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_create: cu_mask names CUs beyond the device's %d", n_cu);
+        continue;
+      }
+      if (w == need_words - 1 && (n_cu % 32) != 0 && (v >> (n_cu % 32)))
+        GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_create: cu_mask names CUs beyond the device's %d", n_cu);
+      mask[w] = v;
+      bits += __builtin_popcount(v);
+    }
+    if (bits == 0) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_create: cu_mask enables no compute unit");
+    GMI_HIP(hipExtStreamCreateWithCUMask(&stream, need_words, mask.data()));
+    cu_count = bits;
+  } else {
+    GMI_HIP(hipStreamCreateWithFlags(&stream, hipStreamNonBlocking));
+  }
+  gmi_instance* g = new gmi_instance();
+  g->magic = gmi::kMagicInstance;
+  g->device = device;
+  g->stream = stream;
+  g->cu_count = cu_count;
+  hipError_t e = hipEventCreateWithFlags(&g->event, hipEventDisableTiming);
+  if (e != hipSuccess) {
+    hipStreamDestroy(stream);
+    delete g;
+    GMI_FAIL(GMI_ERR_HIP, "gmi_create: hipEventCreate failed: %s", hipGetErrorString(e));
+  }
+  *out = g;
+  return GMI_OK;
+}
+
+extern "C" int gmi_destroy(gmi_t g) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_destroy: bad handle");
+  hipStreamSynchronize(g->stream);
+  hipEventDestroy(g->event);
+  hipStreamDestroy(g->stream);
+  g->magic = 0;
+  delete g;
+  return GMI_OK;
+}
+
+extern "C" void* gmi_stream(gmi_t g) { return valid(g) ? (void*)g->stream : nullptr; }
+
+extern "C" int gmi_cu_count(gmi_t g) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_cu_count: bad handle");
+  return g->cu_count;
+}
+
+extern "C" int gmi_sync(gmi_t g) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_sync: bad handle");
+  GMI_HIP(hipStreamSynchronize(g->stream));
+  return GMI_OK;
+}
+
+extern "C" int gmi_transfer(gmi_t src, gmi_t dst, const void* src_ptr, void* dst_ptr, size_t bytes) {
+  if (!valid(src) || !valid(dst)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_transfer: bad handle");
+  if (src->device != dst->device)
+    GMI_FAIL(GMI_ERR_UNSUPPORTED, "gmi_transfer: instances live on different devices");
+  if (bytes > 0 && src_ptr != dst_ptr) {
+    if (!src_ptr || !dst_ptr) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_transfer: NULL pointer with bytes > 0");
+    GMI_HIP(hipMemcpyAsync(dst_ptr, src_ptr, bytes, hipMemcpyDeviceToDevice, src->stream));
+  }
+  if (src != dst) {
+    GMI_HIP(hipEventRecord(src->event, src->stream));
+    GMI_HIP(hipStreamWaitEvent(dst->stream, src->event, 0));
+  }
+  return GMI_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+__global__ void noise_fill_kernel(uint32_t k0, uint32_t k1, uint32_t stream, uint32_t step,
+                                  uint32_t env_offset, int n_envs, int dim, int n_blocks,
+                                  float* __restrict__ out) {
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (int64_t)n_envs * n_blocks) return;
+  const int e = (int)(gid / n_blocks), b = (int)(gid % n_blocks);
+  float z[4];
+  gmi::normal_block(env_offset + (uint32_t)e, step, stream, (uint32_t)b, k0, k1, z);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int j = 4 * b + i;
+    if (j < dim) out[(int64_t)e * dim + j] = z[i];
+  }
+}
+
+__global__ void permutation_kernel(int n, int bits, uint32_t iteration, uint32_t epoch, uint32_t k0,
+                                   uint32_t k1, int32_t* __restrict__ out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = (int32_t)gmi::feistel_perm((uint32_t)i, (uint32_t)n, bits, iteration, epoch, k0, k1);
+}
+
+}  // namespace
+
+namespace gmi {
+int launch_permutation(hipStream_t s, int n, uint64_t seed, uint32_t iteration, uint32_t epoch, int32_t* out) {
+  if (n <= 0) return GMI_OK;
+  int bits = 0;
+  while ((1ll << bits) < (long long)n) ++bits;
+  permutation_kernel<<<(n + 255) / 256, 256, 0, s>>>(n, bits, iteration, epoch, (uint32_t)seed,
+                                                     (uint32_t)(seed >> 32), out);
+  GMI_LAUNCH_CHECK();
+  return GMI_OK;
+}
+}  // namespace gmi
+
+extern "C" int gmi_noise_fill(gmi_t g, uint64_t seed, uint32_t stream, uint32_t step, uint32_t env_offset,
+                              int32_t n_envs, int32_t dim, float* out) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_noise_fill: bad handle");
+  if (n_envs < 0 || dim < 0) GMI_FAIL(GMI_ERR_BAD_SHAPE, "gmi_noise_fill: negative size");
+  if (n_envs == 0 || dim == 0) return GMI_OK;
+  if (!out) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_noise_fill: out is NULL");
+  const int n_blocks = (dim + 3) / 4;
+  const int64_t total = (int64_t)n_envs * n_blocks;
+  noise_fill_kernel<<<(unsigned)((total + 255) / 256), 256, 0, g->stream>>>(
+      (uint32_t)seed, (uint32_t)(seed >> 32), stream, step, env_offset, n_envs, dim, n_blocks, out);
+  GMI_LAUNCH_CHECK();
+  return GMI_OK;
+}
+
+extern "C" int gmi_permutation(gmi_t g, int32_t n, uint64_t seed, uint32_t iteration, uint32_t epoch,
+                               int32_t* out) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_permutation: bad handle");
+  if (n < 0) GMI_FAIL(GMI_ERR_BAD_SHAPE, "gmi_permutation: negative n");
+  if (n == 0) return GMI_OK;
+  if (!out) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_permutation: out is NULL");
+  return gmi::launch_permutation(g->stream, n, seed, iteration, epoch, out);
+}

@@ -1,0 +1,180 @@
+// Experience buffer (one array per data type, time major), its filling, and GAE.
+#include "internal.h"
+
+namespace {
+
+// One thread per (env, field element): copies step t's row of every channel into slot t.
+__global__ void collect_kernel(gmi_buffer_desc d, int t, const float* __restrict__ obs,
+                               const float* __restrict__ act, const float* __restrict__ logp,
+                               const float* __restrict__ value, const float* __restrict__ reward,
+                               const uint8_t* __restrict__ done) {
+  const int W = d.obs_dim + d.act_dim + 4;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)d.n_envs * W) return;
+  const int e = (int)(idx / W), k = (int)(idx % W);
+  const int64_t slot = (int64_t)t * d.ld_envs + e;
+  if (k < d.obs_dim) {
+    d.obs[slot * d.obs_dim + k] = obs[(int64_t)e * d.obs_dim + k];
+  } else if (k < d.obs_dim + d.act_dim) {
+    const int j = k - d.obs_dim;
+    d.act[slot * d.act_dim + j] = act[(int64_t)e * d.act_dim + j];
+  } else {
+    switch (k - d.obs_dim - d.act_dim) {
+      case 0: d.logp[slot] = logp[e]; break;
+      case 1: d.val[slot] = value[e]; break;
+      case 2: d.rew[slot] = reward[e]; break;
+      default: d.done[slot] = done[e]; break;
+    }
+  }
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  return v;
+}
+
+// Reverse recurrence over the horizon, one lane per env: the time-major layout makes every step's
+// loads and stores of a wave one contiguous segment.  Also leaves per-workgroup sums of A and A^2.
+__global__ __launch_bounds__(256) void gae_kernel(gmi_buffer_desc d, const float* __restrict__ last_value,
+                                                  float gamma, float gl, double* __restrict__ part) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  double s1 = 0.0, s2 = 0.0;
+  if (e < d.n_envs) {
+    float adv_next = 0.f;
+    float v_next = last_value[e];
+#pragma unroll 4
+    for (int t = d.horizon - 1; t >= 0; --t) {
+      const int64_t i = (int64_t)t * d.ld_envs + e;
+      const float r = d.rew[i], v = d.val[i];
+      const float nd = 1.0f - (float)d.done[i];
+      const float delta = r + gamma * v_next * nd - v;
+      adv_next = delta + gl * nd * adv_next;
+      d.adv[i] = adv_next;
+      d.ret[i] = adv_next + v;
+      v_next = v;
+      s1 += (double)adv_next;
+      s2 += (double)adv_next * (double)adv_next;
+    }
+  }
+  if (part) {
+    __shared__ double sh[2][4];
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { sh[0][w] = s1; sh[1][w] = s2; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      part[2 * blockIdx.x + 0] = sh[0][0] + sh[0][1] + sh[0][2] + sh[0][3];
+      part[2 * blockIdx.x + 1] = sh[1][0] + sh[1][1] + sh[1][2] + sh[1][3];
+    }
+  }
+}
+
+// A <- (A - mean) / (std + 1e-8); every workgroup re-reduces the (small) partial array in the same
+// order, so the statistics are identical everywhere and reproducible.
+__global__ __launch_bounds__(256) void normalize_kernel(gmi_buffer_desc d, const double* __restrict__ part,
+                                                        int n_part) {
+  __shared__ double sh[2][4];
+  __shared__ float s_mean, s_inv;
+  double s1 = 0.0, s2 = 0.0;
+  for (int i = threadIdx.x; i < n_part; i += 256) { s1 += part[2 * i]; s2 += part[2 * i + 1]; }
+  s1 = wave_sum(s1);
+  s2 = wave_sum(s2);
+  const int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { sh[0][w] = s1; sh[1][w] = s2; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const double n = (double)d.horizon * (double)d.n_envs;
+    const double mean = (sh[0][0] + sh[0][1] + sh[0][2] + sh[0][3]) / n;
+    double var = (sh[1][0] + sh[1][1] + sh[1][2] + sh[1][3]) / n - mean * mean;
+    if (var < 0.0) var = 0.0;
+    s_mean = (float)mean;
+    s_inv = 1.0f / ((float)sqrt(var) + 1e-8f);
+  }
+  __syncthreads();
+  const float mean = s_mean, inv = s_inv;
+  const int64_t total = (int64_t)d.horizon * d.n_envs;
+  for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+    const int t = (int)(idx / d.n_envs), e = (int)(idx % d.n_envs);
+    const int64_t i = (int64_t)t * d.ld_envs + e;
+    d.adv[i] = (d.adv[i] - mean) * inv;
+  }
+}
+
+}  // namespace
+
+extern "C" int gmi_buffer_bind(gmi_t g, const gmi_buffer_desc* d, gmi_buffer_t* out) {
+  if (!out) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_buffer_bind: out is NULL");
+  *out = nullptr;
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_buffer_bind: bad instance");
+  if (!d) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_buffer_bind: desc is NULL");
+  if (d->horizon < 0 || d->n_envs < 0 || d->ld_envs < d->n_envs || d->obs_dim < 1 || d->act_dim < 1)
+    GMI_FAIL(GMI_ERR_BAD_SHAPE, "gmi_buffer_bind: need horizon, n_envs >= 0, ld_envs >= n_envs, dims >= 1");
+  if ((int64_t)d->horizon * d->ld_envs > 0 &&
+      (!d->obs || !d->act || !d->logp || !d->val || !d->rew || !d->done || !d->adv || !d->ret))
+    GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_buffer_bind: NULL array");
+  if ((int64_t)d->horizon * d->n_envs >= (1ll << 31))
+    GMI_FAIL(GMI_ERR_BAD_SHAPE, "gmi_buffer_bind: horizon * n_envs must be below 2^31");
+  gmi_buffer* b = new gmi_buffer();
+  b->magic = gmi::kMagicBuffer;
+  b->d = *d;
+  b->n_part = (d->n_envs + 255) / 256;
+  b->part = nullptr;
+  b->perm = nullptr;
+  if (b->n_part > 0) {
+    hipError_t e = hipMalloc(&b->part, sizeof(double) * 2 * (size_t)b->n_part);
+    if (e == hipSuccess && d->horizon > 0) {
+      e = hipMalloc(&b->perm, sizeof(int32_t) * (size_t)d->horizon * d->n_envs);
+      if (e != hipSuccess) hipFree(b->part);
+    }
+    if (e != hipSuccess) {
+      delete b;
+      GMI_FAIL(GMI_ERR_HIP, "gmi_buffer_bind: hipMalloc failed: %s", hipGetErrorString(e));
+    }
+  }
+  *out = b;
+  return GMI_OK;
+}
+
+extern "C" int gmi_buffer_destroy(gmi_buffer_t b) {
+  if (!valid(b)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_buffer_destroy: bad handle");
+  if (b->part) hipFree(b->part);
+  if (b->perm) hipFree(b->perm);
+  b->magic = 0;
+  delete b;
+  return GMI_OK;
+}
+
+extern "C" int collect_experience(gmi_t g, gmi_buffer_t b, int32_t t, const float* obs, const float* act,
+                                  const float* logp, const float* value, const float* reward,
+                                  const uint8_t* done) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "collect_experience: bad instance");
+  if (!valid(b)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "collect_experience: bad buffer");
+  if (t < 0 || t >= b->d.horizon) GMI_FAIL(GMI_ERR_INVALID_ARG, "collect_experience: t=%d outside [0,%d)", t, b->d.horizon);
+  if (b->d.n_envs == 0) return GMI_OK;
+  if (!obs || !act || !logp || !value || !reward || !done) GMI_FAIL(GMI_ERR_INVALID_ARG, "collect_experience: NULL pointer");
+  const int64_t total = (int64_t)b->d.n_envs * (b->d.obs_dim + b->d.act_dim + 4);
+  collect_kernel<<<(unsigned)((total + 255) / 256), 256, 0, g->stream>>>(b->d, t, obs, act, logp, value, reward, done);
+  GMI_LAUNCH_CHECK();
+  return GMI_OK;
+}
+
+extern "C" int gae_compute(gmi_t g, gmi_buffer_t b, const float* last_value, float gamma, float lambda,
+                           int normalize) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gae_compute: bad instance");
+  if (!valid(b)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gae_compute: bad buffer");
+  if (b->d.n_envs == 0 || b->d.horizon == 0) return GMI_OK;
+  if (!last_value) GMI_FAIL(GMI_ERR_INVALID_ARG, "gae_compute: last_value is NULL");
+  gae_kernel<<<b->n_part, 256, 0, g->stream>>>(b->d, last_value, gamma, gamma * lambda,
+                                               normalize ? b->part : nullptr);
+  GMI_LAUNCH_CHECK();
+  if (normalize) {
+    const int64_t total = (int64_t)b->d.horizon * b->d.n_envs;
+    int grid = (int)((total + 1023) / 1024);
+    if (grid > 2048) grid = 2048;
+    normalize_kernel<<<grid, 256, 0, g->stream>>>(b->d, b->part, b->n_part);
+    GMI_LAUNCH_CHECK();
+  }
+  return GMI_OK;
+}

@@ -1,0 +1,230 @@
+// Internal declarations shared by the translation units of libgmidrl (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string>
+#include <vector>
+
+#include "../../include/gmidrl.h"
+
+namespace gmi {
+
+void set_error(const char* fmt, ...);
+
+#define GMI_FAIL(code, ...)            \
+  do {                                 \
+    ::gmi::set_error(__VA_ARGS__);     \
+    return (code);                     \
+  } while (0)
+
+#define GMI_HIP(expr)                                                              \
+  do {                                                                             \
+    hipError_t e__ = (expr);                                                       \
+    if (e__ != hipSuccess) {                                                       \
+      ::gmi::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__),     \
+                       __FILE__, __LINE__);                                        \
+      return GMI_ERR_HIP;                                                          \
+    }                                                                              \
+  } while (0)
+
+#define GMI_LAUNCH_CHECK()                                                         \
+  do {                                                                             \
+    hipError_t e__ = hipGetLastError();                                            \
+    if (e__ != hipSuccess) {                                                       \
+      ::gmi::set_error("kernel launch failed: %s (%s:%d)", hipGetErrorString(e__), \
+                       __FILE__, __LINE__);                                        \
+      return GMI_ERR_HIP;                                                          \
+    }                                                                              \
+  } while (0)
+
+constexpr uint32_t kMagicInstance = 0x474d4931;  // "GMI1"
+constexpr uint32_t kMagicModel = 0x474d494d;
+constexpr uint32_t kMagicEnv = 0x474d4945;
+constexpr uint32_t kMagicBuffer = 0x474d4942;
+
+static inline int pad32(int x) { return (x + 31) & ~31; }
+static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace gmi
+
+struct gmi_instance {
+  uint32_t magic;
+  int device;
+  hipStream_t stream;
+  hipEvent_t event;      // used by gmi_transfer
+  int cu_count;
+};
+
+// One linear layer of one net.
+struct LayerInfo {
+  int in, out;           // logical sizes
+  int in_pad, out_pad;   // padded to multiples of 32
+  int64_t w_off, b_off;  // offsets into the flat fp32 parameter vector
+  int64_t sh_w, sh_wt, sh_b;  // byte offsets into the shadow (bf16 W [out_pad,in_pad], bf16 W^T
+                              // [in_pad,out_pad], fp32 bias [out_pad])
+  bool head;
+};
+
+struct ModelLayout {
+  int obs_dim, act_dim, n_hidden, n_layers;   // n_layers = n_hidden + 1
+  int dtype;
+  std::vector<LayerInfo> net[2];              // 0 policy, 1 value
+  int64_t logstd_off;                         // into flat params
+  int64_t sh_logstd;                          // byte offset into shadow (fp32 [act_dim])
+  int64_t n_params;
+  int64_t shadow_bytes;
+  int max_width_pad;                          // widest padded activation
+};
+
+int build_layout(const gmi_model_desc* d, ModelLayout* L);
+
+struct gmi_model {
+  uint32_t magic;
+  int device;
+  ModelLayout L;
+  int max_rows;
+  float* params;
+  char* shadow;
+  float *adam_m, *adam_v;
+  // workspace (device, owned)
+  void* ws_base;
+  size_t ws_bytes;
+  // activations: x0 shared by both nets; h[net][l] for l = 1..n_hidden; element type = dtype
+  void* x0;
+  void* h[2][GMI_MAX_HIDDEN + 1];
+  void* dz[2][GMI_MAX_HIDDEN + 2];   // dz[net][l] = dL/d(pre-activation of layer l-1's output), l=1..n_layers
+  float* mu;        // [max_rows, act_dim]
+  float* val;       // [max_rows]
+  // minibatch gathers
+  float *mb_act, *mb_logp, *mb_adv, *mb_ret;
+  // gradient partials [n_split_max, n_params] and stats partials
+  float* grad_part;
+  int n_split_max;
+  float* stat_part; // [n_split_max, 8]
+};
+
+struct gmi_env {
+  uint32_t magic;
+  gmi_env_desc d;
+  float* m_t;       // dev [(O + A), O]: rows 0..O-1 = A^T, rows O..O+A-1 = B^T
+  uint32_t* episode_step;
+};
+
+struct gmi_buffer {
+  uint32_t magic;
+  gmi_buffer_desc d;
+  double* part;     // dev [n_part, 2] partial sums for normalisation
+  int n_part;
+  int32_t* perm;    // dev [horizon * n_envs] minibatch shuffle of the current epoch
+};
+
+static inline bool valid(gmi_t g) { return g && g->magic == gmi::kMagicInstance; }
+static inline bool valid(gmi_model_t m) { return m && m->magic == gmi::kMagicModel; }
+static inline bool valid(gmi_env_t e) { return e && e->magic == gmi::kMagicEnv; }
+static inline bool valid(gmi_buffer_t b) { return b && b->magic == gmi::kMagicBuffer; }
+
+// ---------------------------------------------------------------------------------------------
+// Linear-layer launchers (mlp.hip).  Element type T of activations is float (F32) or bf16 (BF16).
+namespace gmi {
+
+enum Epilogue { kEpiBiasElu = 0, kEpiBiasHead = 1, kEpiEluGrad = 2 };
+
+// y[r, f] = epi( sum_k x[r, k] * w(f, k) )      r < rows, f < F, k < K
+//   kEpiBiasElu : y = ELU(acc + bias[f])             stored as T       [rows, ldy]
+//   kEpiBiasHead: y = acc + bias[f], f < F_store     stored as float   [rows, ldy]
+//   kEpiEluGrad : y = acc * ELU'(h[r, f]) through the stored output h: 1 if h > 0 else h + 1; T
+// w(f, k): F32 reads w[f * wsf + k * wsk] from the master parameters; BF16 reads the padded shadow
+// copy [F, ldw] (k contiguous).
+struct LinearProblem {
+  const void* x; int ldx;
+  const void* w; int ldw; int wsf, wsk;
+  const float* bias;
+  const void* h; int ldh;
+  void* y; int ldy;
+  int K, F, F_store;
+};
+
+struct LinearBatch {
+  int n;                    // 1 or 2 problems (policy, value) of equal rows / epilogue
+  LinearProblem p[2];
+};
+
+int launch_linear(hipStream_t s, int dtype, int epi, int rows, const LinearBatch& batch);
+
+// dW[o, i] = sum_r dz[r, o] * x[r, i],  db[o] = sum_r dz[r, o], reduced over row splits:
+// split sp covers rows [sp*chunk, min(rows, (sp+1)*chunk)) and writes
+// part[sp * part_stride + w_off + o*in + i] and part[sp * part_stride + b_off + o].
+struct WgradProblem {
+  const void* dz; int lddz;
+  const void* x; int ldx;
+  int out, in, out_pad, in_pad;
+  int64_t w_off, b_off;
+};
+constexpr int kMaxWgradProblems = 2 * (GMI_MAX_HIDDEN + 1);
+struct WgradBatch {
+  int n;
+  WgradProblem p[kMaxWgradProblems];
+  int blk_start[kMaxWgradProblems + 1];
+};
+int launch_wgrad(hipStream_t s, int dtype, int rows, int n_split, int chunk, WgradBatch& batch,
+                 float* part, int64_t part_stride);
+
+}  // namespace gmi
+
+// ---------------------------------------------------------------------------------------------
+// Model-level helpers (model.hip) used by the agent and trainer entry points.
+namespace gmi {
+
+static inline size_t elem_size(int dtype) { return dtype == GMI_DTYPE_BF16 ? 2 : 4; }
+
+// x0[r, :] <- obs of sample idx[r] (identity when idx == NULL), converted to the model's element
+// type, zero padded to the padded width; optionally also gathers act / logp / adv / ret rows.
+// Sample s of a buffer lives at slot (s / n_envs) * ld_envs + s % n_envs.
+int launch_gather(hipStream_t s, gmi_model* m, const float* obs, int n_envs, int ld_envs,
+                  const int32_t* idx, int rows, const gmi_buffer_desc* extras);
+
+// Runs both nets (or only the value net) on the rows staged in m->x0; keeps hidden activations in
+// m->h[net][l]; writes m->mu [rows, A] and m->val [rows].
+int forward_nets(hipStream_t s, gmi_model* m, int rows, bool policy, bool value, float* mu_dst,
+                 float* val_dst);
+
+int launch_permutation(hipStream_t s, int n, uint64_t seed, uint32_t iteration, uint32_t epoch, int32_t* out);
+
+}  // namespace gmi
+
+namespace gmi {
+constexpr int kSplitMax = 16;        // row splits of the weight-gradient reduction
+constexpr int kLossBlocksMax = 256;  // workgroups of the loss kernel (partial statistics)
+constexpr int kStatStride = 8;       // per-workgroup statistics slots before the log_std partials
+
+// Where each parameter lives in the flat vector and in the bf16 shadow (kernel argument).
+struct ShadowLayer {
+  int64_t w_off, b_off;
+  int in, out, in_pad, out_pad;
+  int64_t sh_w, sh_wt, sh_b;
+};
+struct ShadowTable {
+  int n;
+  ShadowLayer l[kMaxWgradProblems];
+  int64_t logstd_off, sh_logstd;
+  int act_dim;
+  int64_t n_params;
+};
+static inline ShadowTable make_shadow_table(const ModelLayout& L) {
+  ShadowTable t;
+  t.n = 0;
+  for (int net = 0; net < 2; ++net)
+    for (const LayerInfo& li : L.net[net]) {
+      ShadowLayer& s = t.l[t.n++];
+      s.w_off = li.w_off; s.b_off = li.b_off; s.in = li.in; s.out = li.out;
+      s.in_pad = li.in_pad; s.out_pad = li.out_pad; s.sh_w = li.sh_w; s.sh_wt = li.sh_wt; s.sh_b = li.sh_b;
+    }
+  t.logstd_off = L.logstd_off;
+  t.sh_logstd = L.sh_logstd;
+  t.act_dim = L.act_dim;
+  t.n_params = L.n_params;
+  return t;
+}
+}  // namespace gmi

@@ -1,0 +1,400 @@
+// Linear layers of the policy / value MLPs: forward, input-gradient and weight-gradient products.
+//
+// BF16 path: v_mfma_f32_32x32x16_bf16 (bf16 operands, fp32 accumulate).  A wavefront of 64 lanes
+// feeds the matrix core with 8 consecutive contraction elements per lane for both operands, so both
+// operands are staged in LDS with the contraction index contiguous; the weight-gradient product
+// contracts over samples, whose index is strided in memory, and transposes 8x8 blocks in registers
+// while staging.  F32 path: plain FMA loops (used for small fp32 configurations only).
+#include "internal.h"
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+constexpr int kBK = 64;          // contraction elements staged per step
+constexpr int kLds = kBK + 8;    // LDS row stride in bf16 elements (144 B: conflict-free 16 B reads)
+
+__device__ __forceinline__ float elu_f(float z) { return z > 0.f ? z : (__expf(z) - 1.0f); }
+__device__ __forceinline__ float bf16_to_f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+// round to nearest even
+__device__ __forceinline__ uint16_t f_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  return (uint32_t)f_to_bf16(lo) | ((uint32_t)f_to_bf16(hi) << 16);
+}
+
+// ------------------------------------------------------------------------------------------------
+// y[r, f] = epi(sum_k x[r,k] w[f,k]).  Matrix-core rows = features (weights), columns = samples, so a
+// lane ends up with 4 consecutive features of one sample per accumulator quad.
+// Workgroup = 4 waves arranged WF x WR; a wave computes TFM x TRM tiles of 32 x 32.
+template <int WF, int WR, int TFM, int TRM, int EPI>
+__global__ __launch_bounds__(256) void linear_bf16_kernel(gmi::LinearBatch batch, int rows) {
+  constexpr int TF = WF * TFM * 32, TR = WR * TRM * 32;
+  constexpr int CH_W = TF * (kBK / 8), CH_X = TR * (kBK / 8);      // 16-byte chunks per stage
+  constexpr int NCH = (CH_W + CH_X + 255) / 256;
+  __shared__ __attribute__((aligned(16))) uint16_t s_w[TF * kLds];
+  __shared__ __attribute__((aligned(16))) uint16_t s_x[TR * kLds];
+
+  const gmi::LinearProblem& P = batch.p[blockIdx.z];
+  const int f0 = blockIdx.y * TF;
+  if (f0 >= P.F) return;
+  const int r0 = blockIdx.x * TR;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wf = wave / WR, wr = wave % WR;
+  const uint16_t* __restrict__ gw = (const uint16_t*)P.w;
+  const uint16_t* __restrict__ gx = (const uint16_t*)P.x;
+
+  floatx16 acc[TFM][TRM];
+#pragma unroll
+  for (int i = 0; i < TFM; ++i)
+#pragma unroll
+    for (int j = 0; j < TRM; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  uint4 stage[NCH];
+  auto load_stage = [&](int k0) {
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int ch = tid + c * 256;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (ch < CH_W) {
+        const int row = ch >> 3, kc = ch & 7;
+        const int f = f0 + row, k = k0 + kc * 8;
+        if (f < P.F && k < P.K) v = *reinterpret_cast<const uint4*>(gw + (int64_t)f * P.ldw + k);
+      } else if (ch < CH_W + CH_X) {
+        const int c2 = ch - CH_W;
+        const int row = c2 >> 3, kc = c2 & 7;
+        const int r = r0 + row, k = k0 + kc * 8;
+        if (r < rows && k < P.K) v = *reinterpret_cast<const uint4*>(gx + (int64_t)r * P.ldx + k);
+      }
+      stage[c] = v;
+    }
+  };
+  auto store_stage = [&]() {
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int ch = tid + c * 256;
+      if (ch < CH_W) {
+        const int row = ch >> 3, kc = ch & 7;
+        *reinterpret_cast<uint4*>(&s_w[row * kLds + kc * 8]) = stage[c];
+      } else if (ch < CH_W + CH_X) {
+        const int c2 = ch - CH_W;
+        const int row = c2 >> 3, kc = c2 & 7;
+        *reinterpret_cast<uint4*>(&s_x[row * kLds + kc * 8]) = stage[c];
+      }
+    }
+  };
+
+  const int nk = (P.K + kBK - 1) / kBK;
+  load_stage(0);
+  for (int kt = 0; kt < nk; ++kt) {
+    store_stage();
+    __syncthreads();
+    if (kt + 1 < nk) load_stage((kt + 1) * kBK);
+#pragma unroll
+    for (int kk = 0; kk < kBK / 16; ++kk) {
+      bf16x8 a[TFM], b[TRM];
+      const int ko = kk * 16 + (lane >> 5) * 8;
+#pragma unroll
+      for (int i = 0; i < TFM; ++i)
+        a[i] = *reinterpret_cast<const bf16x8*>(&s_w[((wf * TFM + i) * 32 + (lane & 31)) * kLds + ko]);
+#pragma unroll
+      for (int j = 0; j < TRM; ++j)
+        b[j] = *reinterpret_cast<const bf16x8*>(&s_x[((wr * TRM + j) * 32 + (lane & 31)) * kLds + ko]);
+#pragma unroll
+      for (int i = 0; i < TFM; ++i)
+#pragma unroll
+        for (int j = 0; j < TRM; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  // epilogue: accumulator v of lane l holds feature 8*(v/4) + 4*(l/32) + v%4, sample l%32 of the tile
+#pragma unroll
+  for (int i = 0; i < TFM; ++i) {
+    const int fb = f0 + (wf * TFM + i) * 32;
+    if (fb >= P.F) continue;
+#pragma unroll
+    for (int j = 0; j < TRM; ++j) {
+      const int r = r0 + (wr * TRM + j) * 32 + (lane & 31);
+      if (r >= rows) continue;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int f = fb + q * 8 + (lane >> 5) * 4;
+        float o[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o[t] = acc[i][j][q * 4 + t];
+        if (EPI == gmi::kEpiBiasElu) {
+          const float4 bv = *reinterpret_cast<const float4*>(P.bias + f);
+          o[0] = elu_f(o[0] + bv.x); o[1] = elu_f(o[1] + bv.y);
+          o[2] = elu_f(o[2] + bv.z); o[3] = elu_f(o[3] + bv.w);
+          uint2 pk = make_uint2(pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]));
+          *reinterpret_cast<uint2*>((uint16_t*)P.y + (int64_t)r * P.ldy + f) = pk;
+        } else if (EPI == gmi::kEpiBiasHead) {
+          float* y = (float*)P.y + (int64_t)r * P.ldy;
+#pragma unroll
+          for (int t = 0; t < 4; ++t)
+            if (f + t < P.F_store) y[f + t] = o[t] + P.bias[f + t];
+        } else {
+          const uint2 hv = *reinterpret_cast<const uint2*>((const uint16_t*)P.h + (int64_t)r * P.ldh + f);
+          const float h0 = bf16_to_f((uint16_t)(hv.x & 0xFFFF)), h1 = bf16_to_f((uint16_t)(hv.x >> 16));
+          const float h2 = bf16_to_f((uint16_t)(hv.y & 0xFFFF)), h3 = bf16_to_f((uint16_t)(hv.y >> 16));
+          o[0] *= h0 > 0.f ? 1.f : h0 + 1.f; o[1] *= h1 > 0.f ? 1.f : h1 + 1.f;
+          o[2] *= h2 > 0.f ? 1.f : h2 + 1.f; o[3] *= h3 > 0.f ? 1.f : h3 + 1.f;
+          uint2 pk = make_uint2(pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]));
+          *reinterpret_cast<uint2*>((uint16_t*)P.y + (int64_t)r * P.ldy + f) = pk;
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Weight gradient: D[o, i] = sum_r dz[r, o] x[r, i].  Tile 128 (o) x 128 (i), 2 x 2 waves of 2 x 2
+// matrix-core tiles; the contraction runs over the rows of one split, 64 rows per stage.  Each thread
+// stages one 8 (rows) x 8 (features) block per step and transposes it in registers so that LDS holds
+// [feature][row] with rows contiguous.
+__device__ __forceinline__ void transpose8x8(const uint4 in[8], uint4 out[8]) {
+  // in[j] = 8 bf16 of row j (features 0..7); out[i] = 8 bf16 of feature i (rows 0..7)
+  const uint32_t* s = reinterpret_cast<const uint32_t*>(in);
+  uint32_t* d = reinterpret_cast<uint32_t*>(out);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const uint32_t a = s[(2 * p) * 4 + (i >> 1)];       // row 2p,   features (i&~1), (i|1)
+      const uint32_t b = s[(2 * p + 1) * 4 + (i >> 1)];   // row 2p+1
+      d[i * 4 + p] = (i & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void wgrad_bf16_kernel(gmi::WgradBatch batch, int rows, int n_split,
+                                                         int chunk, float* __restrict__ part,
+                                                         int64_t part_stride) {
+  constexpr int T = 128;
+  __shared__ __attribute__((aligned(16))) uint16_t s_a[T * kLds];   // [o][row]
+  __shared__ __attribute__((aligned(16))) uint16_t s_b[T * kLds];   // [i][row]
+  int pi = 0;
+  while (pi + 1 < batch.n && (int)blockIdx.x >= batch.blk_start[pi + 1]) ++pi;
+  const gmi::WgradProblem& P = batch.p[pi];
+  const int local = blockIdx.x - batch.blk_start[pi];
+  const int sp = local % n_split;
+  const int tile = local / n_split;
+  const int n_ti = (P.in_pad + T - 1) / T;
+  const int o0 = (tile / n_ti) * T, i0 = (tile % n_ti) * T;
+  const int row_begin = sp * chunk;
+  const int row_end = min(rows, row_begin + chunk);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wo = wave >> 1, wi = wave & 1;
+  const bool is_b = tid >= 128;
+  const int t2 = tid & 127;
+  const int fblk = t2 & 15, rblk = t2 >> 4;          // 16 feature blocks x 8 row blocks
+  const uint16_t* __restrict__ src = is_b ? (const uint16_t*)P.x : (const uint16_t*)P.dz;
+  const int ld = is_b ? P.ldx : P.lddz;
+  const int fmax = is_b ? P.in_pad : P.out_pad;
+  const int feat = (is_b ? i0 : o0) + fblk * 8;
+  uint16_t* sdst = (is_b ? s_b : s_a) + (fblk * 8) * kLds + rblk * 8;
+
+  floatx16 acc[2][2];
+  floatx16 accb[2];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    acc[0][0][v] = acc[0][1][v] = acc[1][0][v] = acc[1][1][v] = 0.f;
+    accb[0][v] = accb[1][v] = 0.f;
+  }
+  const bool do_bias = (i0 == 0) && (wi == 0);
+  bf16x8 ones;
+#pragma unroll
+  for (int v = 0; v < 8; ++v) ones[v] = (__bf16)1.0f;
+
+  uint4 stage[8];
+  auto load_stage = [&](int rbase) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int r = rbase + rblk * 8 + j;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (r < row_end && feat < fmax) v = *reinterpret_cast<const uint4*>(src + (int64_t)r * ld + feat);
+      stage[j] = v;
+    }
+  };
+  auto store_stage = [&]() {
+    uint4 tr[8];
+    transpose8x8(stage, tr);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4*>(sdst + i * kLds) = tr[i];
+  };
+
+  if (row_begin < row_end) load_stage(row_begin);
+  for (int rb = row_begin; rb < row_end; rb += kBK) {
+    store_stage();
+    __syncthreads();
+    if (rb + kBK < row_end) load_stage(rb + kBK);
+#pragma unroll
+    for (int kk = 0; kk < kBK / 16; ++kk) {
+      bf16x8 a[2], b[2];
+      const int ko = kk * 16 + (lane >> 5) * 8;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        a[i] = *reinterpret_cast<const bf16x8*>(&s_a[((wo * 2 + i) * 32 + (lane & 31)) * kLds + ko]);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        b[j] = *reinterpret_cast<const bf16x8*>(&s_b[((wi * 2 + j) * 32 + (lane & 31)) * kLds + ko]);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      if (do_bias) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          accb[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], ones, accb[i], 0, 0, 0);
+      }
+    }
+    __syncthreads();
+  }
+
+  float* dst = part + (int64_t)sp * part_stride;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int o = o0 + (wo * 2 + i) * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+      if (o >= P.out) continue;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int ii = i0 + (wi * 2 + j) * 32 + (lane & 31);
+        if (ii < P.in) dst[P.w_off + (int64_t)o * P.in + ii] = acc[i][j][v];
+      }
+      if (do_bias && (lane & 31) == 0) dst[P.b_off + o] = accb[i][v];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// F32 path: one thread per output element.
+template <int EPI>
+__global__ void linear_f32_kernel(gmi::LinearBatch batch, int rows) {
+  const gmi::LinearProblem& P = batch.p[blockIdx.z];
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)rows * P.F) return;
+  const int r = (int)(idx / P.F), f = (int)(idx % P.F);
+  const float* x = (const float*)P.x + (int64_t)r * P.ldx;
+  const float* w = (const float*)P.w + (int64_t)f * P.wsf;
+  float acc = 0.f;
+  for (int k = 0; k < P.K; ++k) acc = fmaf(x[k], w[(int64_t)k * P.wsk], acc);
+  if (EPI == gmi::kEpiBiasElu) {
+    const float z = acc + P.bias[f];
+    ((float*)P.y)[(int64_t)r * P.ldy + f] = z > 0.f ? z : expm1f(z);
+  } else if (EPI == gmi::kEpiBiasHead) {
+    if (f < P.F_store) ((float*)P.y)[(int64_t)r * P.ldy + f] = acc + P.bias[f];
+  } else {
+    const float h = ((const float*)P.h)[(int64_t)r * P.ldh + f];
+    ((float*)P.y)[(int64_t)r * P.ldy + f] = acc * (h > 0.f ? 1.f : h + 1.f);
+  }
+}
+
+// grid.x over (out*in + out) outputs of one problem, grid.y = split, grid.z = problem
+__global__ void wgrad_f32_kernel(gmi::WgradBatch batch, int rows, int chunk, float* __restrict__ part,
+                                 int64_t part_stride) {
+  const gmi::WgradProblem& P = batch.p[blockIdx.z];
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  const int nw = P.out * P.in;
+  if (idx >= nw + P.out) return;
+  const int sp = blockIdx.y;
+  const int rb = sp * chunk, re = min(rows, rb + chunk);
+  const float* dz = (const float*)P.dz;
+  const float* x = (const float*)P.x;
+  float acc = 0.f;
+  float* dst = part + (int64_t)sp * part_stride;
+  if (idx < nw) {
+    const int o = idx / P.in, i = idx % P.in;
+    for (int r = rb; r < re; ++r) acc = fmaf(dz[(int64_t)r * P.lddz + o], x[(int64_t)r * P.ldx + i], acc);
+    dst[P.w_off + idx] = acc;
+  } else {
+    const int o = idx - nw;
+    for (int r = rb; r < re; ++r) acc += dz[(int64_t)r * P.lddz + o];
+    dst[P.b_off + o] = acc;
+  }
+}
+
+template <int WF, int WR, int TFM, int TRM>
+int launch_bf16_cfg(hipStream_t s, int epi, int rows, const gmi::LinearBatch& b, int maxF) {
+  constexpr int TF = WF * TFM * 32, TR = WR * TRM * 32;
+  dim3 grid((rows + TR - 1) / TR, (maxF + TF - 1) / TF, b.n);
+  switch (epi) {
+    case gmi::kEpiBiasElu:
+      linear_bf16_kernel<WF, WR, TFM, TRM, gmi::kEpiBiasElu><<<grid, 256, 0, s>>>(b, rows); break;
+    case gmi::kEpiBiasHead:
+      linear_bf16_kernel<WF, WR, TFM, TRM, gmi::kEpiBiasHead><<<grid, 256, 0, s>>>(b, rows); break;
+    default:
+      linear_bf16_kernel<WF, WR, TFM, TRM, gmi::kEpiEluGrad><<<grid, 256, 0, s>>>(b, rows); break;
+  }
+  GMI_LAUNCH_CHECK();
+  return GMI_OK;
+}
+
+}  // namespace
+
+namespace gmi {
+
+int launch_linear(hipStream_t s, int dtype, int epi, int rows, const LinearBatch& b) {
+  if (rows <= 0 || b.n <= 0) return GMI_OK;
+  int maxF = 0;
+  for (int i = 0; i < b.n; ++i) maxF = b.p[i].F > maxF ? b.p[i].F : maxF;
+  if (dtype == GMI_DTYPE_F32) {
+    dim3 grid((unsigned)(((int64_t)rows * maxF + 255) / 256), 1, b.n);
+    switch (epi) {
+      case kEpiBiasElu: linear_f32_kernel<kEpiBiasElu><<<grid, 256, 0, s>>>(b, rows); break;
+      case kEpiBiasHead: linear_f32_kernel<kEpiBiasHead><<<grid, 256, 0, s>>>(b, rows); break;
+      default: linear_f32_kernel<kEpiEluGrad><<<grid, 256, 0, s>>>(b, rows); break;
+    }
+    GMI_LAUNCH_CHECK();
+    return GMI_OK;
+  }
+  for (int i = 0; i < b.n; ++i) {
+    const LinearProblem& p = b.p[i];
+    if ((p.K & 31) || (p.F & 31) || (p.ldx & 7) || (p.ldw & 7) || (epi != kEpiBiasHead && (p.ldy & 3)) ||
+        (epi == kEpiEluGrad && (p.ldh & 3)))
+      GMI_FAIL(GMI_ERR_BAD_SHAPE, "launch_linear: bf16 path needs padded dims (K=%d F=%d)", p.K, p.F);
+  }
+  if (maxF % 128 == 0 || maxF > 256) return launch_bf16_cfg<2, 2, 2, 2>(s, epi, rows, b, maxF);
+  if (maxF % 64 == 0) return launch_bf16_cfg<1, 4, 2, 2>(s, epi, rows, b, maxF);
+  if (maxF <= 96) return launch_bf16_cfg<1, 4, 1, 2>(s, epi, rows, b, maxF);
+  return launch_bf16_cfg<2, 2, 2, 2>(s, epi, rows, b, maxF);
+}
+
+int launch_wgrad(hipStream_t s, int dtype, int rows, int n_split, int chunk, WgradBatch& b, float* part,
+                 int64_t part_stride) {
+  if (b.n <= 0) return GMI_OK;
+  if (dtype == GMI_DTYPE_F32) {
+    int maxn = 0;
+    for (int i = 0; i < b.n; ++i) {
+      const int n = b.p[i].out * b.p[i].in + b.p[i].out;
+      maxn = n > maxn ? n : maxn;
+    }
+    dim3 grid((maxn + 255) / 256, n_split, b.n);
+    wgrad_f32_kernel<<<grid, 256, 0, s>>>(b, rows, chunk, part, part_stride);
+    GMI_LAUNCH_CHECK();
+    return GMI_OK;
+  }
+  int total = 0;
+  for (int i = 0; i < b.n; ++i) {
+    b.blk_start[i] = total;
+    total += ((b.p[i].out_pad + 127) / 128) * ((b.p[i].in_pad + 127) / 128) * n_split;
+  }
+  b.blk_start[b.n] = total;
+  wgrad_bf16_kernel<<<total, 256, 0, s>>>(b, rows, n_split, chunk, part, part_stride);
+  GMI_LAUNCH_CHECK();
+  return GMI_OK;
+}
+
+}  // namespace gmi

@@ -1,0 +1,349 @@
+// Policy / value model: parameter layout, bf16 shadow, workspace, forward driver, and the agent role's
+// action decision (Section 3 of the paper, "DRL Agent"; model shapes as in its Table 6).
+#include "internal.h"
+#include "rng.cuh"
+
+
+int build_layout(const gmi_model_desc* d, ModelLayout* L) {
+  if (!d) GMI_FAIL(GMI_ERR_INVALID_ARG, "model desc is NULL");
+  if (d->obs_dim < 1 || d->act_dim < 1 || d->n_hidden < 1 || d->n_hidden > GMI_MAX_HIDDEN)
+    GMI_FAIL(GMI_ERR_BAD_SHAPE, "model desc: need obs_dim, act_dim >= 1 and 1 <= n_hidden <= %d", GMI_MAX_HIDDEN);
+  if (d->dtype != GMI_DTYPE_F32 && d->dtype != GMI_DTYPE_BF16)
+    GMI_FAIL(GMI_ERR_UNSUPPORTED, "model desc: dtype %d not supported", d->dtype);
+  if (d->act_dim > 1024 || d->obs_dim > 65536) GMI_FAIL(GMI_ERR_BAD_SHAPE, "model desc: act_dim <= 1024, obs_dim <= 65536");
+  for (int i = 0; i < d->n_hidden; ++i)
+    if (d->hidden[i] < 1 || d->hidden[i] > 65536) GMI_FAIL(GMI_ERR_BAD_SHAPE, "model desc: hidden[%d] = %d", i, d->hidden[i]);
+  L->obs_dim = d->obs_dim;
+  L->act_dim = d->act_dim;
+  L->n_hidden = d->n_hidden;
+  L->n_layers = d->n_hidden + 1;
+  L->dtype = d->dtype;
+  int64_t off = 0, sh = 0;
+  int maxw = gmi::pad32(d->obs_dim);
+  for (int net = 0; net < 2; ++net) {
+    L->net[net].clear();
+    int prev = d->obs_dim;
+    for (int l = 0; l < L->n_layers; ++l) {
+      LayerInfo li;
+      li.in = prev;
+      li.head = (l == L->n_layers - 1);
+      li.out = li.head ? (net == 0 ? d->act_dim : 1) : d->hidden[l];
+      li.in_pad = gmi::pad32(li.in);
+      li.out_pad = gmi::pad32(li.out);
+      li.w_off = off; off += (int64_t)li.in * li.out;
+      li.b_off = off; off += li.out;
+      li.sh_w = sh;  sh += gmi::align_up((int64_t)li.out_pad * li.in_pad * 2, 256);
+      li.sh_wt = sh; sh += gmi::align_up((int64_t)li.out_pad * li.in_pad * 2, 256);
+      li.sh_b = sh;  sh += gmi::align_up((int64_t)li.out_pad * 4, 256);
+      if (li.out_pad > maxw) maxw = li.out_pad;
+      L->net[net].push_back(li);
+      prev = li.out;
+    }
+  }
+  L->logstd_off = off;
+  off += d->act_dim;
+  L->sh_logstd = sh;
+  sh += gmi::align_up((int64_t)d->act_dim * 4, 256);
+  L->n_params = off;
+  L->shadow_bytes = d->dtype == GMI_DTYPE_BF16 ? sh : 0;
+  L->max_width_pad = maxw;
+  return GMI_OK;
+}
+
+extern "C" int64_t gmi_model_param_count(const gmi_model_desc* d) {
+  ModelLayout L;
+  const int rc = build_layout(d, &L);
+  return rc == GMI_OK ? L.n_params : (int64_t)rc;
+}
+
+extern "C" int64_t gmi_model_shadow_bytes(const gmi_model_desc* d) {
+  ModelLayout L;
+  const int rc = build_layout(d, &L);
+  return rc == GMI_OK ? L.shadow_bytes : (int64_t)rc;
+}
+
+namespace {
+
+__device__ __forceinline__ uint16_t f_to_bf16_dev(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// One thread per parameter: writes its bf16 copies (W and W^T layouts) or fp32 bias / log_std copy.
+// Padding entries of the shadow are zeroed by gmi_model_refresh_shadow and never written otherwise.
+__global__ void refresh_shadow_kernel(gmi::ShadowTable tab, const float* __restrict__ params, char* __restrict__ shadow) {
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= tab.n_params) return;
+  const float v = params[p];
+  if (p >= tab.logstd_off) {
+    reinterpret_cast<float*>(shadow + tab.sh_logstd)[p - tab.logstd_off] = v;
+    return;
+  }
+  int li = 0;
+  while (li + 1 < tab.n && p >= tab.l[li + 1].w_off) ++li;
+  const gmi::ShadowLayer& L = tab.l[li];
+  if (p >= L.b_off) {
+    reinterpret_cast<float*>(shadow + L.sh_b)[p - L.b_off] = v;
+  } else {
+    const int64_t q = p - L.w_off;
+    const int o = (int)(q / L.in), i = (int)(q % L.in);
+    const uint16_t b = f_to_bf16_dev(v);
+    reinterpret_cast<uint16_t*>(shadow + L.sh_w)[(int64_t)o * L.in_pad + i] = b;
+    reinterpret_cast<uint16_t*>(shadow + L.sh_wt)[(int64_t)i * L.out_pad + o] = b;
+  }
+}
+
+// Gather / convert: one thread per (row, column) of the widened row
+//   [0, o_pad) -> x0 (converted, zero padded);  then act[A], logp, adv, ret if extras are asked for.
+template <typename T>
+__global__ void gather_kernel(const float* __restrict__ obs, int n_envs, int ld_envs, int O, int o_pad,
+                              const int32_t* __restrict__ idx, int rows, T* __restrict__ x0, int A,
+                              const float* __restrict__ b_act, const float* __restrict__ b_logp,
+                              const float* __restrict__ b_adv, const float* __restrict__ b_ret,
+                              float* __restrict__ m_act, float* __restrict__ m_logp, float* __restrict__ m_adv,
+                              float* __restrict__ m_ret) {
+  const int W = o_pad + (b_act ? A + 3 : 0);
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (int64_t)rows * W) return;
+  const int r = (int)(gid / W), k = (int)(gid % W);
+  const int s = idx ? idx[r] : r;
+  const int64_t slot = (int64_t)(s / n_envs) * ld_envs + (s % n_envs);
+  if (k < o_pad) {
+    const float v = k < O ? obs[slot * O + k] : 0.f;
+    if constexpr (sizeof(T) == 2) x0[(int64_t)r * o_pad + k] = f_to_bf16_dev(v);
+    else x0[(int64_t)r * o_pad + k] = v;
+  } else {
+    const int j = k - o_pad;
+    if (j < A) m_act[(int64_t)r * A + j] = b_act[slot * A + j];
+    else if (j == A) m_logp[r] = b_logp[slot];
+    else if (j == A + 1) m_adv[r] = b_adv[slot];
+    else m_ret[r] = b_ret[slot];
+  }
+}
+
+// act = mu + exp(log_std) * eps; logp = sum_j [-eps_j^2/2 - log_std_j - ln(2 pi)/2]; one thread per env.
+__global__ void sample_kernel(const float* __restrict__ mu, const float* __restrict__ log_std, int n, int A,
+                              uint32_t k0, uint32_t k1, uint32_t step, uint32_t env_offset,
+                              float* __restrict__ act, float* __restrict__ logp, float* __restrict__ mu_out) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n) return;
+  float lp = 0.f;
+  const int nb = (A + 3) / 4;
+  for (int b = 0; b < nb; ++b) {
+    float z[4];
+    gmi::normal_block(env_offset + (uint32_t)e, step, gmi::kStreamAction, (uint32_t)b, k0, k1, z);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int j = 4 * b + i;
+      if (j < A) {
+        const float ls = log_std[j];
+        const float m = mu[(int64_t)e * A + j];
+        act[(int64_t)e * A + j] = fmaf(expf(ls), z[i], m);
+        if (mu_out) mu_out[(int64_t)e * A + j] = m;
+        lp += -0.5f * z[i] * z[i] - ls - 0.918938533204672742f;
+      }
+    }
+  }
+  logp[e] = lp;
+}
+
+}  // namespace
+
+namespace gmi {
+
+int launch_gather(hipStream_t s, gmi_model* m, const float* obs, int n_envs, int ld_envs,
+                  const int32_t* idx, int rows, const gmi_buffer_desc* ex) {
+  if (rows <= 0) return GMI_OK;
+  const int O = m->L.obs_dim, A = m->L.act_dim, o_pad = gmi::pad32(O);
+  const int W = o_pad + (ex ? A + 3 : 0);
+  const int64_t total = (int64_t)rows * W;
+  const unsigned grid = (unsigned)((total + 255) / 256);
+  if (m->L.dtype == GMI_DTYPE_BF16)
+    gather_kernel<uint16_t><<<grid, 256, 0, s>>>(obs, n_envs, ld_envs, O, o_pad, idx, rows, (uint16_t*)m->x0, A,
+                                                 ex ? ex->act : nullptr, ex ? ex->logp : nullptr,
+                                                 ex ? ex->adv : nullptr, ex ? ex->ret : nullptr, m->mb_act,
+                                                 m->mb_logp, m->mb_adv, m->mb_ret);
+  else
+    gather_kernel<float><<<grid, 256, 0, s>>>(obs, n_envs, ld_envs, O, o_pad, idx, rows, (float*)m->x0, A,
+                                              ex ? ex->act : nullptr, ex ? ex->logp : nullptr,
+                                              ex ? ex->adv : nullptr, ex ? ex->ret : nullptr, m->mb_act,
+                                              m->mb_logp, m->mb_adv, m->mb_ret);
+  GMI_LAUNCH_CHECK();
+  return GMI_OK;
+}
+
+// Layer l maps h[l] (input, width in_pad) to h[l+1]; the head writes mu / val in fp32.
+int forward_nets(hipStream_t s, gmi_model* m, int rows, bool policy, bool value, float* mu_dst,
+                 float* val_dst) {
+  const ModelLayout& L = m->L;
+  const bool bf = L.dtype == GMI_DTYPE_BF16;
+  for (int l = 0; l < L.n_layers; ++l) {
+    LinearBatch b;
+    b.n = 0;
+    for (int net = 0; net < 2; ++net) {
+      if ((net == 0 && !policy) || (net == 1 && !value)) continue;
+      const LayerInfo& li = L.net[net][l];
+      LinearProblem& p = b.p[b.n++];
+      p.x = l == 0 ? m->x0 : m->h[net][l];
+      p.ldx = li.in_pad;
+      if (bf) {
+        p.w = m->shadow + li.sh_w; p.ldw = li.in_pad; p.wsf = li.in_pad; p.wsk = 1;
+        p.bias = reinterpret_cast<const float*>(m->shadow + li.sh_b);
+        p.K = li.in_pad; p.F = li.out_pad;
+      } else {
+        p.w = m->params + li.w_off; p.ldw = li.in; p.wsf = li.in; p.wsk = 1;
+        p.bias = m->params + li.b_off;
+        p.K = li.in; p.F = li.out;
+      }
+      p.h = nullptr; p.ldh = 0;
+      if (li.head) {
+        p.y = net == 0 ? (void*)mu_dst : (void*)val_dst;
+        p.ldy = li.out;
+        p.F_store = li.out;
+      } else {
+        p.y = m->h[net][l + 1];
+        p.ldy = li.out_pad;
+        p.F_store = p.F;
+      }
+    }
+    const int rc = launch_linear(s, L.dtype, l == L.n_layers - 1 ? kEpiBiasHead : kEpiBiasElu, rows, b);
+    if (rc != GMI_OK) return rc;
+  }
+  return GMI_OK;
+}
+
+}  // namespace gmi
+
+extern "C" int gmi_model_bind(gmi_t g, const gmi_model_desc* d, float* params, void* shadow, float* adam_m,
+                              float* adam_v, gmi_model_t* out) {
+  if (!out) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_model_bind: out is NULL");
+  *out = nullptr;
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_model_bind: bad instance");
+  ModelLayout L;
+  const int rc = build_layout(d, &L);
+  if (rc != GMI_OK) return rc;
+  if (!params) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_model_bind: params is NULL");
+  if (L.dtype == GMI_DTYPE_BF16 && !shadow) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_model_bind: BF16 needs a shadow buffer");
+  if (L.dtype == GMI_DTYPE_BF16 && ((uintptr_t)shadow & 255)) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_model_bind: shadow must be 256-byte aligned");
+  if ((adam_m == nullptr) != (adam_v == nullptr)) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_model_bind: give both Adam moments or neither");
+  if (d->max_rows < 1) GMI_FAIL(GMI_ERR_BAD_SHAPE, "gmi_model_bind: max_rows must be >= 1");
+
+  gmi_model* m = new gmi_model();
+  m->magic = gmi::kMagicModel;
+  m->device = g->device;
+  m->L = L;
+  m->max_rows = d->max_rows;
+  m->params = params;
+  m->shadow = (char*)shadow;
+  m->adam_m = adam_m;
+  m->adam_v = adam_v;
+  m->n_split_max = gmi::kSplitMax;
+
+  const int64_t rows = d->max_rows;
+  const size_t es = gmi::elem_size(L.dtype);
+  const int A = L.act_dim;
+  // first pass sizes, second pass pointers
+  for (int pass = 0; pass < 2; ++pass) {
+    int64_t off = 0;
+    char* base = (char*)m->ws_base;
+    auto take = [&](int64_t bytes) -> void* {
+      void* p = pass ? (void*)(base + off) : nullptr;
+      off += gmi::align_up(bytes, 256);
+      return p;
+    };
+    m->x0 = take(rows * gmi::pad32(L.obs_dim) * es);
+    for (int net = 0; net < 2; ++net) {
+      m->h[net][0] = m->x0;
+      for (int l = 0; l < L.n_layers; ++l) {
+        const LayerInfo& li = L.net[net][l];
+        if (!li.head) m->h[net][l + 1] = take(rows * li.out_pad * es);
+        m->dz[net][l] = take(rows * li.out_pad * es);
+      }
+    }
+    m->mu = (float*)take(rows * A * 4);
+    m->val = (float*)take(rows * 4);
+    m->mb_act = (float*)take(rows * A * 4);
+    m->mb_logp = (float*)take(rows * 4);
+    m->mb_adv = (float*)take(rows * 4);
+    m->mb_ret = (float*)take(rows * 4);
+    m->grad_part = (float*)take((int64_t)gmi::kSplitMax * L.n_params * 4);
+    m->stat_part = (float*)take((int64_t)gmi::kLossBlocksMax * (8 + A) * 4);
+    if (pass == 0) {
+      m->ws_bytes = (size_t)off;
+      hipError_t e = hipMalloc(&m->ws_base, m->ws_bytes);
+      if (e != hipSuccess) {
+        delete m;
+        GMI_FAIL(GMI_ERR_HIP, "gmi_model_bind: hipMalloc(%zu) failed: %s", (size_t)off, hipGetErrorString(e));
+      }
+    }
+  }
+  hipError_t e = hipMemsetAsync(m->ws_base, 0, m->ws_bytes, g->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(g->stream);
+  if (e != hipSuccess) {
+    hipFree(m->ws_base);
+    delete m;
+    GMI_FAIL(GMI_ERR_HIP, "gmi_model_bind: clearing the workspace failed: %s", hipGetErrorString(e));
+  }
+  *out = m;
+  return GMI_OK;
+}
+
+extern "C" int gmi_model_destroy(gmi_model_t m) {
+  if (!valid(m)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_model_destroy: bad handle");
+  hipFree(m->ws_base);
+  m->magic = 0;
+  delete m;
+  return GMI_OK;
+}
+
+extern "C" int gmi_model_refresh_shadow(gmi_t g, gmi_model_t m) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_model_refresh_shadow: bad instance");
+  if (!valid(m)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_model_refresh_shadow: bad model");
+  if (m->L.dtype != GMI_DTYPE_BF16) return GMI_OK;
+  GMI_HIP(hipMemsetAsync(m->shadow, 0, (size_t)m->L.shadow_bytes, g->stream));
+  const gmi::ShadowTable tab = gmi::make_shadow_table(m->L);
+  refresh_shadow_kernel<<<(unsigned)((m->L.n_params + 255) / 256), 256, 0, g->stream>>>(tab, m->params, m->shadow);
+  GMI_LAUNCH_CHECK();
+  return GMI_OK;
+}
+
+static int check_rows(const char* fn, gmi_model_t m, int n_rows) {
+  if (n_rows < 0) GMI_FAIL(GMI_ERR_BAD_SHAPE, "%s: negative n_rows", fn);
+  if (n_rows > m->max_rows) GMI_FAIL(GMI_ERR_BAD_SHAPE, "%s: n_rows=%d exceeds the binding's max_rows=%d", fn, n_rows, m->max_rows);
+  return GMI_OK;
+}
+
+extern "C" int agent_act(gmi_t g, gmi_model_t m, const float* obs, int32_t n_rows, uint64_t seed, uint32_t step,
+                         uint32_t env_offset, float* act, float* logp, float* value, float* mu) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "agent_act: bad instance");
+  if (!valid(m)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "agent_act: bad model");
+  int rc = check_rows("agent_act", m, n_rows);
+  if (rc != GMI_OK) return rc;
+  if (n_rows == 0) return GMI_OK;
+  if (!obs || !act || !logp || !value) GMI_FAIL(GMI_ERR_INVALID_ARG, "agent_act: NULL pointer");
+  rc = gmi::launch_gather(g->stream, m, obs, n_rows, n_rows, nullptr, n_rows, nullptr);
+  if (rc != GMI_OK) return rc;
+  rc = gmi::forward_nets(g->stream, m, n_rows, true, true, m->mu, value);
+  if (rc != GMI_OK) return rc;
+  const float* log_std = m->L.dtype == GMI_DTYPE_BF16 ? reinterpret_cast<const float*>(m->shadow + m->L.sh_logstd)
+                                                      : m->params + m->L.logstd_off;
+  sample_kernel<<<(n_rows + 127) / 128, 128, 0, g->stream>>>(m->mu, log_std, n_rows, m->L.act_dim, (uint32_t)seed,
+                                                             (uint32_t)(seed >> 32), step, env_offset, act, logp, mu);
+  GMI_LAUNCH_CHECK();
+  return GMI_OK;
+}
+
+extern "C" int agent_value(gmi_t g, gmi_model_t m, const float* obs, int32_t n_rows, float* value) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "agent_value: bad instance");
+  if (!valid(m)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "agent_value: bad model");
+  int rc = check_rows("agent_value", m, n_rows);
+  if (rc != GMI_OK) return rc;
+  if (n_rows == 0) return GMI_OK;
+  if (!obs || !value) GMI_FAIL(GMI_ERR_INVALID_ARG, "agent_value: NULL pointer");
+  rc = gmi::launch_gather(g->stream, m, obs, n_rows, n_rows, nullptr, n_rows, nullptr);
+  if (rc != GMI_OK) return rc;
+  rc = gmi::forward_nets(g->stream, m, n_rows, false, true, nullptr, value);
+  return rc;
+}

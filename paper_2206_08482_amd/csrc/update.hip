@@ -1,0 +1,358 @@
+// Trainer role (Section 3 of the paper, "DRL Trainer"; stage (ii) of Section 5.1): clipped-surrogate
+// loss, exact backward through both MLPs, Adam on the fp32 master parameters, shadow refresh.
+#include <math.h>
+
+#include "internal.h"
+
+namespace {
+
+__device__ __forceinline__ uint16_t f_to_bf16_u(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ void store_elem(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_elem(uint16_t* p, float v) { *p = f_to_bf16_u(v); }
+
+__device__ __forceinline__ float wave_sum_f(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  return v;
+}
+
+// One thread per sample (grid-stride).  Per workgroup partial sums go to
+//   stat_part[blk][0..4] = sum policy term, sum value term, entropy (workgroup 0 only), sum kl, sum clipped
+//   stat_part[blk][kStatStride + j] = partial dL/dlog_std_j (without the entropy term)
+// and, if want_grad, dL/dmu and dL/dv rows are written for the backward products.
+template <typename T>
+__global__ __launch_bounds__(256) void loss_kernel(int rows, int A, const float* __restrict__ mu,
+                                                   const float* __restrict__ val, const float* __restrict__ act,
+                                                   const float* __restrict__ logp_old, const float* __restrict__ adv,
+                                                   const float* __restrict__ ret, const float* __restrict__ log_std,
+                                                   float clip, float c_v, int want_grad, T* __restrict__ dmu,
+                                                   int ld_dmu, T* __restrict__ dv, int ld_dv,
+                                                   float* __restrict__ stat_part) {
+  extern __shared__ float sh[];            // [4][A] log_std partials, then [4][4] stats
+  float* s_dls = sh;
+  float* s_st = sh + 4 * A;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int i = tid; i < 4 * A + 16; i += 256) sh[i] = 0.f;
+  __syncthreads();
+  const float inv_m = 1.0f / (float)rows;
+  float s_pl = 0.f, s_vl = 0.f, s_kl = 0.f, s_cf = 0.f;
+  const int n_iter = (rows + gridDim.x * 256 - 1) / (gridDim.x * 256);
+  for (int it = 0; it < n_iter; ++it) {
+    const int r = (it * gridDim.x + blockIdx.x) * 256 + tid;
+    const bool ok = r < rows;
+    float lp = 0.f;
+    if (ok) {
+      for (int j = 0; j < A; ++j) {
+        const float ls = log_std[j];
+        const float z = (act[(int64_t)r * A + j] - mu[(int64_t)r * A + j]) * expf(-ls);
+        lp += -0.5f * z * z - ls - 0.918938533204672742f;
+      }
+    }
+    float g_lp = 0.f;
+    if (ok) {
+      const float lo = logp_old[r], a = adv[r];
+      const float ratio = expf(lp - lo);
+      const float s1 = ratio * a;
+      const float s2 = fminf(fmaxf(ratio, 1.0f - clip), 1.0f + clip) * a;
+      s_pl += -fminf(s1, s2);
+      s_kl += lo - lp;
+      s_cf += fabsf(ratio - 1.0f) > clip ? 1.f : 0.f;
+      g_lp = (s1 <= s2) ? -(a * ratio) * inv_m : 0.f;
+      const float dvv = val[r] - ret[r];
+      s_vl += dvv * dvv;
+      if (want_grad) store_elem(dv + (int64_t)r * ld_dv, 2.0f * c_v * dvv * inv_m);
+    }
+    // dL/dmu_j = g_lp * z_j / sigma_j ;  dL/dlog_std_j += g_lp * (z_j^2 - 1)   (wave reduction per j)
+    for (int j = 0; j < A; ++j) {
+      float c = 0.f;
+      if (ok) {
+        const float inv_sigma = expf(-log_std[j]);
+        const float z = (act[(int64_t)r * A + j] - mu[(int64_t)r * A + j]) * inv_sigma;
+        if (want_grad) store_elem(dmu + (int64_t)r * ld_dmu + j, g_lp * z * inv_sigma);
+        c = g_lp * (z * z - 1.0f);
+      }
+      c = wave_sum_f(c);
+      if (lane == 0) s_dls[wave * A + j] += c;
+    }
+  }
+  s_pl = wave_sum_f(s_pl); s_vl = wave_sum_f(s_vl); s_kl = wave_sum_f(s_kl); s_cf = wave_sum_f(s_cf);
+  if (lane == 0) { s_st[wave * 4 + 0] = s_pl; s_st[wave * 4 + 1] = s_vl; s_st[wave * 4 + 2] = s_kl; s_st[wave * 4 + 3] = s_cf; }
+  __syncthreads();
+  float* out = stat_part + (int64_t)blockIdx.x * (gmi::kStatStride + A);
+  if (tid < 4) {
+    const float v = s_st[tid] + s_st[4 + tid] + s_st[8 + tid] + s_st[12 + tid];
+    const int slot = tid == 0 ? 0 : (tid == 1 ? 1 : (tid == 2 ? 3 : 4));
+    out[slot] = v;
+  }
+  if (tid == 4) {
+    float ent = 0.f;
+    if (blockIdx.x == 0)
+      for (int j = 0; j < A; ++j) ent += log_std[j] + 1.418938533204672742f;
+    out[2] = ent;
+  }
+  for (int j = tid; j < A; j += 256)
+    out[gmi::kStatStride + j] = s_dls[j] + s_dls[A + j] + s_dls[2 * A + j] + s_dls[3 * A + j];
+}
+
+struct AdamScalars {
+  float lr, b1, b2, eps, c1, c2;   // c1 = 1 - b1^k, c2 = 1 - b2^k
+};
+
+// One thread per parameter: reduce the gradient partials, Adam, and (BF16) refresh the shadow copies.
+// grad(p) = sum_s part[s * part_stride + p] for p < logstd_off, else the loss kernel's log_std partials
+// minus the entropy coefficient.  Workgroup 0 also finalises the minibatch statistics.
+__global__ __launch_bounds__(256) void adam_kernel(gmi::ShadowTable tab, int write_shadow, float* __restrict__ params,
+                                                   float* __restrict__ am, float* __restrict__ av,
+                                                   const float* __restrict__ part, int n_split, int64_t part_stride,
+                                                   const float* __restrict__ stat_part, int n_loss_blocks, int A,
+                                                   float c_e, float inv_rows, AdamScalars hs, char* __restrict__ shadow,
+                                                   float* __restrict__ stats_out, float* __restrict__ grad_out,
+                                                   int do_update) {
+  const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (blockIdx.x == 0 && threadIdx.x < 5 && stats_out && stat_part) {
+    float s = 0.f;
+    for (int b = 0; b < n_loss_blocks; ++b) s += stat_part[(int64_t)b * (gmi::kStatStride + A) + threadIdx.x];
+    stats_out[threadIdx.x] = threadIdx.x == 2 ? s : s * inv_rows;
+  }
+  if (p >= tab.n_params) return;
+  float g = 0.f;
+  if (p >= tab.logstd_off && stat_part) {
+    const int j = (int)(p - tab.logstd_off);
+    for (int b = 0; b < n_loss_blocks; ++b) g += stat_part[(int64_t)b * (gmi::kStatStride + A) + gmi::kStatStride + j];
+    g -= c_e;
+  } else {
+    for (int s = 0; s < n_split; ++s) g += part[(int64_t)s * part_stride + p];
+  }
+  if (grad_out) grad_out[p] = g;
+  if (!do_update) return;
+  const float m = hs.b1 * am[p] + (1.0f - hs.b1) * g;
+  const float v = hs.b2 * av[p] + (1.0f - hs.b2) * g * g;
+  am[p] = m;
+  av[p] = v;
+  const float w = params[p] - hs.lr * (m / hs.c1) / (sqrtf(v / hs.c2) + hs.eps);
+  params[p] = w;
+  if (!write_shadow) return;
+  if (p >= tab.logstd_off) {
+    reinterpret_cast<float*>(shadow + tab.sh_logstd)[p - tab.logstd_off] = w;
+    return;
+  }
+  int li = 0;
+  while (li + 1 < tab.n && p >= tab.l[li + 1].w_off) ++li;
+  const gmi::ShadowLayer& L = tab.l[li];
+  if (p >= L.b_off) {
+    reinterpret_cast<float*>(shadow + L.sh_b)[p - L.b_off] = w;
+  } else {
+    const int64_t q = p - L.w_off;
+    const int o = (int)(q / L.in), i = (int)(q % L.in);
+    const uint16_t b = f_to_bf16_u(w);
+    reinterpret_cast<uint16_t*>(shadow + L.sh_w)[(int64_t)o * L.in_pad + i] = b;
+    reinterpret_cast<uint16_t*>(shadow + L.sh_wt)[(int64_t)i * L.out_pad + o] = b;
+  }
+}
+
+AdamScalars adam_scalars(const gmi_ppo_hparams* hp, uint32_t k) {
+  AdamScalars s;
+  s.lr = hp->lr; s.b1 = hp->beta1; s.b2 = hp->beta2; s.eps = hp->adam_eps;
+  s.c1 = (float)(1.0 - pow((double)hp->beta1, (double)k));
+  s.c2 = (float)(1.0 - pow((double)hp->beta2, (double)k));
+  return s;
+}
+
+int check_hp(const char* fn, const gmi_ppo_hparams* hp) {
+  if (!hp) GMI_FAIL(GMI_ERR_INVALID_ARG, "%s: hparams is NULL", fn);
+  if (!(hp->clip >= 0.f) || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f))
+    GMI_FAIL(GMI_ERR_INVALID_ARG, "%s: need clip >= 0 and betas in [0,1)", fn);
+  return GMI_OK;
+}
+
+int check_model_buffer(const char* fn, gmi_model_t m, gmi_buffer_t b) {
+  if (m->L.obs_dim != b->d.obs_dim || m->L.act_dim != b->d.act_dim)
+    GMI_FAIL(GMI_ERR_BAD_SHAPE, "%s: model (obs %d, act %d) and buffer (obs %d, act %d) disagree", fn, m->L.obs_dim,
+             m->L.act_dim, b->d.obs_dim, b->d.act_dim);
+  return GMI_OK;
+}
+
+// Forward + loss (+ backward products) of the `rows` samples idx[0..rows) of the buffer.
+// Leaves gradient partials in m->grad_part / m->stat_part.  Returns the split count through n_split.
+int minibatch_pass(hipStream_t s, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx,
+                   int rows, bool want_grad, int* n_split_out, int* n_loss_blocks_out) {
+  const ModelLayout& L = m->L;
+  const bool bf = L.dtype == GMI_DTYPE_BF16;
+  const int A = L.act_dim;
+  int rc = gmi::launch_gather(s, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, &b->d);
+  if (rc != GMI_OK) return rc;
+  rc = gmi::forward_nets(s, m, rows, true, true, m->mu, m->val);
+  if (rc != GMI_OK) return rc;
+  int nlb = (rows + 255) / 256;
+  if (nlb > gmi::kLossBlocksMax) nlb = gmi::kLossBlocksMax;
+  *n_loss_blocks_out = nlb;
+  const float* log_std = bf ? reinterpret_cast<const float*>(m->shadow + L.sh_logstd) : m->params + L.logstd_off;
+  const int head = L.n_layers - 1;
+  const size_t lds = sizeof(float) * (4 * A + 16);
+  if (bf)
+    loss_kernel<uint16_t><<<nlb, 256, lds, s>>>(rows, A, m->mu, m->val, m->mb_act, m->mb_logp, m->mb_adv, m->mb_ret,
+                                                log_std, hp->clip, hp->c_v, want_grad ? 1 : 0,
+                                                (uint16_t*)m->dz[0][head], L.net[0][head].out_pad,
+                                                (uint16_t*)m->dz[1][head], L.net[1][head].out_pad, m->stat_part);
+  else
+    loss_kernel<float><<<nlb, 256, lds, s>>>(rows, A, m->mu, m->val, m->mb_act, m->mb_logp, m->mb_adv, m->mb_ret,
+                                             log_std, hp->clip, hp->c_v, want_grad ? 1 : 0, (float*)m->dz[0][head],
+                                             L.net[0][head].out_pad, (float*)m->dz[1][head], L.net[1][head].out_pad,
+                                             m->stat_part);
+  GMI_LAUNCH_CHECK();
+  if (!want_grad) return GMI_OK;
+
+  // input gradients, head to first hidden layer: dz[l-1] = (dz[l] W_l) * ELU'(h[l])
+  for (int l = L.n_layers - 1; l >= 1; --l) {
+    gmi::LinearBatch lb;
+    lb.n = 2;
+    for (int net = 0; net < 2; ++net) {
+      const LayerInfo& li = L.net[net][l];
+      gmi::LinearProblem& p = lb.p[net];
+      p.x = m->dz[net][l]; p.ldx = li.out_pad;
+      if (bf) {
+        p.w = m->shadow + li.sh_wt; p.ldw = li.out_pad; p.wsf = li.out_pad; p.wsk = 1;
+        p.K = li.out_pad; p.F = li.in_pad;
+      } else {
+        p.w = m->params + li.w_off; p.ldw = li.in; p.wsf = 1; p.wsk = li.in;
+        p.K = li.out; p.F = li.in;
+      }
+      p.bias = nullptr;
+      p.h = m->h[net][l]; p.ldh = li.in_pad;
+      p.y = m->dz[net][l - 1]; p.ldy = li.in_pad;
+      p.F_store = p.F;
+    }
+    rc = gmi::launch_linear(s, L.dtype, gmi::kEpiEluGrad, rows, lb);
+    if (rc != GMI_OK) return rc;
+  }
+  // weight / bias gradients of every layer of both nets in one launch
+  int n_split = (rows + 63) / 64;
+  if (n_split > gmi::kSplitMax) n_split = gmi::kSplitMax;
+  if (n_split < 1) n_split = 1;
+  int chunk = (rows + n_split - 1) / n_split;
+  chunk = (chunk + 63) / 64 * 64;
+  *n_split_out = n_split;
+  gmi::WgradBatch wb;
+  wb.n = 0;
+  for (int net = 0; net < 2; ++net)
+    for (int l = 0; l < L.n_layers; ++l) {
+      const LayerInfo& li = L.net[net][l];
+      gmi::WgradProblem& p = wb.p[wb.n++];
+      p.dz = m->dz[net][l]; p.lddz = li.out_pad;
+      p.x = m->h[net][l]; p.ldx = li.in_pad;
+      p.out = li.out; p.in = li.in; p.out_pad = li.out_pad; p.in_pad = li.in_pad;
+      p.w_off = li.w_off; p.b_off = li.b_off;
+    }
+  return gmi::launch_wgrad(s, L.dtype, rows, n_split, chunk, wb, m->grad_part, L.n_params);
+}
+
+int launch_adam(hipStream_t s, gmi_model* m, int n_split, int n_loss_blocks, const gmi_ppo_hparams* hp, int rows,
+                uint32_t k, float* stats_out, float* grad_out, bool do_update) {
+  const gmi::ShadowTable tab = gmi::make_shadow_table(m->L);
+  const unsigned grid = (unsigned)((m->L.n_params + 255) / 256);
+  adam_kernel<<<grid, 256, 0, s>>>(tab, m->L.dtype == GMI_DTYPE_BF16 ? 1 : 0, m->params, m->adam_m, m->adam_v,
+                                   m->grad_part, n_split, m->L.n_params, m->stat_part, n_loss_blocks, m->L.act_dim,
+                                   hp->c_e, 1.0f / (float)rows, adam_scalars(hp, k), m->shadow, stats_out, grad_out,
+                                   do_update ? 1 : 0);
+  GMI_LAUNCH_CHECK();
+  return GMI_OK;
+}
+
+}  // namespace
+
+extern "C" int ppo_update(gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_ppo_hparams* hp, float* stats_out) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "ppo_update: bad instance");
+  if (!valid(m)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "ppo_update: bad model");
+  if (!valid(b)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "ppo_update: bad buffer");
+  int rc = check_hp("ppo_update", hp);
+  if (rc != GMI_OK) return rc;
+  rc = check_model_buffer("ppo_update", m, b);
+  if (rc != GMI_OK) return rc;
+  if (!m->adam_m) GMI_FAIL(GMI_ERR_INVALID_ARG, "ppo_update: the model binding has no Adam state");
+  const int64_t B = (int64_t)b->d.horizon * b->d.n_envs;
+  if (hp->epochs < 0 || hp->minibatch < 1) GMI_FAIL(GMI_ERR_INVALID_ARG, "ppo_update: epochs >= 0 and minibatch >= 1");
+  if (B == 0 || hp->epochs == 0) return GMI_OK;
+  if (B % hp->minibatch != 0)
+    GMI_FAIL(GMI_ERR_BAD_SHAPE, "ppo_update: minibatch %d does not divide T*N = %lld", hp->minibatch, (long long)B);
+  if (hp->minibatch > m->max_rows)
+    GMI_FAIL(GMI_ERR_BAD_SHAPE, "ppo_update: minibatch %d exceeds the binding's max_rows %d", hp->minibatch, m->max_rows);
+  const int nmb = (int)(B / hp->minibatch);
+  uint32_t k = hp->adam_step0;
+  for (int e = 0; e < hp->epochs; ++e) {
+    rc = gmi::launch_permutation(g->stream, (int)B, hp->seed, hp->iteration, (uint32_t)e, b->perm);
+    if (rc != GMI_OK) return rc;
+    for (int j = 0; j < nmb; ++j) {
+      int n_split = 1, nlb = 1;
+      rc = minibatch_pass(g->stream, m, b, hp, b->perm + (int64_t)j * hp->minibatch, hp->minibatch, true, &n_split, &nlb);
+      if (rc != GMI_OK) return rc;
+      ++k;
+      rc = launch_adam(g->stream, m, n_split, nlb, hp, hp->minibatch, k,
+                       stats_out ? stats_out + 5 * ((int64_t)e * nmb + j) : nullptr, nullptr, true);
+      if (rc != GMI_OK) return rc;
+    }
+  }
+  return GMI_OK;
+}
+
+static int check_idx_call(const char* fn, gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_ppo_hparams* hp,
+                          const int32_t* idx, int32_t n) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "%s: bad instance", fn);
+  if (!valid(m)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "%s: bad model", fn);
+  if (!valid(b)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "%s: bad buffer", fn);
+  int rc = check_hp(fn, hp);
+  if (rc != GMI_OK) return rc;
+  rc = check_model_buffer(fn, m, b);
+  if (rc != GMI_OK) return rc;
+  if (n < 1 || n > m->max_rows) GMI_FAIL(GMI_ERR_BAD_SHAPE, "%s: n=%d outside [1, max_rows=%d]", fn, n, m->max_rows);
+  if (!idx) GMI_FAIL(GMI_ERR_INVALID_ARG, "%s: idx is NULL", fn);
+  return GMI_OK;
+}
+
+extern "C" int ppo_evaluate(gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_ppo_hparams* hp, const int32_t* idx,
+                            int32_t n, float* stats_out) {
+  int rc = check_idx_call("ppo_evaluate", g, m, b, hp, idx, n);
+  if (rc != GMI_OK) return rc;
+  if (!stats_out) GMI_FAIL(GMI_ERR_INVALID_ARG, "ppo_evaluate: stats_out is NULL");
+  int n_split = 0, nlb = 1;
+  rc = minibatch_pass(g->stream, m, b, hp, idx, n, false, &n_split, &nlb);
+  if (rc != GMI_OK) return rc;
+  return launch_adam(g->stream, m, 0, nlb, hp, n, 1, stats_out, nullptr, false);
+}
+
+extern "C" int ppo_gradient(gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_ppo_hparams* hp, const int32_t* idx,
+                            int32_t n, float* grad_out, float* stats_out) {
+  int rc = check_idx_call("ppo_gradient", g, m, b, hp, idx, n);
+  if (rc != GMI_OK) return rc;
+  if (!grad_out) GMI_FAIL(GMI_ERR_INVALID_ARG, "ppo_gradient: grad_out is NULL");
+  int n_split = 1, nlb = 1;
+  rc = minibatch_pass(g->stream, m, b, hp, idx, n, true, &n_split, &nlb);
+  if (rc != GMI_OK) return rc;
+  return launch_adam(g->stream, m, n_split, nlb, hp, n, 1, stats_out, grad_out, false);
+}
+
+extern "C" int adam_update(gmi_t g, float* params, float* adam_m, float* adam_v, const float* grad, int64_t n,
+                           const gmi_ppo_hparams* hp, uint32_t step) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "adam_update: bad instance");
+  int rc = check_hp("adam_update", hp);
+  if (rc != GMI_OK) return rc;
+  if (n < 0) GMI_FAIL(GMI_ERR_BAD_SHAPE, "adam_update: negative n");
+  if (n == 0) return GMI_OK;
+  if (step < 1) GMI_FAIL(GMI_ERR_INVALID_ARG, "adam_update: step is 1-based");
+  if (!params || !adam_m || !adam_v || !grad) GMI_FAIL(GMI_ERR_INVALID_ARG, "adam_update: NULL pointer");
+  gmi::ShadowTable tab;
+  tab.n = 0;
+  tab.logstd_off = n;
+  tab.sh_logstd = 0;
+  tab.act_dim = 0;
+  tab.n_params = n;
+  adam_kernel<<<(unsigned)((n + 255) / 256), 256, 0, g->stream>>>(tab, 0, params, adam_m, adam_v, grad, 1, n, nullptr, 0,
+                                                                0, 0.f, 1.f, adam_scalars(hp, step), nullptr, nullptr,
+                                                                nullptr, 1);
+  GMI_LAUNCH_CHECK();
+  return GMI_OK;
+}
