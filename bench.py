@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the PPO agent/trainer hot path on one MI355X.
+
+A "step" is one whole PPO iteration over one batch of synthetic experience: T rounds of
+[agent_act -> env_step -> collect_experience], the bootstrap value, gae_compute, and ppo_update
+(E epochs of shuffled minibatches: forward, loss, backward, Adam).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_FP32_TFLOPS = 157.3       # vector fp32
+
+
+def mac_per_sample(cfg, first_layer=True):
+    """Multiply-accumulates of one forward of both nets for one sample (unpadded)."""
+    total = 0
+    for out_dim in (cfg.act_dim, 1):
+        prev = cfg.obs_dim
+        for li, h in enumerate(list(cfg.hidden) + [out_dim]):
+            if first_layer or li > 0:
+                total += prev * h
+            prev = h
+    return total
+
+
+def class_work(cfg, n_params):
+    """Algorithmic work per *step* of every kernel class: (flops, bytes, launches, bound)."""
+    N, T, B, MB, E = cfg.n_envs, cfg.horizon, cfg.batch, cfg.minibatch, cfg.epochs
+    O, A, L = cfg.obs_dim, cfg.act_dim, len(cfg.hidden)
+    mac = mac_per_sample(cfg)
+    mac_dgrad = mac_per_sample(cfg, first_layer=False)        # no input gradient for the first layer
+    mac_value = sum(a * b for a, b in zip([O] + list(cfg.hidden), list(cfg.hidden) + [1]))
+    n_upd = E * (B // MB)
+    es = 2 if cfg.dtype == "bf16" else 4
+    width = sum(cfg.hidden)
+    return {
+        # forward launches: T agent_act + 1 bootstrap (value net only) + one per update, L+1 layers each
+        "linear_fwd": dict(flops=2.0 * (T * N * mac + N * mac_value + n_upd * MB * mac),
+                           launches=(T + 1 + n_upd) * (L + 1), bound="mfma"),
+        "linear_dgrad": dict(flops=2.0 * n_upd * MB * mac_dgrad, launches=n_upd * L, bound="mfma"),
+        "wgrad": dict(flops=2.0 * n_upd * MB * mac, launches=n_upd, bound="mfma"),
+        "gather": dict(bytes=(T + 1) * N * O * (4 + es) + n_upd * MB * (O * (4 + es) + 8.0 * (A + 3) + 4),
+                       launches=T + 1 + n_upd, bound="hbm"),
+        "loss": dict(bytes=n_upd * MB * (4.0 * (2 * A + 5) + es * (A + 1)), launches=n_upd, bound="hbm"),
+        "adam": dict(bytes=n_upd * n_params * (16.0 + 12.0 + (4 if cfg.dtype == "bf16" else 0)),
+                     launches=n_upd, bound="hbm"),
+        "env_step": dict(bytes=T * N * (4.0 * (2 * O + A) + 8 + 1), flops=T * N * (2.0 * O * (O + A) + 3 * O + 2 * A),
+                         launches=T, bound="hbm"),
+        "sample": dict(bytes=T * N * 4.0 * (2 * A + 1), launches=T, bound="hbm"),
+        "collect": dict(bytes=T * N * 2 * (4.0 * (O + A + 3) + 1), launches=T, bound="hbm"),
+        "gae": dict(bytes=B * (9.0 + 8.0 + 8.0) + 4.0 * N, launches=1, bound="hbm"),
+        "permutation": dict(bytes=E * B * 4.0, launches=E, bound="hbm"),
+    }
+
+
+def cpu_baseline(cfg, budget_s=12.0):
+    """The numpy oracle, as it stands, on the host cores: whole iterations of the same workload."""
+    import numpy as np
+
+    from oracle import ppo as oppo
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_util import oracle_pieces
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    shape, theta, env, state0, hp = oracle_pieces(cfg)
+    z = np.zeros_like(theta)
+    n_it, t0 = 0, time.perf_counter()
+    m, v, k = z, z, 0
+    while True:
+        out = oppo.ppo_iteration(theta, m, v, k, shape, env, state0, np.zeros(cfg.n_envs, np.uint32), cfg.horizon,
+                                 hp, cfg.gamma, cfg.lam, cfg.seed, n_it)
+        theta, m, v, k = out["theta"], out["m"], out["v"], out["k"]
+        n_it += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or el * (n_it + 1) / n_it > 2.5 * budget_s:
+            break
+    return {"value": n_it * cfg.batch / el, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n_it} whole iteration(s) of {cfg.name} ({cfg.batch} samples each, fresh reset) in {el:.1f} s, "
+                      "numpy fp32 with its BLAS threads"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="C2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (its instances are CU-masked streams of one device); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2206_08482_amd as g
+    from paper_2206_08482_amd.runner import PPOSession
+    from workloads import synthetic as syn
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+    cfg = syn.get_config(args.config)
+    if cfg.n_agents != 1:
+        print("bench.py: multi-instance configurations are measured by bench_instances.py", file=sys.stderr)
+        return 2
+    theta = syn.make_model_params(cfg.obs_dim, cfg.act_dim, cfg.hidden, cfg.seed)
+    a_mat, b_mat = syn.make_env_matrices(cfg.obs_dim, cfg.act_dim, cfg.seed)
+    state0 = syn.make_initial_state(cfg.n_envs, cfg.obs_dim, cfg.seed)
+    thr = (1 << 32) // cfg.done_prob_inv if cfg.done_prob_inv else 0
+    ses = PPOSession(n_envs=cfg.n_envs, obs_dim=cfg.obs_dim, act_dim=cfg.act_dim, hidden=cfg.hidden,
+                     horizon=cfg.horizon, dtype=cfg.dtype, theta=theta, a_mat=a_mat, b_mat=b_mat, state0=state0,
+                     noise_std=cfg.noise_std, reward_scale=cfg.reward_scale, done_period=cfg.done_period,
+                     done_threshold=thr, seed=cfg.seed, minibatch=cfg.minibatch)
+    s0 = torch.tensor(state0, device="cuda:0")
+    ep0 = torch.zeros(cfg.n_envs, dtype=torch.int32, device="cuda:0")
+    torch.cuda.synchronize()
+    hp = dict(clip=cfg.clip, c_v=cfg.c_v, c_e=cfg.c_e, lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2,
+              adam_eps=cfg.adam_eps)
+
+    def step(it: int) -> None:
+        # fresh reset of the environments (the synthetic dynamics are unstable over long horizons):
+        # two small device-to-device copies on the instance's own stream, inside the timed region
+        g.gmi_transfer(ses.gmi, ses.gmi, s0, ses.obs[ses.cur], s0.numel() * 4)
+        g.gmi_transfer(ses.gmi, ses.gmi, ep0, ses.episode_step, ep0.numel() * 4)
+        ses.rollout(it)
+        ses.gae(cfg.gamma, cfg.lam, True)
+        ses.update(it, epochs=cfg.epochs, minibatch=cfg.minibatch, **hp)
+
+    n_cls = g.gmi_profile_classes()
+    names = [g.gmi_profile_class_name(c) for c in range(n_cls)]
+    it = 0
+    for _ in range(max(args.warmup - 1, 0)):
+        step(it); it += 1
+    # last warm-up step with every class timed: finds the kernel class that dominates the step
+    g.gmi_profile_enable(ses.gmi, (1 << n_cls) - 1)
+    step(it); it += 1
+    per_class = {names[c]: g.gmi_profile_read(ses.gmi, c) for c in range(n_cls)}
+    dominant = max(per_class, key=lambda k: per_class[k][0])
+    g.gmi_profile_enable(ses.gmi, 1 << names.index(dominant))
+
+    ses.sync(); torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(it); it += 1
+    ses.sync(); torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dom_ms, dom_launches = g.gmi_profile_read(ses.gmi, names.index(dominant))
+    g.gmi_profile_enable(ses.gmi, 0)
+    assert torch.isfinite(ses.theta).all().item(), "parameters are not finite after the timed steps"
+
+    # rollout alone (env-steps/s), untimed part of the report
+    ses.sync()
+    r0 = time.perf_counter()
+    for _ in range(max(1, args.steps // 2)):
+        g.gmi_transfer(ses.gmi, ses.gmi, s0, ses.obs[ses.cur], s0.numel() * 4)
+        ses.rollout(it); it += 1
+    ses.sync()
+    r1 = time.perf_counter()
+    env_steps_per_s = max(1, args.steps // 2) * cfg.batch / (r1 - r0)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = args.steps * cfg.batch / (t1 - t0)
+    work = class_work(cfg, int(ses.theta.numel()))
+    w = work[dominant]
+    avg_ms = dom_ms / max(dom_launches, 1)
+    launches_per_step = w["launches"]
+    if w["bound"] == "mfma":
+        achieved = w["flops"] / launches_per_step / (avg_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS,
+                "unit": "TFLOP/s"}
+    else:
+        achieved = w["bytes"] / launches_per_step / (avg_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = dominant
+    roof["avg_launch_us"] = avg_ms * 1e3
+    roof["launches_timed"] = dom_launches
+
+    total_ms = sum(v[0] for v in per_class.values())
+    breakdown = {k: {"ms_per_step": round(v[0], 4), "launches": v[1]} for k, v in per_class.items() if v[1]}
+    flops_step = sum(x.get("flops", 0.0) for k, x in work.items() if x["bound"] == "mfma")
+    out = {
+        "metric": "PPO samples/sec (rollout+update) on 1 MI355X",
+        "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.n_envs} envs, obs {cfg.obs_dim}, act {cfg.act_dim}, MLP "
+                               f"{list(cfg.hidden)} ELU x2 nets, horizon {cfg.horizon}, {cfg.epochs} epochs, "
+                               f"minibatch {cfg.minibatch}, linear-Gaussian env, one unmasked instance",
+                   "samples_per_step": cfg.batch},
+        "roofline": roof,
+        "env_steps_per_s": env_steps_per_s,
+        "mlp_gemm_tflops_whole_step": flops_step / (ms_per_step * 1e-3) / 1e12,
+        "kernel_ms_in_profiled_step": breakdown,
+        "kernel_ms_sum": total_ms,
+        "paper_context": "GMI-DRL reports up to 2.81x over Isaac Gym+NCCL on DGX-A100 (different hardware, env, baseline)",
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    ses.close()
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

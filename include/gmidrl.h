@@ -243,6 +243,21 @@ int gmi_noise_fill(gmi_t gmi, uint64_t seed, uint32_t stream, uint32_t step, uin
 int gmi_permutation(gmi_t gmi, int32_t n, uint64_t seed, uint32_t iteration, uint32_t epoch,
                     int32_t* out);
 
+/* ------------------------------------------------------------------ per-launch timing ------- */
+
+/* Built-in timer for measurement runs (the paper's profile() step of Algorithm 2 measures a trial
+ * run; here the unit is one kernel class).  class_mask bit c = 1: every launch of kernel class c on
+ * this instance is bracketed by a pair of HIP timing events on the instance's stream.  Enabling (or
+ * passing 0 to disable) synchronises the stream and clears earlier measurements.  Event pairs are
+ * created on demand, so a profiled call may allocate host-side event objects. */
+int gmi_profile_enable(gmi_t gmi, uint32_t class_mask);
+/* Number of kernel classes, and the name of class cls (NULL if out of range). */
+int gmi_profile_classes(void);
+const char* gmi_profile_class_name(int cls);
+/* Synchronises the stream and returns the summed duration (ms) and the number of bracketed
+ * launches of class cls since profiling was enabled.  host: total_ms, launches. */
+int gmi_profile_read(gmi_t gmi, int cls, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

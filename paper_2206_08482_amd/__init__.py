@@ -24,7 +24,7 @@ EXPORTS = [
     "gmi_model_destroy", "gmi_model_refresh_shadow", "gmi_env_bind", "gmi_env_destroy", "env_step",
     "agent_act", "agent_value", "gmi_buffer_bind", "gmi_buffer_destroy", "collect_experience",
     "gae_compute", "ppo_update", "ppo_evaluate", "ppo_gradient", "adam_update", "gmi_noise_fill",
-    "gmi_permutation",
+    "gmi_permutation", "gmi_profile_enable", "gmi_profile_classes", "gmi_profile_class_name", "gmi_profile_read",
 ]
 
 
@@ -93,6 +93,10 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "adam_update": (C.c_int, [vp, vp, vp, vp, vp, i64, C.POINTER(PPOHparams), u32]),
         "gmi_noise_fill": (C.c_int, [vp, u64, u32, u32, u32, i32, i32, vp]),
         "gmi_permutation": (C.c_int, [vp, i32, u64, u32, u32, vp]),
+        "gmi_profile_enable": (C.c_int, [vp, u32]),
+        "gmi_profile_classes": (C.c_int, []),
+        "gmi_profile_class_name": (C.c_char_p, [C.c_int]),
+        "gmi_profile_read": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -304,3 +308,28 @@ def gmi_noise_fill(gmi: int, seed: int, stream: int, step: int, env_offset: int,
 
 def gmi_permutation(gmi: int, n: int, seed: int, iteration: int, epoch: int, out) -> None:
     _check(_lib.gmi_permutation(gmi, n, seed, iteration, epoch, _ptr(out)))
+
+
+# ---------------------------------------------------------------- per-launch timing
+def gmi_profile_classes() -> int:
+    return _lib.gmi_profile_classes()
+
+
+def gmi_profile_class_name(cls: int) -> Optional[str]:
+    n = _lib.gmi_profile_class_name(cls)
+    return n.decode() if n else None
+
+
+def gmi_profile_enable(gmi: int, class_mask: int) -> None:
+    _check(_lib.gmi_profile_enable(gmi, class_mask))
+
+
+def gmi_profile_read(gmi: int, cls: int):
+    """(total milliseconds, launches) of kernel class `cls` since profiling was enabled."""
+    ms, n = C.c_double(), C.c_int64()
+    _check(_lib.gmi_profile_read(gmi, cls, C.byref(ms), C.byref(n)))
+    return ms.value, n.value
+
+
+def dtype_code(name: str) -> int:
+    return {"f32": DTYPE_F32, "bf16": DTYPE_BF16}[name]

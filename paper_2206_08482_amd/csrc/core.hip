@@ -17,6 +17,59 @@ void set_error(const char* fmt, ...) {
 
 extern "C" const char* gmi_last_error(void) { return gmi::g_err; }
 
+namespace gmi {
+ProfScope::ProfScope(gmi_instance* g_, int cls_) : g(g_), cls(cls_), on(false) {
+  if (!(g->prof_mask & (1u << cls))) return;
+  ProfSlot& s = g->prof[cls];
+  if (s.used == s.start.size()) {
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess) return;
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+    s.start.push_back(a);
+    s.stop.push_back(b);
+  }
+  on = hipEventRecord(s.start[s.used], g->stream) == hipSuccess;
+}
+ProfScope::~ProfScope() {
+  if (!on) return;
+  ProfSlot& s = g->prof[cls];
+  if (hipEventRecord(s.stop[s.used], g->stream) == hipSuccess) ++s.used;
+}
+static const char* kClassNames[kClsCount] = {"gather", "linear_fwd", "linear_dgrad", "wgrad", "loss", "adam",
+                                             "env_step", "sample", "collect", "gae", "permutation"};
+}  // namespace gmi
+
+extern "C" int gmi_profile_enable(gmi_t g, uint32_t class_mask) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_profile_enable: bad handle");
+  GMI_HIP(hipStreamSynchronize(g->stream));
+  g->prof_mask = class_mask & ((1u << gmi::kClsCount) - 1u);
+  for (int c = 0; c < gmi::kClsCount; ++c) g->prof[c].used = 0;
+  return GMI_OK;
+}
+
+extern "C" int gmi_profile_classes(void) { return gmi::kClsCount; }
+
+extern "C" const char* gmi_profile_class_name(int cls) {
+  return (cls >= 0 && cls < gmi::kClsCount) ? gmi::kClassNames[cls] : nullptr;
+}
+
+extern "C" int gmi_profile_read(gmi_t g, int cls, double* total_ms, int64_t* launches) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_profile_read: bad handle");
+  if (cls < 0 || cls >= gmi::kClsCount) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_profile_read: class %d out of range", cls);
+  if (!total_ms || !launches) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_profile_read: NULL output");
+  GMI_HIP(hipStreamSynchronize(g->stream));
+  gmi::ProfSlot& s = g->prof[cls];
+  double sum = 0.0;
+  for (size_t i = 0; i < s.used; ++i) {
+    float ms = 0.f;
+    GMI_HIP(hipEventElapsedTime(&ms, s.start[i], s.stop[i]));
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = (int64_t)s.used;
+  return GMI_OK;
+}
+
 extern "C" int gmi_create(const uint32_t* cu_mask, uint32_t n_words, int device, gmi_t* out) {
   if (!out) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_create: out is NULL");
   *out = nullptr;
@@ -56,6 +109,7 @@ extern "C" int gmi_create(const uint32_t* cu_mask, uint32_t n_words, int device,
   g->device = device;
   g->stream = stream;
   g->cu_count = cu_count;
+  g->prof_mask = 0;
   hipError_t e = hipEventCreateWithFlags(&g->event, hipEventDisableTiming);
   if (e != hipSuccess) {
     hipStreamDestroy(stream);
@@ -68,9 +122,14 @@ extern "C" int gmi_create(const uint32_t* cu_mask, uint32_t n_words, int device,
 
 extern "C" int gmi_destroy(gmi_t g) {
   if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_destroy: bad handle");
-  hipStreamSynchronize(g->stream);
-  hipEventDestroy(g->event);
-  hipStreamDestroy(g->stream);
+  (void)hipStreamSynchronize(g->stream);
+  for (int c = 0; c < gmi::kClsCount; ++c)
+    for (size_t i = 0; i < g->prof[c].start.size(); ++i) {
+      (void)hipEventDestroy(g->prof[c].start[i]);
+      (void)hipEventDestroy(g->prof[c].stop[i]);
+    }
+  (void)hipEventDestroy(g->event);
+  (void)hipStreamDestroy(g->stream);
   g->magic = 0;
   delete g;
   return GMI_OK;
@@ -131,8 +190,10 @@ __global__ void permutation_kernel(int n, int bits, uint32_t iteration, uint32_t
 }  // namespace
 
 namespace gmi {
-int launch_permutation(hipStream_t s, int n, uint64_t seed, uint32_t iteration, uint32_t epoch, int32_t* out) {
+int launch_permutation(gmi_instance* g, int n, uint64_t seed, uint32_t iteration, uint32_t epoch, int32_t* out) {
   if (n <= 0) return GMI_OK;
+  ProfScope ps(g, kClsPermutation);
+  hipStream_t s = g->stream;
   int bits = 0;
   while ((1ll << bits) < (long long)n) ++bits;
   permutation_kernel<<<(n + 255) / 256, 256, 0, s>>>(n, bits, iteration, epoch, (uint32_t)seed,
@@ -162,5 +223,5 @@ extern "C" int gmi_permutation(gmi_t g, int32_t n, uint64_t seed, uint32_t itera
   if (n < 0) GMI_FAIL(GMI_ERR_BAD_SHAPE, "gmi_permutation: negative n");
   if (n == 0) return GMI_OK;
   if (!out) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_permutation: out is NULL");
-  return gmi::launch_permutation(g->stream, n, seed, iteration, epoch, out);
+  return gmi::launch_permutation(g, n, seed, iteration, epoch, out);
 }

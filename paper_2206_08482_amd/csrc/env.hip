@@ -151,7 +151,7 @@ extern "C" int gmi_env_bind(gmi_t g, const gmi_env_desc* d, const float* a_mat, 
   hipError_t e = hipGetLastError();
   if (e == hipSuccess) e = hipStreamSynchronize(g->stream);
   if (e != hipSuccess) {
-    hipFree(m_t);
+    (void)hipFree(m_t);
     GMI_FAIL(GMI_ERR_HIP, "gmi_env_bind: building the transposed matrix failed: %s", hipGetErrorString(e));
   }
   gmi_env* env = new gmi_env();
@@ -165,7 +165,7 @@ extern "C" int gmi_env_bind(gmi_t g, const gmi_env_desc* d, const float* a_mat, 
 
 extern "C" int gmi_env_destroy(gmi_env_t env) {
   if (!valid(env)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_env_destroy: bad handle");
-  hipFree(env->m_t);
+  (void)hipFree(env->m_t);
   env->magic = 0;
   delete env;
   return GMI_OK;
@@ -194,6 +194,7 @@ extern "C" int env_step(gmi_t g, gmi_env_t env, const float* obs, const float* a
   const unsigned grid = (unsigned)((N + EB - 1) / EB);
   const int vec_store = ((O & 3) == 0) && (((uintptr_t)next_obs & 15) == 0);
   const uint32_t k0 = (uint32_t)d.seed, k1 = (uint32_t)(d.seed >> 32);
+  gmi::ProfScope ps(g, gmi::kClsEnvStep);
 #define GMI_ENV_LAUNCH(E)                                                                          \
   env_step_kernel<E><<<grid, 256, lds_bytes(E), g->stream>>>(                                      \
       obs, act, env->m_t, env->episode_step, next_obs, reward, done, N, O, A, o4, nb, G,          \

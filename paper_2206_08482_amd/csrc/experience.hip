@@ -126,7 +126,7 @@ extern "C" int gmi_buffer_bind(gmi_t g, const gmi_buffer_desc* d, gmi_buffer_t* 
     hipError_t e = hipMalloc(&b->part, sizeof(double) * 2 * (size_t)b->n_part);
     if (e == hipSuccess && d->horizon > 0) {
       e = hipMalloc(&b->perm, sizeof(int32_t) * (size_t)d->horizon * d->n_envs);
-      if (e != hipSuccess) hipFree(b->part);
+      if (e != hipSuccess) (void)hipFree(b->part);
     }
     if (e != hipSuccess) {
       delete b;
@@ -139,8 +139,8 @@ extern "C" int gmi_buffer_bind(gmi_t g, const gmi_buffer_desc* d, gmi_buffer_t* 
 
 extern "C" int gmi_buffer_destroy(gmi_buffer_t b) {
   if (!valid(b)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_buffer_destroy: bad handle");
-  if (b->part) hipFree(b->part);
-  if (b->perm) hipFree(b->perm);
+  if (b->part) (void)hipFree(b->part);
+  if (b->perm) (void)hipFree(b->perm);
   b->magic = 0;
   delete b;
   return GMI_OK;
@@ -155,6 +155,7 @@ extern "C" int collect_experience(gmi_t g, gmi_buffer_t b, int32_t t, const floa
   if (b->d.n_envs == 0) return GMI_OK;
   if (!obs || !act || !logp || !value || !reward || !done) GMI_FAIL(GMI_ERR_INVALID_ARG, "collect_experience: NULL pointer");
   const int64_t total = (int64_t)b->d.n_envs * (b->d.obs_dim + b->d.act_dim + 4);
+  gmi::ProfScope ps(g, gmi::kClsCollect);
   collect_kernel<<<(unsigned)((total + 255) / 256), 256, 0, g->stream>>>(b->d, t, obs, act, logp, value, reward, done);
   GMI_LAUNCH_CHECK();
   return GMI_OK;
@@ -166,6 +167,7 @@ extern "C" int gae_compute(gmi_t g, gmi_buffer_t b, const float* last_value, flo
   if (!valid(b)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gae_compute: bad buffer");
   if (b->d.n_envs == 0 || b->d.horizon == 0) return GMI_OK;
   if (!last_value) GMI_FAIL(GMI_ERR_INVALID_ARG, "gae_compute: last_value is NULL");
+  gmi::ProfScope ps(g, gmi::kClsGae);
   gae_kernel<<<b->n_part, 256, 0, g->stream>>>(b->d, last_value, gamma, gamma * lambda,
                                                normalize ? b->part : nullptr);
   GMI_LAUNCH_CHECK();

@@ -49,13 +49,39 @@ static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * 
 
 }  // namespace gmi
 
+namespace gmi {
+// Kernel classes of the built-in per-launch timer (gmi_profile_*).
+enum KernelClass {
+  kClsGather = 0, kClsLinearFwd, kClsLinearDgrad, kClsWgrad, kClsLoss, kClsAdam, kClsEnvStep, kClsSample,
+  kClsCollect, kClsGae, kClsPermutation, kClsCount
+};
+struct ProfSlot {
+  std::vector<hipEvent_t> start, stop;
+  size_t used = 0;
+};
+}  // namespace gmi
+
 struct gmi_instance {
   uint32_t magic;
   int device;
   hipStream_t stream;
   hipEvent_t event;      // used by gmi_transfer
   int cu_count;
+  uint32_t prof_mask;    // bit c set: launches of kernel class c are bracketed by timing events
+  gmi::ProfSlot prof[gmi::kClsCount];
 };
+
+namespace gmi {
+// Brackets the kernel launches issued inside its scope with a pair of timing events when the
+// instance has profiling enabled for the class; otherwise does nothing.
+struct ProfScope {
+  gmi_instance* g;
+  int cls;
+  bool on;
+  ProfScope(gmi_instance* g_, int cls_);
+  ~ProfScope();
+};
+}  // namespace gmi
 
 // One linear layer of one net.
 struct LayerInfo {
@@ -151,7 +177,7 @@ struct LinearBatch {
   LinearProblem p[2];
 };
 
-int launch_linear(hipStream_t s, int dtype, int epi, int rows, const LinearBatch& batch);
+int launch_linear(gmi_instance* g, int dtype, int epi, int rows, const LinearBatch& batch);
 
 // dW[o, i] = sum_r dz[r, o] * x[r, i],  db[o] = sum_r dz[r, o], reduced over row splits:
 // split sp covers rows [sp*chunk, min(rows, (sp+1)*chunk)) and writes
@@ -168,7 +194,7 @@ struct WgradBatch {
   WgradProblem p[kMaxWgradProblems];
   int blk_start[kMaxWgradProblems + 1];
 };
-int launch_wgrad(hipStream_t s, int dtype, int rows, int n_split, int chunk, WgradBatch& batch,
+int launch_wgrad(gmi_instance* g, int dtype, int rows, int n_split, int chunk, WgradBatch& batch,
                  float* part, int64_t part_stride);
 
 }  // namespace gmi
@@ -182,15 +208,15 @@ static inline size_t elem_size(int dtype) { return dtype == GMI_DTYPE_BF16 ? 2 :
 // x0[r, :] <- obs of sample idx[r] (identity when idx == NULL), converted to the model's element
 // type, zero padded to the padded width; optionally also gathers act / logp / adv / ret rows.
 // Sample s of a buffer lives at slot (s / n_envs) * ld_envs + s % n_envs.
-int launch_gather(hipStream_t s, gmi_model* m, const float* obs, int n_envs, int ld_envs,
+int launch_gather(gmi_instance* g, gmi_model* m, const float* obs, int n_envs, int ld_envs,
                   const int32_t* idx, int rows, const gmi_buffer_desc* extras);
 
 // Runs both nets (or only the value net) on the rows staged in m->x0; keeps hidden activations in
 // m->h[net][l]; writes m->mu [rows, A] and m->val [rows].
-int forward_nets(hipStream_t s, gmi_model* m, int rows, bool policy, bool value, float* mu_dst,
+int forward_nets(gmi_instance* g, gmi_model* m, int rows, bool policy, bool value, float* mu_dst,
                  float* val_dst);
 
-int launch_permutation(hipStream_t s, int n, uint64_t seed, uint32_t iteration, uint32_t epoch, int32_t* out);
+int launch_permutation(gmi_instance* g, int n, uint64_t seed, uint32_t iteration, uint32_t epoch, int32_t* out);
 
 }  // namespace gmi
 

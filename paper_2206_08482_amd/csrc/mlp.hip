@@ -346,8 +346,10 @@ int launch_bf16_cfg(hipStream_t s, int epi, int rows, const gmi::LinearBatch& b,
 
 namespace gmi {
 
-int launch_linear(hipStream_t s, int dtype, int epi, int rows, const LinearBatch& b) {
+int launch_linear(gmi_instance* g, int dtype, int epi, int rows, const LinearBatch& b) {
   if (rows <= 0 || b.n <= 0) return GMI_OK;
+  ProfScope ps(g, epi == kEpiEluGrad ? kClsLinearDgrad : kClsLinearFwd);
+  hipStream_t s = g->stream;
   int maxF = 0;
   for (int i = 0; i < b.n; ++i) maxF = b.p[i].F > maxF ? b.p[i].F : maxF;
   if (dtype == GMI_DTYPE_F32) {
@@ -372,9 +374,11 @@ int launch_linear(hipStream_t s, int dtype, int epi, int rows, const LinearBatch
   return launch_bf16_cfg<2, 2, 2, 2>(s, epi, rows, b, maxF);
 }
 
-int launch_wgrad(hipStream_t s, int dtype, int rows, int n_split, int chunk, WgradBatch& b, float* part,
+int launch_wgrad(gmi_instance* g, int dtype, int rows, int n_split, int chunk, WgradBatch& b, float* part,
                  int64_t part_stride) {
   if (b.n <= 0) return GMI_OK;
+  ProfScope ps(g, kClsWgrad);
+  hipStream_t s = g->stream;
   if (dtype == GMI_DTYPE_F32) {
     int maxn = 0;
     for (int i = 0; i < b.n; ++i) {

@@ -153,9 +153,11 @@ __global__ void sample_kernel(const float* __restrict__ mu, const float* __restr
 
 namespace gmi {
 
-int launch_gather(hipStream_t s, gmi_model* m, const float* obs, int n_envs, int ld_envs,
+int launch_gather(gmi_instance* g, gmi_model* m, const float* obs, int n_envs, int ld_envs,
                   const int32_t* idx, int rows, const gmi_buffer_desc* ex) {
   if (rows <= 0) return GMI_OK;
+  ProfScope ps(g, kClsGather);
+  hipStream_t s = g->stream;
   const int O = m->L.obs_dim, A = m->L.act_dim, o_pad = gmi::pad32(O);
   const int W = o_pad + (ex ? A + 3 : 0);
   const int64_t total = (int64_t)rows * W;
@@ -175,7 +177,7 @@ int launch_gather(hipStream_t s, gmi_model* m, const float* obs, int n_envs, int
 }
 
 // Layer l maps h[l] (input, width in_pad) to h[l+1]; the head writes mu / val in fp32.
-int forward_nets(hipStream_t s, gmi_model* m, int rows, bool policy, bool value, float* mu_dst,
+int forward_nets(gmi_instance* g, gmi_model* m, int rows, bool policy, bool value, float* mu_dst,
                  float* val_dst) {
   const ModelLayout& L = m->L;
   const bool bf = L.dtype == GMI_DTYPE_BF16;
@@ -208,7 +210,7 @@ int forward_nets(hipStream_t s, gmi_model* m, int rows, bool policy, bool value,
         p.F_store = p.F;
       }
     }
-    const int rc = launch_linear(s, L.dtype, l == L.n_layers - 1 ? kEpiBiasHead : kEpiBiasElu, rows, b);
+    const int rc = launch_linear(g, L.dtype, l == L.n_layers - 1 ? kEpiBiasHead : kEpiBiasElu, rows, b);
     if (rc != GMI_OK) return rc;
   }
   return GMI_OK;
@@ -282,7 +284,7 @@ extern "C" int gmi_model_bind(gmi_t g, const gmi_model_desc* d, float* params, v
   hipError_t e = hipMemsetAsync(m->ws_base, 0, m->ws_bytes, g->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(g->stream);
   if (e != hipSuccess) {
-    hipFree(m->ws_base);
+    (void)hipFree(m->ws_base);
     delete m;
     GMI_FAIL(GMI_ERR_HIP, "gmi_model_bind: clearing the workspace failed: %s", hipGetErrorString(e));
   }
@@ -292,7 +294,7 @@ extern "C" int gmi_model_bind(gmi_t g, const gmi_model_desc* d, float* params, v
 
 extern "C" int gmi_model_destroy(gmi_model_t m) {
   if (!valid(m)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_model_destroy: bad handle");
-  hipFree(m->ws_base);
+  (void)hipFree(m->ws_base);
   m->magic = 0;
   delete m;
   return GMI_OK;
@@ -323,12 +325,13 @@ extern "C" int agent_act(gmi_t g, gmi_model_t m, const float* obs, int32_t n_row
   if (rc != GMI_OK) return rc;
   if (n_rows == 0) return GMI_OK;
   if (!obs || !act || !logp || !value) GMI_FAIL(GMI_ERR_INVALID_ARG, "agent_act: NULL pointer");
-  rc = gmi::launch_gather(g->stream, m, obs, n_rows, n_rows, nullptr, n_rows, nullptr);
+  rc = gmi::launch_gather(g, m, obs, n_rows, n_rows, nullptr, n_rows, nullptr);
   if (rc != GMI_OK) return rc;
-  rc = gmi::forward_nets(g->stream, m, n_rows, true, true, m->mu, value);
+  rc = gmi::forward_nets(g, m, n_rows, true, true, m->mu, value);
   if (rc != GMI_OK) return rc;
   const float* log_std = m->L.dtype == GMI_DTYPE_BF16 ? reinterpret_cast<const float*>(m->shadow + m->L.sh_logstd)
                                                       : m->params + m->L.logstd_off;
+  gmi::ProfScope ps(g, gmi::kClsSample);
   sample_kernel<<<(n_rows + 127) / 128, 128, 0, g->stream>>>(m->mu, log_std, n_rows, m->L.act_dim, (uint32_t)seed,
                                                              (uint32_t)(seed >> 32), step, env_offset, act, logp, mu);
   GMI_LAUNCH_CHECK();
@@ -342,8 +345,8 @@ extern "C" int agent_value(gmi_t g, gmi_model_t m, const float* obs, int32_t n_r
   if (rc != GMI_OK) return rc;
   if (n_rows == 0) return GMI_OK;
   if (!obs || !value) GMI_FAIL(GMI_ERR_INVALID_ARG, "agent_value: NULL pointer");
-  rc = gmi::launch_gather(g->stream, m, obs, n_rows, n_rows, nullptr, n_rows, nullptr);
+  rc = gmi::launch_gather(g, m, obs, n_rows, n_rows, nullptr, n_rows, nullptr);
   if (rc != GMI_OK) return rc;
-  rc = gmi::forward_nets(g->stream, m, n_rows, false, true, nullptr, value);
+  rc = gmi::forward_nets(g, m, n_rows, false, true, nullptr, value);
   return rc;
 }

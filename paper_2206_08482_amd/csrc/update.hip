@@ -179,14 +179,15 @@ int check_model_buffer(const char* fn, gmi_model_t m, gmi_buffer_t b) {
 
 // Forward + loss (+ backward products) of the `rows` samples idx[0..rows) of the buffer.
 // Leaves gradient partials in m->grad_part / m->stat_part.  Returns the split count through n_split.
-int minibatch_pass(hipStream_t s, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx,
+int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx,
                    int rows, bool want_grad, int* n_split_out, int* n_loss_blocks_out) {
   const ModelLayout& L = m->L;
   const bool bf = L.dtype == GMI_DTYPE_BF16;
   const int A = L.act_dim;
-  int rc = gmi::launch_gather(s, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, &b->d);
+  hipStream_t s = g->stream;
+  int rc = gmi::launch_gather(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, &b->d);
   if (rc != GMI_OK) return rc;
-  rc = gmi::forward_nets(s, m, rows, true, true, m->mu, m->val);
+  rc = gmi::forward_nets(g, m, rows, true, true, m->mu, m->val);
   if (rc != GMI_OK) return rc;
   int nlb = (rows + 255) / 256;
   if (nlb > gmi::kLossBlocksMax) nlb = gmi::kLossBlocksMax;
@@ -194,6 +195,8 @@ int minibatch_pass(hipStream_t s, gmi_model* m, gmi_buffer* b, const gmi_ppo_hpa
   const float* log_std = bf ? reinterpret_cast<const float*>(m->shadow + L.sh_logstd) : m->params + L.logstd_off;
   const int head = L.n_layers - 1;
   const size_t lds = sizeof(float) * (4 * A + 16);
+  {
+  gmi::ProfScope ps(g, gmi::kClsLoss);
   if (bf)
     loss_kernel<uint16_t><<<nlb, 256, lds, s>>>(rows, A, m->mu, m->val, m->mb_act, m->mb_logp, m->mb_adv, m->mb_ret,
                                                 log_std, hp->clip, hp->c_v, want_grad ? 1 : 0,
@@ -204,6 +207,7 @@ int minibatch_pass(hipStream_t s, gmi_model* m, gmi_buffer* b, const gmi_ppo_hpa
                                              log_std, hp->clip, hp->c_v, want_grad ? 1 : 0, (float*)m->dz[0][head],
                                              L.net[0][head].out_pad, (float*)m->dz[1][head], L.net[1][head].out_pad,
                                              m->stat_part);
+  }
   GMI_LAUNCH_CHECK();
   if (!want_grad) return GMI_OK;
 
@@ -227,7 +231,7 @@ int minibatch_pass(hipStream_t s, gmi_model* m, gmi_buffer* b, const gmi_ppo_hpa
       p.y = m->dz[net][l - 1]; p.ldy = li.in_pad;
       p.F_store = p.F;
     }
-    rc = gmi::launch_linear(s, L.dtype, gmi::kEpiEluGrad, rows, lb);
+    rc = gmi::launch_linear(g, L.dtype, gmi::kEpiEluGrad, rows, lb);
     if (rc != GMI_OK) return rc;
   }
   // weight / bias gradients of every layer of both nets in one launch
@@ -248,12 +252,14 @@ int minibatch_pass(hipStream_t s, gmi_model* m, gmi_buffer* b, const gmi_ppo_hpa
       p.out = li.out; p.in = li.in; p.out_pad = li.out_pad; p.in_pad = li.in_pad;
       p.w_off = li.w_off; p.b_off = li.b_off;
     }
-  return gmi::launch_wgrad(s, L.dtype, rows, n_split, chunk, wb, m->grad_part, L.n_params);
+  return gmi::launch_wgrad(g, L.dtype, rows, n_split, chunk, wb, m->grad_part, L.n_params);
 }
 
-int launch_adam(hipStream_t s, gmi_model* m, int n_split, int n_loss_blocks, const gmi_ppo_hparams* hp, int rows,
+int launch_adam(gmi_instance* g, gmi_model* m, int n_split, int n_loss_blocks, const gmi_ppo_hparams* hp, int rows,
                 uint32_t k, float* stats_out, float* grad_out, bool do_update) {
   const gmi::ShadowTable tab = gmi::make_shadow_table(m->L);
+  gmi::ProfScope ps(g, gmi::kClsAdam);
+  hipStream_t s = g->stream;
   const unsigned grid = (unsigned)((m->L.n_params + 255) / 256);
   adam_kernel<<<grid, 256, 0, s>>>(tab, m->L.dtype == GMI_DTYPE_BF16 ? 1 : 0, m->params, m->adam_m, m->adam_v,
                                    m->grad_part, n_split, m->L.n_params, m->stat_part, n_loss_blocks, m->L.act_dim,
@@ -284,14 +290,14 @@ extern "C" int ppo_update(gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_ppo_
   const int nmb = (int)(B / hp->minibatch);
   uint32_t k = hp->adam_step0;
   for (int e = 0; e < hp->epochs; ++e) {
-    rc = gmi::launch_permutation(g->stream, (int)B, hp->seed, hp->iteration, (uint32_t)e, b->perm);
+    rc = gmi::launch_permutation(g, (int)B, hp->seed, hp->iteration, (uint32_t)e, b->perm);
     if (rc != GMI_OK) return rc;
     for (int j = 0; j < nmb; ++j) {
       int n_split = 1, nlb = 1;
-      rc = minibatch_pass(g->stream, m, b, hp, b->perm + (int64_t)j * hp->minibatch, hp->minibatch, true, &n_split, &nlb);
+      rc = minibatch_pass(g, m, b, hp, b->perm + (int64_t)j * hp->minibatch, hp->minibatch, true, &n_split, &nlb);
       if (rc != GMI_OK) return rc;
       ++k;
-      rc = launch_adam(g->stream, m, n_split, nlb, hp, hp->minibatch, k,
+      rc = launch_adam(g, m, n_split, nlb, hp, hp->minibatch, k,
                        stats_out ? stats_out + 5 * ((int64_t)e * nmb + j) : nullptr, nullptr, true);
       if (rc != GMI_OK) return rc;
     }
@@ -319,9 +325,9 @@ extern "C" int ppo_evaluate(gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_pp
   if (rc != GMI_OK) return rc;
   if (!stats_out) GMI_FAIL(GMI_ERR_INVALID_ARG, "ppo_evaluate: stats_out is NULL");
   int n_split = 0, nlb = 1;
-  rc = minibatch_pass(g->stream, m, b, hp, idx, n, false, &n_split, &nlb);
+  rc = minibatch_pass(g, m, b, hp, idx, n, false, &n_split, &nlb);
   if (rc != GMI_OK) return rc;
-  return launch_adam(g->stream, m, 0, nlb, hp, n, 1, stats_out, nullptr, false);
+  return launch_adam(g, m, 0, nlb, hp, n, 1, stats_out, nullptr, false);
 }
 
 extern "C" int ppo_gradient(gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_ppo_hparams* hp, const int32_t* idx,
@@ -330,9 +336,9 @@ extern "C" int ppo_gradient(gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_pp
   if (rc != GMI_OK) return rc;
   if (!grad_out) GMI_FAIL(GMI_ERR_INVALID_ARG, "ppo_gradient: grad_out is NULL");
   int n_split = 1, nlb = 1;
-  rc = minibatch_pass(g->stream, m, b, hp, idx, n, true, &n_split, &nlb);
+  rc = minibatch_pass(g, m, b, hp, idx, n, true, &n_split, &nlb);
   if (rc != GMI_OK) return rc;
-  return launch_adam(g->stream, m, n_split, nlb, hp, n, 1, stats_out, grad_out, false);
+  return launch_adam(g, m, n_split, nlb, hp, n, 1, stats_out, grad_out, false);
 }
 
 extern "C" int adam_update(gmi_t g, float* params, float* adam_m, float* adam_v, const float* grad, int64_t n,
@@ -350,6 +356,7 @@ extern "C" int adam_update(gmi_t g, float* params, float* adam_m, float* adam_v,
   tab.sh_logstd = 0;
   tab.act_dim = 0;
   tab.n_params = n;
+  gmi::ProfScope ps(g, gmi::kClsAdam);
   adam_kernel<<<(unsigned)((n + 255) / 256), 256, 0, g->stream>>>(tab, 0, params, adam_m, adam_v, grad, 1, n, nullptr, 0,
                                                                 0, 0.f, 1.f, adam_scalars(hp, step), nullptr, nullptr,
                                                                 nullptr, 1);
