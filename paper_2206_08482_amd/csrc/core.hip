@@ -99,7 +99,15 @@ extern "C" int gmi_create(const uint32_t* cu_mask, uint32_t n_words, int device,
       bits += __builtin_popcount(v);
     }
     if (bits == 0) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_create: cu_mask enables no compute unit");
-    GMI_HIP(hipExtStreamCreateWithCUMask(&stream, need_words, mask.data()));
+    const hipError_t ce = hipExtStreamCreateWithCUMask(&stream, need_words, mask.data());
+    if (ce != hipSuccess) {
+      (void)hipGetLastError();
+      // Observed on gfx950: bit i addresses a CU of accelerator die i % 8 and the runtime refuses a mask
+      // that leaves a die without any CU (it reports "out of memory").
+      GMI_FAIL(GMI_ERR_INVALID_ARG,
+               "gmi_create: the runtime refused this CU mask (%s); every one of the 8 dies (bit index mod 8) "
+               "needs at least one CU", hipGetErrorString(ce));
+    }
     cu_count = bits;
   } else {
     GMI_HIP(hipStreamCreateWithFlags(&stream, hipStreamNonBlocking));

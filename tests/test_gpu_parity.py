@@ -456,5 +456,9 @@ def test_masked_instances_and_transfer(g):
         g.gmi_sync(b)
         assert np.array_equal(out.cpu().numpy(), px.normal_field(5, 1, rep, n, 8))
         g.gmi_transfer(b, a, None, None, 0)       # ordering only: a may overwrite src again
+    # a mask that leaves an accelerator die (bit index mod 8) without any CU is refused cleanly
+    with pytest.raises(g.GmiError) as ei:
+        g.gmi_create([0x55555555] * words)
+    assert ei.value.code == g.ERR_INVALID_ARG
     for h in (a, b, full):
         g.gmi_destroy(h)
