@@ -258,6 +258,18 @@ const char* gmi_profile_class_name(int cls);
  * launches of class cls since profiling was enabled.  host: total_ms, launches. */
 int gmi_profile_read(gmi_t gmi, int cls, double* total_ms, int64_t* launches);
 
+/* Achievable-peak probes for measurement reports: what = 0 runs a pure bf16 matrix-core loop and
+ * returns TFLOP/s, what = 1 runs a streaming copy over the two halves of `scratch` and returns GB/s
+ * (bytes read + written).  Blocks until done.  scratch: dev, scratch_bytes long; result: host. */
+int gmi_measure_peak(gmi_t gmi, int what, void* scratch, size_t scratch_bytes, double* result);
+
+/* Micro-benchmark of one bf16 linear-layer product of the MLPs (Table 6 shapes) on synthetic operands
+ * carved out of `scratch` (dev; zero or arbitrary finite contents): kind 0 = forward with bias + ELU,
+ * 2 = input gradient, 3 = weight gradient.  rows x K -> F, K and F multiples of 32, n_nets (1 or 2)
+ * problems per launch as in the real path.  us_per_launch (host) = average over reps launches. Blocks. */
+int gmi_bench_linear(gmi_t gmi, int kind, int rows, int K, int F, int n_nets, int reps, void* scratch,
+                     size_t scratch_bytes, double* us_per_launch);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,6 +25,7 @@ EXPORTS = [
     "agent_act", "agent_value", "gmi_buffer_bind", "gmi_buffer_destroy", "collect_experience",
     "gae_compute", "ppo_update", "ppo_evaluate", "ppo_gradient", "adam_update", "gmi_noise_fill",
     "gmi_permutation", "gmi_profile_enable", "gmi_profile_classes", "gmi_profile_class_name", "gmi_profile_read",
+    "gmi_measure_peak", "gmi_bench_linear",
 ]
 
 
@@ -97,6 +98,9 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "gmi_profile_classes": (C.c_int, []),
         "gmi_profile_class_name": (C.c_char_p, [C.c_int]),
         "gmi_profile_read": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]),
+        "gmi_measure_peak": (C.c_int, [vp, C.c_int, vp, C.c_size_t, C.POINTER(C.c_double)]),
+        "gmi_bench_linear": (C.c_int, [vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_size_t,
+                                       C.POINTER(C.c_double)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -333,3 +337,18 @@ def gmi_profile_read(gmi: int, cls: int):
 
 def dtype_code(name: str) -> int:
     return {"f32": DTYPE_F32, "bf16": DTYPE_BF16}[name]
+
+
+def gmi_measure_peak(gmi: int, what: int, scratch) -> float:
+    """what = 0: sustained bf16 MFMA TFLOP/s; what = 1: streaming-copy GB/s over `scratch` (a device tensor)."""
+    out = C.c_double()
+    _check(_lib.gmi_measure_peak(gmi, what, _ptr(scratch), scratch.numel() * scratch.element_size(), C.byref(out)))
+    return out.value
+
+
+def gmi_bench_linear(gmi: int, kind: int, rows: int, K: int, F: int, n_nets: int, reps: int, scratch) -> float:
+    """Average microseconds per launch of one bf16 layer product (kind 0 forward, 2 input grad, 3 weight grad)."""
+    out = C.c_double()
+    _check(_lib.gmi_bench_linear(gmi, kind, rows, K, F, n_nets, reps, _ptr(scratch),
+                                 scratch.numel() * scratch.element_size(), C.byref(out)))
+    return out.value

@@ -15,17 +15,18 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 constexpr int kBK = 64;          // contraction elements staged per step
 constexpr int kLds = kBK + 8;    // LDS row stride in bf16 elements (144 B: conflict-free 16 B reads)
 
-__device__ __forceinline__ float elu_f(float z) { return z > 0.f ? z : (__expf(z) - 1.0f); }
-__device__ __forceinline__ float bf16_to_f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-// round to nearest even
-__device__ __forceinline__ uint16_t f_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+typedef float float2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+
+// ELU through the hardware base-2 exponential (abs. error ~1e-7, far below bf16 resolution)
+__device__ __forceinline__ float elu_f(float z) {
+  return z > 0.f ? z : (__builtin_amdgcn_exp2f(z * 1.44269504f) - 1.0f);
 }
+__device__ __forceinline__ float bf16_to_f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+// two fp32 -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  return (uint32_t)f_to_bf16(lo) | ((uint32_t)f_to_bf16(hi) << 16);
+  float2v v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2v));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -152,6 +153,198 @@ __global__ __launch_bounds__(256) void linear_bf16_kernel(gmi::LinearBatch batch
           *reinterpret_cast<uint2*>((uint16_t*)P.y + (int64_t)r * P.ldy + f) = pk;
         }
       }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Large-tile variant for wide layers: workgroup tile (2*TRW*32 rows) x (2*TFW*32 features), 2 x 2 waves,
+// each wave TFW x TRW matrix-core tiles, so one 16-byte LDS fragment feeds TRW (or TFW) MFMAs and LDS
+// bandwidth stays below the matrix cores' appetite.  K is staged 64 at a time (a full 128-byte line per
+// row) into double-buffered LDS (144-byte row stride: conflict-free 16-byte reads), one barrier per
+// stage.  Two further stages are in flight in registers: the row operand is first-touch data from
+// HBM / the memory-side cache, and with one workgroup per CU only a deep prefetch covers that latency
+// (measured: with a single stage in flight the kernel ran at the pace of one memory round trip per stage).
+// The accumulators leave through LDS so that the epilogue runs and stores with features contiguous across
+// lanes (whole 64..256-byte row segments per store).  Workgroup ids are decoded so that the workgroups
+// sharing a row tile run back to back on the same accelerator die (ids are dealt round-robin over the 8
+// dies), which keeps that tile in the die's L2.
+template <int TFW, int TRW, int EPI>
+__global__ __launch_bounds__(256) void linear_bf16_big_kernel(gmi::LinearBatch batch, int rows, int n_rt,
+                                                              int n_rt_pad, int n_ft) {
+  constexpr int TF = 2 * TFW * 32, TR = 2 * TRW * 32;
+  constexpr int CH_W = TF * (kBK / 8), CH_X = TR * (kBK / 8);
+  constexpr int NCH = (CH_W + CH_X) / 256;
+  static_assert((CH_W + CH_X) % 256 == 0 && CH_W % 256 == 0, "stage must divide evenly over the threads");
+  constexpr int kStageElems = (TF + TR) * kLds;                  // bf16 elements of one LDS stage
+  constexpr int kOutStride = TFW * 32 + 4;                       // floats per staged output row
+  constexpr int kMainBytes = 2 * kStageElems * 2;
+  constexpr int kOutBytes = 4 * 32 * kOutStride * 4;
+  constexpr int kSmemBytes = kMainBytes > kOutBytes ? kMainBytes : kOutBytes;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemBytes];
+  uint16_t* s_stage = reinterpret_cast<uint16_t*>(smem);
+
+  // workgroup id -> (net, feature tile, row tile)
+  const int per_net = n_rt_pad * n_ft;
+  const int z = blockIdx.x / per_net;
+  const int w = blockIdx.x % per_net;
+  const int die = w & 7, slot = w >> 3;
+  const int ft = slot % n_ft;
+  const int rt = (slot / n_ft) * 8 + die;
+  if (rt >= n_rt) return;
+  const gmi::LinearProblem& P = batch.p[z];
+  const int f0 = ft * TF, r0 = rt * TR;
+  if (f0 >= P.F) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wf = wave >> 1, wr = wave & 1;
+  const uint16_t* __restrict__ gw = (const uint16_t*)P.w;
+  const uint16_t* __restrict__ gx = (const uint16_t*)P.x;
+
+  floatx16 acc[TFW][TRW];
+#pragma unroll
+  for (int i = 0; i < TFW; ++i)
+#pragma unroll
+    for (int j = 0; j < TRW; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // chunk = 8 consecutive k of one row; thread t handles rows (t >> 3) + 32 c, k-chunk t & 7.
+  // Loads are unconditional (no branches, so the compiler can keep two stages in flight and wait only for
+  // the older one): row indices are clamped into the operand (rows past the end only feed outputs that
+  // are never stored) and the k offset is clamped into the row, with a select to zero past K.
+  constexpr int NCW = CH_W / 256, NCX = CH_X / 256;
+  const int crow = tid >> 3, kc8 = (tid & 7) * 8;
+  const uint16_t* src_w[NCW];
+  const uint16_t* src_x[NCX];
+#pragma unroll
+  for (int c = 0; c < NCW; ++c) src_w[c] = gw + (int64_t)min(f0 + crow + 32 * c, P.F - 1) * P.ldw;
+#pragma unroll
+  for (int c = 0; c < NCX; ++c) src_x[c] = gx + (int64_t)min(r0 + crow + 32 * c, rows - 1) * P.ldx;
+  const int dst0 = crow * kLds + kc8;
+  const int k_last = P.K - 8;
+  uint4 st0[NCH], st1[NCH];
+  auto load_stage = [&](uint4* st, int k0) {
+    const int k = k0 + kc8;
+    const bool k_ok = k < P.K;
+    const int kq = min(k, k_last);
+#pragma unroll
+    for (int c = 0; c < NCW; ++c) {
+      const uint4 v = *reinterpret_cast<const uint4*>(src_w[c] + kq);
+      st[c] = k_ok ? v : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int c = 0; c < NCX; ++c) st[NCW + c] = *reinterpret_cast<const uint4*>(src_x[c] + kq);
+  };
+  auto store_stage = [&](const uint4* st, int buf) {
+    uint16_t* base = s_stage + buf * kStageElems + dst0;
+#pragma unroll
+    for (int c = 0; c < NCW; ++c) *reinterpret_cast<uint4*>(base + c * 32 * kLds) = st[c];
+#pragma unroll
+    for (int c = 0; c < NCX; ++c) *reinterpret_cast<uint4*>(base + (TF + c * 32) * kLds) = st[NCW + c];
+  };
+  auto compute = [&](int buf) {
+    const uint16_t* sw = s_stage + buf * kStageElems;
+    const uint16_t* sx = sw + TF * kLds;
+#pragma unroll 2
+    for (int kk = 0; kk < kBK / 16; ++kk) {
+      bf16x8 a[TFW], b[TRW];
+      const int ko = kk * 16 + (lane >> 5) * 8;
+#pragma unroll
+      for (int i = 0; i < TFW; ++i)
+        a[i] = *reinterpret_cast<const bf16x8*>(&sw[((wf * TFW + i) * 32 + (lane & 31)) * kLds + ko]);
+#pragma unroll
+      for (int j = 0; j < TRW; ++j)
+        b[j] = *reinterpret_cast<const bf16x8*>(&sx[((wr * TRW + j) * 32 + (lane & 31)) * kLds + ko]);
+#pragma unroll
+      for (int i = 0; i < TFW; ++i)
+#pragma unroll
+        for (int j = 0; j < TRW; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  // stage s lives in LDS buffer s & 1; st1 carries odd stages, st0 even stages.  Stages past K load as
+  // zeros (weight operand), so the loop body needs no conditions: a trailing odd stage multiplies by zero.
+  const int nk = (P.K + kBK - 1) / kBK;
+  load_stage(st0, 0);
+  load_stage(st1, kBK);
+  store_stage(st0, 0);
+  load_stage(st0, 2 * kBK);
+  for (int kt = 0; kt < nk; kt += 2) {
+    __syncthreads();
+    store_stage(st1, 1);
+    load_stage(st1, (kt + 3) * kBK);
+    compute(0);
+    __syncthreads();
+    store_stage(st0, 0);
+    load_stage(st0, (kt + 4) * kBK);
+    compute(1);
+  }
+  __syncthreads();   // every wave is done reading the stages: LDS becomes the output staging area
+
+  // Each wave owns a [32 rows][TFW*32 features] fp32 staging region and drains one row tile at a time.
+  // Everything below is branch-free up to the final predicated store, and the problem's fields live in
+  // registers: a conditional block per row made the compiler wait for every earlier store to be
+  // acknowledged before each LDS read, which serialised the whole epilogue on memory round trips.
+  float* s_out = reinterpret_cast<float*>(smem) + wave * 32 * kOutStride;
+  constexpr int kLanesPerRow = TFW * 8;             // lanes covering one row with 4 features each
+  constexpr int kRowsPerIter = 64 / kLanesPerRow;
+  constexpr int NIT = 32 / kRowsPerIter;
+  const int fl = (lane % kLanesPerRow) * 4;         // feature offset inside the wave's feature range
+  const int f = f0 + wf * TFW * 32 + fl;
+  const bool f_ok = f < P.F;
+  const int fq = f_ok ? f : 0;
+  uint16_t* __restrict__ yp = (uint16_t*)P.y + fq;
+  const uint16_t* __restrict__ hp = (const uint16_t*)P.h + fq;
+  const int ldy = P.ldy, ldh = P.ldh;
+  float4 bias4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (EPI == gmi::kEpiBiasElu) bias4 = *reinterpret_cast<const float4*>(P.bias + fq);
+  const int rl0 = lane / kLanesPerRow;
+#pragma unroll
+  for (int j = 0; j < TRW; ++j) {
+    const int rbase = r0 + (wr * TRW + j) * 32 + rl0;
+    uint2 hv[NIT];
+    if (EPI == gmi::kEpiEluGrad) {
+#pragma unroll
+      for (int it = 0; it < NIT; ++it)
+        hv[it] = *reinterpret_cast<const uint2*>(hp + (int64_t)min(rbase + it * kRowsPerIter, rows - 1) * ldh);
+    }
+#pragma unroll
+    for (int i = 0; i < TFW; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 v4 = make_float4(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+        *reinterpret_cast<float4*>(&s_out[(lane & 31) * kOutStride + i * 32 + q * 8 + (lane >> 5) * 4]) = v4;
+      }
+    __builtin_amdgcn_wave_barrier();     // wave-private region: LDS serves one wave's requests in order
+    float4 o[NIT];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it)
+      o[it] = *reinterpret_cast<const float4*>(&s_out[(it * kRowsPerIter + rl0) * kOutStride + fl]);
+    __builtin_amdgcn_wave_barrier();
+    // Make every pending global load (bias, h rows) land here, once per pass: otherwise each predicated
+    // store block below starts with a wait for *all* outstanding memory operations, earlier stores included.
+    if (EPI == gmi::kEpiBiasElu) {
+      asm volatile("" : "+v"(bias4.x), "+v"(bias4.y), "+v"(bias4.z), "+v"(bias4.w));
+    } else {
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) asm volatile("" : "+v"(hv[it].x), "+v"(hv[it].y));
+    }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      float4 v = o[it];
+      if (EPI == gmi::kEpiBiasElu) {
+        v.x = elu_f(v.x + bias4.x); v.y = elu_f(v.y + bias4.y); v.z = elu_f(v.z + bias4.z); v.w = elu_f(v.w + bias4.w);
+      } else {
+        const float h0 = bf16_to_f((uint16_t)(hv[it].x & 0xFFFF)), h1 = bf16_to_f((uint16_t)(hv[it].x >> 16));
+        const float h2 = bf16_to_f((uint16_t)(hv[it].y & 0xFFFF)), h3 = bf16_to_f((uint16_t)(hv[it].y >> 16));
+        v.x *= h0 > 0.f ? 1.f : h0 + 1.f; v.y *= h1 > 0.f ? 1.f : h1 + 1.f;
+        v.z *= h2 > 0.f ? 1.f : h2 + 1.f; v.w *= h3 > 0.f ? 1.f : h3 + 1.f;
+      }
+      const uint2 pk = make_uint2(pack_bf16(v.x, v.y), pack_bf16(v.z, v.w));
+      const int r = rbase + it * kRowsPerIter;
+      if (r < rows && f_ok) *reinterpret_cast<uint2*>(yp + (int64_t)r * ldy) = pk;
     }
   }
 }
@@ -326,6 +519,20 @@ __global__ void wgrad_f32_kernel(gmi::WgradBatch batch, int rows, int chunk, flo
   }
 }
 
+template <int TFW, int TRW>
+int launch_bf16_big(hipStream_t s, int epi, int rows, const gmi::LinearBatch& b, int maxF) {
+  constexpr int TF = 2 * TFW * 32, TR = 2 * TRW * 32;
+  const int n_rt = (rows + TR - 1) / TR, n_ft = (maxF + TF - 1) / TF;
+  const int n_rt_pad = (n_rt + 7) & ~7;
+  const unsigned grid = (unsigned)(n_rt_pad * n_ft * b.n);
+  if (epi == gmi::kEpiBiasElu)
+    linear_bf16_big_kernel<TFW, TRW, gmi::kEpiBiasElu><<<grid, 256, 0, s>>>(b, rows, n_rt, n_rt_pad, n_ft);
+  else
+    linear_bf16_big_kernel<TFW, TRW, gmi::kEpiEluGrad><<<grid, 256, 0, s>>>(b, rows, n_rt, n_rt_pad, n_ft);
+  GMI_LAUNCH_CHECK();
+  return GMI_OK;
+}
+
 template <int WF, int WR, int TFM, int TRM>
 int launch_bf16_cfg(hipStream_t s, int epi, int rows, const gmi::LinearBatch& b, int maxF) {
   constexpr int TF = WF * TFM * 32, TR = WR * TRM * 32;
@@ -367,6 +574,15 @@ int launch_linear(gmi_instance* g, int dtype, int epi, int rows, const LinearBat
     if ((p.K & 31) || (p.F & 31) || (p.ldx & 7) || (p.ldw & 7) || (epi != kEpiBiasHead && (p.ldy & 3)) ||
         (epi == kEpiEluGrad && (p.ldh & 3)))
       GMI_FAIL(GMI_ERR_BAD_SHAPE, "launch_linear: bf16 path needs padded dims (K=%d F=%d)", p.K, p.F);
+  }
+  if (epi != kEpiBiasHead && rows >= 8192) {
+    // wide layers: large tiles; choose the tile whose padding waste over the feature range is smallest
+    if (maxF > 128) {
+      const int waste256 = (maxF + 255) / 256 * 256 - maxF, waste128 = (maxF + 127) / 128 * 128 - maxF;
+      if (waste256 <= waste128) return launch_bf16_big<4, 4>(s, epi, rows, b, maxF);
+      return launch_bf16_big<2, 4>(s, epi, rows, b, maxF);
+    }
+    if (maxF > 64) return launch_bf16_big<2, 4>(s, epi, rows, b, maxF);
   }
   if (maxF % 128 == 0 || maxF > 256) return launch_bf16_cfg<2, 2, 2, 2>(s, epi, rows, b, maxF);
   if (maxF % 64 == 0) return launch_bf16_cfg<1, 4, 2, 2>(s, epi, rows, b, maxF);

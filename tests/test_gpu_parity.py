@@ -217,7 +217,10 @@ def _theta_and_batch(cfg, T, N, seed=1):
     ("C1", 16, 64, 256, "f32", "straddle"), ("C1", 4, 50, 77, "f32", "straddle"),
     ("C2", 4, 512, 2048, "bf16", "bimodal"), ("C2", 3, 500, 1111, "bf16", "bimodal"),
     ("C3", 2, 1024, 2048, "bf16", "bimodal"), ("C4", 2, 700, 1400, "bf16", "bimodal"),
-    ("C2", 4, 512, 2048, "bf16", "straddle")])
+    ("C2", 4, 512, 2048, "bf16", "straddle"),
+    # large-tile kernels (rows >= 8192), ragged against their 256-row tiles
+    ("C4", 2, 4200, 8400, "bf16", "bimodal"), ("C3", 3, 3000, 8999, "bf16", "bimodal"),
+    ("C2", 2, 8192, 16384, "bf16", "bimodal")])
 def test_gradient_and_stats_match_oracle(g, inst, name, T, N, rows, dtype, ratios):
     """ratios = "straddle": old/new probability ratios spread smoothly across the clip range, so some
     samples sit within rounding distance of a clip boundary.  Which side such a sample falls on is a
