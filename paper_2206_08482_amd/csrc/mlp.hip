@@ -373,8 +373,8 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(gmi::WgradBatch batch, 
                                                          int chunk, float* __restrict__ part,
                                                          int64_t part_stride) {
   constexpr int T = 128;
-  __shared__ __attribute__((aligned(16))) uint16_t s_a[T * kLds];   // [o][row]
-  __shared__ __attribute__((aligned(16))) uint16_t s_b[T * kLds];   // [i][row]
+  constexpr int kBuf = 2 * T * kLds;                                 // one LDS stage: [o][row] then [i][row]
+  __shared__ __attribute__((aligned(16))) uint16_t s_stage[2 * kBuf];
   int pi = 0;
   while (pi + 1 < batch.n && (int)blockIdx.x >= batch.blk_start[pi + 1]) ++pi;
   const gmi::WgradProblem& P = batch.p[pi];
@@ -391,11 +391,18 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(gmi::WgradBatch batch, 
   const bool is_b = tid >= 128;
   const int t2 = tid & 127;
   const int fblk = t2 & 15, rblk = t2 >> 4;          // 16 feature blocks x 8 row blocks
-  const uint16_t* __restrict__ src = is_b ? (const uint16_t*)P.x : (const uint16_t*)P.dz;
   const int ld = is_b ? P.ldx : P.lddz;
   const int fmax = is_b ? P.in_pad : P.out_pad;
   const int feat = (is_b ? i0 : o0) + fblk * 8;
-  uint16_t* sdst = (is_b ? s_b : s_a) + (fblk * 8) * kLds + rblk * 8;
+  const bool feat_ok = feat < fmax;
+  // loads are unconditional (clamped addresses, masked to zero afterwards) so that two stages stay in
+  // flight and the compiler waits only for the older one
+  const uint16_t* __restrict__ src = (is_b ? (const uint16_t*)P.x : (const uint16_t*)P.dz) + (feat_ok ? feat : 0);
+  // LDS holds [feature][row]; the 16-byte slot of row block rblk inside a feature's line is XOR-swizzled
+  // with the feature block index: the 16 lanes that write the same row block of 16 different feature
+  // blocks are 8 LDS lines apart, which without the swizzle is the same bank group for all of them
+  // (measured: 16-way conflicts made every stage cost ~4000 cycles whatever the tile's work).
+  const int sdst = (is_b ? T * kLds : 0) + (fblk * 8) * kLds + ((rblk ^ (fblk & 7)) * 8);
 
   floatx16 acc[2][2];
   floatx16 accb[2];
@@ -409,38 +416,42 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(gmi::WgradBatch batch, 
 #pragma unroll
   for (int v = 0; v < 8; ++v) ones[v] = (__bf16)1.0f;
 
-  uint4 stage[8];
-  auto load_stage = [&](int rbase) {
+  uint4 st0[8], st1[8];
+  auto load_stage = [&](uint4* st, int rbase) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      st[j] = *reinterpret_cast<const uint4*>(src + (int64_t)min(rbase + rblk * 8 + j, rows - 1) * ld);
+  };
+  // rows past the split (and feature blocks past the operand) are zeroed here, when the data is consumed,
+  // not at load time: touching a loaded register right after the load would stall on it
+  auto store_stage = [&](const uint4* st, int buf, int rbase) {
+    uint4 m[8], tr[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const int r = rbase + rblk * 8 + j;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (r < row_end && feat < fmax) v = *reinterpret_cast<const uint4*>(src + (int64_t)r * ld + feat);
-      stage[j] = v;
+      const uint32_t k = (rbase + rblk * 8 + j < row_end && feat_ok) ? 0xFFFFFFFFu : 0u;
+      m[j] = make_uint4(st[j].x & k, st[j].y & k, st[j].z & k, st[j].w & k);
     }
-  };
-  auto store_stage = [&]() {
-    uint4 tr[8];
-    transpose8x8(stage, tr);
+    transpose8x8(m, tr);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4*>(sdst + i * kLds) = tr[i];
+    for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4*>(&s_stage[buf * kBuf + sdst + i * kLds]) = tr[i];
   };
-
-  if (row_begin < row_end) load_stage(row_begin);
-  for (int rb = row_begin; rb < row_end; rb += kBK) {
-    store_stage();
-    __syncthreads();
-    if (rb + kBK < row_end) load_stage(rb + kBK);
+  auto compute = [&](int buf) {
+    const uint16_t* s_a = s_stage + buf * kBuf;
+    const uint16_t* s_b = s_a + T * kLds;
 #pragma unroll
     for (int kk = 0; kk < kBK / 16; ++kk) {
       bf16x8 a[2], b[2];
-      const int ko = kk * 16 + (lane >> 5) * 8;
+      const int kc = kk * 2 + (lane >> 5);          // 16-byte slot (8 rows) of this lane's fragment
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        a[i] = *reinterpret_cast<const bf16x8*>(&s_a[((wo * 2 + i) * 32 + (lane & 31)) * kLds + ko]);
+      for (int i = 0; i < 2; ++i) {
+        const int fr = (wo * 2 + i) * 32 + (lane & 31);
+        a[i] = *reinterpret_cast<const bf16x8*>(&s_a[fr * kLds + ((kc ^ ((fr >> 3) & 7)) * 8)]);
+      }
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-        b[j] = *reinterpret_cast<const bf16x8*>(&s_b[((wi * 2 + j) * 32 + (lane & 31)) * kLds + ko]);
+      for (int j = 0; j < 2; ++j) {
+        const int fr = (wi * 2 + j) * 32 + (lane & 31);
+        b[j] = *reinterpret_cast<const bf16x8*>(&s_b[fr * kLds + ((kc ^ ((fr >> 3) & 7)) * 8)]);
+      }
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -452,7 +463,26 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(gmi::WgradBatch batch, 
           accb[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], ones, accb[i], 0, 0, 0);
       }
     }
-    __syncthreads();
+  };
+
+  // stage s (64 rows) lives in LDS buffer s & 1; rows past the split load as zeros, so a trailing odd
+  // stage adds nothing and the loop body needs no conditions
+  const int nst = row_begin < row_end ? (row_end - row_begin + kBK - 1) / kBK : 0;
+  if (nst > 0) {
+    load_stage(st0, row_begin);
+    load_stage(st1, row_begin + kBK);
+    store_stage(st0, 0, row_begin);
+    load_stage(st0, row_begin + 2 * kBK);
+    for (int s2 = 0; s2 < nst; s2 += 2) {
+      __syncthreads();
+      store_stage(st1, 1, row_begin + (s2 + 1) * kBK);
+      load_stage(st1, row_begin + (s2 + 3) * kBK);
+      compute(0);
+      __syncthreads();
+      store_stage(st0, 0, row_begin + (s2 + 2) * kBK);
+      load_stage(st0, row_begin + (s2 + 4) * kBK);
+      compute(1);
+    }
   }
 
   float* dst = part + (int64_t)sp * part_stride;
