@@ -63,6 +63,11 @@ def class_work(cfg, n_params):
         "collect": dict(bytes=T * N * 2 * (4.0 * (O + A + 3) + 1), launches=T, bound="hbm"),
         "gae": dict(bytes=B * (9.0 + 8.0 + 8.0) + 4.0 * N, launches=1, bound="hbm"),
         "permutation": dict(bytes=E * B * 4.0, launches=E, bound="hbm"),
+        # fused kernels: all layers of both nets for a tile of rows in one launch
+        "fused_agent": dict(flops=2.0 * (T * N * mac + N * mac_value), launches=T + 1, bound="mfma"),
+        "fused_train": dict(flops=2.0 * n_upd * MB * (mac + mac_dgrad), launches=n_upd, bound="mfma"),
+        "fused_rollout": dict(flops=2.0 * (T * N * mac + N * mac_value), launches=1, bound="mfma"),
+        "reduce": dict(bytes=n_upd * (MB / 64.0) * 4.0 * (A + 8), launches=n_upd, bound="hbm"),
     }
 
 

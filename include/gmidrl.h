@@ -72,6 +72,10 @@ int gmi_sync(gmi_t gmi);
 /* Number of compute units enabled for the instance (device CU count if unrestricted). */
 int gmi_cu_count(gmi_t gmi);
 const char* gmi_last_error(void);
+/* enable != 0 (the default): calls on this instance use the row-tile fused kernels (one launch for all
+ * layers of both nets plus the sampling epilogue, ...) whenever the model fits them; 0 forces the
+ * per-layer kernels.  Both give results within the same tolerances. */
+int gmi_set_fusion(gmi_t gmi, int enable);
 
 /* Hands data from instance `src` to instance `dst` (the paper's asynchronous send / synchronous
  * recv of Listing 1, and the experience / parameter movements of Table 5, which on one device need

@@ -25,7 +25,7 @@ EXPORTS = [
     "agent_act", "agent_value", "gmi_buffer_bind", "gmi_buffer_destroy", "collect_experience",
     "gae_compute", "ppo_update", "ppo_evaluate", "ppo_gradient", "adam_update", "gmi_noise_fill",
     "gmi_permutation", "gmi_profile_enable", "gmi_profile_classes", "gmi_profile_class_name", "gmi_profile_read",
-    "gmi_measure_peak", "gmi_bench_linear",
+    "gmi_measure_peak", "gmi_bench_linear", "gmi_set_fusion",
 ]
 
 
@@ -98,6 +98,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "gmi_profile_classes": (C.c_int, []),
         "gmi_profile_class_name": (C.c_char_p, [C.c_int]),
         "gmi_profile_read": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]),
+        "gmi_set_fusion": (C.c_int, [vp, C.c_int]),
         "gmi_measure_peak": (C.c_int, [vp, C.c_int, vp, C.c_size_t, C.POINTER(C.c_double)]),
         "gmi_bench_linear": (C.c_int, [vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_size_t,
                                        C.POINTER(C.c_double)]),
@@ -352,3 +353,7 @@ def gmi_bench_linear(gmi: int, kind: int, rows: int, K: int, F: int, n_nets: int
     _check(_lib.gmi_bench_linear(gmi, kind, rows, K, F, n_nets, reps, _ptr(scratch),
                                  scratch.numel() * scratch.element_size(), C.byref(out)))
     return out.value
+
+
+def gmi_set_fusion(gmi: int, enable: bool) -> None:
+    _check(_lib.gmi_set_fusion(gmi, 1 if enable else 0))

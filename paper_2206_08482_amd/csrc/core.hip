@@ -36,7 +36,8 @@ ProfScope::~ProfScope() {
   if (hipEventRecord(s.stop[s.used], g->stream) == hipSuccess) ++s.used;
 }
 static const char* kClassNames[kClsCount] = {"gather", "linear_fwd", "linear_dgrad", "wgrad", "loss", "adam",
-                                             "env_step", "sample", "collect", "gae", "permutation"};
+                                             "env_step", "sample", "collect", "gae", "permutation", "fused_agent",
+                                             "fused_train", "fused_rollout", "reduce"};
 }  // namespace gmi
 
 extern "C" int gmi_profile_enable(gmi_t g, uint32_t class_mask) {
@@ -118,6 +119,7 @@ extern "C" int gmi_create(const uint32_t* cu_mask, uint32_t n_words, int device,
   g->stream = stream;
   g->cu_count = cu_count;
   g->prof_mask = 0;
+  g->fusion = 1;
   hipError_t e = hipEventCreateWithFlags(&g->event, hipEventDisableTiming);
   if (e != hipSuccess) {
     hipStreamDestroy(stream);
@@ -140,6 +142,12 @@ extern "C" int gmi_destroy(gmi_t g) {
   (void)hipStreamDestroy(g->stream);
   g->magic = 0;
   delete g;
+  return GMI_OK;
+}
+
+extern "C" int gmi_set_fusion(gmi_t g, int enable) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_set_fusion: bad handle");
+  g->fusion = enable ? 1 : 0;
   return GMI_OK;
 }
 

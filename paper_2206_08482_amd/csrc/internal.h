@@ -53,7 +53,7 @@ namespace gmi {
 // Kernel classes of the built-in per-launch timer (gmi_profile_*).
 enum KernelClass {
   kClsGather = 0, kClsLinearFwd, kClsLinearDgrad, kClsWgrad, kClsLoss, kClsAdam, kClsEnvStep, kClsSample,
-  kClsCollect, kClsGae, kClsPermutation, kClsCount
+  kClsCollect, kClsGae, kClsPermutation, kClsFusedAgent, kClsFusedTrain, kClsFusedRollout, kClsReduce, kClsCount
 };
 struct ProfSlot {
   std::vector<hipEvent_t> start, stop;
@@ -67,6 +67,7 @@ struct gmi_instance {
   hipStream_t stream;
   hipEvent_t event;      // used by gmi_transfer
   int cu_count;
+  int fusion;            // 1: use the row-tile fused kernels where the model fits them (default)
   uint32_t prof_mask;    // bit c set: launches of kernel class c are bracketed by timing events
   gmi::ProfSlot prof[gmi::kClsCount];
 };
@@ -215,6 +216,9 @@ int launch_gather(gmi_instance* g, gmi_model* m, const float* obs, int n_envs, i
 // m->h[net][l]; writes m->mu [rows, A] and m->val [rows].
 int forward_nets(gmi_instance* g, gmi_model* m, int rows, bool policy, bool value, float* mu_dst,
                  float* val_dst);
+
+int launch_agent_fused(gmi_instance* g, gmi_model* m, const float* obs, int n, uint64_t seed, uint32_t step,
+                       uint32_t env_offset, float* act, float* logp, float* value, float* mu_out, bool do_policy);
 
 int launch_permutation(gmi_instance* g, int n, uint64_t seed, uint32_t iteration, uint32_t epoch, int32_t* out);
 

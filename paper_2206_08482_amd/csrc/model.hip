@@ -325,6 +325,10 @@ extern "C" int agent_act(gmi_t g, gmi_model_t m, const float* obs, int32_t n_row
   if (rc != GMI_OK) return rc;
   if (n_rows == 0) return GMI_OK;
   if (!obs || !act || !logp || !value) GMI_FAIL(GMI_ERR_INVALID_ARG, "agent_act: NULL pointer");
+  if (g->fusion) {
+    rc = gmi::launch_agent_fused(g, m, obs, n_rows, seed, step, env_offset, act, logp, value, mu, true);
+    if (rc != GMI_ERR_UNSUPPORTED) return rc;
+  }
   rc = gmi::launch_gather(g, m, obs, n_rows, n_rows, nullptr, n_rows, nullptr);
   if (rc != GMI_OK) return rc;
   rc = gmi::forward_nets(g, m, n_rows, true, true, m->mu, value);
@@ -345,6 +349,10 @@ extern "C" int agent_value(gmi_t g, gmi_model_t m, const float* obs, int32_t n_r
   if (rc != GMI_OK) return rc;
   if (n_rows == 0) return GMI_OK;
   if (!obs || !value) GMI_FAIL(GMI_ERR_INVALID_ARG, "agent_value: NULL pointer");
+  if (g->fusion) {
+    rc = gmi::launch_agent_fused(g, m, obs, n_rows, 0, 0, 0, nullptr, nullptr, value, nullptr, false);
+    if (rc != GMI_ERR_UNSUPPORTED) return rc;
+  }
   rc = gmi::launch_gather(g, m, obs, n_rows, n_rows, nullptr, n_rows, nullptr);
   if (rc != GMI_OK) return rc;
   rc = gmi::forward_nets(g, m, n_rows, false, true, nullptr, value);

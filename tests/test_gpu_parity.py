@@ -167,8 +167,11 @@ def _bind_model(g, inst, cfg, theta, rows, dtype=None, with_adam=True):
 
 
 @pytest.mark.parametrize("name,n,dtype", [("C1", 64, "f32"), ("C1", 1, "f32"), ("C2", 1000, "f32"), ("C2", 4096, "bf16"),
-                                          ("C3", 777, "bf16"), ("C4", 600, "bf16"), ("C1", 100, "bf16")])
-def test_agent_act_matches_oracle(g, inst, name, n, dtype):
+                                          ("C3", 777, "bf16"), ("C4", 600, "bf16"), ("C1", 100, "bf16"),
+                                          ("C3", 4096, "bf16"), ("C4", 5000, "bf16"), ("C2", 33, "bf16")])
+@pytest.mark.parametrize("fused", [True, False])
+def test_agent_act_matches_oracle(g, inst, name, n, dtype, fused):
+    g.gmi_set_fusion(inst, fused)
     cfg = syn.get_config(name)
     shape, theta, env, _, _ = oracle_pieces(cfg, n_envs=n)
     theta = syn.make_model_params(cfg.obs_dim, cfg.act_dim, cfg.hidden, 3, policy_head_scale=1.0)
@@ -193,6 +196,7 @@ def test_agent_act_matches_oracle(g, inst, name, n, dtype):
     eps = px.normal_field(42, px.STREAM_ACTION, 9, n, A, env_offset=100)
     close32(act.cpu().numpy(), mu.cpu().numpy() + np.exp(theta[-A:]) * eps)
     g.gmi_model_destroy(hm)
+    g.gmi_set_fusion(inst, True)
 
 
 # ----------------------------------------------------------------------------- trainer
