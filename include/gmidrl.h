@@ -72,9 +72,12 @@ int gmi_sync(gmi_t gmi);
 /* Number of compute units enabled for the instance (device CU count if unrestricted). */
 int gmi_cu_count(gmi_t gmi);
 const char* gmi_last_error(void);
-/* enable != 0 (the default): calls on this instance use the row-tile fused kernels (one launch for all
- * layers of both nets plus the sampling epilogue, ...) whenever the model fits them; 0 forces the
- * per-layer kernels.  Both give results within the same tolerances. */
+/* Fusion level of the instance.  0: per-layer kernels only.  1 (default): agent_act / agent_value use
+ * the row-tile fused kernel (observation conversion, all layers of both nets and the sampling epilogue
+ * in one launch) whenever the model fits it.  2: ppo_update also uses the row-tile fused trainer kernel
+ * (gather + forward + loss + input gradients in one launch; currently slower than the per-layer
+ * kernels at minibatches of tens of thousands of rows).  All levels give results within
+ * the same tolerances. */
 int gmi_set_fusion(gmi_t gmi, int enable);
 
 /* Hands data from instance `src` to instance `dst` (the paper's asynchronous send / synchronous

@@ -355,5 +355,6 @@ def gmi_bench_linear(gmi: int, kind: int, rows: int, K: int, F: int, n_nets: int
     return out.value
 
 
-def gmi_set_fusion(gmi: int, enable: bool) -> None:
-    _check(_lib.gmi_set_fusion(gmi, 1 if enable else 0))
+def gmi_set_fusion(gmi: int, level: int) -> None:
+    """0: per-layer kernels; 1 (default): fused agent kernel; 2: also the fused trainer kernel."""
+    _check(_lib.gmi_set_fusion(gmi, int(level)))

@@ -147,7 +147,7 @@ extern "C" int gmi_destroy(gmi_t g) {
 
 extern "C" int gmi_set_fusion(gmi_t g, int enable) {
   if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_set_fusion: bad handle");
-  g->fusion = enable ? 1 : 0;
+  g->fusion = enable < 0 ? 0 : (enable > 2 ? 2 : enable);
   return GMI_OK;
 }
 

@@ -220,13 +220,16 @@ int forward_nets(gmi_instance* g, gmi_model* m, int rows, bool policy, bool valu
 int launch_agent_fused(gmi_instance* g, gmi_model* m, const float* obs, int n, uint64_t seed, uint32_t step,
                        uint32_t env_offset, float* act, float* logp, float* value, float* mu_out, bool do_policy);
 
+int launch_train_fused(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx,
+                       int rows);
+
 int launch_permutation(gmi_instance* g, int n, uint64_t seed, uint32_t iteration, uint32_t epoch, int32_t* out);
 
 }  // namespace gmi
 
 namespace gmi {
 constexpr int kSplitMax = 16;        // row splits of the weight-gradient reduction
-constexpr int kLossBlocksMax = 256;  // workgroups of the loss kernel (partial statistics)
+constexpr int kLossBlocksMax = 2048; // rows of per-workgroup loss statistics (one more row holds their sum)
 constexpr int kStatStride = 8;       // per-workgroup statistics slots before the log_std partials
 
 // Where each parameter lives in the flat vector and in the bf16 shadow (kernel argument).

@@ -271,7 +271,7 @@ extern "C" int gmi_model_bind(gmi_t g, const gmi_model_desc* d, float* params, v
     m->mb_adv = (float*)take(rows * 4);
     m->mb_ret = (float*)take(rows * 4);
     m->grad_part = (float*)take((int64_t)gmi::kSplitMax * L.n_params * 4);
-    m->stat_part = (float*)take((int64_t)gmi::kLossBlocksMax * (8 + A) * 4);
+    m->stat_part = (float*)take((int64_t)(gmi::kLossBlocksMax + 1) * (gmi::kStatStride + A) * 4);
     if (pass == 0) {
       m->ws_bytes = (size_t)off;
       hipError_t e = hipMalloc(&m->ws_base, m->ws_bytes);

@@ -185,7 +185,17 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
   const bool bf = L.dtype == GMI_DTYPE_BF16;
   const int A = L.act_dim;
   hipStream_t s = g->stream;
-  int rc = gmi::launch_gather(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, &b->d);
+  int rc;
+  bool fused = false;
+  if (g->fusion >= 2 && want_grad) {
+    rc = gmi::launch_train_fused(g, m, b, hp, idx, rows);
+    if (rc == GMI_OK) fused = true;
+    else if (rc != GMI_ERR_UNSUPPORTED) return rc;
+  }
+  if (fused) {
+    *n_loss_blocks_out = -1;     // statistics already summed (row kLossBlocksMax of stat_part)
+  } else {
+  rc = gmi::launch_gather(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, &b->d);
   if (rc != GMI_OK) return rc;
   rc = gmi::forward_nets(g, m, rows, true, true, m->mu, m->val);
   if (rc != GMI_OK) return rc;
@@ -234,6 +244,7 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
     rc = gmi::launch_linear(g, L.dtype, gmi::kEpiEluGrad, rows, lb);
     if (rc != GMI_OK) return rc;
   }
+  }  // !fused
   // weight / bias gradients of every layer of both nets in one launch
   int n_split = (rows + 63) / 64;
   if (n_split > gmi::kSplitMax) n_split = gmi::kSplitMax;
@@ -261,8 +272,13 @@ int launch_adam(gmi_instance* g, gmi_model* m, int n_split, int n_loss_blocks, c
   gmi::ProfScope ps(g, gmi::kClsAdam);
   hipStream_t s = g->stream;
   const unsigned grid = (unsigned)((m->L.n_params + 255) / 256);
+  const float* stat = m->stat_part;
+  if (n_loss_blocks < 0) {
+    stat = m->stat_part + (int64_t)gmi::kLossBlocksMax * (gmi::kStatStride + m->L.act_dim);
+    n_loss_blocks = 1;
+  }
   adam_kernel<<<grid, 256, 0, s>>>(tab, m->L.dtype == GMI_DTYPE_BF16 ? 1 : 0, m->params, m->adam_m, m->adam_v,
-                                   m->grad_part, n_split, m->L.n_params, m->stat_part, n_loss_blocks, m->L.act_dim,
+                                   m->grad_part, n_split, m->L.n_params, stat, n_loss_blocks, m->L.act_dim,
                                    hp->c_e, 1.0f / (float)rows, adam_scalars(hp, k), m->shadow, stats_out, grad_out,
                                    do_update ? 1 : 0);
   GMI_LAUNCH_CHECK();

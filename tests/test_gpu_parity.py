@@ -171,7 +171,7 @@ def _bind_model(g, inst, cfg, theta, rows, dtype=None, with_adam=True):
                                           ("C3", 4096, "bf16"), ("C4", 5000, "bf16"), ("C2", 33, "bf16")])
 @pytest.mark.parametrize("fused", [True, False])
 def test_agent_act_matches_oracle(g, inst, name, n, dtype, fused):
-    g.gmi_set_fusion(inst, fused)
+    g.gmi_set_fusion(inst, 1 if fused else 0)
     cfg = syn.get_config(name)
     shape, theta, env, _, _ = oracle_pieces(cfg, n_envs=n)
     theta = syn.make_model_params(cfg.obs_dim, cfg.act_dim, cfg.hidden, 3, policy_head_scale=1.0)
@@ -196,7 +196,7 @@ def test_agent_act_matches_oracle(g, inst, name, n, dtype, fused):
     eps = px.normal_field(42, px.STREAM_ACTION, 9, n, A, env_offset=100)
     close32(act.cpu().numpy(), mu.cpu().numpy() + np.exp(theta[-A:]) * eps)
     g.gmi_model_destroy(hm)
-    g.gmi_set_fusion(inst, True)
+    g.gmi_set_fusion(inst, 1)
 
 
 # ----------------------------------------------------------------------------- trainer
@@ -225,14 +225,20 @@ def _theta_and_batch(cfg, T, N, seed=1):
     # large-tile kernels (rows >= 8192), ragged against their 256-row tiles
     ("C4", 2, 4200, 8400, "bf16", "bimodal"), ("C3", 3, 3000, 8999, "bf16", "bimodal"),
     ("C2", 2, 8192, 16384, "bf16", "bimodal")])
-def test_gradient_and_stats_match_oracle(g, inst, name, T, N, rows, dtype, ratios):
-    """ratios = "straddle": old/new probability ratios spread smoothly across the clip range, so some
+@pytest.mark.parametrize("fused", [True, False])
+def test_gradient_and_stats_match_oracle(g, inst, name, T, N, rows, dtype, ratios, fused):
+    """fused: row-tile fused trainer kernel (gather + forward + loss + input gradients in one launch)
+    where the model fits it, against the per-layer kernels.
+    ratios = "straddle": old/new probability ratios spread smoothly across the clip range, so some
     samples sit within rounding distance of a clip boundary.  Which side such a sample falls on is a
     yes/no decision taken in the arithmetic of the forward pass; in fp32 both sides agree, in bf16 a
     boundary sample may be clipped on one side and not on the other, which changes the policy
     gradient by that sample's whole contribution.  ratios = "bimodal" keeps every ratio either well
     inside or well outside the clip range, so the decisions agree and the comparison measures the
     arithmetic of the products alone."""
+    if fused and (dtype == "f32" or name == "C4"):
+        pytest.skip("the fused trainer kernel covers bf16 models up to 1 MB of weights")
+    g.gmi_set_fusion(inst, 2 if fused else 0)
     cfg = syn.get_config(name)
     shape, theta = _theta_and_batch(cfg, T, N)
     b, rb, hb = _filled_buffer(g, inst, cfg, T, N, seed=2)
@@ -264,7 +270,7 @@ def test_gradient_and_stats_match_oracle(g, inst, name, T, N, rows, dtype, ratio
     r_stats, r_grad = oppo.ppo_loss_and_grad(theta, shape, flat["obs"][idx], flat["act"][idx], flat["logp"][idx],
                                              flat["adv"][idx], flat["ret"][idx], ohp)
     got_g, got_s = grad.cpu().numpy(), stats.cpu().numpy()
-    assert np.array_equal(got_s, stats2.cpu().numpy())
+    assert np.allclose(got_s, stats2.cpu().numpy(), rtol=1e-5, atol=1e-7)   # evaluate = forward + loss only
     assert 0.02 < r_stats[4] < 0.9                         # the clip is active for part of the batch
     tol = 2e-4 if dtype == "f32" else TOL16
     n_pol = sum(i * o + o for i, o in shape.layer_dims(shape.act_dim))
@@ -301,6 +307,7 @@ def test_gradient_and_stats_match_oracle(g, inst, name, T, N, rows, dtype, ratio
     assert abs(got_s[4] - r_stats[4]) <= (2.0 / rows if dtype == "f32" else 0.01)
     g.gmi_model_destroy(hm)
     g.gmi_buffer_destroy(hb)
+    g.gmi_set_fusion(inst, 1)
 
 
 @pytest.mark.parametrize("n", [1, 1000, 2789, 1 << 20])
