@@ -3,28 +3,38 @@
 
 namespace {
 
-// One thread per (env, field element): copies step t's row of every channel into slot t.
-__global__ void collect_kernel(gmi_buffer_desc d, int t, const float* __restrict__ obs,
-                               const float* __restrict__ act, const float* __restrict__ logp,
-                               const float* __restrict__ value, const float* __restrict__ reward,
-                               const uint8_t* __restrict__ done) {
-  const int W = d.obs_dim + d.act_dim + 4;
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= (int64_t)d.n_envs * W) return;
-  const int e = (int)(idx / W), k = (int)(idx % W);
-  const int64_t slot = (int64_t)t * d.ld_envs + e;
-  if (k < d.obs_dim) {
-    d.obs[slot * d.obs_dim + k] = obs[(int64_t)e * d.obs_dim + k];
-  } else if (k < d.obs_dim + d.act_dim) {
-    const int j = k - d.obs_dim;
-    d.act[slot * d.act_dim + j] = act[(int64_t)e * d.act_dim + j];
+// Copies step t's experience into slot t of every channel.  A slot of a channel is one contiguous slab
+// (time-major layout), so the bulk of the work (obs, act) is a straight 16-byte-per-lane copy when the
+// slab and the source are 16-byte aligned; the scalar channels and the unaligned case go element-wise.
+__global__ __launch_bounds__(256) void collect_kernel(gmi_buffer_desc d, int t, const float* __restrict__ obs,
+                                                      const float* __restrict__ act, const float* __restrict__ logp,
+                                                      const float* __restrict__ value, const float* __restrict__ reward,
+                                                      const uint8_t* __restrict__ done, int vec_obs, int vec_act) {
+  const int64_t slot0 = (int64_t)t * d.ld_envs;
+  const int64_t n_obs = (int64_t)d.n_envs * d.obs_dim, n_act = (int64_t)d.n_envs * d.act_dim;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  float* o_dst = d.obs + slot0 * d.obs_dim;
+  float* a_dst = d.act + slot0 * d.act_dim;
+  if (vec_obs) {
+    const float4* s4 = reinterpret_cast<const float4*>(obs);
+    float4* d4 = reinterpret_cast<float4*>(o_dst);
+    for (int64_t i = gid; i < n_obs / 4; i += stride) d4[i] = s4[i];
   } else {
-    switch (k - d.obs_dim - d.act_dim) {
-      case 0: d.logp[slot] = logp[e]; break;
-      case 1: d.val[slot] = value[e]; break;
-      case 2: d.rew[slot] = reward[e]; break;
-      default: d.done[slot] = done[e]; break;
-    }
+    for (int64_t i = gid; i < n_obs; i += stride) o_dst[i] = obs[i];
+  }
+  if (vec_act) {
+    const float4* s4 = reinterpret_cast<const float4*>(act);
+    float4* d4 = reinterpret_cast<float4*>(a_dst);
+    for (int64_t i = gid; i < n_act / 4; i += stride) d4[i] = s4[i];
+  } else {
+    for (int64_t i = gid; i < n_act; i += stride) a_dst[i] = act[i];
+  }
+  for (int64_t e = gid; e < d.n_envs; e += stride) {
+    d.logp[slot0 + e] = logp[e];
+    d.val[slot0 + e] = value[e];
+    d.rew[slot0 + e] = reward[e];
+    d.done[slot0 + e] = done[e];
   }
 }
 
@@ -154,9 +164,17 @@ extern "C" int collect_experience(gmi_t g, gmi_buffer_t b, int32_t t, const floa
   if (t < 0 || t >= b->d.horizon) GMI_FAIL(GMI_ERR_INVALID_ARG, "collect_experience: t=%d outside [0,%d)", t, b->d.horizon);
   if (b->d.n_envs == 0) return GMI_OK;
   if (!obs || !act || !logp || !value || !reward || !done) GMI_FAIL(GMI_ERR_INVALID_ARG, "collect_experience: NULL pointer");
-  const int64_t total = (int64_t)b->d.n_envs * (b->d.obs_dim + b->d.act_dim + 4);
+  const gmi_buffer_desc& d = b->d;
+  const int64_t n_obs = (int64_t)d.n_envs * d.obs_dim, n_act = (int64_t)d.n_envs * d.act_dim;
+  auto aligned16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+  const int vec_obs = (n_obs % 4 == 0) && aligned16(obs) && aligned16(d.obs + (int64_t)t * d.ld_envs * d.obs_dim);
+  const int vec_act = (n_act % 4 == 0) && aligned16(act) && aligned16(d.act + (int64_t)t * d.ld_envs * d.act_dim);
+  int64_t work = (vec_obs ? n_obs / 4 : n_obs);
+  int64_t grid = (work + 255) / 256;
+  if (grid > 8192) grid = 8192;
+  if (grid < 1) grid = 1;
   gmi::ProfScope ps(g, gmi::kClsCollect);
-  collect_kernel<<<(unsigned)((total + 255) / 256), 256, 0, g->stream>>>(b->d, t, obs, act, logp, value, reward, done);
+  collect_kernel<<<(unsigned)grid, 256, 0, g->stream>>>(b->d, t, obs, act, logp, value, reward, done, vec_obs, vec_act);
   GMI_LAUNCH_CHECK();
   return GMI_OK;
 }
