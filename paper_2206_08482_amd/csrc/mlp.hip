@@ -355,7 +355,9 @@ __global__ __launch_bounds__(256) void linear_bf16_big_kernel(gmi::LinearBatch b
 // stages one 8 (rows) x 8 (features) block per step and transposes it in registers so that LDS holds
 // [feature][row] with rows contiguous.
 __device__ __forceinline__ void transpose8x8(const uint4 in[8], uint4 out[8]) {
-  // in[j] = 8 bf16 of row j (features 0..7); out[i] = 8 bf16 of feature i (rows 0..7)
+  // in[j] = 8 bf16 of row j (features 0..7); out[i] = 8 bf16 of feature i (rows 0..7).
+  // One byte-permute per output dword: low halves (even feature) or high halves (odd feature) of the
+  // same dword of two consecutive rows.
   const uint32_t* s = reinterpret_cast<const uint32_t*>(in);
   uint32_t* d = reinterpret_cast<uint32_t*>(out);
 #pragma unroll
@@ -364,7 +366,8 @@ __device__ __forceinline__ void transpose8x8(const uint4 in[8], uint4 out[8]) {
     for (int p = 0; p < 4; ++p) {
       const uint32_t a = s[(2 * p) * 4 + (i >> 1)];       // row 2p,   features (i&~1), (i|1)
       const uint32_t b = s[(2 * p + 1) * 4 + (i >> 1)];   // row 2p+1
-      d[i * 4 + p] = (i & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
+      // v_perm_b32(S0 = b, S1 = a): selector bytes index {S1: 0..3, S0: 4..7}
+      d[i * 4 + p] = __builtin_amdgcn_perm(b, a, (i & 1) ? 0x07060302u : 0x05040100u);
     }
   }
 }
@@ -417,19 +420,33 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(gmi::WgradBatch batch, 
   for (int v = 0; v < 8; ++v) ones[v] = (__bf16)1.0f;
 
   uint4 st0[8], st1[8];
+  // row pointers of the thread's 8 rows for the stage being loaded next; advanced by 64 rows per stage.
+  // Stages wholly inside [row_begin, row_end) need neither clamping nor masking.
+  const int64_t ld64 = ld;
   auto load_stage = [&](uint4* st, int rbase) {
+    if (rbase + kBK <= row_end) {
+      const uint16_t* p = src + (int64_t)(rbase + rblk * 8) * ld64;
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-      st[j] = *reinterpret_cast<const uint4*>(src + (int64_t)min(rbase + rblk * 8 + j, rows - 1) * ld);
+      for (int j = 0; j < 8; ++j) st[j] = *reinterpret_cast<const uint4*>(p + j * ld64);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        st[j] = *reinterpret_cast<const uint4*>(src + (int64_t)min(rbase + rblk * 8 + j, rows - 1) * ld64);
+    }
   };
   // rows past the split (and feature blocks past the operand) are zeroed here, when the data is consumed,
   // not at load time: touching a loaded register right after the load would stall on it
   auto store_stage = [&](const uint4* st, int buf, int rbase) {
     uint4 m[8], tr[8];
+    if (rbase + kBK <= row_end && feat_ok) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const uint32_t k = (rbase + rblk * 8 + j < row_end && feat_ok) ? 0xFFFFFFFFu : 0u;
-      m[j] = make_uint4(st[j].x & k, st[j].y & k, st[j].z & k, st[j].w & k);
+      for (int j = 0; j < 8; ++j) m[j] = st[j];
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint32_t k = (rbase + rblk * 8 + j < row_end && feat_ok) ? 0xFFFFFFFFu : 0u;
+        m[j] = make_uint4(st[j].x & k, st[j].y & k, st[j].z & k, st[j].w & k);
+      }
     }
     transpose8x8(m, tr);
 #pragma unroll
