@@ -228,7 +228,20 @@ int launch_permutation(gmi_instance* g, int n, uint64_t seed, uint32_t iteration
 }  // namespace gmi
 
 namespace gmi {
-constexpr int kSplitMax = 16;        // row splits of the weight-gradient reduction
+constexpr int kSplitMin = 16;        // row splits of the weight-gradient reduction: lower and
+constexpr int kSplitMax = 32;        // upper bound of the per-model choice below
+
+// Row splits for a weight-gradient launch over n_tiles 128x128 output tiles.  Two workgroups fit a
+// compute unit, so up to 512 are resident at once; few-tile models get more splits to approach that.
+// The count stays a multiple of 8: workgroups go round-robin over the 8 XCDs, so with split = index % count
+// every tile of one split (which reads the same rows) lands on the same XCD and shares its L2.  Counts
+// that are not a multiple of 8 measured 1.4-2x slower.
+static inline int wgrad_split_limit(int n_tiles) {
+  int s = (512 / (n_tiles > 0 ? n_tiles : 1)) / 8 * 8;
+  if (s < kSplitMin) s = kSplitMin;
+  if (s > kSplitMax) s = kSplitMax;
+  return s;
+}
 constexpr int kLossBlocksMax = 2048; // rows of per-workgroup loss statistics (one more row holds their sum)
 constexpr int kStatStride = 8;       // per-workgroup statistics slots before the log_std partials
 

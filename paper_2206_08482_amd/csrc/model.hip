@@ -241,7 +241,13 @@ extern "C" int gmi_model_bind(gmi_t g, const gmi_model_desc* d, float* params, v
   m->shadow = (char*)shadow;
   m->adam_m = adam_m;
   m->adam_v = adam_v;
-  m->n_split_max = gmi::kSplitMax;
+  {
+    int n_tiles = 0;
+    for (int net = 0; net < 2; ++net)
+      for (int l = 0; l < L.n_layers; ++l)
+        n_tiles += ((L.net[net][l].out_pad + 127) / 128) * ((L.net[net][l].in_pad + 127) / 128);
+    m->n_split_max = gmi::wgrad_split_limit(n_tiles);
+  }
 
   const int64_t rows = d->max_rows;
   const size_t es = gmi::elem_size(L.dtype);
@@ -270,7 +276,7 @@ extern "C" int gmi_model_bind(gmi_t g, const gmi_model_desc* d, float* params, v
     m->mb_logp = (float*)take(rows * 4);
     m->mb_adv = (float*)take(rows * 4);
     m->mb_ret = (float*)take(rows * 4);
-    m->grad_part = (float*)take((int64_t)gmi::kSplitMax * L.n_params * 4);
+    m->grad_part = (float*)take((int64_t)m->n_split_max * L.n_params * 4);
     m->stat_part = (float*)take((int64_t)(gmi::kLossBlocksMax + 1) * (gmi::kStatStride + A) * 4);
     if (pass == 0) {
       m->ws_bytes = (size_t)off;

@@ -114,7 +114,7 @@ extern "C" int gmi_measure_peak(gmi_t g, int what, void* scratch, size_t scratch
 }
 
 // Micro-benchmark of one linear-layer product on synthetic operands carved out of `scratch`:
-// kind 0 = forward (bias + ELU), 2 = input gradient (ELU' epilogue), 3 = weight gradient (16 splits).
+// kind 0 = forward (bias + ELU), 2 = input gradient (ELU' epilogue), 3 = weight gradient (the split count a model of these tiles would get).
 // rows x K -> F (all padded to multiples of 32 by the caller), n_nets problems per launch, bf16.
 // Returns the average microseconds per launch over `reps` back-to-back launches.
 extern "C" int gmi_bench_linear(gmi_t g, int kind, int rows, int K, int F, int n_nets, int reps, void* scratch,
@@ -145,11 +145,12 @@ extern "C" int gmi_bench_linear(gmi_t g, int kind, int rows, int K, int F, int n
     r.dz = y; r.lddz = F; r.x = x; r.ldx = K; r.out = F; r.in = K; r.out_pad = F; r.in_pad = K;
     r.w_off = (int64_t)z * ((int64_t)K * F + F); r.b_off = r.w_off + (int64_t)K * F;
   }
-  if (kind == 3) part = (float*)take((size_t)gmi::kSplitMax * P * 4);
+  const int n_split = gmi::wgrad_split_limit(n_nets * ((F + 127) / 128) * ((K + 127) / 128));
+  if (kind == 3) part = (float*)take((size_t)n_split * P * 4);
   if (off > scratch_bytes) GMI_FAIL(GMI_ERR_BAD_SHAPE, "gmi_bench_linear: scratch too small (%zu needed)", off);
-  const int chunk = ((rows + gmi::kSplitMax - 1) / gmi::kSplitMax + 63) / 64 * 64;
+  const int chunk = ((rows + n_split - 1) / n_split + 63) / 64 * 64;
   auto launch = [&]() -> int {
-    if (kind == 3) return gmi::launch_wgrad(g, GMI_DTYPE_BF16, rows, gmi::kSplitMax, chunk, wb, part, P);
+    if (kind == 3) return gmi::launch_wgrad(g, GMI_DTYPE_BF16, rows, n_split, chunk, wb, part, P);
     return gmi::launch_linear(g, GMI_DTYPE_BF16, kind == 0 ? gmi::kEpiBiasElu : gmi::kEpiEluGrad, rows, lb);
   };
   hipEvent_t e0, e1;

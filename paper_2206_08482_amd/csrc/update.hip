@@ -103,9 +103,26 @@ struct AdamScalars {
   float lr, b1, b2, eps, c1, c2;   // c1 = 1 - b1^k, c2 = 1 - b2^k
 };
 
-// One thread per parameter: reduce the gradient partials, Adam, and (BF16) refresh the shadow copies.
-// grad(p) = sum_s part[s * part_stride + p] for p < logstd_off, else the loss kernel's log_std partials
-// minus the entropy coefficient.  Workgroup 0 also finalises the minibatch statistics.
+// Adam step of one parameter given its gradient (Adam as in the PPO trainer of Section 2: bias-corrected
+// moments, epsilon outside the square root).
+__device__ __forceinline__ float adam_one(float g, float* __restrict__ params, float* __restrict__ am,
+                                          float* __restrict__ av, int64_t p, const AdamScalars& hs) {
+  const float m = hs.b1 * am[p] + (1.0f - hs.b1) * g;
+  const float v = hs.b2 * av[p] + (1.0f - hs.b2) * g * g;
+  am[p] = m;
+  av[p] = v;
+  const float w = params[p] - hs.lr * (m / hs.c1) / (sqrtf(v / hs.c2) + hs.eps);
+  params[p] = w;
+  return w;
+}
+
+// One thread per weight / bias: reduce the gradient partials, Adam, and (BF16) refresh the bias and the
+// [out_pad, in_pad] weight shadow (the transposed shadow is rebuilt by shadow_transpose_kernel).
+// grad(p) = sum_s part[s * part_stride + p].
+// The last workgroup instead finalises the minibatch statistics and owns log_std, whose gradient is the sum
+// of the loss kernel's per-workgroup partials minus the entropy coefficient; it reduces the
+// [n_loss_blocks, kStatStride + A] partials cooperatively (a serial walk by one thread per column costs
+// one memory round trip per loss workgroup).
 __global__ __launch_bounds__(256) void adam_kernel(gmi::ShadowTable tab, int write_shadow, float* __restrict__ params,
                                                    float* __restrict__ am, float* __restrict__ av,
                                                    const float* __restrict__ part, int n_split, int64_t part_stride,
@@ -113,34 +130,62 @@ __global__ __launch_bounds__(256) void adam_kernel(gmi::ShadowTable tab, int wri
                                                    float c_e, float inv_rows, AdamScalars hs, char* __restrict__ shadow,
                                                    float* __restrict__ stats_out, float* __restrict__ grad_out,
                                                    int do_update) {
-  const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (blockIdx.x == 0 && threadIdx.x < 5 && stats_out && stat_part) {
-    float s = 0.f;
-    for (int b = 0; b < n_loss_blocks; ++b) s += stat_part[(int64_t)b * (gmi::kStatStride + A) + threadIdx.x];
-    stats_out[threadIdx.x] = threadIdx.x == 2 ? s : s * inv_rows;
+  if (blockIdx.x == gridDim.x - 1) {
+    __shared__ float s_col[256];
+    const int C = gmi::kStatStride + A;              // columns of a statistics row
+    const int tid = threadIdx.x;
+    // up to 256 columns per pass; narrow rows are walked by 256 / C row groups in parallel
+    const int width = C < 256 ? C : 256;
+    const int groups = 256 / width;
+    for (int cbase = 0; cbase < C; cbase += 256) {
+      const int col = cbase + tid % width, grp = tid / width;
+      float s = 0.f;
+      if (stat_part && grp < groups && col < C)
+        for (int b = grp; b < n_loss_blocks; b += groups) s += stat_part[(int64_t)b * C + col];
+      s_col[tid] = s;
+      __syncthreads();
+      const int c = cbase + tid;
+      if (tid < width && c < C) {
+        float t = 0.f;
+        for (int q = 0; q < groups; ++q) t += s_col[q * width + tid];
+        if (stat_part && stats_out && c < 5) stats_out[c] = c == 2 ? t : t * inv_rows;
+        if (c >= gmi::kStatStride) {
+          const int j = c - gmi::kStatStride;
+          const int64_t p = tab.logstd_off + j;
+          // without loss partials (a caller-supplied gradient) log_std takes the split sums like any weight
+          float g = 0.f;
+          if (stat_part) g = t - c_e;
+          else for (int q = 0; q < n_split; ++q) g += part[(int64_t)q * part_stride + p];
+          if (grad_out) grad_out[p] = g;
+          if (do_update) {
+            const float w = adam_one(g, params, am, av, p, hs);
+            if (write_shadow) reinterpret_cast<float*>(shadow + tab.sh_logstd)[j] = w;
+          }
+        }
+      }
+      __syncthreads();
+    }
+    return;
   }
-  if (p >= tab.n_params) return;
+  const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (p >= tab.logstd_off) return;
   float g = 0.f;
-  if (p >= tab.logstd_off && stat_part) {
-    const int j = (int)(p - tab.logstd_off);
-    for (int b = 0; b < n_loss_blocks; ++b) g += stat_part[(int64_t)b * (gmi::kStatStride + A) + gmi::kStatStride + j];
-    g -= c_e;
-  } else {
-    for (int s = 0; s < n_split; ++s) g += part[(int64_t)s * part_stride + p];
+  {
+    const float* q = part + p;
+    int sidx = 0;
+    for (; sidx + 8 <= n_split; sidx += 8) {
+      float t[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t[u] = q[(int64_t)(sidx + u) * part_stride];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) g += t[u];
+    }
+    for (; sidx < n_split; ++sidx) g += q[(int64_t)sidx * part_stride];
   }
   if (grad_out) grad_out[p] = g;
   if (!do_update) return;
-  const float m = hs.b1 * am[p] + (1.0f - hs.b1) * g;
-  const float v = hs.b2 * av[p] + (1.0f - hs.b2) * g * g;
-  am[p] = m;
-  av[p] = v;
-  const float w = params[p] - hs.lr * (m / hs.c1) / (sqrtf(v / hs.c2) + hs.eps);
-  params[p] = w;
+  const float w = adam_one(g, params, am, av, p, hs);
   if (!write_shadow) return;
-  if (p >= tab.logstd_off) {
-    reinterpret_cast<float*>(shadow + tab.sh_logstd)[p - tab.logstd_off] = w;
-    return;
-  }
   int li = 0;
   while (li + 1 < tab.n && p >= tab.l[li + 1].w_off) ++li;
   const gmi::ShadowLayer& L = tab.l[li];
@@ -149,9 +194,49 @@ __global__ __launch_bounds__(256) void adam_kernel(gmi::ShadowTable tab, int wri
   } else {
     const int64_t q = p - L.w_off;
     const int o = (int)(q / L.in), i = (int)(q % L.in);
-    const uint16_t b = f_to_bf16_u(w);
-    reinterpret_cast<uint16_t*>(shadow + L.sh_w)[(int64_t)o * L.in_pad + i] = b;
-    reinterpret_cast<uint16_t*>(shadow + L.sh_wt)[(int64_t)i * L.out_pad + o] = b;
+    reinterpret_cast<uint16_t*>(shadow + L.sh_w)[(int64_t)o * L.in_pad + i] = f_to_bf16_u(w);
+  }
+}
+
+// Rebuilds the transposed weight shadows [in_pad, out_pad] from the [out_pad, in_pad] ones through
+// 64x64 LDS tiles, so that both sides move whole 16-byte pieces (one 2-byte store per weight into the
+// transposed copy touched a different memory line for every thread of a wave).
+struct TransposeTiles {
+  int n;
+  int start[gmi::kMaxWgradProblems + 1];
+};
+__global__ __launch_bounds__(256) void shadow_transpose_kernel(gmi::ShadowTable tab, TransposeTiles tt,
+                                                               char* __restrict__ shadow) {
+  __shared__ __attribute__((aligned(16))) uint16_t s_t[64][72];
+  int li = 0;
+  while (li + 1 < tt.n && (int)blockIdx.x >= tt.start[li + 1]) ++li;
+  const gmi::ShadowLayer& L = tab.l[li];
+  const int local = blockIdx.x - tt.start[li];
+  const int n_ti = (L.in_pad + 63) / 64;
+  const int o0 = (local / n_ti) * 64, i0 = (local % n_ti) * 64;
+  const uint16_t* __restrict__ w = reinterpret_cast<const uint16_t*>(shadow + L.sh_w);
+  uint16_t* __restrict__ wt = reinterpret_cast<uint16_t*>(shadow + L.sh_wt);
+  const int tid = threadIdx.x, c8 = (tid & 7) * 8, r = tid >> 3;
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int o = o0 + r + 32 * k, i = i0 + c8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (o < L.out_pad && i < L.in_pad) v = *reinterpret_cast<const uint4*>(w + (int64_t)o * L.in_pad + i);
+    *reinterpret_cast<uint4*>(&s_t[r + 32 * k][c8]) = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int i = i0 + r + 32 * k, o = o0 + c8;
+    if (i < L.in_pad && o < L.out_pad) {
+      uint16_t e[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) e[j] = s_t[c8 + j][r + 32 * k];
+      uint4 v;
+      v.x = e[0] | ((uint32_t)e[1] << 16); v.y = e[2] | ((uint32_t)e[3] << 16);
+      v.z = e[4] | ((uint32_t)e[5] << 16); v.w = e[6] | ((uint32_t)e[7] << 16);
+      *reinterpret_cast<uint4*>(wt + (int64_t)i * L.out_pad + o) = v;
+    }
   }
 }
 
@@ -247,7 +332,7 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
   }  // !fused
   // weight / bias gradients of every layer of both nets in one launch
   int n_split = (rows + 63) / 64;
-  if (n_split > gmi::kSplitMax) n_split = gmi::kSplitMax;
+  if (n_split > m->n_split_max) n_split = m->n_split_max;
   if (n_split < 1) n_split = 1;
   int chunk = (rows + n_split - 1) / n_split;
   chunk = (chunk + 63) / 64 * 64;
@@ -271,17 +356,31 @@ int launch_adam(gmi_instance* g, gmi_model* m, int n_split, int n_loss_blocks, c
   const gmi::ShadowTable tab = gmi::make_shadow_table(m->L);
   gmi::ProfScope ps(g, gmi::kClsAdam);
   hipStream_t s = g->stream;
-  const unsigned grid = (unsigned)((m->L.n_params + 255) / 256);
+  // one workgroup per 256 weights / biases plus one for the statistics and log_std
+  const unsigned grid = (unsigned)((m->L.logstd_off + 255) / 256) + 1;
   const float* stat = m->stat_part;
   if (n_loss_blocks < 0) {
     stat = m->stat_part + (int64_t)gmi::kLossBlocksMax * (gmi::kStatStride + m->L.act_dim);
     n_loss_blocks = 1;
   }
-  adam_kernel<<<grid, 256, 0, s>>>(tab, m->L.dtype == GMI_DTYPE_BF16 ? 1 : 0, m->params, m->adam_m, m->adam_v,
+  const bool bf = m->L.dtype == GMI_DTYPE_BF16;
+  adam_kernel<<<grid, 256, 0, s>>>(tab, bf ? 1 : 0, m->params, m->adam_m, m->adam_v,
                                    m->grad_part, n_split, m->L.n_params, stat, n_loss_blocks, m->L.act_dim,
                                    hp->c_e, 1.0f / (float)rows, adam_scalars(hp, k), m->shadow, stats_out, grad_out,
                                    do_update ? 1 : 0);
   GMI_LAUNCH_CHECK();
+  if (bf && do_update) {
+    TransposeTiles tt;
+    tt.n = tab.n;
+    int total = 0;
+    for (int i = 0; i < tab.n; ++i) {
+      tt.start[i] = total;
+      total += ((tab.l[i].out_pad + 63) / 64) * ((tab.l[i].in_pad + 63) / 64);
+    }
+    tt.start[tab.n] = total;
+    shadow_transpose_kernel<<<total, 256, 0, s>>>(tab, tt, m->shadow);
+    GMI_LAUNCH_CHECK();
+  }
   return GMI_OK;
 }
 
@@ -373,7 +472,7 @@ extern "C" int adam_update(gmi_t g, float* params, float* adam_m, float* adam_v,
   tab.act_dim = 0;
   tab.n_params = n;
   gmi::ProfScope ps(g, gmi::kClsAdam);
-  adam_kernel<<<(unsigned)((n + 255) / 256), 256, 0, g->stream>>>(tab, 0, params, adam_m, adam_v, grad, 1, n, nullptr, 0,
+  adam_kernel<<<(unsigned)((n + 255) / 256) + 1, 256, 0, g->stream>>>(tab, 0, params, adam_m, adam_v, grad, 1, n, nullptr, 0,
                                                                 0, 0.f, 1.f, adam_scalars(hp, step), nullptr, nullptr,
                                                                 nullptr, 1);
   GMI_LAUNCH_CHECK();
