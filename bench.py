@@ -36,8 +36,28 @@ def mac_per_sample(cfg, first_layer=True):
     return total
 
 
-def class_work(cfg, n_params):
-    """Algorithmic work per *step* of every kernel class: (flops, bytes, launches, bound)."""
+def pad32(x):
+    return (x + 31) // 32 * 32
+
+
+def layer_bytes_per_sample(cfg, es, first_layer=True):
+    """Activation bytes one sample moves through the per-layer kernels of both nets: each layer reads its
+    (padded) input row and writes its (padded) output row; the fp32 heads write 4 bytes per output."""
+    total = 0
+    for out_dim in (cfg.act_dim, 1):
+        prev = cfg.obs_dim
+        dims = list(cfg.hidden) + [out_dim]
+        for li, h in enumerate(dims):
+            if first_layer or li > 0:
+                total += pad32(prev) * es + (4 * h if li == len(dims) - 1 else pad32(h) * es)
+            prev = h
+    return total
+
+
+def class_work(cfg, n_params, launched):
+    """Algorithmic work per *step* of every kernel class: flops and/or HBM bytes and launches.
+    `launched` maps class name -> launches seen in the profiled step; it tells which of the alternative
+    paths (per-layer, fused agent, one-launch rollout, fused trainer) carried the rollout's forward passes."""
     N, T, B, MB, E = cfg.n_envs, cfg.horizon, cfg.batch, cfg.minibatch, cfg.epochs
     O, A, L = cfg.obs_dim, cfg.act_dim, len(cfg.hidden)
     mac = mac_per_sample(cfg)
@@ -45,30 +65,43 @@ def class_work(cfg, n_params):
     mac_value = sum(a * b for a, b in zip([O] + list(cfg.hidden), list(cfg.hidden) + [1]))
     n_upd = E * (B // MB)
     es = 2 if cfg.dtype == "bf16" else 4
-    width = sum(cfg.hidden)
+    w_bytes = n_params * es
+    act_b = layer_bytes_per_sample(cfg, es)
+    act_b_dgrad = layer_bytes_per_sample(cfg, es, first_layer=False)
+    rollout_flops = 2.0 * (T * N * mac + N * mac_value)
+    per_layer_rollout = not (launched.get("fused_agent") or launched.get("fused_rollout"))
+    per_layer_update = not launched.get("fused_train")
+    fwd_flops = (rollout_flops if per_layer_rollout else 0.0) + (2.0 * n_upd * MB * mac if per_layer_update else 0.0)
+    fwd_rows = ((T + 0.5) * N if per_layer_rollout else 0.0) + (n_upd * MB if per_layer_update else 0.0)
+    fwd_launches = ((T + 1) * (L + 1) if per_layer_rollout else 0) + (n_upd * (L + 1) if per_layer_update else 0)
+    exp_bytes = T * N * (4.0 * (O + A + 3) + 1)               # one step's experience slot, all envs
     return {
-        # forward launches: T agent_act + 1 bootstrap (value net only) + one per update, L+1 layers each
-        "linear_fwd": dict(flops=2.0 * (T * N * mac + N * mac_value + n_upd * MB * mac),
-                           launches=(T + 1 + n_upd) * (L + 1), bound="mfma"),
-        "linear_dgrad": dict(flops=2.0 * n_upd * MB * mac_dgrad, launches=n_upd * L, bound="mfma"),
-        "wgrad": dict(flops=2.0 * n_upd * MB * mac, launches=n_upd, bound="mfma"),
-        "gather": dict(bytes=(T + 1) * N * O * (4 + es) + n_upd * MB * (O * (4 + es) + 8.0 * (A + 3) + 4),
-                       launches=T + 1 + n_upd, bound="hbm"),
-        "loss": dict(bytes=n_upd * MB * (4.0 * (2 * A + 5) + es * (A + 1)), launches=n_upd, bound="hbm"),
-        "adam": dict(bytes=n_upd * n_params * (16.0 + 12.0 + (4 if cfg.dtype == "bf16" else 0)),
-                     launches=n_upd, bound="hbm"),
-        "env_step": dict(bytes=T * N * (4.0 * (2 * O + A) + 8 + 1), flops=T * N * (2.0 * O * (O + A) + 3 * O + 2 * A),
-                         launches=T, bound="hbm"),
-        "sample": dict(bytes=T * N * 4.0 * (2 * A + 1), launches=T, bound="hbm"),
-        "collect": dict(bytes=T * N * 2 * (4.0 * (O + A + 3) + 1), launches=T, bound="hbm"),
-        "gae": dict(bytes=B * (9.0 + 8.0 + 8.0) + 4.0 * N, launches=1, bound="hbm"),
-        "permutation": dict(bytes=E * B * 4.0, launches=E, bound="hbm"),
+        "linear_fwd": dict(flops=fwd_flops, bytes=fwd_rows * act_b + fwd_launches / (L + 1) * w_bytes,
+                           launches=fwd_launches),
+        # input gradients: read dz[l] and h[l], write dz[l-1]
+        "linear_dgrad": dict(flops=2.0 * n_upd * MB * mac_dgrad,
+                             bytes=n_upd * (MB * (act_b_dgrad + sum(pad32(h) for h in cfg.hidden) * es * 2) + w_bytes),
+                             launches=n_upd * L),
+        # weight gradients: read every layer's input and output gradient once, write the fp32 gradient
+        "wgrad": dict(flops=2.0 * n_upd * MB * mac, bytes=n_upd * (MB * act_b + 4.0 * n_params), launches=n_upd),
+        "gather": dict(bytes=(T + 1) * N * O * (4 + es) * (1 if per_layer_rollout else 0)
+                       + n_upd * MB * (O * (4 + es) + 8.0 * (A + 3) + 4),
+                       launches=(T + 1 if per_layer_rollout else 0) + n_upd),
+        "loss": dict(bytes=n_upd * MB * (4.0 * (2 * A + 5) + es * (A + 1)), launches=n_upd),
+        "adam": dict(bytes=n_upd * n_params * (16.0 + 12.0 + (4 if cfg.dtype == "bf16" else 0)), launches=n_upd),
+        "env_step": dict(bytes=T * N * (4.0 * (2 * O + A) + 8 + 1), launches=T),
+        "sample": dict(bytes=T * N * 4.0 * (2 * A + 1), launches=T),
+        "collect": dict(bytes=2 * exp_bytes, launches=T),
+        "gae": dict(bytes=B * (9.0 + 8.0 + 8.0) + 4.0 * N, launches=1),
+        "permutation": dict(bytes=E * B * 4.0, launches=E),
         # fused kernels: all layers of both nets for a tile of rows in one launch
-        "fused_agent": dict(flops=2.0 * (T * N * mac + N * mac_value), launches=T + 1, bound="mfma"),
-        "fused_train": dict(flops=2.0 * n_upd * MB * (mac + mac_dgrad), launches=n_upd, bound="mfma"),
-        "fused_rollout": dict(flops=2.0 * (T * N * mac + N * mac_value), launches=1, bound="mfma"),
-        "reduce": dict(bytes=n_upd * (MB / 64.0) * 4.0 * (A + 8), launches=n_upd, bound="hbm"),
-    }
+        "fused_agent": dict(flops=rollout_flops, bytes=T * N * 4.0 * (O + 2 * A + 2) + (T + 1) * w_bytes,
+                            launches=T + 1),
+        "fused_train": dict(flops=2.0 * n_upd * MB * (mac + mac_dgrad), bytes=n_upd * MB * 2.0 * act_b,
+                            launches=n_upd),
+        "fused_rollout": dict(flops=rollout_flops, bytes=exp_bytes + 8.0 * N * O + w_bytes, launches=1),
+        "reduce": dict(bytes=n_upd * (MB / 64.0) * 4.0 * (A + 8), launches=n_upd),
+    }, 2.0 * (T * N * mac + N * mac_value + n_upd * MB * (2 * mac + mac_dgrad))
 
 
 def cpu_baseline(cfg, budget_s=12.0):
@@ -182,14 +215,17 @@ def main() -> int:
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = args.steps * cfg.batch / (t1 - t0)
-    work = class_work(cfg, int(ses.theta.numel()))
+    work, flops_step = class_work(cfg, int(ses.theta.numel()), {k: v[1] for k, v in per_class.items()})
     w = work[dominant]
     avg_ms = dom_ms / max(dom_launches, 1)
     launches_per_step = w["launches"]
-    if w["bound"] == "mfma":
+    # the roof that bounds this class: the larger of its matrix-core time and its HBM time at the peaks
+    peak_flops = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
+    t_mfma = w.get("flops", 0.0) / (peak_flops * 1e12)
+    t_hbm = w.get("bytes", 0.0) / (PEAK_HBM_GBS * 1e9)
+    if t_mfma >= t_hbm:
         achieved = w["flops"] / launches_per_step / (avg_ms * 1e-3) / 1e12
-        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS,
-                "unit": "TFLOP/s"}
+        roof = {"bound": "mfma", "achieved": achieved, "peak": peak_flops, "unit": "TFLOP/s"}
     else:
         achieved = w["bytes"] / launches_per_step / (avg_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
@@ -198,10 +234,12 @@ def main() -> int:
     roof["kernel"] = dominant
     roof["avg_launch_us"] = avg_ms * 1e3
     roof["launches_timed"] = dom_launches
+    if "flops" in w and w["flops"]:
+        roof["tflops"] = w["flops"] / launches_per_step / (avg_ms * 1e-3) / 1e12
+    roof["algorithmic_bytes_per_launch"] = w.get("bytes", 0.0) / launches_per_step
 
     total_ms = sum(v[0] for v in per_class.values())
     breakdown = {k: {"ms_per_step": round(v[0], 4), "launches": v[1]} for k, v in per_class.items() if v[1]}
-    flops_step = sum(x.get("flops", 0.0) for k, x in work.items() if x["bound"] == "mfma")
     out = {
         "metric": "PPO samples/sec (rollout+update) on 1 MI355X",
         "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

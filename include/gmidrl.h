@@ -195,6 +195,19 @@ int collect_experience(gmi_t gmi, gmi_buffer_t buf, int32_t t, const float* obs,
                        const float* logp, const float* value, const float* reward,
                        const uint8_t* done);
 
+/* The whole experience-collection stage (Section 5.1, stage (i)) of one instance that hosts simulator and
+ * agent together (Section 3): for t = 0 .. T-1 (T = the buffer's horizon), with step = step0 + t,
+ *   agent_act(obs_t) -> env_step(obs_t, act_t) -> collect_experience(slot t), obs_{t+1} = next_obs,
+ * then last_value = V(obs_T).  Same arithmetic and Philox counters as those calls made one by one, but one
+ * launch: each workgroup keeps its envs' state on chip for all T steps.
+ *  obs dev [N,O]: in = obs_0, out = obs_T (updated in place); last_value dev [N] out;
+ *  seed / env_offset: the agent's (as in agent_act); the simulator uses its binding's own.
+ *  The env's episode_step array advances by T steps.  BF16 models only, whose weight shadow is at most
+ *  2 MiB and whose 32-env tile fits the on-chip memory: otherwise GMI_ERR_UNSUPPORTED and nothing has run
+ *  (use the per-step calls, which are the faster path for larger models). */
+int rollout_collect(gmi_t gmi, gmi_model_t model, gmi_env_t env, gmi_buffer_t buf, float* obs,
+                    uint64_t seed, uint32_t step0, uint32_t env_offset, float* last_value);
+
 /* Generalized advantage estimation over the horizon, then returns, then optional normalisation:
  *   delta_t = r_t + gamma v_{t+1} (1-d_t) - v_t (v_T = last_value),  A_t = delta_t + gamma lambda (1-d_t) A_{t+1}
  *   ret = A + v;  normalize != 0: A <- (A - mean) / (std + 1e-8) over all T*N entries.

@@ -25,7 +25,7 @@ EXPORTS = [
     "agent_act", "agent_value", "gmi_buffer_bind", "gmi_buffer_destroy", "collect_experience",
     "gae_compute", "ppo_update", "ppo_evaluate", "ppo_gradient", "adam_update", "gmi_noise_fill",
     "gmi_permutation", "gmi_profile_enable", "gmi_profile_classes", "gmi_profile_class_name", "gmi_profile_read",
-    "gmi_measure_peak", "gmi_bench_linear", "gmi_set_fusion",
+    "gmi_measure_peak", "gmi_bench_linear", "gmi_set_fusion", "rollout_collect",
 ]
 
 
@@ -87,6 +87,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "gmi_buffer_bind": (C.c_int, [vp, C.POINTER(BufferDesc), C.POINTER(vp)]),
         "gmi_buffer_destroy": (C.c_int, [vp]),
         "collect_experience": (C.c_int, [vp, vp, i32, vp, vp, vp, vp, vp, vp]),
+        "rollout_collect": (C.c_int, [vp, vp, vp, vp, vp, u64, u32, u32, vp]),
         "gae_compute": (C.c_int, [vp, vp, vp, f32, f32, C.c_int]),
         "ppo_update": (C.c_int, [vp, vp, vp, C.POINTER(PPOHparams), vp]),
         "ppo_evaluate": (C.c_int, [vp, vp, vp, C.POINTER(PPOHparams), vp, i32, vp]),
@@ -275,6 +276,11 @@ def gmi_buffer_destroy(buf: int) -> None:
 def collect_experience(gmi: int, buf: int, t: int, obs, act, logp, value, reward, done) -> None:
     _check(_lib.collect_experience(gmi, buf, t, _ptr(obs), _ptr(act), _ptr(logp), _ptr(value),
                                    _ptr(reward), _ptr(done)))
+
+
+def rollout_collect(gmi: int, model: int, env: int, buf: int, obs, seed: int, step0: int, env_offset: int,
+                    last_value) -> None:
+    _check(_lib.rollout_collect(gmi, model, env, buf, _ptr(obs), seed, step0, env_offset, _ptr(last_value)))
 
 
 def gae_compute(gmi: int, buf: int, last_value, gamma: float, lam: float, normalize: bool) -> None:

@@ -12,7 +12,8 @@ import torch
 from . import (DTYPE_BF16, DTYPE_F32, agent_act, agent_value, buffer_desc, collect_experience, env_desc,
                env_step, gae_compute, gmi_buffer_bind, gmi_buffer_destroy, gmi_create, gmi_destroy,
                gmi_env_bind, gmi_env_destroy, gmi_model_bind, gmi_model_destroy, gmi_model_refresh_shadow,
-               gmi_model_shadow_bytes, gmi_stream, gmi_sync, model_desc, ppo_hparams, ppo_update)
+               gmi_model_shadow_bytes, gmi_stream, gmi_sync, model_desc, ppo_hparams, ppo_update,
+               rollout_collect, GmiError, ERR_UNSUPPORTED)
 
 
 def dtype_code(name: str) -> int:
@@ -53,7 +54,8 @@ class PPOSession:
     def __init__(self, *, n_envs: int, obs_dim: int, act_dim: int, hidden: Sequence[int], horizon: int,
                  dtype: str, theta: np.ndarray, a_mat: np.ndarray, b_mat: np.ndarray, state0: np.ndarray,
                  noise_std: float, reward_scale: float, done_period: int, done_threshold: int, seed: int,
-                 minibatch: int, cu_mask: Optional[Sequence[int]] = None, gmi: Optional[int] = None):
+                 minibatch: int, cu_mask: Optional[Sequence[int]] = None, gmi: Optional[int] = None,
+                 fused_rollout: bool = True):
         dev = torch.device("cuda:0")
         self.dev = dev
         self.N, self.O, self.A, self.T = n_envs, obs_dim, act_dim, horizon
@@ -88,11 +90,21 @@ class PPOSession:
         self.reward = torch.zeros(n_envs, **f)
         self.done = torch.zeros(n_envs, dtype=torch.uint8, device=dev)
         self.last_value = torch.zeros(n_envs, **f)
+        self.fused_rollout = fused_rollout and dtype == "bf16"
         torch.cuda.synchronize()
 
     # -- stage (i): experience collection
     def rollout(self, iteration: int) -> None:
         g = self.gmi
+        if self.fused_rollout:
+            try:
+                rollout_collect(g, self.model, self.env, self.buffer, self.obs[self.cur], self.seed,
+                                iteration * self.T, 0, self.last_value)
+                return
+            except GmiError as e:
+                if e.code != ERR_UNSUPPORTED:
+                    raise
+                self.fused_rollout = False      # this model does not fit the one-launch kernel
         for t in range(self.T):
             step = iteration * self.T + t
             obs, nxt = self.obs[self.cur], self.obs[1 - self.cur]

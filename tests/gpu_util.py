@@ -33,7 +33,8 @@ def oracle_pieces(cfg, n_envs=None, seed=None):
     return shape, theta, env, state0, hp
 
 
-def make_session(cfg, theta, env, state0, n_envs=None, minibatch=None, horizon=None, dtype=None):
+def make_session(cfg, theta, env, state0, n_envs=None, minibatch=None, horizon=None, dtype=None,
+                 fused_rollout=True):
     from paper_2206_08482_amd.runner import PPOSession
     n = cfg.n_envs if n_envs is None else n_envs
     return PPOSession(n_envs=n, obs_dim=cfg.obs_dim, act_dim=cfg.act_dim, hidden=cfg.hidden,
@@ -41,4 +42,4 @@ def make_session(cfg, theta, env, state0, n_envs=None, minibatch=None, horizon=N
                       dtype=cfg.dtype if dtype is None else dtype, theta=theta, a_mat=env.a_mat,
                       b_mat=env.b_mat, state0=state0, noise_std=env.noise_std, reward_scale=env.reward_scale,
                       done_period=env.done_period, done_threshold=env.done_threshold, seed=env.seed,
-                      minibatch=cfg.minibatch if minibatch is None else minibatch)
+                      minibatch=cfg.minibatch if minibatch is None else minibatch, fused_rollout=fused_rollout)

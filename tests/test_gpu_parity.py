@@ -329,14 +329,17 @@ def test_adam_matches_oracle_given_identical_gradients(g, inst, n):
     close32(d_v.cpu().numpy(), v)
 
 
-def _run_iteration_both(g, cfg, n_envs, minibatch, horizon, epochs, dtype):
+def _run_iteration_both(g, cfg, n_envs, minibatch, horizon, epochs, dtype, fused_rollout=True):
     shape, theta, env, state0, hp = oracle_pieces(cfg, n_envs=n_envs)
     hp.minibatch, hp.epochs = minibatch, epochs
     z = np.zeros_like(theta)
     ref = oppo.ppo_iteration(theta, z, z, 0, shape, env, state0, np.zeros(n_envs, np.uint32), horizon, hp,
                              cfg.gamma, cfg.lam, cfg.seed, 0)
-    ses = make_session(cfg, theta, env, state0, n_envs=n_envs, minibatch=minibatch, horizon=horizon, dtype=dtype)
+    ses = make_session(cfg, theta, env, state0, n_envs=n_envs, minibatch=minibatch, horizon=horizon, dtype=dtype,
+                       fused_rollout=fused_rollout)
     ses.rollout(0)
+    # the one-launch kernel really ran (C4's weights are beyond its size limit: per-step calls)
+    assert ses.fused_rollout == (fused_rollout and dtype == "bf16" and cfg.name != "C4")
     ses.gae(cfg.gamma, cfg.lam, True)
     nup = epochs * (horizon * n_envs // minibatch)
     stats = zeros(nup, 5)
@@ -382,9 +385,13 @@ def test_whole_iteration_c1_fp32_matches_oracle(g):
 
 @pytest.mark.parametrize("name,n_envs,minibatch,horizon", [("C2", 512, 2048, 8), ("C3", 256, 1024, 8),
                                                            ("C4", 320, 1280, 4)])
-def test_whole_iteration_bf16_matches_oracle(g, name, n_envs, minibatch, horizon):
+@pytest.mark.parametrize("fused_rollout", [True, False])
+def test_whole_iteration_bf16_matches_oracle(g, name, n_envs, minibatch, horizon, fused_rollout):
     cfg = syn.get_config(name)
-    ref, ses, stats, (shape, theta, env, hp) = _run_iteration_both(g, cfg, n_envs, minibatch, horizon, 2, "bf16")
+    ref, ses, stats, (shape, theta, env, hp) = _run_iteration_both(g, cfg, n_envs, minibatch, horizon, 2, "bf16",
+                                                                   fused_rollout)
+    assert rel_l2(ses.state().cpu().numpy(), ref["state"]) <= TOL16
+    assert np.array_equal(ses.episode_step.cpu().numpy().astype(np.uint32), ref["episode_step"])
     got = ses.buf.to_numpy()
     rb = ref["buf"]
     assert np.array_equal(got["done"], rb["done"])
@@ -411,6 +418,49 @@ def test_whole_iteration_bf16_matches_oracle(g, name, n_envs, minibatch, horizon
     # policy part within 1e-3 absolute; the value part is O(|returns|^2) here, compare it relatively
     assert abs(o[0] - r_stats[0]) <= 1e-3
     assert abs(o[1] - r_stats[1]) <= 1e-3 * max(1.0, abs(r_stats[1]))
+    ses.close()
+
+
+@pytest.mark.parametrize("name,n_envs,horizon,prob_inv", [("C2", 100, 5, 4), ("C3", 257, 4, 0), ("C2", 4096, 16, 0),
+                                                          ("C2", 33, 3, 2)])
+def test_rollout_collect_equals_the_step_by_step_calls(g, name, n_envs, horizon, prob_inv):
+    """One-launch experience collection against agent_act / env_step / collect_experience called per step
+    (same kernels' arithmetic, same Philox counters): every array it leaves must be identical, over two
+    iterations in a row (state, episode counters and step offsets carry over), ragged last tile included."""
+    import dataclasses
+    cfg = syn.get_config(name)
+    if prob_inv:
+        cfg = dataclasses.replace(cfg, done_period=0, done_prob_inv=prob_inv)
+    shape, theta, env, state0, hp = oracle_pieces(cfg, n_envs=n_envs)
+    a = make_session(cfg, theta, env, state0, n_envs=n_envs, minibatch=n_envs, horizon=horizon, dtype="bf16",
+                     fused_rollout=True)
+    b = make_session(cfg, theta, env, state0, n_envs=n_envs, minibatch=n_envs, horizon=horizon, dtype="bf16",
+                     fused_rollout=False)
+    for it in range(2):
+        a.rollout(it)
+        b.rollout(it)
+        a.sync()
+        b.sync()
+        assert a.fused_rollout and not b.fused_rollout
+        ga, gb = a.buf.to_numpy(), b.buf.to_numpy()
+        for k in ("obs", "act", "logp", "val", "rew", "done"):
+            assert np.array_equal(ga[k], gb[k]), (it, k, np.abs(ga[k].astype(np.float64) - gb[k]).max())
+        assert np.array_equal(a.state().cpu().numpy(), b.state().cpu().numpy())
+        assert np.array_equal(a.last_value.cpu().numpy(), b.last_value.cpu().numpy())
+        assert np.array_equal(a.episode_step.cpu().numpy(), b.episode_step.cpu().numpy())
+    if prob_inv:
+        assert 0 < ga["done"].sum() < ga["done"].size
+    a.close()
+    b.close()
+
+
+def test_rollout_collect_refuses_fp32_models(g):
+    cfg = syn.get_config("C1")
+    shape, theta, env, state0, hp = oracle_pieces(cfg)
+    ses = make_session(cfg, theta, env, state0, dtype="f32")
+    with pytest.raises(g.GmiError) as ei:
+        g.rollout_collect(ses.gmi, ses.model, ses.env, ses.buffer, ses.state(), cfg.seed, 0, 0, ses.last_value)
+    assert ei.value.code == g.ERR_UNSUPPORTED and "BF16" in str(ei.value)
     ses.close()
 
 
