@@ -202,8 +202,8 @@ int collect_experience(gmi_t gmi, gmi_buffer_t buf, int32_t t, const float* obs,
  * launch: each workgroup keeps its envs' state on chip for all T steps.
  *  obs dev [N,O]: in = obs_0, out = obs_T (updated in place); last_value dev [N] out;
  *  seed / env_offset: the agent's (as in agent_act); the simulator uses its binding's own.
- *  The env's episode_step array advances by T steps.  BF16 models only, whose weight shadow is at most
- *  2 MiB and whose 32-env tile fits the on-chip memory: otherwise GMI_ERR_UNSUPPORTED and nothing has run
+ *  The env's episode_step array advances by T steps.  BF16 models only, whose (padded) bf16 weights total
+ *  at most 1 MiB and whose 32-env tile fits the on-chip memory: otherwise GMI_ERR_UNSUPPORTED and nothing has run
  *  (use the per-step calls, which are the faster path for larger models). */
 int rollout_collect(gmi_t gmi, gmi_model_t model, gmi_env_t env, gmi_buffer_t buf, float* obs,
                     uint64_t seed, uint32_t step0, uint32_t env_offset, float* last_value);

@@ -23,9 +23,11 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 __device__ __forceinline__ float bf16_to_f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
 struct FusedNet {
-  const uint16_t* w[GMI_MAX_HIDDEN + 1];     // bf16 [out_pad, in_pad]
+  const uint16_t* w[GMI_MAX_HIDDEN + 1];     // bf16, fragment-major copy of W [out_pad, in_pad]
   const float* bias[GMI_MAX_HIDDEN + 1];     // fp32 [out_pad]
   int in_pad[GMI_MAX_HIDDEN + 1], out_pad[GMI_MAX_HIDDEN + 1];
+  int bias_off[GMI_MAX_HIDDEN + 1];          // offset (floats) of the layer's bias inside a net's LDS bias block
+  int bias_total;                            // floats of that block
   int n_layers;
   int out_store;                             // logical outputs of the head
 };
@@ -34,33 +36,49 @@ enum { kFEpiElu = 0, kFEpiHead = 1, kFEpiEluGrad = 2 };
 
 // One layer for the workgroup's tile: s_out[r, f] = epi(sum_k s_in[r, k] W[f, k] + bias[f]).
 // Feature tiles of 32 are dealt to the 4 waves; a wave walks its (tile, 64-wide k chunk) pairs in one
-// flat loop with the weight fragments of the next pair already in flight (two register buffers), so the
-// L2 latency of the weight stream is covered across tile boundaries too.
-template <int RT, int EPI>
-__device__ __forceinline__ void fused_layer(const uint16_t* __restrict__ W, const float* __restrict__ bias,
+// flat loop through a ring of 4 register buffers, so the weight fragments of the next three pairs are in
+// flight while one is multiplied: an L2 round trip (~1 us measured here) costs far more than a chunk's
+// products, and with only one pair ahead every chunk waited for it.  The bias comes from LDS (s_bias).
+// FRAG: W is the fragment-major copy (wfrag_index) instead of row-major [out_pad, in_pad].
+template <int RT, int EPI, bool FRAG = true>
+__device__ __forceinline__ void fused_layer(const uint16_t* __restrict__ W, const float* s_bias,
                                             int in_pad, int out_pad, const uint16_t* s_in, int stride_in,
                                             uint16_t* s_out, int stride_out, float* s_head, int head_stride,
-                                            int out_store, const uint16_t* s_h = nullptr, int stride_hh = 0) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+                                            int out_store, const uint16_t* s_h = nullptr, int stride_hh = 0,
+                                            int wave_id = -1) {
+  // wave_id: this wave's index among the 4 that share the layer (default: a 256-thread workgroup's own);
+  // made wave-uniform for the compiler: tile loops and operand addresses then run on the scalar unit
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = wave_id >= 0 ? wave_id : __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n_ft = out_pad >> 5;
   const int n_my = (n_ft - wave + 3) >> 2;                 // tiles wave, wave+4, ...
   const int nchunk = (in_pad + 63) >> 6;
   const int nq = n_my > 0 ? n_my * nchunk : 0;
   const int khalf = (lane >> 5) * 8;
   floatx16 acc[RT];
-  bf16x8 A0[4], A1[4];
+  bf16x8 A0[4], A1[4], A2[4], A3[4];
 
   auto load_chunk = [&](bf16x8* A, int q) {
+    if (q >= nq) return;
     const int tile = q / nchunk, ch = q - tile * nchunk;
-    const int frow = (wave + 4 * tile) * 32 + (lane & 31);
-    const uint16_t* p = W + (int64_t)frow * in_pad;
+    if (FRAG) {
+      // k steps past the ragged end repeat the last one (never multiplied)
+      const int nks = in_pad >> 4;
+      const uint16_t* p = W + ((int64_t)(wave + 4 * tile) * nks) * 512 + lane * 8;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const int k = min(ch * 64 + s * 16 + khalf, in_pad - 8);
-      A[s] = *reinterpret_cast<const bf16x8*>(p + k);
+      for (int s = 0; s < 4; ++s) A[s] = *reinterpret_cast<const bf16x8*>(p + (int64_t)min(ch * 4 + s, nks - 1) * 512);
+    } else {
+      const int frow = (wave + 4 * tile) * 32 + (lane & 31);
+      const uint16_t* p = W + (int64_t)frow * in_pad;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const int k = min(ch * 64 + s * 16 + khalf, in_pad - 8);
+        A[s] = *reinterpret_cast<const bf16x8*>(p + k);
+      }
     }
   };
   auto compute_chunk = [&](const bf16x8* A, int q) {
+    if (q >= nq) return;
     const int tile = q / nchunk, ch = q - tile * nchunk;
     if (ch == 0) {
 #pragma unroll
@@ -68,16 +86,29 @@ __device__ __forceinline__ void fused_layer(const uint16_t* __restrict__ W, cons
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
     }
+    // widths are multiples of 32: a chunk holds 4 k-steps of 16, or 2 at the ragged end.  All activation
+    // fragments of the chunk are read from LDS before the first product, so the reads overlap each other.
+    const uint16_t* xrow = s_in + (lane & 31) * stride_in + ch * 64 + khalf;
+    if (ch * 64 + 64 <= in_pad) {
+      bf16x8 b[RT][4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const int k0 = ch * 64 + s * 16;
-      if (k0 < in_pad) {
+      for (int j = 0; j < RT; ++j)
 #pragma unroll
-        for (int j = 0; j < RT; ++j) {
-          const bf16x8 b = *reinterpret_cast<const bf16x8*>(&s_in[(j * 32 + (lane & 31)) * stride_in + k0 + khalf]);
-          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[s], b, acc[j], 0, 0, 0);
-        }
-      }
+        for (int s = 0; s < 4; ++s) b[j][s] = *reinterpret_cast<const bf16x8*>(xrow + j * 32 * stride_in + s * 16);
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int j = 0; j < RT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[s], b[j][s], acc[j], 0, 0, 0);
+    } else {
+      bf16x8 b[RT][2];
+#pragma unroll
+      for (int j = 0; j < RT; ++j)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) b[j][s] = *reinterpret_cast<const bf16x8*>(xrow + j * 32 * stride_in + s * 16);
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int j = 0; j < RT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[s], b[j][s], acc[j], 0, 0, 0);
     }
     if (ch == nchunk - 1) {
       const int fb = (wave + 4 * tile) * 32;
@@ -85,7 +116,7 @@ __device__ __forceinline__ void fused_layer(const uint16_t* __restrict__ W, cons
       for (int g = 0; g < 4; ++g) {
         const int f = fb + g * 8 + (lane >> 5) * 4;
         float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (EPI != kFEpiEluGrad) bv = *reinterpret_cast<const float4*>(bias + f);
+        if (EPI != kFEpiEluGrad) bv = *reinterpret_cast<const float4*>(s_bias + f);
 #pragma unroll
         for (int j = 0; j < RT; ++j) {
           const int r = j * 32 + (lane & 31);
@@ -114,36 +145,47 @@ __device__ __forceinline__ void fused_layer(const uint16_t* __restrict__ W, cons
     }
   };
 
-  if (nq > 0) {
-    load_chunk(A0, 0);
-    for (int q = 0; q < nq; q += 2) {
-      load_chunk(A1, min(q + 1, nq - 1));
-      compute_chunk(A0, q);
-      load_chunk(A0, min(q + 2, nq - 1));
-      if (q + 1 < nq) compute_chunk(A1, q + 1);
-    }
+  load_chunk(A0, 0);
+  load_chunk(A1, 1);
+  load_chunk(A2, 2);
+  for (int q = 0; q < nq; q += 4) {
+    load_chunk(A3, q + 3);
+    compute_chunk(A0, q);
+    load_chunk(A0, q + 4);
+    compute_chunk(A1, q + 1);
+    load_chunk(A1, q + 5);
+    compute_chunk(A2, q + 2);
+    load_chunk(A2, q + 6);
+    compute_chunk(A3, q + 3);
   }
+}
+
+// Copies the biases of all layers of a net into LDS (dst[bias_off[l] + f]); the caller synchronises.
+__device__ __forceinline__ void stage_biases(const FusedNet& N, float* dst, int tid0, int nthreads) {
+  for (int l = 0; l < N.n_layers; ++l)
+    for (int f = tid0; f < N.out_pad[l]; f += nthreads) dst[N.bias_off[l] + f] = N.bias[l][f];
 }
 
 // Runs all layers of one net on the tile whose input sits in s_x0; hidden activations ping-pong between
 // s_a and s_b; the head's fp32 outputs go to s_head[r * head_stride + j].
 template <int RT>
-__device__ __forceinline__ void fused_net_forward(const FusedNet& N, const uint16_t* s_x0, int stride_x0,
-                                                  uint16_t* s_a, uint16_t* s_b, int stride_h, float* s_head,
-                                                  int head_stride) {
+__device__ __forceinline__ void fused_net_forward(const FusedNet& N, const float* s_bias, const uint16_t* s_x0,
+                                                  int stride_x0, uint16_t* s_a, uint16_t* s_b, int stride_h,
+                                                  float* s_head, int head_stride) {
   const uint16_t* in = s_x0;
   int stride_in = stride_x0;
   uint16_t* out = s_a;
   for (int l = 0; l < N.n_layers - 1; ++l) {
-    fused_layer<RT, kFEpiElu>(N.w[l], N.bias[l], N.in_pad[l], N.out_pad[l], in, stride_in, out, stride_h, nullptr, 0, 0);
+    fused_layer<RT, kFEpiElu>(N.w[l], s_bias + N.bias_off[l], N.in_pad[l], N.out_pad[l], in, stride_in, out, stride_h,
+                              nullptr, 0, 0);
     __syncthreads();
     in = out;
     stride_in = stride_h;
     out = (out == s_a) ? s_b : s_a;
   }
   const int l = N.n_layers - 1;
-  fused_layer<RT, kFEpiHead>(N.w[l], N.bias[l], N.in_pad[l], N.out_pad[l], in, stride_in, nullptr, 0, s_head,
-                             head_stride, N.out_store);
+  fused_layer<RT, kFEpiHead>(N.w[l], s_bias + N.bias_off[l], N.in_pad[l], N.out_pad[l], in, stride_in, nullptr, 0,
+                             s_head, head_stride, N.out_store);
   __syncthreads();
 }
 
@@ -168,9 +210,12 @@ __global__ __launch_bounds__(256) void agent_fused_kernel(AgentArgs a) {
   float* s_mu = reinterpret_cast<float*>(s_b + R * stride_h);       // [R][act_dim]
   float* s_val = s_mu + R * a.act_dim;                              // [R]
   float* s_lp = s_val + R;                                          // [R][nb] log-prob partials
+  float* s_bias = s_lp + R * ((a.act_dim + 3) >> 2);                // biases of the policy net, then the value net
   const int tid = threadIdx.x;
   const int r0 = blockIdx.x * R;
 
+  if (a.do_policy) stage_biases(a.net[0], s_bias, tid, 256);
+  stage_biases(a.net[1], s_bias + a.net[0].bias_total, tid, 256);
   // observations -> bf16 tile (zero padded columns, zero rows past the end)
   for (int idx = tid; idx < R * a.obs_pad; idx += 256) {
     const int r = idx / a.obs_pad, k = idx - r * a.obs_pad;
@@ -179,8 +224,8 @@ __global__ __launch_bounds__(256) void agent_fused_kernel(AgentArgs a) {
     s_x0[r * stride_x0 + k] = (uint16_t)(pack_bf16(v, 0.f) & 0xFFFFu);
   }
   __syncthreads();
-  if (a.do_policy) fused_net_forward<RT>(a.net[0], s_x0, stride_x0, s_a, s_b, stride_h, s_mu, a.act_dim);
-  fused_net_forward<RT>(a.net[1], s_x0, stride_x0, s_a, s_b, stride_h, s_val, 1);
+  if (a.do_policy) fused_net_forward<RT>(a.net[0], s_bias, s_x0, stride_x0, s_a, s_b, stride_h, s_mu, a.act_dim);
+  fused_net_forward<RT>(a.net[1], s_bias + a.net[0].bias_total, s_x0, stride_x0, s_a, s_b, stride_h, s_val, 1);
 
   for (int r = tid; r < R; r += 256)
     if (r0 + r < a.n) a.value[r0 + r] = s_val[r];
@@ -233,65 +278,168 @@ struct RolloutArgs {
   const float* m_t;                 // [(O + A), o4] transposed env matrices
   uint32_t* episode_step;           // [n]
   int n, obs_dim, obs_pad, act_dim, max_h, o4, T, ld_envs;
+  int rows_per_wg;                  // envs owned by a workgroup: the tile height, or half of it
   float noise_std, reward_scale;
   uint32_t done_period, done_threshold;
   uint32_t ak0, ak1, a_env_offset;  // agent's Philox key and env offset
   uint32_t ek0, ek1, e_env_offset;  // simulator's
   uint32_t step0;
+  int mt_lds;                       // m_t: 2 = LDS copy kept for the whole launch, 1 = LDS copy made at every
+                                    // step in the (then idle) hidden-activation space, 0 = read from global
   float* b_obs; float* b_act; float* b_logp; float* b_val; float* b_rew; uint8_t* b_done;
   float* last_value;
 };
 
+// Simulator step for the tile: items (group of EPT envs, block of 4 state elements).  mt points at the
+// transposed matrices (LDS copy or global), row stride nbo float4.
+template <int EPT>
+__device__ __forceinline__ void sim_items(const RolloutArgs& a, int R, int r0, uint32_t step, const float* s_in,
+                                          const float4* mt, float* s_part, float* s_next, const int* s_done) {
+  const int O = a.obs_dim, A = a.act_dim, OA = O + A, o4 = a.o4, nbo = o4 >> 2;
+  for (int item = threadIdx.x; item < (R / EPT) * nbo; item += blockDim.x) {
+    const int g = item / nbo, b = item - g * nbo;
+    const float* xin = s_in + (g * EPT) * OA;
+    const float4* mrow = mt + b;
+    float acc[EPT][4];
+#pragma unroll
+    for (int i = 0; i < EPT; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+#pragma unroll 8
+    for (int k = 0; k < OA; ++k) {
+      const float4 m = mrow[k * nbo];
+#pragma unroll
+      for (int i = 0; i < EPT; ++i) {
+        const float x = xin[i * OA + k];
+        acc[i][0] = fmaf(x, m.x, acc[i][0]);
+        acc[i][1] = fmaf(x, m.y, acc[i][1]);
+        acc[i][2] = fmaf(x, m.z, acc[i][2]);
+        acc[i][3] = fmaf(x, m.w, acc[i][3]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) {
+      const int r = g * EPT + i;
+      float ps = 0.f, pa = 0.f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int o = 4 * b + j;
+        if (o < O) { const float x = xin[i * OA + o]; ps = fmaf(x, x, ps); }
+      }
+      for (int q = b; q < A; q += nbo) { const float x = xin[i * OA + O + q]; pa = fmaf(x, x, pa); }
+      s_part[r * nbo + b] = ps + 0.01f * pa;
+      const int e = r0 + r;
+      float z[4] = {0.f, 0.f, 0.f, 0.f};
+      float outv[4];
+      if (s_done[r]) {
+        if (e < a.n) gmi::normal_block(a.e_env_offset + (uint32_t)e, step, gmi::kStreamReset, (uint32_t)b, a.ek0, a.ek1, z);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) outv[j] = z[j];
+      } else {
+        if (e < a.n) gmi::normal_block(a.e_env_offset + (uint32_t)e, step, gmi::kStreamEnv, (uint32_t)b, a.ek0, a.ek1, z);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) outv[j] = fmaf(a.noise_std, z[j], acc[i][j]);
+      }
+      *reinterpret_cast<float4*>(&s_next[r * o4 + 4 * b]) = make_float4(outv[0], outv[1], outv[2], outv[3]);
+    }
+  }
+}
+
+// 512 threads: waves 0-3 run the policy net and waves 4-7 the value net at the same time (the two nets
+// have the same hidden widths, so their layers finish together and share the barriers); every other phase
+// uses all 8 waves.
 template <int RT>
-__global__ __launch_bounds__(256) void rollout_fused_kernel(RolloutArgs a) {
+__global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   constexpr int R = RT * 32;
+  constexpr int NT = 512;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   const int O = a.obs_dim, A = a.act_dim, OA = O + A, o4 = a.o4, nbo = o4 >> 2, nba = (A + 3) >> 2;
   const int stride_x0 = a.obs_pad + 8, stride_h = a.max_h + 8;
-  // hidden activations (bf16, ping-pong) share their space with the simulator's next-state tile
-  const size_t hid_bytes = 2 * (size_t)R * stride_h * 2, next_bytes = (size_t)R * o4 * 4;
+  // hidden activations (bf16, ping-pong, one pair per net) share their space with the next-state tile
+  const size_t hid_bytes = 4 * (size_t)R * stride_h * 2, next_bytes = (size_t)R * o4 * 4;
   const size_t region = ((hid_bytes > next_bytes ? hid_bytes : next_bytes) + 15) & ~(size_t)15;
   float* s_in = reinterpret_cast<float*>(smem_raw);                                  // [R][O + A] state | action
   uint16_t* s_x0 = reinterpret_cast<uint16_t*>(s_in + ((R * OA + 3) & ~3));          // [R][obs_pad + 8]
   unsigned char* s_reg = reinterpret_cast<unsigned char*>(s_x0 + R * stride_x0);
-  uint16_t* s_a = reinterpret_cast<uint16_t*>(s_reg);
-  uint16_t* s_b = s_a + R * stride_h;
+  uint16_t* s_hid = reinterpret_cast<uint16_t*>(s_reg);                              // [2 nets][2][R][stride_h]
   float* s_next = reinterpret_cast<float*>(s_reg);                                   // [R][o4]
   float* s_mu = reinterpret_cast<float*>(s_reg + region);                            // [R][A]
   float* s_val = s_mu + R * A;                                                       // [R]
   float* s_lp = s_val + R;                                                           // [R][nba]
   float* s_part = s_lp + R * nba;                                                    // [R][nbo]
   int* s_done = reinterpret_cast<int*>(s_part + R * nbo);                            // [R]
+  float* s_bias = reinterpret_cast<float*>(s_done + ((R + 3) & ~3));                 // policy biases, value biases
+  float* s_mt = s_bias + ((a.net[0].bias_total + a.net[1].bias_total + 3) & ~3);     // [O + A][o4] when mt_lds == 2
   const int tid = threadIdx.x;
-  const int r0 = blockIdx.x * R;
+  // wave-uniform values, so that the per-net kernel arguments are fetched by scalar loads
+  const int half = __builtin_amdgcn_readfirstlane(tid >> 8), wave4 = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);
+  // Rv <= R envs are owned by this workgroup (a half-filled tile doubles the workgroups of a small batch);
+  // rows Rv..R-1 of the tile go through the matrix products but are never read or stored
+  const int Rv = a.rows_per_wg;
+  const int r0 = blockIdx.x * Rv;
+  for (int idx = tid; idx < (R - Rv) * stride_x0; idx += NT) s_x0[Rv * stride_x0 + idx] = 0;
 
-  for (int idx = tid; idx < R * O; idx += 256) {
+  for (int idx = tid; idx < Rv * O; idx += NT) {
     const int r = idx / O, k = idx - r * O;
     s_in[r * OA + k] = (r0 + r < a.n) ? a.obs_state[(int64_t)(r0 + r) * O + k] : 0.f;
   }
+  stage_biases(a.net[0], s_bias, tid, NT);
+  stage_biases(a.net[1], s_bias + a.net[0].bias_total, tid, NT);
+  if (a.mt_lds == 2)
+    for (int idx = tid; idx < OA * nbo; idx += NT)
+      reinterpret_cast<float4*>(s_mt)[idx] = reinterpret_cast<const float4*>(a.m_t)[idx];
+  float4* s_stage = reinterpret_cast<float4*>(s_reg + ((next_bytes + 15) & ~(size_t)15));
+  const float4* mt = a.mt_lds == 2 ? reinterpret_cast<const float4*>(s_mt)
+                   : a.mt_lds == 1 ? s_stage : reinterpret_cast<const float4*>(a.m_t);
   uint32_t ep = 0;                                   // thread r < R carries env r's episode counter
-  if (tid < R && r0 + tid < a.n) ep = a.episode_step[r0 + tid];
+  if (tid < Rv && r0 + tid < a.n) ep = a.episode_step[r0 + tid];
   __syncthreads();
 
+  const FusedNet& N = a.net[half];
+  uint16_t* s_a = s_hid + (size_t)half * 2 * R * stride_h;
+  uint16_t* s_b = s_a + R * stride_h;
+  float* s_head = half ? s_val : s_mu;
+  const int head_stride = half ? 1 : A;
+  const float* s_nb = s_bias + (half ? a.net[0].bias_total : 0);
+
   for (int t = 0; t <= a.T; ++t) {
-    for (int idx = tid; idx < R * a.obs_pad; idx += 256) {
+    // both nets, layer by layer; after the last step only the value net (bootstrap value)
+    const bool run = half == 1 || t < a.T;
+    for (int idx = tid; idx < Rv * a.obs_pad; idx += NT) {
       const int r = idx / a.obs_pad, k = idx - r * a.obs_pad;
       const float v = k < O ? s_in[r * OA + k] : 0.f;
       s_x0[r * stride_x0 + k] = (uint16_t)(pack_bf16(v, 0.f) & 0xFFFFu);
     }
     __syncthreads();
+    {
+      const uint16_t* in = s_x0;
+      int stride_in = stride_x0;
+      uint16_t* out = s_a;
+      for (int l = 0; l < N.n_layers - 1; ++l) {
+        if (run) {
+          fused_layer<RT, kFEpiElu>(N.w[l], s_nb + N.bias_off[l], N.in_pad[l], N.out_pad[l], in, stride_in, out, stride_h,
+                                    nullptr, 0, 0, nullptr, 0, wave4);
+        }
+        __syncthreads();
+        in = out;
+        stride_in = stride_h;
+        out = (out == s_a) ? s_b : s_a;
+      }
+      const int l = N.n_layers - 1;
+      if (run)
+        fused_layer<RT, kFEpiHead>(N.w[l], s_nb + N.bias_off[l], N.in_pad[l], N.out_pad[l], in, stride_in, nullptr, 0,
+                                   s_head, head_stride, N.out_store, nullptr, 0, wave4);
+      __syncthreads();
+    }
     if (t == a.T) {
-      fused_net_forward<RT>(a.net[1], s_x0, stride_x0, s_a, s_b, stride_h, s_val, 1);
-      if (tid < R && r0 + tid < a.n) a.last_value[r0 + tid] = s_val[tid];
+      if (tid < Rv && r0 + tid < a.n) a.last_value[r0 + tid] = s_val[tid];
       break;
     }
-    fused_net_forward<RT>(a.net[0], s_x0, stride_x0, s_a, s_b, stride_h, s_mu, A);
-    fused_net_forward<RT>(a.net[1], s_x0, stride_x0, s_a, s_b, stride_h, s_val, 1);
 
     const uint32_t step = a.step0 + (uint32_t)t;
     const int64_t slot0 = (int64_t)t * a.ld_envs + r0;
     // action = mu + exp(log_std) * eps, log-prob partials per block of 4 action elements
-    for (int item = tid; item < R * nba; item += 256) {
+    for (int item = tid; item < Rv * nba; item += NT) {
       const int r = item / nba, b = item - r * nba;
       const int e = r0 + r;
       float lp = 0.f;
@@ -315,11 +463,11 @@ __global__ __launch_bounds__(256) void rollout_fused_kernel(RolloutArgs a) {
       }
       s_lp[r * nba + b] = lp;
     }
-    for (int idx = tid; idx < R * O; idx += 256) {
+    for (int idx = tid; idx < Rv * O; idx += NT) {
       const int r = idx / O, k = idx - r * O;
       if (r0 + r < a.n) a.b_obs[(slot0 + r) * O + k] = s_in[r * OA + k];
     }
-    if (tid < R) {
+    if (tid < Rv) {
       const int e = r0 + tid;
       int d = 0;
       if (e < a.n) {
@@ -336,77 +484,37 @@ __global__ __launch_bounds__(256) void rollout_fused_kernel(RolloutArgs a) {
       s_done[tid] = d;
     }
     __syncthreads();
-    if (tid < R && r0 + tid < a.n) {
+    if (tid < Rv && r0 + tid < a.n) {
       float lp = 0.f;
       for (int b = 0; b < nba; ++b) lp += s_lp[tid * nba + b];
       a.b_logp[slot0 + tid] = lp;
     }
-    // simulator: next = A s + B act + noise_std * eps (or a fresh N(0,1) state after a done); 4 envs per item
-    for (int item = tid; item < (R / 4) * nbo; item += 256) {
-      const int g = item / nbo, b = item - g * nbo;
-      const float* xin = s_in + (g * 4) * OA;
-      const float4* mrow = reinterpret_cast<const float4*>(a.m_t) + b;
-      float acc[4][4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
-#pragma unroll 4
-      for (int k = 0; k < OA; ++k) {
-        const float4 m = mrow[(int64_t)k * nbo];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float x = xin[i * OA + k];
-          acc[i][0] = fmaf(x, m.x, acc[i][0]);
-          acc[i][1] = fmaf(x, m.y, acc[i][1]);
-          acc[i][2] = fmaf(x, m.z, acc[i][2]);
-          acc[i][3] = fmaf(x, m.w, acc[i][3]);
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int r = g * 4 + i;
-        float ps = 0.f, pa = 0.f;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int o = 4 * b + j;
-          if (o < O) { const float x = xin[i * OA + o]; ps = fmaf(x, x, ps); }
-        }
-        for (int q = b; q < A; q += nbo) { const float x = xin[i * OA + O + q]; pa = fmaf(x, x, pa); }
-        s_part[r * nbo + b] = ps + 0.01f * pa;
-        const int e = r0 + r;
-        float z[4] = {0.f, 0.f, 0.f, 0.f};
-        float outv[4];
-        if (s_done[r]) {
-          if (e < a.n) gmi::normal_block(a.e_env_offset + (uint32_t)e, step, gmi::kStreamReset, (uint32_t)b, a.ek0, a.ek1, z);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) outv[j] = z[j];
-        } else {
-          if (e < a.n) gmi::normal_block(a.e_env_offset + (uint32_t)e, step, gmi::kStreamEnv, (uint32_t)b, a.ek0, a.ek1, z);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) outv[j] = fmaf(a.noise_std, z[j], acc[i][j]);
-        }
-        *reinterpret_cast<float4*>(&s_next[r * o4 + 4 * b]) = make_float4(outv[0], outv[1], outv[2], outv[3]);
-      }
+    // simulator: next = A s + B act + noise_std * eps (or a fresh N(0,1) state after a done); as many envs
+    // per item as still leaves an item for every thread
+    if (a.mt_lds == 1) {
+      for (int idx = tid; idx < OA * nbo; idx += NT) s_stage[idx] = reinterpret_cast<const float4*>(a.m_t)[idx];
+      __syncthreads();
     }
+    if ((Rv / 4) * nbo >= 192) sim_items<4>(a, Rv, r0, step, s_in, mt, s_part, s_next, s_done);
+    else sim_items<1>(a, Rv, r0, step, s_in, mt, s_part, s_next, s_done);
     __syncthreads();
-    if (tid < R && r0 + tid < a.n) {
+    if (tid < Rv && r0 + tid < a.n) {
       float sum = 0.f;
       for (int j = 0; j < nbo; ++j) sum += s_part[tid * nbo + j];
       a.b_rew[slot0 + tid] = -a.reward_scale * sum;
     }
-    for (int idx = tid; idx < R * O; idx += 256) {
+    for (int idx = tid; idx < Rv * O; idx += NT) {
       const int r = idx / O, k = idx - r * O;
       s_in[r * OA + k] = (r0 + r < a.n) ? s_next[r * o4 + k] : 0.f;
     }
     __syncthreads();
   }
-  // t == T left the loop right after the bootstrap value; s_in still holds the final state
-  for (int idx = tid; idx < R * O; idx += 256) {
+  // the loop ends right after the bootstrap value; s_in still holds the final state
+  for (int idx = tid; idx < Rv * O; idx += NT) {
     const int r = idx / O, k = idx - r * O;
     if (r0 + r < a.n) a.obs_state[(int64_t)(r0 + r) * O + k] = s_in[r * OA + k];
   }
-  if (tid < R && r0 + tid < a.n) a.episode_step[r0 + tid] = ep;
+  if (tid < Rv && r0 + tid < a.n) a.episode_step[r0 + tid] = ep;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -475,10 +583,12 @@ __global__ __launch_bounds__(256) void train_fused_kernel(TrainArgs a) {
   float* s_head = reinterpret_cast<float*>(s_dzh + R * stride_dh);   // [R][A] (policy) or [R] (value)
   float* s_ex = s_head + R * A;                                      // [R][A + 3]: act, logp_old, adv, ret
   float* s_red = s_ex + R * (A + 3);                                 // [4][A + 4] per-wave partial sums
+  float* s_bias = s_red + 4 * (A + 4);                               // this net's biases
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r0 = blockIdx.x * R;
   const int EW = A + 3;
 
+  stage_biases(N.fwd, s_bias, tid, 256);
   // gather: shuffled rows of the buffer -> bf16 input tile (+ the per-sample scalars of the loss)
   for (int i = tid; i < R * a.obs_pad; i += 256) {
     const int r = i / a.obs_pad, k = i - r * a.obs_pad;
@@ -507,7 +617,7 @@ __global__ __launch_bounds__(256) void train_fused_kernel(TrainArgs a) {
   int stride_in = stride_x0;
   int cur = 0;
   for (int l = 0; l < L; ++l) {
-    fused_layer<RT, kFEpiElu>(N.fwd.w[l], N.fwd.bias[l], N.fwd.in_pad[l], N.fwd.out_pad[l], in, stride_in, s_buf[cur],
+    fused_layer<RT, kFEpiElu>(N.fwd.w[l], s_bias + N.fwd.bias_off[l], N.fwd.in_pad[l], N.fwd.out_pad[l], in, stride_in, s_buf[cur],
                               stride_h, nullptr, 0, 0);
     __syncthreads();
     tile_to_global<R>(s_buf[cur], stride_h, N.h[l + 1], N.fwd.out_pad[l], r0, a.rows);
@@ -516,7 +626,7 @@ __global__ __launch_bounds__(256) void train_fused_kernel(TrainArgs a) {
     cur ^= 1;
   }
   const int hl = cur ^ 1;                       // s_buf[hl] holds h[L] (if L >= 1)
-  fused_layer<RT, kFEpiHead>(N.fwd.w[L], N.fwd.bias[L], N.fwd.in_pad[L], N.fwd.out_pad[L], in, stride_in, nullptr, 0,
+  fused_layer<RT, kFEpiHead>(N.fwd.w[L], s_bias + N.fwd.bias_off[L], N.fwd.in_pad[L], N.fwd.out_pad[L], in, stride_in, nullptr, 0,
                              s_head, net == 0 ? A : 1, N.fwd.out_store);
   for (int i = tid; i < R * stride_dh; i += 256) s_dzh[i] = 0;
   for (int i = tid; i < 4 * (A + 4); i += 256) s_red[i] = 0.f;
@@ -591,7 +701,7 @@ __global__ __launch_bounds__(256) void train_fused_kernel(TrainArgs a) {
   int stride_d = stride_dh;
   int outb = 2;                                 // first result goes to the third buffer
   for (int l = L; l >= 1; --l) {
-    fused_layer<RT, kFEpiEluGrad>(N.wt[l], nullptr, N.fwd.out_pad[l], N.fwd.in_pad[l], d_in, stride_d, s_buf[outb], stride_h,
+    fused_layer<RT, kFEpiEluGrad, false>(N.wt[l], nullptr, N.fwd.out_pad[l], N.fwd.in_pad[l], d_in, stride_d, s_buf[outb], stride_h,
                                   nullptr, 0, 0, s_buf[hl], stride_h);
     __syncthreads();
     tile_to_global<R>(s_buf[outb], stride_h, N.dz[l - 1], N.fwd.in_pad[l], r0, a.rows);
@@ -616,13 +726,21 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restric
   if (threadIdx.x == 0) out[c] = sh[0] + sh[1] + sh[2] + sh[3];
 }
 
+// floats of one net's LDS bias block (the two nets have the same padded widths except for the head,
+// whose padded width is at least as large for the policy net)
+size_t bias_floats(const gmi_model* m, int net) {
+  size_t n = 0;
+  for (int l = 0; l < m->L.n_layers; ++l) n += m->L.net[net][l].out_pad;
+  return n;
+}
+
 size_t train_lds_bytes(const gmi_model* m, int R) {
   const ModelLayout& L = m->L;
   int max_h = 32;
   for (int l = 0; l < L.n_hidden; ++l) max_h = L.net[0][l].out_pad > max_h ? L.net[0][l].out_pad : max_h;
   const int A = L.act_dim;
   return (size_t)R * (gmi::pad32(L.obs_dim) + 8) * 2 + 3 * (size_t)R * (max_h + 8) * 2 + (size_t)R * 40 * 2 +
-         ((size_t)R * A + (size_t)R * (A + 3) + 4 * (A + 4)) * 4;
+         ((size_t)R * A + (size_t)R * (A + 3) + 4 * (A + 4) + bias_floats(m, 0)) * 4;
 }
 
 void fill_net(const gmi_model* m, int net, FusedNet* N) {
@@ -630,11 +748,13 @@ void fill_net(const gmi_model* m, int net, FusedNet* N) {
   N->n_layers = L.n_layers;
   for (int l = 0; l < L.n_layers; ++l) {
     const LayerInfo& li = L.net[net][l];
-    N->w[l] = reinterpret_cast<const uint16_t*>(m->shadow + li.sh_w);
+    N->w[l] = reinterpret_cast<const uint16_t*>(m->shadow + li.sh_wf);
     N->bias[l] = reinterpret_cast<const float*>(m->shadow + li.sh_b);
     N->in_pad[l] = li.in_pad;
     N->out_pad[l] = li.out_pad;
+    N->bias_off[l] = l ? N->bias_off[l - 1] + N->out_pad[l - 1] : 0;
   }
+  N->bias_total = N->bias_off[L.n_layers - 1] + N->out_pad[L.n_layers - 1];
   N->out_store = L.net[net][L.n_layers - 1].out;
 }
 
@@ -644,18 +764,30 @@ size_t agent_lds_bytes(const gmi_model* m, int R) {
   for (int l = 0; l < L.n_hidden; ++l) max_h = L.net[0][l].out_pad > max_h ? L.net[0][l].out_pad : max_h;
   const int nb = (L.act_dim + 3) / 4;
   return (size_t)R * (gmi::pad32(L.obs_dim) + 8) * 2 + 2 * (size_t)R * (max_h + 8) * 2 +
-         (size_t)R * (L.act_dim + 1 + nb) * 4;
+         ((size_t)R * (L.act_dim + 1 + nb) + bias_floats(m, 0) + bias_floats(m, 1)) * 4;
 }
 
-size_t rollout_lds_bytes(const gmi_model* m, int R) {
+// Bytes of the hidden-activation space left over beside the next-state tile while the simulator runs.
+size_t rollout_stage_room(const gmi_model* m, int R) {
+  const ModelLayout& L = m->L;
+  int max_h = 32;
+  for (int l = 0; l < L.n_hidden; ++l) max_h = L.net[0][l].out_pad > max_h ? L.net[0][l].out_pad : max_h;
+  const int o4 = (L.obs_dim + 3) & ~3;
+  const size_t hid = 4 * (size_t)R * (max_h + 8) * 2, nxt = ((size_t)R * o4 * 4 + 15) & ~(size_t)15;
+  return hid > nxt ? hid - nxt : 0;
+}
+
+size_t rollout_lds_bytes(const gmi_model* m, int R, bool mt_lds) {
   const ModelLayout& L = m->L;
   int max_h = 32;
   for (int l = 0; l < L.n_hidden; ++l) max_h = L.net[0][l].out_pad > max_h ? L.net[0][l].out_pad : max_h;
   const int O = L.obs_dim, A = L.act_dim, o4 = (O + 3) & ~3;
-  const size_t hid = 2 * (size_t)R * (max_h + 8) * 2, nxt = (size_t)R * o4 * 4;
+  const size_t hid = 4 * (size_t)R * (max_h + 8) * 2, nxt = (size_t)R * o4 * 4;
   const size_t region = ((hid > nxt ? hid : nxt) + 15) & ~(size_t)15;
   return (size_t)((R * (O + A) + 3) & ~3) * 4 + (size_t)R * (gmi::pad32(O) + 8) * 2 + region +
-         (size_t)R * (A + 1 + (A + 3) / 4 + o4 / 4 + 1) * 4;
+         (size_t)(R * (A + 1 + (A + 3) / 4 + o4 / 4) + ((R + 3) & ~3)) * 4 +
+         ((bias_floats(m, 0) + bias_floats(m, 1) + 3) & ~(size_t)3) * 4 +
+         (mt_lds ? (size_t)(O + A) * o4 * 4 : 0);
 }
 
 }  // namespace
@@ -668,10 +800,10 @@ namespace gmi {
 int launch_agent_fused(gmi_instance* g, gmi_model* m, const float* obs, int n, uint64_t seed, uint32_t step,
                        uint32_t env_offset, float* act, float* logp, float* value, float* mu_out, bool do_policy) {
   if (m->L.dtype != GMI_DTYPE_BF16) return GMI_ERR_UNSUPPORTED;
-  // every row tile streams all weights from L2 once: beyond ~1 MB of bf16 weights (both layouts are in
-  // the shadow, so 2 MB of shadow) the per-layer large-tile kernels are faster (measured on a
+  // every row tile streams all weights from L2 once: beyond ~1 MB of bf16 weights the per-layer
+  // large-tile kernels are faster (measured on a
   // [512,512,256,128] model: 180 us fused against ~140 us per-layer for 16384 rows)
-  if (m->L.shadow_bytes > (2 << 20)) return GMI_ERR_UNSUPPORTED;
+  if (m->L.weight_bytes > (1 << 20)) return GMI_ERR_UNSUPPORTED;
   constexpr size_t kLdsMax = 160 * 1024;
   int R = 64;
   if (agent_lds_bytes(m, R) > kLdsMax) R = 32;
@@ -719,7 +851,7 @@ int launch_agent_fused(gmi_instance* g, gmi_model* m, const float* obs, int n, u
 int launch_train_fused(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx,
                        int rows) {
   if (m->L.dtype != GMI_DTYPE_BF16) return GMI_ERR_UNSUPPORTED;
-  if (m->L.shadow_bytes > (2 << 20)) return GMI_ERR_UNSUPPORTED;
+  if (m->L.weight_bytes > (1 << 20)) return GMI_ERR_UNSUPPORTED;
   constexpr size_t kLdsMax = 160 * 1024;
   int R = 64;
   if (train_lds_bytes(m, R) > kLdsMax) R = 32;
@@ -797,16 +929,19 @@ extern "C" int rollout_collect(gmi_t g, gmi_model_t m, gmi_env_t env, gmi_buffer
   // as for the fused agent kernel: every tile streams all weights from L2 at every step, which loses to the
   // per-layer large-tile kernels beyond ~1 MB of bf16 weights (measured on a [512,512,256,128] model with
   // 16384 envs and 16 steps: 4.1 ms in one launch against 3.3 ms step by step)
-  if (L.shadow_bytes > (2 << 20))
+  if (L.weight_bytes > (1 << 20))
     GMI_FAIL(GMI_ERR_UNSUPPORTED, "rollout_collect: model too large for the one-launch kernel (%lld bytes of bf16 "
-             "weights, limit %d); use agent_act / env_step / collect_experience", (long long)L.shadow_bytes, 2 << 20);
+             "weights, limit %d); use agent_act / env_step / collect_experience", (long long)L.weight_bytes, 1 << 20);
   constexpr size_t kLdsMax = 160 * 1024;
   const int n = bd.n_envs;
   int R = 64;
-  if (rollout_lds_bytes(m, R) > kLdsMax || (n + 63) / 64 < g->cu_count) R = 32;
-  if (rollout_lds_bytes(m, R) > kLdsMax)
+  if (rollout_lds_bytes(m, R, false) > kLdsMax || (n + 63) / 64 < g->cu_count) R = 32;
+  if (rollout_lds_bytes(m, R, false) > kLdsMax)
     GMI_FAIL(GMI_ERR_UNSUPPORTED, "rollout_collect: a 32-env tile of this model needs %zu bytes of LDS (limit %zu); "
-             "use agent_act / env_step / collect_experience", rollout_lds_bytes(m, R), kLdsMax);
+             "use agent_act / env_step / collect_experience", rollout_lds_bytes(m, R, false), kLdsMax);
+  const size_t mt_bytes = (size_t)(L.obs_dim + L.act_dim) * ((L.obs_dim + 3) & ~3) * 4;
+  const bool mt_lds = rollout_lds_bytes(m, R, true) <= kLdsMax;
+  const int mt_mode = mt_lds ? 2 : (rollout_stage_room(m, R) >= mt_bytes ? 1 : 0);
   RolloutArgs a;
   fill_net(m, 0, &a.net[0]);
   fill_net(m, 1, &a.net[1]);
@@ -824,9 +959,13 @@ extern "C" int rollout_collect(gmi_t g, gmi_model_t m, gmi_env_t env, gmi_buffer
   a.ak0 = (uint32_t)seed; a.ak1 = (uint32_t)(seed >> 32); a.a_env_offset = env_offset;
   a.ek0 = (uint32_t)ed.seed; a.ek1 = (uint32_t)(ed.seed >> 32); a.e_env_offset = ed.env_offset;
   a.step0 = step0;
+  a.mt_lds = mt_mode;
   a.b_obs = bd.obs; a.b_act = bd.act; a.b_logp = bd.logp; a.b_val = bd.val; a.b_rew = bd.rew; a.b_done = bd.done;
   a.last_value = last_value;
-  const size_t lds = rollout_lds_bytes(m, R);
+  const size_t lds = rollout_lds_bytes(m, R, mt_lds);
+  // fewer 32-env tiles than compute units: 16 envs per workgroup use twice as many of them
+  const int rows_per_wg = (R == 32 && (n + 31) / 32 < g->cu_count && n > 16) ? 16 : R;
+  a.rows_per_wg = rows_per_wg;
   gmi::ProfScope ps(g, gmi::kClsFusedRollout);
   if (R == 64) {
     static bool attr64 = false;
@@ -834,14 +973,14 @@ extern "C" int rollout_collect(gmi_t g, gmi_model_t m, gmi_env_t env, gmi_buffer
       GMI_HIP(hipFuncSetAttribute((const void*)rollout_fused_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
       attr64 = true;
     }
-    rollout_fused_kernel<2><<<(n + 63) / 64, 256, lds, g->stream>>>(a);
+    rollout_fused_kernel<2><<<(n + 63) / 64, 512, lds, g->stream>>>(a);
   } else {
     static bool attr32 = false;
     if (!attr32) {
       GMI_HIP(hipFuncSetAttribute((const void*)rollout_fused_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
       attr32 = true;
     }
-    rollout_fused_kernel<1><<<(n + 31) / 32, 256, lds, g->stream>>>(a);
+    rollout_fused_kernel<1><<<(n + rows_per_wg - 1) / rows_per_wg, 512, lds, g->stream>>>(a);
   }
   GMI_LAUNCH_CHECK();
   return GMI_OK;

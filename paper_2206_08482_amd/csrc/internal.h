@@ -89,6 +89,7 @@ struct LayerInfo {
   int in, out;           // logical sizes
   int in_pad, out_pad;   // padded to multiples of 32
   int64_t w_off, b_off;  // offsets into the flat fp32 parameter vector
+  int64_t sh_wf;              // bf16 W in matrix-core fragment order (see wfrag_index)
   int64_t sh_w, sh_wt, sh_b;  // byte offsets into the shadow (bf16 W [out_pad,in_pad], bf16 W^T
                               // [in_pad,out_pad], fp32 bias [out_pad])
   bool head;
@@ -102,6 +103,7 @@ struct ModelLayout {
   int64_t sh_logstd;                          // byte offset into shadow (fp32 [act_dim])
   int64_t n_params;
   int64_t shadow_bytes;
+  int64_t weight_bytes;                       // bf16 bytes of one copy of all weights (padded), both nets
   int max_width_pad;                          // widest padded activation
 };
 
@@ -245,11 +247,21 @@ static inline int wgrad_split_limit(int n_tiles) {
 constexpr int kLossBlocksMax = 2048; // rows of per-workgroup loss statistics (one more row holds their sum)
 constexpr int kStatStride = 8;       // per-workgroup statistics slots before the log_std partials
 
+// Fragment-major weight copy for the row-tile fused kernels: the weights of (32-feature tile ft, 16-wide
+// k step ks) form one 1 KiB block in which lane L of a wave owns the 8 consecutive k values of feature
+// ft*32 + L%32 starting at ks*16 + (L/32)*8, i.e. exactly its operand of the 32x32x16 bf16 matrix
+// instruction.  A wave then fetches an operand with one fully coalesced 16-byte-per-lane load instead of
+// touching 32 weight rows (measured: the row-major fetch kept the texture addresser busy ~4x longer).
+__host__ __device__ static inline int64_t wfrag_index(int o, int i, int in_pad) {
+  const int ft = o >> 5, ks = i >> 4, lane = (o & 31) + 32 * ((i & 15) >> 3);
+  return (((int64_t)ft * (in_pad >> 4) + ks) * 64 + lane) * 8 + (i & 7);
+}
+
 // Where each parameter lives in the flat vector and in the bf16 shadow (kernel argument).
 struct ShadowLayer {
   int64_t w_off, b_off;
   int in, out, in_pad, out_pad;
-  int64_t sh_w, sh_wt, sh_b;
+  int64_t sh_w, sh_wt, sh_b, sh_wf;
 };
 struct ShadowTable {
   int n;
@@ -265,7 +277,7 @@ static inline ShadowTable make_shadow_table(const ModelLayout& L) {
     for (const LayerInfo& li : L.net[net]) {
       ShadowLayer& s = t.l[t.n++];
       s.w_off = li.w_off; s.b_off = li.b_off; s.in = li.in; s.out = li.out;
-      s.in_pad = li.in_pad; s.out_pad = li.out_pad; s.sh_w = li.sh_w; s.sh_wt = li.sh_wt; s.sh_b = li.sh_b;
+      s.in_pad = li.in_pad; s.out_pad = li.out_pad; s.sh_w = li.sh_w; s.sh_wt = li.sh_wt; s.sh_b = li.sh_b; s.sh_wf = li.sh_wf;
     }
   t.logstd_off = L.logstd_off;
   t.sh_logstd = L.sh_logstd;

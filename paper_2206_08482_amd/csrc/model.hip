@@ -18,7 +18,7 @@ int build_layout(const gmi_model_desc* d, ModelLayout* L) {
   L->n_hidden = d->n_hidden;
   L->n_layers = d->n_hidden + 1;
   L->dtype = d->dtype;
-  int64_t off = 0, sh = 0;
+  int64_t off = 0, sh = 0, wbytes = 0;
   int maxw = gmi::pad32(d->obs_dim);
   for (int net = 0; net < 2; ++net) {
     L->net[net].clear();
@@ -34,6 +34,8 @@ int build_layout(const gmi_model_desc* d, ModelLayout* L) {
       li.b_off = off; off += li.out;
       li.sh_w = sh;  sh += gmi::align_up((int64_t)li.out_pad * li.in_pad * 2, 256);
       li.sh_wt = sh; sh += gmi::align_up((int64_t)li.out_pad * li.in_pad * 2, 256);
+      li.sh_wf = sh; sh += gmi::align_up((int64_t)li.out_pad * li.in_pad * 2, 256);
+      wbytes += (int64_t)li.out_pad * li.in_pad * 2;
       li.sh_b = sh;  sh += gmi::align_up((int64_t)li.out_pad * 4, 256);
       if (li.out_pad > maxw) maxw = li.out_pad;
       L->net[net].push_back(li);
@@ -46,6 +48,7 @@ int build_layout(const gmi_model_desc* d, ModelLayout* L) {
   sh += gmi::align_up((int64_t)d->act_dim * 4, 256);
   L->n_params = off;
   L->shadow_bytes = d->dtype == GMI_DTYPE_BF16 ? sh : 0;
+  L->weight_bytes = wbytes;
   L->max_width_pad = maxw;
   return GMI_OK;
 }
@@ -71,7 +74,7 @@ __device__ __forceinline__ uint16_t f_to_bf16_dev(float f) {
   return (uint16_t)(u >> 16);
 }
 
-// One thread per parameter: writes its bf16 copies (W and W^T layouts) or fp32 bias / log_std copy.
+// One thread per parameter: writes its bf16 copies (W, W^T and fragment-major layouts) or fp32 bias / log_std copy.
 // Padding entries of the shadow are zeroed by gmi_model_refresh_shadow and never written otherwise.
 __global__ void refresh_shadow_kernel(gmi::ShadowTable tab, const float* __restrict__ params, char* __restrict__ shadow) {
   const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -92,6 +95,7 @@ __global__ void refresh_shadow_kernel(gmi::ShadowTable tab, const float* __restr
     const uint16_t b = f_to_bf16_dev(v);
     reinterpret_cast<uint16_t*>(shadow + L.sh_w)[(int64_t)o * L.in_pad + i] = b;
     reinterpret_cast<uint16_t*>(shadow + L.sh_wt)[(int64_t)i * L.out_pad + o] = b;
+    reinterpret_cast<uint16_t*>(shadow + L.sh_wf)[gmi::wfrag_index(o, i, L.in_pad)] = b;
   }
 }
 

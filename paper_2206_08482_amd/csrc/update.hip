@@ -198,9 +198,9 @@ __global__ __launch_bounds__(256) void adam_kernel(gmi::ShadowTable tab, int wri
   }
 }
 
-// Rebuilds the transposed weight shadows [in_pad, out_pad] from the [out_pad, in_pad] ones through
-// 64x64 LDS tiles, so that both sides move whole 16-byte pieces (one 2-byte store per weight into the
-// transposed copy touched a different memory line for every thread of a wave).
+// Rebuilds the transposed weight shadows [in_pad, out_pad] and the fragment-major ones from the
+// [out_pad, in_pad] ones through 64x64 LDS tiles, so that all sides move whole 16-byte pieces (one 2-byte
+// store per weight into the transposed copy touched a different memory line for every thread of a wave).
 struct TransposeTiles {
   int n;
   int start[gmi::kMaxWgradProblems + 1];
@@ -216,6 +216,7 @@ __global__ __launch_bounds__(256) void shadow_transpose_kernel(gmi::ShadowTable 
   const int o0 = (local / n_ti) * 64, i0 = (local % n_ti) * 64;
   const uint16_t* __restrict__ w = reinterpret_cast<const uint16_t*>(shadow + L.sh_w);
   uint16_t* __restrict__ wt = reinterpret_cast<uint16_t*>(shadow + L.sh_wt);
+  uint16_t* __restrict__ wf = reinterpret_cast<uint16_t*>(shadow + L.sh_wf);
   const int tid = threadIdx.x, c8 = (tid & 7) * 8, r = tid >> 3;
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
@@ -237,6 +238,15 @@ __global__ __launch_bounds__(256) void shadow_transpose_kernel(gmi::ShadowTable 
       v.z = e[4] | ((uint32_t)e[5] << 16); v.w = e[6] | ((uint32_t)e[7] << 16);
       *reinterpret_cast<uint4*>(wt + (int64_t)i * L.out_pad + o) = v;
     }
+  }
+  // the tile holds 2 feature tiles x 4 k steps = 8 fragment blocks of 64 lanes x 16 bytes
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int idx = tid + 256 * k, blk = idx >> 6, lane = idx & 63;
+    const int ol = (blk >> 2) * 32 + (lane & 31), il = (blk & 3) * 16 + (lane >> 5) * 8;
+    if (o0 + ol < L.out_pad && i0 + il < L.in_pad)
+      *reinterpret_cast<uint4*>(wf + gmi::wfrag_index(o0 + ol, i0 + il, L.in_pad)) =
+          *reinterpret_cast<const uint4*>(&s_t[ol][il]);
   }
 }
 
