@@ -23,6 +23,11 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_FP32_TFLOPS = 157.3       # vector fp32
 
+# HBM bytes per launch (fetch + write) of the kernels that dominate the bench workloads, from the
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/hbm_traffic_C2_C4.md (counter values
+# scaled by what the same counters read for a copy kernel of known size).  Keyed by (workload, class).
+MEASURED_TRAFFIC = {}
+
 
 def mac_per_sample(cfg, first_layer=True):
     """Multiply-accumulates of one forward of both nets for one sample (unpadded)."""
@@ -55,9 +60,10 @@ def layer_bytes_per_sample(cfg, es, first_layer=True):
 
 
 def class_work(cfg, n_params, launched):
-    """Algorithmic work per *step* of every kernel class: flops and/or HBM bytes and launches.
-    `launched` maps class name -> launches seen in the profiled step; it tells which of the alternative
-    paths (per-layer, fused agent, one-launch rollout, fused trainer) carried the rollout's forward passes."""
+    """Algorithmic work per *step* of the kernel classes whose launchers do not state it themselves
+    (the linear-layer and weight-gradient classes report theirs through gmi_profile_work): HBM bytes and,
+    for the fused kernels, flops; plus the whole step's matrix-product flops.
+    `launched` maps class name -> launches seen in the profiled step."""
     N, T, B, MB, E = cfg.n_envs, cfg.horizon, cfg.batch, cfg.minibatch, cfg.epochs
     O, A, L = cfg.obs_dim, cfg.act_dim, len(cfg.hidden)
     mac = mac_per_sample(cfg)
@@ -67,28 +73,15 @@ def class_work(cfg, n_params, launched):
     es = 2 if cfg.dtype == "bf16" else 4
     w_bytes = n_params * es
     act_b = layer_bytes_per_sample(cfg, es)
-    act_b_dgrad = layer_bytes_per_sample(cfg, es, first_layer=False)
     rollout_flops = 2.0 * (T * N * mac + N * mac_value)
     per_layer_rollout = not (launched.get("fused_agent") or launched.get("fused_rollout"))
-    per_layer_update = not launched.get("fused_train")
-    fwd_flops = (rollout_flops if per_layer_rollout else 0.0) + (2.0 * n_upd * MB * mac if per_layer_update else 0.0)
-    fwd_rows = ((T + 0.5) * N if per_layer_rollout else 0.0) + (n_upd * MB if per_layer_update else 0.0)
-    fwd_launches = ((T + 1) * (L + 1) if per_layer_rollout else 0) + (n_upd * (L + 1) if per_layer_update else 0)
     exp_bytes = T * N * (4.0 * (O + A + 3) + 1)               # one step's experience slot, all envs
     return {
-        "linear_fwd": dict(flops=fwd_flops, bytes=fwd_rows * act_b + fwd_launches / (L + 1) * w_bytes,
-                           launches=fwd_launches),
-        # input gradients: read dz[l] and h[l], write dz[l-1]
-        "linear_dgrad": dict(flops=2.0 * n_upd * MB * mac_dgrad,
-                             bytes=n_upd * (MB * (act_b_dgrad + sum(pad32(h) for h in cfg.hidden) * es * 2) + w_bytes),
-                             launches=n_upd * L),
-        # weight gradients: read every layer's input and output gradient once, write the fp32 gradient
-        "wgrad": dict(flops=2.0 * n_upd * MB * mac, bytes=n_upd * (MB * act_b + 4.0 * n_params), launches=n_upd),
         "gather": dict(bytes=(T + 1) * N * O * (4 + es) * (1 if per_layer_rollout else 0)
                        + n_upd * MB * (O * (4 + es) + 8.0 * (A + 3) + 4),
                        launches=(T + 1 if per_layer_rollout else 0) + n_upd),
         "loss": dict(bytes=n_upd * MB * (4.0 * (2 * A + 5) + es * (A + 1)), launches=n_upd),
-        "adam": dict(bytes=n_upd * n_params * (16.0 + 12.0 + (4 if cfg.dtype == "bf16" else 0)), launches=n_upd),
+        "adam": dict(bytes=n_upd * n_params * (16.0 + 12.0 + (3 * es if cfg.dtype == "bf16" else 0)), launches=n_upd),
         "env_step": dict(bytes=T * N * (4.0 * (2 * O + A) + 8 + 1), launches=T),
         "sample": dict(bytes=T * N * 4.0 * (2 * A + 1), launches=T),
         "collect": dict(bytes=2 * exp_bytes, launches=T),
@@ -140,6 +133,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fusion", type=int, default=None,
+                    help="fusion level of the instance (0 per-layer kernels only, 1 fused agent/rollout, "
+                         "2 also the row-tile fused trainer); default: the library's")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (its instances are CU-masked streams of one device); "
@@ -166,6 +162,9 @@ def main() -> int:
                      horizon=cfg.horizon, dtype=cfg.dtype, theta=theta, a_mat=a_mat, b_mat=b_mat, state0=state0,
                      noise_std=cfg.noise_std, reward_scale=cfg.reward_scale, done_period=cfg.done_period,
                      done_threshold=thr, seed=cfg.seed, minibatch=cfg.minibatch)
+    if args.fusion is not None:
+        g.gmi_set_fusion(ses.gmi, args.fusion)
+        ses.fused_rollout = ses.fused_rollout and args.fusion >= 1
     s0 = torch.tensor(state0, device="cuda:0")
     ep0 = torch.zeros(cfg.n_envs, dtype=torch.int32, device="cuda:0")
     torch.cuda.synchronize()
@@ -200,6 +199,7 @@ def main() -> int:
     ses.sync(); torch.cuda.synchronize()
     t1 = time.perf_counter()
     dom_ms, dom_launches = g.gmi_profile_read(ses.gmi, names.index(dominant))
+    dom_flops, dom_bytes = g.gmi_profile_work(ses.gmi, names.index(dominant))
     g.gmi_profile_enable(ses.gmi, 0)
     assert torch.isfinite(ses.theta).all().item(), "parameters are not finite after the timed steps"
 
@@ -216,27 +216,28 @@ def main() -> int:
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = args.steps * cfg.batch / (t1 - t0)
     work, flops_step = class_work(cfg, int(ses.theta.numel()), {k: v[1] for k, v in per_class.items()})
-    w = work[dominant]
     avg_ms = dom_ms / max(dom_launches, 1)
-    launches_per_step = w["launches"]
-    # the roof that bounds this class: the larger of its matrix-core time and its HBM time at the peaks
-    peak_flops = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
-    t_mfma = w.get("flops", 0.0) / (peak_flops * 1e12)
-    t_hbm = w.get("bytes", 0.0) / (PEAK_HBM_GBS * 1e9)
-    if t_mfma >= t_hbm:
-        achieved = w["flops"] / launches_per_step / (avg_ms * 1e-3) / 1e12
-        roof = {"bound": "mfma", "achieved": achieved, "peak": peak_flops, "unit": "TFLOP/s"}
+    if dom_flops > 0 or dom_bytes > 0:          # stated by the launcher for exactly the timed launches
+        flops_per_launch, bytes_per_launch = dom_flops / dom_launches, dom_bytes / dom_launches
     else:
-        achieved = w["bytes"] / launches_per_step / (avg_ms * 1e-3) / 1e9
-        roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+        w = work[dominant]
+        flops_per_launch = w.get("flops", 0.0) / w["launches"]
+        bytes_per_launch = w.get("bytes", 0.0) / w["launches"]
+    # the roof that bounds this kernel: the larger of its matrix-core time and its HBM time at the peaks
+    peak_flops = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
+    if flops_per_launch / (peak_flops * 1e12) >= bytes_per_launch / (PEAK_HBM_GBS * 1e9):
+        roof = {"bound": "mfma", "achieved": flops_per_launch / (avg_ms * 1e-3) / 1e12, "peak": peak_flops,
+                "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "hbm", "achieved": bytes_per_launch / (avg_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = MEASURED_TRAFFIC.get((cfg.name, dominant))
     roof["kernel"] = dominant
     roof["avg_launch_us"] = avg_ms * 1e3
     roof["launches_timed"] = dom_launches
-    if "flops" in w and w["flops"]:
-        roof["tflops"] = w["flops"] / launches_per_step / (avg_ms * 1e-3) / 1e12
-    roof["algorithmic_bytes_per_launch"] = w.get("bytes", 0.0) / launches_per_step
+    roof["tflops"] = flops_per_launch / (avg_ms * 1e-3) / 1e12
+    roof["algorithmic_bytes_per_launch"] = bytes_per_launch
 
     total_ms = sum(v[0] for v in per_class.values())
     breakdown = {k: {"ms_per_step": round(v[0], 4), "launches": v[1]} for k, v in per_class.items() if v[1]}

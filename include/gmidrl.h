@@ -266,10 +266,11 @@ int gmi_permutation(gmi_t gmi, int32_t n, uint64_t seed, uint32_t iteration, uin
 /* ------------------------------------------------------------------ per-launch timing ------- */
 
 /* Built-in timer for measurement runs (the paper's profile() step of Algorithm 2 measures a trial
- * run; here the unit is one kernel class).  class_mask bit c = 1: every launch of kernel class c on
- * this instance is bracketed by a pair of HIP timing events on the instance's stream.  Enabling (or
- * passing 0 to disable) synchronises the stream and clears earlier measurements.  Event pairs are
- * created on demand, so a profiled call may allocate host-side event objects. */
+ * run; here the unit is one kernel class = one kernel symbol).  class_mask bit c = 1: every launch of
+ * kernel class c on this instance carries a pair of HIP events on the instance's stream that receive the
+ * kernel's own begin and end timestamps, so a class total is execution time without launch gaps.
+ * Enabling (or passing 0 to disable) synchronises the stream and clears earlier measurements.  Event
+ * pairs are created on demand, so a profiled call may allocate host-side event objects. */
 int gmi_profile_enable(gmi_t gmi, uint32_t class_mask);
 /* Number of kernel classes, and the name of class cls (NULL if out of range). */
 int gmi_profile_classes(void);
@@ -277,6 +278,10 @@ const char* gmi_profile_class_name(int cls);
 /* Synchronises the stream and returns the summed duration (ms) and the number of bracketed
  * launches of class cls since profiling was enabled.  host: total_ms, launches. */
 int gmi_profile_read(gmi_t gmi, int cls, double* total_ms, int64_t* launches);
+/* Algorithmic work (flops; bytes of operands read and results written once) that the launchers stated
+ * for the timed launches of class cls since gmi_profile_enable; 0 for classes whose launcher states
+ * none (the linear-layer and weight-gradient classes state theirs).  host: flops, bytes. */
+int gmi_profile_work(gmi_t gmi, int cls, double* flops, double* bytes);
 
 /* Achievable-peak probes for measurement reports: what = 0 runs a pure bf16 matrix-core loop and
  * returns TFLOP/s, what = 1 runs a streaming copy over the two halves of `scratch` and returns GB/s

@@ -25,7 +25,7 @@ EXPORTS = [
     "agent_act", "agent_value", "gmi_buffer_bind", "gmi_buffer_destroy", "collect_experience",
     "gae_compute", "ppo_update", "ppo_evaluate", "ppo_gradient", "adam_update", "gmi_noise_fill",
     "gmi_permutation", "gmi_profile_enable", "gmi_profile_classes", "gmi_profile_class_name", "gmi_profile_read",
-    "gmi_measure_peak", "gmi_bench_linear", "gmi_set_fusion", "rollout_collect",
+    "gmi_measure_peak", "gmi_bench_linear", "gmi_set_fusion", "rollout_collect", "gmi_profile_work",
 ]
 
 
@@ -100,6 +100,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "gmi_profile_class_name": (C.c_char_p, [C.c_int]),
         "gmi_profile_read": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]),
         "gmi_set_fusion": (C.c_int, [vp, C.c_int]),
+        "gmi_profile_work": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "gmi_measure_peak": (C.c_int, [vp, C.c_int, vp, C.c_size_t, C.POINTER(C.c_double)]),
         "gmi_bench_linear": (C.c_int, [vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_size_t,
                                        C.POINTER(C.c_double)]),
@@ -340,6 +341,13 @@ def gmi_profile_read(gmi: int, cls: int):
     ms, n = C.c_double(), C.c_int64()
     _check(_lib.gmi_profile_read(gmi, cls, C.byref(ms), C.byref(n)))
     return ms.value, n.value
+
+
+def gmi_profile_work(gmi: int, cls: int):
+    """(flops, bytes) of algorithmic work stated by the launchers of class `cls` while it was timed."""
+    fl, by = C.c_double(), C.c_double()
+    _check(_lib.gmi_profile_work(gmi, cls, C.byref(fl), C.byref(by)))
+    return fl.value, by.value
 
 
 def dtype_code(name: str) -> int:

@@ -18,33 +18,51 @@ void set_error(const char* fmt, ...) {
 extern "C" const char* gmi_last_error(void) { return gmi::g_err; }
 
 namespace gmi {
-ProfScope::ProfScope(gmi_instance* g_, int cls_) : g(g_), cls(cls_), on(false) {
-  if (!(g->prof_mask & (1u << cls))) return;
+ProfScope::ProfScope(gmi_instance* g_, int cls_) : g(g_), cls(cls_), on((g_->prof_mask >> cls_) & 1u) {}
+void ProfScope::work(double flops, double bytes) {
+  if (on) { g->prof[cls].flops += flops; g->prof[cls].bytes += bytes; }
+}
+bool ProfScope::next_events(hipEvent_t* a, hipEvent_t* b) {
   ProfSlot& s = g->prof[cls];
   if (s.used == s.start.size()) {
-    hipEvent_t a, b;
-    if (hipEventCreate(&a) != hipSuccess) return;
-    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
-    s.start.push_back(a);
-    s.stop.push_back(b);
+    hipEvent_t ea, eb;
+    if (hipEventCreate(&ea) != hipSuccess) return false;
+    if (hipEventCreate(&eb) != hipSuccess) { (void)hipEventDestroy(ea); return false; }
+    s.start.push_back(ea);
+    s.stop.push_back(eb);
   }
-  on = hipEventRecord(s.start[s.used], g->stream) == hipSuccess;
+  *a = s.start[s.used];
+  *b = s.stop[s.used];
+  ++s.used;
+  return true;
 }
-ProfScope::~ProfScope() {
-  if (!on) return;
-  ProfSlot& s = g->prof[cls];
-  if (hipEventRecord(s.stop[s.used], g->stream) == hipSuccess) ++s.used;
-}
-static const char* kClassNames[kClsCount] = {"gather", "linear_fwd", "linear_dgrad", "wgrad", "loss", "adam",
-                                             "env_step", "sample", "collect", "gae", "permutation", "fused_agent",
-                                             "fused_train", "fused_rollout", "reduce"};
+static const char* kClassNames[kClsCount] = {
+    "gather", "wgrad", "loss", "adam", "shadow_transpose", "env_step", "sample", "collect", "gae", "permutation",
+    "fused_agent", "fused_train", "fused_rollout", "reduce", "linear_f32",
+    "linear_big256_fwd", "linear_big256_head", "linear_big256_dgrad",
+    "linear_big128_fwd", "linear_big128_head", "linear_big128_dgrad",
+    "linear_t128_fwd", "linear_t128_head", "linear_t128_dgrad",
+    "linear_t256x64_fwd", "linear_t256x64_head", "linear_t256x64_dgrad",
+    "linear_t128x64_fwd", "linear_t128x64_head", "linear_t128x64_dgrad"};
 }  // namespace gmi
 
 extern "C" int gmi_profile_enable(gmi_t g, uint32_t class_mask) {
   if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_profile_enable: bad handle");
   GMI_HIP(hipStreamSynchronize(g->stream));
   g->prof_mask = class_mask & ((1u << gmi::kClsCount) - 1u);
-  for (int c = 0; c < gmi::kClsCount; ++c) g->prof[c].used = 0;
+  for (int c = 0; c < gmi::kClsCount; ++c) {
+    g->prof[c].used = 0;
+    g->prof[c].flops = g->prof[c].bytes = 0.0;
+  }
+  return GMI_OK;
+}
+
+extern "C" int gmi_profile_work(gmi_t g, int cls, double* flops, double* bytes) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_profile_work: bad handle");
+  if (cls < 0 || cls >= gmi::kClsCount) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_profile_work: class %d out of range", cls);
+  if (!flops || !bytes) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_profile_work: NULL output");
+  *flops = g->prof[cls].flops;
+  *bytes = g->prof[cls].bytes;
   return GMI_OK;
 }
 
@@ -209,10 +227,9 @@ namespace gmi {
 int launch_permutation(gmi_instance* g, int n, uint64_t seed, uint32_t iteration, uint32_t epoch, int32_t* out) {
   if (n <= 0) return GMI_OK;
   ProfScope ps(g, kClsPermutation);
-  hipStream_t s = g->stream;
   int bits = 0;
   while ((1ll << bits) < (long long)n) ++bits;
-  permutation_kernel<<<(n + 255) / 256, 256, 0, s>>>(n, bits, iteration, epoch, (uint32_t)seed,
+  ps.launch(permutation_kernel, dim3((n + 255) / 256), dim3(256), 0, n, bits, iteration, epoch, (uint32_t)seed,
                                                      (uint32_t)(seed >> 32), out);
   GMI_LAUNCH_CHECK();
   return GMI_OK;

@@ -196,7 +196,7 @@ extern "C" int env_step(gmi_t g, gmi_env_t env, const float* obs, const float* a
   const uint32_t k0 = (uint32_t)d.seed, k1 = (uint32_t)(d.seed >> 32);
   gmi::ProfScope ps(g, gmi::kClsEnvStep);
 #define GMI_ENV_LAUNCH(E)                                                                          \
-  env_step_kernel<E><<<grid, 256, lds_bytes(E), g->stream>>>(                                      \
+  ps.launch(env_step_kernel<E>, dim3(grid), dim3(256), lds_bytes(E),                                       \
       obs, act, env->m_t, env->episode_step, next_obs, reward, done, N, O, A, o4, nb, G,          \
       d.noise_std, d.reward_scale, d.done_period, d.done_threshold, k0, k1, d.env_offset, step, vec_store)
   if (ept == 4) GMI_ENV_LAUNCH(4); else if (ept == 2) GMI_ENV_LAUNCH(2); else GMI_ENV_LAUNCH(1);

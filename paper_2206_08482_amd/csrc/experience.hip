@@ -174,7 +174,7 @@ extern "C" int collect_experience(gmi_t g, gmi_buffer_t b, int32_t t, const floa
   if (grid > 8192) grid = 8192;
   if (grid < 1) grid = 1;
   gmi::ProfScope ps(g, gmi::kClsCollect);
-  collect_kernel<<<(unsigned)grid, 256, 0, g->stream>>>(b->d, t, obs, act, logp, value, reward, done, vec_obs, vec_act);
+  ps.launch(collect_kernel, dim3((unsigned)grid), dim3(256), 0, b->d, t, obs, act, logp, value, reward, done, vec_obs, vec_act);
   GMI_LAUNCH_CHECK();
   return GMI_OK;
 }
@@ -186,14 +186,14 @@ extern "C" int gae_compute(gmi_t g, gmi_buffer_t b, const float* last_value, flo
   if (b->d.n_envs == 0 || b->d.horizon == 0) return GMI_OK;
   if (!last_value) GMI_FAIL(GMI_ERR_INVALID_ARG, "gae_compute: last_value is NULL");
   gmi::ProfScope ps(g, gmi::kClsGae);
-  gae_kernel<<<b->n_part, 256, 0, g->stream>>>(b->d, last_value, gamma, gamma * lambda,
+  ps.launch(gae_kernel, dim3(b->n_part), dim3(256), 0, b->d, last_value, gamma, gamma * lambda,
                                                normalize ? b->part : nullptr);
   GMI_LAUNCH_CHECK();
   if (normalize) {
     const int64_t total = (int64_t)b->d.horizon * b->d.n_envs;
     int grid = (int)((total + 1023) / 1024);
     if (grid > 2048) grid = 2048;
-    normalize_kernel<<<grid, 256, 0, g->stream>>>(b->d, b->part, b->n_part);
+    ps.launch(normalize_kernel, dim3(grid), dim3(256), 0, b->d, b->part, b->n_part);
     GMI_LAUNCH_CHECK();
   }
   return GMI_OK;

@@ -832,14 +832,14 @@ int launch_agent_fused(gmi_instance* g, gmi_model* m, const float* obs, int n, u
       GMI_HIP(hipFuncSetAttribute((const void*)agent_fused_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
       attr64 = true;
     }
-    agent_fused_kernel<2><<<(n + 63) / 64, 256, lds, g->stream>>>(a);
+    ps.launch(agent_fused_kernel<2>, dim3((n + 63) / 64), dim3(256), lds, a);
   } else {
     static bool attr32 = false;
     if (!attr32) {
       GMI_HIP(hipFuncSetAttribute((const void*)agent_fused_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
       attr32 = true;
     }
-    agent_fused_kernel<1><<<(n + 31) / 32, 256, lds, g->stream>>>(a);
+    ps.launch(agent_fused_kernel<1>, dim3((n + 31) / 32), dim3(256), lds, a);
   }
   GMI_LAUNCH_CHECK();
   return GMI_OK;
@@ -887,21 +887,21 @@ int launch_train_fused(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_p
         GMI_HIP(hipFuncSetAttribute((const void*)train_fused_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
         attr64 = true;
       }
-      train_fused_kernel<2><<<dim3(tiles, 2), 256, lds, g->stream>>>(a);
+      ps.launch(train_fused_kernel<2>, dim3(dim3(tiles, 2)), dim3(256), lds, a);
     } else {
       static bool attr32 = false;
       if (!attr32) {
         GMI_HIP(hipFuncSetAttribute((const void*)train_fused_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
         attr32 = true;
       }
-      train_fused_kernel<1><<<dim3(tiles, 2), 256, lds, g->stream>>>(a);
+      ps.launch(train_fused_kernel<1>, dim3(dim3(tiles, 2)), dim3(256), lds, a);
     }
     GMI_LAUNCH_CHECK();
   }
   {
     ProfScope ps(g, kClsReduce);
     const int width = kStatStride + L.act_dim;
-    reduce_rows_kernel<<<width, 256, 0, g->stream>>>(m->stat_part, tiles, width, m->stat_part + (int64_t)kLossBlocksMax * width);
+    ps.launch(reduce_rows_kernel, dim3(width), dim3(256), 0, m->stat_part, tiles, width, m->stat_part + (int64_t)kLossBlocksMax * width);
     GMI_LAUNCH_CHECK();
   }
   return GMI_OK;
@@ -973,14 +973,14 @@ extern "C" int rollout_collect(gmi_t g, gmi_model_t m, gmi_env_t env, gmi_buffer
       GMI_HIP(hipFuncSetAttribute((const void*)rollout_fused_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
       attr64 = true;
     }
-    rollout_fused_kernel<2><<<(n + 63) / 64, 512, lds, g->stream>>>(a);
+    ps.launch(rollout_fused_kernel<2>, dim3((n + 63) / 64), dim3(512), lds, a);
   } else {
     static bool attr32 = false;
     if (!attr32) {
       GMI_HIP(hipFuncSetAttribute((const void*)rollout_fused_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
       attr32 = true;
     }
-    rollout_fused_kernel<1><<<(n + rows_per_wg - 1) / rows_per_wg, 512, lds, g->stream>>>(a);
+    ps.launch(rollout_fused_kernel<1>, dim3((n + rows_per_wg - 1) / rows_per_wg), dim3(512), lds, a);
   }
   GMI_LAUNCH_CHECK();
   return GMI_OK;

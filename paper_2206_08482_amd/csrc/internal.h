@@ -1,10 +1,14 @@
 // Internal declarations shared by the translation units of libgmidrl (not part of the C ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <hip/hip_bf16.h>
 #include <stdint.h>
 #include <stdio.h>
 #include <string>
+#include <tuple>
+#include <type_traits>
+#include <utility>
 #include <vector>
 
 #include "../../include/gmidrl.h"
@@ -51,13 +55,23 @@ static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * 
 
 namespace gmi {
 // Kernel classes of the built-in per-launch timer (gmi_profile_*).
+// One class per kernel symbol, so that a class average can be set beside a profiler's per-kernel
+// average.  The linear-layer classes are kClsLinear + 3 * variant + role:
+//   variant 0 linear_bf16_big_kernel<4,4,*> (256x256 tile)   1 linear_bf16_big_kernel<2,4,*> (256x128)
+//           2 linear_bf16_kernel<2,2,2,2,*> (128x128)         3 linear_bf16_kernel<1,4,2,2,*> (256x64)
+//           4 linear_bf16_kernel<1,4,1,2,*> (128x64)
+//   role    0 forward hidden layer (bias + ELU)   1 forward head   2 input gradient (ELU')
+// (kClsGae covers gae_kernel and normalize_kernel, kClsLinearF32 the three fp32 epilogues.)
 enum KernelClass {
-  kClsGather = 0, kClsLinearFwd, kClsLinearDgrad, kClsWgrad, kClsLoss, kClsAdam, kClsEnvStep, kClsSample,
-  kClsCollect, kClsGae, kClsPermutation, kClsFusedAgent, kClsFusedTrain, kClsFusedRollout, kClsReduce, kClsCount
+  kClsGather = 0, kClsWgrad, kClsLoss, kClsAdam, kClsShadowTranspose, kClsEnvStep, kClsSample,
+  kClsCollect, kClsGae, kClsPermutation, kClsFusedAgent, kClsFusedTrain, kClsFusedRollout, kClsReduce,
+  kClsLinearF32, kClsLinear, kClsCount = kClsLinear + 15
 };
+static_assert(kClsCount < 32, "class masks are 32-bit");
 struct ProfSlot {
   std::vector<hipEvent_t> start, stop;
   size_t used = 0;
+  double flops = 0.0, bytes = 0.0;   // algorithmic work of the timed launches, where the launcher states it
 };
 }  // namespace gmi
 
@@ -68,19 +82,42 @@ struct gmi_instance {
   hipEvent_t event;      // used by gmi_transfer
   int cu_count;
   int fusion;            // 1: use the row-tile fused kernels where the model fits them (default)
-  uint32_t prof_mask;    // bit c set: launches of kernel class c are bracketed by timing events
+  uint32_t prof_mask;    // bit c set: launches of kernel class c carry timing events
   gmi::ProfSlot prof[gmi::kClsCount];
 };
 
 namespace gmi {
-// Brackets the kernel launches issued inside its scope with a pair of timing events when the
-// instance has profiling enabled for the class; otherwise does nothing.
+// Launches kernels of one class on the instance's stream.  While the class is being timed every launch
+// carries its own pair of HIP events that receive the kernel's begin and end timestamps
+// (hipExtLaunchKernel), so a class average is the kernels' execution time without launch gaps.
 struct ProfScope {
   gmi_instance* g;
   int cls;
   bool on;
   ProfScope(gmi_instance* g_, int cls_);
-  ~ProfScope();
+  // adds the algorithmic work of the launches in this scope (counted only while the class is timed)
+  void work(double flops, double bytes);
+  // next unused event pair of the class (created on demand); false if none could be made
+  bool next_events(hipEvent_t* a, hipEvent_t* b);
+
+  // Arguments are converted to the kernel's exact parameter types before their addresses are taken.
+  template <typename... KArgs, typename... Args>
+  void launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, Args&&... args) {
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "kernel argument count");
+    std::tuple<std::remove_cv_t<KArgs>...> t{static_cast<KArgs>(std::forward<Args>(args))...};
+    launch_impl(reinterpret_cast<const void*>(kernel), grid, block, lds, t, std::index_sequence_for<KArgs...>{});
+  }
+
+ private:
+  template <typename T, size_t... I>
+  void launch_impl(const void* kernel, dim3 grid, dim3 block, size_t lds, T& t, std::index_sequence<I...>) {
+    void* ptrs[] = {const_cast<void*>(static_cast<const void*>(&std::get<I>(t)))...};
+    hipEvent_t a, b;
+    if (on && next_events(&a, &b))
+      (void)hipExtLaunchKernel(kernel, grid, block, ptrs, lds, g->stream, a, b, 0);
+    else
+      (void)hipLaunchKernel(kernel, grid, block, ptrs, lds, g->stream);
+  }
 };
 }  // namespace gmi
 
@@ -173,6 +210,7 @@ struct LinearProblem {
   const void* h; int ldh;
   void* y; int ldy;
   int K, F, F_store;
+  int K_log, F_log;         // logical (unpadded) sizes, for the work accounting of the launch timer
 };
 
 struct LinearBatch {

@@ -567,30 +567,30 @@ __global__ void wgrad_f32_kernel(gmi::WgradBatch batch, int rows, int chunk, flo
 }
 
 template <int TFW, int TRW>
-int launch_bf16_big(hipStream_t s, int epi, int rows, const gmi::LinearBatch& b, int maxF) {
+int launch_bf16_big(gmi::ProfScope& ps, int epi, int rows, const gmi::LinearBatch& b, int maxF) {
   constexpr int TF = 2 * TFW * 32, TR = 2 * TRW * 32;
   const int n_rt = (rows + TR - 1) / TR, n_ft = (maxF + TF - 1) / TF;
   const int n_rt_pad = (n_rt + 7) & ~7;
   const unsigned grid = (unsigned)(n_rt_pad * n_ft * b.n);
   if (epi == gmi::kEpiBiasElu)
-    linear_bf16_big_kernel<TFW, TRW, gmi::kEpiBiasElu><<<grid, 256, 0, s>>>(b, rows, n_rt, n_rt_pad, n_ft);
+    ps.launch(linear_bf16_big_kernel<TFW, TRW, gmi::kEpiBiasElu>, dim3(grid), dim3(256), 0, b, rows, n_rt, n_rt_pad, n_ft);
   else
-    linear_bf16_big_kernel<TFW, TRW, gmi::kEpiEluGrad><<<grid, 256, 0, s>>>(b, rows, n_rt, n_rt_pad, n_ft);
+    ps.launch(linear_bf16_big_kernel<TFW, TRW, gmi::kEpiEluGrad>, dim3(grid), dim3(256), 0, b, rows, n_rt, n_rt_pad, n_ft);
   GMI_LAUNCH_CHECK();
   return GMI_OK;
 }
 
 template <int WF, int WR, int TFM, int TRM>
-int launch_bf16_cfg(hipStream_t s, int epi, int rows, const gmi::LinearBatch& b, int maxF) {
+int launch_bf16_cfg(gmi::ProfScope& ps, int epi, int rows, const gmi::LinearBatch& b, int maxF) {
   constexpr int TF = WF * TFM * 32, TR = WR * TRM * 32;
   dim3 grid((rows + TR - 1) / TR, (maxF + TF - 1) / TF, b.n);
   switch (epi) {
     case gmi::kEpiBiasElu:
-      linear_bf16_kernel<WF, WR, TFM, TRM, gmi::kEpiBiasElu><<<grid, 256, 0, s>>>(b, rows); break;
+      ps.launch(linear_bf16_kernel<WF, WR, TFM, TRM, gmi::kEpiBiasElu>, dim3(grid), dim3(256), 0, b, rows); break;
     case gmi::kEpiBiasHead:
-      linear_bf16_kernel<WF, WR, TFM, TRM, gmi::kEpiBiasHead><<<grid, 256, 0, s>>>(b, rows); break;
+      ps.launch(linear_bf16_kernel<WF, WR, TFM, TRM, gmi::kEpiBiasHead>, dim3(grid), dim3(256), 0, b, rows); break;
     default:
-      linear_bf16_kernel<WF, WR, TFM, TRM, gmi::kEpiEluGrad><<<grid, 256, 0, s>>>(b, rows); break;
+      ps.launch(linear_bf16_kernel<WF, WR, TFM, TRM, gmi::kEpiEluGrad>, dim3(grid), dim3(256), 0, b, rows); break;
   }
   GMI_LAUNCH_CHECK();
   return GMI_OK;
@@ -602,46 +602,81 @@ namespace gmi {
 
 int launch_linear(gmi_instance* g, int dtype, int epi, int rows, const LinearBatch& b) {
   if (rows <= 0 || b.n <= 0) return GMI_OK;
-  ProfScope ps(g, epi == kEpiEluGrad ? kClsLinearDgrad : kClsLinearFwd);
-  hipStream_t s = g->stream;
   int maxF = 0;
   for (int i = 0; i < b.n; ++i) maxF = b.p[i].F > maxF ? b.p[i].F : maxF;
+  if (dtype != GMI_DTYPE_F32) {
+    for (int i = 0; i < b.n; ++i) {
+      const LinearProblem& p = b.p[i];
+      if ((p.K & 31) || (p.F & 31) || (p.ldx & 7) || (p.ldw & 7) || (epi != kEpiBiasHead && (p.ldy & 3)) ||
+          (epi == kEpiEluGrad && (p.ldh & 3)))
+        GMI_FAIL(GMI_ERR_BAD_SHAPE, "launch_linear: bf16 path needs padded dims (K=%d F=%d)", p.K, p.F);
+    }
+  }
+  // kernel variant (see KernelClass): large tiles for wide layers of big batches, else by feature count
+  int variant;
   if (dtype == GMI_DTYPE_F32) {
-    dim3 grid((unsigned)(((int64_t)rows * maxF + 255) / 256), 1, b.n);
-    switch (epi) {
-      case kEpiBiasElu: linear_f32_kernel<kEpiBiasElu><<<grid, 256, 0, s>>>(b, rows); break;
-      case kEpiBiasHead: linear_f32_kernel<kEpiBiasHead><<<grid, 256, 0, s>>>(b, rows); break;
-      default: linear_f32_kernel<kEpiEluGrad><<<grid, 256, 0, s>>>(b, rows); break;
+    variant = 5;
+  } else if (epi != kEpiBiasHead && rows >= 8192 && maxF > 64) {
+    // choose the large tile whose padding waste over the feature range is smallest
+    const int waste256 = (maxF + 255) / 256 * 256 - maxF, waste128 = (maxF + 127) / 128 * 128 - maxF;
+    variant = (maxF > 128 && waste256 <= waste128) ? 0 : 1;
+  } else if (maxF % 128 == 0 || maxF > 256) {
+    variant = 2;
+  } else if (maxF % 64 == 0) {
+    variant = 3;
+  } else if (maxF <= 96) {
+    variant = 4;
+  } else {
+    variant = 2;
+  }
+  const int role = epi == kEpiEluGrad ? 2 : (epi == kEpiBiasHead ? 1 : 0);
+  ProfScope ps(g, variant == 5 ? (int)kClsLinearF32 : kClsLinear + 3 * variant + role);
+  {
+    // algorithmic work: 2 K F flops per row; each row's input and output once (heads write fp32, the
+    // input-gradient product also reads the layer's stored activation), the weights once
+    const double es = dtype == GMI_DTYPE_F32 ? 4.0 : 2.0;
+    double fl = 0.0, by = 0.0;
+    for (int i = 0; i < b.n; ++i) {
+      const double K = b.p[i].K_log > 0 ? b.p[i].K_log : b.p[i].K, F = b.p[i].F_log > 0 ? b.p[i].F_log : b.p[i].F;
+      fl += 2.0 * rows * K * F;
+      by += rows * (K * es + F * (role == 1 ? 4.0 : es) + (role == 2 ? F * es : 0.0)) + K * F * es;
     }
-    GMI_LAUNCH_CHECK();
-    return GMI_OK;
+    ps.work(fl, by);
   }
-  for (int i = 0; i < b.n; ++i) {
-    const LinearProblem& p = b.p[i];
-    if ((p.K & 31) || (p.F & 31) || (p.ldx & 7) || (p.ldw & 7) || (epi != kEpiBiasHead && (p.ldy & 3)) ||
-        (epi == kEpiEluGrad && (p.ldh & 3)))
-      GMI_FAIL(GMI_ERR_BAD_SHAPE, "launch_linear: bf16 path needs padded dims (K=%d F=%d)", p.K, p.F);
-  }
-  if (epi != kEpiBiasHead && rows >= 8192) {
-    // wide layers: large tiles; choose the tile whose padding waste over the feature range is smallest
-    if (maxF > 128) {
-      const int waste256 = (maxF + 255) / 256 * 256 - maxF, waste128 = (maxF + 127) / 128 * 128 - maxF;
-      if (waste256 <= waste128) return launch_bf16_big<4, 4>(s, epi, rows, b, maxF);
-      return launch_bf16_big<2, 4>(s, epi, rows, b, maxF);
+  switch (variant) {
+    case 5: {
+      dim3 grid((unsigned)(((int64_t)rows * maxF + 255) / 256), 1, b.n);
+      switch (epi) {
+        case kEpiBiasElu: ps.launch(linear_f32_kernel<kEpiBiasElu>, dim3(grid), dim3(256), 0, b, rows); break;
+        case kEpiBiasHead: ps.launch(linear_f32_kernel<kEpiBiasHead>, dim3(grid), dim3(256), 0, b, rows); break;
+        default: ps.launch(linear_f32_kernel<kEpiEluGrad>, dim3(grid), dim3(256), 0, b, rows); break;
+      }
+      GMI_LAUNCH_CHECK();
+      return GMI_OK;
     }
-    if (maxF > 64) return launch_bf16_big<2, 4>(s, epi, rows, b, maxF);
+    case 0: return launch_bf16_big<4, 4>(ps, epi, rows, b, maxF);
+    case 1: return launch_bf16_big<2, 4>(ps, epi, rows, b, maxF);
+    case 2: return launch_bf16_cfg<2, 2, 2, 2>(ps, epi, rows, b, maxF);
+    case 3: return launch_bf16_cfg<1, 4, 2, 2>(ps, epi, rows, b, maxF);
+    default: return launch_bf16_cfg<1, 4, 1, 2>(ps, epi, rows, b, maxF);
   }
-  if (maxF % 128 == 0 || maxF > 256) return launch_bf16_cfg<2, 2, 2, 2>(s, epi, rows, b, maxF);
-  if (maxF % 64 == 0) return launch_bf16_cfg<1, 4, 2, 2>(s, epi, rows, b, maxF);
-  if (maxF <= 96) return launch_bf16_cfg<1, 4, 1, 2>(s, epi, rows, b, maxF);
-  return launch_bf16_cfg<2, 2, 2, 2>(s, epi, rows, b, maxF);
 }
 
 int launch_wgrad(gmi_instance* g, int dtype, int rows, int n_split, int chunk, WgradBatch& b, float* part,
                  int64_t part_stride) {
   if (b.n <= 0) return GMI_OK;
   ProfScope ps(g, kClsWgrad);
-  hipStream_t s = g->stream;
+  {
+    // algorithmic work: 2 in out flops per row; every layer's input and output gradient read once, one
+    // fp32 partial per split written
+    const double es = dtype == GMI_DTYPE_F32 ? 4.0 : 2.0;
+    double fl = 0.0, by = 0.0;
+    for (int i = 0; i < b.n; ++i) {
+      fl += 2.0 * rows * (double)b.p[i].in * b.p[i].out;
+      by += rows * es * (b.p[i].in + b.p[i].out) + 4.0 * n_split * ((double)b.p[i].in * b.p[i].out + b.p[i].out);
+    }
+    ps.work(fl, by);
+  }
   if (dtype == GMI_DTYPE_F32) {
     int maxn = 0;
     for (int i = 0; i < b.n; ++i) {
@@ -649,7 +684,7 @@ int launch_wgrad(gmi_instance* g, int dtype, int rows, int n_split, int chunk, W
       maxn = n > maxn ? n : maxn;
     }
     dim3 grid((maxn + 255) / 256, n_split, b.n);
-    wgrad_f32_kernel<<<grid, 256, 0, s>>>(b, rows, chunk, part, part_stride);
+    ps.launch(wgrad_f32_kernel, dim3(grid), dim3(256), 0, b, rows, chunk, part, part_stride);
     GMI_LAUNCH_CHECK();
     return GMI_OK;
   }
@@ -659,7 +694,7 @@ int launch_wgrad(gmi_instance* g, int dtype, int rows, int n_split, int chunk, W
     total += ((b.p[i].out_pad + 127) / 128) * ((b.p[i].in_pad + 127) / 128) * n_split;
   }
   b.blk_start[b.n] = total;
-  wgrad_bf16_kernel<<<total, 256, 0, s>>>(b, rows, n_split, chunk, part, part_stride);
+  ps.launch(wgrad_bf16_kernel, dim3(total), dim3(256), 0, b, rows, n_split, chunk, part, part_stride);
   GMI_LAUNCH_CHECK();
   return GMI_OK;
 }

@@ -161,18 +161,17 @@ int launch_gather(gmi_instance* g, gmi_model* m, const float* obs, int n_envs, i
                   const int32_t* idx, int rows, const gmi_buffer_desc* ex) {
   if (rows <= 0) return GMI_OK;
   ProfScope ps(g, kClsGather);
-  hipStream_t s = g->stream;
   const int O = m->L.obs_dim, A = m->L.act_dim, o_pad = gmi::pad32(O);
   const int W = o_pad + (ex ? A + 3 : 0);
   const int64_t total = (int64_t)rows * W;
   const unsigned grid = (unsigned)((total + 255) / 256);
   if (m->L.dtype == GMI_DTYPE_BF16)
-    gather_kernel<uint16_t><<<grid, 256, 0, s>>>(obs, n_envs, ld_envs, O, o_pad, idx, rows, (uint16_t*)m->x0, A,
+    ps.launch(gather_kernel<uint16_t>, dim3(grid), dim3(256), 0, obs, n_envs, ld_envs, O, o_pad, idx, rows, (uint16_t*)m->x0, A,
                                                  ex ? ex->act : nullptr, ex ? ex->logp : nullptr,
                                                  ex ? ex->adv : nullptr, ex ? ex->ret : nullptr, m->mb_act,
                                                  m->mb_logp, m->mb_adv, m->mb_ret);
   else
-    gather_kernel<float><<<grid, 256, 0, s>>>(obs, n_envs, ld_envs, O, o_pad, idx, rows, (float*)m->x0, A,
+    ps.launch(gather_kernel<float>, dim3(grid), dim3(256), 0, obs, n_envs, ld_envs, O, o_pad, idx, rows, (float*)m->x0, A,
                                               ex ? ex->act : nullptr, ex ? ex->logp : nullptr,
                                               ex ? ex->adv : nullptr, ex ? ex->ret : nullptr, m->mb_act,
                                               m->mb_logp, m->mb_adv, m->mb_ret);
@@ -203,6 +202,7 @@ int forward_nets(gmi_instance* g, gmi_model* m, int rows, bool policy, bool valu
         p.bias = m->params + li.b_off;
         p.K = li.in; p.F = li.out;
       }
+      p.K_log = li.in; p.F_log = li.out;
       p.h = nullptr; p.ldh = 0;
       if (li.head) {
         p.y = net == 0 ? (void*)mu_dst : (void*)val_dst;
@@ -346,7 +346,7 @@ extern "C" int agent_act(gmi_t g, gmi_model_t m, const float* obs, int32_t n_row
   const float* log_std = m->L.dtype == GMI_DTYPE_BF16 ? reinterpret_cast<const float*>(m->shadow + m->L.sh_logstd)
                                                       : m->params + m->L.logstd_off;
   gmi::ProfScope ps(g, gmi::kClsSample);
-  sample_kernel<<<(n_rows + 127) / 128, 128, 0, g->stream>>>(m->mu, log_std, n_rows, m->L.act_dim, (uint32_t)seed,
+  ps.launch(sample_kernel, dim3((n_rows + 127) / 128), dim3(128), 0, m->mu, log_std, n_rows, m->L.act_dim, (uint32_t)seed,
                                                              (uint32_t)(seed >> 32), step, env_offset, act, logp, mu);
   GMI_LAUNCH_CHECK();
   return GMI_OK;

@@ -279,7 +279,6 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
   const ModelLayout& L = m->L;
   const bool bf = L.dtype == GMI_DTYPE_BF16;
   const int A = L.act_dim;
-  hipStream_t s = g->stream;
   int rc;
   bool fused = false;
   if (g->fusion >= 2 && want_grad) {
@@ -303,12 +302,12 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
   {
   gmi::ProfScope ps(g, gmi::kClsLoss);
   if (bf)
-    loss_kernel<uint16_t><<<nlb, 256, lds, s>>>(rows, A, m->mu, m->val, m->mb_act, m->mb_logp, m->mb_adv, m->mb_ret,
+    ps.launch(loss_kernel<uint16_t>, dim3(nlb), dim3(256), lds, rows, A, m->mu, m->val, m->mb_act, m->mb_logp, m->mb_adv, m->mb_ret,
                                                 log_std, hp->clip, hp->c_v, want_grad ? 1 : 0,
                                                 (uint16_t*)m->dz[0][head], L.net[0][head].out_pad,
                                                 (uint16_t*)m->dz[1][head], L.net[1][head].out_pad, m->stat_part);
   else
-    loss_kernel<float><<<nlb, 256, lds, s>>>(rows, A, m->mu, m->val, m->mb_act, m->mb_logp, m->mb_adv, m->mb_ret,
+    ps.launch(loss_kernel<float>, dim3(nlb), dim3(256), lds, rows, A, m->mu, m->val, m->mb_act, m->mb_logp, m->mb_adv, m->mb_ret,
                                              log_std, hp->clip, hp->c_v, want_grad ? 1 : 0, (float*)m->dz[0][head],
                                              L.net[0][head].out_pad, (float*)m->dz[1][head], L.net[1][head].out_pad,
                                              m->stat_part);
@@ -335,6 +334,7 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
       p.h = m->h[net][l]; p.ldh = li.in_pad;
       p.y = m->dz[net][l - 1]; p.ldy = li.in_pad;
       p.F_store = p.F;
+      p.K_log = li.out; p.F_log = li.in;
     }
     rc = gmi::launch_linear(g, L.dtype, gmi::kEpiEluGrad, rows, lb);
     if (rc != GMI_OK) return rc;
@@ -365,7 +365,6 @@ int launch_adam(gmi_instance* g, gmi_model* m, int n_split, int n_loss_blocks, c
                 uint32_t k, float* stats_out, float* grad_out, bool do_update) {
   const gmi::ShadowTable tab = gmi::make_shadow_table(m->L);
   gmi::ProfScope ps(g, gmi::kClsAdam);
-  hipStream_t s = g->stream;
   // one workgroup per 256 weights / biases plus one for the statistics and log_std
   const unsigned grid = (unsigned)((m->L.logstd_off + 255) / 256) + 1;
   const float* stat = m->stat_part;
@@ -374,7 +373,7 @@ int launch_adam(gmi_instance* g, gmi_model* m, int n_split, int n_loss_blocks, c
     n_loss_blocks = 1;
   }
   const bool bf = m->L.dtype == GMI_DTYPE_BF16;
-  adam_kernel<<<grid, 256, 0, s>>>(tab, bf ? 1 : 0, m->params, m->adam_m, m->adam_v,
+  ps.launch(adam_kernel, dim3(grid), dim3(256), 0, tab, bf ? 1 : 0, m->params, m->adam_m, m->adam_v,
                                    m->grad_part, n_split, m->L.n_params, stat, n_loss_blocks, m->L.act_dim,
                                    hp->c_e, 1.0f / (float)rows, adam_scalars(hp, k), m->shadow, stats_out, grad_out,
                                    do_update ? 1 : 0);
@@ -388,7 +387,8 @@ int launch_adam(gmi_instance* g, gmi_model* m, int n_split, int n_loss_blocks, c
       total += ((tab.l[i].out_pad + 63) / 64) * ((tab.l[i].in_pad + 63) / 64);
     }
     tt.start[tab.n] = total;
-    shadow_transpose_kernel<<<total, 256, 0, s>>>(tab, tt, m->shadow);
+    gmi::ProfScope ps2(g, gmi::kClsShadowTranspose);
+    ps2.launch(shadow_transpose_kernel, dim3(total), dim3(256), 0, tab, tt, m->shadow);
     GMI_LAUNCH_CHECK();
   }
   return GMI_OK;
@@ -482,7 +482,7 @@ extern "C" int adam_update(gmi_t g, float* params, float* adam_m, float* adam_v,
   tab.act_dim = 0;
   tab.n_params = n;
   gmi::ProfScope ps(g, gmi::kClsAdam);
-  adam_kernel<<<(unsigned)((n + 255) / 256) + 1, 256, 0, g->stream>>>(tab, 0, params, adam_m, adam_v, grad, 1, n, nullptr, 0,
+  ps.launch(adam_kernel, dim3((unsigned)((n + 255) / 256) + 1), dim3(256), 0, tab, 0, params, adam_m, adam_v, grad, 1, n, nullptr, 0,
                                                                 0, 0.f, 1.f, adam_scalars(hp, step), nullptr, nullptr,
                                                                 nullptr, 1);
   GMI_LAUNCH_CHECK();
