@@ -26,7 +26,11 @@ PEAK_FP32_TFLOPS = 157.3       # vector fp32
 # HBM bytes per launch (fetch + write) of the kernels that dominate the bench workloads, from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/hbm_traffic_C2_C4.md (counter values
 # scaled by what the same counters read for a copy kernel of known size).  Keyed by (workload, class).
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    ("C2", "wgrad"): 163.63e6, ("C2", "fused_rollout"): 23.37e6, ("C2", "linear_big256_dgrad"): 85.34e6,
+    ("C2", "linear_big256_fwd"): 38.70e6,
+    ("C4", "linear_big256_fwd"): 94.85e6, ("C4", "linear_big256_dgrad"): 155.95e6, ("C4", "wgrad"): 626.66e6,
+}
 
 
 def mac_per_sample(cfg, first_layer=True):
