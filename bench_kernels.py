@@ -43,9 +43,9 @@ def main() -> int:
         g.gmi_profile_enable(h, 1 << names.index(cls))
         for _ in range(reps):
             fn()
-        ms, n = g.gmi_profile_read(h, names.index(cls))
+        ms, _ = g.gmi_profile_read(h, names.index(cls))   # summed kernel time; a call may launch several
         g.gmi_profile_enable(h, 0)
-        return ms / n
+        return ms / reps
 
     rows = []
     # GAE: T x N rewards, values, dones -> advantages, returns (25 B per sample + 4 B per env)
