@@ -99,31 +99,50 @@ __global__ void refresh_shadow_kernel(gmi::ShadowTable tab, const float* __restr
   }
 }
 
-// Gather / convert: one thread per (row, column) of the widened row
-//   [0, o_pad) -> x0 (converted, zero padded);  then act[A], logp, adv, ret if extras are asked for.
-template <typename T>
-__global__ void gather_kernel(const float* __restrict__ obs, int n_envs, int ld_envs, int O, int o_pad,
-                              const int32_t* __restrict__ idx, int rows, T* __restrict__ x0, int A,
-                              const float* __restrict__ b_act, const float* __restrict__ b_logp,
-                              const float* __restrict__ b_adv, const float* __restrict__ b_ret,
-                              float* __restrict__ m_act, float* __restrict__ m_logp, float* __restrict__ m_adv,
-                              float* __restrict__ m_ret) {
-  const int W = o_pad + (b_act ? A + 3 : 0);
-  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (gid >= (int64_t)rows * W) return;
-  const int r = (int)(gid / W), k = (int)(gid % W);
+// Gather / convert: tpr threads share one row.  Each takes 4 consecutive observation columns per pass
+// (one 16-byte load when VEC: obs_dim % 4 == 0 and a 16-byte aligned base), converts them to the model's
+// element type and stores them as one 8- or 16-byte piece of x0 (zero padded to o_pad); the same threads
+// then copy the row's act[A], logp, adv, ret if extras are asked for.
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void gather_kernel(const float* __restrict__ obs, int n_envs, int ld_envs, int O,
+                                                     int o_pad, const int32_t* __restrict__ idx, int rows,
+                                                     T* __restrict__ x0, int A, const float* __restrict__ b_act,
+                                                     const float* __restrict__ b_logp, const float* __restrict__ b_adv,
+                                                     const float* __restrict__ b_ret, float* __restrict__ m_act,
+                                                     float* __restrict__ m_logp, float* __restrict__ m_adv,
+                                                     float* __restrict__ m_ret, int tpr) {
+  const int tr = threadIdx.x / tpr, tc = threadIdx.x - tr * tpr;
+  const int r = blockIdx.x * (256 / tpr) + tr;
+  if (r >= rows) return;
   const int s = idx ? idx[r] : r;
   const int64_t slot = (int64_t)(s / n_envs) * ld_envs + (s % n_envs);
-  if (k < o_pad) {
-    const float v = k < O ? obs[slot * O + k] : 0.f;
-    if constexpr (sizeof(T) == 2) x0[(int64_t)r * o_pad + k] = f_to_bf16_dev(v);
-    else x0[(int64_t)r * o_pad + k] = v;
-  } else {
-    const int j = k - o_pad;
-    if (j < A) m_act[(int64_t)r * A + j] = b_act[slot * A + j];
-    else if (j == A) m_logp[r] = b_logp[slot];
-    else if (j == A + 1) m_adv[r] = b_adv[slot];
-    else m_ret[r] = b_ret[slot];
+  const float* __restrict__ src = obs + slot * O;
+  for (int c = tc * 4; c < o_pad; c += tpr * 4) {
+    float4 v;
+    if (VEC && c + 4 <= O) {
+      v = *reinterpret_cast<const float4*>(src + c);
+    } else {
+      v.x = c + 0 < O ? src[c + 0] : 0.f;
+      v.y = c + 1 < O ? src[c + 1] : 0.f;
+      v.z = c + 2 < O ? src[c + 2] : 0.f;
+      v.w = c + 3 < O ? src[c + 3] : 0.f;
+    }
+    if constexpr (sizeof(T) == 2) {
+      uint2 o;
+      o.x = (uint32_t)f_to_bf16_dev(v.x) | ((uint32_t)f_to_bf16_dev(v.y) << 16);
+      o.y = (uint32_t)f_to_bf16_dev(v.z) | ((uint32_t)f_to_bf16_dev(v.w) << 16);
+      *reinterpret_cast<uint2*>(x0 + (int64_t)r * o_pad + c) = o;
+    } else {
+      *reinterpret_cast<float4*>(x0 + (int64_t)r * o_pad + c) = v;
+    }
+  }
+  if (b_act) {
+    for (int j = tc; j < A + 3; j += tpr) {
+      if (j < A) m_act[(int64_t)r * A + j] = b_act[slot * A + j];
+      else if (j == A) m_logp[r] = b_logp[slot];
+      else if (j == A + 1) m_adv[r] = b_adv[slot];
+      else m_ret[r] = b_ret[slot];
+    }
   }
 }
 
@@ -162,19 +181,23 @@ int launch_gather(gmi_instance* g, gmi_model* m, const float* obs, int n_envs, i
   if (rows <= 0) return GMI_OK;
   ProfScope ps(g, kClsGather);
   const int O = m->L.obs_dim, A = m->L.act_dim, o_pad = gmi::pad32(O);
-  const int W = o_pad + (ex ? A + 3 : 0);
-  const int64_t total = (int64_t)rows * W;
-  const unsigned grid = (unsigned)((total + 255) / 256);
-  if (m->L.dtype == GMI_DTYPE_BF16)
-    ps.launch(gather_kernel<uint16_t>, dim3(grid), dim3(256), 0, obs, n_envs, ld_envs, O, o_pad, idx, rows, (uint16_t*)m->x0, A,
-                                                 ex ? ex->act : nullptr, ex ? ex->logp : nullptr,
-                                                 ex ? ex->adv : nullptr, ex ? ex->ret : nullptr, m->mb_act,
-                                                 m->mb_logp, m->mb_adv, m->mb_ret);
-  else
-    ps.launch(gather_kernel<float>, dim3(grid), dim3(256), 0, obs, n_envs, ld_envs, O, o_pad, idx, rows, (float*)m->x0, A,
-                                              ex ? ex->act : nullptr, ex ? ex->logp : nullptr,
-                                              ex ? ex->adv : nullptr, ex ? ex->ret : nullptr, m->mb_act,
-                                              m->mb_logp, m->mb_adv, m->mb_ret);
+  int tpr = 8;                                   // threads per row: a power of two covering o_pad / 4, at most 64
+  while (tpr < 64 && tpr * 4 < o_pad) tpr <<= 1;
+  const unsigned grid = (unsigned)((rows + 256 / tpr - 1) / (256 / tpr));
+  const bool vec = (O % 4 == 0) && (((uintptr_t)obs & 15) == 0);
+  const float* e_act = ex ? ex->act : nullptr;
+  const float* e_logp = ex ? ex->logp : nullptr;
+  const float* e_adv = ex ? ex->adv : nullptr;
+  const float* e_ret = ex ? ex->ret : nullptr;
+#define GMI_GATHER(T, V)                                                                                     \
+  ps.launch(gather_kernel<T, V>, dim3(grid), dim3(256), 0, obs, n_envs, ld_envs, O, o_pad, idx, rows, (T*)m->x0, A, \
+            e_act, e_logp, e_adv, e_ret, m->mb_act, m->mb_logp, m->mb_adv, m->mb_ret, tpr)
+  if (m->L.dtype == GMI_DTYPE_BF16) {
+    if (vec) GMI_GATHER(uint16_t, true); else GMI_GATHER(uint16_t, false);
+  } else {
+    if (vec) GMI_GATHER(float, true); else GMI_GATHER(float, false);
+  }
+#undef GMI_GATHER
   GMI_LAUNCH_CHECK();
   return GMI_OK;
 }
