@@ -57,7 +57,7 @@ namespace gmi {
 // Kernel classes of the built-in per-launch timer (gmi_profile_*).
 // One class per kernel symbol, so that a class average can be set beside a profiler's per-kernel
 // average.  The linear-layer classes are kClsLinear + 3 * variant + role:
-//   variant 0 linear_bf16_big_kernel<4,4,*> (256x256 tile)   1 linear_bf16_big_kernel<2,4,*> (256x128)
+//   variant 0 linear_bf16_big_kernel<4,2,*,4> (256x256 tile)  1 linear_bf16_big_kernel<2,2,*,4> (256x128)
 //           2 linear_bf16_kernel<2,2,2,2,*> (128x128)         3 linear_bf16_kernel<1,4,2,2,*> (256x64)
 //           4 linear_bf16_kernel<1,4,1,2,*> (128x64)
 //   role    0 forward hidden layer (bias + ELU)   1 forward head   2 input gradient (ELU')

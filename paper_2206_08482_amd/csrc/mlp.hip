@@ -158,9 +158,13 @@ __global__ __launch_bounds__(256) void linear_bf16_kernel(gmi::LinearBatch batch
 }
 
 // ------------------------------------------------------------------------------------------------
-// Large-tile variant for wide layers: workgroup tile (2*TRW*32 rows) x (2*TFW*32 features), 2 x 2 waves,
-// each wave TFW x TRW matrix-core tiles, so one 16-byte LDS fragment feeds TRW (or TFW) MFMAs and LDS
-// bandwidth stays below the matrix cores' appetite.  K is staged 64 at a time (a full 128-byte line per
+// Large-tile variant for wide layers: workgroup tile (WRN*TRW*32 rows) x (2*TFW*32 features), 2 x WRN
+// waves, each wave TFW x TRW matrix-core tiles, so one 16-byte LDS fragment feeds TRW (or TFW) MFMAs and
+// LDS bandwidth stays below the matrix cores' appetite.  The launcher uses 2 x 4 waves of 4 x 2 (or 2 x 2)
+// tiles: two waves per SIMD cover each other's LDS and epilogue latencies, which measured 8-17 % faster
+// than 2 x 2 waves of 4 x 4 tiles on the same 256 x 256 workgroup tile (the epilogue alone - ELU on 256
+// values per lane - took a third of a workgroup's time with one wave per SIMD).
+// K is staged 64 at a time (a full 128-byte line per
 // row) into double-buffered LDS (144-byte row stride: conflict-free 16-byte reads), one barrier per
 // stage.  Two further stages are in flight in registers: the row operand is first-touch data from
 // HBM / the memory-side cache, and with one workgroup per CU only a deep prefetch covers that latency
@@ -169,17 +173,19 @@ __global__ __launch_bounds__(256) void linear_bf16_kernel(gmi::LinearBatch batch
 // lanes (whole 64..256-byte row segments per store).  Workgroup ids are decoded so that the workgroups
 // sharing a row tile run back to back on the same accelerator die (ids are dealt round-robin over the 8
 // dies), which keeps that tile in the die's L2.
-template <int TFW, int TRW, int EPI>
-__global__ __launch_bounds__(256) void linear_bf16_big_kernel(gmi::LinearBatch batch, int rows, int n_rt,
-                                                              int n_rt_pad, int n_ft) {
-  constexpr int TF = 2 * TFW * 32, TR = 2 * TRW * 32;
+template <int TFW, int TRW, int EPI, int WRN>
+__global__ __launch_bounds__(128 * WRN) void linear_bf16_big_kernel(gmi::LinearBatch batch, int rows, int n_rt,
+                                                                    int n_rt_pad, int n_ft) {
+  constexpr int NT = 128 * WRN;                                  // 2 x WRN waves
+  constexpr int TF = 2 * TFW * 32, TR = WRN * TRW * 32;
   constexpr int CH_W = TF * (kBK / 8), CH_X = TR * (kBK / 8);
-  constexpr int NCH = (CH_W + CH_X) / 256;
-  static_assert((CH_W + CH_X) % 256 == 0 && CH_W % 256 == 0, "stage must divide evenly over the threads");
+  constexpr int NCH = (CH_W + CH_X) / NT;
+  constexpr int RPP = NT / 8;                                    // rows staged per pass of the workgroup
+  static_assert((CH_W + CH_X) % NT == 0 && CH_W % NT == 0, "stage must divide evenly over the threads");
   constexpr int kStageElems = (TF + TR) * kLds;                  // bf16 elements of one LDS stage
   constexpr int kOutStride = TFW * 32 + 4;                       // floats per staged output row
   constexpr int kMainBytes = 2 * kStageElems * 2;
-  constexpr int kOutBytes = 4 * 32 * kOutStride * 4;
+  constexpr int kOutBytes = 2 * WRN * 32 * kOutStride * 4;
   constexpr int kSmemBytes = kMainBytes > kOutBytes ? kMainBytes : kOutBytes;
   __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemBytes];
   uint16_t* s_stage = reinterpret_cast<uint16_t*>(smem);
@@ -197,7 +203,7 @@ __global__ __launch_bounds__(256) void linear_bf16_big_kernel(gmi::LinearBatch b
   if (f0 >= P.F) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wf = wave >> 1, wr = wave & 1;
+  const int wf = wave / WRN, wr = wave % WRN;
   const uint16_t* __restrict__ gw = (const uint16_t*)P.w;
   const uint16_t* __restrict__ gx = (const uint16_t*)P.x;
 
@@ -213,14 +219,14 @@ __global__ __launch_bounds__(256) void linear_bf16_big_kernel(gmi::LinearBatch b
   // Loads are unconditional (no branches, so the compiler can keep two stages in flight and wait only for
   // the older one): row indices are clamped into the operand (rows past the end only feed outputs that
   // are never stored) and the k offset is clamped into the row, with a select to zero past K.
-  constexpr int NCW = CH_W / 256, NCX = CH_X / 256;
+  constexpr int NCW = CH_W / NT, NCX = CH_X / NT;
   const int crow = tid >> 3, kc8 = (tid & 7) * 8;
   const uint16_t* src_w[NCW];
   const uint16_t* src_x[NCX];
 #pragma unroll
-  for (int c = 0; c < NCW; ++c) src_w[c] = gw + (int64_t)min(f0 + crow + 32 * c, P.F - 1) * P.ldw;
+  for (int c = 0; c < NCW; ++c) src_w[c] = gw + (int64_t)min(f0 + crow + RPP * c, P.F - 1) * P.ldw;
 #pragma unroll
-  for (int c = 0; c < NCX; ++c) src_x[c] = gx + (int64_t)min(r0 + crow + 32 * c, rows - 1) * P.ldx;
+  for (int c = 0; c < NCX; ++c) src_x[c] = gx + (int64_t)min(r0 + crow + RPP * c, rows - 1) * P.ldx;
   const int dst0 = crow * kLds + kc8;
   const int k_last = P.K - 8;
   uint4 st0[NCH], st1[NCH];
@@ -239,9 +245,9 @@ __global__ __launch_bounds__(256) void linear_bf16_big_kernel(gmi::LinearBatch b
   auto store_stage = [&](const uint4* st, int buf) {
     uint16_t* base = s_stage + buf * kStageElems + dst0;
 #pragma unroll
-    for (int c = 0; c < NCW; ++c) *reinterpret_cast<uint4*>(base + c * 32 * kLds) = st[c];
+    for (int c = 0; c < NCW; ++c) *reinterpret_cast<uint4*>(base + c * RPP * kLds) = st[c];
 #pragma unroll
-    for (int c = 0; c < NCX; ++c) *reinterpret_cast<uint4*>(base + (TF + c * 32) * kLds) = st[NCW + c];
+    for (int c = 0; c < NCX; ++c) *reinterpret_cast<uint4*>(base + (TF + c * RPP) * kLds) = st[NCW + c];
   };
   auto compute = [&](int buf) {
     const uint16_t* sw = s_stage + buf * kStageElems;
@@ -566,16 +572,18 @@ __global__ void wgrad_f32_kernel(gmi::WgradBatch batch, int rows, int chunk, flo
   }
 }
 
-template <int TFW, int TRW>
+template <int TFW, int TRW, int WRN>
 int launch_bf16_big(gmi::ProfScope& ps, int epi, int rows, const gmi::LinearBatch& b, int maxF) {
-  constexpr int TF = 2 * TFW * 32, TR = 2 * TRW * 32;
+  constexpr int TF = 2 * TFW * 32, TR = WRN * TRW * 32;
   const int n_rt = (rows + TR - 1) / TR, n_ft = (maxF + TF - 1) / TF;
   const int n_rt_pad = (n_rt + 7) & ~7;
   const unsigned grid = (unsigned)(n_rt_pad * n_ft * b.n);
   if (epi == gmi::kEpiBiasElu)
-    ps.launch(linear_bf16_big_kernel<TFW, TRW, gmi::kEpiBiasElu>, dim3(grid), dim3(256), 0, b, rows, n_rt, n_rt_pad, n_ft);
+    ps.launch(linear_bf16_big_kernel<TFW, TRW, gmi::kEpiBiasElu, WRN>, dim3(grid), dim3(128 * WRN), 0, b, rows, n_rt,
+              n_rt_pad, n_ft);
   else
-    ps.launch(linear_bf16_big_kernel<TFW, TRW, gmi::kEpiEluGrad>, dim3(grid), dim3(256), 0, b, rows, n_rt, n_rt_pad, n_ft);
+    ps.launch(linear_bf16_big_kernel<TFW, TRW, gmi::kEpiEluGrad, WRN>, dim3(grid), dim3(128 * WRN), 0, b, rows, n_rt,
+              n_rt_pad, n_ft);
   GMI_LAUNCH_CHECK();
   return GMI_OK;
 }
@@ -654,8 +662,8 @@ int launch_linear(gmi_instance* g, int dtype, int epi, int rows, const LinearBat
       GMI_LAUNCH_CHECK();
       return GMI_OK;
     }
-    case 0: return launch_bf16_big<4, 4>(ps, epi, rows, b, maxF);
-    case 1: return launch_bf16_big<2, 4>(ps, epi, rows, b, maxF);
+    case 0: return launch_bf16_big<4, 2, 4>(ps, epi, rows, b, maxF);
+    case 1: return launch_bf16_big<2, 2, 4>(ps, epi, rows, b, maxF);
     case 2: return launch_bf16_cfg<2, 2, 2, 2>(ps, epi, rows, b, maxF);
     case 3: return launch_bf16_cfg<1, 4, 2, 2>(ps, epi, rows, b, maxF);
     default: return launch_bf16_cfg<1, 4, 1, 2>(ps, epi, rows, b, maxF);
