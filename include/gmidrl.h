@@ -265,6 +265,31 @@ int gmi_permutation(gmi_t gmi, int32_t n, uint64_t seed, uint32_t iteration, uin
 
 /* ------------------------------------------------------------------ per-launch timing ------- */
 
+/* ------------------------------------------------------------------ instance selection ------ */
+
+/* Trial run of one point of the search: instances per GPU and environments per instance in; runnable
+ * (0/1), throughput of ONE instance and its memory footprint out (any consistent units).  Non-zero return
+ * aborts the search with an error.  user: the pointer given to gmi_explore. */
+typedef int (*gmi_profile_fn)(int32_t gmi_per_gpu, int32_t num_env, int32_t* runnable, double* throughput,
+                              double* memory, void* user);
+/* Projection of one instance's throughput to the whole system. */
+typedef double (*gmi_estimate_fn)(int32_t gmi_per_gpu, int32_t num_gpu, double throughput, void* user);
+
+/* Profiling-based instance exploration (Algorithm 2, Section 5.3 "Workload-aware GMI Selection").
+ * For each instances-per-GPU value (in the order given; the paper walks 10 .. 1) the environments-per-
+ * instance values are profiled in the order given (the paper: 128, 256, .. 16384).  Non-runnable points are
+ * skipped; the first runnable point of an instance size only initialises the trackers; for every later one
+ *   R_top = (top - pre_top) / pre_top,  R_mem = (mem - pre_mem) / pre_mem,  Sat = R_top / R_mem
+ * (IEEE divisions), the trackers move to this point, Sat < alpha ends this instance size, otherwise the
+ * point is projected with estimate() and kept if it beats every earlier projection (strictly).
+ * estimate == NULL: throughput * gmi_per_gpu * num_gpu.  All pointers host.  Outputs: the chosen pair
+ * (0, 0 if no point was ever recorded) and, if projected != NULL, its projection.  Host-only: no GPU work
+ * happens inside this call except what the callbacks do. */
+int gmi_explore(gmi_profile_fn profile, void* profile_user, gmi_estimate_fn estimate, void* estimate_user,
+                int32_t num_gpu, double alpha, const int32_t* gmi_per_gpu_values, int32_t n_gmi,
+                const int32_t* num_env_values, int32_t n_env, int32_t* num_env_out, int32_t* gmi_per_gpu_out,
+                double* projected);
+
 /* Built-in timer for measurement runs (the paper's profile() step of Algorithm 2 measures a trial
  * run; here the unit is one kernel class = one kernel symbol).  class_mask bit c = 1: every launch of
  * kernel class c on this instance carries a pair of HIP events on the instance's stream that receive the

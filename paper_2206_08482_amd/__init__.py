@@ -25,8 +25,13 @@ EXPORTS = [
     "agent_act", "agent_value", "gmi_buffer_bind", "gmi_buffer_destroy", "collect_experience",
     "gae_compute", "ppo_update", "ppo_evaluate", "ppo_gradient", "adam_update", "gmi_noise_fill",
     "gmi_permutation", "gmi_profile_enable", "gmi_profile_classes", "gmi_profile_class_name", "gmi_profile_read",
-    "gmi_measure_peak", "gmi_bench_linear", "gmi_set_fusion", "rollout_collect", "gmi_profile_work",
+    "gmi_measure_peak", "gmi_bench_linear", "gmi_set_fusion", "rollout_collect", "gmi_profile_work", "gmi_explore",
 ]
+
+
+PROFILE_FN = C.CFUNCTYPE(C.c_int, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_double),
+                        C.POINTER(C.c_double), C.c_void_p)
+ESTIMATE_FN = C.CFUNCTYPE(C.c_double, C.c_int32, C.c_int32, C.c_double, C.c_void_p)
 
 
 class GmiError(RuntimeError):
@@ -100,6 +105,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "gmi_profile_class_name": (C.c_char_p, [C.c_int]),
         "gmi_profile_read": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]),
         "gmi_set_fusion": (C.c_int, [vp, C.c_int]),
+        "gmi_explore": (C.c_int, [PROFILE_FN, vp, ESTIMATE_FN, vp, i32, C.c_double, C.POINTER(i32), i32,
+                                  C.POINTER(i32), i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_double)]),
         "gmi_profile_work": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "gmi_measure_peak": (C.c_int, [vp, C.c_int, vp, C.c_size_t, C.POINTER(C.c_double)]),
         "gmi_bench_linear": (C.c_int, [vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_size_t,
@@ -348,6 +355,39 @@ def gmi_profile_work(gmi: int, cls: int):
     fl, by = C.c_double(), C.c_double()
     _check(_lib.gmi_profile_work(gmi, cls, C.byref(fl), C.byref(by)))
     return fl.value, by.value
+
+
+def gmi_explore(profile, num_gpu: int, alpha: float, gmi_per_gpu_values, num_env_values, estimate=None):
+    """Algorithm 2 through the C ABI.  profile(gmi_per_gpu, num_env) -> (runnable, throughput, memory);
+    estimate(gmi_per_gpu, num_gpu, throughput) -> projected throughput (None: the library's default).
+    Returns (num_env, gmi_per_gpu, projected) or None if no point was recorded."""
+    failure = []
+
+    def _profile(k, n, runnable, top, mem, _user):
+        try:
+            r, t, m = profile(int(k), int(n))
+            runnable[0], top[0], mem[0] = (1 if r else 0), float(t), float(m)
+            return 0
+        except Exception as e:           # an exception cannot cross the C frame: report it afterwards
+            failure.append(e)
+            return 1
+
+    def _estimate(k, g, top, _user):
+        return float(estimate(int(k), int(g), float(top)))
+
+    cb_p = PROFILE_FN(_profile)
+    cb_e = ESTIMATE_FN(_estimate) if estimate is not None else C.cast(None, ESTIMATE_FN)
+    ks = (C.c_int32 * len(gmi_per_gpu_values))(*gmi_per_gpu_values)
+    ns = (C.c_int32 * len(num_env_values))(*num_env_values)
+    out_n, out_k, out_p = C.c_int32(), C.c_int32(), C.c_double()
+    rc = _lib.gmi_explore(cb_p, None, cb_e, None, num_gpu, alpha, ks, len(gmi_per_gpu_values), ns,
+                          len(num_env_values), C.byref(out_n), C.byref(out_k), C.byref(out_p))
+    if failure:
+        raise failure[0]
+    _check(rc)
+    if out_n.value == 0 and out_k.value == 0:
+        return None
+    return out_n.value, out_k.value, out_p.value
 
 
 def dtype_code(name: str) -> int:

@@ -145,3 +145,44 @@ def test_sync_schedule_bf16_runs_and_stays_close():
     assert torch.equal(pipe.shadow[0], pipe.shadow[1])
     assert torch.isfinite(pipe.theta).all().item()
     pipe.close()
+
+
+def test_instance_exploration_on_real_trial_runs():
+    """Algorithm 2 with profile() = real PPO iterations on CU-masked holistic instances: every point of a
+    small grid runs, throughput and memory are positive, and the pair the library returns is the one the
+    oracle picks from the very same measurements (replayed as a table)."""
+    import paper_2206_08482_amd as g
+    from gpu_util import make_session, oracle_pieces
+    from oracle import selection as osel
+    from paper_2206_08482_amd.selection import InstanceProfiler, cus_per_instance
+
+    cfg = syn.get_config("C2")
+    shape, theta, env, _, hp = oracle_pieces(cfg, n_envs=64)
+
+    def build(num_env, cu_mask):
+        from paper_2206_08482_amd.runner import PPOSession
+        state0 = syn.make_initial_state(num_env, cfg.obs_dim, cfg.seed)
+        return PPOSession(n_envs=num_env, obs_dim=cfg.obs_dim, act_dim=cfg.act_dim, hidden=cfg.hidden, horizon=4,
+                          dtype="bf16", theta=theta, a_mat=env.a_mat, b_mat=env.b_mat, state0=state0,
+                          noise_std=env.noise_std, reward_scale=env.reward_scale, done_period=env.done_period,
+                          done_threshold=env.done_threshold, seed=env.seed, minibatch=2 * num_env, cu_mask=cu_mask)
+
+    def step(ses, it):
+        ses.rollout(it)
+        ses.gae(cfg.gamma, cfg.lam, True)
+        ses.update(it, epochs=1, minibatch=2 * ses.N, clip=cfg.clip, c_v=cfg.c_v, c_e=cfg.c_e, lr=cfg.lr)
+
+    prof = InstanceProfiler(build, step, lambda n: 4 * n, iterations=2)
+    ks, ns = [4, 3, 1], [128, 256, 512]
+    assert [cus_per_instance(prof.device_cus, k) for k in ks] == [prof.device_cus // 4, prof.device_cus // 3 // 8 * 8,
+                                                                 prof.device_cus]
+    got = g.gmi_explore(prof, 1, -1.0, ks, ns)            # alpha < any Sat with growing throughput: no early stop
+    assert len(prof.log) == 9 and all(r["runnable"] for r in prof.log), prof.log
+    assert all(r["samples_per_s"] > 0 and r["bytes"] >= 0 for r in prof.log)
+    table = {(r["gmi_per_gpu"], r["num_env"]): (True, r["samples_per_s"], r["bytes"]) for r in prof.log}
+    ref = osel.explore(lambda k, n: table[(k, n)], lambda k, gpus, top: top * k * gpus, 1, -1.0, ks, ns)
+    assert (got is None and ref is None) or got[:2] == ref
+    # a point that cannot run (fewer than one CU per die for each instance) is reported as not runnable
+    prof2 = InstanceProfiler(build, step, lambda n: 4 * n, iterations=1)
+    assert prof2(prof.device_cus, 128) == (False, 0.0, 0.0)
+    assert prof2.log[-1]["runnable"] is False
