@@ -365,6 +365,41 @@ def ppo_update(theta, m, v, k0: int, shape: ModelShape, buf: dict, hp: PPOHyper,
     return theta, m, v, k, np.stack(stats)
 
 
+def ppo_update_group(theta, m, v, k0: int, shape: ModelShape, bufs, hp: PPOHyper, seed: int,
+                     iteration: int, dtype=np.float32):
+    """Synchronized training of several trainer instances that hold replicas of one model (Section 4.1:
+    the replicas' gradients are reduced so that every replica applies the same update; with the instances
+    of one GPU sharing an address space the reduction is a plain in-memory mean).
+
+    Instance i owns buffer bufs[i] (all of the same size) and shuffles it with its own permutation, keyed
+    by seed + i.  Minibatch j of an epoch is the union of the instances' j-th slices of ``hp.minibatch``
+    samples each; its gradient is the mean of the instances' minibatch-mean gradients, followed by one
+    Adam step on the shared parameters.  Statistics are the mean over the instances.
+    Returns (theta, m, v, k, stats[epochs * n_minibatches, 5])."""
+    flats = [flatten_buffer(b) for b in bufs]
+    B = flats[0]["logp"].shape[0]
+    assert all(f["logp"].shape[0] == B for f in flats) and B % hp.minibatch == 0
+    n = len(flats)
+    nmb = B // hp.minibatch
+    stats = []
+    k = k0
+    for e in range(hp.epochs):
+        perms = [px.feistel_permutation(B, seed + i, iteration, e) for i in range(n)]
+        for j in range(nmb):
+            g_sum = None
+            st_sum = np.zeros(5, np.float64)
+            for i, f in enumerate(flats):
+                idx = perms[i][j * hp.minibatch:(j + 1) * hp.minibatch]
+                st, g = ppo_loss_and_grad(theta, shape, f["obs"][idx], f["act"][idx], f["logp"][idx],
+                                          f["adv"][idx], f["ret"][idx], hp, dtype)
+                g_sum = g.astype(np.float64) if g_sum is None else g_sum + g
+                st_sum += st
+            k += 1
+            theta, m, v = adam_step(theta, m, v, (g_sum / n).astype(dtype), k, hp, dtype)
+            stats.append((st_sum / n).astype(dtype))
+    return theta, m, v, k, np.stack(stats)
+
+
 def ppo_iteration(theta, m, v, k0, shape: ModelShape, env: EnvSpec, state, episode_step,
                   T: int, hp: PPOHyper, gamma: float, lam: float, seed: int, iteration: int,
                   normalize: bool = True, dtype=np.float32):

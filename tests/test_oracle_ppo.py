@@ -449,3 +449,86 @@ def test_whole_iteration_on_c1_is_deterministic_and_learns_something():
     # value loss goes down over the four minibatch steps of one epoch on average
     assert out1["k"] == 4 and out1["stats"].shape == (4, 5)
     assert np.isfinite(out1["stats"]).all()
+
+
+# ----------------------------------------------------------------------------- several trainer instances
+def _random_buffer(rng, T, N, O, A):
+    b = ppo.new_buffer(T, N, O, A, np.float64)
+    b["obs"] = rng.standard_normal((T, N, O))
+    b["act"] = rng.standard_normal((T, N, A))
+    b["logp"] = -0.5 * (b["act"] ** 2).sum(-1) - A * 0.9189385332 + 0.05 * rng.standard_normal((T, N))
+    b["adv"] = rng.standard_normal((T, N))
+    b["ret"] = rng.standard_normal((T, N))
+    return b
+
+
+def test_group_update_of_one_instance_is_the_plain_update():
+    rng = np.random.default_rng(11)
+    shape = ppo.ModelShape(5, 2, (8, 6))
+    theta = syn.make_model_params(5, 2, (8, 6), 3).astype(np.float64)
+    buf = _random_buffer(rng, 4, 8, 5, 2)
+    hp = ppo.PPOHyper(epochs=2, minibatch=16, c_e=0.01)
+    z = np.zeros_like(theta)
+    a = ppo.ppo_update(theta, z, z, 0, shape, buf, hp, 7, 3, np.float64)
+    b = ppo.ppo_update_group(theta, z, z, 0, shape, [buf], hp, 7, 3, np.float64)
+    for x, y in zip(a, b):
+        assert np.array_equal(np.asarray(x), np.asarray(y))
+
+
+def test_group_step_is_the_step_on_the_union_minibatch():
+    """Mean of the instances' minibatch-mean gradients = gradient of the mean loss over the union of their
+    (equally sized) slices.  With one minibatch per buffer the union is all rows of all buffers, whatever
+    the shuffles: the group's single Adam step must equal the step computed by ppo_loss_and_grad on the
+    concatenated rows (a wrong 1/n, a sum instead of a mean, or per-instance Adam steps all fail this)."""
+    rng = np.random.default_rng(5)
+    O, A = 6, 3
+    shape = ppo.ModelShape(O, A, (7,))
+    theta = syn.make_model_params(O, A, (7,), 1).astype(np.float64)
+    bufs = [_random_buffer(rng, 2, 4, O, A) for _ in range(3)]
+    hp = ppo.PPOHyper(epochs=1, minibatch=8, c_e=0.02, lr=1e-3)
+    z = np.zeros_like(theta)
+    th, m, v, k, stats = ppo.ppo_update_group(theta, z, z, 0, shape, bufs, hp, 21, 0, np.float64)
+    assert k == 1 and stats.shape == (1, 5)
+    cat = {key: np.concatenate([ppo.flatten_buffer(b)[key] for b in bufs]) for key in ("obs", "act", "logp", "adv", "ret")}
+    st, g = ppo.ppo_loss_and_grad(theta, shape, cat["obs"], cat["act"], cat["logp"], cat["adv"], cat["ret"], hp,
+                                  np.float64)
+    th1, m1, v1 = ppo.adam_step(theta, z, z, g, 1, hp, np.float64)
+    assert np.allclose(stats[0], st, rtol=1e-12, atol=1e-14)
+    assert np.allclose(m, m1, rtol=1e-10, atol=1e-18) and np.allclose(v, v1, rtol=1e-10, atol=1e-30)
+    assert np.allclose(th, th1, rtol=1e-12, atol=1e-15)
+    assert np.abs(th - theta).max() > 1e-4
+    # replicas holding identical data: the group step equals the single-instance step
+    a = ppo.ppo_update_group(theta, z, z, 0, shape, [bufs[0], bufs[0]], hp, 21, 0, np.float64)
+    b = ppo.ppo_update(theta, z, z, 0, shape, bufs[0], hp, 21, 0, np.float64)
+    assert np.allclose(a[0], b[0], rtol=1e-12, atol=1e-15)
+
+
+def test_group_instances_shuffle_with_their_own_keys():
+    # two epochs of two minibatches: instance i must use the permutation of seed + i (same key for all
+    # instances, or a shared permutation, changes which rows meet in a minibatch and so the result)
+    rng = np.random.default_rng(9)
+    O, A = 4, 2
+    shape = ppo.ModelShape(O, A, (5,))
+    theta = syn.make_model_params(O, A, (5,), 2).astype(np.float64)
+    bufs = [_random_buffer(rng, 2, 8, O, A) for _ in range(2)]
+    hp = ppo.PPOHyper(epochs=2, minibatch=8, lr=1e-3)
+    z = np.zeros_like(theta)
+    th, m, v, k, stats = ppo.ppo_update_group(theta, z, z, 0, shape, bufs, hp, 40, 2, np.float64)
+    assert k == 4
+    # replay by hand
+    t2, m2, v2, kk = theta, z, z, 0
+    flats = [ppo.flatten_buffer(b) for b in bufs]
+    for e in range(2):
+        perms = [px.feistel_permutation(16, 40 + i, 2, e) for i in range(2)]
+        for j in range(2):
+            gs = []
+            for i in range(2):
+                idx = perms[i][8 * j:8 * j + 8]
+                f = flats[i]
+                gs.append(ppo.ppo_loss_and_grad(t2, shape, f["obs"][idx], f["act"][idx], f["logp"][idx], f["adv"][idx],
+                                                f["ret"][idx], hp, np.float64)[1])
+            kk += 1
+            t2, m2, v2 = ppo.adam_step(t2, m2, v2, 0.5 * (gs[0] + gs[1]), kk, hp, np.float64)
+    assert np.allclose(th, t2, rtol=1e-12, atol=1e-15)
+    wrong = [px.feistel_permutation(16, 40, 2, 0), px.feistel_permutation(16, 41, 2, 0)]
+    assert not np.array_equal(wrong[0], wrong[1])
