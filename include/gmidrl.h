@@ -238,6 +238,20 @@ typedef struct {
 int ppo_update(gmi_t gmi, gmi_model_t model, gmi_buffer_t buf, const gmi_ppo_hparams* hp,
                float* stats_out);
 
+/* Synchronized training of n trainer instances that hold replicas of one model on one GPU (Section 4.1:
+ * the replicas' gradients are reduced so that all apply the same update; instances that share an address
+ * space need no ring or tree, only an in-memory mean).  models[i] are bindings on instance i of the SAME
+ * params / shadow / adam_m / adam_v arrays (each with its own workspace), bufs[i] instance i's experience
+ * (all of one size).  Per epoch instance i shuffles its buffer with the key seed + i; minibatch j is the
+ * union of the instances' j-th slices of hp->minibatch samples; every instance runs forward / loss /
+ * backward of its slice on its own stream, instance 0 then sums all partials (fixed order), divides by n,
+ * takes the Adam step and refreshes the shared shadow, and the others wait for it before their next slice.
+ * stats_out dev fp32 [epochs * (T*N/minibatch), 5]: means over the instances; may be NULL.
+ * host: the three handle arrays.  n = 1 is ppo_update.  At most 16 instances; the row-tile fused trainer
+ * is not used here. */
+int ppo_update_group(const gmi_t* gmis, const gmi_model_t* models, const gmi_buffer_t* bufs, int32_t n,
+                     const gmi_ppo_hparams* hp, float* stats_out);
+
 /* Loss statistics of one minibatch given by explicit sample indices, without updating anything
  * (forward + loss only).  idx dev i32 [n]; stats_out dev fp32 [5]. */
 int ppo_evaluate(gmi_t gmi, gmi_model_t model, gmi_buffer_t buf, const gmi_ppo_hparams* hp,

@@ -25,7 +25,7 @@ EXPORTS = [
     "agent_act", "agent_value", "gmi_buffer_bind", "gmi_buffer_destroy", "collect_experience",
     "gae_compute", "ppo_update", "ppo_evaluate", "ppo_gradient", "adam_update", "gmi_noise_fill",
     "gmi_permutation", "gmi_profile_enable", "gmi_profile_classes", "gmi_profile_class_name", "gmi_profile_read",
-    "gmi_measure_peak", "gmi_bench_linear", "gmi_set_fusion", "rollout_collect", "gmi_profile_work", "gmi_explore",
+    "gmi_measure_peak", "gmi_bench_linear", "gmi_set_fusion", "rollout_collect", "gmi_profile_work", "gmi_explore", "ppo_update_group",
 ]
 
 
@@ -95,6 +95,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "rollout_collect": (C.c_int, [vp, vp, vp, vp, vp, u64, u32, u32, vp]),
         "gae_compute": (C.c_int, [vp, vp, vp, f32, f32, C.c_int]),
         "ppo_update": (C.c_int, [vp, vp, vp, C.POINTER(PPOHparams), vp]),
+        "ppo_update_group": (C.c_int, [C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), i32, C.POINTER(PPOHparams), vp]),
         "ppo_evaluate": (C.c_int, [vp, vp, vp, C.POINTER(PPOHparams), vp, i32, vp]),
         "ppo_gradient": (C.c_int, [vp, vp, vp, C.POINTER(PPOHparams), vp, i32, vp, vp]),
         "adam_update": (C.c_int, [vp, vp, vp, vp, vp, i64, C.POINTER(PPOHparams), u32]),
@@ -306,6 +307,13 @@ def ppo_hparams(clip=0.2, c_v=0.5, c_e=0.0, lr=3e-4, beta1=0.9, beta2=0.999, ada
 
 def ppo_update(gmi: int, model: int, buf: int, hp: PPOHparams, stats_out=None) -> None:
     _check(_lib.ppo_update(gmi, model, buf, C.byref(hp), _ptr(stats_out)))
+
+
+def ppo_update_group(gmis, models, bufs, hp: PPOHparams, stats_out=None) -> None:
+    n = len(gmis)
+    assert len(models) == n and len(bufs) == n
+    arr = lambda xs: (C.c_void_p * n)(*xs)
+    _check(_lib.ppo_update_group(arr(gmis), arr(models), arr(bufs), n, C.byref(hp), _ptr(stats_out)))
 
 
 def ppo_evaluate(gmi: int, model: int, buf: int, hp: PPOHparams, idx, n: int, stats_out) -> None:

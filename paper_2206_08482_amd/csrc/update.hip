@@ -116,17 +116,28 @@ __device__ __forceinline__ float adam_one(float g, float* __restrict__ params, f
   return w;
 }
 
+// Gradient partials of the trainer instances whose replicas are reduced into one update (one entry for an
+// ordinary single-instance update): per instance [n_split, part_stride] weight partials and the loss
+// kernel's [n_loss_blocks, kStatStride + A] statistics partials.
+constexpr int kMaxGroup = 16;
+struct PartSet {
+  int n;
+  const float* part[kMaxGroup];
+  const float* stat[kMaxGroup];
+};
+
 // One thread per weight / bias: reduce the gradient partials, Adam, and (BF16) refresh the bias and the
 // [out_pad, in_pad] weight shadow (the transposed shadow is rebuilt by shadow_transpose_kernel).
-// grad(p) = sum_s part[s * part_stride + p].
+// grad(p) = (1/n) sum_i sum_s part_i[s * part_stride + p]: the in-memory mean over the n replicas
+// (Section 4.1's gradient reduction for instances that share one address space), fixed summation order.
 // The last workgroup instead finalises the minibatch statistics and owns log_std, whose gradient is the sum
 // of the loss kernel's per-workgroup partials minus the entropy coefficient; it reduces the
 // [n_loss_blocks, kStatStride + A] partials cooperatively (a serial walk by one thread per column costs
 // one memory round trip per loss workgroup).
 __global__ __launch_bounds__(256) void adam_kernel(gmi::ShadowTable tab, int write_shadow, float* __restrict__ params,
                                                    float* __restrict__ am, float* __restrict__ av,
-                                                   const float* __restrict__ part, int n_split, int64_t part_stride,
-                                                   const float* __restrict__ stat_part, int n_loss_blocks, int A,
+                                                   PartSet ps, int n_split, int64_t part_stride,
+                                                   int n_loss_blocks, int A,
                                                    float c_e, float inv_rows, AdamScalars hs, char* __restrict__ shadow,
                                                    float* __restrict__ stats_out, float* __restrict__ grad_out,
                                                    int do_update) {
@@ -137,25 +148,29 @@ __global__ __launch_bounds__(256) void adam_kernel(gmi::ShadowTable tab, int wri
     // up to 256 columns per pass; narrow rows are walked by 256 / C row groups in parallel
     const int width = C < 256 ? C : 256;
     const int groups = 256 / width;
+    const bool have_stat = ps.stat[0] != nullptr;
+    const float inv_n = 1.0f / (float)ps.n;
     for (int cbase = 0; cbase < C; cbase += 256) {
       const int col = cbase + tid % width, grp = tid / width;
       float s = 0.f;
-      if (stat_part && grp < groups && col < C)
-        for (int b = grp; b < n_loss_blocks; b += groups) s += stat_part[(int64_t)b * C + col];
+      if (have_stat && grp < groups && col < C)
+        for (int i = 0; i < ps.n; ++i)
+          for (int b = grp; b < n_loss_blocks; b += groups) s += ps.stat[i][(int64_t)b * C + col];
       s_col[tid] = s;
       __syncthreads();
       const int c = cbase + tid;
       if (tid < width && c < C) {
         float t = 0.f;
         for (int q = 0; q < groups; ++q) t += s_col[q * width + tid];
-        if (stat_part && stats_out && c < 5) stats_out[c] = c == 2 ? t : t * inv_rows;
+        t *= inv_n;                                   // mean over the replicas (exact for one)
+        if (have_stat && stats_out && c < 5) stats_out[c] = c == 2 ? t : t * inv_rows;
         if (c >= gmi::kStatStride) {
           const int j = c - gmi::kStatStride;
           const int64_t p = tab.logstd_off + j;
           // without loss partials (a caller-supplied gradient) log_std takes the split sums like any weight
           float g = 0.f;
-          if (stat_part) g = t - c_e;
-          else for (int q = 0; q < n_split; ++q) g += part[(int64_t)q * part_stride + p];
+          if (have_stat) g = t - c_e;
+          else for (int q = 0; q < n_split; ++q) g += ps.part[0][(int64_t)q * part_stride + p];
           if (grad_out) grad_out[p] = g;
           if (do_update) {
             const float w = adam_one(g, params, am, av, p, hs);
@@ -170,8 +185,8 @@ __global__ __launch_bounds__(256) void adam_kernel(gmi::ShadowTable tab, int wri
   const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (p >= tab.logstd_off) return;
   float g = 0.f;
-  {
-    const float* q = part + p;
+  for (int i = 0; i < ps.n; ++i) {
+    const float* q = ps.part[i] + p;
     int sidx = 0;
     for (; sidx + 8 <= n_split; sidx += 8) {
       float t[8];
@@ -182,6 +197,7 @@ __global__ __launch_bounds__(256) void adam_kernel(gmi::ShadowTable tab, int wri
     }
     for (; sidx < n_split; ++sidx) g += q[(int64_t)sidx * part_stride];
   }
+  g *= 1.0f / (float)ps.n;
   if (grad_out) grad_out[p] = g;
   if (!do_update) return;
   const float w = adam_one(g, params, am, av, p, hs);
@@ -275,13 +291,13 @@ int check_model_buffer(const char* fn, gmi_model_t m, gmi_buffer_t b) {
 // Forward + loss (+ backward products) of the `rows` samples idx[0..rows) of the buffer.
 // Leaves gradient partials in m->grad_part / m->stat_part.  Returns the split count through n_split.
 int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx,
-                   int rows, bool want_grad, int* n_split_out, int* n_loss_blocks_out) {
+                   int rows, bool want_grad, int* n_split_out, int* n_loss_blocks_out, bool allow_fused = true) {
   const ModelLayout& L = m->L;
   const bool bf = L.dtype == GMI_DTYPE_BF16;
   const int A = L.act_dim;
   int rc;
   bool fused = false;
-  if (g->fusion >= 2 && want_grad) {
+  if (g->fusion >= 2 && want_grad && allow_fused) {
     rc = gmi::launch_train_fused(g, m, b, hp, idx, rows);
     if (rc == GMI_OK) fused = true;
     else if (rc != GMI_ERR_UNSUPPORTED) return rc;
@@ -361,22 +377,29 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
   return gmi::launch_wgrad(g, L.dtype, rows, n_split, chunk, wb, m->grad_part, L.n_params);
 }
 
-int launch_adam(gmi_instance* g, gmi_model* m, int n_split, int n_loss_blocks, const gmi_ppo_hparams* hp, int rows,
-                uint32_t k, float* stats_out, float* grad_out, bool do_update) {
+// Reduces the partials of the n bindings ms[0..n) (replicas of one model: same parameter arrays, own
+// workspaces) and applies one Adam step through ms[0]; launched on instance g.
+int launch_adam(gmi_instance* g, gmi_model* const* ms, int n, int n_split, int n_loss_blocks,
+                const gmi_ppo_hparams* hp, int rows, uint32_t k, float* stats_out, float* grad_out, bool do_update) {
+  gmi_model* m = ms[0];
   const gmi::ShadowTable tab = gmi::make_shadow_table(m->L);
   gmi::ProfScope ps(g, gmi::kClsAdam);
   // one workgroup per 256 weights / biases plus one for the statistics and log_std
   const unsigned grid = (unsigned)((m->L.logstd_off + 255) / 256) + 1;
-  const float* stat = m->stat_part;
-  if (n_loss_blocks < 0) {
-    stat = m->stat_part + (int64_t)gmi::kLossBlocksMax * (gmi::kStatStride + m->L.act_dim);
+  PartSet set;
+  set.n = n;
+  for (int i = 0; i < kMaxGroup; ++i) {
+    set.part[i] = i < n ? ms[i]->grad_part : nullptr;
+    set.stat[i] = i < n ? ms[i]->stat_part : nullptr;
+  }
+  if (n_loss_blocks < 0) {      // fused trainer (single instance): statistics already summed into one row
+    set.stat[0] = m->stat_part + (int64_t)gmi::kLossBlocksMax * (gmi::kStatStride + m->L.act_dim);
     n_loss_blocks = 1;
   }
   const bool bf = m->L.dtype == GMI_DTYPE_BF16;
-  ps.launch(adam_kernel, dim3(grid), dim3(256), 0, tab, bf ? 1 : 0, m->params, m->adam_m, m->adam_v,
-                                   m->grad_part, n_split, m->L.n_params, stat, n_loss_blocks, m->L.act_dim,
-                                   hp->c_e, 1.0f / (float)rows, adam_scalars(hp, k), m->shadow, stats_out, grad_out,
-                                   do_update ? 1 : 0);
+  ps.launch(adam_kernel, dim3(grid), dim3(256), 0, tab, bf ? 1 : 0, m->params, m->adam_m, m->adam_v, set, n_split,
+            m->L.n_params, n_loss_blocks, m->L.act_dim, hp->c_e, 1.0f / (float)rows, adam_scalars(hp, k), m->shadow,
+            stats_out, grad_out, do_update ? 1 : 0);
   GMI_LAUNCH_CHECK();
   if (bf && do_update) {
     TransposeTiles tt;
@@ -422,9 +445,83 @@ extern "C" int ppo_update(gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_ppo_
       rc = minibatch_pass(g, m, b, hp, b->perm + (int64_t)j * hp->minibatch, hp->minibatch, true, &n_split, &nlb);
       if (rc != GMI_OK) return rc;
       ++k;
-      rc = launch_adam(g, m, n_split, nlb, hp, hp->minibatch, k,
+      rc = launch_adam(g, &m, 1, n_split, nlb, hp, hp->minibatch, k,
                        stats_out ? stats_out + 5 * ((int64_t)e * nmb + j) : nullptr, nullptr, true);
       if (rc != GMI_OK) return rc;
+    }
+  }
+  return GMI_OK;
+}
+
+extern "C" int ppo_update_group(const gmi_t* gs, const gmi_model_t* ms, const gmi_buffer_t* bs, int32_t n,
+                                const gmi_ppo_hparams* hp, float* stats_out) {
+  if (n < 1 || n > kMaxGroup) GMI_FAIL(GMI_ERR_INVALID_ARG, "ppo_update_group: 1 <= n <= %d instances", kMaxGroup);
+  if (!gs || !ms || !bs) GMI_FAIL(GMI_ERR_INVALID_ARG, "ppo_update_group: NULL handle array");
+  int rc = check_hp("ppo_update_group", hp);
+  if (rc != GMI_OK) return rc;
+  for (int i = 0; i < n; ++i) {
+    if (!valid(gs[i])) GMI_FAIL(GMI_ERR_BAD_HANDLE, "ppo_update_group: bad instance %d", i);
+    if (!valid(ms[i])) GMI_FAIL(GMI_ERR_BAD_HANDLE, "ppo_update_group: bad model %d", i);
+    if (!valid(bs[i])) GMI_FAIL(GMI_ERR_BAD_HANDLE, "ppo_update_group: bad buffer %d", i);
+    rc = check_model_buffer("ppo_update_group", ms[i], bs[i]);
+    if (rc != GMI_OK) return rc;
+    for (int j = 0; j < i; ++j)
+      if (gs[j] == gs[i] || ms[j] == ms[i] || bs[j] == bs[i])
+        GMI_FAIL(GMI_ERR_INVALID_ARG, "ppo_update_group: entries %d and %d share a handle", j, i);
+    // replicas of one model: same arrays, own workspaces
+    if (ms[i]->params != ms[0]->params || ms[i]->adam_m != ms[0]->adam_m || ms[i]->adam_v != ms[0]->adam_v ||
+        ms[i]->shadow != ms[0]->shadow || ms[i]->L.n_params != ms[0]->L.n_params || ms[i]->L.dtype != ms[0]->L.dtype ||
+        ms[i]->n_split_max != ms[0]->n_split_max)
+      GMI_FAIL(GMI_ERR_INVALID_ARG, "ppo_update_group: model %d is not a binding of model 0's parameter arrays", i);
+    if (bs[i]->d.horizon != bs[0]->d.horizon || bs[i]->d.n_envs != bs[0]->d.n_envs)
+      GMI_FAIL(GMI_ERR_BAD_SHAPE, "ppo_update_group: buffer %d has another size than buffer 0", i);
+    if (gs[i]->device != gs[0]->device) GMI_FAIL(GMI_ERR_INVALID_ARG, "ppo_update_group: instances on different devices");
+  }
+  if (!ms[0]->adam_m) GMI_FAIL(GMI_ERR_INVALID_ARG, "ppo_update_group: the model bindings have no Adam state");
+  const int64_t B = (int64_t)bs[0]->d.horizon * bs[0]->d.n_envs;
+  if (hp->epochs < 0 || hp->minibatch < 1) GMI_FAIL(GMI_ERR_INVALID_ARG, "ppo_update_group: epochs >= 0 and minibatch >= 1");
+  if (B == 0 || hp->epochs == 0) return GMI_OK;
+  if (B % hp->minibatch != 0)
+    GMI_FAIL(GMI_ERR_BAD_SHAPE, "ppo_update_group: minibatch %d does not divide T*N = %lld", hp->minibatch, (long long)B);
+  for (int i = 0; i < n; ++i)
+    if (hp->minibatch > ms[i]->max_rows)
+      GMI_FAIL(GMI_ERR_BAD_SHAPE, "ppo_update_group: minibatch %d exceeds binding %d's max_rows %d", hp->minibatch, i,
+               ms[i]->max_rows);
+  const int nmb = (int)(B / hp->minibatch);
+  uint32_t k = hp->adam_step0;
+  gmi_instance* g0 = gs[0];
+  gmi_model* models[kMaxGroup];
+  for (int i = 0; i < n; ++i) models[i] = ms[i];
+  // instance 0's stream also reads what the other instances' earlier calls left (e.g. their buffers are
+  // theirs alone, but the shared parameters were last written on stream 0): nothing to order before the loop.
+  for (int e = 0; e < hp->epochs; ++e) {
+    for (int i = 0; i < n; ++i) {
+      rc = gmi::launch_permutation(gs[i], (int)B, hp->seed + (uint64_t)i, hp->iteration, (uint32_t)e, bs[i]->perm);
+      if (rc != GMI_OK) return rc;
+    }
+    for (int j = 0; j < nmb; ++j) {
+      int n_split = 1, nlb = 1;
+      for (int i = 0; i < n; ++i) {
+        int ns_i = 1, nlb_i = 1;
+        rc = minibatch_pass(gs[i], ms[i], bs[i], hp, bs[i]->perm + (int64_t)j * hp->minibatch, hp->minibatch, true,
+                            &ns_i, &nlb_i, false);
+        if (rc != GMI_OK) return rc;
+        if (i == 0) { n_split = ns_i; nlb = nlb_i; }
+        // replica i's partials are complete: let instance 0 see them
+        if (i > 0) {
+          GMI_HIP(hipEventRecord(gs[i]->event, gs[i]->stream));
+          GMI_HIP(hipStreamWaitEvent(g0->stream, gs[i]->event, 0));
+        }
+      }
+      ++k;
+      rc = launch_adam(g0, models, n, n_split, nlb, hp, hp->minibatch, k,
+                       stats_out ? stats_out + 5 * ((int64_t)e * nmb + j) : nullptr, nullptr, true);
+      if (rc != GMI_OK) return rc;
+      // the updated parameters are complete: the other instances may start their next forward pass
+      if (n > 1) {
+        GMI_HIP(hipEventRecord(g0->event, g0->stream));
+        for (int i = 1; i < n; ++i) GMI_HIP(hipStreamWaitEvent(gs[i]->stream, g0->event, 0));
+      }
     }
   }
   return GMI_OK;
@@ -452,7 +549,7 @@ extern "C" int ppo_evaluate(gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_pp
   int n_split = 0, nlb = 1;
   rc = minibatch_pass(g, m, b, hp, idx, n, false, &n_split, &nlb);
   if (rc != GMI_OK) return rc;
-  return launch_adam(g, m, 0, nlb, hp, n, 1, stats_out, nullptr, false);
+  return launch_adam(g, &m, 1, 0, nlb, hp, n, 1, stats_out, nullptr, false);
 }
 
 extern "C" int ppo_gradient(gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_ppo_hparams* hp, const int32_t* idx,
@@ -463,7 +560,7 @@ extern "C" int ppo_gradient(gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_pp
   int n_split = 1, nlb = 1;
   rc = minibatch_pass(g, m, b, hp, idx, n, true, &n_split, &nlb);
   if (rc != GMI_OK) return rc;
-  return launch_adam(g, m, n_split, nlb, hp, n, 1, stats_out, grad_out, false);
+  return launch_adam(g, &m, 1, n_split, nlb, hp, n, 1, stats_out, grad_out, false);
 }
 
 extern "C" int adam_update(gmi_t g, float* params, float* adam_m, float* adam_v, const float* grad, int64_t n,
@@ -482,9 +579,12 @@ extern "C" int adam_update(gmi_t g, float* params, float* adam_m, float* adam_v,
   tab.act_dim = 0;
   tab.n_params = n;
   gmi::ProfScope ps(g, gmi::kClsAdam);
-  ps.launch(adam_kernel, dim3((unsigned)((n + 255) / 256) + 1), dim3(256), 0, tab, 0, params, adam_m, adam_v, grad, 1, n, nullptr, 0,
-                                                                0, 0.f, 1.f, adam_scalars(hp, step), nullptr, nullptr,
-                                                                nullptr, 1);
+  PartSet set;
+  set.n = 1;
+  for (int i = 0; i < kMaxGroup; ++i) set.part[i] = set.stat[i] = nullptr;
+  set.part[0] = grad;
+  ps.launch(adam_kernel, dim3((unsigned)((n + 255) / 256) + 1), dim3(256), 0, tab, 0, params, adam_m, adam_v, set, 1, n,
+            0, 0, 0.f, 1.f, adam_scalars(hp, step), nullptr, nullptr, nullptr, 1);
   GMI_LAUNCH_CHECK();
   return GMI_OK;
 }

@@ -13,7 +13,7 @@ from . import (DTYPE_BF16, DTYPE_F32, agent_act, agent_value, buffer_desc, colle
                env_step, gae_compute, gmi_buffer_bind, gmi_buffer_destroy, gmi_create, gmi_destroy,
                gmi_env_bind, gmi_env_destroy, gmi_model_bind, gmi_model_destroy, gmi_model_refresh_shadow,
                gmi_model_shadow_bytes, gmi_stream, gmi_sync, model_desc, ppo_hparams, ppo_update,
-               rollout_collect, GmiError, ERR_UNSUPPORTED)
+               rollout_collect, GmiError, ERR_UNSUPPORTED, ppo_update_group)
 
 
 def dtype_code(name: str) -> int:
@@ -55,7 +55,10 @@ class PPOSession:
                  dtype: str, theta: np.ndarray, a_mat: np.ndarray, b_mat: np.ndarray, state0: np.ndarray,
                  noise_std: float, reward_scale: float, done_period: int, done_threshold: int, seed: int,
                  minibatch: int, cu_mask: Optional[Sequence[int]] = None, gmi: Optional[int] = None,
-                 fused_rollout: bool = True):
+                 fused_rollout: bool = True, env_offset: int = 0, replica_of: Optional["PPOSession"] = None):
+        """env_offset: index of this session's env 0 in the Philox counters (distinct per instance when several
+        instances simulate disjoint env shards).  replica_of: bind the model to that session's parameter,
+        Adam and shadow arrays (a replica trained in lockstep through ``update_group``) instead of own ones."""
         dev = torch.device("cuda:0")
         self.dev = dev
         self.N, self.O, self.A, self.T = n_envs, obs_dim, act_dim, horizon
@@ -64,20 +67,29 @@ class PPOSession:
         self.gmi = gmi_create(cu_mask) if gmi is None else gmi
         self.stream = torch.cuda.ExternalStream(gmi_stream(self.gmi), device=dev)
         f = dict(dtype=torch.float32, device=dev)
-        self.theta = torch.tensor(theta, **f)
-        self.adam_m = torch.zeros_like(self.theta)
-        self.adam_v = torch.zeros_like(self.theta)
+        self.env_offset = env_offset
+        if replica_of is None:
+            self.theta = torch.tensor(theta, **f)
+            self.adam_m = torch.zeros_like(self.theta)
+            self.adam_v = torch.zeros_like(self.theta)
+        else:
+            self.theta, self.adam_m, self.adam_v = replica_of.theta, replica_of.adam_m, replica_of.adam_v
         self.adam_steps = 0
         rows = max(n_envs, minibatch)
         self.mdesc = model_desc(obs_dim, act_dim, list(hidden), dtype_code(dtype), rows)
         nshadow = gmi_model_shadow_bytes(self.mdesc)
-        self.shadow = torch.zeros(max(nshadow, 256), dtype=torch.uint8, device=dev) if nshadow else None
+        if replica_of is None:
+            self.shadow = torch.zeros(max(nshadow, 256), dtype=torch.uint8, device=dev) if nshadow else None
+        else:
+            self.shadow = replica_of.shadow
         self.model = gmi_model_bind(self.gmi, self.mdesc, self.theta, self.shadow, self.adam_m, self.adam_v)
-        gmi_model_refresh_shadow(self.gmi, self.model)
+        if replica_of is None:
+            gmi_model_refresh_shadow(self.gmi, self.model)
         self.a_mat = torch.tensor(a_mat, **f)
         self.b_mat = torch.tensor(b_mat, **f)
         self.episode_step = torch.zeros(n_envs, dtype=torch.int32, device=dev)
-        self.edesc = env_desc(n_envs, obs_dim, act_dim, noise_std, reward_scale, done_period, done_threshold, seed)
+        self.edesc = env_desc(n_envs, obs_dim, act_dim, noise_std, reward_scale, done_period, done_threshold, seed,
+                              env_offset)
         self.env = gmi_env_bind(self.gmi, self.edesc, self.a_mat, self.b_mat, self.episode_step)
         self.buf = RolloutBuffers(horizon, n_envs, obs_dim, act_dim, dev)
         self.bdesc = self.buf.desc(0, n_envs)
@@ -99,7 +111,7 @@ class PPOSession:
         if self.fused_rollout:
             try:
                 rollout_collect(g, self.model, self.env, self.buffer, self.obs[self.cur], self.seed,
-                                iteration * self.T, 0, self.last_value)
+                                iteration * self.T, self.env_offset, self.last_value)
                 return
             except GmiError as e:
                 if e.code != ERR_UNSUPPORTED:
@@ -108,7 +120,7 @@ class PPOSession:
         for t in range(self.T):
             step = iteration * self.T + t
             obs, nxt = self.obs[self.cur], self.obs[1 - self.cur]
-            agent_act(g, self.model, obs, self.N, self.seed, step, 0, self.act, self.logp, self.value)
+            agent_act(g, self.model, obs, self.N, self.seed, step, self.env_offset, self.act, self.logp, self.value)
             env_step(g, self.env, obs, self.act, step, nxt, self.reward, self.done)
             collect_experience(g, self.buffer, t, obs, self.act, self.logp, self.value, self.reward, self.done)
             self.cur = 1 - self.cur
@@ -123,6 +135,19 @@ class PPOSession:
                         adam_step0=self.adam_steps, **hp)
         ppo_update(self.gmi, self.model, self.buffer, h, stats)
         self.adam_steps += epochs * (self.T * self.N // minibatch)
+
+    @staticmethod
+    def update_group(sessions: Sequence["PPOSession"], iteration: int, *, epochs: int, minibatch: int, stats=None,
+                     **hp) -> None:
+        """Stage (ii) for replicas trained in lockstep (sessions[1:] built with replica_of=sessions[0]):
+        one synchronized update over all sessions' buffers, gradients averaged in memory."""
+        lead = sessions[0]
+        h = ppo_hparams(epochs=epochs, minibatch=minibatch, seed=lead.seed, iteration=iteration,
+                        adam_step0=lead.adam_steps, **hp)
+        ppo_update_group([s.gmi for s in sessions], [s.model for s in sessions], [s.buffer for s in sessions], h, stats)
+        steps = epochs * (lead.T * lead.N // minibatch)
+        for s in sessions:
+            s.adam_steps += steps
 
     def sync(self) -> None:
         gmi_sync(self.gmi)

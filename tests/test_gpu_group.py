@@ -1,0 +1,197 @@
+"""GPU parity of the synchronized update of several trainer instances (replicas of one model on one GPU,
+gradients reduced by an in-memory mean) against the oracle's ppo_update_group."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import philox as px
+from oracle import ppo as oppo
+from workloads import synthetic as syn
+from gpu_util import oracle_pieces, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+TOL16 = 2e-2
+
+
+@pytest.fixture(scope="module")
+def g():
+    import paper_2206_08482_amd as lib
+    return lib
+
+
+def _sessions(g, cfg, n, n_envs, horizon, minibatch, dtype, theta, env, states, masks=None):
+    from paper_2206_08482_amd.runner import PPOSession
+    out = []
+    for i in range(n):
+        out.append(PPOSession(
+            n_envs=n_envs, obs_dim=cfg.obs_dim, act_dim=cfg.act_dim, hidden=cfg.hidden, horizon=horizon, dtype=dtype,
+            theta=theta, a_mat=env.a_mat, b_mat=env.b_mat, state0=states[i], noise_std=env.noise_std,
+            reward_scale=env.reward_scale, done_period=env.done_period, done_threshold=env.done_threshold,
+            seed=env.seed, minibatch=minibatch, env_offset=i * n_envs, replica_of=out[0] if i else None,
+            cu_mask=masks[i] if masks else None))
+    return out
+
+
+def _oracle_collect(cfg, shape, theta, env, states, n_envs, horizon, iteration=0):
+    bufs = []
+    for i, s in enumerate(states):
+        buf = oppo.new_buffer(horizon, n_envs, cfg.obs_dim, cfg.act_dim)
+        _, _, last = oppo.rollout(theta, shape, env, s.copy(), np.zeros(n_envs, np.uint32), buf, env.seed, iteration,
+                                  env_offset=i * n_envs)
+        buf["adv"], buf["ret"] = oppo.gae(buf["rew"], buf["val"], buf["done"], last, cfg.gamma, cfg.lam, True)
+        bufs.append(buf)
+    return bufs
+
+
+def _hp_kwargs(cfg):
+    return dict(clip=cfg.clip, c_v=cfg.c_v, c_e=cfg.c_e, lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2,
+                adam_eps=cfg.adam_eps)
+
+
+def _even_masks(g, n):
+    from paper_2206_08482_amd.instances import cu_masks
+    probe = g.gmi_create()
+    n_cu = g.gmi_cu_count(probe)
+    g.gmi_destroy(probe)
+    share = (n_cu // n) // 8 * 8
+    return cu_masks(n_cu, [share] * (n - 1) + [n_cu - share * (n - 1)], "contiguous")
+
+
+@pytest.mark.parametrize("n,masked", [(3, False), (2, True)])
+def test_group_iteration_fp32_matches_oracle(g, n, masked):
+    """Whole iteration of n holistic instances in fp32 (own env shard each, shared parameters): collection,
+    GAE and the synchronized update agree with the oracle at the fp32 tolerances."""
+    cfg = syn.get_config("C1")
+    N, T, mb, epochs = cfg.n_envs, cfg.horizon, cfg.minibatch, 2
+    shape, theta, env, _, hp = oracle_pieces(cfg)
+    hp.epochs = epochs
+    states = [syn.make_initial_state(N, cfg.obs_dim, cfg.seed + 20 + i) for i in range(n)]
+    bufs = _oracle_collect(cfg, shape, theta, env, states, N, T)
+    z = np.zeros_like(theta)
+    r_theta, r_m, r_v, r_k, r_stats = oppo.ppo_update_group(theta, z, z, 0, shape, bufs, hp, env.seed, 0)
+
+    ses = _sessions(g, cfg, n, N, T, mb, "f32", theta, env, states, _even_masks(g, n) if masked else None)
+    for s in ses:
+        s.rollout(0)
+        s.gae(cfg.gamma, cfg.lam, True)
+    for s in ses:
+        s.sync()
+    for i, s in enumerate(ses):
+        got = s.buf.to_numpy()
+        assert np.array_equal(got["done"], bufs[i]["done"])
+        for k in ("obs", "act", "logp", "val", "rew", "adv", "ret"):
+            assert rel_l2(got[k], bufs[i][k]) <= 2e-5, (i, k)
+    nup = epochs * (T * N // mb)
+    stats = torch.zeros(nup, 5, device="cuda")
+    type(ses[0]).update_group(ses, 0, epochs=epochs, minibatch=mb, stats=stats, **_hp_kwargs(cfg))
+    for s in ses:
+        s.sync()
+    assert all(s.adam_steps == r_k for s in ses)
+    assert np.abs(stats.cpu().numpy() - r_stats).max() <= 1e-3
+    th = ses[0].theta.cpu().numpy()
+    assert np.abs(r_theta - theta).max() > 1e-4
+    assert rel_l2(th, r_theta) <= 1e-5
+    assert rel_l2(ses[0].adam_m.cpu().numpy(), r_m) <= 1e-4
+    assert rel_l2(ses[0].adam_v.cpu().numpy(), r_v) <= 1e-4
+    # every replica sees the same arrays
+    assert all(s.theta.data_ptr() == ses[0].theta.data_ptr() for s in ses)
+    for s in reversed(ses):
+        s.close()
+
+
+@pytest.mark.parametrize("name,n,n_envs,horizon,minibatch", [("C2", 2, 512, 8, 1024), ("C3", 4, 256, 4, 512),
+                                                             ("C4", 2, 4200, 2, 8400)])
+def test_group_update_bf16_matches_oracle(g, name, n, n_envs, horizon, minibatch):
+    """bf16 path on the oracle's experience (copied into the instances' buffers): per-minibatch statistics
+    at the bf16 tolerance, and the loss of the next forward after all updates within 1e-3."""
+    cfg = syn.get_config(name)
+    shape, theta, env, _, hp = oracle_pieces(cfg, n_envs=n_envs)
+    hp.minibatch, hp.epochs = minibatch, 2
+    states = [syn.make_initial_state(n_envs, cfg.obs_dim, cfg.seed + 20 + i) for i in range(n)]
+    bufs = _oracle_collect(cfg, shape, theta, env, states, n_envs, horizon)
+    z = np.zeros_like(theta)
+    r_theta, _, _, r_k, r_stats = oppo.ppo_update_group(theta, z, z, 0, shape, bufs, hp, env.seed, 0)
+
+    ses = _sessions(g, cfg, n, n_envs, horizon, minibatch, "bf16", theta, env, states)
+    for s, b in zip(ses, bufs):
+        for k in ("obs", "act", "logp", "val", "rew", "done", "adv", "ret"):
+            getattr(s.buf, k).copy_(torch.tensor(b[k], device="cuda"))
+    torch.cuda.synchronize()
+    nup = 2 * (horizon * n_envs // minibatch)
+    stats = torch.zeros(nup, 5, device="cuda")
+    type(ses[0]).update_group(ses, 0, epochs=2, minibatch=minibatch, stats=stats, **_hp_kwargs(cfg))
+    for s in ses:
+        s.sync()
+    got = stats.cpu().numpy()
+    assert got.shape == r_stats.shape
+    assert np.abs(got - r_stats).max() <= TOL16 * max(1.0, np.abs(r_stats).max())
+    r_step = r_theta - theta
+    assert np.abs(r_step).max() > 1e-4
+    assert rel_l2(ses[0].theta.cpu().numpy(), r_theta) <= 5e-3      # Adam's early steps are sign-like
+    # next forward on instance 1's first minibatch, same samples on both sides
+    flat = oppo.flatten_buffer(bufs[1])
+    idx = px.feistel_permutation(n_envs * horizon, env.seed + 1, 0, 0)[:minibatch]
+    r_eval, _ = oppo.ppo_loss_and_grad(r_theta, shape, flat["obs"][idx], flat["act"][idx], flat["logp"][idx],
+                                       flat["adv"][idx], flat["ret"][idx], hp, want_grad=False)
+    out = torch.zeros(5, device="cuda")
+    h = g.ppo_hparams(clip=cfg.clip, c_v=cfg.c_v, c_e=cfg.c_e, minibatch=minibatch)
+    g.ppo_evaluate(ses[1].gmi, ses[1].model, ses[1].buffer, h, torch.tensor(idx.astype(np.int32), device="cuda"),
+                   minibatch, out)
+    ses[1].sync()
+    o = out.cpu().numpy()
+    assert abs(o[0] - r_eval[0]) <= 1e-3
+    assert abs(o[1] - r_eval[1]) <= 1e-3 * max(1.0, abs(r_eval[1]))
+    for s in reversed(ses):
+        s.close()
+
+
+def test_group_of_one_is_the_plain_update_bit_for_bit(g):
+    cfg = syn.get_config("C2")
+    N, T, mb = 300, 4, 400
+    shape, theta, env, _, hp = oracle_pieces(cfg, n_envs=N)
+    states = [syn.make_initial_state(N, cfg.obs_dim, 3)]
+    res = []
+    for group in (False, True):
+        g_ses = _sessions(g, cfg, 1, N, T, mb, "bf16", theta, env, states)
+        s = g_ses[0]
+        s.rollout(0)
+        s.gae(cfg.gamma, cfg.lam, True)
+        stats = torch.zeros(2 * (N * T // mb), 5, device="cuda")
+        if group:
+            type(s).update_group(g_ses, 0, epochs=2, minibatch=mb, stats=stats, **_hp_kwargs(cfg))
+        else:
+            s.update(0, epochs=2, minibatch=mb, stats=stats, **_hp_kwargs(cfg))
+        s.sync()
+        res.append((s.theta.cpu().numpy().copy(), stats.cpu().numpy().copy()))
+        s.close()
+    assert np.array_equal(res[0][0], res[1][0])
+    assert np.array_equal(res[0][1], res[1][1])
+
+
+def test_group_error_paths(g):
+    cfg = syn.get_config("C1")
+    N, T, mb = 64, 16, 256
+    shape, theta, env, _, hp = oracle_pieces(cfg)
+    states = [syn.make_initial_state(N, cfg.obs_dim, i) for i in range(2)]
+    ses = _sessions(g, cfg, 2, N, T, mb, "f32", theta, env, states)
+    from paper_2206_08482_amd.runner import PPOSession
+    other = PPOSession(n_envs=N, obs_dim=cfg.obs_dim, act_dim=cfg.act_dim, hidden=cfg.hidden, horizon=T, dtype="f32",
+                       theta=theta, a_mat=env.a_mat, b_mat=env.b_mat, state0=states[0], noise_std=env.noise_std,
+                       reward_scale=env.reward_scale, done_period=env.done_period,
+                       done_threshold=env.done_threshold, seed=env.seed, minibatch=mb)
+    h = g.ppo_hparams(epochs=1, minibatch=mb)
+    gm = [s.gmi for s in ses]
+    mo = [s.model for s in ses]
+    bu = [s.buffer for s in ses]
+    with pytest.raises(g.GmiError):                      # no instances
+        g.ppo_update_group([], [], [], h)
+    with pytest.raises(g.GmiError):                      # the same handle twice
+        g.ppo_update_group([gm[0], gm[0]], mo, bu, h)
+    with pytest.raises(g.GmiError):                      # a model with its own parameter arrays
+        g.ppo_update_group([gm[0], other.gmi], [mo[0], other.model], [bu[0], other.buffer], h)
+    with pytest.raises(g.GmiError):                      # minibatch does not divide the buffer
+        g.ppo_update_group(gm, mo, bu, g.ppo_hparams(epochs=1, minibatch=100))
+    other.close()
+    for s in reversed(ses):
+        s.close()

@@ -176,11 +176,12 @@ def test_instance_exploration_on_real_trial_runs():
     ks, ns = [4, 3, 1], [128, 256, 512]
     assert [cus_per_instance(prof.device_cus, k) for k in ks] == [prof.device_cus // 4, prof.device_cus // 3 // 8 * 8,
                                                                  prof.device_cus]
-    got = g.gmi_explore(prof, 1, -1.0, ks, ns)            # alpha < any Sat with growing throughput: no early stop
+    ninf = float("-inf")                                  # no Sat is below it: the search never stops early
+    got = g.gmi_explore(prof, 1, ninf, ks, ns)
     assert len(prof.log) == 9 and all(r["runnable"] for r in prof.log), prof.log
     assert all(r["samples_per_s"] > 0 and r["bytes"] >= 0 for r in prof.log)
     table = {(r["gmi_per_gpu"], r["num_env"]): (True, r["samples_per_s"], r["bytes"]) for r in prof.log}
-    ref = osel.explore(lambda k, n: table[(k, n)], lambda k, gpus, top: top * k * gpus, 1, -1.0, ks, ns)
+    ref = osel.explore(lambda k, n: table[(k, n)], lambda k, gpus, top: top * k * gpus, 1, ninf, ks, ns)
     assert (got is None and ref is None) or got[:2] == ref
     # a point that cannot run (fewer than one CU per die for each instance) is reported as not runnable
     prof2 = InstanceProfiler(build, step, lambda n: 4 * n, iterations=1)
