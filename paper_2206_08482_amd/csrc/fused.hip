@@ -279,6 +279,7 @@ struct RolloutArgs {
   uint32_t* episode_step;           // [n]
   int n, obs_dim, obs_pad, act_dim, max_h, o4, T, ld_envs;
   int rows_per_wg;                  // envs owned by a workgroup: the tile height, or half of it
+  int n_tiles;                      // ceil(n / rows_per_wg); the grid may be smaller (workgroups loop)
   float noise_std, reward_scale;
   uint32_t done_period, done_threshold;
   uint32_t ak0, ak1, a_env_offset;  // agent's Philox key and env offset
@@ -376,13 +377,7 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   // Rv <= R envs are owned by this workgroup (a half-filled tile doubles the workgroups of a small batch);
   // rows Rv..R-1 of the tile go through the matrix products but are never read or stored
   const int Rv = a.rows_per_wg;
-  const int r0 = blockIdx.x * Rv;
   for (int idx = tid; idx < (R - Rv) * stride_x0; idx += NT) s_x0[Rv * stride_x0 + idx] = 0;
-
-  for (int idx = tid; idx < Rv * O; idx += NT) {
-    const int r = idx / O, k = idx - r * O;
-    s_in[r * OA + k] = (r0 + r < a.n) ? a.obs_state[(int64_t)(r0 + r) * O + k] : 0.f;
-  }
   stage_biases(a.net[0], s_bias, tid, NT);
   stage_biases(a.net[1], s_bias + a.net[0].bias_total, tid, NT);
   if (a.mt_lds == 2)
@@ -391,16 +386,25 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   float4* s_stage = reinterpret_cast<float4*>(s_reg + ((next_bytes + 15) & ~(size_t)15));
   const float4* mt = a.mt_lds == 2 ? reinterpret_cast<const float4*>(s_mt)
                    : a.mt_lds == 1 ? s_stage : reinterpret_cast<const float4*>(a.m_t);
-  uint32_t ep = 0;                                   // thread r < R carries env r's episode counter
-  if (tid < Rv && r0 + tid < a.n) ep = a.episode_step[r0 + tid];
-  __syncthreads();
-
   const FusedNet& N = a.net[half];
   uint16_t* s_a = s_hid + (size_t)half * 2 * R * stride_h;
   uint16_t* s_b = s_a + R * stride_h;
   float* s_head = half ? s_val : s_mu;
   const int head_stride = half ? 1 : A;
   const float* s_nb = s_bias + (half ? a.net[0].bias_total : 0);
+
+  // The grid never exceeds what the instance's compute units hold at once: a workgroup takes the tiles
+  // blockIdx.x, blockIdx.x + gridDim.x, ... one after the other, each through all T steps.  (Workgroups
+  // that wait for a free compute unit would keep the dispatcher from placing other instances' kernels.)
+  for (int tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
+  const int r0 = tile * Rv;
+  for (int idx = tid; idx < Rv * O; idx += NT) {
+    const int r = idx / O, k = idx - r * O;
+    s_in[r * OA + k] = (r0 + r < a.n) ? a.obs_state[(int64_t)(r0 + r) * O + k] : 0.f;
+  }
+  uint32_t ep = 0;                                   // thread r < R carries env r's episode counter
+  if (tid < Rv && r0 + tid < a.n) ep = a.episode_step[r0 + tid];
+  __syncthreads();
 
   for (int t = 0; t <= a.T; ++t) {
     // both nets, layer by layer; after the last step only the value net (bootstrap value)
@@ -515,6 +519,8 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
     if (r0 + r < a.n) a.obs_state[(int64_t)(r0 + r) * O + k] = s_in[r * OA + k];
   }
   if (tid < Rv && r0 + tid < a.n) a.episode_step[r0 + tid] = ep;
+  __syncthreads();                                   // the next tile overwrites the state rows
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -966,22 +972,23 @@ extern "C" int rollout_collect(gmi_t g, gmi_model_t m, gmi_env_t env, gmi_buffer
   // fewer 32-env tiles than compute units: 16 envs per workgroup use twice as many of them
   const int rows_per_wg = (R == 32 && (n + 31) / 32 < g->cu_count && n > 16) ? 16 : R;
   a.rows_per_wg = rows_per_wg;
-  gmi::ProfScope ps(g, gmi::kClsFusedRollout);
-  if (R == 64) {
-    static bool attr64 = false;
-    if (!attr64) {
-      GMI_HIP(hipFuncSetAttribute((const void*)rollout_fused_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
-      attr64 = true;
-    }
-    ps.launch(rollout_fused_kernel<2>, dim3((n + 63) / 64), dim3(512), lds, a);
-  } else {
-    static bool attr32 = false;
-    if (!attr32) {
-      GMI_HIP(hipFuncSetAttribute((const void*)rollout_fused_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
-      attr32 = true;
-    }
-    ps.launch(rollout_fused_kernel<1>, dim3((n + rows_per_wg - 1) / rows_per_wg), dim3(512), lds, a);
+  a.n_tiles = (n + rows_per_wg - 1) / rows_per_wg;
+  const void* kern = R == 64 ? (const void*)rollout_fused_kernel<2> : (const void*)rollout_fused_kernel<1>;
+  static bool attr_set[2] = {false, false};
+  if (!attr_set[R == 64]) {
+    GMI_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
+    attr_set[R == 64] = true;
   }
+  // no more workgroups than the instance's compute units hold at once; the rest of the tiles are taken
+  // by the same workgroups in turn
+  int per_cu = 0;
+  GMI_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 512, lds));
+  if (per_cu < 1) per_cu = 1;
+  const int64_t resident = (int64_t)per_cu * g->cu_count;
+  const int grid = (int)(a.n_tiles < resident ? a.n_tiles : resident);
+  gmi::ProfScope ps(g, gmi::kClsFusedRollout);
+  if (R == 64) ps.launch(rollout_fused_kernel<2>, dim3(grid), dim3(512), lds, a);
+  else ps.launch(rollout_fused_kernel<1>, dim3(grid), dim3(512), lds, a);
   GMI_LAUNCH_CHECK();
   return GMI_OK;
 }

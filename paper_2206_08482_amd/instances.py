@@ -24,7 +24,8 @@ import torch
 from . import (agent_act, agent_value, collect_experience, dtype_code, env_desc, env_step, gae_compute,
                gmi_buffer_bind, gmi_buffer_destroy, gmi_create, gmi_cu_count, gmi_destroy, gmi_env_bind,
                gmi_env_destroy, gmi_model_bind, gmi_model_destroy, gmi_model_refresh_shadow,
-               gmi_model_shadow_bytes, gmi_sync, gmi_transfer, model_desc, ppo_hparams, ppo_update)
+               gmi_model_shadow_bytes, gmi_sync, gmi_transfer, model_desc, ppo_hparams, ppo_update, rollout_collect,
+               GmiError, ERR_UNSUPPORTED)
 from .runner import RolloutBuffers
 
 
@@ -82,13 +83,15 @@ class InstancePipeline:
                  state0: Sequence[np.ndarray], noise_std: float, reward_scale: float, done_period: int,
                  done_threshold: int, seed: int, minibatch: int,
                  agent_masks: Optional[Sequence[Optional[Sequence[int]]]] = None,
-                 trainer_mask: Optional[Sequence[int]] = None, single_stream: bool = False):
+                 trainer_mask: Optional[Sequence[int]] = None, single_stream: bool = False,
+                 fused_rollout: bool = True):
         dev = torch.device("cuda:0")
         f = dict(dtype=torch.float32, device=dev)
         self.n_agents, self.N, self.O, self.A, self.T = n_agents, n_envs, obs_dim, act_dim, horizon
         self.Ntot = n_agents * n_envs
         self.seed = seed
         self.single_stream = single_stream
+        self.fused_rollout = fused_rollout and dtype == "bf16"      # one launch per agent and horizon where it fits
         self.trainer = gmi_create(trainer_mask)
         self.theta = torch.tensor(theta, **f)
         self.adam_m = torch.zeros_like(self.theta)
@@ -152,6 +155,18 @@ class InstancePipeline:
         """Stage (i) on every agent instance: T rounds of act -> step -> store, then the bootstrap value,
         into experience buffer `slot`; ends with the ordering-only hand-off to the trainer."""
         T = self.T
+        if self.fused_rollout:
+            try:
+                for i, ag in enumerate(self.agents):
+                    lv = self.last_value[slot].data_ptr() + i * self.N * 4
+                    rollout_collect(ag.gmi, ag.model, ag.env, ag.buffer[slot], ag.obs[ag.cur], ag.seed, iteration * T,
+                                    0, lv)
+                    gmi_transfer(ag.gmi, self.trainer, None, None, 0)
+                return
+            except GmiError as e:
+                if e.code != ERR_UNSUPPORTED:
+                    raise
+                self.fused_rollout = False      # refused before anything ran: the per-step calls below
         for t in range(T):
             step = iteration * T + t
             for ag in self.agents:                      # round-robin so the streams fill evenly

@@ -127,14 +127,17 @@ def test_pipelined_schedule_matches_oracle_fp32():
     pipe.close()
 
 
-def test_sync_schedule_bf16_runs_and_stays_close():
+@pytest.mark.parametrize("fused_rollout", [True, False])
+def test_sync_schedule_bf16_runs_and_stays_close(fused_rollout):
     cfg = syn.get_config("C3")
     n_agents, n_envs, horizon, minibatch = 4, 128, 4, 1024
     shape, theta, a_mat, b_mat, thr, envs, states, hp = _setup(cfg, n_agents, n_envs, horizon, minibatch)
     pipe = _pipeline(cfg, "bf16", n_agents, n_envs, horizon, minibatch, theta, a_mat, b_mat, thr, states, True)
+    pipe.fused_rollout = fused_rollout
     ora = _OracleAgents(shape, envs, states, n_envs, horizon, cfg)
     pipe.iteration_sync(0, **_train_args(cfg, minibatch))
     pipe.sync_all()
+    assert pipe.fused_rollout == fused_rollout        # the one-launch collection really ran for this model
     buf = ora.collect(theta, 0)
     got = pipe.bufs[0].to_numpy()
     assert np.array_equal(got["done"], buf["done"])
