@@ -38,7 +38,7 @@ bool ProfScope::next_events(hipEvent_t* a, hipEvent_t* b) {
 }
 static const char* kClassNames[kClsCount] = {
     "gather", "wgrad", "loss", "adam", "shadow_transpose", "env_step", "sample", "collect", "gae", "permutation",
-    "fused_agent", "fused_train", "fused_rollout", "reduce", "linear_f32",
+    "fused_agent", "fused_train", "fused_rollout", "reduce", "linear_f32", "chain_train",
     "linear_big256_fwd", "linear_big256_head", "linear_big256_dgrad",
     "linear_big128_fwd", "linear_big128_head", "linear_big128_dgrad",
     "linear_t128_fwd", "linear_t128_head", "linear_t128_dgrad",

@@ -65,7 +65,7 @@ namespace gmi {
 enum KernelClass {
   kClsGather = 0, kClsWgrad, kClsLoss, kClsAdam, kClsShadowTranspose, kClsEnvStep, kClsSample,
   kClsCollect, kClsGae, kClsPermutation, kClsFusedAgent, kClsFusedTrain, kClsFusedRollout, kClsReduce,
-  kClsLinearF32, kClsLinear, kClsCount = kClsLinear + 15
+  kClsLinearF32, kClsChainTrain, kClsLinear, kClsCount = kClsLinear + 15
 };
 static_assert(kClsCount < 32, "class masks are 32-bit");
 struct ProfSlot {
@@ -141,6 +141,8 @@ struct ModelLayout {
   int64_t n_params;
   int64_t shadow_bytes;
   int64_t weight_bytes;                       // bf16 bytes of one copy of all weights (padded), both nets
+  int64_t sh_chain[2];                        // byte offsets of the two nets' chain streams (chain.hip)
+  int64_t sh_chain_bytes;                     // bytes of one stream; 0 = this model has none
   int max_width_pad;                          // widest padded activation
 };
 
@@ -264,6 +266,11 @@ int launch_train_fused(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_p
                        int rows);
 
 int launch_permutation(gmi_instance* g, int n, uint64_t seed, uint32_t iteration, uint32_t epoch, int32_t* out);
+
+// Register-chained trainer kernel (chain.hip): its weight stream in the shadow and the launch.
+int64_t chain_stream_bytes(const ModelLayout& L);
+int launch_chain_pack(gmi_instance* g, gmi_model* m);
+int launch_train_chain(gmi_instance* g, gmi_model* m, const gmi_ppo_hparams* hp, int rows);
 
 }  // namespace gmi
 

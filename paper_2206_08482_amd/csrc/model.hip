@@ -47,9 +47,15 @@ int build_layout(const gmi_model_desc* d, ModelLayout* L) {
   L->sh_logstd = sh;
   sh += gmi::align_up((int64_t)d->act_dim * 4, 256);
   L->n_params = off;
-  L->shadow_bytes = d->dtype == GMI_DTYPE_BF16 ? sh : 0;
   L->weight_bytes = wbytes;
   L->max_width_pad = maxw;
+  // the register-chained trainer kernel's weight streams (one per net), after everything else
+  L->sh_chain_bytes = gmi::chain_stream_bytes(*L);
+  for (int net = 0; net < 2; ++net) {
+    L->sh_chain[net] = sh;
+    sh += gmi::align_up(L->sh_chain_bytes, 256);
+  }
+  L->shadow_bytes = d->dtype == GMI_DTYPE_BF16 ? sh : 0;
   return GMI_OK;
 }
 
@@ -288,13 +294,16 @@ extern "C" int gmi_model_bind(gmi_t g, const gmi_model_desc* d, float* params, v
       off += gmi::align_up(bytes, 256);
       return p;
     };
-    m->x0 = take(rows * gmi::pad32(L.obs_dim) * es);
+    // activation arrays hold a whole number of 256-row tiles: the register-chained trainer kernel stores
+    // (and loads) the ragged last tile without bounds checks; rows past the batch are never used
+    const int64_t arows = (rows + 255) / 256 * 256;
+    m->x0 = take(arows * gmi::pad32(L.obs_dim) * es);
     for (int net = 0; net < 2; ++net) {
       m->h[net][0] = m->x0;
       for (int l = 0; l < L.n_layers; ++l) {
         const LayerInfo& li = L.net[net][l];
-        if (!li.head) m->h[net][l + 1] = take(rows * li.out_pad * es);
-        m->dz[net][l] = take(rows * li.out_pad * es);
+        if (!li.head) m->h[net][l + 1] = take(arows * li.out_pad * es);
+        m->dz[net][l] = take(arows * li.out_pad * es);
       }
     }
     m->mu = (float*)take(rows * A * 4);
@@ -341,7 +350,7 @@ extern "C" int gmi_model_refresh_shadow(gmi_t g, gmi_model_t m) {
   const gmi::ShadowTable tab = gmi::make_shadow_table(m->L);
   refresh_shadow_kernel<<<(unsigned)((m->L.n_params + 255) / 256), 256, 0, g->stream>>>(tab, m->params, m->shadow);
   GMI_LAUNCH_CHECK();
-  return GMI_OK;
+  return gmi::launch_chain_pack(g, m);
 }
 
 static int check_rows(const char* fn, gmi_model_t m, int n_rows) {

@@ -302,11 +302,23 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
     if (rc == GMI_OK) fused = true;
     else if (rc != GMI_ERR_UNSUPPORTED) return rc;
   }
+  bool gathered = false;
+  if (!fused && g->fusion >= 1 && want_grad && bf) {
+    // register-chained kernel (forward + loss + input gradients in one launch) where this shape has one
+    rc = gmi::launch_gather(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, &b->d);
+    if (rc != GMI_OK) return rc;
+    gathered = true;
+    rc = gmi::launch_train_chain(g, m, hp, rows);
+    if (rc == GMI_OK) fused = true;
+    else if (rc != GMI_ERR_UNSUPPORTED) return rc;
+  }
   if (fused) {
     *n_loss_blocks_out = -1;     // statistics already summed (row kLossBlocksMax of stat_part)
   } else {
-  rc = gmi::launch_gather(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, &b->d);
-  if (rc != GMI_OK) return rc;
+  if (!gathered) {
+    rc = gmi::launch_gather(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, &b->d);
+    if (rc != GMI_OK) return rc;
+  }
   rc = gmi::forward_nets(g, m, rows, true, true, m->mu, m->val);
   if (rc != GMI_OK) return rc;
   int nlb = (rows + 255) / 256;
@@ -392,8 +404,9 @@ int launch_adam(gmi_instance* g, gmi_model* const* ms, int n, int n_split, int n
     set.part[i] = i < n ? ms[i]->grad_part : nullptr;
     set.stat[i] = i < n ? ms[i]->stat_part : nullptr;
   }
-  if (n_loss_blocks < 0) {      // fused trainer (single instance): statistics already summed into one row
-    set.stat[0] = m->stat_part + (int64_t)gmi::kLossBlocksMax * (gmi::kStatStride + m->L.act_dim);
+  if (n_loss_blocks < 0) {      // fused / chained trainer: every replica's statistics are already summed into one row
+    for (int i = 0; i < n; ++i)
+      set.stat[i] = ms[i]->stat_part + (int64_t)gmi::kLossBlocksMax * (gmi::kStatStride + m->L.act_dim);
     n_loss_blocks = 1;
   }
   const bool bf = m->L.dtype == GMI_DTYPE_BF16;
@@ -413,6 +426,7 @@ int launch_adam(gmi_instance* g, gmi_model* const* ms, int n, int n_split, int n
     gmi::ProfScope ps2(g, gmi::kClsShadowTranspose);
     ps2.launch(shadow_transpose_kernel, dim3(total), dim3(256), 0, tab, tt, m->shadow);
     GMI_LAUNCH_CHECK();
+    return gmi::launch_chain_pack(g, m);
   }
   return GMI_OK;
 }
