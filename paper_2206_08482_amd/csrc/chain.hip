@@ -193,6 +193,9 @@ struct ChainArgs {
   int rows, act_dim;
   float clip, c_v;
   float* stat_part;                                // [tiles][kStatStride + act_dim]
+#ifdef GMI_CHAIN_TIMING
+  long long* dbg;                                  // [n_chunks + 1] clock at the start of every chunk (workgroup 0, wave 0)
+#endif
 };
 
 constexpr int kSlotBytes = 16 * 1024;              // one chunk
@@ -222,7 +225,7 @@ struct ChainShape {
     return n;
   }
   static constexpr size_t lds_bytes() {
-    return kSlots * (size_t)kSlotBytes + (size_t)NW * kScrBytes + (size_t)bias_total() * 4 + (size_t)NW * 40 * 4;
+    return kSlots * (size_t)kSlotBytes + (size_t)NW * kScrBytes + (size_t)bias_total() * 4 + (size_t)(NW * 40 + 64) * 4;
   }
 };
 
@@ -233,6 +236,8 @@ struct Ctx {
   uint4 stage[S::DEPTH][S::LPT];         // weight chunks in flight
   bf16x8 wq[3][4];                       // weight operands of k steps g, g+1, g+2 (ring indexed by g % 3)
   uint4 ht[8];                           // stored activations of the group (input-gradient segments)
+  float l_act[16], l_lo, l_ad, l_rt;     // this lane's loss inputs (fetched at kernel start): actions of its 16
+                                         // features, old log-prob, advantage, return
   const uint4* wsrc;                     // this net's stream
   char* lds;                             // workgroup LDS base
   char* scr;                             // this wave's transposition buffer
@@ -296,11 +301,6 @@ __device__ __forceinline__ void regs_to_scr(const uint4* ht, int lane, char* scr
   }
 }
 
-__device__ __forceinline__ float half_sum(float v) {      // sum over the 32 lanes of a wave half
-#pragma unroll
-  for (int off = 16; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
 __device__ __forceinline__ float wave_sum64(float v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -311,36 +311,58 @@ __device__ __forceinline__ float wave_sum64(float v) {
 // 8 (i / 4) + 4 hh + i % 4).  Leaves the head gradient as the first two k steps of `xo` and in the wave's
 // transposition buffer, and per-wave partial sums in s_red[wave][0..2] (policy: surrogate, kl, clipped;
 // value: squared error in [0]) and s_red[wave][8 + f] (log_std gradient partials).
+// This lane's loss inputs, fetched one layer before the head needs them (unconditional loads: rows and features
+// past the end read a valid neighbour, their results are dropped).
+template <class S>
+__device__ __forceinline__ void fetch_loss_inputs(Ctx<S>& c, const ChainArgs& a) {
+  const int row = c.row0 + c.s;
+  const int rowc = row < a.rows ? row : a.rows - 1;
+  c.l_lo = a.mb_logp[rowc]; c.l_ad = a.mb_adv[rowc]; c.l_rt = a.mb_ret[rowc];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int f = 8 * (i >> 2) + 4 * c.hh + (i & 3);
+    const int fc = f < a.act_dim ? f : a.act_dim - 1;
+    c.l_act[i] = a.mb_act[(int64_t)rowc * a.act_dim + fc];
+  }
+}
+
 template <class S>
 __device__ __forceinline__ void loss_epilogue(Ctx<S>& c, const ChainArgs& a, uint4* xo) {
   constexpr int HB = S::bias_off(S::NL - 1);
   const int A = a.act_dim;
   const int row = c.row0 + c.s;
   const bool ok = row < a.rows;
-  const int rowc = ok ? row : a.rows - 1;           // loads are unconditional; results of rows past the batch are dropped
   const float inv_m = 1.0f / (float)a.rows;
   const floatx16& acc = c.acc[0];
   float d[16];
   float* red = c.s_red + c.wave * 40;
   if (c.net == 0) {
+    // s_ls[f] = log_std, s_ls[32 + f] = exp(-log_std) (0 for f >= A), staged at kernel start
+    const float* s_ls = c.s_red + S::NW * 40;
     float z[16], isg[16];
     float lp = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int f = 8 * (i >> 2) + 4 * c.hh + (i & 3);
-      const int fc = f < A ? f : A - 1;
-      const float ls = a.log_std[fc];
-      const float mu = acc[i] + c.s_bias[HB + f];
-      const float av = a.mb_act[(int64_t)rowc * A + fc];
-      isg[i] = f < A ? expf(-ls) : 0.f;
-      z[i] = f < A ? (av - mu) * isg[i] : 0.f;
-      lp += f < A ? -0.5f * z[i] * z[i] - ls - 0.918938533204672742f : 0.f;
+    for (int q = 0; q < 4; ++q) {
+      const int f0 = 8 * q + 4 * c.hh;
+      const float4 ls4 = *reinterpret_cast<const float4*>(s_ls + f0);
+      const float4 ig4 = *reinterpret_cast<const float4*>(s_ls + 32 + f0);
+      const float4 b4 = *reinterpret_cast<const float4*>(c.s_bias + HB + f0);
+      const float lsv[4] = {ls4.x, ls4.y, ls4.z, ls4.w}, igv[4] = {ig4.x, ig4.y, ig4.z, ig4.w};
+      const float bv[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int i = 4 * q + e;
+        const float mu = acc[i] + bv[e];
+        isg[i] = igv[e];
+        z[i] = (c.l_act[i] - mu) * igv[e];                    // 0 for f >= A
+        lp += f0 + e < A ? -0.5f * z[i] * z[i] - lsv[e] - 0.918938533204672742f : 0.f;
+      }
     }
     lp += __shfl_xor(lp, 32, 64);                   // the other half holds the other 16 features
     float s_pl = 0.f, s_kl = 0.f, s_cf = 0.f, g_lp = 0.f;
-    const float lo = a.mb_logp[rowc], ad = a.mb_adv[rowc];
     if (ok) {
-      const float ratio = expf(lp - lo);
+      const float lo = c.l_lo, ad = c.l_ad;
+      const float ratio = __expf(lp - lo);
       const float u1 = ratio * ad;
       const float u2 = fminf(fmaxf(ratio, 1.0f - a.clip), 1.0f + a.clip) * ad;
       g_lp = (u1 <= u2) ? -(ad * ratio) * inv_m : 0.f;
@@ -350,14 +372,20 @@ __device__ __forceinline__ void loss_epilogue(Ctx<S>& c, const ChainArgs& a, uin
         s_cf = fabsf(ratio - 1.0f) > a.clip ? 1.f : 0.f;
       }
     }
+    // log_std gradient partials g_lp (z^2 - 1): transposed through the wave's LDS buffer as [feature][sample]
+    // fp32, then lane f < 32 sums feature f's 32 samples in a fixed order
+    float* tp = reinterpret_cast<float*>(c.scr);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int f = 8 * (i >> 2) + 4 * c.hh + (i & 3);
       d[i] = g_lp * z[i] * isg[i];
-      float gls = g_lp * (z[i] * z[i] - 1.0f);      // zero for f >= A (z = 0 but -1 remains: mask)
-      if (f >= A) gls = 0.f;
-      gls = half_sum(gls);
-      if (c.s == 0 && f < A) red[8 + f] = gls;
+      tp[f * 33 + c.s] = g_lp * (z[i] * z[i] - 1.0f);
+    }
+    if (c.lane < 32) {
+      float sum = 0.f;
+#pragma unroll
+      for (int k = 0; k < 32; ++k) sum += tp[c.lane * 33 + k];
+      red[8 + c.lane] = c.lane < A ? sum : 0.f;
     }
     s_pl = wave_sum64(s_pl); s_kl = wave_sum64(s_kl); s_cf = wave_sum64(s_cf);
     if (c.lane == 0) { red[0] = s_pl; red[1] = s_kl; red[2] = s_cf; }
@@ -365,9 +393,8 @@ __device__ __forceinline__ void loss_epilogue(Ctx<S>& c, const ChainArgs& a, uin
     float s_vl = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) d[i] = 0.f;
-    const float rt = a.mb_ret[rowc];
     if (ok && c.hh == 0) {
-      const float dv = acc[0] + c.s_bias[HB] - rt;
+      const float dv = acc[0] + c.s_bias[HB] - c.l_rt;
       s_vl = dv * dv;
       d[0] = 2.0f * a.c_v * dv * inv_m;
     }
@@ -412,8 +439,6 @@ __device__ __forceinline__ void loss_epilogue(Ctx<S>& c, const ChainArgs& a, uin
   }
 }
 
-// Reads the weight operands of k step k of chunk C (or, past its end, of the following chunk) from LDS into ring
-// entry RING.
 template <class S, int C, int K, int RING>
 __device__ __forceinline__ void fetch_kstep(Ctx<S>& c) {
   if constexpr (C < S::nch()) {
@@ -470,8 +495,12 @@ __device__ __forceinline__ void chain_step(Ctx<S>& c, const ChainArgs& a) {
   // even segments read xa and write xb, odd ones the other way round
   uint4* xi = (seg & 1) ? c.xb : c.xa;
   uint4* xo = (seg & 1) ? c.xa : c.xb;
+#ifdef GMI_CHAIN_TIMING
+  if (blockIdx.x == 0 && blockIdx.y == 0 && c.tid == 0) a.dbg[C] = __builtin_readcyclecounter();
+#endif
 
   issue_chunk<S, C + 1 + S::DEPTH>(c);
+  if constexpr (seg == NL - 2 && ci.gi == 0 && ci.first) fetch_loss_inputs<S>(c, a);
 
   if constexpr (bwd && ci.last)        // stored activations of this group's features, for ELU'
     global_to_regs<GS>(c.ht, c.lane, a.h[c.net][layer], D.d[layer], 32 * ci.tile0, c.row0, a.rows);
@@ -566,6 +595,12 @@ __global__ __launch_bounds__(S::NW * 64) void train_chain_kernel(ChainArgs a) {
     }
   }
   for (int i = c.tid; i < S::NW * 40; i += S::NT) c.s_red[i] = 0.f;
+  if (c.tid < 32) {                      // per-feature constants of the Gaussian log-prob (policy net)
+    const int fc = c.tid < a.act_dim ? c.tid : a.act_dim - 1;
+    const float ls = a.log_std[fc];
+    c.s_red[S::NW * 40 + c.tid] = ls;
+    c.s_red[S::NW * 40 + 32 + c.tid] = c.tid < a.act_dim ? expf(-ls) : 0.f;
+  }
   {
     // first layer's operand in natural order: lane (s, hh) holds features 16 ks + 8 hh .. + 7 of its sample
     const int row = c.row0 + c.s;
@@ -579,19 +614,6 @@ __global__ __launch_bounds__(S::NW * 64) void train_chain_kernel(ChainArgs a) {
   fetch_kstep<S, 0, 0, 0>(c);
   fetch_kstep<S, 0, 1, 1>(c);
   chain_step<S, 0>(c, a);
-}
-
-// out[col] = sum over rows of part[row][col]; one workgroup per column, fixed summation order
-__global__ __launch_bounds__(256) void chain_reduce_rows_kernel(const float* __restrict__ part, int n_rows, int width,
-                                                                float* __restrict__ out) {
-  __shared__ float sh[4];
-  const int col = blockIdx.x;
-  float s = 0.f;
-  for (int r = threadIdx.x; r < n_rows; r += 256) s += part[(int64_t)r * width + col];
-  s = wave_sum64(s);
-  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
-  __syncthreads();
-  if (threadIdx.x == 0) out[col] = sh[0] + sh[1] + sh[2] + sh[3];
 }
 
 // The shapes with a compiled kernel: padded widths of the three benchmark model families (observation and
@@ -637,6 +659,14 @@ ChainDims dims_of(const ModelLayout& L) {
 
 }  // namespace
 
+#ifdef GMI_CHAIN_TIMING
+static long long* g_chain_dbg = nullptr;
+extern "C" int gmi_chain_timing(long long* out, int n) {
+  if (!g_chain_dbg) return -1;
+  return (int)hipMemcpy(out, g_chain_dbg, (size_t)n * 8, hipMemcpyDeviceToHost);
+}
+#endif
+
 namespace gmi {
 
 // Bytes of one net's chain stream (0 if the two nets' padded widths differ, which only a policy head wider
@@ -679,9 +709,9 @@ int launch_chain_pack(gmi_instance* g, gmi_model* m) {
 }
 
 // Forward + loss + input gradients of the minibatch whose rows were gathered into m->x0 / m->mb_* (launch_gather).
-// Leaves m->h, m->dz ready for the weight-gradient launch and the summed statistics / log_std partials in row
-// kLossBlocksMax of m->stat_part.  GMI_ERR_UNSUPPORTED (no message) if no kernel is compiled for this shape.
-int launch_train_chain(gmi_instance* g, gmi_model* m, const gmi_ppo_hparams* hp, int rows) {
+// Leaves m->h, m->dz ready for the weight-gradient launch and one row of statistics / log_std partials per
+// tile in m->stat_part (*n_stat_rows rows, the layout of the loss kernel's per-workgroup rows).  GMI_ERR_UNSUPPORTED (no message) if no kernel is compiled for this shape.
+int launch_train_chain(gmi_instance* g, gmi_model* m, const gmi_ppo_hparams* hp, int rows, int* n_stat_rows) {
   const ModelLayout& L = m->L;
   if (L.dtype != GMI_DTYPE_BF16 || L.sh_chain_bytes == 0 || L.act_dim > 32) return GMI_ERR_UNSUPPORTED;
   ChainArgs a;
@@ -699,6 +729,12 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, const gmi_ppo_hparams* hp,
   a.rows = rows; a.act_dim = L.act_dim;
   a.clip = hp->clip; a.c_v = hp->c_v;
   a.stat_part = m->stat_part;
+#ifdef GMI_CHAIN_TIMING
+  static long long* dbg = nullptr;
+  if (!dbg) { GMI_HIP(hipMalloc(&dbg, 4096 * 8)); GMI_HIP(hipMemset(dbg, 0, 4096 * 8)); }
+  a.dbg = dbg;
+  g_chain_dbg = dbg;
+#endif
   int tiles = 0, rc;
   if (rows < 1 || rows > m->max_rows) return GMI_ERR_UNSUPPORTED;      // the activation arrays hold max_rows (in whole tiles)
   // algorithmic work at the logical (unpadded) widths: forward products of every layer, input-gradient products
@@ -721,13 +757,7 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, const gmi_ppo_hparams* hp,
   else if (shape_matches<ShapeC4>(L)) rc = launch_shape<ShapeC4>(g, a, rows, &tiles, flops, bytes);
   else return GMI_ERR_UNSUPPORTED;
   if (rc != GMI_OK) return rc;
-  {
-    ProfScope ps(g, kClsReduce);
-    const int width = kStatStride + L.act_dim;
-    ps.launch(chain_reduce_rows_kernel, dim3(width), dim3(256), 0, m->stat_part, tiles, width,
-              m->stat_part + (int64_t)kLossBlocksMax * width);
-    GMI_LAUNCH_CHECK();
-  }
+  *n_stat_rows = tiles;
   return GMI_OK;
 }
 

@@ -154,8 +154,18 @@ __global__ __launch_bounds__(256) void adam_kernel(gmi::ShadowTable tab, int wri
       const int col = cbase + tid % width, grp = tid / width;
       float s = 0.f;
       if (have_stat && grp < groups && col < C)
-        for (int i = 0; i < ps.n; ++i)
-          for (int b = grp; b < n_loss_blocks; b += groups) s += ps.stat[i][(int64_t)b * C + col];
+        for (int i = 0; i < ps.n; ++i) {
+          // rows grp, grp + groups, ...: eight loads in flight, fixed order of additions
+          const float* q = ps.stat[i] + col;
+          int b = grp;
+          for (; b + 7 * groups < n_loss_blocks; b += 8 * groups) {
+            float t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = q[(int64_t)(b + u * groups) * C];
+            s += ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
+          }
+          for (; b < n_loss_blocks; b += groups) s += q[(int64_t)b * C];
+        }
       s_col[tid] = s;
       __syncthreads();
       const int c = cbase + tid;
@@ -302,18 +312,19 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
     if (rc == GMI_OK) fused = true;
     else if (rc != GMI_ERR_UNSUPPORTED) return rc;
   }
-  bool gathered = false;
+  bool gathered = false, chained = false;
   if (!fused && g->fusion >= 1 && want_grad && bf) {
     // register-chained kernel (forward + loss + input gradients in one launch) where this shape has one
     rc = gmi::launch_gather(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, &b->d);
     if (rc != GMI_OK) return rc;
     gathered = true;
-    rc = gmi::launch_train_chain(g, m, hp, rows);
-    if (rc == GMI_OK) fused = true;
+    int n_stat_rows = 0;
+    rc = gmi::launch_train_chain(g, m, hp, rows, &n_stat_rows);
+    if (rc == GMI_OK) { fused = true; chained = true; *n_loss_blocks_out = n_stat_rows; }
     else if (rc != GMI_ERR_UNSUPPORTED) return rc;
   }
   if (fused) {
-    *n_loss_blocks_out = -1;     // statistics already summed (row kLossBlocksMax of stat_part)
+    if (!chained) *n_loss_blocks_out = -1;     // statistics already summed (row kLossBlocksMax of stat_part)
   } else {
   if (!gathered) {
     rc = gmi::launch_gather(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, &b->d);
