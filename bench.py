@@ -27,9 +27,8 @@ PEAK_FP32_TFLOPS = 157.3       # vector fp32
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/hbm_traffic_C2_C4.md (counter values
 # scaled by what the same counters read for a copy kernel of known size).  Keyed by (workload, class).
 MEASURED_TRAFFIC = {
-    ("C2", "wgrad"): 163.63e6, ("C2", "fused_rollout"): 23.37e6, ("C2", "linear_big256_dgrad"): 85.34e6,
-    ("C2", "linear_big256_fwd"): 38.70e6,
-    ("C4", "linear_big256_fwd"): 94.85e6, ("C4", "linear_big256_dgrad"): 155.95e6, ("C4", "wgrad"): 626.66e6,
+    ("C2", "chain_train"): 189.80e6, ("C2", "wgrad"): 163.62e6, ("C2", "fused_rollout"): 23.37e6,
+    ("C4", "chain_train"): 628.64e6, ("C4", "wgrad"): 672.37e6,
 }
 
 
@@ -224,9 +223,9 @@ def main() -> int:
     if dom_flops > 0 or dom_bytes > 0:          # stated by the launcher for exactly the timed launches
         flops_per_launch, bytes_per_launch = dom_flops / dom_launches, dom_bytes / dom_launches
     else:
-        w = work[dominant]
-        flops_per_launch = w.get("flops", 0.0) / w["launches"]
-        bytes_per_launch = w.get("bytes", 0.0) / w["launches"]
+        w = work.get(dominant, {"launches": 1})       # a class without stated work (only ever dominant under a profiler)
+        flops_per_launch = w.get("flops", 0.0) / max(w["launches"], 1)
+        bytes_per_launch = w.get("bytes", 0.0) / max(w["launches"], 1)
     # the roof that bounds this kernel: the larger of its matrix-core time and its HBM time at the peaks
     peak_flops = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
     if flops_per_launch / (peak_flops * 1e12) >= bytes_per_launch / (PEAK_HBM_GBS * 1e9):
