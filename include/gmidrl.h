@@ -304,6 +304,33 @@ int gmi_explore(gmi_profile_fn profile, void* profile_user, gmi_estimate_fn esti
                 const int32_t* num_env_values, int32_t n_env, int32_t* num_env_out, int32_t* gmi_per_gpu_out,
                 double* projected);
 
+/* ------------------------------------------------------------------ reduction strategy ------ */
+
+/* The three gradient-reduction strategies for trainer instances (Section 4.1, "Layout-aware Gradient
+ * Reduction"). */
+#define GMI_REDUCE_MULTI_PROCESS 0   /* reduce across the processes through host memory */
+#define GMI_REDUCE_MULTI_RING    1   /* one ring per instance index across GPUs, then a ring over the partial results */
+#define GMI_REDUCE_HIERARCHICAL  2   /* per GPU among its instances, then one leader per GPU across GPUs */
+
+/* Communication strategy selection (Algorithm 1).  gmis_per_gpu host i32 [n_gpus]: how many trainer instances
+ * each GPU hosts (the lengths of the paper's GMI-to-GPU mapping list).  n_gpus <= 1: multi-process; counts that
+ * differ between GPUs, or more instances per GPU than GPUs: hierarchical; otherwise multi-ring.  Host-only.  On
+ * the one GPU this build runs on the answer is always the first, and ppo_update_group performs that reduction
+ * in device memory. */
+int gmi_select_reduction(const int32_t* gmis_per_gpu, int32_t n_gpus, int32_t* strategy_out);
+
+/* Leaders of the hierarchical reduction's cross-GPU step (Section 4.1): on every GPU the instance whose id
+ * satisfies id % M == t, M = instances on that GPU.  gmi_ids host i32: the ids GPU by GPU; gpu_start host i32
+ * [n_gpus + 1]: GPU p owns gmi_ids[gpu_start[p] .. gpu_start[p+1]); leaders_out host i32 [n_gpus], -1 where no
+ * id has that residue. */
+int gmi_har_leaders(const int32_t* gmi_ids, const int32_t* gpu_start, int32_t n_gpus, int32_t t,
+                    int32_t* leaders_out);
+
+/* Time models of the three strategies (Table 3): g GPUs, t instances per GPU, m_p parameter bytes, b1 the
+ * inter-instance bandwidth through host memory, b2 the inter-GPU collective bandwidth (bytes/s). */
+int gmi_reduction_time(int32_t strategy, int32_t g, int32_t t, double m_p, double b1, double b2,
+                       double* seconds_out);
+
 /* Built-in timer for measurement runs (the paper's profile() step of Algorithm 2 measures a trial
  * run; here the unit is one kernel class = one kernel symbol).  class_mask bit c = 1: every launch of
  * kernel class c on this instance carries a pair of HIP events on the instance's stream that receive the

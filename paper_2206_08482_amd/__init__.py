@@ -25,7 +25,8 @@ EXPORTS = [
     "agent_act", "agent_value", "gmi_buffer_bind", "gmi_buffer_destroy", "collect_experience",
     "gae_compute", "ppo_update", "ppo_evaluate", "ppo_gradient", "adam_update", "gmi_noise_fill",
     "gmi_permutation", "gmi_profile_enable", "gmi_profile_classes", "gmi_profile_class_name", "gmi_profile_read",
-    "gmi_measure_peak", "gmi_bench_linear", "gmi_set_fusion", "rollout_collect", "gmi_profile_work", "gmi_explore", "ppo_update_group",
+    "gmi_measure_peak", "gmi_bench_linear", "gmi_set_fusion", "rollout_collect", "gmi_profile_work", "gmi_explore", "ppo_update_group", "gmi_select_reduction",
+    "gmi_har_leaders", "gmi_reduction_time",
 ]
 
 
@@ -97,6 +98,9 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "ppo_update": (C.c_int, [vp, vp, vp, C.POINTER(PPOHparams), vp]),
         "ppo_update_group": (C.c_int, [C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), i32, C.POINTER(PPOHparams), vp]),
         "ppo_evaluate": (C.c_int, [vp, vp, vp, C.POINTER(PPOHparams), vp, i32, vp]),
+        "gmi_select_reduction": (C.c_int, [C.POINTER(i32), i32, C.POINTER(i32)]),
+        "gmi_har_leaders": (C.c_int, [C.POINTER(i32), C.POINTER(i32), i32, i32, C.POINTER(i32)]),
+        "gmi_reduction_time": (C.c_int, [i32, i32, i32, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double)]),
         "ppo_gradient": (C.c_int, [vp, vp, vp, C.POINTER(PPOHparams), vp, i32, vp, vp]),
         "adam_update": (C.c_int, [vp, vp, vp, vp, vp, i64, C.POINTER(PPOHparams), u32]),
         "gmi_noise_fill": (C.c_int, [vp, u64, u32, u32, u32, i32, i32, vp]),
@@ -314,6 +318,35 @@ def ppo_update_group(gmis, models, bufs, hp: PPOHparams, stats_out=None) -> None
     assert len(models) == n and len(bufs) == n
     arr = lambda xs: (C.c_void_p * n)(*xs)
     _check(_lib.ppo_update_group(arr(gmis), arr(models), arr(bufs), n, C.byref(hp), _ptr(stats_out)))
+
+
+REDUCE_MULTI_PROCESS, REDUCE_MULTI_RING, REDUCE_HIERARCHICAL = 0, 1, 2
+
+
+def gmi_select_reduction(mpl) -> int:
+    """mpl: the GMI-to-GPU mapping list (ids of the trainer instances GPU by GPU)."""
+    counts = (C.c_int32 * max(len(mpl), 1))(*[len(x) for x in mpl])
+    out = C.c_int32(-1)
+    _check(_lib.gmi_select_reduction(counts, len(mpl), C.byref(out)))
+    return out.value
+
+
+def gmi_har_leaders(mpl, t: int):
+    ids = [i for li in mpl for i in li]
+    start = [0]
+    for li in mpl:
+        start.append(start[-1] + len(li))
+    a = (C.c_int32 * max(len(ids), 1))(*ids)
+    b = (C.c_int32 * len(start))(*start)
+    out = (C.c_int32 * max(len(mpl), 1))()
+    _check(_lib.gmi_har_leaders(a, b, len(mpl), t, out))
+    return [None if out[p] < 0 else out[p] for p in range(len(mpl))]
+
+
+def gmi_reduction_time(strategy: int, g: int, t: int, m_p: float, b1: float, b2: float) -> float:
+    out = C.c_double(0.0)
+    _check(_lib.gmi_reduction_time(strategy, g, t, m_p, b1, b2, C.byref(out)))
+    return out.value
 
 
 def ppo_evaluate(gmi: int, model: int, buf: int, hp: PPOHparams, idx, n: int, stats_out) -> None:

@@ -67,3 +67,56 @@ extern "C" int gmi_explore(gmi_profile_fn profile, void* profile_user, gmi_estim
   if (projected_out) *projected_out = have_best ? max_top : 0.0;
   return GMI_OK;
 }
+
+// ---------------------------------------------------------------------------------------------------------
+// Layout-aware gradient reduction, host logic (Section 4.1 of the paper): which of the three strategies a
+// layout of trainer instances calls for (Algorithm 1), which instance leads its GPU in the cross-GPU step of
+// the hierarchical form, and the time models of Table 3.  On one GPU only the first answer ever occurs and
+// this build performs that reduction in memory (ppo_update_group); the functions describe layouts this build
+// does not run.
+extern "C" int gmi_select_reduction(const int32_t* gmis_per_gpu, int32_t n_gpus, int32_t* strategy_out) {
+  if (!strategy_out) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_select_reduction: NULL output");
+  if (n_gpus < 0 || (n_gpus > 0 && !gmis_per_gpu)) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_select_reduction: bad layout");
+  for (int p = 0; p < n_gpus; ++p)
+    if (gmis_per_gpu[p] < 0) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_select_reduction: negative count for GPU %d", p);
+  if (n_gpus <= 1) {                               // all instances on the same GPU
+    *strategy_out = GMI_REDUCE_MULTI_PROCESS;
+    return GMI_OK;
+  }
+  bool equal = true;                               // do all GPUs host the same number of instances?
+  for (int p = 1; p < n_gpus; ++p) equal = equal && gmis_per_gpu[p] == gmis_per_gpu[0];
+  if (!equal || gmis_per_gpu[0] > n_gpus) *strategy_out = GMI_REDUCE_HIERARCHICAL;
+  else *strategy_out = GMI_REDUCE_MULTI_RING;
+  return GMI_OK;
+}
+
+extern "C" int gmi_har_leaders(const int32_t* gmi_ids, const int32_t* gpu_start, int32_t n_gpus, int32_t t,
+                               int32_t* leaders_out) {
+  if (n_gpus < 0 || (n_gpus > 0 && (!gpu_start || !leaders_out)))
+    GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_har_leaders: bad arguments");
+  for (int p = 0; p < n_gpus; ++p) {
+    const int b = gpu_start[p], e = gpu_start[p + 1];
+    if (e < b || (e > b && !gmi_ids)) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_har_leaders: bad range for GPU %d", p);
+    const int m = e - b;
+    leaders_out[p] = -1;
+    for (int i = b; i < e; ++i)
+      if (gmi_ids[i] >= 0 && gmi_ids[i] % m == t) { leaders_out[p] = gmi_ids[i]; break; }
+  }
+  return GMI_OK;
+}
+
+extern "C" int gmi_reduction_time(int32_t strategy, int32_t g, int32_t t, double m_p, double b1, double b2,
+                                  double* seconds_out) {
+  if (!seconds_out) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_reduction_time: NULL output");
+  if (g < 1 || t < 1) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_reduction_time: need g >= 1 GPUs and t >= 1 instances per GPU");
+  const double gd = g, td = t;
+  switch (strategy) {
+    case GMI_REDUCE_MULTI_PROCESS: *seconds_out = 2.0 * (gd * td - 1.0) * m_p / (gd * td * b1); break;
+    case GMI_REDUCE_MULTI_RING: *seconds_out = 2.0 * (gd - 1.0) * (td + 1.0) * m_p / (gd * b2); break;
+    case GMI_REDUCE_HIERARCHICAL:
+      *seconds_out = 2.0 * (gd - 1.0) * m_p / (gd * b2) + 2.0 * (td - 1.0) * m_p / (td * b1);
+      break;
+    default: GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_reduction_time: unknown strategy %d", strategy);
+  }
+  return GMI_OK;
+}
