@@ -16,7 +16,9 @@
  *    read during the call.  The library allocates device memory only inside *_bind / gmi_create
  *    and frees it in the matching *_destroy; no compute call allocates.
  *  - Every compute call is asynchronous on its instance's stream.  Ordering between instances is
- *    established only by gmi_transfer(); gmi_sync() blocks the host.
+ *    established only by gmi_transfer(); gmi_sync() blocks the host.  The library never waits for
+ *    streams it does not own: whatever the caller put into a dev buffer on another stream (an
+ *    allocator's fill, a copy) must have completed before the call that touches the buffer is made.
  *  - All randomness is a pure function of (seed, stream id, step, env index, element) through
  *    Philox4x32-10: counter = (env index, step, stream id, block), key = (seed low, seed high).
  *    Stream ids: 0 action noise, 1 environment noise, 2 done draw, 3 reset state, 4 shuffle.

@@ -10,7 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libgmidrl.so")
-SOURCES = ["core.hip", "env.hip", "experience.hip", "mlp.hip", "model.hip", "update.hip", "peaks.hip", "fused.hip", "select.hip", "chain.hip"]
+SOURCES = ["core.hip", "env.hip", "experience.hip", "mlp.hip", "model.hip", "update.hip", "peaks.hip", "fused.hip", "select.hip", "chain.hip",
+           "chain_p0.hip", "chain_p1.hip", "chain_p2.hip", "chain_p3.hip", "chain_p4.hip", "chain_p5.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Wno-unused-value", "-Wno-unused-result", "-fhip-fp32-correctly-rounded-divide-sqrt",
          # keep fp32 arithmetic scalar: packed fp32 forms are not trusted on the test machines
@@ -38,7 +39,7 @@ def _compile(src: str) -> str:
 
 def build(verbose: bool = True) -> str:
     os.makedirs(BUILD_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+    with ThreadPoolExecutor(max_workers=8) as pool:
         objs = list(pool.map(_compile, SOURCES))
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)

@@ -1,127 +1,9 @@
-// Register-chained trainer kernel: forward pass, clipped-surrogate / value loss and the whole input-gradient
-// chain of one minibatch (stage (ii) of Section 5.1 of the paper, the "DRL Trainer" role of Section 3) in one
-// launch per minibatch.
-//
-// A wave owns 32 samples and carries their activations from layer to layer IN REGISTERS.  Every product is
-// computed transposed, H^T = W X^T: the weights are the first operand of the 32x32x16 matrix instruction
-// (row = output feature), the activations the second (lane = sample).  The result then has lane = sample and
-// its 16 registers hold 16 of the tile's 32 features, which is -- up to a fixed permutation of the features
-// inside each 16-wide k step -- exactly the second-operand layout of the next layer.  A permutation of the
-// contraction index is free as long as the weights use the same one, so the weights are kept in a second
-// shadow copy (the "chain stream") whose 1 KiB blocks are already permuted and already in the order the kernel
-// consumes them.  No activation ever goes through LDS on its way to the next layer.
-//
-// The 4 or 8 waves of a workgroup walk the stream in lockstep; the stream is staged through a
-// double-buffered LDS slot (16 KiB chunks, global loads issued several chunks ahead into registers), so a
-// workgroup reads every weight once for its 128 or 256 samples.  Activations and gradients that the
-// weight-gradient kernel needs are written row-major through a small per-wave LDS transposition buffer, so
-// that rows leave the chip as 64..256-byte pieces.
-#include "internal.h"
+// Host side of the register-chained trainer kernel (chain_kernel.h): the weight stream in the shadow, its packing
+// kernel and the launch.  The kernel itself is compiled once per model shape in chain_p<k>.hip.
+#include "chain_kernel.h"
 
 namespace {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
-typedef float float2v __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
-
-__device__ __forceinline__ float elu_f(float z) {
-  return z > 0.f ? z : (__builtin_amdgcn_exp2f(z * 1.44269504f) - 1.0f);
-}
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  float2v v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2v));
-}
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
-
-// ---------------------------------------------------------------------------------------------------------
-// The plan: which 1 KiB weight blocks the kernel consumes in which order.  Pure functions of the padded layer
-// widths d[0..nl] (d[0] = input, d[nl] = head), used at compile time by the kernel and at run time by the
-// host when it describes the stream to the packing kernel.
-//
-// Segment s < nl is the forward product of layer s (K = d[s] in, F = d[s+1] out); segment s >= nl is the
-// input-gradient product of layer l = 2 nl - 1 - s (K = d[l+1], F = d[l]), l = nl-1 .. 1.  A segment's F/32
-// feature tiles are cut into groups of 4, then 2, then 1 tiles; a group's blocks are ordered k step major
-// (block (ks, t) = tile t of the group, k step ks); a chunk is 16 / (group size) k steps of one group,
-// i.e. at most 16 blocks.
-struct ChainDims {
-  int nl;
-  int d[GMI_MAX_HIDDEN + 2];
-};
-__host__ __device__ constexpr int cd_nseg(const ChainDims& D) { return 2 * D.nl - 1; }
-__host__ __device__ constexpr int cd_layer(const ChainDims& D, int s) { return s < D.nl ? s : 2 * D.nl - 1 - s; }
-__host__ __device__ constexpr int cd_K(const ChainDims& D, int s) { return s < D.nl ? D.d[s] : D.d[cd_layer(D, s) + 1]; }
-__host__ __device__ constexpr int cd_F(const ChainDims& D, int s) { return s < D.nl ? D.d[s + 1] : D.d[cd_layer(D, s)]; }
-__host__ __device__ constexpr int cd_ngroups(int nft) { return nft / 4 + ((nft & 3) >= 2 ? 1 : 0) + (nft & 1); }
-__host__ __device__ constexpr int cd_gsize(int nft, int gi) {
-  const int full = nft / 4;
-  if (gi < full) return 4;
-  if (gi == full && (nft & 3) >= 2) return 2;
-  return 1;
-}
-__host__ __device__ constexpr int cd_gtile0(int nft, int gi) {
-  const int full = nft / 4;
-  if (gi <= full) return 4 * gi;
-  return 4 * full + 2;
-}
-__host__ __device__ constexpr int cd_kcsteps(int gs) { return 16 / gs; }
-__host__ __device__ constexpr int cd_group_chunks(int nks, int gs) { return (nks + cd_kcsteps(gs) - 1) / cd_kcsteps(gs); }
-__host__ __device__ constexpr int cd_seg_chunks(const ChainDims& D, int s) {
-  const int nft = cd_F(D, s) / 32, nks = cd_K(D, s) / 16;
-  int n = 0;
-  for (int gi = 0; gi < cd_ngroups(nft); ++gi) n += cd_group_chunks(nks, cd_gsize(nft, gi));
-  return n;
-}
-__host__ __device__ constexpr int cd_seg_blocks(const ChainDims& D, int s) { return (cd_F(D, s) / 32) * (cd_K(D, s) / 16); }
-__host__ __device__ constexpr int cd_nchunks(const ChainDims& D) {
-  int n = 0;
-  for (int s = 0; s < cd_nseg(D); ++s) n += cd_seg_chunks(D, s);
-  return n;
-}
-__host__ __device__ constexpr int cd_nblocks(const ChainDims& D) {
-  int n = 0;
-  for (int s = 0; s < cd_nseg(D); ++s) n += cd_seg_blocks(D, s);
-  return n;
-}
-__host__ __device__ constexpr int cd_maxdim(const ChainDims& D) {
-  int m = 0;
-  for (int i = 0; i <= D.nl; ++i) m = D.d[i] > m ? D.d[i] : m;
-  return m;
-}
-
-struct ChunkInfo {
-  int seg, gi, gs, tile0, ks0, nks, blk_off, nblk;
-  bool first, last;      // first / last chunk of its group
-};
-__host__ __device__ constexpr ChunkInfo cd_chunk(const ChainDims& D, int c) {
-  ChunkInfo ci = {0, 0, 0, 0, 0, 0, 0, 0, false, false};
-  int blk = 0, cc = 0;
-  for (int s = 0; s < cd_nseg(D); ++s) {
-    const int nft = cd_F(D, s) / 32, nks = cd_K(D, s) / 16;
-    for (int gi = 0; gi < cd_ngroups(nft); ++gi) {
-      const int gs = cd_gsize(nft, gi), nc = cd_group_chunks(nks, gs), kcs = cd_kcsteps(gs);
-      for (int kc = 0; kc < nc; ++kc) {
-        const int k0 = kc * kcs, n = (nks - k0) < kcs ? (nks - k0) : kcs;
-        if (cc == c) {
-          ci.seg = s; ci.gi = gi; ci.gs = gs; ci.tile0 = cd_gtile0(nft, gi); ci.ks0 = k0; ci.nks = n;
-          ci.blk_off = blk; ci.nblk = n * gs; ci.first = kc == 0; ci.last = kc == nc - 1;
-          return ci;
-        }
-        blk += n * gs;
-        ++cc;
-      }
-    }
-  }
-  return ci;
-}
-
-// number of k steps in the chunks before chunk c (the operand ring below is indexed by it)
-__host__ __device__ constexpr int cd_ksteps_before(const ChainDims& D, int c) {
-  int n = 0;
-  for (int i = 0; i < c; ++i) n += cd_chunk(D, i).nks;
-  return n;
-}
+using namespace gmi_chain;
 
 // ---------------------------------------------------------------------------------------------------------
 // Packing kernel: builds one net's chain stream from the row-major bf16 shadows.  One thread per lane of a
@@ -181,475 +63,6 @@ __global__ __launch_bounds__(256) void chain_pack_kernel(PackTable t0, PackTable
   reinterpret_cast<uint4*>(out)[(int64_t)blk * 64 + lane] = v;
 }
 
-// ---------------------------------------------------------------------------------------------------------
-struct ChainArgs {
-  const char* wstream[2];                          // chain stream of the policy / value net
-  const float* bias[2][GMI_MAX_HIDDEN + 1];        // fp32 [out_pad] per layer
-  const uint16_t* x0;                              // [rows, d[0]] bf16, the gathered observations
-  uint16_t* h[2][GMI_MAX_HIDDEN + 1];              // h[net][l], l = 1 .. nl-1: input of layer l, [rows, d[l]]
-  uint16_t* dz[2][GMI_MAX_HIDDEN + 1];             // dz[net][l], l = 0 .. nl-1: gradient at layer l's output, [rows, d[l+1]]
-  const float* log_std;
-  const float *mb_act, *mb_logp, *mb_adv, *mb_ret; // gathered per-sample rows
-  int rows, act_dim;
-  float clip, c_v;
-  float* stat_part;                                // [tiles][kStatStride + act_dim]
-#ifdef GMI_CHAIN_TIMING
-  long long* dbg;                                  // [n_chunks + 1] clock at the start of every chunk (workgroup 0, wave 0)
-#endif
-};
-
-constexpr int kSlotBytes = 16 * 1024;              // one chunk
-constexpr int kSlots = 3;                          // chunk c lives in slot c % 3: while chunk c is multiplied, chunk c+1 is
-                                                   // already visible (its first operands are prefetched) and c+2 lands
-constexpr int kScrStride = 272;                    // bytes per row of a wave's transposition buffer (256 + 16)
-constexpr int kScrBytes = 32 * kScrStride;
-
-// A compile-time description of one model shape: NW waves per workgroup, DEPTH chunks of weights in flight,
-// then the padded widths d[0..nl].
-template <int NW_, int DEPTH_, int... DIMS>
-struct ChainShape {
-  static constexpr int NW = NW_, NT = NW_ * 64, DEPTH = DEPTH_;
-  static constexpr int NL = (int)sizeof...(DIMS) - 1;
-  static constexpr int LPT = (16 * 64 + NT - 1) / NT;      // 16-byte pieces of a chunk per thread
-  static constexpr ChainDims dims() { return ChainDims{NL, {DIMS...}}; }
-  static constexpr int maxks() { return cd_maxdim(dims()) / 16; }
-  static constexpr int nch() { return cd_nchunks(dims()); }
-  static constexpr int bias_total() {
-    int n = 0;
-    for (int l = 0; l < NL; ++l) n += dims().d[l + 1];
-    return n;
-  }
-  static constexpr int bias_off(int l) {
-    int n = 0;
-    for (int i = 0; i < l; ++i) n += dims().d[i + 1];
-    return n;
-  }
-  static constexpr size_t lds_bytes() {
-    return kSlots * (size_t)kSlotBytes + (size_t)NW * kScrBytes + (size_t)bias_total() * 4 + (size_t)(NW * 40 + 64) * 4;
-  }
-};
-
-template <class S>
-struct Ctx {
-  uint4 xa[S::maxks()], xb[S::maxks()];      // activation operands of the current layer: in / out (ping-pong by segment)
-  floatx16 acc[4];
-  uint4 stage[S::DEPTH][S::LPT];         // weight chunks in flight
-  bf16x8 wq[3][4];                       // weight operands of k steps g, g+1, g+2 (ring indexed by g % 3)
-  uint4 ht[8];                           // stored activations of the group (input-gradient segments)
-  float l_act[16], l_lo, l_ad, l_rt;     // this lane's loss inputs (fetched at kernel start): actions of its 16
-                                         // features, old log-prob, advantage, return
-  const uint4* wsrc;                     // this net's stream
-  char* lds;                             // workgroup LDS base
-  char* scr;                             // this wave's transposition buffer
-  const float* s_bias;
-  float* s_red;                          // [NW][40]
-  int tid, lane, wave, s, hh;            // s = lane % 32 (sample in the wave's tile), hh = lane / 32
-  int row0, net;
-};
-
-// Every chunk moves as a full 16 KiB: pieces past a short chunk's end belong to the next chunk (or to the
-// stream's tail padding) and land in slot space nobody reads.  No branch surrounds a load or store: the
-// memory-counter bookkeeping of the compiler then waits for exactly the chunk that is needed (with a branch it
-// waited for almost every load in flight).
-template <class S, int C>
-__device__ __forceinline__ void issue_chunk(Ctx<S>& c) {
-  if constexpr (C < S::nch()) {
-    constexpr ChunkInfo ci = cd_chunk(S::dims(), C);
-#pragma unroll
-    for (int i = 0; i < S::LPT; ++i) c.stage[C % S::DEPTH][i] = c.wsrc[(int64_t)ci.blk_off * 64 + c.tid + i * S::NT];
-  }
-}
-template <class S, int C>
-__device__ __forceinline__ void land_chunk(Ctx<S>& c) {
-  if constexpr (C < S::nch()) {
-    uint4* slot = reinterpret_cast<uint4*>(c.lds + (C % kSlots) * kSlotBytes);
-#pragma unroll
-    for (int i = 0; i < S::LPT; ++i) slot[c.tid + i * S::NT] = c.stage[C % S::DEPTH][i];
-  }
-}
-
-// Row-major store of a group's packed results: the wave's transposition buffer holds [32 samples][GS*32
-// features] bf16; rows leave as 64 * GS byte pieces.
-template <int GS>
-__device__ __forceinline__ void scr_to_global(const char* scr, int lane, uint16_t* dst, int ld, int col0, int row0,
-                                              int rows) {
-  constexpr int LPR = 4 * GS, RPI = 64 / LPR;    // lanes per row, rows per instruction
-#pragma unroll
-  for (int it = 0; it < 32 / RPI; ++it) {
-    const int r = it * RPI + lane / LPR, ch = lane % LPR;
-    const uint4 v = *reinterpret_cast<const uint4*>(scr + r * kScrStride + ch * 16);
-    *reinterpret_cast<uint4*>(dst + (int64_t)(row0 + r) * ld + col0 + ch * 8) = v;     // arrays hold whole tiles
-  }
-}
-template <int GS>
-__device__ __forceinline__ void global_to_regs(uint4* ht, int lane, const uint16_t* src, int ld, int col0, int row0,
-                                               int rows) {
-  constexpr int LPR = 4 * GS, RPI = 64 / LPR;
-#pragma unroll
-  for (int it = 0; it < 32 / RPI; ++it) {
-    const int r = it * RPI + lane / LPR, ch = lane % LPR;
-    ht[it] = *reinterpret_cast<const uint4*>(src + (int64_t)(row0 + r) * ld + col0 + ch * 8);
-  }
-}
-template <int GS>
-__device__ __forceinline__ void regs_to_scr(const uint4* ht, int lane, char* scr) {
-  constexpr int LPR = 4 * GS, RPI = 64 / LPR;
-#pragma unroll
-  for (int it = 0; it < 32 / RPI; ++it) {
-    const int r = it * RPI + lane / LPR, ch = lane % LPR;
-    *reinterpret_cast<uint4*>(scr + r * kScrStride + ch * 16) = ht[it];
-  }
-}
-
-__device__ __forceinline__ float wave_sum64(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
-
-// Loss on the wave's 32 samples, from the head's accumulators (lane = sample s, half hh; register i = feature
-// 8 (i / 4) + 4 hh + i % 4).  Leaves the head gradient as the first two k steps of `xo` and in the wave's
-// transposition buffer, and per-wave partial sums in s_red[wave][0..2] (policy: surrogate, kl, clipped;
-// value: squared error in [0]) and s_red[wave][8 + f] (log_std gradient partials).
-// This lane's loss inputs, fetched one layer before the head needs them (unconditional loads: rows and features
-// past the end read a valid neighbour, their results are dropped).
-template <class S>
-__device__ __forceinline__ void fetch_loss_inputs(Ctx<S>& c, const ChainArgs& a) {
-  const int row = c.row0 + c.s;
-  const int rowc = row < a.rows ? row : a.rows - 1;
-  c.l_lo = a.mb_logp[rowc]; c.l_ad = a.mb_adv[rowc]; c.l_rt = a.mb_ret[rowc];
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int f = 8 * (i >> 2) + 4 * c.hh + (i & 3);
-    const int fc = f < a.act_dim ? f : a.act_dim - 1;
-    c.l_act[i] = a.mb_act[(int64_t)rowc * a.act_dim + fc];
-  }
-}
-
-template <class S>
-__device__ __forceinline__ void loss_epilogue(Ctx<S>& c, const ChainArgs& a, uint4* xo) {
-  constexpr int HB = S::bias_off(S::NL - 1);
-  const int A = a.act_dim;
-  const int row = c.row0 + c.s;
-  const bool ok = row < a.rows;
-  const float inv_m = 1.0f / (float)a.rows;
-  const floatx16& acc = c.acc[0];
-  float d[16];
-  float* red = c.s_red + c.wave * 40;
-  if (c.net == 0) {
-    // s_ls[f] = log_std, s_ls[32 + f] = exp(-log_std) (0 for f >= A), staged at kernel start
-    const float* s_ls = c.s_red + S::NW * 40;
-    float z[16], isg[16];
-    float lp = 0.f;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int f0 = 8 * q + 4 * c.hh;
-      const float4 ls4 = *reinterpret_cast<const float4*>(s_ls + f0);
-      const float4 ig4 = *reinterpret_cast<const float4*>(s_ls + 32 + f0);
-      const float4 b4 = *reinterpret_cast<const float4*>(c.s_bias + HB + f0);
-      const float lsv[4] = {ls4.x, ls4.y, ls4.z, ls4.w}, igv[4] = {ig4.x, ig4.y, ig4.z, ig4.w};
-      const float bv[4] = {b4.x, b4.y, b4.z, b4.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int i = 4 * q + e;
-        const float mu = acc[i] + bv[e];
-        isg[i] = igv[e];
-        z[i] = (c.l_act[i] - mu) * igv[e];                    // 0 for f >= A
-        lp += f0 + e < A ? -0.5f * z[i] * z[i] - lsv[e] - 0.918938533204672742f : 0.f;
-      }
-    }
-    lp += __shfl_xor(lp, 32, 64);                   // the other half holds the other 16 features
-    float s_pl = 0.f, s_kl = 0.f, s_cf = 0.f, g_lp = 0.f;
-    if (ok) {
-      const float lo = c.l_lo, ad = c.l_ad;
-      const float ratio = __expf(lp - lo);
-      const float u1 = ratio * ad;
-      const float u2 = fminf(fmaxf(ratio, 1.0f - a.clip), 1.0f + a.clip) * ad;
-      g_lp = (u1 <= u2) ? -(ad * ratio) * inv_m : 0.f;
-      if (c.hh == 0) {                               // each sample counts once
-        s_pl = -fminf(u1, u2);
-        s_kl = lo - lp;
-        s_cf = fabsf(ratio - 1.0f) > a.clip ? 1.f : 0.f;
-      }
-    }
-    // log_std gradient partials g_lp (z^2 - 1): transposed through the wave's LDS buffer as [feature][sample]
-    // fp32, then lane f < 32 sums feature f's 32 samples in a fixed order
-    float* tp = reinterpret_cast<float*>(c.scr);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int f = 8 * (i >> 2) + 4 * c.hh + (i & 3);
-      d[i] = g_lp * z[i] * isg[i];
-      tp[f * 33 + c.s] = g_lp * (z[i] * z[i] - 1.0f);
-    }
-    if (c.lane < 32) {
-      float sum = 0.f;
-#pragma unroll
-      for (int k = 0; k < 32; ++k) sum += tp[c.lane * 33 + k];
-      red[8 + c.lane] = c.lane < A ? sum : 0.f;
-    }
-    s_pl = wave_sum64(s_pl); s_kl = wave_sum64(s_kl); s_cf = wave_sum64(s_cf);
-    if (c.lane == 0) { red[0] = s_pl; red[1] = s_kl; red[2] = s_cf; }
-  } else {
-    float s_vl = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) d[i] = 0.f;
-    if (ok && c.hh == 0) {
-      const float dv = acc[0] + c.s_bias[HB] - c.l_rt;
-      s_vl = dv * dv;
-      d[0] = 2.0f * a.c_v * dv * inv_m;
-    }
-    s_vl = wave_sum64(s_vl);
-    if (c.lane == 0) red[0] = s_vl;
-  }
-  uint32_t w[8];
-#pragma unroll
-  for (int q = 0; q < 8; ++q) w[q] = pack_bf16(d[2 * q], d[2 * q + 1]);
-  xo[0] = make_uint4(w[0], w[1], w[2], w[3]);
-  xo[1] = make_uint4(w[4], w[5], w[6], w[7]);
-#pragma unroll
-  for (int q = 0; q < 4; ++q)
-    *reinterpret_cast<uint2*>(c.scr + c.s * kScrStride + (8 * q + 4 * c.hh) * 2) = make_uint2(w[2 * q], w[2 * q + 1]);
-  scr_to_global<1>(c.scr, c.lane, a.dz[c.net][S::NL - 1], 32, 0, c.row0, a.rows);
-  // workgroup sums -> this tile's row of the statistics partials
-  __syncthreads();
-  float* out = a.stat_part + (int64_t)blockIdx.x * (gmi::kStatStride + A);
-  if (c.net == 0) {
-    if (c.tid < 3) {
-      float v = 0.f;
-      for (int wv = 0; wv < S::NW; ++wv) v += c.s_red[wv * 40 + c.tid];
-      out[c.tid == 0 ? 0 : (c.tid == 1 ? 3 : 4)] = v;
-    }
-    if (c.tid == 3) {
-      float ent = 0.f;
-      if (blockIdx.x == 0)
-        for (int j = 0; j < A; ++j) ent += a.log_std[j] + 1.418938533204672742f;
-      out[2] = ent;
-      out[5] = out[6] = out[7] = 0.f;
-    }
-    if (c.tid >= 64 && c.tid < 64 + A) {
-      const int j = c.tid - 64;
-      float v = 0.f;
-      for (int wv = 0; wv < S::NW; ++wv) v += c.s_red[wv * 40 + 8 + j];
-      out[gmi::kStatStride + j] = v;
-    }
-  } else if (c.tid == 0) {
-    float v = 0.f;
-    for (int wv = 0; wv < S::NW; ++wv) v += c.s_red[wv * 40];
-    out[1] = v;
-  }
-}
-
-template <class S, int C, int K, int RING>
-__device__ __forceinline__ void fetch_kstep(Ctx<S>& c) {
-  if constexpr (C < S::nch()) {
-    constexpr ChunkInfo ci = cd_chunk(S::dims(), C);
-    if constexpr (K >= ci.nks) {
-      fetch_kstep<S, C + 1, K - ci.nks, RING>(c);
-    } else {
-      const char* slot = c.lds + (C % kSlots) * kSlotBytes + c.lane * 16;
-#pragma unroll
-      for (int t = 0; t < ci.gs; ++t)
-        c.wq[RING][t] = *reinterpret_cast<const bf16x8*>(slot + (K * ci.gs + t) * 1024);
-    }
-  }
-}
-
-// number of operands fetch_kstep<S, C, K, *> reads
-template <class S, int C, int K>
-__host__ __device__ constexpr int fetch_count() {
-  if constexpr (C < S::nch()) {
-    constexpr ChunkInfo ci = cd_chunk(S::dims(), C);
-    if constexpr (K >= ci.nks) return fetch_count<S, C + 1, K - ci.nks>();
-    else return ci.gs;
-  } else {
-    return 0;
-  }
-}
-
-template <class S, int C, int K>
-__device__ __forceinline__ void compute_ksteps(Ctx<S>& c, const uint4* xi) {
-  constexpr ChunkInfo ci = cd_chunk(S::dims(), C);
-  if constexpr (K < ci.nks) {
-    constexpr int g = cd_ksteps_before(S::dims(), C) + K;
-    fetch_kstep<S, C, K + 2, (g + 2) % 3>(c);
-    const bf16x8 xk = __builtin_bit_cast(bf16x8, xi[ci.ks0 + K]);
-#pragma unroll
-    for (int t = 0; t < ci.gs; ++t)
-      c.acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c.wq[g % 3][t], xk, c.acc[t], 0, 0, 0);
-    // nothing moves across this point: the schedule keeps the LDS reads of k step g+2 ahead of the products of
-    // k step g (left to itself the scheduler sinks every read to just before its use, and with one wave per
-    // SIMD each product then waits a full LDS round trip)
-    __builtin_amdgcn_sched_barrier(0);
-    compute_ksteps<S, C, K + 1>(c, xi);
-  }
-}
-
-template <class S, int C>
-__device__ __forceinline__ void chain_step(Ctx<S>& c, const ChainArgs& a) {
-  constexpr ChainDims D = S::dims();
-  constexpr ChunkInfo ci = cd_chunk(D, C);
-  constexpr int seg = ci.seg, NL = S::NL;
-  constexpr bool bwd = seg >= NL;
-  constexpr int layer = cd_layer(D, seg);
-  constexpr int GS = ci.gs;
-  // even segments read xa and write xb, odd ones the other way round
-  uint4* xi = (seg & 1) ? c.xb : c.xa;
-  uint4* xo = (seg & 1) ? c.xa : c.xb;
-#ifdef GMI_CHAIN_TIMING
-  if (blockIdx.x == 0 && blockIdx.y == 0 && c.tid == 0) a.dbg[C] = __builtin_readcyclecounter();
-#endif
-
-  issue_chunk<S, C + 1 + S::DEPTH>(c);
-  if constexpr (seg == NL - 2 && ci.gi == 0 && ci.first) fetch_loss_inputs<S>(c, a);
-
-  if constexpr (bwd && ci.last)        // stored activations of this group's features, for ELU'
-    global_to_regs<GS>(c.ht, c.lane, a.h[c.net][layer], D.d[layer], 32 * ci.tile0, c.row0, a.rows);
-
-  if constexpr (ci.first) {
-#pragma unroll
-    for (int t = 0; t < GS; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) c.acc[t][v] = 0.f;
-  }
-  compute_ksteps<S, C, 0>(c, xi);
-
-  if constexpr (ci.last) {
-    if constexpr (!bwd && layer == NL - 1) {
-      static_assert(GS == 1, "the head is one 32-wide tile");
-      loss_epilogue<S>(c, a, xo);
-    } else {
-      if constexpr (bwd) regs_to_scr<GS>(c.ht, c.lane, c.scr);
-      constexpr int boff = bwd ? 0 : S::bias_off(layer);
-#pragma unroll
-      for (int t = 0; t < GS; ++t) {
-        uint32_t w[8];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          float v0 = c.acc[t][4 * q + 0], v1 = c.acc[t][4 * q + 1], v2 = c.acc[t][4 * q + 2], v3 = c.acc[t][4 * q + 3];
-          char* sp = c.scr + c.s * kScrStride + (32 * t + 8 * q + 4 * c.hh) * 2;
-          if constexpr (bwd) {
-            // times ELU'(z) through the stored output h = ELU(z): 1 if h > 0 else h + 1
-            const uint2 hv = *reinterpret_cast<const uint2*>(sp);
-            const float h0 = bf16_lo(hv.x), h1 = bf16_hi(hv.x), h2 = bf16_lo(hv.y), h3 = bf16_hi(hv.y);
-            v0 *= h0 > 0.f ? 1.f : h0 + 1.f; v1 *= h1 > 0.f ? 1.f : h1 + 1.f;
-            v2 *= h2 > 0.f ? 1.f : h2 + 1.f; v3 *= h3 > 0.f ? 1.f : h3 + 1.f;
-          } else {
-            const float4 bv = *reinterpret_cast<const float4*>(c.s_bias + boff + 32 * (ci.tile0 + t) + 8 * q + 4 * c.hh);
-            v0 = elu_f(v0 + bv.x); v1 = elu_f(v1 + bv.y); v2 = elu_f(v2 + bv.z); v3 = elu_f(v3 + bv.w);
-          }
-          w[2 * q] = pack_bf16(v0, v1);
-          w[2 * q + 1] = pack_bf16(v2, v3);
-          *reinterpret_cast<uint2*>(sp) = make_uint2(w[2 * q], w[2 * q + 1]);
-        }
-        xo[2 * (ci.tile0 + t)] = make_uint4(w[0], w[1], w[2], w[3]);
-        xo[2 * (ci.tile0 + t) + 1] = make_uint4(w[4], w[5], w[6], w[7]);
-      }
-      if constexpr (bwd)
-        scr_to_global<GS>(c.scr, c.lane, a.dz[c.net][layer - 1], D.d[layer], 32 * ci.tile0, c.row0, a.rows);
-      else
-        scr_to_global<GS>(c.scr, c.lane, a.h[c.net][layer + 1], D.d[layer + 1], 32 * ci.tile0, c.row0, a.rows);
-    }
-  }
-
-  if constexpr (C + 1 < S::nch()) {
-    land_chunk<S, C + 2>(c);
-    __syncthreads();
-    chain_step<S, C + 1>(c, a);
-  }
-}
-
-template <class S>
-__global__ __launch_bounds__(S::NW * 64) void train_chain_kernel(ChainArgs a) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  constexpr ChainDims D = S::dims();
-  Ctx<S> c;
-  c.tid = threadIdx.x;
-  c.lane = c.tid & 63;
-  c.wave = __builtin_amdgcn_readfirstlane(c.tid >> 6);
-  c.s = c.lane & 31;
-  c.hh = c.lane >> 5;
-  c.net = blockIdx.y;
-  c.row0 = (blockIdx.x * S::NW + c.wave) * 32;
-  c.lds = reinterpret_cast<char*>(smem_raw);
-  c.scr = c.lds + kSlots * kSlotBytes + c.wave * kScrBytes;
-  float* s_bias = reinterpret_cast<float*>(c.lds + kSlots * kSlotBytes + S::NW * kScrBytes);
-  c.s_bias = s_bias;
-  c.s_red = s_bias + S::bias_total();
-  c.wsrc = reinterpret_cast<const uint4*>(a.wstream[c.net]);
-
-  // weights first (the longest latency), then biases and the input rows.  Chunk c travels in register set
-  // c % DEPTH: chunk 0 is landed at once, which frees its set for chunk DEPTH.
-  static_assert(S::DEPTH >= 1 && S::DEPTH <= 4, "1..4 chunks in flight");
-  issue_chunk<S, 0>(c);
-  land_chunk<S, 0>(c);
-  issue_chunk<S, 1>(c);
-  if constexpr (S::DEPTH > 1) issue_chunk<S, 2>(c);
-  if constexpr (S::DEPTH > 2) issue_chunk<S, 3>(c);
-  if constexpr (S::DEPTH > 3) issue_chunk<S, 4>(c);
-  {
-    int off = 0;
-#pragma unroll
-    for (int l = 0; l < S::NL; ++l) {
-      for (int f = c.tid; f < D.d[l + 1]; f += S::NT) s_bias[off + f] = a.bias[c.net][l][f];
-      off += D.d[l + 1];
-    }
-  }
-  for (int i = c.tid; i < S::NW * 40; i += S::NT) c.s_red[i] = 0.f;
-  if (c.tid < 32) {                      // per-feature constants of the Gaussian log-prob (policy net)
-    const int fc = c.tid < a.act_dim ? c.tid : a.act_dim - 1;
-    const float ls = a.log_std[fc];
-    c.s_red[S::NW * 40 + c.tid] = ls;
-    c.s_red[S::NW * 40 + 32 + c.tid] = c.tid < a.act_dim ? expf(-ls) : 0.f;
-  }
-  {
-    // first layer's operand in natural order: lane (s, hh) holds features 16 ks + 8 hh .. + 7 of its sample
-    const int row = c.row0 + c.s;
-    const uint16_t* xr = a.x0 + (int64_t)row * D.d[0] + 8 * c.hh;
-#pragma unroll
-    for (int ks = 0; ks < D.d[0] / 16; ++ks)
-      c.xa[ks] = *reinterpret_cast<const uint4*>(xr + 16 * ks);       // rows past the batch: whatever the tile holds
-  }
-  land_chunk<S, 1>(c);
-  __syncthreads();
-  fetch_kstep<S, 0, 0, 0>(c);
-  fetch_kstep<S, 0, 1, 1>(c);
-  chain_step<S, 0>(c, a);
-}
-
-// The shapes with a compiled kernel: padded widths of the three benchmark model families (observation and
-// hidden widths rounded up to multiples of 32, 32-wide head), narrow ones with 8 waves per workgroup.
-using ShapeC2 = ChainShape<8, 3, 64, 256, 128, 64, 32>;
-using ShapeC3 = ChainShape<4, 3, 128, 416, 224, 128, 32>;
-using ShapeC4 = ChainShape<4, 3, 224, 512, 512, 256, 128, 32>;
-
-template <class S>
-bool shape_matches(const ModelLayout& L) {
-  constexpr ChainDims D = S::dims();
-  if (L.n_layers != D.nl) return false;
-  for (int net = 0; net < 2; ++net)
-    for (int l = 0; l < D.nl; ++l)
-      if (L.net[net][l].in_pad != D.d[l] || L.net[net][l].out_pad != D.d[l + 1]) return false;
-  return true;
-}
-
-template <class S>
-int launch_shape(gmi_instance* g, const ChainArgs& a, int rows, int* tiles_out, double flops, double bytes) {
-  static bool attr = false;
-  const size_t lds = S::lds_bytes();
-  const int tiles = (rows + 32 * S::NW - 1) / (32 * S::NW);
-  *tiles_out = tiles;
-  if (tiles > gmi::kLossBlocksMax) return GMI_ERR_UNSUPPORTED;      // one statistics row per tile
-  if (!attr) {
-    GMI_HIP(hipFuncSetAttribute((const void*)train_chain_kernel<S>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr = true;
-  }
-  gmi::ProfScope ps(g, gmi::kClsChainTrain);
-  ps.work(flops, bytes);
-  ps.launch(train_chain_kernel<S>, dim3(tiles, 2), dim3(S::NT), lds, a);
-  GMI_LAUNCH_CHECK();
-  return GMI_OK;
-}
-
 ChainDims dims_of(const ModelLayout& L) {
   ChainDims D;
   D.nl = L.n_layers;
@@ -668,6 +81,7 @@ extern "C" int gmi_chain_timing(long long* out, int n) {
 #endif
 
 namespace gmi {
+using namespace gmi_chain;
 
 // Bytes of one net's chain stream (0 if the two nets' padded widths differ, which only a policy head wider
 // than 32 outputs can cause: such models have no chain stream).
@@ -752,10 +166,11 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, const gmi_ppo_hparams* hp,
     }
   }
   bytes += 4.0 * rows * (L.act_dim + 3);
-  if (shape_matches<ShapeC2>(L)) rc = launch_shape<ShapeC2>(g, a, rows, &tiles, flops, bytes);
-  else if (shape_matches<ShapeC3>(L)) rc = launch_shape<ShapeC3>(g, a, rows, &tiles, flops, bytes);
-  else if (shape_matches<ShapeC4>(L)) rc = launch_shape<ShapeC4>(g, a, rows, &tiles, flops, bytes);
-  else return GMI_ERR_UNSUPPORTED;
+  typedef int (*part_fn)(gmi_instance*, const ModelLayout&, const ChainArgs&, int, int*, double, double);
+  static const part_fn parts[kChainParts] = {launch_chain_part0, launch_chain_part1, launch_chain_part2,
+                                             launch_chain_part3, launch_chain_part4, launch_chain_part5};
+  rc = GMI_ERR_UNSUPPORTED;
+  for (int p = 0; p < kChainParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = parts[p](g, L, a, rows, &tiles, flops, bytes);
   if (rc != GMI_OK) return rc;
   *n_stat_rows = tiles;
   return GMI_OK;

@@ -105,6 +105,7 @@ class InstancePipeline:
         # shadow[0]: written by the trainer; shadow[1]: the published copy the agents read
         self.shadow = [torch.zeros(max(nsh, 256), dtype=torch.uint8, device=dev) for _ in range(2)] if nsh else [None, None]
         self.theta_pub = torch.tensor(theta, **f)       # fp32 path: the published parameters
+        torch.cuda.synchronize()    # torch filled the arrays on its own stream; the library works on the instances' streams
         self.t_model = gmi_model_bind(self.trainer, t_desc, self.theta, self.shadow[0], self.adam_m, self.adam_v)
         gmi_model_refresh_shadow(self.trainer, self.t_model)
         # two experience buffers (the pipelined schedule trains on one while the other fills)

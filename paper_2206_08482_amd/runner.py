@@ -82,6 +82,8 @@ class PPOSession:
             self.shadow = torch.zeros(max(nshadow, 256), dtype=torch.uint8, device=dev) if nshadow else None
         else:
             self.shadow = replica_of.shadow
+        # torch filled the arrays above on its own stream; the library works on the instance's stream
+        torch.cuda.synchronize()
         self.model = gmi_model_bind(self.gmi, self.mdesc, self.theta, self.shadow, self.adam_m, self.adam_v)
         if replica_of is None:
             gmi_model_refresh_shadow(self.gmi, self.model)

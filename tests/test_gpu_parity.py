@@ -160,6 +160,7 @@ def _bind_model(g, inst, cfg, theta, rows, dtype=None, with_adam=True):
     nb = g.gmi_model_shadow_bytes(desc)
     shadow = zeros(max(nb, 256), dtype=torch.uint8) if nb else None
     m, v = (zeros(theta.size), zeros(theta.size)) if with_adam else (None, None)
+    torch.cuda.synchronize()      # the fills above run on torch's stream, the library on the instance's
     h = g.gmi_model_bind(inst, desc, t, shadow, m, v)
     g.gmi_model_refresh_shadow(inst, h)
     g.gmi_sync(inst)
@@ -224,7 +225,11 @@ def _theta_and_batch(cfg, T, N, seed=1):
     ("C2", 4, 512, 2048, "bf16", "straddle"),
     # large-tile kernels (rows >= 8192), ragged against their 256-row tiles
     ("C4", 2, 4200, 8400, "bf16", "bimodal"), ("C3", 3, 3000, 8999, "bf16", "bimodal"),
-    ("C2", 2, 8192, 16384, "bf16", "bimodal")])
+    ("C2", 2, 8192, 16384, "bf16", "bimodal"),
+    # the paper's Table 6 model shapes under their own layer orders
+    ("BB", 3, 400, 1200, "bf16", "bimodal"), ("FC", 2, 300, 555, "bf16", "bimodal"),
+    ("AY", 2, 512, 1024, "bf16", "bimodal"), ("HM", 2, 700, 1400, "bf16", "bimodal"),
+    ("SH", 2, 600, 1111, "bf16", "bimodal")])
 @pytest.mark.parametrize("path", ["chain", "rowtile", "layers"])
 def test_gradient_and_stats_match_oracle(g, inst, name, T, N, rows, dtype, ratios, path):
     """path: which trainer kernels compute forward, loss and input gradients: "chain" the register-chained
@@ -237,7 +242,7 @@ def test_gradient_and_stats_match_oracle(g, inst, name, T, N, rows, dtype, ratio
     gradient by that sample's whole contribution.  ratios = "bimodal" keeps every ratio either well
     inside or well outside the clip range, so the decisions agree and the comparison measures the
     arithmetic of the products alone."""
-    if path == "rowtile" and (dtype == "f32" or name == "C4"):
+    if path == "rowtile" and (dtype == "f32" or name in ("C4", "SH")):
         pytest.skip("the row-tile fused trainer kernel covers bf16 models up to 1 MB of weights")
     if path == "chain" and (dtype == "f32" or name == "C1"):
         pytest.skip("the register-chained kernel covers the bf16 benchmark shapes")

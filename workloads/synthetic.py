@@ -63,6 +63,14 @@ CONFIGS: Dict[str, PPOConfig] = {
                     done_prob_inv=1000, reward_scale=0.01),
     "C5": PPOConfig("C5", 4096, 108, 21, (400, 200, 100), 32, 5, 65536, "bf16",
                     done_prob_inv=1000, n_agents=4),
+    # The policy models of the paper's Table 6 under their own layer orders (its Ant model is C2's), on the same
+    # synthetic env family: 4096 envs, horizon 16, 4 epochs, minibatch 32768 as for C2.
+    "AY": PPOConfig("AY", 4096, 48, 12, (256, 128, 64), 16, 4, 32768, "bf16", done_prob_inv=1000),
+    "BB": PPOConfig("BB", 4096, 24, 3, (256, 128, 64), 16, 4, 32768, "bf16", done_prob_inv=1000),
+    "FC": PPOConfig("FC", 4096, 23, 9, (256, 128, 64), 16, 4, 32768, "bf16", done_prob_inv=1000),
+    "HM": PPOConfig("HM", 4096, 108, 21, (200, 400, 100), 16, 4, 32768, "bf16", done_prob_inv=1000),
+    "SH": PPOConfig("SH", 8192, 211, 20, (512, 512, 512, 256), 16, 4, 32768, "bf16", done_prob_inv=1000,
+                    reward_scale=0.01),
 }
 
 
