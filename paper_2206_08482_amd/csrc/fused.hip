@@ -295,7 +295,8 @@ struct RolloutArgs {
 // transposed matrices (LDS copy or global), row stride nbo float4.
 template <int EPT>
 __device__ __forceinline__ void sim_items(const RolloutArgs& a, int R, int r0, uint32_t step, const float* s_in,
-                                          const float4* mt, float* s_part, float* s_next, const int* s_done) {
+                                          const float4* mt, float* s_part, float* s_next, const int* s_done,
+                                          const float4* s_noise, int npr, int nba) {
   const int O = a.obs_dim, A = a.act_dim, OA = O + A, o4 = a.o4, nbo = o4 >> 2;
   for (int item = threadIdx.x; item < (R / EPT) * nbo; item += blockDim.x) {
     const int g = item / nbo, b = item - g * nbo;
@@ -306,8 +307,29 @@ __device__ __forceinline__ void sim_items(const RolloutArgs& a, int R, int r0, u
     for (int i = 0; i < EPT; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
-#pragma unroll 8
-    for (int k = 0; k < OA; ++k) {
+    // eight matrix rows (and state elements) are fetched before the first of their products: left to the
+    // compiler under this kernel's register pressure, every k waited a full LDS round trip for its row
+    int k = 0;
+    for (; k + 8 <= OA; k += 8) {
+      float4 m[8];
+      float xv[EPT][8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) m[u] = mrow[(k + u) * nbo];
+#pragma unroll
+      for (int i = 0; i < EPT; ++i)
+#pragma unroll
+        for (int u = 0; u < 8; ++u) xv[i][u] = xin[i * OA + k + u];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+          acc[i][0] = fmaf(xv[i][u], m[u].x, acc[i][0]);
+          acc[i][1] = fmaf(xv[i][u], m[u].y, acc[i][1]);
+          acc[i][2] = fmaf(xv[i][u], m[u].z, acc[i][2]);
+          acc[i][3] = fmaf(xv[i][u], m[u].w, acc[i][3]);
+        }
+    }
+    for (; k < OA; ++k) {
       const float4 m = mrow[k * nbo];
 #pragma unroll
       for (int i = 0; i < EPT; ++i) {
@@ -337,7 +359,8 @@ __device__ __forceinline__ void sim_items(const RolloutArgs& a, int R, int r0, u
 #pragma unroll
         for (int j = 0; j < 4; ++j) outv[j] = z[j];
       } else {
-        if (e < a.n) gmi::normal_block(a.e_env_offset + (uint32_t)e, step, gmi::kStreamEnv, (uint32_t)b, a.ek0, a.ek1, z);
+        const float4 zn = s_noise[r * npr + nba + b];       // drawn at the top of the step
+        z[0] = zn.x; z[1] = zn.y; z[2] = zn.z; z[3] = zn.w;
 #pragma unroll
         for (int j = 0; j < 4; ++j) outv[j] = fmaf(a.noise_std, z[j], acc[i][j]);
       }
@@ -346,10 +369,135 @@ __device__ __forceinline__ void sim_items(const RolloutArgs& a, int R, int r0, u
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Weight-stationary form of the layers, for model shapes whose share of the weights fits a wave's registers:
+// the one-launch rollout runs the same layers T + 1 times, so each wave fetches the operand blocks of ITS
+// feature tiles once, at kernel start, and keeps them in registers for all steps (streamed from L2 they cost
+// ~2000 cycles of latency per layer and step).  Same products in the same order as fused_layer: results are
+// bit-identical.  DIMS = padded widths d[0..NL] (input, hidden..., head).
+template <class WS> struct WsFrags { static constexpr int value = WS::n_frags(); };
+template <> struct WsFrags<void> { static constexpr int value = 1; };
+
+template <int... DIMS>
+struct WsShape {
+  static constexpr int NL = (int)sizeof...(DIMS) - 1;
+  static constexpr int dim(int i) {
+    constexpr int d[] = {DIMS...};
+    return d[i];
+  }
+  static constexpr int max_tiles(int l) { return (dim(l + 1) / 32 + 3) / 4; }      // feature tiles of one wave
+  static constexpr int frag_base(int l) {
+    int n = 0;
+    for (int i = 0; i < l; ++i) n += max_tiles(i) * (dim(i) / 16);
+    return n;
+  }
+  static constexpr int n_frags() { return frag_base(NL); }
+};
+
+template <class WS, int L>
+__device__ __forceinline__ void ws_load(bf16x8* wreg, const FusedNet& N, int wave, int lane) {
+  if constexpr (L < WS::NL) {
+    constexpr int nks = WS::dim(L) / 16, nft = WS::dim(L + 1) / 32, base = WS::frag_base(L);
+#pragma unroll
+    for (int i = 0; i < WS::max_tiles(L); ++i) {
+      const int tile = wave + 4 * i;
+      const int tc = tile < nft ? tile : nft - 1;       // a wave without an i-th tile loads a valid block it never uses
+      const uint16_t* p = N.w[L] + ((int64_t)tc * nks) * 512 + lane * 8;
+#pragma unroll
+      for (int ks = 0; ks < nks; ++ks) wreg[base + i * nks + ks] = *reinterpret_cast<const bf16x8*>(p + (int64_t)ks * 512);
+    }
+    ws_load<WS, L + 1>(wreg, N, wave, lane);
+  }
+}
+
+template <class WS, int L, int RT, int EPI>
+__device__ __forceinline__ void ws_layer(const bf16x8* wreg, const float* s_bias, const uint16_t* s_in, int stride_in,
+                                         uint16_t* s_out, int stride_out, float* s_head, int head_stride,
+                                         int out_store, int wave, int lane) {
+  constexpr int nks = WS::dim(L) / 16, nft = WS::dim(L + 1) / 32, base = WS::frag_base(L);
+  const int khalf = (lane >> 5) * 8;
+  const uint16_t* xrow = s_in + (lane & 31) * stride_in + khalf;
+#pragma unroll
+  for (int i = 0; i < WS::max_tiles(L); ++i) {
+    const int tile = wave + 4 * i;
+    if (tile < nft) {                                   // wave-uniform
+      floatx16 acc[RT];
+#pragma unroll
+      for (int j = 0; j < RT; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < nks; ++ks)
+#pragma unroll
+        for (int j = 0; j < RT; ++j) {
+          const bf16x8 b = *reinterpret_cast<const bf16x8*>(xrow + j * 32 * stride_in + ks * 16);
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[base + i * nks + ks], b, acc[j], 0, 0, 0);
+        }
+      const int fb = tile * 32;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int f = fb + g * 8 + (lane >> 5) * 4;
+        const float4 bv = *reinterpret_cast<const float4*>(s_bias + f);
+#pragma unroll
+        for (int j = 0; j < RT; ++j) {
+          const int r = j * 32 + (lane & 31);
+          const float o0 = acc[j][g * 4 + 0] + bv.x, o1 = acc[j][g * 4 + 1] + bv.y;
+          const float o2 = acc[j][g * 4 + 2] + bv.z, o3 = acc[j][g * 4 + 3] + bv.w;
+          if (EPI == kFEpiElu) {
+            *reinterpret_cast<uint2*>(&s_out[r * stride_out + f]) =
+                make_uint2(pack_bf16(elu_f(o0), elu_f(o1)), pack_bf16(elu_f(o2), elu_f(o3)));
+          } else {
+            float* d = s_head + r * head_stride + f;
+            if (f + 0 < out_store) d[0] = o0;
+            if (f + 1 < out_store) d[1] = o1;
+            if (f + 2 < out_store) d[2] = o2;
+            if (f + 3 < out_store) d[3] = o3;
+          }
+        }
+      }
+    }
+  }
+}
+
+// All layers of one net from layer L on, hidden activations ping-ponging between s_a and s_b as in the
+// streaming form; every layer ends with a workgroup barrier.
+template <class WS, int L, int RT>
+__device__ __forceinline__ void ws_net(const bf16x8* wreg, const FusedNet& N, const float* s_nb, const uint16_t* in,
+                                       int stride_in, uint16_t* s_a, uint16_t* s_b, int stride_h, float* s_head,
+                                       int head_stride, bool run, int wave, int lane) {
+  if constexpr (L < WS::NL - 1) {
+    uint16_t* out = (L & 1) ? s_b : s_a;
+    if (run)
+      ws_layer<WS, L, RT, kFEpiElu>(wreg, s_nb + N.bias_off[L], in, stride_in, out, stride_h, nullptr, 0, 0, wave, lane);
+    __syncthreads();
+    ws_net<WS, L + 1, RT>(wreg, N, s_nb, out, stride_h, s_a, s_b, stride_h, s_head, head_stride, run, wave, lane);
+  } else {
+    if (run)
+      ws_layer<WS, L, RT, kFEpiHead>(wreg, s_nb + N.bias_off[L], in, stride_in, nullptr, 0, s_head, head_stride,
+                                     N.out_store, wave, lane);
+    __syncthreads();
+  }
+}
+
+// Shapes with a weight-stationary rollout: at most 36 operand blocks (144 registers) per wave.
+using WsAnt = WsShape<64, 256, 128, 64, 32>;         // 60:256:128:64:8 (benchmark workload C2), 48:256:128:64:12
+using WsSmallObs = WsShape<32, 256, 128, 64, 32>;    // 24:256:128:64:3, 23:256:128:64:9
+
+template <class WS>
+bool ws_matches(const ModelLayout& L) {
+  if (L.n_layers != WS::NL) return false;
+  for (int net = 0; net < 2; ++net)
+    for (int l = 0; l < WS::NL; ++l)
+      if (L.net[net][l].in_pad != WS::dim(l) || L.net[net][l].out_pad != WS::dim(l + 1)) return false;
+  return true;
+}
+
 // 512 threads: waves 0-3 run the policy net and waves 4-7 the value net at the same time (the two nets
 // have the same hidden widths, so their layers finish together and share the barriers); every other phase
 // uses all 8 waves.
-template <int RT>
+// WS: a WsShape whose widths the model has (weights held in registers for the whole launch), or void (weights
+// streamed from L2 at every step).
+template <int RT, class WS = void>
 __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   constexpr int R = RT * 32;
   constexpr int NT = 512;
@@ -357,8 +505,11 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   const int O = a.obs_dim, A = a.act_dim, OA = O + A, o4 = a.o4, nbo = o4 >> 2, nba = (A + 3) >> 2;
   const int stride_x0 = a.obs_pad + 8, stride_h = a.max_h + 8;
   // hidden activations (bf16, ping-pong, one pair per net) share their space with the next-state tile
-  const size_t hid_bytes = 4 * (size_t)R * stride_h * 2, next_bytes = (size_t)R * o4 * 4;
-  const size_t region = ((hid_bytes > next_bytes ? hid_bytes : next_bytes) + 15) & ~(size_t)15;
+  // (after the nets: next-state tile, then this step's random draws, then the staged simulator matrix)
+  const int npr = nba + nbo + 1;                     // random blocks per env and step: action, env noise, done
+  const size_t hid_bytes = 4 * (size_t)R * stride_h * 2, next_bytes = ((size_t)R * o4 * 4 + 15) & ~(size_t)15;
+  const size_t noise_bytes = (size_t)R * npr * 16;
+  const size_t region = ((hid_bytes > next_bytes + noise_bytes ? hid_bytes : next_bytes + noise_bytes) + 15) & ~(size_t)15;
   float* s_in = reinterpret_cast<float*>(smem_raw);                                  // [R][O + A] state | action
   uint16_t* s_x0 = reinterpret_cast<uint16_t*>(s_in + ((R * OA + 3) & ~3));          // [R][obs_pad + 8]
   unsigned char* s_reg = reinterpret_cast<unsigned char*>(s_x0 + R * stride_x0);
@@ -370,6 +521,9 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   float* s_part = s_lp + R * nba;                                                    // [R][nbo]
   int* s_done = reinterpret_cast<int*>(s_part + R * nbo);                            // [R]
   float* s_bias = reinterpret_cast<float*>(s_done + ((R + 3) & ~3));                 // policy biases, value biases
+  // this step's random draws, one float4 per (env, block): nba action-noise blocks, nbo env-noise blocks, then
+  // the done draw (raw word in .x); in the hidden-activation space, which is idle once the heads are done
+  float4* s_noise = reinterpret_cast<float4*>(s_reg + next_bytes);
   float* s_mt = s_bias + ((a.net[0].bias_total + a.net[1].bias_total + 3) & ~3);     // [O + A][o4] when mt_lds == 2
   const int tid = threadIdx.x;
   // wave-uniform values, so that the per-net kernel arguments are fetched by scalar loads
@@ -383,15 +537,22 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   if (a.mt_lds == 2)
     for (int idx = tid; idx < OA * nbo; idx += NT)
       reinterpret_cast<float4*>(s_mt)[idx] = reinterpret_cast<const float4*>(a.m_t)[idx];
-  float4* s_stage = reinterpret_cast<float4*>(s_reg + ((next_bytes + 15) & ~(size_t)15));
-  const float4* mt = a.mt_lds == 2 ? reinterpret_cast<const float4*>(s_mt)
-                   : a.mt_lds == 1 ? s_stage : reinterpret_cast<const float4*>(a.m_t);
+  float4* s_stage = reinterpret_cast<float4*>(s_reg + next_bytes + noise_bytes);
+  // the simulator matrix as an LDS pointer (resident copy or per-step staging) or as a global pointer: kept apart,
+  // because one pointer that may be either makes every access a flat load (measured: the 68-step matrix-vector
+  // loop of a 60-dimensional env took 8600 cycles through flat loads)
+  const float4* mt_lds_ptr = a.mt_lds == 2 ? reinterpret_cast<const float4*>(s_mt) : s_stage;
+  const float4* mt_glb_ptr = reinterpret_cast<const float4*>(a.m_t);
   const FusedNet& N = a.net[half];
   uint16_t* s_a = s_hid + (size_t)half * 2 * R * stride_h;
   uint16_t* s_b = s_a + R * stride_h;
   float* s_head = half ? s_val : s_mu;
   const int head_stride = half ? 1 : A;
   const float* s_nb = s_bias + (half ? a.net[0].bias_total : 0);
+  constexpr bool kStationary = !std::is_void<WS>::value;
+  // this wave's weight operands, fetched once (a dummy single entry in the streaming form)
+  bf16x8 wreg[WsFrags<WS>::value];
+  if constexpr (kStationary) ws_load<WS, 0>(wreg, N, wave4, tid & 63);
 
   // The grid never exceeds what the instance's compute units hold at once: a workgroup takes the tiles
   // blockIdx.x, blockIdx.x + gridDim.x, ... one after the other, each through all T steps.  (Workgroups
@@ -415,7 +576,9 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       s_x0[r * stride_x0 + k] = (uint16_t)(pack_bf16(v, 0.f) & 0xFFFFu);
     }
     __syncthreads();
-    {
+    if constexpr (kStationary) {
+      ws_net<WS, 0, RT>(wreg, N, s_nb, s_x0, stride_x0, s_a, s_b, stride_h, s_head, head_stride, run, wave4, tid & 63);
+    } else {
       const uint16_t* in = s_x0;
       int stride_in = stride_x0;
       uint16_t* out = s_a;
@@ -440,6 +603,26 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       break;
     }
 
+    // All random draws of this step, one block per thread and the same instructions for every kind of block
+    // (left where they are used, they ran on the few threads of the sampling phase and inside the simulator's
+    // matrix product).
+    {
+      const uint32_t stp = a.step0 + (uint32_t)t;
+      for (int item = tid; item < Rv * npr; item += NT) {
+        const int r = item / npr, q = item - r * npr;
+        const uint32_t e = (uint32_t)(r0 + r < a.n ? r0 + r : a.n - 1);
+        const bool is_act = q < nba, is_env = q >= nba && q < nba + nbo;
+        const uint32_t strm = is_act ? gmi::kStreamAction : (is_env ? gmi::kStreamEnv : gmi::kStreamDone);
+        const uint32_t blk = is_act ? (uint32_t)q : (is_env ? (uint32_t)(q - nba) : 0u);
+        const gmi::Words4 w = gmi::philox4x32_10((is_act ? a.a_env_offset : a.e_env_offset) + e, stp, strm, blk,
+                                                 is_act ? a.ak0 : a.ek0, is_act ? a.ak1 : a.ek1);
+        float z0, z1, z2, z3;
+        gmi::normal_pair(w.w[0], w.w[1], z0, z1);
+        gmi::normal_pair(w.w[2], w.w[3], z2, z3);
+        s_noise[item] = (is_act || is_env) ? make_float4(z0, z1, z2, z3) : make_float4(__uint_as_float(w.w[0]), 0.f, 0.f, 0.f);
+      }
+    }
+    __syncthreads();
     const uint32_t step = a.step0 + (uint32_t)t;
     const int64_t slot0 = (int64_t)t * a.ld_envs + r0;
     // action = mu + exp(log_std) * eps, log-prob partials per block of 4 action elements
@@ -448,8 +631,8 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       const int e = r0 + r;
       float lp = 0.f;
       if (e < a.n) {
-        float z[4];
-        gmi::normal_block(a.a_env_offset + (uint32_t)e, step, gmi::kStreamAction, (uint32_t)b, a.ak0, a.ak1, z);
+        const float4 zn = s_noise[r * npr + b];
+        const float z[4] = {zn.x, zn.y, zn.z, zn.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int j = 4 * b + i;
@@ -478,8 +661,7 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
         if (a.done_period > 0) {
           d = ((ep + 1u) % a.done_period) == 0u;
         } else {
-          const gmi::Words4 w = gmi::philox4x32_10(a.e_env_offset + (uint32_t)e, step, gmi::kStreamDone, 0u, a.ek0, a.ek1);
-          d = w.w[0] < a.done_threshold;
+          d = __float_as_uint(s_noise[tid * npr + nba + nbo].x) < a.done_threshold;
         }
         ep = d ? 0u : ep + 1u;
         a.b_done[slot0 + tid] = (uint8_t)d;
@@ -499,8 +681,13 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       for (int idx = tid; idx < OA * nbo; idx += NT) s_stage[idx] = reinterpret_cast<const float4*>(a.m_t)[idx];
       __syncthreads();
     }
-    if ((Rv / 4) * nbo >= 192) sim_items<4>(a, Rv, r0, step, s_in, mt, s_part, s_next, s_done);
-    else sim_items<1>(a, Rv, r0, step, s_in, mt, s_part, s_next, s_done);
+    if (a.mt_lds != 0) {
+      if ((Rv / 4) * nbo >= 192) sim_items<4>(a, Rv, r0, step, s_in, mt_lds_ptr, s_part, s_next, s_done, s_noise, npr, nba);
+      else sim_items<1>(a, Rv, r0, step, s_in, mt_lds_ptr, s_part, s_next, s_done, s_noise, npr, nba);
+    } else {
+      if ((Rv / 4) * nbo >= 192) sim_items<4>(a, Rv, r0, step, s_in, mt_glb_ptr, s_part, s_next, s_done, s_noise, npr, nba);
+      else sim_items<1>(a, Rv, r0, step, s_in, mt_glb_ptr, s_part, s_next, s_done, s_noise, npr, nba);
+    }
     __syncthreads();
     if (tid < Rv && r0 + tid < a.n) {
       float sum = 0.f;
@@ -773,14 +960,21 @@ size_t agent_lds_bytes(const gmi_model* m, int R) {
          ((size_t)R * (L.act_dim + 1 + nb) + bias_floats(m, 0) + bias_floats(m, 1)) * 4;
 }
 
-// Bytes of the hidden-activation space left over beside the next-state tile while the simulator runs.
+// Bytes of one step's random draws for a tile of R envs (one float4 per block).
+size_t rollout_noise_bytes(const gmi_model* m, int R) {
+  const int O = m->L.obs_dim, A = m->L.act_dim, o4 = (O + 3) & ~3;
+  return (size_t)R * ((A + 3) / 4 + o4 / 4 + 1) * 16;
+}
+
+// Bytes of the hidden-activation space left over beside the next-state tile and the random draws while the
+// simulator runs.
 size_t rollout_stage_room(const gmi_model* m, int R) {
   const ModelLayout& L = m->L;
   int max_h = 32;
   for (int l = 0; l < L.n_hidden; ++l) max_h = L.net[0][l].out_pad > max_h ? L.net[0][l].out_pad : max_h;
   const int o4 = (L.obs_dim + 3) & ~3;
-  const size_t hid = 4 * (size_t)R * (max_h + 8) * 2, nxt = ((size_t)R * o4 * 4 + 15) & ~(size_t)15;
-  return hid > nxt ? hid - nxt : 0;
+  const size_t hid = 4 * (size_t)R * (max_h + 8) * 2, used = (((size_t)R * o4 * 4 + 15) & ~(size_t)15) + rollout_noise_bytes(m, R);
+  return hid > used ? hid - used : 0;
 }
 
 size_t rollout_lds_bytes(const gmi_model* m, int R, bool mt_lds) {
@@ -788,8 +982,8 @@ size_t rollout_lds_bytes(const gmi_model* m, int R, bool mt_lds) {
   int max_h = 32;
   for (int l = 0; l < L.n_hidden; ++l) max_h = L.net[0][l].out_pad > max_h ? L.net[0][l].out_pad : max_h;
   const int O = L.obs_dim, A = L.act_dim, o4 = (O + 3) & ~3;
-  const size_t hid = 4 * (size_t)R * (max_h + 8) * 2, nxt = (size_t)R * o4 * 4;
-  const size_t region = ((hid > nxt ? hid : nxt) + 15) & ~(size_t)15;
+  const size_t hid = 4 * (size_t)R * (max_h + 8) * 2, used = (((size_t)R * o4 * 4 + 15) & ~(size_t)15) + rollout_noise_bytes(m, R);
+  const size_t region = ((hid > used ? hid : used) + 15) & ~(size_t)15;
   return (size_t)((R * (O + A) + 3) & ~3) * 4 + (size_t)R * (gmi::pad32(O) + 8) * 2 + region +
          (size_t)(R * (A + 1 + (A + 3) / 4 + o4 / 4) + ((R + 3) & ~3)) * 4 +
          ((bias_floats(m, 0) + bias_floats(m, 1) + 3) & ~(size_t)3) * 4 +
@@ -973,22 +1167,26 @@ extern "C" int rollout_collect(gmi_t g, gmi_model_t m, gmi_env_t env, gmi_buffer
   const int rows_per_wg = (R == 32 && (n + 31) / 32 < g->cu_count && n > 16) ? 16 : R;
   a.rows_per_wg = rows_per_wg;
   a.n_tiles = (n + rows_per_wg - 1) / rows_per_wg;
-  const void* kern = R == 64 ? (const void*)rollout_fused_kernel<2> : (const void*)rollout_fused_kernel<1>;
-  static bool attr_set[2] = {false, false};
-  if (!attr_set[R == 64]) {
-    GMI_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
-    attr_set[R == 64] = true;
+  // weight-stationary variant where this model's padded widths have one (both nets share them)
+  typedef void (*rollout_fn)(RolloutArgs);
+  rollout_fn kfn = R == 64 ? rollout_fused_kernel<2> : rollout_fused_kernel<1>;
+  int variant = R == 64 ? 1 : 0;
+  if (ws_matches<WsAnt>(L)) { kfn = R == 64 ? rollout_fused_kernel<2, WsAnt> : rollout_fused_kernel<1, WsAnt>; variant += 2; }
+  else if (ws_matches<WsSmallObs>(L)) { kfn = R == 64 ? rollout_fused_kernel<2, WsSmallObs> : rollout_fused_kernel<1, WsSmallObs>; variant += 4; }
+  static bool attr_set[6] = {false, false, false, false, false, false};
+  if (!attr_set[variant]) {
+    GMI_HIP(hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
+    attr_set[variant] = true;
   }
   // no more workgroups than the instance's compute units hold at once; the rest of the tiles are taken
   // by the same workgroups in turn
   int per_cu = 0;
-  GMI_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 512, lds));
+  GMI_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)kfn, 512, lds));
   if (per_cu < 1) per_cu = 1;
   const int64_t resident = (int64_t)per_cu * g->cu_count;
   const int grid = (int)(a.n_tiles < resident ? a.n_tiles : resident);
   gmi::ProfScope ps(g, gmi::kClsFusedRollout);
-  if (R == 64) ps.launch(rollout_fused_kernel<2>, dim3(grid), dim3(512), lds, a);
-  else ps.launch(rollout_fused_kernel<1>, dim3(grid), dim3(512), lds, a);
+  ps.launch(kfn, dim3(grid), dim3(512), lds, a);
   GMI_LAUNCH_CHECK();
   return GMI_OK;
 }
