@@ -306,6 +306,48 @@ int gmi_explore(gmi_profile_fn profile, void* profile_user, gmi_estimate_fn esti
                 const int32_t* num_env_values, int32_t n_env, int32_t* num_env_out, int32_t* gmi_per_gpu_out,
                 double* projected);
 
+/* ------------------------------------------------------------------ experience channels ---- */
+
+/* Channel-based experience sharing between agent and trainer instances (Section 4.2, "Channel-based Experience
+ * Sharing") on one GPU.  A channel set is a ring of `capacity` slabs in device memory (allocated by
+ * gmi_channels_create, freed by gmi_channels_destroy); a slab is one agent instance's experience of one
+ * collection round: [horizon, n_envs] samples.  mode GMI_CHANNELS_MULTI keeps one array per type of data
+ * (state, action, log-prob, value, reward, done: the paper's per-type channels); GMI_CHANNELS_UNI keeps one
+ * array of interleaved records [obs | act | logp | val | rew | done as float] per sample, the single-channel
+ * form the paper compares against.  Every value arrives bit for bit. */
+typedef struct gmi_channels* gmi_channels_t;
+#define GMI_CHANNELS_MULTI 0
+#define GMI_CHANNELS_UNI 1
+typedef struct {
+  int32_t horizon, n_envs, obs_dim, act_dim;   /* shape of a slab */
+  int32_t capacity;                            /* slabs in the ring, 1 .. 4096 */
+  int32_t mode;
+} gmi_channels_desc;
+int gmi_channels_create(const gmi_channels_desc* desc, int device, gmi_channels_t* out);
+int gmi_channels_destroy(gmi_channels_t ch);     /* synchronises the device first */
+
+/* Agent side (the paper's dispenser and compressor): copies the filled experience buffer `src` (its n_envs
+ * columns, all arrays, in one launch on the agent's stream) and last_value dev [n_envs] into the next free
+ * slab.  The agent may refill `src` as soon as its own stream has passed this call.  GMI_ERR_UNSUPPORTED (and
+ * nothing done) when all slabs are waiting for the trainer; GMI_ERR_BAD_SHAPE when src is not slab-shaped. */
+int gmi_channels_push(gmi_t agent, gmi_channels_t ch, gmi_buffer_t src, const float* last_value);
+
+/* Trainer side (the paper's migrator and batcher): takes the n_slabs (1..8) oldest slabs, of each the env
+ * columns [env0, env0 + take) (slicing), and places them side by side in arrival order (stacking) into the
+ * columns [dst_col0, dst_col0 + n_slabs * take) of `dst` (obs, act, logp, val, rew, done) and into
+ * last_value_out dev [n_slabs * take], in one launch on the trainer's stream, which first waits for the agents'
+ * pushes of these slabs.  The slabs are free again once the trainer's stream has passed this call.
+ * GMI_ERR_UNSUPPORTED (nothing done) when fewer than n_slabs slabs are waiting. */
+int gmi_channels_pop(gmi_t trainer, gmi_channels_t ch, int32_t n_slabs, int32_t env0, int32_t take,
+                     gmi_buffer_t dst, int32_t dst_col0, float* last_value_out);
+
+/* Ring state: slabs waiting, and the totals pushed / popped so far (any pointer may be NULL).  Host only. */
+int gmi_channels_count(gmi_channels_t ch, int32_t* waiting, int64_t* pushed, int64_t* popped);
+
+/* The migrator's choice among several trainer instances (Section 4.2: the trainer "with the least workload"):
+ * index of the smallest entry of samples_so_far host i64 [n_trainers], the lowest index on ties. */
+int gmi_route_least_loaded(const int64_t* samples_so_far, int32_t n_trainers, int32_t* trainer_out);
+
 /* ------------------------------------------------------------------ reduction strategy ------ */
 
 /* The three gradient-reduction strategies for trainer instances (Section 4.1, "Layout-aware Gradient

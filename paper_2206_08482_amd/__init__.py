@@ -26,7 +26,8 @@ EXPORTS = [
     "gae_compute", "ppo_update", "ppo_evaluate", "ppo_gradient", "adam_update", "gmi_noise_fill",
     "gmi_permutation", "gmi_profile_enable", "gmi_profile_classes", "gmi_profile_class_name", "gmi_profile_read",
     "gmi_measure_peak", "gmi_bench_linear", "gmi_set_fusion", "rollout_collect", "gmi_profile_work", "gmi_explore", "ppo_update_group", "gmi_select_reduction",
-    "gmi_har_leaders", "gmi_reduction_time",
+    "gmi_har_leaders", "gmi_reduction_time", "gmi_channels_create", "gmi_channels_destroy", "gmi_channels_push",
+    "gmi_channels_pop", "gmi_channels_count", "gmi_route_least_loaded",
 ]
 
 
@@ -57,6 +58,11 @@ class BufferDesc(C.Structure):
                 ("obs_dim", C.c_int32), ("act_dim", C.c_int32),
                 ("obs", C.c_void_p), ("act", C.c_void_p), ("logp", C.c_void_p), ("val", C.c_void_p),
                 ("rew", C.c_void_p), ("done", C.c_void_p), ("adv", C.c_void_p), ("ret", C.c_void_p)]
+
+
+class ChannelsDesc(C.Structure):
+    _fields_ = [("horizon", C.c_int32), ("n_envs", C.c_int32), ("obs_dim", C.c_int32), ("act_dim", C.c_int32),
+                ("capacity", C.c_int32), ("mode", C.c_int32)]
 
 
 class PPOHparams(C.Structure):
@@ -98,6 +104,12 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "ppo_update": (C.c_int, [vp, vp, vp, C.POINTER(PPOHparams), vp]),
         "ppo_update_group": (C.c_int, [C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), i32, C.POINTER(PPOHparams), vp]),
         "ppo_evaluate": (C.c_int, [vp, vp, vp, C.POINTER(PPOHparams), vp, i32, vp]),
+        "gmi_channels_create": (C.c_int, [C.POINTER(ChannelsDesc), C.c_int, C.POINTER(vp)]),
+        "gmi_channels_destroy": (C.c_int, [vp]),
+        "gmi_channels_push": (C.c_int, [vp, vp, vp, vp]),
+        "gmi_channels_pop": (C.c_int, [vp, vp, i32, i32, i32, vp, i32, vp]),
+        "gmi_channels_count": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]),
+        "gmi_route_least_loaded": (C.c_int, [C.POINTER(i64), i32, C.POINTER(i32)]),
         "gmi_select_reduction": (C.c_int, [C.POINTER(i32), i32, C.POINTER(i32)]),
         "gmi_har_leaders": (C.c_int, [C.POINTER(i32), C.POINTER(i32), i32, i32, C.POINTER(i32)]),
         "gmi_reduction_time": (C.c_int, [i32, i32, i32, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double)]),
@@ -318,6 +330,44 @@ def ppo_update_group(gmis, models, bufs, hp: PPOHparams, stats_out=None) -> None
     assert len(models) == n and len(bufs) == n
     arr = lambda xs: (C.c_void_p * n)(*xs)
     _check(_lib.ppo_update_group(arr(gmis), arr(models), arr(bufs), n, C.byref(hp), _ptr(stats_out)))
+
+
+CHANNELS_MULTI, CHANNELS_UNI = 0, 1
+
+
+def gmi_channels_create(horizon: int, n_envs: int, obs_dim: int, act_dim: int, capacity: int, mode: int = CHANNELS_MULTI,
+                        device: int = 0) -> int:
+    d = ChannelsDesc(horizon, n_envs, obs_dim, act_dim, capacity, mode)
+    out = C.c_void_p()
+    _check(_lib.gmi_channels_create(C.byref(d), device, C.byref(out)))
+    return out.value
+
+
+def gmi_channels_destroy(ch: int) -> None:
+    _check(_lib.gmi_channels_destroy(ch))
+
+
+def gmi_channels_push(agent: int, ch: int, src_buffer: int, last_value) -> None:
+    _check(_lib.gmi_channels_push(agent, ch, src_buffer, _ptr(last_value)))
+
+
+def gmi_channels_pop(trainer: int, ch: int, n_slabs: int, env0: int, take: int, dst_buffer: int, dst_col0: int,
+                     last_value_out) -> None:
+    _check(_lib.gmi_channels_pop(trainer, ch, n_slabs, env0, take, dst_buffer, dst_col0, _ptr(last_value_out)))
+
+
+def gmi_channels_count(ch: int):
+    w, a, b = C.c_int32(0), C.c_int64(0), C.c_int64(0)
+    _check(_lib.gmi_channels_count(ch, C.byref(w), C.byref(a), C.byref(b)))
+    return w.value, a.value, b.value
+
+
+def gmi_route_least_loaded(samples_so_far) -> int:
+    n = len(samples_so_far)
+    arr = (C.c_int64 * n)(*[int(x) for x in samples_so_far])
+    out = C.c_int32(-1)
+    _check(_lib.gmi_route_least_loaded(arr, n, C.byref(out)))
+    return out.value
 
 
 REDUCE_MULTI_PROCESS, REDUCE_MULTI_RING, REDUCE_HIERARCHICAL = 0, 1, 2

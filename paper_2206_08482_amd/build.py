@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libgmidrl.so")
-SOURCES = ["core.hip", "env.hip", "experience.hip", "mlp.hip", "model.hip", "update.hip", "peaks.hip", "fused.hip", "select.hip", "chain.hip",
+SOURCES = ["core.hip", "env.hip", "experience.hip", "mlp.hip", "model.hip", "update.hip", "peaks.hip", "fused.hip", "select.hip", "channels.hip", "chain.hip",
            "chain_p0.hip", "chain_p1.hip", "chain_p2.hip", "chain_p3.hip", "chain_p4.hip", "chain_p5.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Wno-unused-value", "-Wno-unused-result", "-fhip-fp32-correctly-rounded-divide-sqrt",

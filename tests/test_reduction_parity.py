@@ -52,3 +52,12 @@ def test_error_paths():
         g.gmi_reduction_time(7, 1, 1, 1.0, 1.0, 1.0)
     with pytest.raises(g.GmiError):
         g.gmi_reduction_time(g.REDUCE_MULTI_RING, 0, 1, 1.0, 1.0, 1.0)
+
+
+def test_least_loaded_routing_matches_oracle():
+    from oracle import channels as och
+    rng = np.random.default_rng(2)
+    for _ in range(200):
+        n = int(rng.integers(1, 9))
+        load = [int(x) for x in rng.integers(0, 5, size=n) * 1000]
+        assert g.gmi_route_least_loaded(load) == och.route_least_loaded(load)
