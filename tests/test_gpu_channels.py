@@ -143,3 +143,33 @@ def test_channel_error_paths(g):
     g.gmi_buffer_destroy(wrong); g.gmi_buffer_destroy(ok)
     g.gmi_channels_destroy(ch)
     g.gmi_destroy(inst)
+
+
+def test_channel_pipeline_equals_the_direct_hand_off_bit_for_bit(g):
+    """The same agents, seeds and schedule through channels (both forms) and through the direct column-slice
+    hand-off: the trainer sees identical batches, so the parameters after two iterations are identical."""
+    from paper_2206_08482_amd.channels import ChannelPipeline
+    from paper_2206_08482_amd.instances import InstancePipeline
+    cfg = syn.get_config("C2")
+    n_ag, n, T, mb = 3, 96, 4, 288
+    theta = syn.make_model_params(cfg.obs_dim, cfg.act_dim, cfg.hidden, cfg.seed)
+    a_mat, b_mat = syn.make_env_matrices(cfg.obs_dim, cfg.act_dim, cfg.seed)
+    states = [syn.make_initial_state(n, cfg.obs_dim, 40 + i) for i in range(n_ag)]
+    common = dict(n_agents=n_ag, n_envs=n, obs_dim=cfg.obs_dim, act_dim=cfg.act_dim, hidden=cfg.hidden, horizon=T,
+                  dtype="bf16", theta=theta, a_mat=a_mat, b_mat=b_mat, state0=states, noise_std=cfg.noise_std,
+                  reward_scale=1.0, done_period=0, done_threshold=(1 << 32) // 50, seed=3, minibatch=mb)
+    targs = dict(gamma=0.99, lam=0.95, epochs=2, minibatch=mb, clip=0.2, c_v=0.5, c_e=0.0, lr=3e-4)
+    results = []
+    for make in (lambda: InstancePipeline(**common), lambda: ChannelPipeline(mode=g.CHANNELS_MULTI, **common),
+                 lambda: ChannelPipeline(mode=g.CHANNELS_UNI, **common)):
+        pipe = make()
+        pipe.prologue_pipelined()
+        for k in range(2):
+            pipe.iteration_pipelined(k, **targs)
+        pipe.sync_all()
+        results.append((pipe.theta.cpu().numpy().copy(), pipe.bufs[1].to_numpy()))     # slot 1 holds round 1 in both
+        pipe.close()
+    for th, buf in results[1:]:
+        assert np.array_equal(th, results[0][0])
+        for k in och.TYPES + ("adv", "ret"):
+            assert np.array_equal(buf[k], results[0][1][k]), k
