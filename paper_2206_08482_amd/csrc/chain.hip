@@ -122,10 +122,11 @@ int launch_chain_pack(gmi_instance* g, gmi_model* m) {
   return GMI_OK;
 }
 
-// Forward + loss + input gradients of the minibatch whose rows were gathered into m->x0 / m->mb_* (launch_gather).
+// Gather of the minibatch rows idx[0..rows) of buffer b + forward + loss + input gradients.
 // Leaves m->h, m->dz ready for the weight-gradient launch and one row of statistics / log_std partials per
 // tile in m->stat_part (*n_stat_rows rows, the layout of the loss kernel's per-workgroup rows).  GMI_ERR_UNSUPPORTED (no message) if no kernel is compiled for this shape.
-int launch_train_chain(gmi_instance* g, gmi_model* m, const gmi_ppo_hparams* hp, int rows, int* n_stat_rows) {
+int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx, int rows,
+                       int* n_stat_rows) {
   const ModelLayout& L = m->L;
   if (L.dtype != GMI_DTYPE_BF16 || L.sh_chain_bytes == 0 || L.act_dim > 32) return GMI_ERR_UNSUPPORTED;
   ChainArgs a;
@@ -137,9 +138,12 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, const gmi_ppo_hparams* hp,
       a.dz[net][l] = (uint16_t*)m->dz[net][l];
     }
   }
-  a.x0 = (const uint16_t*)m->x0;
+  a.x0 = (uint16_t*)m->x0;
   a.log_std = reinterpret_cast<const float*>(m->shadow + L.sh_logstd);
-  a.mb_act = m->mb_act; a.mb_logp = m->mb_logp; a.mb_adv = m->mb_adv; a.mb_ret = m->mb_ret;
+  a.idx = idx;
+  a.b_obs = b->d.obs; a.b_act = b->d.act; a.b_logp = b->d.logp; a.b_adv = b->d.adv; a.b_ret = b->d.ret;
+  a.n_envs = b->d.n_envs; a.ld_envs = b->d.ld_envs; a.obs_dim = L.obs_dim;
+  a.x0_ready = (L.obs_dim % 4 == 0 && ((uintptr_t)b->d.obs & 15) == 0) ? 0 : 1;
   a.rows = rows; a.act_dim = L.act_dim;
   a.clip = hp->clip; a.c_v = hp->c_v;
   a.stat_part = m->stat_part;
@@ -161,7 +165,8 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, const gmi_ppo_hparams* hp,
       flops += 2.0 * rows * (double)li.in * li.out * (l == 0 ? 1.0 : 2.0);
       bytes += 2.0 * li.in * li.out * (l == 0 ? 1.0 : 2.0);                 // bf16 weights, forward (+ transposed)
       bytes += 2.0 * rows * li.out;                                          // gradient at the layer's output
-      if (l == 0) bytes += 2.0 * rows * li.in;                               // gathered input rows
+      if (l == 0) bytes += net == 0 ? (a.x0_ready ? 2.0 : 6.0) * rows * li.in : 0.0;   // fp32 observation rows read and the bf16 copy
+                                                                              // written (once), or the bf16 copy read
       else bytes += 2.0 * 2.0 * rows * li.in;                                // hidden activation: written, read back
     }
   }
@@ -169,6 +174,14 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, const gmi_ppo_hparams* hp,
   typedef int (*part_fn)(gmi_instance*, const ModelLayout&, const ChainArgs&, int, int*, double, double);
   static const part_fn parts[kChainParts] = {launch_chain_part0, launch_chain_part1, launch_chain_part2,
                                              launch_chain_part3, launch_chain_part4, launch_chain_part5};
+  if (a.x0_ready) {       // unaligned observation rows: the gather kernel converts them (a lane-wise gather of 4-byte
+                          // pieces at the start of the chained kernel measured slower than the separate launch)
+    rc = GMI_ERR_UNSUPPORTED;
+    for (int p = 0; p < kChainParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = parts[p](g, L, a, 0, &tiles, 0.0, 0.0);
+    if (rc != GMI_OK) return rc;
+    rc = launch_gather(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, nullptr);
+    if (rc != GMI_OK) return rc;
+  }
   rc = GMI_ERR_UNSUPPORTED;
   for (int p = 0; p < kChainParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = parts[p](g, L, a, rows, &tiles, flops, bytes);
   if (rc != GMI_OK) return rc;

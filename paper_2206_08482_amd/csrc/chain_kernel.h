@@ -130,11 +130,18 @@ __host__ __device__ constexpr int cd_ksteps_before(const ChainDims& D, int c) {
 struct ChainArgs {
   const char* wstream[2];                          // chain stream of the policy / value net
   const float* bias[2][GMI_MAX_HIDDEN + 1];        // fp32 [out_pad] per layer
-  const uint16_t* x0;                              // [rows, d[0]] bf16, the gathered observations
+  uint16_t* x0;                                    // [rows, d[0]] bf16: the minibatch's observations, written here for
+                                                   // the weight-gradient kernel (by the policy net's workgroups)
   uint16_t* h[2][GMI_MAX_HIDDEN + 1];              // h[net][l], l = 1 .. nl-1: input of layer l, [rows, d[l]]
   uint16_t* dz[2][GMI_MAX_HIDDEN + 1];             // dz[net][l], l = 0 .. nl-1: gradient at layer l's output, [rows, d[l+1]]
   const float* log_std;
-  const float *mb_act, *mb_logp, *mb_adv, *mb_ret; // gathered per-sample rows
+  // the experience buffer the minibatch is drawn from: sample idx[r] lives at slot
+  // (idx[r] / n_envs) * ld_envs + idx[r] % n_envs of its time-major arrays
+  const int32_t* idx;                              // [rows]
+  const float *b_obs, *b_act, *b_logp, *b_adv, *b_ret;
+  int n_envs, ld_envs, obs_dim;
+  int x0_ready;                                    // 1: x0 already holds the gathered rows (observation rows that cannot
+                                                   // be read as 16-byte pieces are gathered by gather_kernel beforehand)
   int rows, act_dim;
   float clip, c_v;
   float* stat_part;                                // [tiles][kStatStride + act_dim]
@@ -181,6 +188,7 @@ struct Ctx {
   uint4 stage[S::DEPTH][S::LPT];         // weight chunks in flight
   bf16x8 wq[3][4];                       // weight operands of k steps g, g+1, g+2 (ring indexed by g % 3)
   uint4 ht[8];                           // stored activations of the group (input-gradient segments)
+  int64_t slot;                          // this lane's sample in the experience buffer
   float l_act[16], l_lo, l_ad, l_rt;     // this lane's loss inputs (fetched at kernel start): actions of its 16
                                          // features, old log-prob, advantage, return
   const uint4* wsrc;                     // this net's stream
@@ -260,14 +268,12 @@ __device__ __forceinline__ float wave_sum64(float v) {
 // past the end read a valid neighbour, their results are dropped).
 template <class S>
 __device__ __forceinline__ void fetch_loss_inputs(Ctx<S>& c, const ChainArgs& a) {
-  const int row = c.row0 + c.s;
-  const int rowc = row < a.rows ? row : a.rows - 1;
-  c.l_lo = a.mb_logp[rowc]; c.l_ad = a.mb_adv[rowc]; c.l_rt = a.mb_ret[rowc];
+  c.l_lo = a.b_logp[c.slot]; c.l_ad = a.b_adv[c.slot]; c.l_rt = a.b_ret[c.slot];
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     const int f = 8 * (i >> 2) + 4 * c.hh + (i & 3);
     const int fc = f < a.act_dim ? f : a.act_dim - 1;
-    c.l_act[i] = a.mb_act[(int64_t)rowc * a.act_dim + fc];
+    c.l_act[i] = a.b_act[c.slot * a.act_dim + fc];
   }
 }
 
@@ -547,12 +553,35 @@ __global__ __launch_bounds__(S::NW * 64) void train_chain_kernel(ChainArgs a) {
     c.s_red[S::NW * 40 + 32 + c.tid] = c.tid < a.act_dim ? expf(-ls) : 0.f;
   }
   {
-    // first layer's operand in natural order: lane (s, hh) holds features 16 ks + 8 hh .. + 7 of its sample
+    // The gather: this lane's sample (rows past the batch take the last sample; their results are dropped) and
+    // the first layer's operand in natural order, lane (s, hh) holding features 16 ks + 8 hh .. + 7 of its
+    // observation, converted to bf16 and zero padded.  The policy net's workgroups also leave the converted rows
+    // in x0 for the weight-gradient kernel.  All loads unconditional (clamped addresses, selected values).
     const int row = c.row0 + c.s;
-    const uint16_t* xr = a.x0 + (int64_t)row * D.d[0] + 8 * c.hh;
+    const int sm = a.idx[row < a.rows ? row : a.rows - 1];
+    c.slot = (int64_t)(sm / a.n_envs) * a.ld_envs + (sm % a.n_envs);
+    const float* orow = a.b_obs + c.slot * a.obs_dim;
+    const int O = a.obs_dim;
+    uint16_t* xw = a.x0 + (int64_t)row * D.d[0] + 8 * c.hh;
+    if (a.x0_ready) {                                  // wave-uniform
 #pragma unroll
-    for (int ks = 0; ks < D.d[0] / 16; ++ks)
-      c.xa[ks] = *reinterpret_cast<const uint4*>(xr + 16 * ks);       // rows past the batch: whatever the tile holds
+      for (int ks = 0; ks < D.d[0] / 16; ++ks) c.xa[ks] = *reinterpret_cast<const uint4*>(xw + 16 * ks);
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < D.d[0] / 16; ++ks) {
+        const int f0 = 16 * ks + 8 * c.hh;
+        float v[8];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          const int f = f0 + 4 * q;                    // O % 4 == 0: a piece is inside the row or past it
+          const float4 t = *reinterpret_cast<const float4*>(orow + (f < O ? f : O - 4));
+          v[4 * q + 0] = f < O ? t.x : 0.f; v[4 * q + 1] = f < O ? t.y : 0.f;
+          v[4 * q + 2] = f < O ? t.z : 0.f; v[4 * q + 3] = f < O ? t.w : 0.f;
+        }
+        c.xa[ks] = make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
+        if (c.net == 0) *reinterpret_cast<uint4*>(xw + 16 * ks) = c.xa[ks];      // arrays hold whole tiles
+      }
+    }
   }
   land_chunk<S, 1>(c);
   __syncthreads();
@@ -594,7 +623,7 @@ int launch_shape(gmi_instance* g, const ChainArgs& a, int rows, int* tiles_out, 
 
 namespace gmi {
 // One function per compiled shape (chain_p<k>.hip): launches the kernel if the model has exactly that shape,
-// GMI_ERR_UNSUPPORTED otherwise.
+// GMI_ERR_UNSUPPORTED otherwise.  rows == 0 only asks whether the shape matches.
 constexpr int kChainParts = 6;
 #define GMI_CHAIN_PART_DECL(k)                                                                              \
   int launch_chain_part##k(gmi_instance* g, const ModelLayout& L, const gmi_chain::ChainArgs& a, int rows, \
@@ -606,6 +635,7 @@ GMI_CHAIN_PART_DECL(3); GMI_CHAIN_PART_DECL(4); GMI_CHAIN_PART_DECL(5);
   GMI_CHAIN_PART_DECL(k) {                                                                        \
     using S = gmi_chain::ChainShape<__VA_ARGS__>;                                                 \
     if (!gmi_chain::shape_matches<S>(L)) return GMI_ERR_UNSUPPORTED;                              \
+    if (rows == 0) return GMI_OK;                                                                 \
     return gmi_chain::launch_shape<S>(g, a, rows, tiles_out, flops, bytes);                       \
   }
 }  // namespace gmi

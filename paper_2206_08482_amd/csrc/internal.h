@@ -270,7 +270,8 @@ int launch_permutation(gmi_instance* g, int n, uint64_t seed, uint32_t iteration
 // Register-chained trainer kernel (chain.hip): its weight stream in the shadow and the launch.
 int64_t chain_stream_bytes(const ModelLayout& L);
 int launch_chain_pack(gmi_instance* g, gmi_model* m);
-int launch_train_chain(gmi_instance* g, gmi_model* m, const gmi_ppo_hparams* hp, int rows, int* n_stat_rows);
+int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx, int rows,
+                       int* n_stat_rows);
 
 }  // namespace gmi
 

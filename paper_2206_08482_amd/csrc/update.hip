@@ -314,12 +314,9 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
   }
   bool gathered = false, chained = false;
   if (!fused && g->fusion >= 1 && want_grad && bf) {
-    // register-chained kernel (forward + loss + input gradients in one launch) where this shape has one
-    rc = gmi::launch_gather(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, &b->d);
-    if (rc != GMI_OK) return rc;
-    gathered = true;
+    // register-chained kernel (gather + forward + loss + input gradients in one launch) where this shape has one
     int n_stat_rows = 0;
-    rc = gmi::launch_train_chain(g, m, hp, rows, &n_stat_rows);
+    rc = gmi::launch_train_chain(g, m, b, hp, idx, rows, &n_stat_rows);
     if (rc == GMI_OK) { fused = true; chained = true; *n_loss_blocks_out = n_stat_rows; }
     else if (rc != GMI_ERR_UNSUPPORTED) return rc;
   }

@@ -136,8 +136,9 @@ def test_group_update_bf16_matches_oracle(g, name, n, n_envs, horizon, minibatch
                                        flat["adv"][idx], flat["ret"][idx], hp, want_grad=False)
     out = torch.zeros(5, device="cuda")
     h = g.ppo_hparams(clip=cfg.clip, c_v=cfg.c_v, c_e=cfg.c_e, minibatch=minibatch)
-    g.ppo_evaluate(ses[1].gmi, ses[1].model, ses[1].buffer, h, torch.tensor(idx.astype(np.int32), device="cuda"),
-                   minibatch, out)
+    d_idx = torch.tensor(idx.astype(np.int32), device="cuda")      # must outlive the asynchronous call
+    torch.cuda.synchronize()
+    g.ppo_evaluate(ses[1].gmi, ses[1].model, ses[1].buffer, h, d_idx, minibatch, out)
     ses[1].sync()
     o = out.cpu().numpy()
     assert abs(o[0] - r_eval[0]) <= 1e-3

@@ -30,11 +30,26 @@ def inst(g):
     g.gmi_destroy(h)
 
 
+# Tensors handed to the library must outlive the asynchronous work that reads them: a temporary passed straight
+# into a call is freed when the call returns, and the allocator may hand its memory to the next tensor (whose fill
+# runs on torch's stream) while the kernel is still reading it.  Everything dev() makes lives until the test ends.
+_KEEP = []
+
+
+@pytest.fixture(autouse=True)
+def _keep_device_inputs_alive():
+    yield
+    if torch.cuda.is_available():
+        torch.cuda.synchronize()
+    _KEEP.clear()
+
+
 def dev(x, dtype=None):
     t = torch.tensor(np.ascontiguousarray(x), device="cuda:0")
     if dtype is not None:
         t = t.to(dtype)
     torch.cuda.synchronize()
+    _KEEP.append(t)
     return t
 
 
