@@ -20,6 +20,7 @@ struct PackSeg {
 struct PackTable {
   int n;
   int total_blocks;
+  int gmax;               // tiles in the largest group (4 or 2)
   PackSeg s[2 * (GMI_MAX_HIDDEN + 1)];
 };
 
@@ -35,16 +36,16 @@ __global__ __launch_bounds__(256) void chain_pack_kernel(PackTable t0, PackTable
   const PackSeg& S = tab.s[si];
   const int nft = S.F >> 5, nks = S.K >> 4;
   int lb = blk - S.blk_start;
-  // locate the group: full groups of 4 tiles first, then (2), then (1)
-  const int full = nft >> 2;
+  // locate the group: full groups of gmax tiles first, then (2), then (1)
+  const int gm = tab.gmax, full = nft / gm;
   int tile0, gs;
-  if (lb < full * 4 * nks) {
-    const int gi = lb / (4 * nks);
-    tile0 = 4 * gi; gs = 4; lb -= gi * 4 * nks;
+  if (lb < full * gm * nks) {
+    const int gi = lb / (gm * nks);
+    tile0 = gm * gi; gs = gm; lb -= gi * gm * nks;
   } else {
-    lb -= full * 4 * nks;
-    tile0 = 4 * full;
-    if ((nft & 3) >= 2) {
+    lb -= full * gm * nks;
+    tile0 = gm * full;
+    if ((nft % gm) >= 2) {
       if (lb < 2 * nks) { gs = 2; }
       else { lb -= 2 * nks; tile0 += 2; gs = 1; }
     } else {
@@ -63,11 +64,25 @@ __global__ __launch_bounds__(256) void chain_pack_kernel(PackTable t0, PackTable
   reinterpret_cast<uint4*>(out)[(int64_t)blk * 64 + lane] = v;
 }
 
-ChainDims dims_of(const ModelLayout& L) {
+ChainDims dims_of(const ModelLayout& L, int gmax = 4) {
   ChainDims D;
   D.nl = L.n_layers;
+  D.gmax = gmax;
   for (int l = 0; l < L.n_layers; ++l) { D.d[l] = L.net[0][l].in_pad; D.d[l + 1] = L.net[0][l].out_pad; }
   return D;
+}
+
+typedef int (*part_fn)(gmi_instance*, const ModelLayout&, const ChainArgs&, int, int*, double, double);
+const part_fn kParts[gmi::kChainParts] = {gmi::launch_chain_part0, gmi::launch_chain_part1, gmi::launch_chain_part2,
+                                          gmi::launch_chain_part3, gmi::launch_chain_part4, gmi::launch_chain_part5};
+
+// The largest group of the kernel compiled for this model's shape; 0 if there is none.
+int compiled_gmax(const ModelLayout& L) {
+  ChainArgs none = {};
+  int gmax = 0;
+  for (int p = 0; p < gmi::kChainParts; ++p)
+    if (kParts[p](nullptr, L, none, 0, &gmax, 0.0, 0.0) == GMI_OK) return gmax;
+  return 0;
 }
 
 }  // namespace
@@ -97,10 +112,13 @@ int64_t chain_stream_bytes(const ModelLayout& L) {
 int launch_chain_pack(gmi_instance* g, gmi_model* m) {
   const ModelLayout& L = m->L;
   if (L.sh_chain_bytes == 0) return GMI_OK;
-  const ChainDims D = dims_of(L);
+  const int gmax = compiled_gmax(L);
+  if (gmax == 0) return GMI_OK;                        // no chained kernel for this shape: nobody reads the stream
+  const ChainDims D = dims_of(L, gmax);
   PackTable t[2];
   for (int net = 0; net < 2; ++net) {
     t[net].n = cd_nseg(D);
+    t[net].gmax = gmax;
     int blk = 0;
     for (int s = 0; s < cd_nseg(D); ++s) {
       PackSeg& ps = t[net].s[s];
@@ -171,19 +189,14 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_p
     }
   }
   bytes += 4.0 * rows * (L.act_dim + 3);
-  typedef int (*part_fn)(gmi_instance*, const ModelLayout&, const ChainArgs&, int, int*, double, double);
-  static const part_fn parts[kChainParts] = {launch_chain_part0, launch_chain_part1, launch_chain_part2,
-                                             launch_chain_part3, launch_chain_part4, launch_chain_part5};
+  if (compiled_gmax(L) == 0) return GMI_ERR_UNSUPPORTED;
   if (a.x0_ready) {       // unaligned observation rows: the gather kernel converts them (a lane-wise gather of 4-byte
                           // pieces at the start of the chained kernel measured slower than the separate launch)
-    rc = GMI_ERR_UNSUPPORTED;
-    for (int p = 0; p < kChainParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = parts[p](g, L, a, 0, &tiles, 0.0, 0.0);
-    if (rc != GMI_OK) return rc;
     rc = launch_gather(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, nullptr);
     if (rc != GMI_OK) return rc;
   }
   rc = GMI_ERR_UNSUPPORTED;
-  for (int p = 0; p < kChainParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = parts[p](g, L, a, rows, &tiles, flops, bytes);
+  for (int p = 0; p < kChainParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = kParts[p](g, L, a, rows, &tiles, flops, bytes);
   if (rc != GMI_OK) return rc;
   *n_stat_rows = tiles;
   return GMI_OK;

@@ -50,30 +50,34 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w 
 // i.e. at most 16 blocks.
 struct ChainDims {
   int nl;
+  int gmax;              // largest group: 4 or 2 feature tiles
   int d[GMI_MAX_HIDDEN + 2];
 };
 __host__ __device__ constexpr int cd_nseg(const ChainDims& D) { return 2 * D.nl - 1; }
 __host__ __device__ constexpr int cd_layer(const ChainDims& D, int s) { return s < D.nl ? s : 2 * D.nl - 1 - s; }
 __host__ __device__ constexpr int cd_K(const ChainDims& D, int s) { return s < D.nl ? D.d[s] : D.d[cd_layer(D, s) + 1]; }
 __host__ __device__ constexpr int cd_F(const ChainDims& D, int s) { return s < D.nl ? D.d[s + 1] : D.d[cd_layer(D, s)]; }
-__host__ __device__ constexpr int cd_ngroups(int nft) { return nft / 4 + ((nft & 3) >= 2 ? 1 : 0) + (nft & 1); }
-__host__ __device__ constexpr int cd_gsize(int nft, int gi) {
-  const int full = nft / 4;
-  if (gi < full) return 4;
-  if (gi == full && (nft & 3) >= 2) return 2;
+// nft tiles = nft / gmax groups of gmax, then (2), then (1)
+__host__ __device__ constexpr int cd_ngroups(int nft, int gmax) {
+  return nft / gmax + ((nft % gmax) >= 2 ? 1 : 0) + ((nft % gmax) & 1);
+}
+__host__ __device__ constexpr int cd_gsize(int nft, int gi, int gmax) {
+  const int full = nft / gmax;
+  if (gi < full) return gmax;
+  if (gi == full && (nft % gmax) >= 2) return 2;
   return 1;
 }
-__host__ __device__ constexpr int cd_gtile0(int nft, int gi) {
-  const int full = nft / 4;
-  if (gi <= full) return 4 * gi;
-  return 4 * full + 2;
+__host__ __device__ constexpr int cd_gtile0(int nft, int gi, int gmax) {
+  const int full = nft / gmax;
+  if (gi <= full) return gmax * gi;
+  return gmax * full + 2;
 }
 __host__ __device__ constexpr int cd_kcsteps(int gs) { return 16 / gs; }
 __host__ __device__ constexpr int cd_group_chunks(int nks, int gs) { return (nks + cd_kcsteps(gs) - 1) / cd_kcsteps(gs); }
 __host__ __device__ constexpr int cd_seg_chunks(const ChainDims& D, int s) {
   const int nft = cd_F(D, s) / 32, nks = cd_K(D, s) / 16;
   int n = 0;
-  for (int gi = 0; gi < cd_ngroups(nft); ++gi) n += cd_group_chunks(nks, cd_gsize(nft, gi));
+  for (int gi = 0; gi < cd_ngroups(nft, D.gmax); ++gi) n += cd_group_chunks(nks, cd_gsize(nft, gi, D.gmax));
   return n;
 }
 __host__ __device__ constexpr int cd_seg_blocks(const ChainDims& D, int s) { return (cd_F(D, s) / 32) * (cd_K(D, s) / 16); }
@@ -96,19 +100,24 @@ __host__ __device__ constexpr int cd_maxdim(const ChainDims& D) {
 struct ChunkInfo {
   int seg, gi, gs, tile0, ks0, nks, blk_off, nblk;
   bool first, last;      // first / last chunk of its group
+  int gord;              // ordinal of the group among all groups of the plan
+  int prev_last;         // index of the last chunk of the previous group (-1 for the first group)
+  int seg_nks;           // k steps of the segment
 };
 __host__ __device__ constexpr ChunkInfo cd_chunk(const ChainDims& D, int c) {
-  ChunkInfo ci = {0, 0, 0, 0, 0, 0, 0, 0, false, false};
-  int blk = 0, cc = 0;
+  ChunkInfo ci = {0, 0, 0, 0, 0, 0, 0, 0, false, false, 0, -1, 0};
+  int blk = 0, cc = 0, gord = 0;
   for (int s = 0; s < cd_nseg(D); ++s) {
     const int nft = cd_F(D, s) / 32, nks = cd_K(D, s) / 16;
-    for (int gi = 0; gi < cd_ngroups(nft); ++gi) {
-      const int gs = cd_gsize(nft, gi), nc = cd_group_chunks(nks, gs), kcs = cd_kcsteps(gs);
+    for (int gi = 0; gi < cd_ngroups(nft, D.gmax); ++gi, ++gord) {
+      const int gs = cd_gsize(nft, gi, D.gmax), nc = cd_group_chunks(nks, gs), kcs = cd_kcsteps(gs);
+      const int group_first = cc;
       for (int kc = 0; kc < nc; ++kc) {
         const int k0 = kc * kcs, n = (nks - k0) < kcs ? (nks - k0) : kcs;
         if (cc == c) {
-          ci.seg = s; ci.gi = gi; ci.gs = gs; ci.tile0 = cd_gtile0(nft, gi); ci.ks0 = k0; ci.nks = n;
+          ci.seg = s; ci.gi = gi; ci.gs = gs; ci.tile0 = cd_gtile0(nft, gi, D.gmax); ci.ks0 = k0; ci.nks = n;
           ci.blk_off = blk; ci.nblk = n * gs; ci.first = kc == 0; ci.last = kc == nc - 1;
+          ci.gord = gord; ci.prev_last = group_first - 1; ci.seg_nks = nks;
           return ci;
         }
         blk += n * gs;
@@ -117,6 +126,24 @@ __host__ __device__ constexpr ChunkInfo cd_chunk(const ChainDims& D, int c) {
     }
   }
   return ci;
+}
+
+// The epilogue of a group (bias + ELU or ELU', conversion, row-major store) is cut into items: 4 per tile
+// (a quad of the lane's 16 results each) and then the 2 * gs store steps of the transposition buffer.
+__host__ __device__ constexpr int cd_items(int gs) { return 6 * gs; }
+// Deferred epilogues: a group whose last chunk is cl may run its items inside the k steps of the next group
+// (on a second accumulator set), where the matrix unit hides them.  avail = the k steps of the next group that
+// may carry items: all of them inside a segment; across a segment boundary only those before the next
+// segment starts to read this group's results (k step 2 * tile0).  0 = the epilogue runs at once: the head
+// (its loss needs the whole workgroup), the last group of the plan, and groups with too few k steps after them.
+__host__ __device__ constexpr int cd_defer_avail(const ChainDims& D, int cl, bool enabled) {
+  if (!enabled || cl < 0 || cl + 1 >= cd_nchunks(D)) return 0;
+  const ChunkInfo ci = cd_chunk(D, cl);
+  if (!ci.last || ci.seg == D.nl - 1) return 0;
+  const ChunkInfo nx = cd_chunk(D, cl + 1);
+  int avail = nx.seg_nks;
+  if (nx.seg != ci.seg && 2 * ci.tile0 < avail) avail = 2 * ci.tile0;
+  return avail >= 4 ? avail : 0;
 }
 
 // number of k steps in the chunks before chunk c (the operand ring below is indexed by it)
@@ -157,13 +184,16 @@ constexpr int kScrStride = 272;                    // bytes per row of a wave's 
 constexpr int kScrBytes = 32 * kScrStride;
 
 // A compile-time description of one model shape: NW waves per workgroup, DEPTH chunks of weights in flight,
-// then the padded widths d[0..nl].
-template <int NW_, int DEPTH_, int... DIMS>
+// GMAX tiles in the largest group, DEFER = 1 if epilogues run inside the next group's products, then the padded
+// widths d[0..nl].
+template <int NW_, int DEPTH_, int GMAX_, int DEFER_, int... DIMS>
 struct ChainShape {
-  static constexpr int NW = NW_, NT = NW_ * 64, DEPTH = DEPTH_;
+  static constexpr int NW = NW_, NT = NW_ * 64, DEPTH = DEPTH_, GMAX = GMAX_;
+  static constexpr bool DEFER = DEFER_ != 0;
+  static_assert(GMAX_ == 4 || GMAX_ == 2, "groups of at most 4 or 2 tiles");
   static constexpr int NL = (int)sizeof...(DIMS) - 1;
   static constexpr int LPT = (16 * 64 + NT - 1) / NT;      // 16-byte pieces of a chunk per thread
-  static constexpr ChainDims dims() { return ChainDims{NL, {DIMS...}}; }
+  static constexpr ChainDims dims() { return ChainDims{NL, GMAX_, {DIMS...}}; }
   static constexpr int maxks() { return cd_maxdim(dims()) / 16; }
   static constexpr int nch() { return cd_nchunks(dims()); }
   static constexpr int bias_total() {
@@ -184,10 +214,11 @@ struct ChainShape {
 template <class S>
 struct Ctx {
   uint4 xa[S::maxks()], xb[S::maxks()];      // activation operands of the current layer: in / out (ping-pong by segment)
-  floatx16 acc[4];
+  floatx16 acc[2][4];                    // two accumulator sets: groups alternate (see cd_defer_avail)
   uint4 stage[S::DEPTH][S::LPT];         // weight chunks in flight
   bf16x8 wq[3][4];                       // weight operands of k steps g, g+1, g+2 (ring indexed by g % 3)
   uint4 ht[8];                           // stored activations of the group (input-gradient segments)
+  uint4 ipre[2];                         // LDS operand of the epilogue item in work / of the next one
   int64_t slot;                          // this lane's sample in the experience buffer
   float l_act[16], l_lo, l_ad, l_rt;     // this lane's loss inputs (fetched at kernel start): actions of its 16
                                          // features, old log-prob, advantage, return
@@ -234,6 +265,15 @@ __device__ __forceinline__ void scr_to_global(const char* scr, int lane, uint16_
     *reinterpret_cast<uint4*>(dst + (int64_t)(row0 + r) * ld + col0 + ch * 8) = v;     // arrays hold whole tiles
   }
 }
+// one of the 2 * GS steps of scr_to_global
+template <int GS>
+__device__ __forceinline__ void scr_to_global_step(const char* scr, int lane, uint16_t* dst, int ld, int col0, int row0,
+                                                   int it) {
+  constexpr int LPR = 4 * GS, RPI = 64 / LPR;
+  const int r = it * RPI + lane / LPR, ch = lane % LPR;
+  const uint4 v = *reinterpret_cast<const uint4*>(scr + r * kScrStride + ch * 16);
+  *reinterpret_cast<uint4*>(dst + (int64_t)(row0 + r) * ld + col0 + ch * 8) = v;     // arrays hold whole tiles
+}
 template <int GS>
 __device__ __forceinline__ void global_to_regs(uint4* ht, int lane, const uint16_t* src, int ld, int col0, int row0,
                                                int rows) {
@@ -278,13 +318,12 @@ __device__ __forceinline__ void fetch_loss_inputs(Ctx<S>& c, const ChainArgs& a)
 }
 
 template <class S>
-__device__ __forceinline__ void loss_epilogue(Ctx<S>& c, const ChainArgs& a, uint4* xo) {
+__device__ __forceinline__ void loss_epilogue(Ctx<S>& c, const ChainArgs& a, const floatx16& acc, uint4* xo) {
   constexpr int HB = S::bias_off(S::NL - 1);
   const int A = a.act_dim;
   const int row = c.row0 + c.s;
   const bool ok = row < a.rows;
   const float inv_m = 1.0f / (float)a.rows;
-  const floatx16& acc = c.acc[0];
   float d[16];
   float* red = c.s_red + c.wave * 40;
   if (c.net == 0) {
@@ -417,21 +456,140 @@ __host__ __device__ constexpr int fetch_count() {
   }
 }
 
-template <class S, int C, int K>
-__device__ __forceinline__ void compute_ksteps(Ctx<S>& c, const uint4* xi) {
-  constexpr ChunkInfo ci = cd_chunk(S::dims(), C);
-  if constexpr (K < ci.nks) {
-    constexpr int g = cd_ksteps_before(S::dims(), C) + K;
-    fetch_kstep<S, C, K + 2, (g + 2) % 3>(c);
-    const bf16x8 xk = __builtin_bit_cast(bf16x8, xi[ci.ks0 + K]);
-#pragma unroll
-    for (int t = 0; t < ci.gs; ++t)
-      c.acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c.wq[g % 3][t], xk, c.acc[t], 0, 0, 0);
+// Item I of the epilogue of the group whose last chunk is PC (cd_items): quads first, then the store steps.
+// Each item is cut in two: its LDS read into c.ipre[I % 2] (item_load) and the rest (item_compute), so that the
+// read of item I + 1 is in flight while item I is worked on.
+template <class S, int PC, int I>
+__device__ __forceinline__ void item_load(Ctx<S>& c) {
+  constexpr ChainDims D = S::dims();
+  constexpr ChunkInfo pi = cd_chunk(D, PC);
+  constexpr int NL = S::NL, GS = pi.gs;
+  constexpr bool bwd = pi.seg >= NL;
+  if constexpr (I < 4 * GS) {
+    constexpr int t = I / 4, q = I % 4;
+    if constexpr (bwd) {
+      const uint2 hv = *reinterpret_cast<const uint2*>(c.scr + c.s * kScrStride + (32 * t + 8 * q + 4 * c.hh) * 2);
+      c.ipre[I % 2].x = hv.x; c.ipre[I % 2].y = hv.y;
+    } else {
+      constexpr int boff = S::bias_off(cd_layer(D, pi.seg));
+      c.ipre[I % 2] = *reinterpret_cast<const uint4*>(c.s_bias + boff + 32 * (pi.tile0 + t) + 8 * q + 4 * c.hh);
+    }
+  } else if constexpr (I < cd_items(GS)) {
+    constexpr int LPR = 4 * GS, RPI = 64 / LPR, it = I - 4 * GS;
+    const int r = it * RPI + c.lane / LPR, ch = c.lane % LPR;
+    c.ipre[I % 2] = *reinterpret_cast<const uint4*>(c.scr + r * kScrStride + ch * 16);
+  }
+}
+template <class S, int PC, int I>
+__device__ __forceinline__ void item_compute(Ctx<S>& c, const ChainArgs& a) {
+  constexpr ChainDims D = S::dims();
+  constexpr ChunkInfo pi = cd_chunk(D, PC);
+  constexpr int NL = S::NL, GS = pi.gs;
+  constexpr bool bwd = pi.seg >= NL;
+  constexpr int layer = cd_layer(D, pi.seg);
+  uint4* xo = (pi.seg & 1) ? c.xa : c.xb;
+  const uint4 pre = c.ipre[I % 2];
+  if constexpr (I < 4 * GS) {
+    constexpr int t = I / 4, q = I % 4;
+    const floatx16& acc = c.acc[pi.gord & 1][t];
+    float v0 = acc[4 * q + 0], v1 = acc[4 * q + 1], v2 = acc[4 * q + 2], v3 = acc[4 * q + 3];
+    if constexpr (bwd) {
+      // times ELU'(z) through the stored output h = ELU(z): 1 if h > 0 else h + 1
+      const float h0 = bf16_lo(pre.x), h1 = bf16_hi(pre.x), h2 = bf16_lo(pre.y), h3 = bf16_hi(pre.y);
+      v0 *= h0 > 0.f ? 1.f : h0 + 1.f; v1 *= h1 > 0.f ? 1.f : h1 + 1.f;
+      v2 *= h2 > 0.f ? 1.f : h2 + 1.f; v3 *= h3 > 0.f ? 1.f : h3 + 1.f;
+    } else {
+      v0 = elu_f(v0 + __uint_as_float(pre.x)); v1 = elu_f(v1 + __uint_as_float(pre.y));
+      v2 = elu_f(v2 + __uint_as_float(pre.z)); v3 = elu_f(v3 + __uint_as_float(pre.w));
+    }
+    const uint32_t w0 = pack_bf16(v0, v1), w1 = pack_bf16(v2, v3);
+    *reinterpret_cast<uint2*>(c.scr + c.s * kScrStride + (32 * t + 8 * q + 4 * c.hh) * 2) = make_uint2(w0, w1);
+    uint4& x = xo[2 * (pi.tile0 + t) + q / 2];
+    if constexpr (q % 2 == 0) { x.x = w0; x.y = w1; } else { x.z = w0; x.w = w1; }
+  } else {
+    constexpr int LPR = 4 * GS, RPI = 64 / LPR, it = I - 4 * GS;
+    const int r = it * RPI + c.lane / LPR, ch = c.lane % LPR;
+    uint16_t* dst = bwd ? a.dz[c.net][layer - 1] : a.h[c.net][layer + 1];
+    constexpr int ld = bwd ? D.d[layer] : D.d[layer + 1];
+    *reinterpret_cast<uint4*>(dst + (int64_t)(c.row0 + r) * ld + 32 * pi.tile0 + ch * 8) = pre;    // arrays hold whole tiles
+  }
+}
+// Item I with the read of item I + 1 issued ahead of it -- except the first store step's, which reads what the
+// last quad writes.
+template <class S, int PC, int I>
+__device__ __forceinline__ void item_step(Ctx<S>& c, const ChainArgs& a) {
+  constexpr int NQ = 4 * cd_chunk(S::dims(), PC).gs;
+  if constexpr (I + 1 != NQ) item_load<S, PC, I + 1>(c);
+  item_compute<S, PC, I>(c, a);
+  if constexpr (I + 1 == NQ) item_load<S, PC, I + 1>(c);
+}
+// Items [I, END) one after the other, each in a scheduling region of its own (so that the read of the next
+// item stays ahead of the work on this one).  The read of item I must have been issued.
+template <class S, int PC, int I, int END>
+__device__ __forceinline__ void epilogue_items(Ctx<S>& c, const ChainArgs& a) {
+  if constexpr (I < END) {
+    item_step<S, PC, I>(c, a);
+    __builtin_amdgcn_sched_barrier(0);
+    epilogue_items<S, PC, I + 1, END>(c, a);
+  }
+}
+
+// One k step: its GS products, with the previous group's deferred items between them -- a wave issues in order,
+// so an item placed behind a block of products would start only when the last of them has entered the matrix
+// unit.  Item i of the slice [I0, I1) follows product i.
+template <class S, int C, int K, int T, int I0, int I1>
+__device__ __forceinline__ void kstep_products(Ctx<S>& c, const ChainArgs& a, const bf16x8& xk) {
+  constexpr ChainDims D = S::dims();
+  constexpr ChunkInfo ci = cd_chunk(D, C);
+  if constexpr (T < ci.gs || I0 + T < I1) {
+    constexpr int g = cd_ksteps_before(D, C) + K;
+    if constexpr (T < ci.gs)
+      c.acc[ci.gord & 1][T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c.wq[g % 3][T], xk, c.acc[ci.gord & 1][T], 0, 0, 0);
+    if constexpr (I0 + T < I1) {
+      item_step<S, ci.prev_last, I0 + T>(c, a);
+    }
     // nothing moves across this point: the schedule keeps the LDS reads of k step g+2 ahead of the products of
     // k step g (left to itself the scheduler sinks every read to just before its use, and with one wave per
     // SIMD each product then waits a full LDS round trip)
-    __builtin_amdgcn_sched_barrier(0);
-    compute_ksteps<S, C, K + 1>(c, xi);
+    if constexpr (I0 + T < I1 || T + 1 >= ci.gs) __builtin_amdgcn_sched_barrier(0);
+    kstep_products<S, C, K, T + 1, I0, I1>(c, a, xk);
+  }
+}
+
+template <class S, int C, int K>
+__device__ __forceinline__ void compute_ksteps(Ctx<S>& c, const ChainArgs& a, const uint4* xi) {
+  constexpr ChainDims D = S::dims();
+  constexpr ChunkInfo ci = cd_chunk(D, C);
+  if constexpr (K < ci.nks) {
+    constexpr int g = cd_ksteps_before(D, C) + K;
+    fetch_kstep<S, C, K + 2, (g + 2) % 3>(c);
+    const bf16x8 xk = __builtin_bit_cast(bf16x8, xi[ci.ks0 + K]);
+    // the slice of the previous group's deferred epilogue that this k step carries
+    constexpr int avail = cd_defer_avail(D, ci.prev_last, S::DEFER);
+    if constexpr (avail > 0) {
+      constexpr int N = cd_items(cd_chunk(D, ci.prev_last).gs), ipk = (N + avail - 1) / avail;
+      constexpr int kg = ci.ks0 + K, i0 = kg * ipk < N ? kg * ipk : N, i1 = (i0 + ipk) < N ? (i0 + ipk) : N;
+      kstep_products<S, C, K, 0, i0, i1>(c, a, xk);
+    } else {
+      kstep_products<S, C, K, 0, 0, 0>(c, a, xk);
+    }
+    compute_ksteps<S, C, K + 1>(c, a, xi);
+  }
+}
+
+// The stored activations that the input-gradient group after chunk C multiplies its results with (ELU'), fetched
+// one group ahead: from the head's chunk for the first such group, then as soon as a group has handed its own
+// to the transposition buffer.  (A group's k steps are over long before a fetch issued inside them returns.)
+template <class S, int C>
+__device__ __forceinline__ void fetch_next_h(Ctx<S>& c, const ChainArgs& a) {
+  constexpr ChainDims D = S::dims();
+  if constexpr (S::DEFER && C + 1 < S::nch()) {       // without deferred epilogues a group fetches its own, in its last chunk
+    constexpr ChunkInfo nx = cd_chunk(D, C + 1);
+    static_assert(nx.first, "called at the end of a group");
+    if constexpr (nx.seg >= S::NL) {
+      constexpr int layer = cd_layer(D, nx.seg);
+      global_to_regs<nx.gs>(c.ht, c.lane, a.h[c.net][layer], D.d[layer], 32 * nx.tile0, c.row0, a.rows);
+    }
   }
 }
 
@@ -453,52 +611,31 @@ __device__ __forceinline__ void chain_step(Ctx<S>& c, const ChainArgs& a) {
   issue_chunk<S, C + 1 + S::DEPTH>(c);
   if constexpr (seg == NL - 2 && ci.gi == 0 && ci.first) fetch_loss_inputs<S>(c, a);
 
-  if constexpr (bwd && ci.last)        // stored activations of this group's features, for ELU'
+  if constexpr (!S::DEFER && bwd && ci.last)        // stored activations of this group's features, for ELU'
     global_to_regs<GS>(c.ht, c.lane, a.h[c.net][layer], D.d[layer], 32 * ci.tile0, c.row0, a.rows);
 
   if constexpr (ci.first) {
 #pragma unroll
     for (int t = 0; t < GS; ++t)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) c.acc[t][v] = 0.f;
+      for (int v = 0; v < 16; ++v) c.acc[ci.gord & 1][t][v] = 0.f;
   }
-  compute_ksteps<S, C, 0>(c, xi);
+  compute_ksteps<S, C, 0>(c, a, xi);
 
   if constexpr (ci.last) {
     if constexpr (!bwd && layer == NL - 1) {
       static_assert(GS == 1, "the head is one 32-wide tile");
-      loss_epilogue<S>(c, a, xo);
+      fetch_next_h<S, C>(c, a);
+      loss_epilogue<S>(c, a, c.acc[ci.gord & 1][0], xo);
     } else {
-      if constexpr (bwd) regs_to_scr<GS>(c.ht, c.lane, c.scr);
-      constexpr int boff = bwd ? 0 : S::bias_off(layer);
-#pragma unroll
-      for (int t = 0; t < GS; ++t) {
-        uint32_t w[8];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          float v0 = c.acc[t][4 * q + 0], v1 = c.acc[t][4 * q + 1], v2 = c.acc[t][4 * q + 2], v3 = c.acc[t][4 * q + 3];
-          char* sp = c.scr + c.s * kScrStride + (32 * t + 8 * q + 4 * c.hh) * 2;
-          if constexpr (bwd) {
-            // times ELU'(z) through the stored output h = ELU(z): 1 if h > 0 else h + 1
-            const uint2 hv = *reinterpret_cast<const uint2*>(sp);
-            const float h0 = bf16_lo(hv.x), h1 = bf16_hi(hv.x), h2 = bf16_lo(hv.y), h3 = bf16_hi(hv.y);
-            v0 *= h0 > 0.f ? 1.f : h0 + 1.f; v1 *= h1 > 0.f ? 1.f : h1 + 1.f;
-            v2 *= h2 > 0.f ? 1.f : h2 + 1.f; v3 *= h3 > 0.f ? 1.f : h3 + 1.f;
-          } else {
-            const float4 bv = *reinterpret_cast<const float4*>(c.s_bias + boff + 32 * (ci.tile0 + t) + 8 * q + 4 * c.hh);
-            v0 = elu_f(v0 + bv.x); v1 = elu_f(v1 + bv.y); v2 = elu_f(v2 + bv.z); v3 = elu_f(v3 + bv.w);
-          }
-          w[2 * q] = pack_bf16(v0, v1);
-          w[2 * q + 1] = pack_bf16(v2, v3);
-          *reinterpret_cast<uint2*>(sp) = make_uint2(w[2 * q], w[2 * q + 1]);
-        }
-        xo[2 * (ci.tile0 + t)] = make_uint4(w[0], w[1], w[2], w[3]);
-        xo[2 * (ci.tile0 + t) + 1] = make_uint4(w[4], w[5], w[6], w[7]);
+      // the stored activations go to the transposition buffer now (the previous group's items are done with it),
+      // the rest of the epilogue either now or inside the next group's k steps
+      if constexpr (bwd) {
+        regs_to_scr<GS>(c.ht, c.lane, c.scr);
+        fetch_next_h<S, C>(c, a);
       }
-      if constexpr (bwd)
-        scr_to_global<GS>(c.scr, c.lane, a.dz[c.net][layer - 1], D.d[layer], 32 * ci.tile0, c.row0, a.rows);
-      else
-        scr_to_global<GS>(c.scr, c.lane, a.h[c.net][layer + 1], D.d[layer + 1], 32 * ci.tile0, c.row0, a.rows);
+      item_load<S, C, 0>(c);
+      if constexpr (cd_defer_avail(D, C, S::DEFER) == 0) epilogue_items<S, C, 0, cd_items(GS)>(c, a);
     }
   }
 
@@ -623,7 +760,8 @@ int launch_shape(gmi_instance* g, const ChainArgs& a, int rows, int* tiles_out, 
 
 namespace gmi {
 // One function per compiled shape (chain_p<k>.hip): launches the kernel if the model has exactly that shape,
-// GMI_ERR_UNSUPPORTED otherwise.  rows == 0 only asks whether the shape matches.
+// GMI_ERR_UNSUPPORTED otherwise.  rows == 0 only asks whether the shape matches (*tiles_out = the
+// shape's largest group, which the layout of the weight stream depends on).
 constexpr int kChainParts = 6;
 #define GMI_CHAIN_PART_DECL(k)                                                                              \
   int launch_chain_part##k(gmi_instance* g, const ModelLayout& L, const gmi_chain::ChainArgs& a, int rows, \
@@ -635,7 +773,7 @@ GMI_CHAIN_PART_DECL(3); GMI_CHAIN_PART_DECL(4); GMI_CHAIN_PART_DECL(5);
   GMI_CHAIN_PART_DECL(k) {                                                                        \
     using S = gmi_chain::ChainShape<__VA_ARGS__>;                                                 \
     if (!gmi_chain::shape_matches<S>(L)) return GMI_ERR_UNSUPPORTED;                              \
-    if (rows == 0) return GMI_OK;                                                                 \
+    if (rows == 0) { *tiles_out = S::GMAX; return GMI_OK; }                                       \
     return gmi_chain::launch_shape<S>(g, a, rows, tiles_out, flops, bytes);                       \
   }
 }  // namespace gmi
