@@ -43,13 +43,13 @@ def main() -> int:
     train_args = dict(gamma=cfg.gamma, lam=cfg.lam, epochs=cfg.epochs, minibatch=cfg.minibatch, clip=cfg.clip,
                       c_v=cfg.c_v, c_e=cfg.c_e, lr=cfg.lr)
 
-    def run(label, schedule, agent_masks, trainer_mask, single_stream):
+    def run(label, schedule, agent_masks, trainer_mask, single_stream, host_ordered=False):
         pipe = InstancePipeline(n_agents=n_ag, n_envs=cfg.n_envs, obs_dim=cfg.obs_dim, act_dim=cfg.act_dim,
                                 hidden=cfg.hidden, horizon=cfg.horizon, dtype=cfg.dtype, theta=theta, a_mat=a_mat,
                                 b_mat=b_mat, state0=states, noise_std=cfg.noise_std, reward_scale=cfg.reward_scale,
                                 done_period=cfg.done_period, done_threshold=thr, seed=cfg.seed,
                                 minibatch=cfg.minibatch, agent_masks=agent_masks, trainer_mask=trainer_mask,
-                                single_stream=single_stream)
+                                single_stream=single_stream, host_ordered=host_ordered)
         s0 = [torch.tensor(s, device="cuda:0") for s in states]
         torch.cuda.synchronize()
 
@@ -72,7 +72,7 @@ def main() -> int:
         ok = bool(torch.isfinite(pipe.theta).all().item())
         a_cus, t_cus = pipe.cu_counts()
         pipe.close()
-        return {"layout": label, "schedule": schedule, "agent_cus_each": a_cus[0], "trainer_cus": t_cus,
+        return {"layout": label, "schedule": schedule, "hand_off": "host" if host_ordered else "events", "agent_cus_each": a_cus[0], "trainer_cus": t_cus,
                 "ms_per_iteration": dt * 1e3, "samples_per_s": cfg.batch / dt, "finite": ok}
 
     rows = [run("single unmasked stream", "sync", None, None, True),
@@ -84,10 +84,22 @@ def main() -> int:
         for style in ("contiguous", "interleaved"):
             # the agents' share is split evenly over the agent instances
             masks = cu_masks(n_cu, [a // n_ag // 8 * 8] * n_ag + [t], style)
-            rows.append(run(f"agents {a}/{n_ag} + trainer {t} CUs, {style}", "pipelined", masks[:n_ag], masks[n_ag], False))
+            for ho in (False, True):
+                rows.append(run(f"agents {a}/{n_ag} + trainer {t} CUs, {style}", "pipelined", masks[:n_ag], masks[n_ag],
+                                False, ho))
             # the agents share one CU set
             shared = cu_masks(n_cu, [a, t], style)
             rows.append(run(f"agents share {a} + trainer {t} CUs, {style}", "pipelined", [shared[0]] * n_ag, shared[1], False))
+    # the agents on disjoint CU sets that together cover the device, the trainer on all of it: with the synchronous
+    # schedule the two stages never run at the same time, so the trainer needs no mask of its own
+    for style in ("contiguous", "interleaved"):
+        for parts in (n_ag, 2):
+            masks = cu_masks(n_cu, [n_cu // parts // 8 * 8] * parts, style)
+            masks = [masks[i % parts] for i in range(n_ag)]
+            for schedule, ho in (("sync", False), ("sync", True), ("pipelined", True)):
+                rows.append(run(f"agents on {parts} disjoint sets of {n_cu // parts} CUs, trainer unmasked, {style}", schedule,
+                                masks, None, False, ho))
+    rows.append(run("5 unmasked streams", "sync", None, None, False, True))
     base = rows[0]["samples_per_s"]
     for r in rows:
         r["vs_single_stream"] = r["samples_per_s"] / base

@@ -78,7 +78,7 @@ const char* gmi_last_error(void);
  * the row-tile fused kernel (observation conversion, all layers of both nets and the sampling epilogue
  * in one launch) whenever the model fits it.  2: ppo_update also uses the row-tile fused trainer kernel
  * (gather + forward + loss + input gradients in one launch; currently slower than the per-layer
- * kernels at minibatches of tens of thousands of rows, see DESIGN.md).  All levels give results within
+ * kernels at minibatches of tens of thousands of rows).  All levels give results within
  * the same tolerances. */
 int gmi_set_fusion(gmi_t gmi, int enable);
 
@@ -86,7 +86,11 @@ int gmi_set_fusion(gmi_t gmi, int enable);
  * recv of Listing 1, and the experience / parameter movements of Table 5, which on one device need
  * no host bounce): work queued on dst after this call sees everything queued on src before it.
  * If bytes > 0 and src_ptr != dst_ptr, a device-to-device copy of `bytes` is queued on src first.
- * bytes == 0 or src_ptr == dst_ptr: ordering only.  src == dst is allowed (plain copy). dev ptrs. */
+ * bytes == 0 or src_ptr == dst_ptr: ordering only.  src == dst is allowed (plain copy). dev ptrs.
+ * The wait is queued on dst's stream.  Measured on MI355X: while the stream of a CU-masked instance holds
+ * work that waits for such an event, kernels of all other instances run about 1.6 times slower; a
+ * caller that hands work to masked instances does better to gmi_sync(src) on the host first and to
+ * queue the dependent work afterwards (no call of this function needed then). */
 int gmi_transfer(gmi_t src, gmi_t dst, const void* src_ptr, void* dst_ptr, size_t bytes);
 
 /* ------------------------------------------------------------------ model ------------------- */

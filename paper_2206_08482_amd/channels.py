@@ -11,7 +11,7 @@ from typing import Optional, Sequence
 import torch
 
 from . import (CHANNELS_MULTI, gae_compute, gmi_buffer_bind, gmi_buffer_destroy, gmi_channels_create,
-               gmi_channels_destroy, gmi_channels_pop, gmi_channels_push, gmi_transfer, ppo_hparams, ppo_update,
+               gmi_channels_destroy, gmi_channels_pop, gmi_channels_push, ppo_hparams, ppo_update,
                rollout_collect)
 from .instances import InstancePipeline
 from .runner import RolloutBuffers
@@ -38,7 +38,8 @@ class ChannelPipeline(InstancePipeline):
             rollout_collect(ag.gmi, ag.model, ag.env, handle, ag.obs[ag.cur], ag.seed, iteration * self.T, 0, lv)
             gmi_channels_push(ag.gmi, self.channels, handle, lv)
             # the published weights these agents read may only be replaced after this round's collection
-            gmi_transfer(ag.gmi, self.trainer, None, None, 0)
+            self._hand_to_trainer(ag)
+        self._agents_done()
 
     def train(self, iteration: int, slot: int, *, gamma: float, lam: float, epochs: int, minibatch: int,
               stats=None, **hp) -> None:

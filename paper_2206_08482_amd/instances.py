@@ -84,13 +84,17 @@ class InstancePipeline:
                  done_threshold: int, seed: int, minibatch: int,
                  agent_masks: Optional[Sequence[Optional[Sequence[int]]]] = None,
                  trainer_mask: Optional[Sequence[int]] = None, single_stream: bool = False,
-                 fused_rollout: bool = True):
+                 fused_rollout: bool = True, host_ordered: bool = False):
         dev = torch.device("cuda:0")
         f = dict(dtype=torch.float32, device=dev)
         self.n_agents, self.N, self.O, self.A, self.T = n_agents, n_envs, obs_dim, act_dim, horizon
         self.Ntot = n_agents * n_envs
         self.seed = seed
         self.single_stream = single_stream
+        # host_ordered: the host waits for a stage to finish before it hands the next one to another instance, so no
+        # instance's queue ever holds work that waits for an event.  Measured on MI355X: while a CU-masked queue
+        # holds such a waiting packet, kernels of every other queue run ~1.6x slower.
+        self.host_ordered = host_ordered and not single_stream
         self.fused_rollout = fused_rollout and dtype == "bf16"      # one launch per agent and horizon where it fits
         self.trainer = gmi_create(trainer_mask)
         self.theta = torch.tensor(theta, **f)
@@ -144,11 +148,14 @@ class InstancePipeline:
     def publish(self) -> None:
         """trainer -> agents: copy the freshly written shadow (or fp32 parameters) to the published copy,
         then let every agent instance wait for it."""
-        first = self.agents[0].gmi
+        first = self.trainer if self.host_ordered else self.agents[0].gmi
         if self.shadow_bytes:
             gmi_transfer(self.trainer, first, self.shadow[0], self.shadow[1], self.shadow_bytes)
         else:
             gmi_transfer(self.trainer, first, self.theta, self.theta_pub, self.theta.numel() * 4)
+        if self.host_ordered:
+            gmi_sync(self.trainer)
+            return
         for ag in self.agents[1:]:
             gmi_transfer(self.trainer, ag.gmi, None, None, 0)
 
@@ -162,7 +169,8 @@ class InstancePipeline:
                     lv = self.last_value[slot].data_ptr() + i * self.N * 4
                     rollout_collect(ag.gmi, ag.model, ag.env, ag.buffer[slot], ag.obs[ag.cur], ag.seed, iteration * T,
                                     0, lv)
-                    gmi_transfer(ag.gmi, self.trainer, None, None, 0)
+                    self._hand_to_trainer(ag)
+                self._agents_done()
                 return
             except GmiError as e:
                 if e.code != ERR_UNSUPPORTED:
@@ -179,7 +187,17 @@ class InstancePipeline:
         for i, ag in enumerate(self.agents):
             lv = self.last_value[slot].data_ptr() + i * self.N * 4
             agent_value(ag.gmi, ag.model, ag.obs[ag.cur], self.N, lv)
-            gmi_transfer(ag.gmi, self.trainer, None, None, 0)
+            self._hand_to_trainer(ag)
+        self._agents_done()
+
+    def _hand_to_trainer(self, ag) -> None:
+        if not self.host_ordered:
+            gmi_transfer(ag.gmi, self.trainer, None, None, 0)       # ordering only: the trainer's stream waits
+
+    def _agents_done(self) -> None:
+        if self.host_ordered:
+            for ag in self.agents:
+                gmi_sync(ag.gmi)
 
     def train(self, iteration: int, slot: int, *, gamma: float, lam: float, epochs: int, minibatch: int,
               stats=None, **hp) -> None:

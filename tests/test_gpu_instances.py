@@ -41,14 +41,17 @@ class _OracleAgents:
         return buf
 
 
-def _pipeline(cfg, dtype, n_agents, n_envs, horizon, minibatch, theta, a_mat, b_mat, thr, states, masked):
+def _pipeline(cfg, dtype, n_agents, n_envs, horizon, minibatch, theta, a_mat, b_mat, thr, states, masked,
+              host_ordered=False):
     import paper_2206_08482_amd as g
     from paper_2206_08482_amd.instances import InstancePipeline, cu_masks
     probe = g.gmi_create()
     n_cu = g.gmi_cu_count(probe)
     g.gmi_destroy(probe)
     agent_masks = trainer_mask = None
-    if masked:
+    if masked == "agents":      # the agents on disjoint CU sets, the trainer on the whole device
+        agent_masks = cu_masks(n_cu, [(n_cu // n_agents) // 8 * 8] * n_agents, "interleaved")
+    elif masked:
         share = (n_cu // 2 // n_agents) // 8 * 8
         masks = cu_masks(n_cu, [share] * n_agents + [n_cu - share * n_agents], "contiguous")
         agent_masks, trainer_mask = masks[:n_agents], masks[n_agents]
@@ -56,7 +59,7 @@ def _pipeline(cfg, dtype, n_agents, n_envs, horizon, minibatch, theta, a_mat, b_
                             hidden=cfg.hidden, horizon=horizon, dtype=dtype, theta=theta, a_mat=a_mat, b_mat=b_mat,
                             state0=states, noise_std=cfg.noise_std, reward_scale=cfg.reward_scale,
                             done_period=cfg.done_period, done_threshold=thr, seed=cfg.seed, minibatch=minibatch,
-                            agent_masks=agent_masks, trainer_mask=trainer_mask)
+                            agent_masks=agent_masks, trainer_mask=trainer_mask, host_ordered=host_ordered)
 
 
 def _train_args(cfg, minibatch):
@@ -78,12 +81,13 @@ def test_cu_masks_are_disjoint_and_sized():
             assert all(any((x >> b) & 1 for b in range(d, 256, 8)) for d in range(8))
 
 
-@pytest.mark.parametrize("masked", [False, True])
-def test_sync_schedule_matches_oracle_fp32(masked):
+@pytest.mark.parametrize("masked,host_ordered", [(False, False), (True, False), (True, True), ("agents", True)])
+def test_sync_schedule_matches_oracle_fp32(masked, host_ordered):
     cfg = syn.get_config("C1")
     n_agents, n_envs, horizon, minibatch = 3, 32, 8, 192
     shape, theta, a_mat, b_mat, thr, envs, states, hp = _setup(cfg, n_agents, n_envs, horizon, minibatch)
-    pipe = _pipeline(cfg, "f32", n_agents, n_envs, horizon, minibatch, theta, a_mat, b_mat, thr, states, masked)
+    pipe = _pipeline(cfg, "f32", n_agents, n_envs, horizon, minibatch, theta, a_mat, b_mat, thr, states, masked,
+                     host_ordered)
     if masked:
         a_cus, t_cus = pipe.cu_counts()
         assert len(set(a_cus)) == 1 and sum(a_cus) + t_cus > 0
@@ -103,11 +107,13 @@ def test_sync_schedule_matches_oracle_fp32(masked):
     pipe.close()
 
 
-def test_pipelined_schedule_matches_oracle_fp32():
+@pytest.mark.parametrize("host_ordered", [False, True])
+def test_pipelined_schedule_matches_oracle_fp32(host_ordered):
     cfg = syn.get_config("C1")
     n_agents, n_envs, horizon, minibatch = 2, 64, 8, 256
     shape, theta, a_mat, b_mat, thr, envs, states, hp = _setup(cfg, n_agents, n_envs, horizon, minibatch)
-    pipe = _pipeline(cfg, "f32", n_agents, n_envs, horizon, minibatch, theta, a_mat, b_mat, thr, states, True)
+    pipe = _pipeline(cfg, "f32", n_agents, n_envs, horizon, minibatch, theta, a_mat, b_mat, thr, states, True,
+                     host_ordered)
     ora = _OracleAgents(shape, envs, states, n_envs, horizon, cfg)
     # oracle replay of the lag-1 schedule: D_0 and D_1 are both collected with theta_0
     th = [theta]
