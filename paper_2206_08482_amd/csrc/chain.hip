@@ -140,6 +140,26 @@ int launch_chain_pack(gmi_instance* g, gmi_model* m) {
   return GMI_OK;
 }
 
+void fill_chain_emit(const ModelLayout& L, ChainEmit* ce) {
+  ce->gmax = 0;
+  ce->n_layers = L.n_layers;
+  if (L.sh_chain_bytes == 0) return;
+  const int gmax = compiled_gmax(L);
+  if (gmax == 0) return;
+  const ChainDims D = dims_of(L, gmax);
+  ce->gmax = gmax;
+  for (int net = 0; net < 2; ++net) {
+    ce->out[net] = L.sh_chain[net];
+    for (int l = 0; l < L.n_layers; ++l) ce->l[net * L.n_layers + l] = ChainEmitLayer{0, -1, l == 0 ? 1 : 0};
+    int blk = 0;
+    for (int s = 0; s < cd_nseg(D); ++s) {
+      ChainEmitLayer& e = ce->l[net * L.n_layers + cd_layer(D, s)];
+      if (s < D.nl) e.fwd_blk = blk; else e.bwd_blk = blk;
+      blk += cd_seg_blocks(D, s);
+    }
+  }
+}
+
 // Gather of the minibatch rows idx[0..rows) of buffer b + forward + loss + input gradients.
 // Leaves m->h, m->dz ready for the weight-gradient launch and one row of statistics / log_std partials per
 // tile in m->stat_part (*n_stat_rows rows, the layout of the loss kernel's per-workgroup rows).  GMI_ERR_UNSUPPORTED (no message) if no kernel is compiled for this shape.

@@ -103,9 +103,11 @@ struct ChunkInfo {
   int gord;              // ordinal of the group among all groups of the plan
   int prev_last;         // index of the last chunk of the previous group (-1 for the first group)
   int seg_nks;           // k steps of the segment
+  int group_chunks;      // chunks of this chunk's group
+  int last_in;           // 0 for the group's last chunk, 1 for the one before, ...
 };
 __host__ __device__ constexpr ChunkInfo cd_chunk(const ChainDims& D, int c) {
-  ChunkInfo ci = {0, 0, 0, 0, 0, 0, 0, 0, false, false, 0, -1, 0};
+  ChunkInfo ci = {0, 0, 0, 0, 0, 0, 0, 0, false, false, 0, -1, 0, 0, 0};
   int blk = 0, cc = 0, gord = 0;
   for (int s = 0; s < cd_nseg(D); ++s) {
     const int nft = cd_F(D, s) / 32, nks = cd_K(D, s) / 16;
@@ -117,7 +119,7 @@ __host__ __device__ constexpr ChunkInfo cd_chunk(const ChainDims& D, int c) {
         if (cc == c) {
           ci.seg = s; ci.gi = gi; ci.gs = gs; ci.tile0 = cd_gtile0(nft, gi, D.gmax); ci.ks0 = k0; ci.nks = n;
           ci.blk_off = blk; ci.nblk = n * gs; ci.first = kc == 0; ci.last = kc == nc - 1;
-          ci.gord = gord; ci.prev_last = group_first - 1; ci.seg_nks = nks;
+          ci.gord = gord; ci.prev_last = group_first - 1; ci.seg_nks = nks; ci.group_chunks = nc; ci.last_in = nc - 1 - kc;
           return ci;
         }
         blk += n * gs;
@@ -184,12 +186,13 @@ constexpr int kScrStride = 272;                    // bytes per row of a wave's 
 constexpr int kScrBytes = 32 * kScrStride;
 
 // A compile-time description of one model shape: NW waves per workgroup, DEPTH chunks of weights in flight,
-// GMAX tiles in the largest group, DEFER = 1 if epilogues run inside the next group's products, then the padded
-// widths d[0..nl].
-template <int NW_, int DEPTH_, int GMAX_, int DEFER_, int... DIMS>
+// GMAX tiles in the largest group, DEFER = 1 if epilogues run inside the next group's products, HFETCH (see below),
+// then the padded widths d[0..nl].
+template <int NW_, int DEPTH_, int GMAX_, int DEFER_, int HFETCH_, int... DIMS>
 struct ChainShape {
   static constexpr int NW = NW_, NT = NW_ * 64, DEPTH = DEPTH_, GMAX = GMAX_;
   static constexpr bool DEFER = DEFER_ != 0;
+  static constexpr int HFETCH = HFETCH_;      // without DEFER: a group fetches its stored activations this many chunks before its end
   static_assert(GMAX_ == 4 || GMAX_ == 2, "groups of at most 4 or 2 tiles");
   static constexpr int NL = (int)sizeof...(DIMS) - 1;
   static constexpr int LPT = (16 * 64 + NT - 1) / NT;      // 16-byte pieces of a chunk per thread
@@ -611,7 +614,8 @@ __device__ __forceinline__ void chain_step(Ctx<S>& c, const ChainArgs& a) {
   issue_chunk<S, C + 1 + S::DEPTH>(c);
   if constexpr (seg == NL - 2 && ci.gi == 0 && ci.first) fetch_loss_inputs<S>(c, a);
 
-  if constexpr (!S::DEFER && bwd && ci.last)        // stored activations of this group's features, for ELU'
+  // stored activations of this group's features, for ELU': fetched HFETCH chunks before the group's end
+  if constexpr (!S::DEFER && bwd && (ci.last_in == (S::HFETCH < ci.group_chunks ? S::HFETCH : ci.group_chunks) - 1))
     global_to_regs<GS>(c.ht, c.lane, a.h[c.net][layer], D.d[layer], 32 * ci.tile0, c.row0, a.rows);
 
   if constexpr (ci.first) {

@@ -270,6 +270,19 @@ int launch_permutation(gmi_instance* g, int n, uint64_t seed, uint32_t iteration
 // Register-chained trainer kernel (chain.hip): its weight stream in the shadow and the launch.
 int64_t chain_stream_bytes(const ModelLayout& L);
 int launch_chain_pack(gmi_instance* g, gmi_model* m);
+// Where shadow_transpose_kernel puts the blocks of the chain streams (the layout launch_chain_pack writes): per
+// entry of the shadow table (net-major) the first block of the layer's forward and input-gradient segments.
+struct ChainEmitLayer {
+  int fwd_blk, bwd_blk;      // bwd_blk < 0: the first layer has no input-gradient segment
+  int natural;               // 1: k indices of a lane in natural order (first forward layer)
+};
+struct ChainEmit {
+  int gmax;                  // tiles in the largest group; 0: the model has no chain stream
+  int n_layers;
+  int64_t out[2];            // byte offsets of the two nets' streams in the shadow
+  ChainEmitLayer l[kMaxWgradProblems];
+};
+void fill_chain_emit(const ModelLayout& L, ChainEmit* ce);
 int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx, int rows,
                        int* n_stat_rows);
 

@@ -231,7 +231,28 @@ struct TransposeTiles {
   int n;
   int start[gmi::kMaxWgradProblems + 1];
 };
-__global__ __launch_bounds__(256) void shadow_transpose_kernel(gmi::ShadowTable tab, TransposeTiles tt,
+// Index of block (feature tile ft, k step ks) inside a chain-stream segment of nft tiles and nks k steps whose
+// tiles are grouped gm, .., gm, (2), (1): groups one after the other, a group's blocks k step major.
+__device__ __forceinline__ int chain_block_index(int nft, int nks, int gm, int ft, int ks) {
+  const int full = nft / gm;
+  int base, gs, t;
+  if (ft < gm * full) {
+    const int gi = ft / gm;
+    base = gi * gm * nks; gs = gm; t = ft - gi * gm;
+  } else {
+    base = full * gm * nks;
+    const int r = ft - gm * full;
+    if ((nft % gm) >= 2) {
+      if (r < 2) { gs = 2; t = r; }
+      else { base += 2 * nks; gs = 1; t = 0; }
+    } else {
+      gs = 1; t = 0;
+    }
+  }
+  return base + ks * gs + t;
+}
+
+__global__ __launch_bounds__(256) void shadow_transpose_kernel(gmi::ShadowTable tab, TransposeTiles tt, gmi::ChainEmit ce,
                                                                char* __restrict__ shadow) {
   __shared__ __attribute__((aligned(16))) uint16_t s_t[64][72];
   int li = 0;
@@ -273,6 +294,44 @@ __global__ __launch_bounds__(256) void shadow_transpose_kernel(gmi::ShadowTable 
     if (o0 + ol < L.out_pad && i0 + il < L.in_pad)
       *reinterpret_cast<uint4*>(wf + gmi::wfrag_index(o0 + ol, i0 + il, L.in_pad)) =
           *reinterpret_cast<const uint4*>(&s_t[ol][il]);
+  }
+  // the same 8 + 8 blocks in the order and with the k permutation of the chained trainer kernel's streams:
+  // lane (s, h) of a block holds, for its row, the k indices 16 ks + 8 (j / 4) + 4 h + j % 4, j = 0..7 (natural
+  // order 8 h + j in the first forward layer)
+  if (ce.gmax == 0) return;
+  uint4* __restrict__ cs = reinterpret_cast<uint4*>(shadow + ce.out[li / ce.n_layers]);
+  const gmi::ChainEmitLayer& E = ce.l[li];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int idx = tid + 256 * k, blk = idx >> 6, lane = idx & 63, h = lane >> 5;
+    {   // forward segment: rows = output features, k = input features
+      const int ol = (blk >> 2) * 32 + (lane & 31), il = (blk & 3) * 16;
+      if (o0 + ol < L.out_pad && i0 + il < L.in_pad) {
+        uint4 v;
+        if (E.natural) {
+          v = *reinterpret_cast<const uint4*>(&s_t[ol][il + 8 * h]);
+        } else {
+          const uint2 a = *reinterpret_cast<const uint2*>(&s_t[ol][il + 4 * h]);
+          const uint2 b = *reinterpret_cast<const uint2*>(&s_t[ol][il + 8 + 4 * h]);
+          v = make_uint4(a.x, a.y, b.x, b.y);
+        }
+        const int dst = E.fwd_blk + chain_block_index(L.out_pad >> 5, L.in_pad >> 4, ce.gmax, (o0 + ol) >> 5, (i0 + il) >> 4);
+        cs[(int64_t)dst * 64 + lane] = v;
+      }
+    }
+    if (E.bwd_blk >= 0) {   // input-gradient segment: rows = input features, k = output features
+      const int il = (blk >> 2) * 32 + (lane & 31), ol = (blk & 3) * 16;
+      if (i0 + il < L.in_pad && o0 + ol < L.out_pad) {
+        uint16_t e[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = s_t[ol + 8 * (j >> 2) + 4 * h + (j & 3)][il];
+        uint4 v;
+        v.x = e[0] | ((uint32_t)e[1] << 16); v.y = e[2] | ((uint32_t)e[3] << 16);
+        v.z = e[4] | ((uint32_t)e[5] << 16); v.w = e[6] | ((uint32_t)e[7] << 16);
+        const int dst = E.bwd_blk + chain_block_index(L.in_pad >> 5, L.out_pad >> 4, ce.gmax, (i0 + il) >> 5, (o0 + ol) >> 4);
+        cs[(int64_t)dst * 64 + lane] = v;
+      }
+    }
   }
 }
 
@@ -432,9 +491,11 @@ int launch_adam(gmi_instance* g, gmi_model* const* ms, int n, int n_split, int n
     }
     tt.start[tab.n] = total;
     gmi::ProfScope ps2(g, gmi::kClsShadowTranspose);
-    ps2.launch(shadow_transpose_kernel, dim3(total), dim3(256), 0, tab, tt, m->shadow);
+    gmi::ChainEmit ce;
+    gmi::fill_chain_emit(m->L, &ce);
+    ps2.launch(shadow_transpose_kernel, dim3(total), dim3(256), 0, tab, tt, ce, m->shadow);
     GMI_LAUNCH_CHECK();
-    return gmi::launch_chain_pack(g, m);
+    return GMI_OK;
   }
   return GMI_OK;
 }
