@@ -1,6 +1,6 @@
-// Register-chained trainer kernel: forward pass, clipped-surrogate / value loss and the whole input-gradient
-// chain of one minibatch (stage (ii) of Section 5.1 of the paper, the "DRL Trainer" role of Section 3) in one
-// launch per minibatch.
+// Register-chained trainer kernel: minibatch gather, forward pass, clipped-surrogate / value loss and the whole
+// input-gradient chain of one minibatch (stage (ii) of Section 5.1 of the paper, the "DRL Trainer" role of
+// Section 3) in one launch per minibatch.
 //
 // A wave owns 32 samples and carries their activations from layer to layer IN REGISTERS.  Every product is
 // computed transposed, H^T = W X^T: the weights are the first operand of the 32x32x16 matrix instruction
@@ -11,11 +11,17 @@
 // shadow copy (the "chain stream") whose 1 KiB blocks are already permuted and already in the order the kernel
 // consumes them.  No activation ever goes through LDS on its way to the next layer.
 //
-// The 4 or 8 waves of a workgroup walk the stream in lockstep; the stream is staged through a
-// double-buffered LDS slot (16 KiB chunks, global loads issued several chunks ahead into registers), so a
-// workgroup reads every weight once for its 128 or 256 samples.  Activations and gradients that the
-// weight-gradient kernel needs are written row-major through a small per-wave LDS transposition buffer, so
-// that rows leave the chip as 64..256-byte pieces.
+// The 4 or 8 waves of a workgroup walk the stream in lockstep; the stream is staged through three LDS slots
+// (16 KiB chunks, global loads issued several chunks ahead into registers), so a workgroup reads every weight
+// once for its 128 or 256 samples.  Activations and gradients that the weight-gradient kernel needs are written
+// row-major through a small per-wave LDS transposition buffer, so that rows leave the chip as 64..256-byte
+// pieces.  The epilogue of a group of feature tiles (bias + ELU or ELU', conversion, that store) is a list of
+// small items; shapes with room for a second accumulator set run the items of one group between the matrix
+// instructions of the next (DEFER).
+//
+// Layout of this file: the plan (cd_*: pure functions of the layer widths, shared by kernel and host), the
+// kernel's arguments and per-lane context, chunk movement, epilogue items, the k-step loop, the kernel, and the
+// launch helpers that chain_p<k>.hip instantiate for one shape each.
 
 #pragma once
 #include "internal.h"
