@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Experience channels against the direct hand-off, configuration C5 (4 agent instances x 4096 envs + 1 trainer
-instance on one MI355X, unmasked streams, lag-1 pipelined schedule = the one-GPU form of the paper's asynchronous
-serving / training): every agent pushes its round as a slab, the trainer's batcher stacks the four slabs into its
+instance on one MI355X, unmasked streams unless a row says otherwise, lag-1 pipelined schedule = the one-GPU form
+of the paper's asynchronous serving / training; two rows let the agents run further ahead): every agent pushes its round as a slab, the trainer's batcher stacks the four slabs into its
 batch.  Rows: direct column-slice hand-off (no bytes moved), multi-channel slabs (one array per type), uni-channel
 slabs (interleaved records).  Reports the paper's two throughput metrics of this setting: PPS (predictions per
 second: env steps the agents serve) and TTOP (training throughput: samples per second the trainer consumes); in
@@ -49,7 +49,7 @@ def main() -> int:
                   done_threshold=thr, seed=cfg.seed, minibatch=cfg.minibatch)
     slab_bytes = cfg.horizon * cfg.n_envs * (4 * (cfg.obs_dim + cfg.act_dim + 3) + 1) + 4 * cfg.n_envs
 
-    def run(label, make):
+    def run(label, make, lag=0):
         pipe = make()
         s0 = [torch.tensor(s, device="cuda:0") for s in states]
         torch.cuda.synchronize()
@@ -59,13 +59,18 @@ def main() -> int:
                 g.gmi_transfer(ag.gmi, ag.gmi, s, ag.obs[ag.cur], s.numel() * 4)
 
         k = 0
-        pipe.prologue_pipelined()
+        if lag:
+            pipe.prologue_lagged(lag)
+            step = lambda kk: pipe.iteration_lagged(kk, lag, **train_args)
+        else:
+            pipe.prologue_pipelined()
+            step = lambda kk: pipe.iteration_pipelined(kk, **train_args)
         for _ in range(args.warmup):
-            reset(); pipe.iteration_pipelined(k, **train_args); k += 1
+            reset(); step(k); k += 1
         pipe.sync_all()
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            reset(); pipe.iteration_pipelined(k, **train_args); k += 1
+            reset(); step(k); k += 1
         pipe.sync_all()
         dt = (time.perf_counter() - t0) / args.steps
         ok = bool(torch.isfinite(pipe.theta).all().item())
@@ -77,6 +82,19 @@ def main() -> int:
     rows = [run("direct (agents write column slices of the trainer's batch)", lambda: InstancePipeline(**common)),
             run("multi-channel slabs (one array per type)", lambda: ChannelPipeline(mode=g.CHANNELS_MULTI, **common)),
             run("uni-channel slabs (interleaved records)", lambda: ChannelPipeline(mode=g.CHANNELS_UNI, **common))]
+    # bounded staleness: the agents `lag` rounds ahead of the trainer (the channels hold lag rounds)
+    for lag in (2, 4):
+        rows.append(run(f"multi-channel slabs, agents {lag} rounds ahead",
+                        lambda: ChannelPipeline(mode=g.CHANNELS_MULTI, capacity=(lag + 1) * n_ag, **common), lag))
+    # the layout that wins in bench_instances.py (agents on disjoint quarters of the device, trainer unmasked, the
+    # host orders the hand-offs), through channels
+    probe = g.gmi_create()
+    n_cu = g.gmi_cu_count(probe)
+    g.gmi_destroy(probe)
+    from paper_2206_08482_amd.instances import cu_masks
+    masks = cu_masks(n_cu, [n_cu // n_ag // 8 * 8] * n_ag, "contiguous")
+    rows.append(run("multi-channel slabs, agents on disjoint CU sets, host-ordered",
+                    lambda: ChannelPipeline(mode=g.CHANNELS_MULTI, agent_masks=masks, host_ordered=True, **common)))
     for r in rows:
         r["vs_direct"] = r["ttop_samples_per_s"] / rows[0]["ttop_samples_per_s"]
     print(json.dumps({"workload": f"C5: {n_ag} agent instances x {cfg.n_envs} envs, obs {cfg.obs_dim}, MLP {list(cfg.hidden)}, "

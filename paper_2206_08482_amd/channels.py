@@ -1,9 +1,11 @@
 """Agent instances feeding a trainer instance through experience channels (Section 4.2 of the paper) instead of
 writing straight into the trainer's batch: every agent instance collects into a buffer of its own and pushes it
 as a slab; the trainer pops the slabs of a round, stacked side by side, into its batch.  Same two schedules as
-`instances.InstancePipeline` (whose direct hand-off moves no bytes and is the comparison point); the lag-1
-pipelined one is the one-GPU form of the paper's asynchronous serving / training.  No arithmetic of the method
-happens here."""
+`instances.InstancePipeline` (whose direct hand-off moves no bytes and is the comparison point), plus the
+bounded-staleness schedule that the queue makes possible: the agents run `lag` rounds ahead of the trainer, round
+k + lag being collected with the parameters after k updates while the trainer works on round k.  This is the
+one-GPU, replayable form of the paper's asynchronous serving / training (Section 5.2: agents and trainers
+decoupled by the channels); lag = 1 is the pipelined schedule.  No arithmetic of the method happens here."""
 from __future__ import annotations
 
 from typing import Optional, Sequence
@@ -24,6 +26,7 @@ class ChannelPipeline(InstancePipeline):
             raise ValueError("ChannelPipeline collects with rollout_collect (bf16 models)")
         dev = torch.device("cuda:0")
         cap = 2 * self.n_agents if capacity is None else capacity
+        self.capacity = cap
         self.channels = gmi_channels_create(self.T, self.N, self.O, self.A, cap, mode)
         self.own = []                         # every agent's own experience buffer and bootstrap values
         for ag in self.agents:
@@ -51,6 +54,22 @@ class ChannelPipeline(InstancePipeline):
                         adam_step0=self.adam_steps, **hp)
         ppo_update(self.trainer, self.t_model, self.t_buffer[slot], h, stats)
         self.adam_steps += epochs * (self.T * self.Ntot // minibatch)
+
+    # ------------------------------------------------------------------ bounded staleness
+    def prologue_lagged(self, lag: int) -> None:
+        """Rounds 0 .. lag-1, all collected with theta_0, queued in the channels."""
+        if lag < 1 or (lag + 1) * self.n_agents > self.capacity:
+            raise ValueError(f"lag {lag} needs channels of capacity >= {(max(lag, 1) + 1) * self.n_agents} slabs "
+                             f"(have {self.capacity})")
+        for r in range(lag):
+            self.collect(r, 0)
+
+    def iteration_lagged(self, k: int, lag: int, **train_args) -> None:
+        """Trainer: theta_{k+1} from round k, the oldest in the channels.  Agents, concurrently: round k + lag with
+        the published theta_k.  Then theta_{k+1} is published (after the agents' hand-off)."""
+        self.train(k, k % 2, **train_args)
+        self.collect(k + lag, 0)
+        self.publish()
 
     def close(self) -> None:
         self.sync_all()

@@ -173,3 +173,105 @@ def test_channel_pipeline_equals_the_direct_hand_off_bit_for_bit(g):
         assert np.array_equal(th, results[0][0])
         for k in och.TYPES + ("adv", "ret"):
             assert np.array_equal(buf[k], results[0][1][k]), k
+
+
+def _lag_common(cfg, n_ag, n, T, mb, lr=3e-4):
+    theta = syn.make_model_params(cfg.obs_dim, cfg.act_dim, cfg.hidden, cfg.seed)
+    a_mat, b_mat = syn.make_env_matrices(cfg.obs_dim, cfg.act_dim, cfg.seed)
+    states = [syn.make_initial_state(n, cfg.obs_dim, 70 + i) for i in range(n_ag)]
+    common = dict(n_agents=n_ag, n_envs=n, obs_dim=cfg.obs_dim, act_dim=cfg.act_dim, hidden=cfg.hidden, horizon=T,
+                  dtype="bf16", theta=theta, a_mat=a_mat, b_mat=b_mat, state0=states, noise_std=cfg.noise_std,
+                  reward_scale=1.0, done_period=0, done_threshold=(1 << 32) // 50, seed=5, minibatch=mb)
+    targs = dict(gamma=0.99, lam=0.95, epochs=2, minibatch=mb, clip=0.2, c_v=0.5, c_e=0.0, lr=lr)
+    return theta, a_mat, b_mat, states, common, targs
+
+
+@pytest.mark.parametrize("host_ordered", [False, True])
+def test_lagged_schedule_bit_for_bit(g, host_ordered):
+    """lag = 1 is the pipelined schedule; for lag = 3 the concurrent form (agents and trainer overlap) gives the
+    same bits as the same stages run one at a time with the host waiting in between."""
+    from paper_2206_08482_amd.channels import ChannelPipeline
+    cfg = syn.get_config("C2")
+    n_ag, n, T, mb = 2, 64, 4, 128
+    _, _, _, _, common, targs = _lag_common(cfg, n_ag, n, T, mb)
+    out = {}
+    for name in ("pipelined", "lag1", "lag3", "lag3_sequential"):
+        lag = 3 if name.startswith("lag3") else 1
+        pipe = ChannelPipeline(mode=g.CHANNELS_MULTI, capacity=(lag + 1) * n_ag, host_ordered=host_ordered, **common)
+        if name == "pipelined":
+            pipe.prologue_pipelined()
+            for k in range(3):
+                pipe.iteration_pipelined(k, **targs)
+        elif name == "lag3_sequential":
+            pipe.prologue_lagged(lag); pipe.sync_all()
+            for k in range(3):      # the same stages in an order that never overlaps two instances
+                pipe.collect(k + lag, 0); pipe.sync_all()
+                pipe.train(k, k % 2, **targs); pipe.sync_all()
+                pipe.publish(); pipe.sync_all()
+        else:
+            pipe.prologue_lagged(lag)
+            for k in range(3):
+                pipe.iteration_lagged(k, lag, **targs)
+        pipe.sync_all()
+        out[name] = (pipe.theta.cpu().numpy().copy(), pipe.bufs[0].to_numpy())
+        assert g.gmi_channels_count(pipe.channels)[0] == lag * n_ag        # the agents stay `lag` rounds ahead
+        pipe.close()
+    assert np.array_equal(out["lag1"][0], out["pipelined"][0])
+    assert np.array_equal(out["lag3"][0], out["lag3_sequential"][0])
+    for key in och.TYPES + ("adv", "ret"):
+        assert np.array_equal(out["lag3"][1][key], out["lag3_sequential"][1][key]), key
+    assert not np.array_equal(out["lag3"][0], out["lag1"][0])           # staleness changes the result
+
+
+def test_lagged_schedule_uses_the_parameters_it_states(g):
+    """Oracle replay with a step size large enough that parameter versions differ visibly: round r is collected
+    with theta_{max(0, r - lag)}; replaying with any other version misses by far more than the bf16 band."""
+    from oracle import ppo as oppo
+    from paper_2206_08482_amd.channels import ChannelPipeline
+    from gpu_util import rel_l2
+    cfg = syn.get_config("C2")
+    n_ag, n, T, mb, lag, lr = 2, 64, 4, 256, 2, 2e-2
+    theta, a_mat, b_mat, states, common, targs = _lag_common(cfg, n_ag, n, T, mb, lr=lr)
+    shape = oppo.ModelShape(cfg.obs_dim, cfg.act_dim, tuple(cfg.hidden))
+    envs = [oppo.EnvSpec(a_mat, b_mat, cfg.noise_std, 1.0, 0, (1 << 32) // 50, 5 + i) for i in range(n_ag)]
+
+    class Replay:
+        def __init__(self):
+            self.states = [s.copy() for s in states]
+            self.eps = [np.zeros(n, np.uint32) for _ in envs]
+
+        def collect(self, th, r, keep=True):
+            buf = oppo.new_buffer(T, n_ag * n, cfg.obs_dim, cfg.act_dim)
+            last = np.zeros(n_ag * n, np.float32)
+            st, ep = [], []
+            for i, env in enumerate(envs):
+                s2, e2, lv = oppo.rollout(th, shape, env, self.states[i], self.eps[i], buf, env.seed, r, col0=i * n)
+                st.append(s2); ep.append(e2)
+                last[i * n:(i + 1) * n] = lv
+            if keep:
+                self.states, self.eps = st, ep
+            buf["adv"], buf["ret"] = oppo.gae(buf["rew"], buf["val"], buf["done"], last, 0.99, 0.95, True)
+            return buf
+
+    pipe = ChannelPipeline(mode=g.CHANNELS_MULTI, capacity=(lag + 1) * n_ag, **common)
+    rep = Replay()
+    th = [theta]            # the trainer's own parameter versions (Adam at this step size amplifies bf16 noise in
+                            # near-zero gradients, so the update itself is compared elsewhere, at the usual step size)
+    rounds = [rep.collect(theta, r) for r in range(lag)]
+    pipe.prologue_lagged(lag)
+    for k in range(3):
+        pipe.iteration_lagged(k, lag, **targs)
+        pipe.sync_all()
+        th.append(pipe.theta.cpu().numpy().copy())
+        newer = rep.collect(th[k + 1], k + lag, keep=False)       # what agents that had not lagged would have collected
+        rounds.append(rep.collect(th[k], k + lag))
+        # the trainer's batch of iteration k is round k; what the agents just pushed is round k + lag (their own
+        # buffers still hold it)
+        got = pipe.bufs[k % 2].to_numpy()
+        for name in ("obs", "act", "rew"):
+            assert rel_l2(got[name], rounds[k][name]) <= 2e-2, (k, name)
+        own_act = np.concatenate([rb.to_numpy()["act"] for rb, _, _ in pipe.own], axis=1)
+        err = rel_l2(own_act, rounds[k + lag]["act"])
+        assert err <= 2e-2, (k, err)
+        assert rel_l2(own_act, newer["act"]) > 5 * err, k
+    pipe.close()
