@@ -10,8 +10,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libgmidrl.so")
-SOURCES = ["core.hip", "env.hip", "experience.hip", "mlp.hip", "model.hip", "update.hip", "peaks.hip", "fused.hip", "select.hip", "channels.hip", "chain.hip",
-           "chain_p0.hip", "chain_p1.hip", "chain_p2.hip", "chain_p3.hip", "chain_p4.hip", "chain_p5.hip"]
+# the slowest compiles first (the chained trainer kernel of the widest shapes takes minutes), so that they overlap
+# all the others
+SOURCES = ["chain_p5.hip", "chain_p2.hip", "fused.hip", "mlp.hip", "chain_p1.hip", "chain_p4.hip", "chain_p0.hip", "chain_p3.hip",
+           "core.hip", "env.hip", "experience.hip", "model.hip", "update.hip", "peaks.hip", "select.hip", "channels.hip", "chain.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Wno-unused-value", "-Wno-unused-result", "-fhip-fp32-correctly-rounded-divide-sqrt",
          # keep fp32 arithmetic scalar: packed fp32 forms are not trusted on the test machines
@@ -34,6 +36,7 @@ def _compile(src: str) -> str:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
     if err.strip():
         sys.stderr.write(err + "\n")
+    print(f"compiled {src}", flush=True)
     return obj
 
 
