@@ -75,6 +75,7 @@ ChainDims dims_of(const ModelLayout& L, int gmax = 4) {
 typedef int (*part_fn)(gmi_instance*, const ModelLayout&, const ChainArgs&, int, int*, double, double);
 const part_fn kParts[gmi::kChainParts] = {gmi::launch_chain_part0, gmi::launch_chain_part1, gmi::launch_chain_part2,
                                           gmi::launch_chain_part3, gmi::launch_chain_part4, gmi::launch_chain_part5};
+const part_fn kFwdParts[gmi::kChainFwdParts] = {gmi::launch_chain_fwd_part0, gmi::launch_chain_fwd_part1};
 
 // The largest group of the kernel compiled for this model's shape; 0 if there is none.
 int compiled_gmax(const ModelLayout& L) {
@@ -220,6 +221,48 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_p
   if (rc != GMI_OK) return rc;
   *n_stat_rows = tiles;
   return GMI_OK;
+}
+
+// Inference through the forward-only chained kernel (agent_act / agent_value of the models too large for the fused
+// agent kernel): the same stream, the same products in the same order as the trainer's forward pass.
+int launch_forward_chain(gmi_instance* g, gmi_model* m, const float* obs, int n_rows, float* mu, float* val) {
+  const ModelLayout& L = m->L;
+  if (L.dtype != GMI_DTYPE_BF16 || L.sh_chain_bytes == 0 || L.act_dim > 32) return GMI_ERR_UNSUPPORTED;
+  if (n_rows < 1 || n_rows > m->max_rows) return GMI_ERR_UNSUPPORTED;
+  ChainArgs a = {};
+  int gm_fwd = 0, rc = GMI_ERR_UNSUPPORTED;
+  for (int p = 0; p < kChainFwdParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = kFwdParts[p](nullptr, L, a, 0, &gm_fwd, 0.0, 0.0);
+  if (rc != GMI_OK) return rc;
+  if (gm_fwd != compiled_gmax(L)) return GMI_ERR_UNSUPPORTED;      // the stream is laid out for the trainer kernel's groups
+  for (int net = 0; net < 2; ++net) {
+    a.wstream[net] = m->shadow + L.sh_chain[net];
+    for (int l = 0; l < L.n_layers; ++l) a.bias[net][l] = reinterpret_cast<const float*>(m->shadow + L.net[net][l].sh_b);
+  }
+  a.x0 = (uint16_t*)m->x0;
+  a.log_std = reinterpret_cast<const float*>(m->shadow + L.sh_logstd);
+  a.idx = nullptr;
+  a.b_obs = obs;
+  a.n_envs = n_rows; a.ld_envs = n_rows; a.obs_dim = L.obs_dim;
+  a.x0_ready = (L.obs_dim % 4 == 0 && ((uintptr_t)obs & 15) == 0) ? 0 : 1;
+  a.rows = n_rows; a.act_dim = L.act_dim;
+  a.net0 = mu ? 0 : 1;
+  a.mu_out = mu; a.val_out = val;
+  if (a.x0_ready) {
+    rc = launch_gather(g, m, obs, n_rows, n_rows, nullptr, n_rows, nullptr);
+    if (rc != GMI_OK) return rc;
+  }
+  double flops = 0.0, bytes = 0.0;
+  for (int net = a.net0; net < 2; ++net)
+    for (int l = 0; l < L.n_layers; ++l) {
+      const LayerInfo& li = L.net[net][l];
+      flops += 2.0 * n_rows * (double)li.in * li.out;
+      bytes += 2.0 * li.in * li.out;
+    }
+  bytes += (a.x0_ready ? 2.0 : 4.0) * n_rows * L.obs_dim * (2 - a.net0) + 4.0 * n_rows * ((mu ? L.act_dim : 0) + 1);
+  int tiles = 0;
+  rc = GMI_ERR_UNSUPPORTED;
+  for (int p = 0; p < kChainFwdParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = kFwdParts[p](g, L, a, n_rows, &tiles, flops, bytes);
+  return rc;
 }
 
 }  // namespace gmi

@@ -1,7 +1,7 @@
-// Register-chained trainer kernel compiled for one model shape (waves per workgroup, weight chunks in flight, largest group, deferred epilogues, chunks between the fetch of stored activations and their use,
+// Register-chained trainer kernel compiled for one model shape (waves per workgroup, weight chunks in flight, largest group, deferred epilogues, chunks between the fetch of stored activations and their use, forward-only,
 // padded layer widths): benchmark workloads C3 / C5 (108:400:200:100:21).
 #include "chain_kernel.h"
 
 namespace gmi {
-GMI_CHAIN_PART_DEFINE(1, 4, 3, 4, 1, 1, 128, 416, 224, 128, 32)
+GMI_CHAIN_PART_DEFINE(1, 4, 3, 4, 1, 1, 0, 128, 416, 224, 128, 32)
 }  // namespace gmi

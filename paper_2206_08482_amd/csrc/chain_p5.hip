@@ -1,7 +1,7 @@
-// Register-chained trainer kernel compiled for one model shape (waves per workgroup, weight chunks in flight, largest group, deferred epilogues, chunks between the fetch of stored activations and their use,
+// Register-chained trainer kernel compiled for one model shape (waves per workgroup, weight chunks in flight, largest group, deferred epilogues, chunks between the fetch of stored activations and their use, forward-only,
 // padded layer widths): the paper's Table 6 model 211:512:512:512:256:20.
 #include "chain_kernel.h"
 
 namespace gmi {
-GMI_CHAIN_PART_DEFINE(5, 4, 3, 4, 0, 1, 224, 512, 512, 512, 256, 32)
+GMI_CHAIN_PART_DEFINE(5, 4, 3, 4, 0, 1, 0, 224, 512, 512, 512, 256, 32)
 }  // namespace gmi

@@ -61,7 +61,9 @@ namespace gmi {
 //           2 linear_bf16_kernel<2,2,2,2,*> (128x128)         3 linear_bf16_kernel<1,4,2,2,*> (256x64)
 //           4 linear_bf16_kernel<1,4,1,2,*> (128x64)
 //   role    0 forward hidden layer (bias + ELU)   1 forward head   2 input gradient (ELU')
-// (kClsGae covers gae_kernel and normalize_kernel, kClsLinearF32 the three fp32 epilogues.)
+// (kClsGae covers gae_kernel and normalize_kernel, kClsLinearF32 the three fp32 epilogues, kClsFusedAgent the
+// one-launch agent forward of a model: agent_fused_kernel, or the forward-only chained kernel for the shapes that
+// have one -- a model uses one or the other.)
 enum KernelClass {
   kClsGather = 0, kClsWgrad, kClsLoss, kClsAdam, kClsShadowTranspose, kClsEnvStep, kClsSample,
   kClsCollect, kClsGae, kClsPermutation, kClsFusedAgent, kClsFusedTrain, kClsFusedRollout, kClsReduce,
@@ -283,6 +285,9 @@ struct ChainEmit {
   ChainEmitLayer l[kMaxWgradProblems];
 };
 void fill_chain_emit(const ModelLayout& L, ChainEmit* ce);
+// Forward pass of n_rows observation rows through the forward-only chained kernel: policy means into mu (NULL: value
+// net only) and values into val.  GMI_ERR_UNSUPPORTED (no message) if no such kernel is compiled for the shape.
+int launch_forward_chain(gmi_instance* g, gmi_model* m, const float* obs, int n_rows, float* mu, float* val);
 int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx, int rows,
                        int* n_stat_rows);
 

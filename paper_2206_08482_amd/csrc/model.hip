@@ -371,9 +371,12 @@ extern "C" int agent_act(gmi_t g, gmi_model_t m, const float* obs, int32_t n_row
     rc = gmi::launch_agent_fused(g, m, obs, n_rows, seed, step, env_offset, act, logp, value, mu, true);
     if (rc != GMI_ERR_UNSUPPORTED) return rc;
   }
-  rc = gmi::launch_gather(g, m, obs, n_rows, n_rows, nullptr, n_rows, nullptr);
-  if (rc != GMI_OK) return rc;
-  rc = gmi::forward_nets(g, m, n_rows, true, true, m->mu, value);
+  rc = g->fusion ? gmi::launch_forward_chain(g, m, obs, n_rows, m->mu, value) : GMI_ERR_UNSUPPORTED;
+  if (rc == GMI_ERR_UNSUPPORTED) {
+    rc = gmi::launch_gather(g, m, obs, n_rows, n_rows, nullptr, n_rows, nullptr);
+    if (rc != GMI_OK) return rc;
+    rc = gmi::forward_nets(g, m, n_rows, true, true, m->mu, value);
+  }
   if (rc != GMI_OK) return rc;
   const float* log_std = m->L.dtype == GMI_DTYPE_BF16 ? reinterpret_cast<const float*>(m->shadow + m->L.sh_logstd)
                                                       : m->params + m->L.logstd_off;
@@ -395,6 +398,8 @@ extern "C" int agent_value(gmi_t g, gmi_model_t m, const float* obs, int32_t n_r
     rc = gmi::launch_agent_fused(g, m, obs, n_rows, 0, 0, 0, nullptr, nullptr, value, nullptr, false);
     if (rc != GMI_ERR_UNSUPPORTED) return rc;
   }
+  rc = g->fusion ? gmi::launch_forward_chain(g, m, obs, n_rows, nullptr, value) : GMI_ERR_UNSUPPORTED;
+  if (rc != GMI_ERR_UNSUPPORTED) return rc;
   rc = gmi::launch_gather(g, m, obs, n_rows, n_rows, nullptr, n_rows, nullptr);
   if (rc != GMI_OK) return rc;
   rc = gmi::forward_nets(g, m, n_rows, false, true, nullptr, value);

@@ -184,7 +184,7 @@ def _bind_model(g, inst, cfg, theta, rows, dtype=None, with_adam=True):
 
 @pytest.mark.parametrize("name,n,dtype", [("C1", 64, "f32"), ("C1", 1, "f32"), ("C2", 1000, "f32"), ("C2", 4096, "bf16"),
                                           ("C3", 777, "bf16"), ("C4", 600, "bf16"), ("C1", 100, "bf16"),
-                                          ("C3", 4096, "bf16"), ("C4", 5000, "bf16"), ("C2", 33, "bf16")])
+                                          ("C3", 4096, "bf16"), ("C4", 5000, "bf16"), ("C2", 33, "bf16"), ("SH", 700, "bf16")])
 @pytest.mark.parametrize("fused", [True, False])
 def test_agent_act_matches_oracle(g, inst, name, n, dtype, fused):
     g.gmi_set_fusion(inst, 1 if fused else 0)
