@@ -217,19 +217,20 @@ __global__ void noise_fill_kernel(uint32_t k0, uint32_t k1, uint32_t stream, uin
 
 __global__ void permutation_kernel(int n, int bits, uint32_t iteration, uint32_t epoch, uint32_t k0,
                                    uint32_t k1, int32_t* __restrict__ out) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) out[i] = (int32_t)gmi::feistel_perm((uint32_t)i, (uint32_t)n, bits, iteration, epoch, k0, k1);
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;      // blockIdx.y: epoch after the first
+  if (i < n)
+    out[(int64_t)blockIdx.y * n + i] = (int32_t)gmi::feistel_perm((uint32_t)i, (uint32_t)n, bits, iteration, epoch + blockIdx.y, k0, k1);
 }
 
 }  // namespace
 
 namespace gmi {
-int launch_permutation(gmi_instance* g, int n, uint64_t seed, uint32_t iteration, uint32_t epoch, int32_t* out) {
-  if (n <= 0) return GMI_OK;
+int launch_permutation(gmi_instance* g, int n, uint64_t seed, uint32_t iteration, uint32_t epoch, int n_epochs, int32_t* out) {
+  if (n <= 0 || n_epochs <= 0) return GMI_OK;
   ProfScope ps(g, kClsPermutation);
   int bits = 0;
   while ((1ll << bits) < (long long)n) ++bits;
-  ps.launch(permutation_kernel, dim3((n + 255) / 256), dim3(256), 0, n, bits, iteration, epoch, (uint32_t)seed,
+  ps.launch(permutation_kernel, dim3((n + 255) / 256, n_epochs), dim3(256), 0, n, bits, iteration, epoch, (uint32_t)seed,
                                                      (uint32_t)(seed >> 32), out);
   GMI_LAUNCH_CHECK();
   return GMI_OK;
@@ -256,5 +257,5 @@ extern "C" int gmi_permutation(gmi_t g, int32_t n, uint64_t seed, uint32_t itera
   if (n < 0) GMI_FAIL(GMI_ERR_BAD_SHAPE, "gmi_permutation: negative n");
   if (n == 0) return GMI_OK;
   if (!out) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_permutation: out is NULL");
-  return gmi::launch_permutation(g, n, seed, iteration, epoch, out);
+  return gmi::launch_permutation(g, n, seed, iteration, epoch, 1, out);
 }

@@ -135,7 +135,7 @@ extern "C" int gmi_buffer_bind(gmi_t g, const gmi_buffer_desc* d, gmi_buffer_t* 
   if (b->n_part > 0) {
     hipError_t e = hipMalloc(&b->part, sizeof(double) * 2 * (size_t)b->n_part);
     if (e == hipSuccess && d->horizon > 0) {
-      e = hipMalloc(&b->perm, sizeof(int32_t) * (size_t)d->horizon * d->n_envs);
+      e = hipMalloc(&b->perm, sizeof(int32_t) * (size_t)gmi::kPermEpochs * d->horizon * d->n_envs);
       if (e != hipSuccess) (void)hipFree(b->part);
     }
     if (e != hipSuccess) {

@@ -187,7 +187,7 @@ struct gmi_buffer {
   gmi_buffer_desc d;
   double* part;     // dev [n_part, 2] partial sums for normalisation
   int n_part;
-  int32_t* perm;    // dev [horizon * n_envs] minibatch shuffle of the current epoch
+  int32_t* perm;    // dev [kPermEpochs][horizon * n_envs] minibatch shuffles of up to kPermEpochs epochs at once
 };
 
 static inline bool valid(gmi_t g) { return g && g->magic == gmi::kMagicInstance; }
@@ -267,7 +267,9 @@ int launch_agent_fused(gmi_instance* g, gmi_model* m, const float* obs, int n, u
 int launch_train_fused(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx,
                        int rows);
 
-int launch_permutation(gmi_instance* g, int n, uint64_t seed, uint32_t iteration, uint32_t epoch, int32_t* out);
+// Shuffles of epochs epoch0 .. epoch0 + n_epochs - 1 into out[e][n], one launch.
+constexpr int kPermEpochs = 8;
+int launch_permutation(gmi_instance* g, int n, uint64_t seed, uint32_t iteration, uint32_t epoch0, int n_epochs, int32_t* out);
 
 // Register-chained trainer kernel (chain.hip): its weight stream in the shadow and the launch.
 int64_t chain_stream_bytes(const ModelLayout& L);

@@ -521,11 +521,16 @@ extern "C" int ppo_update(gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_ppo_
   const int nmb = (int)(B / hp->minibatch);
   uint32_t k = hp->adam_step0;
   for (int e = 0; e < hp->epochs; ++e) {
-    rc = gmi::launch_permutation(g, (int)B, hp->seed, hp->iteration, (uint32_t)e, b->perm);
-    if (rc != GMI_OK) return rc;
+    // the shuffles of up to kPermEpochs epochs in one launch (each launch of this small kernel is mostly latency)
+    const int32_t* perm = b->perm + (int64_t)(e % gmi::kPermEpochs) * B;
+    if (e % gmi::kPermEpochs == 0) {
+      const int ne = hp->epochs - e < gmi::kPermEpochs ? hp->epochs - e : gmi::kPermEpochs;
+      rc = gmi::launch_permutation(g, (int)B, hp->seed, hp->iteration, (uint32_t)e, ne, b->perm);
+      if (rc != GMI_OK) return rc;
+    }
     for (int j = 0; j < nmb; ++j) {
       int n_split = 1, nlb = 1;
-      rc = minibatch_pass(g, m, b, hp, b->perm + (int64_t)j * hp->minibatch, hp->minibatch, true, &n_split, &nlb);
+      rc = minibatch_pass(g, m, b, hp, perm + (int64_t)j * hp->minibatch, hp->minibatch, true, &n_split, &nlb);
       if (rc != GMI_OK) return rc;
       ++k;
       rc = launch_adam(g, &m, 1, n_split, nlb, hp, hp->minibatch, k,
@@ -578,15 +583,19 @@ extern "C" int ppo_update_group(const gmi_t* gs, const gmi_model_t* ms, const gm
   // instance 0's stream also reads what the other instances' earlier calls left (e.g. their buffers are
   // theirs alone, but the shared parameters were last written on stream 0): nothing to order before the loop.
   for (int e = 0; e < hp->epochs; ++e) {
-    for (int i = 0; i < n; ++i) {
-      rc = gmi::launch_permutation(gs[i], (int)B, hp->seed + (uint64_t)i, hp->iteration, (uint32_t)e, bs[i]->perm);
-      if (rc != GMI_OK) return rc;
+    if (e % gmi::kPermEpochs == 0) {
+      const int ne = hp->epochs - e < gmi::kPermEpochs ? hp->epochs - e : gmi::kPermEpochs;
+      for (int i = 0; i < n; ++i) {
+        rc = gmi::launch_permutation(gs[i], (int)B, hp->seed + (uint64_t)i, hp->iteration, (uint32_t)e, ne, bs[i]->perm);
+        if (rc != GMI_OK) return rc;
+      }
     }
+    const int64_t perm_off = (int64_t)(e % gmi::kPermEpochs) * B;
     for (int j = 0; j < nmb; ++j) {
       int n_split = 1, nlb = 1;
       for (int i = 0; i < n; ++i) {
         int ns_i = 1, nlb_i = 1;
-        rc = minibatch_pass(gs[i], ms[i], bs[i], hp, bs[i]->perm + (int64_t)j * hp->minibatch, hp->minibatch, true,
+        rc = minibatch_pass(gs[i], ms[i], bs[i], hp, bs[i]->perm + perm_off + (int64_t)j * hp->minibatch, hp->minibatch, true,
                             &ns_i, &nlb_i, false);
         if (rc != GMI_OK) return rc;
         if (i == 0) { n_split = ns_i; nlb = nlb_i; }

@@ -411,6 +411,17 @@ def test_whole_iteration_c1_fp32_matches_oracle(g):
     ses.close()
 
 
+def test_update_over_more_epochs_than_one_shuffle_launch_covers(g):
+    """The shuffles of 8 epochs are made by one launch; 11 epochs need a second one that refills the same
+    array.  fp32, so the parameters after 22 Adam steps follow the oracle closely."""
+    cfg = syn.get_config("C1")
+    ref, ses, stats, _ = _run_iteration_both(g, cfg, cfg.n_envs, 512, cfg.horizon, 11, "f32")
+    assert stats.shape == ref["stats"].shape == (22, 5)
+    assert np.abs(stats - ref["stats"]).max() <= 2e-3
+    assert rel_l2(ses.theta.cpu().numpy(), ref["theta"]) <= 1e-4
+    ses.close()
+
+
 @pytest.mark.parametrize("name,n_envs,minibatch,horizon", [("C2", 512, 2048, 8), ("C3", 256, 1024, 8),
                                                            ("C4", 320, 1280, 4)])
 @pytest.mark.parametrize("fused_rollout", [True, False])
