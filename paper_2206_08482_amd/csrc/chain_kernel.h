@@ -287,15 +287,6 @@ __device__ __forceinline__ void scr_to_global(const char* scr, int lane, uint16_
     *reinterpret_cast<uint4*>(dst + (int64_t)(row0 + r) * ld + col0 + ch * 8) = v;     // arrays hold whole tiles
   }
 }
-// one of the 2 * GS steps of scr_to_global
-template <int GS>
-__device__ __forceinline__ void scr_to_global_step(const char* scr, int lane, uint16_t* dst, int ld, int col0, int row0,
-                                                   int it) {
-  constexpr int LPR = 4 * GS, RPI = 64 / LPR;
-  const int r = it * RPI + lane / LPR, ch = lane % LPR;
-  const uint4 v = *reinterpret_cast<const uint4*>(scr + r * kScrStride + ch * 16);
-  *reinterpret_cast<uint4*>(dst + (int64_t)(row0 + r) * ld + col0 + ch * 8) = v;     // arrays hold whole tiles
-}
 template <int GS>
 __device__ __forceinline__ void global_to_regs(uint4* ht, int lane, const uint16_t* src, int ld, int col0, int row0,
                                                int rows) {
@@ -481,18 +472,6 @@ __device__ __forceinline__ void fetch_kstep(Ctx<S>& c) {
       for (int t = 0; t < ci.gs; ++t)
         c.wq[RING][t] = *reinterpret_cast<const bf16x8*>(slot + (K * ci.gs + t) * 1024);
     }
-  }
-}
-
-// number of operands fetch_kstep<S, C, K, *> reads
-template <class S, int C, int K>
-__host__ __device__ constexpr int fetch_count() {
-  if constexpr (C < S::nch()) {
-    constexpr ChunkInfo ci = cd_chunk(S::dims(), C);
-    if constexpr (K >= ci.nks) return fetch_count<S, C + 1, K - ci.nks>();
-    else return ci.gs;
-  } else {
-    return 0;
   }
 }
 
