@@ -42,8 +42,12 @@ def cu_masks(n_cu: int, counts: Sequence[int], style: str = "contiguous") -> Lis
     contiguous: instance i takes the next counts[i] / 8 rows; interleaved: rows are dealt out
     round-robin in proportion to the counts, so every instance's CUs are spread over the CU index range
     of each die."""
-    assert sum(counts) <= n_cu and n_cu % XCDS == 0
-    assert all(c % XCDS == 0 and c > 0 for c in counts), "CU counts must be positive multiples of 8"
+    if n_cu % XCDS or sum(counts) > n_cu:
+        raise ValueError(f"{sum(counts)} compute units asked for, the device has {n_cu}")
+    if not all(c % XCDS == 0 and c > 0 for c in counts):
+        raise ValueError("CU counts must be positive multiples of 8 (the same number on every die)")
+    if style not in ("contiguous", "interleaved"):
+        raise ValueError(f"unknown style {style!r}")
     words = (n_cu + 31) // 32
     n_rows = n_cu // XCDS
     rows = [c // XCDS for c in counts]
