@@ -327,7 +327,8 @@ def ppo_update(gmi: int, model: int, buf: int, hp: PPOHparams, stats_out=None) -
 
 def ppo_update_group(gmis, models, bufs, hp: PPOHparams, stats_out=None) -> None:
     n = len(gmis)
-    assert len(models) == n and len(bufs) == n
+    if len(models) != n or len(bufs) != n:
+        raise ValueError("ppo_update_group: one model and one buffer per instance")
     arr = lambda xs: (C.c_void_p * n)(*xs)
     _check(_lib.ppo_update_group(arr(gmis), arr(models), arr(bufs), n, C.byref(hp), _ptr(stats_out)))
 
