@@ -357,35 +357,15 @@ int check_model_buffer(const char* fn, gmi_model_t m, gmi_buffer_t b) {
   return GMI_OK;
 }
 
-// Forward + loss (+ backward products) of the `rows` samples idx[0..rows) of the buffer.
-// Leaves gradient partials in m->grad_part / m->stat_part.  Returns the split count through n_split.
-int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx,
-                   int rows, bool want_grad, int* n_split_out, int* n_loss_blocks_out, bool allow_fused = true) {
+// The per-layer form of a minibatch pass: gather, forward of every layer, loss, and (want_grad) the input-gradient
+// products, one launch each.  Leaves h, dz and one statistics row per loss workgroup (*n_loss_blocks_out rows).
+int layers_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx, int rows,
+                bool want_grad, int* n_loss_blocks_out) {
   const ModelLayout& L = m->L;
   const bool bf = L.dtype == GMI_DTYPE_BF16;
   const int A = L.act_dim;
-  int rc;
-  bool fused = false;
-  if (g->fusion >= 2 && want_grad && allow_fused) {
-    rc = gmi::launch_train_fused(g, m, b, hp, idx, rows);
-    if (rc == GMI_OK) fused = true;
-    else if (rc != GMI_ERR_UNSUPPORTED) return rc;
-  }
-  bool gathered = false, chained = false;
-  if (!fused && g->fusion >= 1 && want_grad && bf) {
-    // register-chained kernel (gather + forward + loss + input gradients in one launch) where this shape has one
-    int n_stat_rows = 0;
-    rc = gmi::launch_train_chain(g, m, b, hp, idx, rows, &n_stat_rows);
-    if (rc == GMI_OK) { fused = true; chained = true; *n_loss_blocks_out = n_stat_rows; }
-    else if (rc != GMI_ERR_UNSUPPORTED) return rc;
-  }
-  if (fused) {
-    if (!chained) *n_loss_blocks_out = -1;     // statistics already summed (row kLossBlocksMax of stat_part)
-  } else {
-  if (!gathered) {
-    rc = gmi::launch_gather(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, &b->d);
-    if (rc != GMI_OK) return rc;
-  }
+  int rc = gmi::launch_gather(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, &b->d);
+  if (rc != GMI_OK) return rc;
   rc = gmi::forward_nets(g, m, rows, true, true, m->mu, m->val);
   if (rc != GMI_OK) return rc;
   int nlb = (rows + 255) / 256;
@@ -395,14 +375,14 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
   const int head = L.n_layers - 1;
   const size_t lds = sizeof(float) * (4 * A + 16);
   {
-  gmi::ProfScope ps(g, gmi::kClsLoss);
-  if (bf)
-    ps.launch(loss_kernel<uint16_t>, dim3(nlb), dim3(256), lds, rows, A, m->mu, m->val, m->mb_act, m->mb_logp, m->mb_adv, m->mb_ret,
+    gmi::ProfScope ps(g, gmi::kClsLoss);
+    if (bf)
+      ps.launch(loss_kernel<uint16_t>, dim3(nlb), dim3(256), lds, rows, A, m->mu, m->val, m->mb_act, m->mb_logp, m->mb_adv, m->mb_ret,
                                                 log_std, hp->clip, hp->c_v, want_grad ? 1 : 0,
                                                 (uint16_t*)m->dz[0][head], L.net[0][head].out_pad,
                                                 (uint16_t*)m->dz[1][head], L.net[1][head].out_pad, m->stat_part);
-  else
-    ps.launch(loss_kernel<float>, dim3(nlb), dim3(256), lds, rows, A, m->mu, m->val, m->mb_act, m->mb_logp, m->mb_adv, m->mb_ret,
+    else
+      ps.launch(loss_kernel<float>, dim3(nlb), dim3(256), lds, rows, A, m->mu, m->val, m->mb_act, m->mb_logp, m->mb_adv, m->mb_ret,
                                              log_std, hp->clip, hp->c_v, want_grad ? 1 : 0, (float*)m->dz[0][head],
                                              L.net[0][head].out_pad, (float*)m->dz[1][head], L.net[1][head].out_pad,
                                              m->stat_part);
@@ -434,7 +414,27 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
     rc = gmi::launch_linear(g, L.dtype, gmi::kEpiEluGrad, rows, lb);
     if (rc != GMI_OK) return rc;
   }
-  }  // !fused
+  return GMI_OK;
+}
+
+// Forward + loss (+ backward products) of the `rows` samples idx[0..rows) of the buffer.
+// Leaves gradient partials in m->grad_part / m->stat_part.  Returns the split count through n_split.
+int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx,
+                   int rows, bool want_grad, int* n_split_out, int* n_loss_blocks_out, bool allow_fused = true) {
+  const ModelLayout& L = m->L;
+  const bool bf = L.dtype == GMI_DTYPE_BF16;
+  int rc = GMI_ERR_UNSUPPORTED;
+  if (g->fusion >= 2 && want_grad && allow_fused) {
+    // row-tile fused kernel (opt-in): statistics already summed (row kLossBlocksMax of stat_part)
+    rc = gmi::launch_train_fused(g, m, b, hp, idx, rows);
+    if (rc == GMI_OK) *n_loss_blocks_out = -1;
+  }
+  if (rc == GMI_ERR_UNSUPPORTED && g->fusion >= 1 && want_grad && bf) {
+    // register-chained kernel (gather + forward + loss + input gradients in one launch) where this shape has one
+    rc = gmi::launch_train_chain(g, m, b, hp, idx, rows, n_loss_blocks_out);
+  }
+  if (rc == GMI_ERR_UNSUPPORTED) rc = layers_pass(g, m, b, hp, idx, rows, want_grad, n_loss_blocks_out);
+  if (rc != GMI_OK || !want_grad) return rc;
   // weight / bias gradients of every layer of both nets in one launch
   int n_split = (rows + 63) / 64;
   if (n_split > m->n_split_max) n_split = m->n_split_max;
