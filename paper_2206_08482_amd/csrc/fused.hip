@@ -4,6 +4,11 @@
 // (Section 3 of the paper, "DRL Agent"): observation conversion, every layer of both nets, and the Gaussian
 // sampling epilogue.
 #include "internal.h"
+#ifdef GMI_ROLLOUT_TIMING
+#define GMI_RT_MARK(i) do { if (blockIdx.x == 0 && tid == 0 && t == 3) a.dbg[i] = __builtin_readcyclecounter(); } while (0)
+#else
+#define GMI_RT_MARK(i) do { } while (0)
+#endif
 #include "rng.cuh"
 
 namespace {
@@ -289,6 +294,9 @@ struct RolloutArgs {
                                     // step in the (then idle) hidden-activation space, 0 = read from global
   float* b_obs; float* b_act; float* b_logp; float* b_val; float* b_rew; uint8_t* b_done;
   float* last_value;
+#ifdef GMI_ROLLOUT_TIMING
+  long long* dbg;                   // [16] clock at the phase boundaries of one step (workgroup 0, thread 0)
+#endif
 };
 
 // Simulator step for the tile: items (group of EPT envs, block of 4 state elements).  mt points at the
@@ -570,12 +578,14 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   for (int t = 0; t <= a.T; ++t) {
     // both nets, layer by layer; after the last step only the value net (bootstrap value)
     const bool run = half == 1 || t < a.T;
+    GMI_RT_MARK(0);
     for (int idx = tid; idx < Rv * a.obs_pad; idx += NT) {
       const int r = idx / a.obs_pad, k = idx - r * a.obs_pad;
       const float v = k < O ? s_in[r * OA + k] : 0.f;
       s_x0[r * stride_x0 + k] = (uint16_t)(pack_bf16(v, 0.f) & 0xFFFFu);
     }
     __syncthreads();
+    GMI_RT_MARK(1);
     if constexpr (kStationary) {
       ws_net<WS, 0, RT>(wreg, N, s_nb, s_x0, stride_x0, s_a, s_b, stride_h, s_head, head_stride, run, wave4, tid & 63);
     } else {
@@ -598,6 +608,7 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
                                    s_head, head_stride, N.out_store, nullptr, 0, wave4);
       __syncthreads();
     }
+    GMI_RT_MARK(2);
     if (t == a.T) {
       if (tid < Rv && r0 + tid < a.n) a.last_value[r0 + tid] = s_val[tid];
       break;
@@ -623,6 +634,7 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       }
     }
     __syncthreads();
+    GMI_RT_MARK(3);
     const uint32_t step = a.step0 + (uint32_t)t;
     const int64_t slot0 = (int64_t)t * a.ld_envs + r0;
     // action = mu + exp(log_std) * eps, log-prob partials per block of 4 action elements
@@ -650,10 +662,12 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       }
       s_lp[r * nba + b] = lp;
     }
+    GMI_RT_MARK(8);
     for (int idx = tid; idx < Rv * O; idx += NT) {
       const int r = idx / O, k = idx - r * O;
       if (r0 + r < a.n) a.b_obs[(slot0 + r) * O + k] = s_in[r * OA + k];
     }
+    GMI_RT_MARK(9);
     if (tid < Rv) {
       const int e = r0 + tid;
       int d = 0;
@@ -669,7 +683,9 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       }
       s_done[tid] = d;
     }
+    GMI_RT_MARK(10);
     __syncthreads();
+    GMI_RT_MARK(4);
     if (tid < Rv && r0 + tid < a.n) {
       float lp = 0.f;
       for (int b = 0; b < nba; ++b) lp += s_lp[tid * nba + b];
@@ -688,7 +704,9 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       if ((Rv / 4) * nbo >= 192) sim_items<4>(a, Rv, r0, step, s_in, mt_glb_ptr, s_part, s_next, s_done, s_noise, npr, nba);
       else sim_items<1>(a, Rv, r0, step, s_in, mt_glb_ptr, s_part, s_next, s_done, s_noise, npr, nba);
     }
+    GMI_RT_MARK(5);
     __syncthreads();
+    GMI_RT_MARK(6);
     if (tid < Rv && r0 + tid < a.n) {
       float sum = 0.f;
       for (int j = 0; j < nbo; ++j) sum += s_part[tid * nbo + j];
@@ -699,6 +717,7 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       s_in[r * OA + k] = (r0 + r < a.n) ? s_next[r * o4 + k] : 0.f;
     }
     __syncthreads();
+    GMI_RT_MARK(7);
   }
   // the loop ends right after the bootstrap value; s_in still holds the final state
   for (int idx = tid; idx < Rv * O; idx += NT) {
@@ -1109,6 +1128,14 @@ int launch_train_fused(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_p
 
 }  // namespace gmi
 
+#ifdef GMI_ROLLOUT_TIMING
+static long long* g_rollout_dbg = nullptr;
+extern "C" int gmi_rollout_timing(long long* out, int n) {
+  if (!g_rollout_dbg) return -1;
+  return (int)hipMemcpy(out, g_rollout_dbg, (size_t)n * 8, hipMemcpyDeviceToHost);
+}
+#endif
+
 extern "C" int rollout_collect(gmi_t g, gmi_model_t m, gmi_env_t env, gmi_buffer_t b, float* obs, uint64_t seed,
                                uint32_t step0, uint32_t env_offset, float* last_value) {
   if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "rollout_collect: bad instance");
@@ -1162,6 +1189,12 @@ extern "C" int rollout_collect(gmi_t g, gmi_model_t m, gmi_env_t env, gmi_buffer
   a.mt_lds = mt_mode;
   a.b_obs = bd.obs; a.b_act = bd.act; a.b_logp = bd.logp; a.b_val = bd.val; a.b_rew = bd.rew; a.b_done = bd.done;
   a.last_value = last_value;
+#ifdef GMI_ROLLOUT_TIMING
+  static long long* dbg = nullptr;
+  if (!dbg) { GMI_HIP(hipMalloc(&dbg, 16 * 8)); GMI_HIP(hipMemset(dbg, 0, 16 * 8)); }
+  a.dbg = dbg;
+  g_rollout_dbg = dbg;
+#endif
   const size_t lds = rollout_lds_bytes(m, R, mt_lds);
   // fewer 32-env tiles than compute units: 16 envs per workgroup use twice as many of them
   const int rows_per_wg = (R == 32 && (n + 31) / 32 < g->cu_count && n > 16) ? 16 : R;
