@@ -574,17 +574,18 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   uint32_t ep = 0;                                   // thread r < R carries env r's episode counter
   if (tid < Rv && r0 + tid < a.n) ep = a.episode_step[r0 + tid];
   __syncthreads();
+  // the nets' bf16 copy of the state, zero padded; every later step refreshes it together with the state itself
+  for (int idx = tid; idx < Rv * a.obs_pad; idx += NT) {
+    const int r = idx / a.obs_pad, k = idx - r * a.obs_pad;
+    const float v = k < O ? s_in[r * OA + k] : 0.f;
+    s_x0[r * stride_x0 + k] = (uint16_t)(pack_bf16(v, 0.f) & 0xFFFFu);
+  }
+  __syncthreads();
 
   for (int t = 0; t <= a.T; ++t) {
     // both nets, layer by layer; after the last step only the value net (bootstrap value)
     const bool run = half == 1 || t < a.T;
     GMI_RT_MARK(0);
-    for (int idx = tid; idx < Rv * a.obs_pad; idx += NT) {
-      const int r = idx / a.obs_pad, k = idx - r * a.obs_pad;
-      const float v = k < O ? s_in[r * OA + k] : 0.f;
-      s_x0[r * stride_x0 + k] = (uint16_t)(pack_bf16(v, 0.f) & 0xFFFFu);
-    }
-    __syncthreads();
     GMI_RT_MARK(1);
     if constexpr (kStationary) {
       ws_net<WS, 0, RT>(wreg, N, s_nb, s_x0, stride_x0, s_a, s_b, stride_h, s_head, head_stride, run, wave4, tid & 63);
@@ -712,9 +713,13 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       for (int j = 0; j < nbo; ++j) sum += s_part[tid * nbo + j];
       a.b_rew[slot0 + tid] = -a.reward_scale * sum;
     }
-    for (int idx = tid; idx < Rv * O; idx += NT) {
-      const int r = idx / O, k = idx - r * O;
-      s_in[r * OA + k] = (r0 + r < a.n) ? s_next[r * o4 + k] : 0.f;
+    // the new state, in fp32 for the simulator and the stores and in bf16 for the next step's nets (one pass and
+    // one barrier instead of two)
+    for (int idx = tid; idx < Rv * a.obs_pad; idx += NT) {
+      const int r = idx / a.obs_pad, k = idx - r * a.obs_pad;
+      const float v = (k < O && r0 + r < a.n) ? s_next[r * o4 + k] : 0.f;
+      if (k < O) s_in[r * OA + k] = v;
+      s_x0[r * stride_x0 + k] = (uint16_t)(pack_bf16(v, 0.f) & 0xFFFFu);
     }
     __syncthreads();
     GMI_RT_MARK(7);
