@@ -386,9 +386,13 @@ __device__ __forceinline__ void sim_items(const RolloutArgs& a, int R, int r0, u
 template <class WS> struct WsFrags { static constexpr int value = WS::n_frags(); };
 template <> struct WsFrags<void> { static constexpr int value = 1; };
 
-template <int... DIMS>
+// Layers LDSL.. keep their operand blocks in LDS instead (one copy per net, fragment-major as in global memory):
+// with every layer in registers the kernel needed more than the 256 registers two waves per SIMD leave and the
+// compiler parked values in scratch memory, whose reloads sat in every phase of every step.
+template <int LDSL, int... DIMS>
 struct WsShape {
   static constexpr int NL = (int)sizeof...(DIMS) - 1;
+  static constexpr int lds_from = LDSL;
   static constexpr int dim(int i) {
     constexpr int d[] = {DIMS...};
     return d[i];
@@ -396,15 +400,22 @@ struct WsShape {
   static constexpr int max_tiles(int l) { return (dim(l + 1) / 32 + 3) / 4; }      // feature tiles of one wave
   static constexpr int frag_base(int l) {
     int n = 0;
-    for (int i = 0; i < l; ++i) n += max_tiles(i) * (dim(i) / 16);
+    for (int i = 0; i < l && i < LDSL; ++i) n += max_tiles(i) * (dim(i) / 16);
     return n;
   }
-  static constexpr int n_frags() { return frag_base(NL); }
+  static constexpr int n_frags() { return frag_base(NL) > 0 ? frag_base(NL) : 1; }
+  // bf16 elements of the LDS-resident layers before layer l / of all of them (one net)
+  static constexpr int lds_base(int l) {
+    int n = 0;
+    for (int i = LDSL; i < l; ++i) n += (dim(i + 1) / 32) * (dim(i) / 16) * 512;
+    return n;
+  }
+  static constexpr int lds_elems() { return lds_base(NL); }
 };
 
 template <class WS, int L>
 __device__ __forceinline__ void ws_load(bf16x8* wreg, const FusedNet& N, int wave, int lane) {
-  if constexpr (L < WS::NL) {
+  if constexpr (L < WS::NL && L < WS::lds_from) {
     constexpr int nks = WS::dim(L) / 16, nft = WS::dim(L + 1) / 32, base = WS::frag_base(L);
 #pragma unroll
     for (int i = 0; i < WS::max_tiles(L); ++i) {
@@ -418,8 +429,22 @@ __device__ __forceinline__ void ws_load(bf16x8* wreg, const FusedNet& N, int wav
   }
 }
 
+// Copies the operand blocks of the LDS-resident layers of one net into s_w (all threads of the workgroup).
+template <class WS, int L>
+__device__ __forceinline__ void ws_stage(uint16_t* s_w, const FusedNet& N, int tid, int nthreads) {
+  if constexpr (L < WS::NL) {
+    if constexpr (L >= WS::lds_from) {
+      constexpr int n16 = (WS::dim(L + 1) / 32) * (WS::dim(L) / 16) * 64;       // 16-byte pieces
+      const uint4* src = reinterpret_cast<const uint4*>(N.w[L]);
+      uint4* dst = reinterpret_cast<uint4*>(s_w + WS::lds_base(L));
+      for (int i = tid; i < n16; i += nthreads) dst[i] = src[i];
+    }
+    ws_stage<WS, L + 1>(s_w, N, tid, nthreads);
+  }
+}
+
 template <class WS, int L, int RT, int EPI>
-__device__ __forceinline__ void ws_layer(const bf16x8* wreg, const float* s_bias, const uint16_t* s_in, int stride_in,
+__device__ __forceinline__ void ws_layer(const bf16x8* wreg, const uint16_t* s_w, const float* s_bias, const uint16_t* s_in, int stride_in,
                                          uint16_t* s_out, int stride_out, float* s_head, int head_stride,
                                          int out_store, int wave, int lane) {
   constexpr int nks = WS::dim(L) / 16, nft = WS::dim(L + 1) / 32, base = WS::frag_base(L);
@@ -439,7 +464,10 @@ __device__ __forceinline__ void ws_layer(const bf16x8* wreg, const float* s_bias
 #pragma unroll
         for (int j = 0; j < RT; ++j) {
           const bf16x8 b = *reinterpret_cast<const bf16x8*>(xrow + j * 32 * stride_in + ks * 16);
-          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[base + i * nks + ks], b, acc[j], 0, 0, 0);
+          bf16x8 w;
+          if constexpr (L < WS::lds_from) w = wreg[base + i * nks + ks];
+          else w = *reinterpret_cast<const bf16x8*>(s_w + WS::lds_base(L) + (tile * nks + ks) * 512 + lane * 8);
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, b, acc[j], 0, 0, 0);
         }
       const int fb = tile * 32;
 #pragma unroll
@@ -470,26 +498,27 @@ __device__ __forceinline__ void ws_layer(const bf16x8* wreg, const float* s_bias
 // All layers of one net from layer L on, hidden activations ping-ponging between s_a and s_b as in the
 // streaming form; every layer ends with a workgroup barrier.
 template <class WS, int L, int RT>
-__device__ __forceinline__ void ws_net(const bf16x8* wreg, const FusedNet& N, const float* s_nb, const uint16_t* in,
+__device__ __forceinline__ void ws_net(const bf16x8* wreg, const uint16_t* s_w, const FusedNet& N, const float* s_nb, const uint16_t* in,
                                        int stride_in, uint16_t* s_a, uint16_t* s_b, int stride_h, float* s_head,
                                        int head_stride, bool run, int wave, int lane) {
   if constexpr (L < WS::NL - 1) {
     uint16_t* out = (L & 1) ? s_b : s_a;
     if (run)
-      ws_layer<WS, L, RT, kFEpiElu>(wreg, s_nb + N.bias_off[L], in, stride_in, out, stride_h, nullptr, 0, 0, wave, lane);
+      ws_layer<WS, L, RT, kFEpiElu>(wreg, s_w, s_nb + N.bias_off[L], in, stride_in, out, stride_h, nullptr, 0, 0, wave, lane);
     __syncthreads();
-    ws_net<WS, L + 1, RT>(wreg, N, s_nb, out, stride_h, s_a, s_b, stride_h, s_head, head_stride, run, wave, lane);
+    ws_net<WS, L + 1, RT>(wreg, s_w, N, s_nb, out, stride_h, s_a, s_b, stride_h, s_head, head_stride, run, wave, lane);
   } else {
     if (run)
-      ws_layer<WS, L, RT, kFEpiHead>(wreg, s_nb + N.bias_off[L], in, stride_in, nullptr, 0, s_head, head_stride,
+      ws_layer<WS, L, RT, kFEpiHead>(wreg, s_w, s_nb + N.bias_off[L], in, stride_in, nullptr, 0, s_head, head_stride,
                                      N.out_store, wave, lane);
     __syncthreads();
   }
 }
 
-// Shapes with a weight-stationary rollout: at most 36 operand blocks (144 registers) per wave.
-using WsAnt = WsShape<64, 256, 128, 64, 32>;         // 60:256:128:64:8 (benchmark workload C2), 48:256:128:64:12
-using WsSmallObs = WsShape<32, 256, 128, 64, 32>;    // 24:256:128:64:3, 23:256:128:64:9
+// Shapes with a weight-stationary rollout: the first two layers in registers (24 operand blocks = 96 registers per
+// wave), the last two in LDS (20 KiB per net).
+using WsAnt = WsShape<2, 64, 256, 128, 64, 32>;         // 60:256:128:64:8 (benchmark workload C2), 48:256:128:64:12
+using WsSmallObs = WsShape<2, 32, 256, 128, 64, 32>;    // 24:256:128:64:3, 23:256:128:64:9
 
 template <class WS>
 bool ws_matches(const ModelLayout& L) {
@@ -533,6 +562,8 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   // the done draw (raw word in .x); in the hidden-activation space, which is idle once the heads are done
   float4* s_noise = reinterpret_cast<float4*>(s_reg + next_bytes);
   float* s_mt = s_bias + ((a.net[0].bias_total + a.net[1].bias_total + 3) & ~3);     // [O + A][o4] when mt_lds == 2
+  // weight-stationary form: operand blocks of the LDS-resident layers, policy net then value net
+  uint16_t* s_wl = reinterpret_cast<uint16_t*>(s_mt + (a.mt_lds == 2 ? OA * o4 : 0));
   const int tid = threadIdx.x;
   // wave-uniform values, so that the per-net kernel arguments are fetched by scalar loads
   const int half = __builtin_amdgcn_readfirstlane(tid >> 8), wave4 = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);
@@ -560,7 +591,13 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   constexpr bool kStationary = !std::is_void<WS>::value;
   // this wave's weight operands, fetched once (a dummy single entry in the streaming form)
   bf16x8 wreg[WsFrags<WS>::value];
-  if constexpr (kStationary) ws_load<WS, 0>(wreg, N, wave4, tid & 63);
+  const uint16_t* s_w = s_wl;
+  if constexpr (kStationary) {
+    ws_load<WS, 0>(wreg, N, wave4, tid & 63);
+    ws_stage<WS, 0>(s_wl, a.net[0], tid, NT);
+    ws_stage<WS, 0>(s_wl + WS::lds_elems(), a.net[1], tid, NT);
+    s_w = s_wl + (half ? WS::lds_elems() : 0);
+  }
 
   // The grid never exceeds what the instance's compute units hold at once: a workgroup takes the tiles
   // blockIdx.x, blockIdx.x + gridDim.x, ... one after the other, each through all T steps.  (Workgroups
@@ -588,7 +625,7 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
     GMI_RT_MARK(0);
     GMI_RT_MARK(1);
     if constexpr (kStationary) {
-      ws_net<WS, 0, RT>(wreg, N, s_nb, s_x0, stride_x0, s_a, s_b, stride_h, s_head, head_stride, run, wave4, tid & 63);
+      ws_net<WS, 0, RT>(wreg, s_w, N, s_nb, s_x0, stride_x0, s_a, s_b, stride_h, s_head, head_stride, run, wave4, tid & 63);
     } else {
       const uint16_t* in = s_x0;
       int stride_in = stride_x0;
@@ -709,8 +746,18 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
     __syncthreads();
     GMI_RT_MARK(6);
     if (tid < Rv && r0 + tid < a.n) {
+      // same order of additions as one by one, eight LDS reads in flight
+      const float* q = s_part + tid * nbo;
       float sum = 0.f;
-      for (int j = 0; j < nbo; ++j) sum += s_part[tid * nbo + j];
+      int j = 0;
+      for (; j + 8 <= nbo; j += 8) {
+        float t8[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t8[u] = q[j + u];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sum += t8[u];
+      }
+      for (; j < nbo; ++j) sum += q[j];
       a.b_rew[slot0 + tid] = -a.reward_scale * sum;
     }
     // the new state, in fp32 for the simulator and the stores and in bf16 for the next step's nets (one pass and
@@ -1001,6 +1048,13 @@ size_t rollout_stage_room(const gmi_model* m, int R) {
   return hid > used ? hid - used : 0;
 }
 
+// LDS of the operand blocks that the weight-stationary form keeps there (both nets); 0 for other shapes.
+size_t rollout_ws_lds_bytes(const ModelLayout& L) {
+  if (ws_matches<WsAnt>(L)) return 2 * (size_t)WsAnt::lds_elems() * 2;
+  if (ws_matches<WsSmallObs>(L)) return 2 * (size_t)WsSmallObs::lds_elems() * 2;
+  return 0;
+}
+
 size_t rollout_lds_bytes(const gmi_model* m, int R, bool mt_lds) {
   const ModelLayout& L = m->L;
   int max_h = 32;
@@ -1011,7 +1065,7 @@ size_t rollout_lds_bytes(const gmi_model* m, int R, bool mt_lds) {
   return (size_t)((R * (O + A) + 3) & ~3) * 4 + (size_t)R * (gmi::pad32(O) + 8) * 2 + region +
          (size_t)(R * (A + 1 + (A + 3) / 4 + o4 / 4) + ((R + 3) & ~3)) * 4 +
          ((bias_floats(m, 0) + bias_floats(m, 1) + 3) & ~(size_t)3) * 4 +
-         (mt_lds ? (size_t)(O + A) * o4 * 4 : 0);
+         (mt_lds ? (size_t)(O + A) * o4 * 4 : 0) + rollout_ws_lds_bytes(L);
 }
 
 }  // namespace
