@@ -675,30 +675,30 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
     GMI_RT_MARK(3);
     const uint32_t step = a.step0 + (uint32_t)t;
     const int64_t slot0 = (int64_t)t * a.ld_envs + r0;
-    // action = mu + exp(log_std) * eps, log-prob partials per block of 4 action elements
-    for (int item = tid; item < Rv * nba; item += NT) {
-      const int r = item / nba, b = item - r * nba;
-      const int e = r0 + r;
-      float lp = 0.f;
-      if (e < a.n) {
-        const float4 zn = s_noise[r * npr + b];
-        const float z[4] = {zn.x, zn.y, zn.z, zn.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int j = 4 * b + i;
-          if (j < A) {
-            const float ls = a.log_std[j];
-            const float act = fmaf(expf(ls), z[i], s_mu[r * A + j]);
-            s_in[r * OA + O + j] = act;
-            a.b_act[(slot0 + r) * A + j] = act;
-            lp += -0.5f * z[i] * z[i] - ls - 0.918938533204672742f;
-          }
+    // action = mu + exp(log_std) * eps, log-prob partials per block of 4 action elements: one thread per element;
+    // the four terms of a block are added in index order through lane exchanges (((t0 + t1) + t2) + t3, the order
+    // of a single accumulator), so that one thread per block no longer walks its four elements one after the other
+    for (int item = tid; item < Rv * nba * 4; item += NT) {
+      const int blk = item >> 2, i = item & 3;
+      const int r = blk / nba, b = blk - r * nba;
+      const int e = r0 + r, j = 4 * b + i;
+      float term = 0.f;
+      if (j < A) {
+        float act = 0.f;
+        if (e < a.n) {
+          const float z = reinterpret_cast<const float*>(s_noise + r * npr + b)[i];
+          const float ls = a.log_std[j];
+          act = fmaf(expf(ls), z, s_mu[r * A + j]);
+          a.b_act[(slot0 + r) * A + j] = act;
+          term = -0.5f * z * z - ls - 0.918938533204672742f;
         }
-      } else {
-        for (int i = 0; i < 4; ++i)
-          if (4 * b + i < A) s_in[r * OA + O + 4 * b + i] = 0.f;
+        s_in[r * OA + O + j] = act;
       }
-      s_lp[r * nba + b] = lp;
+      float lp = term;
+      lp += __shfl_down(term, 1, 64);
+      lp += __shfl_down(term, 2, 64);
+      lp += __shfl_down(term, 3, 64);
+      if (i == 0) s_lp[blk] = lp;
     }
     GMI_RT_MARK(8);
     for (int idx = tid; idx < Rv * O; idx += NT) {
