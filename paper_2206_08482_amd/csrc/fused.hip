@@ -608,8 +608,11 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
     const int r = idx / O, k = idx - r * O;
     s_in[r * OA + k] = (r0 + r < a.n) ? a.obs_state[(int64_t)(r0 + r) * O + k] : 0.f;
   }
-  uint32_t ep = 0;                                   // thread r < R carries env r's episode counter
-  if (tid < Rv && r0 + tid < a.n) ep = a.episode_step[r0 + tid];
+  // thread 256 + r (r < Rv; the fifth wave, which has no action items) carries env r's episode counter and makes
+  // its done flag
+  const int dtid = tid - 256;
+  uint32_t ep = 0;
+  if (dtid >= 0 && dtid < Rv && r0 + dtid < a.n) ep = a.episode_step[r0 + dtid];
   __syncthreads();
   // the nets' bf16 copy of the state, zero padded; every later step refreshes it together with the state itself
   for (int idx = tid; idx < Rv * a.obs_pad; idx += NT) {
@@ -706,20 +709,20 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       if (r0 + r < a.n) a.b_obs[(slot0 + r) * O + k] = s_in[r * OA + k];
     }
     GMI_RT_MARK(9);
-    if (tid < Rv) {
-      const int e = r0 + tid;
+    if (dtid >= 0 && dtid < Rv) {
+      const int e = r0 + dtid;
       int d = 0;
       if (e < a.n) {
         if (a.done_period > 0) {
           d = ((ep + 1u) % a.done_period) == 0u;
         } else {
-          d = __float_as_uint(s_noise[tid * npr + nba + nbo].x) < a.done_threshold;
+          d = __float_as_uint(s_noise[dtid * npr + nba + nbo].x) < a.done_threshold;
         }
         ep = d ? 0u : ep + 1u;
-        a.b_done[slot0 + tid] = (uint8_t)d;
-        a.b_val[slot0 + tid] = s_val[tid];
+        a.b_done[slot0 + dtid] = (uint8_t)d;
+        a.b_val[slot0 + dtid] = s_val[dtid];
       }
-      s_done[tid] = d;
+      s_done[dtid] = d;
     }
     GMI_RT_MARK(10);
     __syncthreads();
@@ -776,7 +779,7 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
     const int r = idx / O, k = idx - r * O;
     if (r0 + r < a.n) a.obs_state[(int64_t)(r0 + r) * O + k] = s_in[r * OA + k];
   }
-  if (tid < Rv && r0 + tid < a.n) a.episode_step[r0 + tid] = ep;
+  if (dtid >= 0 && dtid < Rv && r0 + dtid < a.n) a.episode_step[r0 + dtid] = ep;
   __syncthreads();                                   // the next tile overwrites the state rows
   }
 }
