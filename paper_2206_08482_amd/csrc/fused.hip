@@ -292,6 +292,9 @@ struct RolloutArgs {
   uint32_t step0;
   int mt_lds;                       // m_t: 2 = LDS copy kept for the whole launch, 1 = LDS copy made at every
                                     // step in the (then idle) hidden-activation space, 0 = read from global
+  int noise_ahead;                  // 1 = the waves without simulator items make step t+1's random draws while the
+                                    // others run step t's simulator (two buffers at byte ahead_off of the LDS)
+  int ahead_off;
   float* b_obs; float* b_act; float* b_logp; float* b_val; float* b_rew; uint8_t* b_done;
   float* last_value;
 #ifdef GMI_ROLLOUT_TIMING
@@ -529,6 +532,25 @@ bool ws_matches(const ModelLayout& L) {
   return true;
 }
 
+// Random blocks first, first + stride, ... of one step of a tile, one float4 per (env, block): nba action-noise
+// blocks, nbo env-noise blocks, then the done draw (raw word in .x).
+__device__ __forceinline__ void draw_items(const RolloutArgs& a, float4* dst, uint32_t stp, int Rv, int r0, int npr, int nba,
+                                           int nbo, int first, int stride) {
+  for (int item = first; item < Rv * npr; item += stride) {
+    const int r = item / npr, q = item - r * npr;
+    const uint32_t e = (uint32_t)(r0 + r < a.n ? r0 + r : a.n - 1);
+    const bool is_act = q < nba, is_env = q >= nba && q < nba + nbo;
+    const uint32_t strm = is_act ? gmi::kStreamAction : (is_env ? gmi::kStreamEnv : gmi::kStreamDone);
+    const uint32_t blk = is_act ? (uint32_t)q : (is_env ? (uint32_t)(q - nba) : 0u);
+    const gmi::Words4 w = gmi::philox4x32_10((is_act ? a.a_env_offset : a.e_env_offset) + e, stp, strm, blk,
+                                             is_act ? a.ak0 : a.ek0, is_act ? a.ak1 : a.ek1);
+    float z0, z1, z2, z3;
+    gmi::normal_pair(w.w[0], w.w[1], z0, z1);
+    gmi::normal_pair(w.w[2], w.w[3], z2, z3);
+    dst[item] = (is_act || is_env) ? make_float4(z0, z1, z2, z3) : make_float4(__uint_as_float(w.w[0]), 0.f, 0.f, 0.f);
+  }
+}
+
 // 512 threads: waves 0-3 run the policy net and waves 4-7 the value net at the same time (the two nets
 // have the same hidden widths, so their layers finish together and share the barriers); every other phase
 // uses all 8 waves.
@@ -560,16 +582,19 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   float* s_bias = reinterpret_cast<float*>(s_done + ((R + 3) & ~3));                 // policy biases, value biases
   // this step's random draws, one float4 per (env, block): nba action-noise blocks, nbo env-noise blocks, then
   // the done draw (raw word in .x); in the hidden-activation space, which is idle once the heads are done
-  float4* s_noise = reinterpret_cast<float4*>(s_reg + next_bytes);
+  float4* s_noise_inplace = reinterpret_cast<float4*>(s_reg + next_bytes);
   float* s_mt = s_bias + ((a.net[0].bias_total + a.net[1].bias_total + 3) & ~3);     // [O + A][o4] when mt_lds == 2
   // weight-stationary form: operand blocks of the LDS-resident layers, policy net then value net
   uint16_t* s_wl = reinterpret_cast<uint16_t*>(s_mt + (a.mt_lds == 2 ? OA * o4 : 0));
+  float4* s_ahead = reinterpret_cast<float4*>(smem_raw + a.ahead_off);                // [2][Rv][npr] when noise_ahead
   const int tid = threadIdx.x;
   // wave-uniform values, so that the per-net kernel arguments are fetched by scalar loads
   const int half = __builtin_amdgcn_readfirstlane(tid >> 8), wave4 = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);
   // Rv <= R envs are owned by this workgroup (a half-filled tile doubles the workgroups of a small batch);
   // rows Rv..R-1 of the tile go through the matrix products but are never read or stored
   const int Rv = a.rows_per_wg;
+  // first thread of the first wave without a simulator item (rollout_sim_threads on the host)
+  const int ahead_tid0 = ((((Rv / 4) * nbo >= 192 ? (Rv / 4) * nbo : Rv * nbo) + 63) & ~63);
   for (int idx = tid; idx < (R - Rv) * stride_x0; idx += NT) s_x0[Rv * stride_x0 + idx] = 0;
   stage_biases(a.net[0], s_bias, tid, NT);
   stage_biases(a.net[1], s_bias + a.net[0].bias_total, tid, NT);
@@ -613,6 +638,7 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   const int dtid = tid - 256;
   uint32_t ep = 0;
   if (dtid >= 0 && dtid < Rv && r0 + dtid < a.n) ep = a.episode_step[r0 + dtid];
+  if (a.noise_ahead) draw_items(a, s_ahead, a.step0, Rv, r0, npr, nba, nbo, tid, NT);
   __syncthreads();
   // the nets' bf16 copy of the state, zero padded; every later step refreshes it together with the state itself
   for (int idx = tid; idx < Rv * a.obs_pad; idx += NT) {
@@ -657,24 +683,12 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
 
     // All random draws of this step, one block per thread and the same instructions for every kind of block
     // (left where they are used, they ran on the few threads of the sampling phase and inside the simulator's
-    // matrix product).
-    {
-      const uint32_t stp = a.step0 + (uint32_t)t;
-      for (int item = tid; item < Rv * npr; item += NT) {
-        const int r = item / npr, q = item - r * npr;
-        const uint32_t e = (uint32_t)(r0 + r < a.n ? r0 + r : a.n - 1);
-        const bool is_act = q < nba, is_env = q >= nba && q < nba + nbo;
-        const uint32_t strm = is_act ? gmi::kStreamAction : (is_env ? gmi::kStreamEnv : gmi::kStreamDone);
-        const uint32_t blk = is_act ? (uint32_t)q : (is_env ? (uint32_t)(q - nba) : 0u);
-        const gmi::Words4 w = gmi::philox4x32_10((is_act ? a.a_env_offset : a.e_env_offset) + e, stp, strm, blk,
-                                                 is_act ? a.ak0 : a.ek0, is_act ? a.ak1 : a.ek1);
-        float z0, z1, z2, z3;
-        gmi::normal_pair(w.w[0], w.w[1], z0, z1);
-        gmi::normal_pair(w.w[2], w.w[3], z2, z3);
-        s_noise[item] = (is_act || is_env) ? make_float4(z0, z1, z2, z3) : make_float4(__uint_as_float(w.w[0]), 0.f, 0.f, 0.f);
-      }
+    // matrix product).  With noise_ahead they were made during the previous step's simulator phase.
+    float4* s_noise = a.noise_ahead ? s_ahead + (size_t)(t & 1) * Rv * npr : s_noise_inplace;
+    if (!a.noise_ahead) {
+      draw_items(a, s_noise, a.step0 + (uint32_t)t, Rv, r0, npr, nba, nbo, tid, NT);
+      __syncthreads();
     }
-    __syncthreads();
     GMI_RT_MARK(3);
     const uint32_t step = a.step0 + (uint32_t)t;
     const int64_t slot0 = (int64_t)t * a.ld_envs + r0;
@@ -738,6 +752,9 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       for (int idx = tid; idx < OA * nbo; idx += NT) s_stage[idx] = reinterpret_cast<const float4*>(a.m_t)[idx];
       __syncthreads();
     }
+    // the next step's draws, by the waves that have no simulator item
+    if (a.noise_ahead && t + 1 < a.T && tid >= ahead_tid0)
+      draw_items(a, s_ahead + (size_t)((t + 1) & 1) * Rv * npr, step + 1u, Rv, r0, npr, nba, nbo, tid - ahead_tid0, NT - ahead_tid0);
     if (a.mt_lds != 0) {
       if ((Rv / 4) * nbo >= 192) sim_items<4>(a, Rv, r0, step, s_in, mt_lds_ptr, s_part, s_next, s_done, s_noise, npr, nba);
       else sim_items<1>(a, Rv, r0, step, s_in, mt_lds_ptr, s_part, s_next, s_done, s_noise, npr, nba);
@@ -1257,10 +1274,21 @@ extern "C" int rollout_collect(gmi_t g, gmi_model_t m, gmi_env_t env, gmi_buffer
   a.dbg = dbg;
   g_rollout_dbg = dbg;
 #endif
-  const size_t lds = rollout_lds_bytes(m, R, mt_lds);
+  size_t lds = rollout_lds_bytes(m, R, mt_lds);
   // fewer 32-env tiles than compute units: 16 envs per workgroup use twice as many of them
   const int rows_per_wg = (R == 32 && (n + 31) / 32 < g->cu_count && n > 16) ? 16 : R;
   a.rows_per_wg = rows_per_wg;
+  // Draws one step ahead: when the simulator's items leave enough whole waves idle to make a step's draws in two
+  // rounds at most, and two buffers of them still fit
+  {
+    const int nbo = a.o4 / 4, nba = (L.act_dim + 3) / 4, npr = nba + nbo + 1;
+    const int sim_items = (rows_per_wg / 4) * nbo >= 192 ? (rows_per_wg / 4) * nbo : rows_per_wg * nbo;
+    const int idle = 512 - ((sim_items + 63) & ~63);
+    const size_t off = (lds + 15) & ~(size_t)15, need = off + 2 * (size_t)rows_per_wg * npr * 16;
+    a.noise_ahead = (idle > 0 && idle * 2 >= rows_per_wg * npr && need <= kLdsMax) ? 1 : 0;
+    a.ahead_off = (int)off;
+    if (a.noise_ahead) lds = need;
+  }
   a.n_tiles = (n + rows_per_wg - 1) / rows_per_wg;
   // weight-stationary variant where this model's padded widths have one (both nets share them)
   typedef void (*rollout_fn)(RolloutArgs);
