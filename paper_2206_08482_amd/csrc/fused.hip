@@ -595,6 +595,10 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   const int Rv = a.rows_per_wg;
   // first thread of the first wave without a simulator item (rollout_sim_threads on the host)
   const int ahead_tid0 = ((((Rv / 4) * nbo >= 192 ? (Rv / 4) * nbo : Rv * nbo) + 63) & ~63);
+  // the observation stores go to the waves without action items when those are at least half of the workgroup
+  // (in the simulator phase the idle waves have no time to spare: measured, the next step's draws fill it)
+  const int act_waves_end = (Rv * nba * 4 + 63) & ~63;
+  const int obs_tid0 = act_waves_end <= NT / 2 ? act_waves_end : 0;
   for (int idx = tid; idx < (R - Rv) * stride_x0; idx += NT) s_x0[Rv * stride_x0 + idx] = 0;
   stage_biases(a.net[0], s_bias, tid, NT);
   stage_biases(a.net[1], s_bias + a.net[0].bias_total, tid, NT);
@@ -718,9 +722,12 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       if (i == 0) s_lp[blk] = lp;
     }
     GMI_RT_MARK(8);
-    for (int idx = tid; idx < Rv * O; idx += NT) {
-      const int r = idx / O, k = idx - r * O;
-      if (r0 + r < a.n) a.b_obs[(slot0 + r) * O + k] = s_in[r * OA + k];
+    // this step's observations to the buffer, by the waves without action items
+    if (tid >= obs_tid0) {
+      for (int idx = tid - obs_tid0; idx < Rv * O; idx += NT - obs_tid0) {
+        const int r = idx / O, k = idx - r * O;
+        if (r0 + r < a.n) a.b_obs[(slot0 + r) * O + k] = s_in[r * OA + k];
+      }
     }
     GMI_RT_MARK(9);
     if (dtid >= 0 && dtid < Rv) {
