@@ -35,8 +35,14 @@ typedef float float2v __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float elu_f(float z) {
-  return z > 0.f ? z : (__builtin_amdgcn_exp2f(z * 1.44269504f) - 1.0f);
+  // The [0, 1] clamp (an output modifier of the exponential, no instruction of its own) makes the exponential term
+  // 0 for z > 0, so that one maximum replaces the compare and select; for z <= 0, e^z - 1 >= z, and where rounding
+  // puts the computed difference below z (|z| < 1e-7) z is the closer value anyway.
+  const float e = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(z * 1.44269504f), 0.f, 1.f);
+  return __builtin_fmaxf(z, e - 1.0f);
 }
+// ELU'(z) from the stored output h = ELU(z) >= -1: 1 if h > 0 else h + 1, as one add with the [0, 1] clamp
+__device__ __forceinline__ float elu_grad_f(float h) { return __builtin_amdgcn_fmed3f(h + 1.0f, 0.f, 1.f); }
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   float2v v = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2v));
@@ -515,8 +521,8 @@ __device__ __forceinline__ void item_compute(Ctx<S>& c, const ChainArgs& a) {
     if constexpr (bwd) {
       // times ELU'(z) through the stored output h = ELU(z): 1 if h > 0 else h + 1
       const float h0 = bf16_lo(pre.x), h1 = bf16_hi(pre.x), h2 = bf16_lo(pre.y), h3 = bf16_hi(pre.y);
-      v0 *= h0 > 0.f ? 1.f : h0 + 1.f; v1 *= h1 > 0.f ? 1.f : h1 + 1.f;
-      v2 *= h2 > 0.f ? 1.f : h2 + 1.f; v3 *= h3 > 0.f ? 1.f : h3 + 1.f;
+      v0 *= elu_grad_f(h0); v1 *= elu_grad_f(h1);
+      v2 *= elu_grad_f(h2); v3 *= elu_grad_f(h3);
     } else {
       v0 = elu_f(v0 + __uint_as_float(pre.x)); v1 = elu_f(v1 + __uint_as_float(pre.y));
       v2 = elu_f(v2 + __uint_as_float(pre.z)); v3 = elu_f(v3 + __uint_as_float(pre.w));

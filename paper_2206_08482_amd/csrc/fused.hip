@@ -19,8 +19,14 @@ typedef float float2v __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float elu_f(float z) {
-  return z > 0.f ? z : (__builtin_amdgcn_exp2f(z * 1.44269504f) - 1.0f);
+  // The [0, 1] clamp (an output modifier of the exponential, no instruction of its own) makes the exponential term
+  // 0 for z > 0, so that one maximum replaces the compare and select; for z <= 0, e^z - 1 >= z, and where rounding
+  // puts the computed difference below z (|z| < 1e-7) z is the closer value anyway.
+  const float e = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(z * 1.44269504f), 0.f, 1.f);
+  return __builtin_fmaxf(z, e - 1.0f);
 }
+// ELU'(z) from the stored output h = ELU(z) >= -1: 1 if h > 0 else h + 1, as one add with the [0, 1] clamp
+__device__ __forceinline__ float elu_grad_f(float h) { return __builtin_amdgcn_fmed3f(h + 1.0f, 0.f, 1.f); }
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   float2v v = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2v));
@@ -132,8 +138,8 @@ __device__ __forceinline__ void fused_layer(const uint16_t* __restrict__ W, cons
             const uint2 hv = *reinterpret_cast<const uint2*>(&s_h[r * stride_hh + f]);
             const float h0 = bf16_to_f((uint16_t)(hv.x & 0xFFFF)), h1 = bf16_to_f((uint16_t)(hv.x >> 16));
             const float h2 = bf16_to_f((uint16_t)(hv.y & 0xFFFF)), h3 = bf16_to_f((uint16_t)(hv.y >> 16));
-            o0 *= h0 > 0.f ? 1.f : h0 + 1.f; o1 *= h1 > 0.f ? 1.f : h1 + 1.f;
-            o2 *= h2 > 0.f ? 1.f : h2 + 1.f; o3 *= h3 > 0.f ? 1.f : h3 + 1.f;
+            o0 *= elu_grad_f(h0); o1 *= elu_grad_f(h1);
+            o2 *= elu_grad_f(h2); o3 *= elu_grad_f(h3);
             *reinterpret_cast<uint2*>(&s_out[r * stride_out + f]) = make_uint2(pack_bf16(o0, o1), pack_bf16(o2, o3));
           } else if (EPI == kFEpiElu) {
             *reinterpret_cast<uint2*>(&s_out[r * stride_out + f]) =

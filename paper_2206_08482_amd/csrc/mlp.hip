@@ -20,8 +20,14 @@ typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
 
 // ELU through the hardware base-2 exponential (abs. error ~1e-7, far below bf16 resolution)
 __device__ __forceinline__ float elu_f(float z) {
-  return z > 0.f ? z : (__builtin_amdgcn_exp2f(z * 1.44269504f) - 1.0f);
+  // The [0, 1] clamp (an output modifier of the exponential, no instruction of its own) makes the exponential term
+  // 0 for z > 0, so that one maximum replaces the compare and select; for z <= 0, e^z - 1 >= z, and where rounding
+  // puts the computed difference below z (|z| < 1e-7) z is the closer value anyway.
+  const float e = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(z * 1.44269504f), 0.f, 1.f);
+  return __builtin_fmaxf(z, e - 1.0f);
 }
+// ELU'(z) from the stored output h = ELU(z) >= -1: 1 if h > 0 else h + 1, as one add with the [0, 1] clamp
+__device__ __forceinline__ float elu_grad_f(float h) { return __builtin_amdgcn_fmed3f(h + 1.0f, 0.f, 1.f); }
 __device__ __forceinline__ float bf16_to_f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 // two fp32 -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
@@ -147,8 +153,8 @@ __global__ __launch_bounds__(256) void linear_bf16_kernel(gmi::LinearBatch batch
           const uint2 hv = *reinterpret_cast<const uint2*>((const uint16_t*)P.h + (int64_t)r * P.ldh + f);
           const float h0 = bf16_to_f((uint16_t)(hv.x & 0xFFFF)), h1 = bf16_to_f((uint16_t)(hv.x >> 16));
           const float h2 = bf16_to_f((uint16_t)(hv.y & 0xFFFF)), h3 = bf16_to_f((uint16_t)(hv.y >> 16));
-          o[0] *= h0 > 0.f ? 1.f : h0 + 1.f; o[1] *= h1 > 0.f ? 1.f : h1 + 1.f;
-          o[2] *= h2 > 0.f ? 1.f : h2 + 1.f; o[3] *= h3 > 0.f ? 1.f : h3 + 1.f;
+          o[0] *= elu_grad_f(h0); o[1] *= elu_grad_f(h1);
+          o[2] *= elu_grad_f(h2); o[3] *= elu_grad_f(h3);
           uint2 pk = make_uint2(pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]));
           *reinterpret_cast<uint2*>((uint16_t*)P.y + (int64_t)r * P.ldy + f) = pk;
         }
@@ -345,8 +351,8 @@ __global__ __launch_bounds__(128 * WRN) void linear_bf16_big_kernel(gmi::LinearB
       } else {
         const float h0 = bf16_to_f((uint16_t)(hv[it].x & 0xFFFF)), h1 = bf16_to_f((uint16_t)(hv[it].x >> 16));
         const float h2 = bf16_to_f((uint16_t)(hv[it].y & 0xFFFF)), h3 = bf16_to_f((uint16_t)(hv[it].y >> 16));
-        v.x *= h0 > 0.f ? 1.f : h0 + 1.f; v.y *= h1 > 0.f ? 1.f : h1 + 1.f;
-        v.z *= h2 > 0.f ? 1.f : h2 + 1.f; v.w *= h3 > 0.f ? 1.f : h3 + 1.f;
+        v.x *= elu_grad_f(h0); v.y *= elu_grad_f(h1);
+        v.z *= elu_grad_f(h2); v.w *= elu_grad_f(h3);
       }
       const uint2 pk = make_uint2(pack_bf16(v.x, v.y), pack_bf16(v.z, v.w));
       const int r = rbase + it * kRowsPerIter;
@@ -544,7 +550,7 @@ __global__ void linear_f32_kernel(gmi::LinearBatch batch, int rows) {
     if (f < P.F_store) ((float*)P.y)[(int64_t)r * P.ldy + f] = acc + P.bias[f];
   } else {
     const float h = ((const float*)P.h)[(int64_t)r * P.ldh + f];
-    ((float*)P.y)[(int64_t)r * P.ldy + f] = acc * (h > 0.f ? 1.f : h + 1.f);
+    ((float*)P.y)[(int64_t)r * P.ldy + f] = acc * elu_grad_f(h);
   }
 }
 
