@@ -461,11 +461,12 @@ def test_whole_iteration_bf16_matches_oracle(g, name, n_envs, minibatch, horizon
 
 
 @pytest.mark.parametrize("name,n_envs,horizon,prob_inv", [("C2", 100, 5, 4), ("C3", 257, 4, 0), ("C2", 4096, 16, 0),
-                                                          ("C2", 33, 3, 2)])
+                                                          ("C2", 33, 3, 2), ("C2", 6000, 3, 7)])
 def test_rollout_collect_equals_the_step_by_step_calls(g, name, n_envs, horizon, prob_inv):
     """One-launch experience collection against agent_act / env_step / collect_experience called per step
     (same kernels' arithmetic, same Philox counters): every array it leaves must be identical, over two
-    iterations in a row (state, episode counters and step offsets carry over), ragged last tile included."""
+    iterations in a row (state, episode counters and step offsets carry over), ragged last tile included.
+    (6000 envs: more 16-env tiles than compute units, so a workgroup takes several tiles in turn.)"""
     import dataclasses
     cfg = syn.get_config(name)
     if prob_inv:
