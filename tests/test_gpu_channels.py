@@ -167,7 +167,7 @@ def test_channel_pipeline_equals_the_direct_hand_off_bit_for_bit(g):
         for k in range(2):
             pipe.iteration_pipelined(k, **targs)
         pipe.sync_all()
-        results.append((pipe.theta.cpu().numpy().copy(), pipe.bufs[1].to_numpy()))     # slot 1 holds round 1 in both
+        results.append((pipe.theta.cpu().numpy().copy(), pipe.bufs[1].to_numpy()))     # slot 1 holds the second collection in both
         pipe.close()
     for th, buf in results[1:]:
         assert np.array_equal(th, results[0][0])
