@@ -194,10 +194,21 @@ __global__ __launch_bounds__(256) void adam_kernel(gmi::ShadowTable tab, int wri
   }
   const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (p >= tab.logstd_off) return;
+  // the moments and the parameter are fetched ahead of the partials (their latency would otherwise follow the sum's)
+  float m0 = 0.f, v0 = 0.f, w0 = 0.f;
+  if (do_update) { m0 = am[p]; v0 = av[p]; w0 = params[p]; }
   float g = 0.f;
   for (int i = 0; i < ps.n; ++i) {
     const float* q = ps.part[i] + p;
     int sidx = 0;
+    // fixed order of additions, 16 (then 8) loads in flight
+    for (; sidx + 16 <= n_split; sidx += 16) {
+      float t[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) t[u] = q[(int64_t)(sidx + u) * part_stride];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) g += t[u];
+    }
     for (; sidx + 8 <= n_split; sidx += 8) {
       float t[8];
 #pragma unroll
@@ -210,7 +221,13 @@ __global__ __launch_bounds__(256) void adam_kernel(gmi::ShadowTable tab, int wri
   g *= 1.0f / (float)ps.n;
   if (grad_out) grad_out[p] = g;
   if (!do_update) return;
-  const float w = adam_one(g, params, am, av, p, hs);
+  // same expressions as adam_one
+  const float mn = hs.b1 * m0 + (1.0f - hs.b1) * g;
+  const float vn = hs.b2 * v0 + (1.0f - hs.b2) * g * g;
+  am[p] = mn;
+  av[p] = vn;
+  const float w = w0 - hs.lr * (mn / hs.c1) / (sqrtf(vn / hs.c2) + hs.eps);
+  params[p] = w;
   if (!write_shadow) return;
   int li = 0;
   while (li + 1 < tab.n && p >= tab.l[li + 1].w_off) ++li;
