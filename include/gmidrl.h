@@ -193,7 +193,9 @@ typedef struct {
 /* Experience buffer: one array per type of data (the per-type "channels" of Section 4.2), time
  * major so that one step's write is one contiguous slab per array.  The binding owns a small
  * workspace on the device (partial sums of the advantage normalisation; 8 index arrays of T * N
- * int32 for the minibatch shuffles of ppo_update), freed by gmi_buffer_destroy. */
+ * int32 for the minibatch shuffles of ppo_update; if obs_dim is not a multiple of 4 or obs is not
+ * 16-byte aligned, T * N rows of obs_dim rounded up to a multiple of 32 two-byte elements, into which
+ * ppo_update copies the observations it is called on), freed by gmi_buffer_destroy. */
 int gmi_buffer_bind(gmi_t gmi, const gmi_buffer_desc* desc, gmi_buffer_t* out);
 int gmi_buffer_destroy(gmi_buffer_t buf);
 

@@ -164,8 +164,20 @@ void fill_chain_emit(const ModelLayout& L, ChainEmit* ce) {
 // Gather of the minibatch rows idx[0..rows) of buffer b + forward + loss + input gradients.
 // Leaves m->h, m->dz ready for the weight-gradient launch and one row of statistics / log_std partials per
 // tile in m->stat_part (*n_stat_rows rows, the layout of the loss kernel's per-workgroup rows).  GMI_ERR_UNSUPPORTED (no message) if no kernel is compiled for this shape.
+int prepare_obs16(gmi_instance* g, gmi_model* m, gmi_buffer* b, bool* ready) {
+  const ModelLayout& L = m->L;
+  *ready = false;
+  if (!b->obs16 || g->fusion < 1 || L.dtype != GMI_DTYPE_BF16 || L.sh_chain_bytes == 0 || L.act_dim > 32 ||
+      compiled_gmax(L) == 0)
+    return GMI_OK;
+  const int64_t B = (int64_t)b->d.horizon * b->d.n_envs;
+  const int rc = launch_gather_to(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, nullptr, (int)B, nullptr, b->obs16);
+  if (rc == GMI_OK) *ready = true;
+  return rc;
+}
+
 int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx, int rows,
-                       int* n_stat_rows) {
+                       int* n_stat_rows, bool obs16_ready) {
   const ModelLayout& L = m->L;
   if (L.dtype != GMI_DTYPE_BF16 || L.sh_chain_bytes == 0 || L.act_dim > 32) return GMI_ERR_UNSUPPORTED;
   ChainArgs a;
@@ -183,6 +195,8 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_p
   a.b_obs = b->d.obs; a.b_act = b->d.act; a.b_logp = b->d.logp; a.b_adv = b->d.adv; a.b_ret = b->d.ret;
   a.n_envs = b->d.n_envs; a.ld_envs = b->d.ld_envs; a.obs_dim = L.obs_dim;
   a.x0_ready = (L.obs_dim % 4 == 0 && ((uintptr_t)b->d.obs & 15) == 0) ? 0 : 1;
+  a.x16 = b->obs16;
+  if (a.x0_ready == 1 && obs16_ready && b->obs16 && idx) a.x0_ready = 2;
   a.rows = rows; a.act_dim = L.act_dim;
   a.clip = hp->clip; a.c_v = hp->c_v;
   a.stat_part = m->stat_part;
@@ -204,14 +218,15 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_p
       flops += 2.0 * rows * (double)li.in * li.out * (l == 0 ? 1.0 : 2.0);
       bytes += 2.0 * li.in * li.out * (l == 0 ? 1.0 : 2.0);                 // bf16 weights, forward (+ transposed)
       bytes += 2.0 * rows * li.out;                                          // gradient at the layer's output
-      if (l == 0) bytes += net == 0 ? (a.x0_ready ? 2.0 : 6.0) * rows * li.in : 0.0;   // fp32 observation rows read and the bf16 copy
-                                                                              // written (once), or the bf16 copy read
+      // fp32 observation rows read and the bf16 copy written (once), or the gathered bf16 rows read, or those read
+      // from the copy of all observations and written in minibatch order
+      if (l == 0) bytes += net == 0 ? (a.x0_ready == 1 ? 2.0 : (a.x0_ready == 2 ? 4.0 : 6.0)) * rows * li.in : 0.0;
       else bytes += 2.0 * 2.0 * rows * li.in;                                // hidden activation: written, read back
     }
   }
   bytes += 4.0 * rows * (L.act_dim + 3);
   if (compiled_gmax(L) == 0) return GMI_ERR_UNSUPPORTED;
-  if (a.x0_ready) {       // unaligned observation rows: the gather kernel converts them (a lane-wise gather of 4-byte
+  if (a.x0_ready == 1) {  // unaligned observation rows: the gather kernel converts them (a lane-wise gather of 4-byte
                           // pieces at the start of the chained kernel measured slower than the separate launch)
     rc = launch_gather(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, idx, rows, nullptr);
     if (rc != GMI_OK) return rc;

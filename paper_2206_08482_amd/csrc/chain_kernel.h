@@ -188,7 +188,9 @@ struct ChainArgs {
   const float *b_obs, *b_act, *b_logp, *b_adv, *b_ret;
   int n_envs, ld_envs, obs_dim;
   int x0_ready;                                    // 1: x0 already holds the gathered rows (observation rows that cannot
-                                                   // be read as 16-byte pieces are gathered by gather_kernel beforehand)
+                                                   // be read as 16-byte pieces are gathered by gather_kernel beforehand);
+                                                   // 2: the rows are gathered from x16
+  const uint16_t* x16;                             // bf16 copy of all observations, [sample index][d[0]] (x0_ready == 2)
   int rows, act_dim;
   float clip, c_v;
   float* stat_part;                                // [tiles][kStatStride + act_dim]
@@ -732,9 +734,17 @@ __global__ __launch_bounds__(S::NW * 64) void train_chain_kernel(ChainArgs a) {
     const float* orow = a.b_obs + c.slot * a.obs_dim;
     const int O = a.obs_dim;
     uint16_t* xw = a.x0 + (int64_t)row * D.d[0] + 8 * c.hh;
-    if (a.x0_ready) {                                  // wave-uniform
+    if (a.x0_ready == 1) {                             // wave-uniform
 #pragma unroll
       for (int ks = 0; ks < D.d[0] / 16; ++ks) c.xa[ks] = *reinterpret_cast<const uint4*>(xw + 16 * ks);
+    } else if (a.x0_ready == 2) {
+      // the gather from the bf16 copy of all observations (rows of d[0] elements by sample index)
+      const uint16_t* xs = a.x16 + (int64_t)sm * D.d[0] + 8 * c.hh;
+#pragma unroll
+      for (int ks = 0; ks < D.d[0] / 16; ++ks) {
+        c.xa[ks] = *reinterpret_cast<const uint4*>(xs + 16 * ks);
+        if (!S::FWD && c.net == 0) *reinterpret_cast<uint4*>(xw + 16 * ks) = c.xa[ks];
+      }
     } else {
 #pragma unroll
       for (int ks = 0; ks < D.d[0] / 16; ++ks) {

@@ -132,11 +132,17 @@ extern "C" int gmi_buffer_bind(gmi_t g, const gmi_buffer_desc* d, gmi_buffer_t* 
   b->n_part = (d->n_envs + 255) / 256;
   b->part = nullptr;
   b->perm = nullptr;
+  b->obs16 = nullptr;
   if (b->n_part > 0) {
     hipError_t e = hipMalloc(&b->part, sizeof(double) * 2 * (size_t)b->n_part);
     if (e == hipSuccess && d->horizon > 0) {
       e = hipMalloc(&b->perm, sizeof(int32_t) * (size_t)gmi::kPermEpochs * d->horizon * d->n_envs);
       if (e != hipSuccess) (void)hipFree(b->part);
+      // observation rows that 16-byte loads cannot read: room for their bf16 copy (the trainer's chained kernel)
+      if (e == hipSuccess && (d->obs_dim % 4 != 0 || ((uintptr_t)d->obs & 15) != 0)) {
+        e = hipMalloc(&b->obs16, sizeof(uint16_t) * (size_t)d->horizon * d->n_envs * gmi::pad32(d->obs_dim));
+        if (e != hipSuccess) { (void)hipFree(b->part); (void)hipFree(b->perm); }
+      }
     }
     if (e != hipSuccess) {
       delete b;
@@ -151,6 +157,7 @@ extern "C" int gmi_buffer_destroy(gmi_buffer_t b) {
   if (!valid(b)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_buffer_destroy: bad handle");
   if (b->part) (void)hipFree(b->part);
   if (b->perm) (void)hipFree(b->perm);
+  if (b->obs16) (void)hipFree(b->obs16);
   b->magic = 0;
   delete b;
   return GMI_OK;

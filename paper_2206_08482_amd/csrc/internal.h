@@ -188,6 +188,8 @@ struct gmi_buffer {
   double* part;     // dev [n_part, 2] partial sums for normalisation
   int n_part;
   int32_t* perm;    // dev [kPermEpochs][horizon * n_envs] minibatch shuffles of up to kPermEpochs epochs at once
+  uint16_t* obs16;  // dev [horizon * n_envs][pad32(obs_dim)] bf16 copy of the observations by sample index, made at
+                    // the start of an update; only for observation rows that 16-byte loads cannot read (else NULL)
 };
 
 static inline bool valid(gmi_t g) { return g && g->magic == gmi::kMagicInstance; }
@@ -255,6 +257,9 @@ static inline size_t elem_size(int dtype) { return dtype == GMI_DTYPE_BF16 ? 2 :
 // Sample s of a buffer lives at slot (s / n_envs) * ld_envs + s % n_envs.
 int launch_gather(gmi_instance* g, gmi_model* m, const float* obs, int n_envs, int ld_envs,
                   const int32_t* idx, int rows, const gmi_buffer_desc* extras);
+// The same with the rows written to x_out (of the model's activation type) instead of m->x0.
+int launch_gather_to(gmi_instance* g, gmi_model* m, const float* obs, int n_envs, int ld_envs,
+                     const int32_t* idx, int rows, const gmi_buffer_desc* extras, void* x_out);
 
 // Runs both nets (or only the value net) on the rows staged in m->x0; keeps hidden activations in
 // m->h[net][l]; writes m->mu [rows, A] and m->val [rows].
@@ -290,8 +295,12 @@ void fill_chain_emit(const ModelLayout& L, ChainEmit* ce);
 // Forward pass of n_rows observation rows through the forward-only chained kernel: policy means into mu (NULL: value
 // net only) and values into val.  GMI_ERR_UNSUPPORTED (no message) if no such kernel is compiled for the shape.
 int launch_forward_chain(gmi_instance* g, gmi_model* m, const float* obs, int n_rows, float* mu, float* val);
+// obs16_ready: b->obs16 holds the bf16 copy of the buffer's present observations (prepare_obs16).
 int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx, int rows,
-                       int* n_stat_rows);
+                       int* n_stat_rows, bool obs16_ready);
+// Before the minibatches of an update: converts all observations of the buffer into b->obs16 if the chained kernel
+// will run and cannot read the fp32 rows itself.  *ready = whether it did.
+int prepare_obs16(gmi_instance* g, gmi_model* m, gmi_buffer* b, bool* ready);
 
 }  // namespace gmi
 

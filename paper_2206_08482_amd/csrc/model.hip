@@ -184,6 +184,11 @@ namespace gmi {
 
 int launch_gather(gmi_instance* g, gmi_model* m, const float* obs, int n_envs, int ld_envs,
                   const int32_t* idx, int rows, const gmi_buffer_desc* ex) {
+  return launch_gather_to(g, m, obs, n_envs, ld_envs, idx, rows, ex, m->x0);
+}
+
+int launch_gather_to(gmi_instance* g, gmi_model* m, const float* obs, int n_envs, int ld_envs,
+                     const int32_t* idx, int rows, const gmi_buffer_desc* ex, void* x_out) {
   if (rows <= 0) return GMI_OK;
   ProfScope ps(g, kClsGather);
   const int O = m->L.obs_dim, A = m->L.act_dim, o_pad = gmi::pad32(O);
@@ -196,7 +201,7 @@ int launch_gather(gmi_instance* g, gmi_model* m, const float* obs, int n_envs, i
   const float* e_adv = ex ? ex->adv : nullptr;
   const float* e_ret = ex ? ex->ret : nullptr;
 #define GMI_GATHER(T, V)                                                                                     \
-  ps.launch(gather_kernel<T, V>, dim3(grid), dim3(256), 0, obs, n_envs, ld_envs, O, o_pad, idx, rows, (T*)m->x0, A, \
+  ps.launch(gather_kernel<T, V>, dim3(grid), dim3(256), 0, obs, n_envs, ld_envs, O, o_pad, idx, rows, (T*)x_out, A, \
             e_act, e_logp, e_adv, e_ret, m->mb_act, m->mb_logp, m->mb_adv, m->mb_ret, tpr)
   if (m->L.dtype == GMI_DTYPE_BF16) {
     if (vec) GMI_GATHER(uint16_t, true); else GMI_GATHER(uint16_t, false);

@@ -437,7 +437,8 @@ int layers_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hpar
 // Forward + loss (+ backward products) of the `rows` samples idx[0..rows) of the buffer.
 // Leaves gradient partials in m->grad_part / m->stat_part.  Returns the split count through n_split.
 int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx,
-                   int rows, bool want_grad, int* n_split_out, int* n_loss_blocks_out, bool allow_fused = true) {
+                   int rows, bool want_grad, int* n_split_out, int* n_loss_blocks_out, bool allow_fused = true,
+                   bool obs16_ready = false) {
   const ModelLayout& L = m->L;
   const bool bf = L.dtype == GMI_DTYPE_BF16;
   int rc = GMI_ERR_UNSUPPORTED;
@@ -448,7 +449,7 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
   }
   if (rc == GMI_ERR_UNSUPPORTED && g->fusion >= 1 && want_grad && bf) {
     // register-chained kernel (gather + forward + loss + input gradients in one launch) where this shape has one
-    rc = gmi::launch_train_chain(g, m, b, hp, idx, rows, n_loss_blocks_out);
+    rc = gmi::launch_train_chain(g, m, b, hp, idx, rows, n_loss_blocks_out, obs16_ready);
   }
   if (rc == GMI_ERR_UNSUPPORTED) rc = layers_pass(g, m, b, hp, idx, rows, want_grad, n_loss_blocks_out);
   if (rc != GMI_OK || !want_grad) return rc;
@@ -537,6 +538,9 @@ extern "C" int ppo_update(gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_ppo_
     GMI_FAIL(GMI_ERR_BAD_SHAPE, "ppo_update: minibatch %d exceeds the binding's max_rows %d", hp->minibatch, m->max_rows);
   const int nmb = (int)(B / hp->minibatch);
   uint32_t k = hp->adam_step0;
+  bool obs16 = false;
+  rc = gmi::prepare_obs16(g, m, b, &obs16);
+  if (rc != GMI_OK) return rc;
   for (int e = 0; e < hp->epochs; ++e) {
     // the shuffles of up to kPermEpochs epochs in one launch (each launch of this small kernel is mostly latency)
     const int32_t* perm = b->perm + (int64_t)(e % gmi::kPermEpochs) * B;
@@ -547,7 +551,7 @@ extern "C" int ppo_update(gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_ppo_
     }
     for (int j = 0; j < nmb; ++j) {
       int n_split = 1, nlb = 1;
-      rc = minibatch_pass(g, m, b, hp, perm + (int64_t)j * hp->minibatch, hp->minibatch, true, &n_split, &nlb);
+      rc = minibatch_pass(g, m, b, hp, perm + (int64_t)j * hp->minibatch, hp->minibatch, true, &n_split, &nlb, true, obs16);
       if (rc != GMI_OK) return rc;
       ++k;
       rc = launch_adam(g, &m, 1, n_split, nlb, hp, hp->minibatch, k,
@@ -599,6 +603,11 @@ extern "C" int ppo_update_group(const gmi_t* gs, const gmi_model_t* ms, const gm
   for (int i = 0; i < n; ++i) models[i] = ms[i];
   // instance 0's stream also reads what the other instances' earlier calls left (e.g. their buffers are
   // theirs alone, but the shared parameters were last written on stream 0): nothing to order before the loop.
+  bool obs16[kMaxGroup];
+  for (int i = 0; i < n; ++i) {
+    rc = gmi::prepare_obs16(gs[i], ms[i], bs[i], &obs16[i]);
+    if (rc != GMI_OK) return rc;
+  }
   for (int e = 0; e < hp->epochs; ++e) {
     if (e % gmi::kPermEpochs == 0) {
       const int ne = hp->epochs - e < gmi::kPermEpochs ? hp->epochs - e : gmi::kPermEpochs;
@@ -613,7 +622,7 @@ extern "C" int ppo_update_group(const gmi_t* gs, const gmi_model_t* ms, const gm
       for (int i = 0; i < n; ++i) {
         int ns_i = 1, nlb_i = 1;
         rc = minibatch_pass(gs[i], ms[i], bs[i], hp, bs[i]->perm + perm_off + (int64_t)j * hp->minibatch, hp->minibatch, true,
-                            &ns_i, &nlb_i, false);
+                            &ns_i, &nlb_i, false, obs16[i]);
         if (rc != GMI_OK) return rc;
         if (i == 0) { n_split = ns_i; nlb = nlb_i; }
         // replica i's partials are complete: let instance 0 see them

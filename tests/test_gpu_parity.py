@@ -423,7 +423,7 @@ def test_update_over_more_epochs_than_one_shuffle_launch_covers(g):
 
 
 @pytest.mark.parametrize("name,n_envs,minibatch,horizon", [("C2", 512, 2048, 8), ("C3", 256, 1024, 8),
-                                                           ("C4", 320, 1280, 4)])
+                                                           ("C4", 320, 1280, 4), ("FC", 300, 600, 4)])
 @pytest.mark.parametrize("fused_rollout", [True, False])
 def test_whole_iteration_bf16_matches_oracle(g, name, n_envs, minibatch, horizon, fused_rollout):
     cfg = syn.get_config(name)
