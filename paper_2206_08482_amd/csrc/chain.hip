@@ -77,14 +77,17 @@ const part_fn kParts[gmi::kChainParts] = {gmi::launch_chain_part0, gmi::launch_c
                                           gmi::launch_chain_part3, gmi::launch_chain_part4, gmi::launch_chain_part5};
 const part_fn kFwdParts[gmi::kChainFwdParts] = {gmi::launch_chain_fwd_part0, gmi::launch_chain_fwd_part1};
 
-// The largest group of the kernel compiled for this model's shape; 0 if there is none.
-int compiled_gmax(const ModelLayout& L) {
+// What the trainer kernel compiled for this model's shape answers to the probe: its largest group, plus 256 if it
+// can gather its rows from the bf16 copy of all observations; 0 if there is none.
+int compiled_probe(const ModelLayout& L) {
   ChainArgs none = {};
-  int gmax = 0;
+  int v = 0;
   for (int p = 0; p < gmi::kChainParts; ++p)
-    if (kParts[p](nullptr, L, none, 0, &gmax, 0.0, 0.0) == GMI_OK) return gmax;
+    if (kParts[p](nullptr, L, none, 0, &v, 0.0, 0.0) == GMI_OK) return v;
   return 0;
 }
+int compiled_gmax(const ModelLayout& L) { return compiled_probe(L) & 255; }
+bool compiled_x16(const ModelLayout& L) { return (compiled_probe(L) & 256) != 0; }
 
 }  // namespace
 
@@ -168,7 +171,7 @@ int prepare_obs16(gmi_instance* g, gmi_model* m, gmi_buffer* b, bool* ready) {
   const ModelLayout& L = m->L;
   *ready = false;
   if (!b->obs16 || g->fusion < 1 || L.dtype != GMI_DTYPE_BF16 || L.sh_chain_bytes == 0 || L.act_dim > 32 ||
-      compiled_gmax(L) == 0)
+      !compiled_x16(L))
     return GMI_OK;
   const int64_t B = (int64_t)b->d.horizon * b->d.n_envs;
   const int rc = launch_gather_to(g, m, b->d.obs, b->d.n_envs, b->d.ld_envs, nullptr, (int)B, nullptr, b->obs16);
@@ -196,7 +199,7 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_p
   a.n_envs = b->d.n_envs; a.ld_envs = b->d.ld_envs; a.obs_dim = L.obs_dim;
   a.x0_ready = (L.obs_dim % 4 == 0 && ((uintptr_t)b->d.obs & 15) == 0) ? 0 : 1;
   a.x16 = b->obs16;
-  if (a.x0_ready == 1 && obs16_ready && b->obs16 && idx) a.x0_ready = 2;
+  if (a.x0_ready == 1 && obs16_ready && b->obs16 && idx && compiled_x16(L)) a.x0_ready = 2;
   a.rows = rows; a.act_dim = L.act_dim;
   a.clip = hp->clip; a.c_v = hp->c_v;
   a.stat_part = m->stat_part;

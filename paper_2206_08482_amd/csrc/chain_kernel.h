@@ -210,14 +210,18 @@ constexpr int kScrStride = 272;                    // bytes per row of a wave's 
 constexpr int kScrBytes = 32 * kScrStride;
 
 // A compile-time description of one model shape: NW waves per workgroup, DEPTH chunks of weights in flight,
-// GMAX tiles in the largest group, DEFER = 1 if epilogues run inside the next group's products, HFETCH and FWD (see
+// GMAX tiles in the largest group, DEFER = 1 if epilogues run inside the next group's products, HFETCH and MODE (see
 // below), then the padded widths d[0..nl].
-template <int NW_, int DEPTH_, int GMAX_, int DEFER_, int HFETCH_, int FWD_, int... DIMS>
+template <int NW_, int DEPTH_, int GMAX_, int DEFER_, int HFETCH_, int MODE_, int... DIMS>
 struct ChainShape {
   static constexpr int NW = NW_, NT = NW_ * 64, DEPTH = DEPTH_, GMAX = GMAX_;
   static constexpr bool DEFER = DEFER_ != 0;
-  static constexpr bool FWD = FWD_ != 0;      // inference: the forward segments only, nothing stored for the weight gradients,
+  static constexpr bool FWD = MODE_ == 1;     // inference: the forward segments only, nothing stored for the weight gradients,
                                               // the head's results written out instead of the loss
+  static constexpr bool X16 = MODE_ == 2;     // trainer that can also gather its rows from the bf16 copy of all observations
+                                              // (x0_ready == 2; only the shapes of models with unaligned observation rows
+                                              // carry that code: its mere presence cost the 400-wide shapes 8 %)
+  static_assert(MODE_ >= 0 && MODE_ <= 2, "MODE: 0 trainer, 1 forward-only, 2 trainer with the bf16-copy gather");
   static constexpr int HFETCH = HFETCH_;      // without DEFER: a group fetches its stored activations this many chunks before its end
   static_assert(GMAX_ == 4 || GMAX_ == 2, "groups of at most 4 or 2 tiles");
   static constexpr int NL = (int)sizeof...(DIMS) - 1;
@@ -737,13 +741,15 @@ __global__ __launch_bounds__(S::NW * 64) void train_chain_kernel(ChainArgs a) {
     if (a.x0_ready == 1) {                             // wave-uniform
 #pragma unroll
       for (int ks = 0; ks < D.d[0] / 16; ++ks) c.xa[ks] = *reinterpret_cast<const uint4*>(xw + 16 * ks);
-    } else if (a.x0_ready == 2) {
+    } else if (S::X16 && a.x0_ready == 2) {
       // the gather from the bf16 copy of all observations (rows of d[0] elements by sample index)
-      const uint16_t* xs = a.x16 + (int64_t)sm * D.d[0] + 8 * c.hh;
+      if constexpr (S::X16) {
+        const uint16_t* xs = a.x16 + (int64_t)sm * D.d[0] + 8 * c.hh;
 #pragma unroll
-      for (int ks = 0; ks < D.d[0] / 16; ++ks) {
-        c.xa[ks] = *reinterpret_cast<const uint4*>(xs + 16 * ks);
-        if (!S::FWD && c.net == 0) *reinterpret_cast<uint4*>(xw + 16 * ks) = c.xa[ks];
+        for (int ks = 0; ks < D.d[0] / 16; ++ks) {
+          c.xa[ks] = *reinterpret_cast<const uint4*>(xs + 16 * ks);
+          if (c.net == 0) *reinterpret_cast<uint4*>(xw + 16 * ks) = c.xa[ks];
+        }
       }
     } else {
 #pragma unroll
@@ -803,7 +809,8 @@ int launch_shape(gmi_instance* g, const ChainArgs& a, int rows, int* tiles_out, 
 namespace gmi {
 // One function per compiled shape (chain_p<k>.hip): launches the kernel if the model has exactly that shape,
 // GMI_ERR_UNSUPPORTED otherwise.  rows == 0 only asks whether the shape matches (*tiles_out = the
-// shape's largest group, which the layout of the weight stream depends on).
+// shape's largest group, which the layout of the weight stream depends on, plus 256 for a trainer shape
+// with the bf16-copy gather).
 constexpr int kChainParts = 6;
 #define GMI_CHAIN_PART_DECL(k)                                                                              \
   int launch_chain_part##k(gmi_instance* g, const ModelLayout& L, const gmi_chain::ChainArgs& a, int rows, \
@@ -829,7 +836,7 @@ GMI_CHAIN_FWD_DECL(0); GMI_CHAIN_FWD_DECL(1);
   GMI_CHAIN_PART_DECL(k) {                                                                        \
     using S = gmi_chain::ChainShape<__VA_ARGS__>;                                                 \
     if (!gmi_chain::shape_matches<S>(L)) return GMI_ERR_UNSUPPORTED;                              \
-    if (rows == 0) { *tiles_out = S::GMAX; return GMI_OK; }                                       \
+    if (rows == 0) { *tiles_out = S::GMAX | (S::X16 ? 256 : 0); return GMI_OK; }                  \
     return gmi_chain::launch_shape<S>(g, a, rows, tiles_out, flops, bytes);                       \
   }
 }  // namespace gmi

@@ -3,5 +3,5 @@
 #include "chain_kernel.h"
 
 namespace gmi {
-GMI_CHAIN_PART_DEFINE(2, 4, 3, 4, 0, 1, 0, 224, 512, 512, 256, 128, 32)
+GMI_CHAIN_PART_DEFINE(2, 4, 3, 4, 0, 1, 2, 224, 512, 512, 256, 128, 32)
 }  // namespace gmi

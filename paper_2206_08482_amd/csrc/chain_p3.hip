@@ -3,5 +3,5 @@
 #include "chain_kernel.h"
 
 namespace gmi {
-GMI_CHAIN_PART_DEFINE(3, 8, 3, 4, 0, 1, 0, 32, 256, 128, 64, 32)
+GMI_CHAIN_PART_DEFINE(3, 8, 3, 4, 0, 1, 2, 32, 256, 128, 64, 32)
 }  // namespace gmi

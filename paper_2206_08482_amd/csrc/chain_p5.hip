@@ -3,5 +3,5 @@
 #include "chain_kernel.h"
 
 namespace gmi {
-GMI_CHAIN_PART_DEFINE(5, 4, 2, 4, 0, 1, 0, 224, 512, 512, 512, 256, 32)
+GMI_CHAIN_PART_DEFINE(5, 4, 2, 4, 0, 1, 2, 224, 512, 512, 512, 256, 32)
 }  // namespace gmi
