@@ -15,6 +15,7 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 typedef float float2v __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
 
@@ -413,6 +414,13 @@ struct WsShape {
     return n;
   }
   static constexpr int n_frags() { return frag_base(NL) > 0 ? frag_base(NL) : 1; }
+  // the 16-env form (16x16x32 products): 16-feature tiles of one wave, and its register fragments before layer l
+  static constexpr int max_tiles16(int l) { return (dim(l + 1) / 16 + 3) / 4; }
+  static constexpr int frag_base16(int l) {
+    int n = 0;
+    for (int i = 0; i < l && i < LDSL; ++i) n += max_tiles16(i) * (dim(i) / 32);
+    return n;
+  }
   // bf16 elements of the LDS-resident layers before layer l / of all of them (one net)
   static constexpr int lds_base(int l) {
     int n = 0;
@@ -504,6 +512,91 @@ __device__ __forceinline__ void ws_layer(const bf16x8* wreg, const uint16_t* s_w
   }
 }
 
+// ---- The 16-env form of the weight-stationary nets (a workgroup that owns 16 envs): 16x16x32 products on
+// 16-feature tiles, so that no row of a tile is padding -- half the matrix-instruction passes and half the epilogue
+// arithmetic of the 32-row tiles.  The sums are bit-identical to those of the 32x32x16 products over the same k order
+// (checked on the device over 256000 outputs of mixed magnitudes before this form was written), so the rollout stays
+// bit-identical to the per-step kernels.
+// Element offset, inside a layer's fragment-major array, of the 8 consecutive k values from k0 (a multiple of 8) of
+// feature f: block (f / 32, k0 / 16), lane f % 32 + 32 * ((k0 / 8) % 2) of the 32x32x16 layout.
+__device__ __forceinline__ int wfrag16_off(int f, int k0, int nks16) {
+  return ((((f >> 5) * nks16 + (k0 >> 4)) * 64) + (f & 31) + 32 * ((k0 >> 3) & 1)) * 8;
+}
+
+template <class WS, int L>
+__device__ __forceinline__ void ws_load16(bf16x8* wreg, const FusedNet& N, int wave, int lane) {
+  if constexpr (L < WS::NL && L < WS::lds_from) {
+    constexpr int nks = WS::dim(L) / 32, nks16 = WS::dim(L) / 16, nft = WS::dim(L + 1) / 16, base = WS::frag_base16(L);
+    static_assert(WS::frag_base16(L + 1) <= WS::n_frags(), "the 16-env form fits the register fragments of the 32-env form");
+#pragma unroll
+    for (int i = 0; i < WS::max_tiles16(L); ++i) {
+      const int tile = wave + 4 * i;
+      const int tc = tile < nft ? tile : nft - 1;       // a wave without an i-th tile loads a valid block it never uses
+      const int f = tc * 16 + (lane & 15);
+#pragma unroll
+      for (int ks = 0; ks < nks; ++ks)
+        wreg[base + i * nks + ks] =
+            *reinterpret_cast<const bf16x8*>(N.w[L] + wfrag16_off(f, ks * 32 + (lane >> 4) * 8, nks16));
+    }
+    ws_load16<WS, L + 1>(wreg, N, wave, lane);
+  }
+}
+
+template <class WS, int L, int EPI>
+__device__ __forceinline__ void ws_layer16(const bf16x8* wreg, const uint16_t* s_w, const float* s_bias, const uint16_t* s_in,
+                                           int stride_in, uint16_t* s_out, int stride_out, float* s_head, int head_stride,
+                                           int out_store, int wave, int lane) {
+  constexpr int nks = WS::dim(L) / 32, nks16 = WS::dim(L) / 16, nft = WS::dim(L + 1) / 16, base = WS::frag_base16(L);
+  const int q = lane >> 4, n = lane & 15;               // lane (n, q): env n, k values 8 q .. + 7 of a k step, features 4 q .. + 3 of a tile
+  const uint16_t* xrow = s_in + n * stride_in + q * 8;
+#pragma unroll
+  for (int i = 0; i < WS::max_tiles16(L); ++i) {
+    const int tile = wave + 4 * i;
+    if (tile < nft) {                                   // wave-uniform
+      floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < nks; ++ks) {
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(xrow + ks * 32);
+        bf16x8 w;
+        if constexpr (L < WS::lds_from) w = wreg[base + i * nks + ks];
+        else w = *reinterpret_cast<const bf16x8*>(s_w + WS::lds_base(L) + wfrag16_off(tile * 16 + n, ks * 32 + q * 8, nks16));
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, b, acc, 0, 0, 0);
+      }
+      const int f = tile * 16 + 4 * q;
+      const float4 bv = *reinterpret_cast<const float4*>(s_bias + f);
+      const float o0 = acc[0] + bv.x, o1 = acc[1] + bv.y, o2 = acc[2] + bv.z, o3 = acc[3] + bv.w;
+      if (EPI == kFEpiElu) {
+        *reinterpret_cast<uint2*>(&s_out[n * stride_out + f]) =
+            make_uint2(pack_bf16(elu_f(o0), elu_f(o1)), pack_bf16(elu_f(o2), elu_f(o3)));
+      } else {
+        float* d = s_head + n * head_stride + f;
+        if (f + 0 < out_store) d[0] = o0;
+        if (f + 1 < out_store) d[1] = o1;
+        if (f + 2 < out_store) d[2] = o2;
+        if (f + 3 < out_store) d[3] = o3;
+      }
+    }
+  }
+}
+
+template <class WS, int L>
+__device__ __forceinline__ void ws_net16(const bf16x8* wreg, const uint16_t* s_w, const FusedNet& N, const float* s_nb,
+                                         const uint16_t* in, int stride_in, uint16_t* s_a, uint16_t* s_b, int stride_h,
+                                         float* s_head, int head_stride, bool run, int wave, int lane) {
+  if constexpr (L < WS::NL - 1) {
+    uint16_t* out = (L & 1) ? s_b : s_a;
+    if (run)
+      ws_layer16<WS, L, kFEpiElu>(wreg, s_w, s_nb + N.bias_off[L], in, stride_in, out, stride_h, nullptr, 0, 0, wave, lane);
+    __syncthreads();
+    ws_net16<WS, L + 1>(wreg, s_w, N, s_nb, out, stride_h, s_a, s_b, stride_h, s_head, head_stride, run, wave, lane);
+  } else {
+    if (run)
+      ws_layer16<WS, L, kFEpiHead>(wreg, s_w, s_nb + N.bias_off[L], in, stride_in, nullptr, 0, s_head, head_stride,
+                                   N.out_store, wave, lane);
+    __syncthreads();
+  }
+}
+
 // All layers of one net from layer L on, hidden activations ping-ponging between s_a and s_b as in the
 // streaming form; every layer ends with a workgroup barrier.
 template <class WS, int L, int RT>
@@ -562,7 +655,8 @@ __device__ __forceinline__ void draw_items(const RolloutArgs& a, float4* dst, ui
 // uses all 8 waves.
 // WS: a WsShape whose widths the model has (weights held in registers for the whole launch), or void (weights
 // streamed from L2 at every step).
-template <int RT, class WS = void>
+// R16: the 16-env form of the weight-stationary nets (rows_per_wg == 16).
+template <int RT, class WS = void, bool R16 = false>
 __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   constexpr int R = RT * 32;
   constexpr int NT = 512;
@@ -628,7 +722,8 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   bf16x8 wreg[WsFrags<WS>::value];
   const uint16_t* s_w = s_wl;
   if constexpr (kStationary) {
-    ws_load<WS, 0>(wreg, N, wave4, tid & 63);
+    if constexpr (R16) ws_load16<WS, 0>(wreg, N, wave4, tid & 63);
+    else ws_load<WS, 0>(wreg, N, wave4, tid & 63);
     ws_stage<WS, 0>(s_wl, a.net[0], tid, NT);
     ws_stage<WS, 0>(s_wl + WS::lds_elems(), a.net[1], tid, NT);
     s_w = s_wl + (half ? WS::lds_elems() : 0);
@@ -664,7 +759,10 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
     GMI_RT_MARK(0);
     GMI_RT_MARK(1);
     if constexpr (kStationary) {
-      ws_net<WS, 0, RT>(wreg, s_w, N, s_nb, s_x0, stride_x0, s_a, s_b, stride_h, s_head, head_stride, run, wave4, tid & 63);
+      if constexpr (R16)
+        ws_net16<WS, 0>(wreg, s_w, N, s_nb, s_x0, stride_x0, s_a, s_b, stride_h, s_head, head_stride, run, wave4, tid & 63);
+      else
+        ws_net<WS, 0, RT>(wreg, s_w, N, s_nb, s_x0, stride_x0, s_a, s_b, stride_h, s_head, head_stride, run, wave4, tid & 63);
     } else {
       const uint16_t* in = s_x0;
       int stride_in = stride_x0;
@@ -1309,7 +1407,10 @@ extern "C" int rollout_collect(gmi_t g, gmi_model_t m, gmi_env_t env, gmi_buffer
   int variant = R == 64 ? 1 : 0;
   if (ws_matches<WsAnt>(L)) { kfn = R == 64 ? rollout_fused_kernel<2, WsAnt> : rollout_fused_kernel<1, WsAnt>; variant += 2; }
   else if (ws_matches<WsSmallObs>(L)) { kfn = R == 64 ? rollout_fused_kernel<2, WsSmallObs> : rollout_fused_kernel<1, WsSmallObs>; variant += 4; }
-  static bool attr_set[6] = {false, false, false, false, false, false};
+  // 16 envs per workgroup: the weight-stationary nets on 16-row products
+  if (rows_per_wg == 16 && variant == 2) { kfn = rollout_fused_kernel<1, WsAnt, true>; variant = 6; }
+  else if (rows_per_wg == 16 && variant == 4) { kfn = rollout_fused_kernel<1, WsSmallObs, true>; variant = 7; }
+  static bool attr_set[8] = {false, false, false, false, false, false, false, false};
   if (!attr_set[variant]) {
     GMI_HIP(hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
     attr_set[variant] = true;
