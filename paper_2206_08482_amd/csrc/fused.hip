@@ -903,11 +903,22 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
     }
     // the new state, in fp32 for the simulator and the stores and in bf16 for the next step's nets (one pass and
     // one barrier instead of two)
-    for (int idx = tid; idx < Rv * a.obs_pad; idx += NT) {
-      const int r = idx / a.obs_pad, k = idx - r * a.obs_pad;
-      const float v = (k < O && r0 + r < a.n) ? s_next[r * o4 + k] : 0.f;
-      if (k < O) s_in[r * OA + k] = v;
-      s_x0[r * stride_x0 + k] = (uint16_t)(pack_bf16(v, 0.f) & 0xFFFFu);
+    if (a.obs_vec) {            // four elements per thread (O, O + A and the padded width are multiples of 4)
+      const int p4 = a.obs_pad >> 2;
+      for (int idx = tid; idx < Rv * p4; idx += NT) {
+        const int r = idx / p4, k = 4 * (idx - r * p4);
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k < O && r0 + r < a.n) v = *reinterpret_cast<const float4*>(s_next + r * o4 + k);
+        if (k < O) *reinterpret_cast<float4*>(s_in + r * OA + k) = v;
+        *reinterpret_cast<uint2*>(s_x0 + r * stride_x0 + k) = make_uint2(pack_bf16(v.x, v.y), pack_bf16(v.z, v.w));
+      }
+    } else {
+      for (int idx = tid; idx < Rv * a.obs_pad; idx += NT) {
+        const int r = idx / a.obs_pad, k = idx - r * a.obs_pad;
+        const float v = (k < O && r0 + r < a.n) ? s_next[r * o4 + k] : 0.f;
+        if (k < O) s_in[r * OA + k] = v;
+        s_x0[r * stride_x0 + k] = (uint16_t)(pack_bf16(v, 0.f) & 0xFFFFu);
+      }
     }
     __syncthreads();
     GMI_RT_MARK(7);
