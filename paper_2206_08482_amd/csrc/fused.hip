@@ -886,9 +886,11 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
     GMI_RT_MARK(5);
     __syncthreads();
     GMI_RT_MARK(6);
-    if (tid < Rv && r0 + tid < a.n) {
+    // the reward on the last wave (the state update below starts with the first threads)
+    const int rt = tid - (NT - 64);
+    if (rt >= 0 && rt < Rv && r0 + rt < a.n) {
       // same order of additions as one by one, eight LDS reads in flight
-      const float* q = s_part + tid * nbo;
+      const float* q = s_part + rt * nbo;
       float sum = 0.f;
       int j = 0;
       for (; j + 8 <= nbo; j += 8) {
@@ -899,7 +901,7 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
         for (int u = 0; u < 8; ++u) sum += t8[u];
       }
       for (; j < nbo; ++j) sum += q[j];
-      a.b_rew[slot0 + tid] = -a.reward_scale * sum;
+      a.b_rew[slot0 + rt] = -a.reward_scale * sum;
     }
     // the new state, in fp32 for the simulator and the stores and in bf16 for the next step's nets (one pass and
     // one barrier instead of two)
