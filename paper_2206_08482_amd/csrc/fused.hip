@@ -524,6 +524,89 @@ __device__ __forceinline__ int wfrag16_off(int f, int k0, int nks16) {
   return ((((f >> 5) * nks16 + (k0 >> 4)) * 64) + (f & 31) + 32 * ((k0 >> 3) & 1)) * 8;
 }
 
+// The streaming layer (fused_layer) for a 16-env tile: the same 32-feature tiles, 64-wide k chunks and ring of 4
+// register buffers, but every chunk's weights fetched as the operands of 16x16x32 products (two 16-feature halves x
+// two k steps of 32, from the same fragment-major copy) -- half the instruction passes and half the epilogue
+// arithmetic; k runs in the same order, so the sums are those of fused_layer bit for bit.
+template <int EPI>
+__device__ __forceinline__ void fused_layer16(const uint16_t* __restrict__ W, const float* s_bias, int in_pad, int out_pad,
+                                              const uint16_t* s_in, int stride_in, uint16_t* s_out, int stride_out,
+                                              float* s_head, int head_stride, int out_store, int wave) {
+  const int lane = threadIdx.x & 63, q = lane >> 4, n = lane & 15;
+  const int n_ft = out_pad >> 5;
+  const int n_my = (n_ft - wave + 3) >> 2;                 // tiles wave, wave+4, ...
+  const int nchunk = (in_pad + 63) >> 6;
+  const int nq = n_my > 0 ? n_my * nchunk : 0;
+  const int nks16 = in_pad >> 4;
+  floatx4 acc[2];
+  bf16x8 A0[4], A1[4], A2[4], A3[4];
+
+  auto load_chunk = [&](bf16x8* A, int qq) {
+    if (qq >= nq) return;
+    const int tile = qq / nchunk, ch = qq - tile * nchunk;
+#pragma unroll
+    for (int fh = 0; fh < 2; ++fh)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        // a k step past the ragged end repeats the last one (never multiplied)
+        const int k0 = min(ch * 64 + ks * 32, in_pad - 32);
+        A[fh * 2 + ks] = *reinterpret_cast<const bf16x8*>(W + wfrag16_off((wave + 4 * tile) * 32 + fh * 16 + n, k0 + q * 8, nks16));
+      }
+  };
+  auto compute_chunk = [&](const bf16x8* A, int qq) {
+    if (qq >= nq) return;
+    const int tile = qq / nchunk, ch = qq - tile * nchunk;
+    if (ch == 0) {
+      acc[0] = floatx4{0.f, 0.f, 0.f, 0.f};
+      acc[1] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+    const uint16_t* xrow = s_in + n * stride_in + ch * 64 + q * 8;
+    const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(xrow);
+    if (ch * 64 + 64 <= in_pad) {
+      const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(xrow + 32);
+      acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[0], b0, acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[2], b0, acc[1], 0, 0, 0);
+      acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[1], b1, acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[3], b1, acc[1], 0, 0, 0);
+    } else {                                              // widths are multiples of 32: one k step at the ragged end
+      acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[0], b0, acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[2], b0, acc[1], 0, 0, 0);
+    }
+    if (ch == nchunk - 1) {
+#pragma unroll
+      for (int fh = 0; fh < 2; ++fh) {
+        const int f = (wave + 4 * tile) * 32 + fh * 16 + 4 * q;
+        const float4 bv = *reinterpret_cast<const float4*>(s_bias + f);
+        const float o0 = acc[fh][0] + bv.x, o1 = acc[fh][1] + bv.y, o2 = acc[fh][2] + bv.z, o3 = acc[fh][3] + bv.w;
+        if (EPI == kFEpiElu) {
+          *reinterpret_cast<uint2*>(&s_out[n * stride_out + f]) =
+              make_uint2(pack_bf16(elu_f(o0), elu_f(o1)), pack_bf16(elu_f(o2), elu_f(o3)));
+        } else {
+          float* d = s_head + n * head_stride + f;
+          if (f + 0 < out_store) d[0] = o0;
+          if (f + 1 < out_store) d[1] = o1;
+          if (f + 2 < out_store) d[2] = o2;
+          if (f + 3 < out_store) d[3] = o3;
+        }
+      }
+    }
+  };
+
+  load_chunk(A0, 0);
+  load_chunk(A1, 1);
+  load_chunk(A2, 2);
+  for (int qq = 0; qq < nq; qq += 4) {
+    load_chunk(A3, qq + 3);
+    compute_chunk(A0, qq);
+    load_chunk(A0, qq + 4);
+    compute_chunk(A1, qq + 1);
+    load_chunk(A1, qq + 5);
+    compute_chunk(A2, qq + 2);
+    load_chunk(A2, qq + 6);
+    compute_chunk(A3, qq + 3);
+  }
+}
+
 template <class WS, int L>
 __device__ __forceinline__ void ws_load16(bf16x8* wreg, const FusedNet& N, int wave, int lane) {
   if constexpr (L < WS::NL && L < WS::lds_from) {
@@ -770,8 +853,12 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       uint16_t* out = s_a;
       for (int l = 0; l < N.n_layers - 1; ++l) {
         if (run) {
-          fused_layer<RT, kFEpiElu>(N.w[l], s_nb + N.bias_off[l], N.in_pad[l], N.out_pad[l], in, stride_in, out, stride_h,
-                                    nullptr, 0, 0, nullptr, 0, wave4);
+          if constexpr (R16)
+            fused_layer16<kFEpiElu>(N.w[l], s_nb + N.bias_off[l], N.in_pad[l], N.out_pad[l], in, stride_in, out, stride_h,
+                                    nullptr, 0, 0, wave4);
+          else
+            fused_layer<RT, kFEpiElu>(N.w[l], s_nb + N.bias_off[l], N.in_pad[l], N.out_pad[l], in, stride_in, out, stride_h,
+                                      nullptr, 0, 0, nullptr, 0, wave4);
         }
         __syncthreads();
         in = out;
@@ -779,9 +866,14 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
         out = (out == s_a) ? s_b : s_a;
       }
       const int l = N.n_layers - 1;
-      if (run)
-        fused_layer<RT, kFEpiHead>(N.w[l], s_nb + N.bias_off[l], N.in_pad[l], N.out_pad[l], in, stride_in, nullptr, 0,
-                                   s_head, head_stride, N.out_store, nullptr, 0, wave4);
+      if (run) {
+        if constexpr (R16)
+          fused_layer16<kFEpiHead>(N.w[l], s_nb + N.bias_off[l], N.in_pad[l], N.out_pad[l], in, stride_in, nullptr, 0,
+                                   s_head, head_stride, N.out_store, wave4);
+        else
+          fused_layer<RT, kFEpiHead>(N.w[l], s_nb + N.bias_off[l], N.in_pad[l], N.out_pad[l], in, stride_in, nullptr, 0,
+                                     s_head, head_stride, N.out_store, nullptr, 0, wave4);
+      }
       __syncthreads();
     }
     GMI_RT_MARK(2);
@@ -1434,7 +1526,8 @@ extern "C" int rollout_collect(gmi_t g, gmi_model_t m, gmi_env_t env, gmi_buffer
   // 16 envs per workgroup: the weight-stationary nets on 16-row products
   if (rows_per_wg == 16 && variant == 2) { kfn = rollout_fused_kernel<1, WsAnt, true>; variant = 6; }
   else if (rows_per_wg == 16 && variant == 4) { kfn = rollout_fused_kernel<1, WsSmallObs, true>; variant = 7; }
-  static bool attr_set[8] = {false, false, false, false, false, false, false, false};
+  else if (rows_per_wg == 16 && variant == 0) { kfn = rollout_fused_kernel<1, void, true>; variant = 8; }
+  static bool attr_set[9] = {false, false, false, false, false, false, false, false, false};
   if (!attr_set[variant]) {
     GMI_HIP(hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
     attr_set[variant] = true;
