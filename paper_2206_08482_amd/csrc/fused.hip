@@ -822,9 +822,10 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
     const int r = idx / O, k = idx - r * O;
     s_in[r * OA + k] = (r0 + r < a.n) ? a.obs_state[(int64_t)(r0 + r) * O + k] : 0.f;
   }
-  // thread 256 + r (r < Rv; the fifth wave, which has no action items) carries env r's episode counter and makes
-  // its done flag
-  const int dtid = tid - 256;
+  // thread NT - 64 + r (r < Rv; the last wave, which has no action items and gets an observation-store item last of
+  // all: on the fifth wave the done flags came after an observation store and that wave ended the sampling phase
+  // 1000 cycles after the others) carries env r's episode counter and makes its done flag
+  const int dtid = tid - (NT - 64);
   uint32_t ep = 0;
   if (dtid >= 0 && dtid < Rv && r0 + dtid < a.n) ep = a.episode_step[r0 + dtid];
   if (a.noise_ahead) draw_items(a, s_ahead, a.step0, Rv, r0, npr, nba, nbo, tid, NT);
