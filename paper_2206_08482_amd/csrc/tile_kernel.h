@@ -1,0 +1,618 @@
+// Row-tile trainer kernel for the wide model shapes (every hidden width a multiple of 128): minibatch gather,
+// forward pass, clipped-surrogate / value loss and the whole input-gradient chain of one minibatch (stage (ii)
+// of Section 5.1 of the paper, the "DRL Trainer" role of Section 3) in one launch per minibatch.
+//
+// A workgroup of 4 waves owns 128 samples and keeps their current activations in LDS, as the second operands of
+// the 32x32x16 matrix instruction: block (k step ks, row tile rt) = 1 KiB, lane L of it = the 8 contraction
+// values of sample 32 rt + L % 32 that operand lane L takes.  Every product is computed transposed,
+// H^T = W X^T, and a wave owns a slice of the layer's OUTPUT FEATURES for all 128 samples (F / 128 feature tiles x
+// 4 row tiles, at most 16 accumulator tiles = 256 registers): per k step it fetches its own weight blocks straight
+// from the second-level cache into registers (no other wave of the workgroup needs them) and the 4 activation
+// blocks from LDS, i.e. 8 KiB of operands for 16 matrix instructions.  (With a wave per 32 samples and the weights
+// in LDS every wave reads every weight block: 1 KiB of LDS traffic per matrix instruction, which is the LDS
+// bandwidth of a compute unit.)  The weights come from the chain stream of the register-chained kernel
+// (chain_kernel.h): its blocks are the first operands of exactly these products, its k order inside a 16-wide
+// step is the order in which the matrix instruction leaves its results in a lane, so a lane's 8 results of a
+// k step are written back to LDS as one 16-byte piece at its own lane's slot.
+//
+// A layer is: k loop (all accumulators of the layer live at once) - barrier - epilogue (bias + ELU, or x ELU' of
+// the stored activation; conversion; the results into LDS in place of the layer's input, and row-major to memory
+// for the weight-gradient kernel) - barrier.  The next layer's first weight blocks are fetched before the epilogue.
+#pragma once
+#include "chain_kernel.h"
+#ifndef TILE_X_NOSTORE
+#define TILE_X_NOSTORE 0
+#endif
+#ifndef TILE_X_NOH
+#define TILE_X_NOH 0
+#endif
+
+namespace gmi_tile {
+using namespace gmi_chain;
+
+constexpr int kRows = 128;        // samples per workgroup
+constexpr int kWaves = 4;
+constexpr int kRing = 16;         // weight blocks in flight per wave: 16 / (feature tiles per wave) k steps
+constexpr int kHPre = 3;          // tiles whose stored activations are fetched ahead in an input-gradient epilogue
+
+template <int... DIMS>
+struct TileShape {
+  static constexpr int NL = (int)sizeof...(DIMS) - 1;
+  static constexpr ChainDims dims() { return ChainDims{NL, 4, {DIMS...}}; }
+  static constexpr int nseg() { return cd_nseg(dims()); }
+  static constexpr int maxks() { return cd_maxdim(dims()) / 16; }
+  static constexpr int bias_total() {
+    int n = 0;
+    for (int l = 0; l < NL; ++l) n += dims().d[l + 1];
+    return n;
+  }
+  static constexpr int bias_off(int l) {
+    int n = 0;
+    for (int i = 0; i < l; ++i) n += dims().d[i + 1];
+    return n;
+  }
+  static constexpr int seg_blk0(int s) {
+    int n = 0;
+    for (int i = 0; i < s; ++i) n += cd_seg_blocks(dims(), i);
+    return n;
+  }
+  static constexpr size_t x_bytes() { return (size_t)maxks() * 4 * 1024; }
+  static constexpr size_t lds_bytes() { return x_bytes() + (size_t)bias_total() * 4 + (size_t)(kWaves * 40 + 64) * 4; }
+  static constexpr bool valid() {
+    const ChainDims D = dims();
+    if (D.d[NL] != 32 || D.d[0] % 16 != 0) return false;
+    for (int l = 1; l < NL; ++l)
+      if (D.d[l] % 128 != 0) return false;
+    // the loss epilogue's per-wave transposition buffers live in the activation area behind the head layer's input
+    return x_bytes() >= 65536 + (size_t)kWaves * kScrBytes && D.d[NL - 1] / 16 * 4096 <= 65536;
+  }
+};
+
+template <class S, int SEG>
+struct Seg {
+  static constexpr ChainDims D = S::dims();
+  static constexpr int K = cd_K(D, SEG), F = cd_F(D, SEG), NKS = K / 16, NFT = F / 32;
+  static constexpr bool head = SEG == S::NL - 1;
+  static constexpr bool bwd = SEG >= S::NL;
+  static constexpr bool last = SEG == S::nseg() - 1;
+  static constexpr int layer = cd_layer(D, SEG);
+  static constexpr int FTW = head ? 1 : NFT / kWaves;     // feature tiles per wave
+  static constexpr int RT = head ? 1 : 4;                 // row tiles per wave (the head: one row tile per wave)
+  static constexpr int GS = NFT >= 4 ? 4 : NFT;           // tiles per group of the stream (chain_kernel.h)
+  static constexpr int DEP = kRing / FTW < NKS ? kRing / FTW : NKS;      // k steps of weight blocks in flight
+  static constexpr int XD = FTW >= 4 ? 1 : 2;             // k steps the activation blocks are read ahead (a k step of
+                                                          // fewer products is shorter than an LDS round trip)
+  static constexpr int blk0 = S::seg_blk0(SEG);
+  // The segment's input, which the previous segment's epilogue left in LDS, goes row-major to memory (for the
+  // weight-gradient kernel and for ELU') DURING this segment's k loop: h[layer] in a forward segment, dz[layer] in an
+  // input-gradient segment.  (Stores issued in the epilogue would all be older than the next k loop's weight
+  // fetches, and the memory counter is in order: the loop would wait for every one of them.)  Not for the first
+  // segment (the gather stores its rows) nor the first input-gradient segment (the loss epilogue stores the head's).
+  static constexpr int HK = NKS > 6 ? NKS - 6 : 0;        // k step at which an input-gradient segment starts to fetch ELU' inputs
+  static constexpr bool store_x = (SEG >= 1 && SEG <= S::NL - 1) || SEG > S::NL;
+  static_assert(!store_x || NKS % 2 == 0, "the store walks the k steps in pairs");
+  static_assert(head || NFT % kWaves == 0, "feature tiles divide over the waves");
+  static_assert(!head || NFT == 1, "the head is one 32-wide tile");
+};
+
+template <class S>
+struct Ctx {
+  floatx16 acc[4][4];
+  uint4 wq[kRing];                   // weight blocks of k steps g .. g + DEP - 1: block (ks, a) at (ks % DEP) * FTW + a
+  uint4 xq[3][4];                    // activation blocks of k steps g .. g + XD (ring indexed by k step % 3)
+  uint4 sx[2];                       // a row's two halves of a k step on their way to memory (store_x)
+  uint2 hq[kHPre + 1][4];            // stored activations of the tiles ahead (input-gradient epilogues)
+  const uint4* wnet;                 // this net's stream
+  uint4* X;                          // activation area
+  const float* s_bias;
+  float* s_red;
+  char* scr;                         // this wave's transposition buffer (loss epilogue only)
+  int64_t slot;                      // experience slot of this lane's sample of the head layer
+  float l_act[16], l_lo, l_ad, l_rt;
+  int tid, lane, wave, s, hh;
+  int row0, net;                     // first row of the workgroup's tile
+#ifdef GMI_CHAIN_TIMING
+  long long ts[32];
+#endif
+};
+
+// First weight block of wave `wave` in segment SEG: its FTW tiles are consecutive tiles of one group of the stream.
+template <class S, int SEG>
+__device__ __forceinline__ const uint4* seg_weights(const Ctx<S>& c) {
+  using G = Seg<S, SEG>;
+  const int ft0 = G::head ? 0 : c.wave * G::FTW;
+  const int off = G::blk0 + (ft0 / 4) * 4 * G::NKS + (ft0 % 4);
+  return c.wnet + (int64_t)off * 64;
+}
+template <class S, int SEG, int KS>
+__device__ __forceinline__ void issue_weights(Ctx<S>& c, const uint4* wseg) {
+  using G = Seg<S, SEG>;
+  if constexpr (KS < G::NKS) {
+#pragma unroll
+    for (int a = 0; a < G::FTW; ++a) c.wq[(KS % G::DEP) * G::FTW + a] = (wseg + (KS * G::GS + a) * 64)[c.lane];
+  }
+}
+// The first DEP k steps of segment SEG (issued before the previous segment's epilogue).
+template <class S, int SEG, int KS = 0>
+__device__ __forceinline__ void issue_first_weights(Ctx<S>& c) {
+  if constexpr (SEG < S::nseg()) {
+    if constexpr (KS < Seg<S, SEG>::DEP) {
+      issue_weights<S, SEG, KS>(c, seg_weights<S, SEG>(c));
+      issue_first_weights<S, SEG, KS + 1>(c);
+    }
+  }
+}
+
+template <class S, int SEG, int KS>
+__device__ __forceinline__ void read_x(Ctx<S>& c) {
+  using G = Seg<S, SEG>;
+  if constexpr (KS < G::NKS) {
+#pragma unroll
+    for (int b = 0; b < G::RT; ++b) c.xq[KS % 3][b] = c.X[(KS * 4 + (G::head ? c.wave : b)) * 64 + c.lane];
+  }
+}
+
+// Stored activations h[layer] of tile T = a * RT + b of this wave (input-gradient epilogue of segment SEG): for
+// every quad q the 4 features 32 ft + 8 q + 4 hh .. + 3 of sample 32 b + s.
+template <class S, int SEG, int T>
+__device__ __forceinline__ void fetch_h(Ctx<S>& c, const ChainArgs& a) {
+  using G = Seg<S, SEG>;
+  if constexpr (G::bwd && T < G::FTW * G::RT && !TILE_X_NOH) {
+    constexpr int ta = T / G::RT, tb = T % G::RT;
+    constexpr int ld = G::D.d[G::layer];
+    const int ft = c.wave * G::FTW + ta;
+    const uint16_t* p = a.h[c.net][G::layer] + (int64_t)(c.row0 + 32 * tb + c.s) * ld + 32 * ft + 4 * c.hh;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) c.hq[T % (kHPre + 1)][q] = *reinterpret_cast<const uint2*>(p + 8 * q);
+  }
+}
+
+template <class S, int SEG, int KS>
+__device__ __forceinline__ void k_steps(Ctx<S>& c, const ChainArgs& a, const uint4* wseg) {
+  using G = Seg<S, SEG>;
+  if constexpr (KS < G::NKS) {
+    bf16x8 wa[G::FTW];
+#pragma unroll
+    for (int a = 0; a < G::FTW; ++a) wa[a] = __builtin_bit_cast(bf16x8, c.wq[(KS % G::DEP) * G::FTW + a]);
+    issue_weights<S, SEG, KS + G::DEP>(c, wseg);
+    read_x<S, SEG, KS + G::XD>(c);
+    if constexpr (G::bwd && KS == G::HK) {          // the first tiles' stored activations, late enough not to hold up
+      fetch_h<S, SEG, 0>(c, a);                     // the weight fetches behind them, early enough to be there
+      fetch_h<S, SEG, 1>(c, a);
+      fetch_h<S, SEG, 2>(c, a);
+      static_assert(kHPre == 3, "three tiles ahead");
+    }
+    if constexpr (G::store_x && !TILE_X_NOSTORE) {
+      // wave w moves row tile w: lane (s, kk) takes sample s's 16 values of k step KS + kk -- the halves h = 0 / 1
+      // of the block hold values {0..3, 8..11} / {4..7, 12..15} -- and stores them as two 16-byte pieces one k step later
+      if constexpr (KS % 2 == 0) {
+        const uint4* blk = c.X + ((KS + c.hh) * 4 + c.wave) * 64 + c.s;
+        c.sx[0] = blk[0];
+        c.sx[1] = blk[32];
+      } else {
+        uint16_t* arr = G::bwd ? a.dz[c.net][G::layer] : a.h[c.net][G::layer];
+        uint4* dst = reinterpret_cast<uint4*>(arr + (int64_t)(c.row0 + 32 * c.wave + c.s) * G::K + 16 * (KS - 1 + c.hh));
+        dst[0] = make_uint4(c.sx[0].x, c.sx[0].y, c.sx[1].x, c.sx[1].y);      // arrays hold whole tiles
+        dst[1] = make_uint4(c.sx[0].z, c.sx[0].w, c.sx[1].z, c.sx[1].w);
+      }
+    }
+#pragma unroll
+    for (int a = 0; a < G::FTW; ++a)
+#pragma unroll
+      for (int b = 0; b < G::RT; ++b)
+        c.acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], __builtin_bit_cast(bf16x8, c.xq[KS % 3][b]), c.acc[a][b], 0, 0, 0);
+    // nothing moves across this point: the fetches stay ahead of the products they feed
+    __builtin_amdgcn_sched_barrier(0);
+    k_steps<S, SEG, KS + 1>(c, a, wseg);
+  }
+}
+
+// Epilogue of tile T of a hidden forward layer or of an input-gradient layer.
+template <class S, int SEG, int T>
+__device__ __forceinline__ void tile_epilogue(Ctx<S>& c, const ChainArgs& a) {
+  using G = Seg<S, SEG>;
+  if constexpr (T < G::FTW * G::RT) {
+    constexpr int ta = T / G::RT, tb = T % G::RT;
+    const int ft = c.wave * G::FTW + ta;
+    fetch_h<S, SEG, T + kHPre>(c, a);
+    const floatx16& acc = c.acc[ta][tb];
+    uint32_t w[8];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float v0 = acc[4 * q + 0], v1 = acc[4 * q + 1], v2 = acc[4 * q + 2], v3 = acc[4 * q + 3];
+      if constexpr (G::bwd) {
+        const uint2 hv = TILE_X_NOH ? make_uint2(0x3f803f80u, 0xbf003f80u) : c.hq[T % (kHPre + 1)][q];
+        v0 *= elu_grad_f(bf16_lo(hv.x)); v1 *= elu_grad_f(bf16_hi(hv.x));
+        v2 *= elu_grad_f(bf16_lo(hv.y)); v3 *= elu_grad_f(bf16_hi(hv.y));
+      } else {
+        v0 = elu_f(v0); v1 = elu_f(v1); v2 = elu_f(v2); v3 = elu_f(v3);      // the bias is in the sums already
+      }
+      w[2 * q] = pack_bf16(v0, v1);
+      w[2 * q + 1] = pack_bf16(v2, v3);
+    }
+    c.X[((2 * ft + 0) * 4 + tb) * 64 + c.lane] = make_uint4(w[0], w[1], w[2], w[3]);
+    c.X[((2 * ft + 1) * 4 + tb) * 64 + c.lane] = make_uint4(w[4], w[5], w[6], w[7]);
+    tile_epilogue<S, SEG, T + 1>(c, a);
+  }
+}
+
+// This lane's loss inputs (sample row0 + 32 wave + s): unconditional loads, rows and features past the end read a
+// valid neighbour, their results are dropped.
+template <class S>
+__device__ __forceinline__ void fetch_loss_inputs(Ctx<S>& c, const ChainArgs& a) {
+  c.l_lo = a.b_logp[c.slot]; c.l_ad = a.b_adv[c.slot]; c.l_rt = a.b_ret[c.slot];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int f = 8 * (i >> 2) + 4 * c.hh + (i & 3);
+    const int fc = f < a.act_dim ? f : a.act_dim - 1;
+    c.l_act[i] = a.b_act[c.slot * a.act_dim + fc];
+  }
+}
+
+// Loss on the wave's 32 samples (row tile `wave` of the workgroup) from the head's accumulators: lane = sample s,
+// half hh; register i = feature 8 (i / 4) + 4 hh + i % 4.  Leaves the head gradient as the two k steps of the first
+// input-gradient product in the activation area, row-major in dz[NL - 1], and the workgroup's statistics row.
+template <class S>
+__device__ __forceinline__ void loss_epilogue(Ctx<S>& c, const ChainArgs& a, const floatx16& acc) {
+  constexpr int HB = S::bias_off(S::NL - 1);
+  const int A = a.act_dim;
+  const int wrow0 = c.row0 + 32 * c.wave;
+  const int row = wrow0 + c.s;
+  const bool ok = row < a.rows;
+  const float inv_m = 1.0f / (float)a.rows;
+  float d[16];
+  float* red = c.s_red + c.wave * 40;
+  if (c.net == 0) {
+    const float* s_ls = c.s_red + kWaves * 40;      // [f] log_std, [32 + f] exp(-log_std) (0 for f >= A)
+    float z[16], isg[16];
+    float lp = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int f0 = 8 * q + 4 * c.hh;
+      const float4 ls4 = *reinterpret_cast<const float4*>(s_ls + f0);
+      const float4 ig4 = *reinterpret_cast<const float4*>(s_ls + 32 + f0);
+      const float4 b4 = *reinterpret_cast<const float4*>(c.s_bias + HB + f0);
+      const float lsv[4] = {ls4.x, ls4.y, ls4.z, ls4.w}, igv[4] = {ig4.x, ig4.y, ig4.z, ig4.w};
+      const float bv[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int i = 4 * q + e;
+        const float mu = acc[i] + bv[e];
+        isg[i] = igv[e];
+        z[i] = (c.l_act[i] - mu) * igv[e];                    // 0 for f >= A
+        lp += f0 + e < A ? -0.5f * z[i] * z[i] - lsv[e] - 0.918938533204672742f : 0.f;
+      }
+    }
+    lp += __shfl_xor(lp, 32, 64);                   // the other half holds the other 16 features
+    float s_pl = 0.f, s_kl = 0.f, s_cf = 0.f, g_lp = 0.f;
+    if (ok) {
+      const float lo = c.l_lo, ad = c.l_ad;
+      const float ratio = __expf(lp - lo);
+      const float u1 = ratio * ad;
+      const float u2 = fminf(fmaxf(ratio, 1.0f - a.clip), 1.0f + a.clip) * ad;
+      g_lp = (u1 <= u2) ? -(ad * ratio) * inv_m : 0.f;
+      if (c.hh == 0) {                               // each sample counts once
+        s_pl = -fminf(u1, u2);
+        s_kl = lo - lp;
+        s_cf = fabsf(ratio - 1.0f) > a.clip ? 1.f : 0.f;
+      }
+    }
+    // log_std gradient partials g_lp (z^2 - 1): transposed through the wave's buffer as [feature][sample] fp32,
+    // then lane f < 32 sums feature f's 32 samples in a fixed order
+    float* tp = reinterpret_cast<float*>(c.scr);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int f = 8 * (i >> 2) + 4 * c.hh + (i & 3);
+      d[i] = g_lp * z[i] * isg[i];
+      tp[f * 33 + c.s] = g_lp * (z[i] * z[i] - 1.0f);
+    }
+    if (c.lane < 32) {
+      float sum = 0.f;
+#pragma unroll
+      for (int k = 0; k < 32; ++k) sum += tp[c.lane * 33 + k];
+      red[8 + c.lane] = c.lane < A ? sum : 0.f;
+    }
+    s_pl = wave_sum64(s_pl); s_kl = wave_sum64(s_kl); s_cf = wave_sum64(s_cf);
+    if (c.lane == 0) { red[0] = s_pl; red[1] = s_kl; red[2] = s_cf; }
+  } else {
+    float s_vl = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) d[i] = 0.f;
+    if (ok && c.hh == 0) {
+      const float dv = acc[0] + c.s_bias[HB] - c.l_rt;
+      s_vl = dv * dv;
+      d[0] = 2.0f * a.c_v * dv * inv_m;
+    }
+    s_vl = wave_sum64(s_vl);
+    if (c.lane == 0) red[0] = s_vl;
+  }
+  uint32_t w[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) w[q] = pack_bf16(d[2 * q], d[2 * q + 1]);
+  c.X[(0 * 4 + c.wave) * 64 + c.lane] = make_uint4(w[0], w[1], w[2], w[3]);
+  c.X[(1 * 4 + c.wave) * 64 + c.lane] = make_uint4(w[4], w[5], w[6], w[7]);
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    *reinterpret_cast<uint2*>(c.scr + c.s * kScrStride + (8 * q + 4 * c.hh) * 2) = make_uint2(w[2 * q], w[2 * q + 1]);
+  scr_to_global<1>(c.scr, c.lane, a.dz[c.net][S::NL - 1], 32, 0, wrow0, a.rows);
+  // workgroup sums -> this tile's row of the statistics partials
+  __syncthreads();
+  float* out = a.stat_part + (int64_t)blockIdx.x * (gmi::kStatStride + A);
+  if (c.net == 0) {
+    if (c.tid < 3) {
+      float v = 0.f;
+      for (int wv = 0; wv < kWaves; ++wv) v += c.s_red[wv * 40 + c.tid];
+      out[c.tid == 0 ? 0 : (c.tid == 1 ? 3 : 4)] = v;
+    }
+    if (c.tid == 3) {
+      float ent = 0.f;
+      if (blockIdx.x == 0)
+        for (int j = 0; j < A; ++j) ent += a.log_std[j] + 1.418938533204672742f;
+      out[2] = ent;
+      out[5] = out[6] = out[7] = 0.f;
+    }
+    if (c.tid >= 64 && c.tid < 64 + A) {
+      const int j = c.tid - 64;
+      float v = 0.f;
+      for (int wv = 0; wv < kWaves; ++wv) v += c.s_red[wv * 40 + 8 + j];
+      out[gmi::kStatStride + j] = v;
+    }
+  } else if (c.tid == 0) {
+    float v = 0.f;
+    for (int wv = 0; wv < kWaves; ++wv) v += c.s_red[wv * 40];
+    out[1] = v;
+  }
+}
+
+template <class S, int SEG>
+__device__ __forceinline__ void run_segment(Ctx<S>& c, const ChainArgs& a) {
+  if constexpr (SEG < S::nseg()) {
+    using G = Seg<S, SEG>;
+    const uint4* wseg = seg_weights<S, SEG>(c);
+#ifdef GMI_CHAIN_TIMING
+    c.ts[3 * SEG] = __builtin_readcyclecounter();
+#endif
+    if constexpr (!G::bwd && !G::head) {
+      // the accumulators start at the bias (register i of a lane = feature 8 (i / 4) + 4 hh + i % 4 of the tile)
+      constexpr int boff = S::bias_off(G::layer);
+#pragma unroll
+      for (int ta = 0; ta < G::FTW; ++ta) {
+        const float* bp = c.s_bias + boff + 32 * (c.wave * G::FTW + ta) + 4 * c.hh;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float4 b4 = *reinterpret_cast<const float4*>(bp + 8 * q);
+#pragma unroll
+          for (int tb = 0; tb < G::RT; ++tb) {
+            c.acc[ta][tb][4 * q + 0] = b4.x; c.acc[ta][tb][4 * q + 1] = b4.y;
+            c.acc[ta][tb][4 * q + 2] = b4.z; c.acc[ta][tb][4 * q + 3] = b4.w;
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int ta = 0; ta < G::FTW; ++ta)
+#pragma unroll
+        for (int tb = 0; tb < G::RT; ++tb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) c.acc[ta][tb][v] = 0.f;
+    }
+    read_x<S, SEG, 0>(c);
+    if constexpr (G::XD > 1) read_x<S, SEG, 1>(c);
+    k_steps<S, SEG, 0>(c, a, wseg);
+#ifdef GMI_CHAIN_TIMING
+    c.ts[3 * SEG + 1] = __builtin_readcyclecounter();
+#endif
+    issue_first_weights<S, SEG + 1>(c);
+    __syncthreads();                       // every wave is done with the layer's input
+#ifdef GMI_CHAIN_TIMING
+    c.ts[3 * SEG + 2] = __builtin_readcyclecounter();
+#endif
+    // this lane's loss inputs: cold loads, issued where a long stretch of arithmetic follows and no younger load is
+    // waited for (the memory counter is in order)
+    if constexpr (SEG == (S::NL >= 3 ? S::NL - 3 : 0)) fetch_loss_inputs<S>(c, a);
+    if constexpr (G::head) {
+      loss_epilogue<S>(c, a, c.acc[0][0]);
+    } else {
+      tile_epilogue<S, SEG, 0>(c, a);
+    }
+    __syncthreads();
+    if constexpr (G::last) {
+      // nothing consumes the last results on chip: row tile `wave` of the activation area goes row-major to
+      // dz[layer - 1] the way a k loop moves its input (k_steps)
+      uint16_t* arr = a.dz[c.net][G::layer - 1];
+#pragma unroll 4
+      for (int ks = 0; ks < G::F / 16; ks += 2) {
+        const uint4* blk = c.X + ((ks + c.hh) * 4 + c.wave) * 64 + c.s;
+        const uint4 lo = blk[0], hi = blk[32];
+        uint4* dst = reinterpret_cast<uint4*>(arr + (int64_t)(c.row0 + 32 * c.wave + c.s) * G::F + 16 * (ks + c.hh));
+        dst[0] = make_uint4(lo.x, lo.y, hi.x, hi.y);      // arrays hold whole tiles
+        dst[1] = make_uint4(lo.z, lo.w, hi.z, hi.w);
+      }
+    }
+#ifdef GMI_CHAIN_TIMING
+    if constexpr (G::last) c.ts[3 * SEG + 3] = __builtin_readcyclecounter();
+#endif
+    run_segment<S, SEG + 1>(c, a);
+  }
+}
+
+template <class S>
+__global__ __launch_bounds__(kWaves * 64) void train_tile_kernel(ChainArgs a) {
+  static_assert(S::valid(), "shape not supported by the row-tile trainer kernel");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  constexpr ChainDims D = S::dims();
+  Ctx<S> c;
+  c.tid = threadIdx.x;
+  c.lane = c.tid & 63;
+  c.wave = __builtin_amdgcn_readfirstlane(c.tid >> 6);
+  c.s = c.lane & 31;
+  c.hh = c.lane >> 5;
+  c.net = blockIdx.y;
+  c.row0 = blockIdx.x * kRows;
+  c.X = reinterpret_cast<uint4*>(smem_raw);
+  float* s_bias = reinterpret_cast<float*>(smem_raw + S::x_bytes());
+  c.s_bias = s_bias;
+  c.s_red = s_bias + S::bias_total();
+  c.scr = reinterpret_cast<char*>(smem_raw) + 65536 + c.wave * kScrBytes;
+  c.wnet = reinterpret_cast<const uint4*>(a.wstream[c.net]);
+#ifdef GMI_CHAIN_TIMING
+  c.ts[30] = __builtin_readcyclecounter();
+  const long long t_real0 = __builtin_amdgcn_s_memrealtime();
+#endif
+
+  issue_first_weights<S, 0>(c);
+  {
+    int off = 0;
+#pragma unroll
+    for (int l = 0; l < S::NL; ++l) {
+      for (int f = c.tid; f < D.d[l + 1]; f += kWaves * 64) s_bias[off + f] = a.bias[c.net][l][f];
+      off += D.d[l + 1];
+    }
+  }
+  for (int i = c.tid; i < kWaves * 40; i += kWaves * 64) c.s_red[i] = 0.f;
+  if (c.tid < 32) {                      // per-feature constants of the Gaussian log-prob (policy net)
+    const int fc = c.tid < a.act_dim ? c.tid : a.act_dim - 1;
+    const float ls = a.log_std[fc];
+    c.s_red[kWaves * 40 + c.tid] = ls;
+    c.s_red[kWaves * 40 + 32 + c.tid] = c.tid < a.act_dim ? expf(-ls) : 0.f;
+  }
+  {
+    // this lane's sample of the head layer (rows past the batch take the last sample; their results are dropped)
+    const int row = c.row0 + 32 * c.wave + c.s;
+    const int rc = row < a.rows ? row : a.rows - 1;
+    const int sm = a.idx ? a.idx[rc] : rc;
+    c.slot = (int64_t)(sm / a.n_envs) * a.ld_envs + (sm % a.n_envs);
+  }
+  {
+    // The gather: the workgroup's 128 observation rows as the first layer's operand blocks in natural k order (lane
+    // (s, h) of block (ks, rt) holds features 16 ks + 8 h .. + 7 of sample 32 rt + s), zero padded.  A lane takes
+    // 16-byte piece jj + 4 it of row 16 g + rr: 16 lanes write 256 consecutive bytes of LDS, 4 lanes read 64
+    // consecutive bytes of a row.  The policy net's workgroups also leave the bf16 rows in x0 for the
+    // weight-gradient kernel.  All loads unconditional (clamped addresses, selected values).
+    constexpr int NP = D.d[0] / 8;                       // 16-byte pieces of a row
+    const int rr = c.lane & 15, jj = c.lane >> 4;
+    const int O = a.obs_dim;
+    constexpr int NI = (NP + 3) / 4;
+    int sm[2];
+#pragma unroll
+    for (int gi = 0; gi < 2; ++gi) {
+      const int row = c.row0 + 16 * (c.wave + kWaves * gi) + rr;
+      const int rc = row < a.rows ? row : a.rows - 1;
+      sm[gi] = a.idx ? a.idx[rc] : rc;
+    }
+    uint4 v[2][NI];
+    if (a.x0_ready != 0) {                               // workgroup-uniform; no branch around a single load
+#pragma unroll
+      for (int gi = 0; gi < 2; ++gi) {
+        const int row = c.row0 + 16 * (c.wave + kWaves * gi) + rr;
+        const uint16_t* src = a.x0_ready == 1 ? a.x0 + (int64_t)row * D.d[0] : a.x16 + (int64_t)sm[gi] * D.d[0];
+#pragma unroll
+        for (int it = 0; it < NI; ++it) {
+          const int j = 4 * it + jj;
+          v[gi][it] = *reinterpret_cast<const uint4*>(src + 8 * (j < NP ? j : NP - 1));
+        }
+      }
+    } else {
+#pragma unroll
+      for (int gi = 0; gi < 2; ++gi) {
+        const int64_t slot = (int64_t)(sm[gi] / a.n_envs) * a.ld_envs + (sm[gi] % a.n_envs);
+        const float* orow = a.b_obs + slot * O;
+#pragma unroll
+        for (int it = 0; it < NI; ++it) {
+          const int j = 4 * it + jj;
+          const int jc = j < NP ? j : NP - 1;
+          float f[8];
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            const int f0 = 8 * jc + 4 * q;                  // O % 4 == 0: a piece is inside the row or past it
+            const float4 t = *reinterpret_cast<const float4*>(orow + (f0 < O ? f0 : O - 4));
+            f[4 * q + 0] = f0 < O ? t.x : 0.f; f[4 * q + 1] = f0 < O ? t.y : 0.f;
+            f[4 * q + 2] = f0 < O ? t.z : 0.f; f[4 * q + 3] = f0 < O ? t.w : 0.f;
+          }
+          v[gi][it] = make_uint4(pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7]));
+        }
+      }
+    }
+    const bool keep = a.x0_ready != 1 && c.net == 0;
+#pragma unroll
+    for (int gi = 0; gi < 2; ++gi) {
+      const int r = 16 * (c.wave + kWaves * gi) + rr;
+      uint16_t* xw = a.x0 + (int64_t)(c.row0 + r) * D.d[0];
+#pragma unroll
+      for (int it = 0; it < NI; ++it) {
+        const int j = 4 * it + jj;
+        if (j < NP) {
+          c.X[((j >> 1) * 4 + (r >> 5)) * 64 + (r & 31) + 32 * (j & 1)] = v[gi][it];
+          if (keep) *reinterpret_cast<uint4*>(xw + 8 * j) = v[gi][it];      // arrays hold whole tiles
+        }
+      }
+    }
+  }
+  __syncthreads();
+#ifdef GMI_CHAIN_TIMING
+  c.ts[31] = __builtin_readcyclecounter();
+#endif
+  run_segment<S, 0>(c, a);
+#ifdef GMI_CHAIN_TIMING
+  if (blockIdx.x == gridDim.x / 2 && blockIdx.y == 0 && c.tid == 64) {
+#pragma unroll
+    for (int i = 0; i < 32; ++i) a.dbg[i] = c.ts[i];
+  }
+  if (c.tid == 0) {      // wall clock (100 MHz) and cycle counter of every workgroup's start and end
+    const int wg = blockIdx.y * gridDim.x + blockIdx.x;
+    a.dbg[64 + 4 * wg] = t_real0;
+    a.dbg[64 + 4 * wg + 1] = __builtin_amdgcn_s_memrealtime();
+    a.dbg[64 + 4 * wg + 2] = c.ts[30];
+    a.dbg[64 + 4 * wg + 3] = __builtin_readcyclecounter();
+  }
+#endif
+}
+
+template <class S>
+bool shape_matches(const ModelLayout& L) {
+  constexpr ChainDims D = S::dims();
+  if (L.n_layers != D.nl) return false;
+  for (int net = 0; net < 2; ++net)
+    for (int l = 0; l < D.nl; ++l)
+      if (L.net[net][l].in_pad != D.d[l] || L.net[net][l].out_pad != D.d[l + 1]) return false;
+  return true;
+}
+
+template <class S>
+int launch_shape(gmi_instance* g, const ChainArgs& a, int rows, int* tiles_out, double flops, double bytes) {
+  static bool attr = false;
+  const size_t lds = S::lds_bytes();
+  const int tiles = (rows + kRows - 1) / kRows;
+  *tiles_out = tiles;
+  if (tiles > gmi::kLossBlocksMax) return GMI_ERR_UNSUPPORTED;      // one statistics row per tile
+  if (a.x0_ready == 0 && (a.obs_dim % 4 != 0 || a.obs_dim < 4)) return GMI_ERR_UNSUPPORTED;
+  if (!attr) {
+    GMI_HIP(hipFuncSetAttribute((const void*)train_tile_kernel<S>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr = true;
+  }
+  gmi::ProfScope ps(g, gmi::kClsChainTrain);
+  ps.work(flops, bytes);
+  ps.launch(train_tile_kernel<S>, dim3(tiles, 2), dim3(kWaves * 64), lds, a);
+  GMI_LAUNCH_CHECK();
+  return GMI_OK;
+}
+
+}  // namespace gmi_tile
+
+namespace gmi {
+// One function per shape compiled for the row-tile kernel (tile_p<k>.hip), with the contract of the chained kernel's
+// parts (chain_kernel.h): GMI_ERR_UNSUPPORTED if the model has another shape; rows == 0 only asks (the answer: the
+// stream's group size 4, plus 256 for the gather from the bf16 copy of all observations).
+constexpr int kTileParts = 2;
+#define GMI_TILE_PART_DECL(k)                                                                              \
+  int launch_tile_part##k(gmi_instance* g, const ModelLayout& L, const gmi_chain::ChainArgs& a, int rows, \
+                          int* tiles_out, double flops, double bytes)
+GMI_TILE_PART_DECL(0); GMI_TILE_PART_DECL(1);
+#define GMI_TILE_PART_DEFINE(k, ...)                                                              \
+  GMI_TILE_PART_DECL(k) {                                                                         \
+    using S = gmi_tile::TileShape<__VA_ARGS__>;                                                   \
+    if (!gmi_tile::shape_matches<S>(L)) return GMI_ERR_UNSUPPORTED;                               \
+    if (rows == 0) { *tiles_out = 4 | 256; return GMI_OK; }                                       \
+    return gmi_tile::launch_shape<S>(g, a, rows, tiles_out, flops, bytes);                        \
+  }
+}  // namespace gmi
