@@ -191,7 +191,7 @@ int prepare_obs16(gmi_instance* g, gmi_model* m, gmi_buffer* b, bool* ready) {
 }
 
 int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx, int rows,
-                       int* n_stat_rows, bool obs16_ready) {
+                       int* n_stat_rows, bool obs16_ready, bool* blocks) {
   const ModelLayout& L = m->L;
   if (L.dtype != GMI_DTYPE_BF16 || L.sh_chain_bytes == 0 || L.act_dim > 32) return GMI_ERR_UNSUPPORTED;
   ChainArgs a;
@@ -204,6 +204,7 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_p
     }
   }
   a.x0 = (uint16_t*)m->x0;
+  a.x0b = (uint16_t*)m->x0b;
   a.log_std = reinterpret_cast<const float*>(m->shadow + L.sh_logstd);
   a.idx = idx;
   a.b_obs = b->d.obs; a.b_act = b->d.act; a.b_logp = b->d.logp; a.b_adv = b->d.adv; a.b_ret = b->d.ret;
@@ -246,8 +247,10 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_p
     if (rc != GMI_OK) return rc;
   }
   rc = GMI_ERR_UNSUPPORTED;
+  *blocks = false;
   if (tile_enabled())
     for (int p = 0; p < kTileParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = kTileFns[p](g, L, a, rows, &tiles, flops, bytes);
+  if (rc == GMI_OK) *blocks = true;
   for (int p = 0; p < kChainParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = kParts[p](g, L, a, rows, &tiles, flops, bytes);
   if (rc != GMI_OK) return rc;
   *n_stat_rows = tiles;

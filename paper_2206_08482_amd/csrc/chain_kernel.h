@@ -198,6 +198,7 @@ struct ChainArgs {
   int net0;
   float* mu_out;                                   // [rows, act_dim] policy means
   float* val_out;                                  // [rows] values
+  uint16_t* x0b;                                   // row-tile kernel: x0 in its block layout (tile_kernel.h)
 #ifdef GMI_CHAIN_TIMING
   long long* dbg;                                  // [n_chunks + 1] clock at the start of every chunk (workgroup 0, wave 0)
 #endif

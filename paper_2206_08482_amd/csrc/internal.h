@@ -163,6 +163,7 @@ struct gmi_model {
   size_t ws_bytes;
   // activations: x0 shared by both nets; h[net][l] for l = 1..n_hidden; element type = dtype
   void* x0;
+  void* x0b;         // x0 in the block layout of the row-tile trainer kernel (written by that kernel)
   void* h[2][GMI_MAX_HIDDEN + 1];
   void* dz[2][GMI_MAX_HIDDEN + 2];   // dz[net][l] = dL/d(pre-activation of layer l-1's output), l=1..n_layers
   float* mu;        // [max_rows, act_dim]
@@ -232,6 +233,11 @@ int launch_linear(gmi_instance* g, int dtype, int epi, int rows, const LinearBat
 struct WgradProblem {
   const void* dz; int lddz;
   const void* x; int ldx;
+  // 0: the operand is row-major [rows, ld]; 1, 2 (bf16 only): it is in the block layout the row-tile trainer kernel
+  // leaves (tile_kernel.h): per 128 rows, per 16-wide feature step ks, per 32-row tile rt, a 1 KiB block whose
+  // 16-byte slot s + 32 h holds, of row 32 rt + s, the features 16 ks + 4 h + {0..3} and 16 ks + 8 + 4 h + {0..3} (1)
+  // or 16 ks + 8 h + {0..7} (2: the gathered observation rows).  Either both operands are row-major or none is.
+  int dz_blocks, x_blocks;
   int out, in, out_pad, in_pad;
   int64_t w_off, b_off;
 };
@@ -296,8 +302,9 @@ void fill_chain_emit(const ModelLayout& L, ChainEmit* ce);
 // net only) and values into val.  GMI_ERR_UNSUPPORTED (no message) if no such kernel is compiled for the shape.
 int launch_forward_chain(gmi_instance* g, gmi_model* m, const float* obs, int n_rows, float* mu, float* val);
 // obs16_ready: b->obs16 holds the bf16 copy of the buffer's present observations (prepare_obs16).
+// *blocks = whether the hidden activations and gradients were left in the row-tile kernel's block layout.
 int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx, int rows,
-                       int* n_stat_rows, bool obs16_ready);
+                       int* n_stat_rows, bool obs16_ready, bool* blocks);
 // Before the minibatches of an update: converts all observations of the buffer into b->obs16 if the chained kernel
 // will run and cannot read the fp32 rows itself.  *ready = whether it did.
 int prepare_obs16(gmi_instance* g, gmi_model* m, gmi_buffer* b, bool* ready);

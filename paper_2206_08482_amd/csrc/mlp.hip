@@ -384,16 +384,16 @@ __device__ __forceinline__ void transpose8x8(const uint4 in[8], uint4 out[8]) {
   }
 }
 
-__global__ __launch_bounds__(256) void wgrad_bf16_kernel(gmi::WgradBatch batch, int rows, int n_split,
-                                                         int chunk, float* __restrict__ part,
-                                                         int64_t part_stride) {
-  constexpr int T = 128;
-  constexpr int kBuf = 2 * T * kLds;                                 // one LDS stage: [o][row] then [i][row]
-  __shared__ __attribute__((aligned(16))) uint16_t s_stage[2 * kBuf];
-  int pi = 0;
-  while (pi + 1 < batch.n && (int)blockIdx.x >= batch.blk_start[pi + 1]) ++pi;
-  const gmi::WgradProblem& P = batch.p[pi];
-  const int local = blockIdx.x - batch.blk_start[pi];
+// LAYOUT: 0 both operands row-major, 1 both in the block layout.  A compile-time constant: a run-time branch around
+// the staging loads makes the compiler wait for every load in flight where it should wait for the older of two
+// stages (measured: 1.8x the kernel's time).
+constexpr int kWgradT = 128;
+constexpr int kWgradBuf = 2 * kWgradT * kLds;                        // one LDS stage: [o][row] then [i][row]
+template <int LAYOUT>
+__device__ __forceinline__ void wgrad_tile(const gmi::WgradProblem& P, int local, int rows, int n_split, int chunk,
+                                           float* __restrict__ part, int64_t part_stride, uint16_t* s_stage) {
+  constexpr int T = kWgradT;
+  constexpr int kBuf = kWgradBuf;
   const int sp = local % n_split;
   const int tile = local / n_split;
   const int n_ti = (P.in_pad + T - 1) / T;
@@ -405,19 +405,45 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(gmi::WgradBatch batch, 
   const int wo = wave >> 1, wi = wave & 1;
   const bool is_b = tid >= 128;
   const int t2 = tid & 127;
-  const int fblk = t2 & 15, rblk = t2 >> 4;          // 16 feature blocks x 8 row blocks
   const int ld = is_b ? P.ldx : P.lddz;
   const int fmax = is_b ? P.in_pad : P.out_pad;
-  const int feat = (is_b ? i0 : o0) + fblk * 8;
+  const int f0 = is_b ? i0 : o0;                      // first feature of the operand's 128-wide slice
+  constexpr bool blocks = LAYOUT == 1;
+  const bool natural = blocks && (is_b ? P.x_blocks : P.dz_blocks) == 2;      // k order inside a block's 16-wide step
+  const uint16_t* __restrict__ opnd = is_b ? (const uint16_t*)P.x : (const uint16_t*)P.dz;
+  // A thread stages 8 rows x 8 features per step: the rows rblk + 8 jj + 32 rt (jj = 0..3, rt = 0, 1) of the stage's
+  // 64 -- which 8 rows share a 16-byte piece of LDS does not matter to a sum over rows, as long as both operands
+  // agree.  Row-major operand: 16 feature blocks x 8 row blocks, the thread's features are feat .. feat + 7 and it
+  // reads 16 bytes of each of its rows.  Block layout (internal.h): 8 feature steps x 2 halves x 8 row blocks; the
+  // thread's features are 16 ks + 4 h + {0..3} and 16 ks + 8 + 4 h + {0..3}, row j is slot rblk + 8 (j % 4) of row
+  // tile j / 4 of the stage.
+  int fblk, rblk, feat;
+  int ksl = 0, hb = 0;
+  if (blocks) {
+    rblk = t2 & 7; hb = (t2 >> 3) & 1; ksl = t2 >> 4;  // 8 consecutive lanes read 128 consecutive bytes of a block
+    fblk = 2 * ksl;
+    feat = f0 + 16 * ksl;
+  } else {
+    fblk = t2 & 15; rblk = t2 >> 4;
+    feat = f0 + fblk * 8;
+  }
   const bool feat_ok = feat < fmax;
   // loads are unconditional (clamped addresses, masked to zero afterwards) so that two stages stay in
   // flight and the compiler waits only for the older one
-  const uint16_t* __restrict__ src = (is_b ? (const uint16_t*)P.x : (const uint16_t*)P.dz) + (feat_ok ? feat : 0);
+  const uint16_t* __restrict__ src = opnd + (feat_ok ? feat : 0);
   // LDS holds [feature][row]; the 16-byte slot of row block rblk inside a feature's line is XOR-swizzled
   // with the feature block index: the 16 lanes that write the same row block of 16 different feature
   // blocks are 8 LDS lines apart, which without the swizzle is the same bank group for all of them
   // (measured: 16-way conflicts made every stage cost ~4000 cycles whatever the tile's work).
-  const int sdst = (is_b ? T * kLds : 0) + (fblk * 8) * kLds + ((rblk ^ (fblk & 7)) * 8);
+  // Feature i of the thread's 8 sits at local feature fl(i); its slot is swizzled with fl(i) / 8.
+  const int obase = is_b ? T * kLds : 0;
+  int sdst_i[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int fl = blocks ? 16 * ksl + (natural ? 8 * hb + i : (i < 4 ? 4 * hb + i : 8 + 4 * hb + (i - 4))) : fblk * 8 + i;
+    sdst_i[i] = obase + fl * kLds + ((rblk ^ ((fl >> 3) & 7)) * 8);
+  }
+  const int nks_op = fmax >> 4;                        // feature steps of a block-layout operand
 
   floatx16 acc[2][2];
   floatx16 accb[2];
@@ -435,15 +461,24 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(gmi::WgradBatch batch, 
   // row pointers of the thread's 8 rows for the stage being loaded next; advanced by 64 rows per stage.
   // Stages wholly inside [row_begin, row_end) need neither clamping nor masking.
   const int64_t ld64 = ld;
+  const int rows_alloc = (rows + 127) & ~127;          // block-layout arrays hold whole 128-row tiles
   auto load_stage = [&](uint4* st, int rbase) {
-    if (rbase + kBK <= row_end) {
-      const uint16_t* p = src + (int64_t)(rbase + rblk * 8) * ld64;
+    if (blocks) {
+      // stage = rows rbase .. rbase + 63 = row tiles 2 (rbase / 64 % 2) + {0, 1} of workgroup tile rbase / 128
+      const int rb = rbase < rows_alloc ? rbase : rows_alloc - 64;      // stages past the end re-read the last one (masked)
+      const int tr = rb >> 7, rt = ((rb >> 6) & 1) * 2;
+      const int ksg = (feat_ok ? feat : 0) >> 4;
+      const uint4* p = reinterpret_cast<const uint4*>(opnd) + (((int64_t)tr * nks_op + ksg) * 4 + rt) * 64 + 32 * hb + rblk;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) st[j] = *reinterpret_cast<const uint4*>(p + j * ld64);
+      for (int j = 0; j < 8; ++j) st[j] = p[(j >> 2) * 64 + 8 * (j & 3)];
+    } else if (rbase + kBK <= row_end) {
+      const uint16_t* p = src + (int64_t)(rbase + rblk) * ld64;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) st[j] = *reinterpret_cast<const uint4*>(p + (32 * (j >> 2) + 8 * (j & 3)) * ld64);
     } else {
 #pragma unroll
       for (int j = 0; j < 8; ++j)
-        st[j] = *reinterpret_cast<const uint4*>(src + (int64_t)min(rbase + rblk * 8 + j, rows - 1) * ld64);
+        st[j] = *reinterpret_cast<const uint4*>(src + (int64_t)min(rbase + rblk + 32 * (j >> 2) + 8 * (j & 3), rows - 1) * ld64);
     }
   };
   // rows past the split (and feature blocks past the operand) are zeroed here, when the data is consumed,
@@ -456,13 +491,13 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(gmi::WgradBatch batch, 
     } else {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const uint32_t k = (rbase + rblk * 8 + j < row_end && feat_ok) ? 0xFFFFFFFFu : 0u;
+        const uint32_t k = (rbase + rblk + 32 * (j >> 2) + 8 * (j & 3) < row_end && feat_ok) ? 0xFFFFFFFFu : 0u;
         m[j] = make_uint4(st[j].x & k, st[j].y & k, st[j].z & k, st[j].w & k);
       }
     }
     transpose8x8(m, tr);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4*>(&s_stage[buf * kBuf + sdst + i * kLds]) = tr[i];
+    for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4*>(&s_stage[buf * kBuf + sdst_i[i]]) = tr[i];
   };
   auto compute = [&](int buf) {
     const uint16_t* s_a = s_stage + buf * kBuf;
@@ -529,6 +564,18 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(gmi::WgradBatch batch, 
       if (do_bias && (lane & 31) == 0) dst[P.b_off + o] = accb[i][v];
     }
   }
+}
+
+__global__ __launch_bounds__(256) void wgrad_bf16_kernel(gmi::WgradBatch batch, int rows, int n_split,
+                                                         int chunk, float* __restrict__ part,
+                                                         int64_t part_stride) {
+  __shared__ __attribute__((aligned(16))) uint16_t s_stage[2 * kWgradBuf];
+  int pi = 0;
+  while (pi + 1 < batch.n && (int)blockIdx.x >= batch.blk_start[pi + 1]) ++pi;
+  const gmi::WgradProblem& P = batch.p[pi];
+  const int local = blockIdx.x - batch.blk_start[pi];
+  if (P.dz_blocks) wgrad_tile<1>(P, local, rows, n_split, chunk, part, part_stride, s_stage);
+  else wgrad_tile<0>(P, local, rows, n_split, chunk, part, part_stride, s_stage);
 }
 
 // ------------------------------------------------------------------------------------------------

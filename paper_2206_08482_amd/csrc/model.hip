@@ -303,6 +303,7 @@ extern "C" int gmi_model_bind(gmi_t g, const gmi_model_desc* d, float* params, v
     // (and loads) the ragged last tile without bounds checks; rows past the batch are never used
     const int64_t arows = (rows + 255) / 256 * 256;
     m->x0 = take(arows * gmi::pad32(L.obs_dim) * es);
+    m->x0b = take(arows * gmi::pad32(L.obs_dim) * es);      // the same rows in the row-tile trainer kernel's block layout
     for (int net = 0; net < 2; ++net) {
       m->h[net][0] = m->x0;
       for (int l = 0; l < L.n_layers; ++l) {

@@ -142,7 +142,7 @@ extern "C" int gmi_bench_linear(gmi_t g, int kind, int rows, int K, int F, int n
     q.x = x; q.ldx = K; q.w = w; q.ldw = K; q.wsf = K; q.wsk = 1; q.bias = bias; q.h = h; q.ldh = F; q.y = y; q.ldy = F;
     q.K = K; q.F = F; q.F_store = F; q.K_log = K; q.F_log = F;
     gmi::WgradProblem& r = wb.p[z];            // dW[F, K] = y^T x
-    r.dz = y; r.lddz = F; r.x = x; r.ldx = K; r.out = F; r.in = K; r.out_pad = F; r.in_pad = K;
+    r.dz = y; r.lddz = F; r.x = x; r.ldx = K; r.out = F; r.in = K; r.out_pad = F; r.in_pad = K; r.dz_blocks = r.x_blocks = 0;
     r.w_off = (int64_t)z * ((int64_t)K * F + F); r.b_off = r.w_off + (int64_t)K * F;
   }
   const int n_split = gmi::wgrad_split_limit(n_nets * ((F + 127) / 128) * ((K + 127) / 128));

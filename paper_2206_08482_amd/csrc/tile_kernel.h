@@ -16,7 +16,7 @@
 // k step are written back to LDS as one 16-byte piece at its own lane's slot.
 //
 // A layer is: k loop (all accumulators of the layer live at once) - barrier - epilogue (bias + ELU, or x ELU' of
-// the stored activation; conversion; the results into LDS in place of the layer's input, and row-major to memory
+// the stored activation; conversion; the results into LDS in place of the layer's input; from there they go to memory
 // for the weight-gradient kernel) - barrier.  The next layer's first weight blocks are fetched before the epilogue.
 #pragma once
 #include "chain_kernel.h"
@@ -83,14 +83,13 @@ struct Seg {
   static constexpr int XD = FTW >= 4 ? 1 : 2;             // k steps the activation blocks are read ahead (a k step of
                                                           // fewer products is shorter than an LDS round trip)
   static constexpr int blk0 = S::seg_blk0(SEG);
-  // The segment's input, which the previous segment's epilogue left in LDS, goes row-major to memory (for the
+  // The segment's input, which the previous segment's epilogue left in LDS, goes to memory block by block (for the
   // weight-gradient kernel and for ELU') DURING this segment's k loop: h[layer] in a forward segment, dz[layer] in an
   // input-gradient segment.  (Stores issued in the epilogue would all be older than the next k loop's weight
   // fetches, and the memory counter is in order: the loop would wait for every one of them.)  Not for the first
   // segment (the gather stores its rows) nor the first input-gradient segment (the loss epilogue stores the head's).
   static constexpr int HK = NKS > 6 ? NKS - 6 : 0;        // k step at which an input-gradient segment starts to fetch ELU' inputs
   static constexpr bool store_x = (SEG >= 1 && SEG <= S::NL - 1) || SEG > S::NL;
-  static_assert(!store_x || NKS % 2 == 0, "the store walks the k steps in pairs");
   static_assert(head || NFT % kWaves == 0, "feature tiles divide over the waves");
   static_assert(!head || NFT == 1, "the head is one 32-wide tile");
 };
@@ -100,8 +99,8 @@ struct Ctx {
   floatx16 acc[4][4];
   uint4 wq[kRing];                   // weight blocks of k steps g .. g + DEP - 1: block (ks, a) at (ks % DEP) * FTW + a
   uint4 xq[3][4];                    // activation blocks of k steps g .. g + XD (ring indexed by k step % 3)
-  uint4 sx[2];                       // a row's two halves of a k step on their way to memory (store_x)
-  uint2 hq[kHPre + 1][4];            // stored activations of the tiles ahead (input-gradient epilogues)
+  uint4 sx[2];                       // blocks of the activation area on their way to memory (store_x)
+  uint4 hq[kHPre + 1][2];            // stored activations of the tiles ahead (input-gradient epilogues)
   const uint4* wnet;                 // this net's stream
   uint4* X;                          // activation area
   const float* s_bias;
@@ -152,18 +151,85 @@ __device__ __forceinline__ void read_x(Ctx<S>& c) {
   }
 }
 
-// Stored activations h[layer] of tile T = a * RT + b of this wave (input-gradient epilogue of segment SEG): for
-// every quad q the 4 features 32 ft + 8 q + 4 hh .. + 3 of sample 32 b + s.
+// Block layout of the activation / gradient arrays this kernel leaves for the weight-gradient kernel and for its own
+// ELU' factors: exactly the 1 KiB operand blocks of the activation area, workgroup tile after workgroup tile:
+// block (k step ks, row tile rt) of the 128 rows of tile tr of an array of NKS k steps starts at 16-byte word
+// ((tr * NKS + ks) * 4 + rt) * 64.  (Row-major, a lane's 8 values of a k step are two 8-byte pieces of a row:
+// 32 rows x 16 bytes per load or store instruction; as blocks every access is 1 KiB contiguous.)
+__device__ __forceinline__ int64_t block_word(int tr, int nks, int ks, int rt) { return (((int64_t)tr * nks + ks) * 4 + rt) * 64; }
+
+// Stored activations h[layer] of tile T = a * RT + b of this wave (input-gradient epilogue of segment SEG): the
+// lane's own slots of the blocks (2 ft, b) and (2 ft + 1, b), i.e. the values at the positions of its 16 results.
 template <class S, int SEG, int T>
 __device__ __forceinline__ void fetch_h(Ctx<S>& c, const ChainArgs& a) {
   using G = Seg<S, SEG>;
   if constexpr (G::bwd && T < G::FTW * G::RT && !TILE_X_NOH) {
     constexpr int ta = T / G::RT, tb = T % G::RT;
-    constexpr int ld = G::D.d[G::layer];
+    constexpr int nks = G::D.d[G::layer] / 16;
     const int ft = c.wave * G::FTW + ta;
-    const uint16_t* p = a.h[c.net][G::layer] + (int64_t)(c.row0 + 32 * tb + c.s) * ld + 32 * ft + 4 * c.hh;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) c.hq[T % (kHPre + 1)][q] = *reinterpret_cast<const uint2*>(p + 8 * q);
+    const uint4* p = reinterpret_cast<const uint4*>(a.h[c.net][G::layer]) + block_word(blockIdx.x, nks, 2 * ft, tb) + c.lane;
+    c.hq[T % (kHPre + 1)][0] = p[0];
+    c.hq[T % (kHPre + 1)][1] = p[4 * 64];
+  }
+}
+
+// The small operations that ride along with the products of k step KS, by index I: I < RT: the activation block of
+// row tile I for k step KS + XD; then, where the segment's input goes to memory (store_x), wave w's share of that
+// move: I = RT reads block (KS, w) of the activation area, I = RT + 1 stores the block read a k step earlier.
+template <class S, int SEG>
+__device__ __forceinline__ uint4* store_x_array(const Ctx<S>& c, const ChainArgs& a) {
+  using G = Seg<S, SEG>;
+  return reinterpret_cast<uint4*>(G::bwd ? a.dz[c.net][G::layer] : a.h[c.net][G::layer]);
+}
+template <class S, int SEG, int KS, int I>
+__device__ __forceinline__ void aux_op(Ctx<S>& c, const ChainArgs& a) {
+  using G = Seg<S, SEG>;
+  if constexpr (I < G::RT) {
+    if constexpr (KS + G::XD < G::NKS)
+      c.xq[(KS + G::XD) % 3][I] = c.X[((KS + G::XD) * 4 + (G::head ? c.wave : I)) * 64 + c.lane];
+  } else if constexpr (G::store_x && !TILE_X_NOSTORE) {
+    if constexpr (I == G::RT) {
+      c.sx[KS & 1] = c.X[(KS * 4 + c.wave) * 64 + c.lane];
+    } else if constexpr (KS >= 1) {
+      (store_x_array<S, SEG>(c, a) + block_word(blockIdx.x, G::NKS, KS - 1, c.wave))[c.lane] = c.sx[(KS - 1) & 1];      // arrays hold whole tiles
+    }
+  }
+}
+template <class S, int SEG, int KS, int FIDX, int I>
+__device__ __forceinline__ void aux_slot(Ctx<S>& c, const ChainArgs& a) {
+  using G = Seg<S, SEG>;
+  constexpr int NAUX = G::RT + 2, NFREE = G::FTW * (G::RT - 1);
+  if constexpr (I < NAUX) {
+    if constexpr (I % NFREE == FIDX) aux_op<S, SEG, KS, I>(c, a);
+    aux_slot<S, SEG, KS, FIDX, I + 1>(c, a);
+  }
+}
+
+// Product M = a * RT + b of k step KS and what follows it.  A wave issues in order and a matrix instruction keeps
+// its unit busy for 32 cycles: the fetches and address arithmetic of a k step, issued in one block, leave the unit
+// idle meanwhile (measured: ~100-170 of a k step's 256 / 512 cycles), one or two of them after every product do not.
+// The next weight block of feature tile a follows the last product that reads the present one.
+template <class S, int SEG, int KS, int M>
+__device__ __forceinline__ void k_products(Ctx<S>& c, const ChainArgs& a, const uint4* wseg) {
+  using G = Seg<S, SEG>;
+  if constexpr (M < G::FTW * G::RT) {
+    constexpr int ta = M / G::RT, tb = M % G::RT;
+    c.acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+        __builtin_bit_cast(bf16x8, c.wq[(KS % G::DEP) * G::FTW + ta]), __builtin_bit_cast(bf16x8, c.xq[KS % 3][tb]),
+        c.acc[ta][tb], 0, 0, 0);
+    if constexpr (tb == G::RT - 1) {
+      if constexpr (KS + G::DEP < G::NKS)
+        c.wq[(KS % G::DEP) * G::FTW + ta] = (wseg + ((KS + G::DEP) * G::GS + ta) * 64)[c.lane];
+      if constexpr (G::RT == 1) {                                 // the head: one product per k step
+        aux_op<S, SEG, KS, 0>(c, a);
+        aux_op<S, SEG, KS, 1>(c, a);
+        aux_op<S, SEG, KS, 2>(c, a);
+      }
+    } else {
+      aux_slot<S, SEG, KS, ta * (G::RT - 1) + tb, 0>(c, a);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    k_products<S, SEG, KS, M + 1>(c, a, wseg);
   }
 }
 
@@ -171,38 +237,13 @@ template <class S, int SEG, int KS>
 __device__ __forceinline__ void k_steps(Ctx<S>& c, const ChainArgs& a, const uint4* wseg) {
   using G = Seg<S, SEG>;
   if constexpr (KS < G::NKS) {
-    bf16x8 wa[G::FTW];
-#pragma unroll
-    for (int a = 0; a < G::FTW; ++a) wa[a] = __builtin_bit_cast(bf16x8, c.wq[(KS % G::DEP) * G::FTW + a]);
-    issue_weights<S, SEG, KS + G::DEP>(c, wseg);
-    read_x<S, SEG, KS + G::XD>(c);
     if constexpr (G::bwd && KS == G::HK) {          // the first tiles' stored activations, late enough not to hold up
       fetch_h<S, SEG, 0>(c, a);                     // the weight fetches behind them, early enough to be there
       fetch_h<S, SEG, 1>(c, a);
       fetch_h<S, SEG, 2>(c, a);
       static_assert(kHPre == 3, "three tiles ahead");
     }
-    if constexpr (G::store_x && !TILE_X_NOSTORE) {
-      // wave w moves row tile w: lane (s, kk) takes sample s's 16 values of k step KS + kk -- the halves h = 0 / 1
-      // of the block hold values {0..3, 8..11} / {4..7, 12..15} -- and stores them as two 16-byte pieces one k step later
-      if constexpr (KS % 2 == 0) {
-        const uint4* blk = c.X + ((KS + c.hh) * 4 + c.wave) * 64 + c.s;
-        c.sx[0] = blk[0];
-        c.sx[1] = blk[32];
-      } else {
-        uint16_t* arr = G::bwd ? a.dz[c.net][G::layer] : a.h[c.net][G::layer];
-        uint4* dst = reinterpret_cast<uint4*>(arr + (int64_t)(c.row0 + 32 * c.wave + c.s) * G::K + 16 * (KS - 1 + c.hh));
-        dst[0] = make_uint4(c.sx[0].x, c.sx[0].y, c.sx[1].x, c.sx[1].y);      // arrays hold whole tiles
-        dst[1] = make_uint4(c.sx[0].z, c.sx[0].w, c.sx[1].z, c.sx[1].w);
-      }
-    }
-#pragma unroll
-    for (int a = 0; a < G::FTW; ++a)
-#pragma unroll
-      for (int b = 0; b < G::RT; ++b)
-        c.acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], __builtin_bit_cast(bf16x8, c.xq[KS % 3][b]), c.acc[a][b], 0, 0, 0);
-    // nothing moves across this point: the fetches stay ahead of the products they feed
-    __builtin_amdgcn_sched_barrier(0);
+    k_products<S, SEG, KS, 0>(c, a, wseg);
     k_steps<S, SEG, KS + 1>(c, a, wseg);
   }
 }
@@ -221,9 +262,10 @@ __device__ __forceinline__ void tile_epilogue(Ctx<S>& c, const ChainArgs& a) {
     for (int q = 0; q < 4; ++q) {
       float v0 = acc[4 * q + 0], v1 = acc[4 * q + 1], v2 = acc[4 * q + 2], v3 = acc[4 * q + 3];
       if constexpr (G::bwd) {
-        const uint2 hv = TILE_X_NOH ? make_uint2(0x3f803f80u, 0xbf003f80u) : c.hq[T % (kHPre + 1)][q];
-        v0 *= elu_grad_f(bf16_lo(hv.x)); v1 *= elu_grad_f(bf16_hi(hv.x));
-        v2 *= elu_grad_f(bf16_lo(hv.y)); v3 *= elu_grad_f(bf16_hi(hv.y));
+        const uint4 hb = c.hq[T % (kHPre + 1)][q / 2];
+        const uint32_t h01 = q % 2 == 0 ? hb.x : hb.z, h23 = q % 2 == 0 ? hb.y : hb.w;
+        v0 *= elu_grad_f(bf16_lo(h01)); v1 *= elu_grad_f(bf16_hi(h01));
+        v2 *= elu_grad_f(bf16_lo(h23)); v3 *= elu_grad_f(bf16_hi(h23));
       } else {
         v0 = elu_f(v0); v1 = elu_f(v1); v2 = elu_f(v2); v3 = elu_f(v3);      // the bias is in the sums already
       }
@@ -251,7 +293,8 @@ __device__ __forceinline__ void fetch_loss_inputs(Ctx<S>& c, const ChainArgs& a)
 
 // Loss on the wave's 32 samples (row tile `wave` of the workgroup) from the head's accumulators: lane = sample s,
 // half hh; register i = feature 8 (i / 4) + 4 hh + i % 4.  Leaves the head gradient as the two k steps of the first
-// input-gradient product in the activation area, row-major in dz[NL - 1], and the workgroup's statistics row.
+// input-gradient product in the activation area and, as the same blocks, in dz[NL - 1], and the workgroup's
+// statistics row.
 template <class S>
 __device__ __forceinline__ void loss_epilogue(Ctx<S>& c, const ChainArgs& a, const floatx16& acc) {
   constexpr int HB = S::bias_off(S::NL - 1);
@@ -331,10 +374,11 @@ __device__ __forceinline__ void loss_epilogue(Ctx<S>& c, const ChainArgs& a, con
   for (int q = 0; q < 8; ++q) w[q] = pack_bf16(d[2 * q], d[2 * q + 1]);
   c.X[(0 * 4 + c.wave) * 64 + c.lane] = make_uint4(w[0], w[1], w[2], w[3]);
   c.X[(1 * 4 + c.wave) * 64 + c.lane] = make_uint4(w[4], w[5], w[6], w[7]);
-#pragma unroll
-  for (int q = 0; q < 4; ++q)
-    *reinterpret_cast<uint2*>(c.scr + c.s * kScrStride + (8 * q + 4 * c.hh) * 2) = make_uint2(w[2 * q], w[2 * q + 1]);
-  scr_to_global<1>(c.scr, c.lane, a.dz[c.net][S::NL - 1], 32, 0, wrow0, a.rows);
+  {
+    uint4* arr = reinterpret_cast<uint4*>(a.dz[c.net][S::NL - 1]);
+    (arr + block_word(blockIdx.x, 2, 0, c.wave))[c.lane] = make_uint4(w[0], w[1], w[2], w[3]);      // arrays hold whole tiles
+    (arr + block_word(blockIdx.x, 2, 1, c.wave))[c.lane] = make_uint4(w[4], w[5], w[6], w[7]);
+  }
   // workgroup sums -> this tile's row of the statistics partials
   __syncthreads();
   float* out = a.stat_part + (int64_t)blockIdx.x * (gmi::kStatStride + A);
@@ -399,6 +443,8 @@ __device__ __forceinline__ void run_segment(Ctx<S>& c, const ChainArgs& a) {
     read_x<S, SEG, 0>(c);
     if constexpr (G::XD > 1) read_x<S, SEG, 1>(c);
     k_steps<S, SEG, 0>(c, a, wseg);
+    if constexpr (G::store_x && !TILE_X_NOSTORE)
+      (store_x_array<S, SEG>(c, a) + block_word(blockIdx.x, G::NKS, G::NKS - 1, c.wave))[c.lane] = c.sx[(G::NKS - 1) & 1];
 #ifdef GMI_CHAIN_TIMING
     c.ts[3 * SEG + 1] = __builtin_readcyclecounter();
 #endif
@@ -417,17 +463,12 @@ __device__ __forceinline__ void run_segment(Ctx<S>& c, const ChainArgs& a) {
     }
     __syncthreads();
     if constexpr (G::last) {
-      // nothing consumes the last results on chip: row tile `wave` of the activation area goes row-major to
-      // dz[layer - 1] the way a k loop moves its input (k_steps)
-      uint16_t* arr = a.dz[c.net][G::layer - 1];
-#pragma unroll 4
-      for (int ks = 0; ks < G::F / 16; ks += 2) {
-        const uint4* blk = c.X + ((ks + c.hh) * 4 + c.wave) * 64 + c.s;
-        const uint4 lo = blk[0], hi = blk[32];
-        uint4* dst = reinterpret_cast<uint4*>(arr + (int64_t)(c.row0 + 32 * c.wave + c.s) * G::F + 16 * (ks + c.hh));
-        dst[0] = make_uint4(lo.x, lo.y, hi.x, hi.y);      // arrays hold whole tiles
-        dst[1] = make_uint4(lo.z, lo.w, hi.z, hi.w);
-      }
+      // nothing consumes the last results on chip: row tile `wave` of the activation area goes to dz[layer - 1]
+      // block by block, the way a k loop moves its input
+      uint4* arr = reinterpret_cast<uint4*>(a.dz[c.net][G::layer - 1]);
+#pragma unroll 8
+      for (int ks = 0; ks < G::F / 16; ++ks)
+        (arr + block_word(blockIdx.x, G::F / 16, ks, c.wave))[c.lane] = c.X[(ks * 4 + c.wave) * 64 + c.lane];      // arrays hold whole tiles
     }
 #ifdef GMI_CHAIN_TIMING
     if constexpr (G::last) c.ts[3 * SEG + 3] = __builtin_readcyclecounter();
@@ -487,7 +528,7 @@ __global__ __launch_bounds__(kWaves * 64) void train_tile_kernel(ChainArgs a) {
     // The gather: the workgroup's 128 observation rows as the first layer's operand blocks in natural k order (lane
     // (s, h) of block (ks, rt) holds features 16 ks + 8 h .. + 7 of sample 32 rt + s), zero padded.  A lane takes
     // 16-byte piece jj + 4 it of row 16 g + rr: 16 lanes write 256 consecutive bytes of LDS, 4 lanes read 64
-    // consecutive bytes of a row.  The policy net's workgroups also leave the bf16 rows in x0 for the
+    // consecutive bytes of a row.  The policy net's workgroups also leave the same blocks in x0b for the
     // weight-gradient kernel.  All loads unconditional (clamped addresses, selected values).
     constexpr int NP = D.d[0] / 8;                       // 16-byte pieces of a row
     const int rr = c.lane & 15, jj = c.lane >> 4;
@@ -533,17 +574,17 @@ __global__ __launch_bounds__(kWaves * 64) void train_tile_kernel(ChainArgs a) {
         }
       }
     }
-    const bool keep = a.x0_ready != 1 && c.net == 0;
+    uint4* xb = reinterpret_cast<uint4*>(a.x0b) + block_word(blockIdx.x, D.d[0] / 16, 0, 0);
 #pragma unroll
     for (int gi = 0; gi < 2; ++gi) {
       const int r = 16 * (c.wave + kWaves * gi) + rr;
-      uint16_t* xw = a.x0 + (int64_t)(c.row0 + r) * D.d[0];
 #pragma unroll
       for (int it = 0; it < NI; ++it) {
         const int j = 4 * it + jj;
         if (j < NP) {
-          c.X[((j >> 1) * 4 + (r >> 5)) * 64 + (r & 31) + 32 * (j & 1)] = v[gi][it];
-          if (keep) *reinterpret_cast<uint4*>(xw + 8 * j) = v[gi][it];      // arrays hold whole tiles
+          const int w = ((j >> 1) * 4 + (r >> 5)) * 64 + (r & 31) + 32 * (j & 1);
+          c.X[w] = v[gi][it];
+          if (c.net == 0) xb[w] = v[gi][it];      // arrays hold whole tiles
         }
       }
     }

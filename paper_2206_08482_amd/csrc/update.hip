@@ -442,6 +442,7 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
   const ModelLayout& L = m->L;
   const bool bf = L.dtype == GMI_DTYPE_BF16;
   int rc = GMI_ERR_UNSUPPORTED;
+  bool blocks = false;
   if (g->fusion >= 2 && want_grad && allow_fused) {
     // row-tile fused kernel (opt-in): statistics already summed (row kLossBlocksMax of stat_part)
     rc = gmi::launch_train_fused(g, m, b, hp, idx, rows);
@@ -449,7 +450,7 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
   }
   if (rc == GMI_ERR_UNSUPPORTED && g->fusion >= 1 && want_grad && bf) {
     // register-chained kernel (gather + forward + loss + input gradients in one launch) where this shape has one
-    rc = gmi::launch_train_chain(g, m, b, hp, idx, rows, n_loss_blocks_out, obs16_ready);
+    rc = gmi::launch_train_chain(g, m, b, hp, idx, rows, n_loss_blocks_out, obs16_ready, &blocks);
   }
   if (rc == GMI_ERR_UNSUPPORTED) rc = layers_pass(g, m, b, hp, idx, rows, want_grad, n_loss_blocks_out);
   if (rc != GMI_OK || !want_grad) return rc;
@@ -470,6 +471,10 @@ int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_h
       p.x = m->h[net][l]; p.ldx = li.in_pad;
       p.out = li.out; p.in = li.in; p.out_pad = li.out_pad; p.in_pad = li.in_pad;
       p.w_off = li.w_off; p.b_off = li.b_off;
+      // the row-tile kernel leaves every activation and every gradient in its block layout
+      if (blocks && l == 0) p.x = m->x0b;
+      p.x_blocks = blocks ? (l == 0 ? 2 : 1) : 0;
+      p.dz_blocks = blocks ? 1 : 0;
     }
   return gmi::launch_wgrad(g, L.dtype, rows, n_split, chunk, wb, m->grad_part, L.n_params);
 }
