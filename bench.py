@@ -5,7 +5,11 @@ A "step" is one whole PPO iteration over one batch of synthetic experience: T ro
 [agent_act -> env_step -> collect_experience], the bootstrap value, gae_compute, and ppo_update
 (E epochs of shuffled minibatches: forward, loss, backward, Adam).  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C4] [--no-cpu-baseline] [--no-extras]
+
+The default run also reports, as extra keys of the same line, the step times of the other single-instance
+workloads, the agent/trainer CU-split sweep of the multi-instance configuration (benchmarks/instances.py) and the
+bandwidth-bound kernels on scaled inputs (benchmarks/kernels.py).
 """
 from __future__ import annotations
 
@@ -101,7 +105,10 @@ def class_work(cfg, n_params, launched):
 
 
 def cpu_baseline(cfg, budget_s=12.0):
-    """The numpy oracle, as it stands, on the host cores: whole iterations of the same workload."""
+    """The numpy oracle, as it stands, on the host cores: whole iterations of the same workload -- of a slice of
+    its environments where one iteration of all of them would take minutes (the sample is stated in the result)."""
+    import dataclasses
+
     import numpy as np
 
     from oracle import ppo as oppo
@@ -112,51 +119,40 @@ def cpu_baseline(cfg, budget_s=12.0):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = 1
-    shape, theta, env, state0, hp = oracle_pieces(cfg)
+    # about 2e11 matrix-product flops per iteration keep one iteration within the budget on a host like the GPU machine's
+    _, flops_iter = class_work(cfg, 0, {})
+    n_envs = cfg.n_envs
+    while flops_iter * n_envs / cfg.n_envs > 1.2e12 and n_envs * cfg.horizon > cfg.minibatch and n_envs % 2 == 0:
+        n_envs //= 2
+    sub = dataclasses.replace(cfg, n_envs=n_envs) if n_envs != cfg.n_envs else cfg
+    shape, theta, env, state0, hp = oracle_pieces(sub)
     z = np.zeros_like(theta)
     n_it, t0 = 0, time.perf_counter()
     m, v, k = z, z, 0
     while True:
-        out = oppo.ppo_iteration(theta, m, v, k, shape, env, state0, np.zeros(cfg.n_envs, np.uint32), cfg.horizon,
-                                 hp, cfg.gamma, cfg.lam, cfg.seed, n_it)
+        out = oppo.ppo_iteration(theta, m, v, k, shape, env, state0, np.zeros(sub.n_envs, np.uint32), sub.horizon,
+                                 hp, sub.gamma, sub.lam, sub.seed, n_it)
         theta, m, v, k = out["theta"], out["m"], out["v"], out["k"]
         n_it += 1
         el = time.perf_counter() - t0
         if el >= budget_s or el * (n_it + 1) / n_it > 2.5 * budget_s:
             break
-    return {"value": n_it * cfg.batch / el, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{n_it} whole iteration(s) of {cfg.name} ({cfg.batch} samples each, fresh reset) in {el:.1f} s, "
-                      "numpy fp32 with its BLAS threads"}
+    what = (f"{n_it} whole iteration(s) of {cfg.name}" if sub is cfg else
+            f"{n_it} whole iteration(s) of {cfg.name} on {sub.n_envs} of its {cfg.n_envs} environments (same horizon, "
+            f"epochs and minibatch size)")
+    return {"value": n_it * sub.batch / el, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{what} ({sub.batch} samples each, fresh reset) in {el:.1f} s, numpy fp32 with its BLAS threads"}
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="C2")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--fusion", type=int, default=None,
-                    help="fusion level of the instance (0 per-layer kernels only, 1 fused agent/rollout, "
-                         "2 also the row-tile fused trainer); default: the library's")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (its instances are CU-masked streams of one device); "
-              f"--gpus {args.gpus} is not supported", file=sys.stderr)
-        return 2
+# kernel classes whose work is matrix products (judged against the matrix-core roof)
+def is_matrix_class(name):
+    return name in ("chain_train", "wgrad", "fused_agent", "fused_train", "fused_rollout") or name.startswith("linear_")
 
-    import numpy as np
-    import torch
 
-    import paper_2206_08482_amd as g
-    from paper_2206_08482_amd.runner import PPOSession
-    from workloads import synthetic as syn
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-
-    cfg = syn.get_config(args.config)
-    if cfg.n_agents != 1:
-        print("bench.py: multi-instance configurations are measured by bench_instances.py", file=sys.stderr)
-        return 2
+def run_workload(g, torch, syn, PPOSession, name, steps, warmup, fusion=None, detail=True):
+    """Times `steps` whole PPO iterations of workload `name` on one unmasked instance.  detail: also the per-class
+    kernel times of the last warm-up step and the launch timer on the dominant class during the timed steps."""
+    cfg = syn.get_config(name)
     theta = syn.make_model_params(cfg.obs_dim, cfg.act_dim, cfg.hidden, cfg.seed)
     a_mat, b_mat = syn.make_env_matrices(cfg.obs_dim, cfg.act_dim, cfg.seed)
     state0 = syn.make_initial_state(cfg.n_envs, cfg.obs_dim, cfg.seed)
@@ -165,9 +161,9 @@ def main() -> int:
                      horizon=cfg.horizon, dtype=cfg.dtype, theta=theta, a_mat=a_mat, b_mat=b_mat, state0=state0,
                      noise_std=cfg.noise_std, reward_scale=cfg.reward_scale, done_period=cfg.done_period,
                      done_threshold=thr, seed=cfg.seed, minibatch=cfg.minibatch)
-    if args.fusion is not None:
-        g.gmi_set_fusion(ses.gmi, args.fusion)
-        ses.fused_rollout = ses.fused_rollout and args.fusion >= 1
+    if fusion is not None:
+        g.gmi_set_fusion(ses.gmi, fusion)
+        ses.fused_rollout = ses.fused_rollout and fusion >= 1
     s0 = torch.tensor(state0, device="cuda:0")
     ep0 = torch.zeros(cfg.n_envs, dtype=torch.int32, device="cuda:0")
     torch.cuda.synchronize()
@@ -186,39 +182,81 @@ def main() -> int:
     n_cls = g.gmi_profile_classes()
     names = [g.gmi_profile_class_name(c) for c in range(n_cls)]
     it = 0
-    for _ in range(max(args.warmup - 1, 0)):
+    res = {"cfg": cfg, "n_params": int(ses.theta.numel())}
+    for _ in range(max(warmup - 1, 0)):
         step(it); it += 1
-    # last warm-up step with every class timed: finds the kernel class that dominates the step
-    g.gmi_profile_enable(ses.gmi, (1 << n_cls) - 1)
+    if detail:
+        # last warm-up step with every class timed: finds the kernel class that dominates the step
+        g.gmi_profile_enable(ses.gmi, (1 << n_cls) - 1)
     step(it); it += 1
-    per_class = {names[c]: g.gmi_profile_read(ses.gmi, c) for c in range(n_cls)}
-    dominant = max(per_class, key=lambda k: per_class[k][0])
-    g.gmi_profile_enable(ses.gmi, 1 << names.index(dominant))
+    if detail:
+        per_class = {names[c]: g.gmi_profile_read(ses.gmi, c) for c in range(n_cls)}
+        dominant = max(per_class, key=lambda k: per_class[k][0])
+        g.gmi_profile_enable(ses.gmi, 1 << names.index(dominant))
+        res.update(per_class=per_class, dominant=dominant)
 
     ses.sync(); torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step(it); it += 1
     ses.sync(); torch.cuda.synchronize()
     t1 = time.perf_counter()
-    dom_ms, dom_launches = g.gmi_profile_read(ses.gmi, names.index(dominant))
-    dom_flops, dom_bytes = g.gmi_profile_work(ses.gmi, names.index(dominant))
-    g.gmi_profile_enable(ses.gmi, 0)
+    if detail:
+        res["dom_ms"], res["dom_launches"] = g.gmi_profile_read(ses.gmi, names.index(dominant))
+        res["dom_flops"], res["dom_bytes"] = g.gmi_profile_work(ses.gmi, names.index(dominant))
+        g.gmi_profile_enable(ses.gmi, 0)
     assert torch.isfinite(ses.theta).all().item(), "parameters are not finite after the timed steps"
+    res["seconds"] = t1 - t0
 
     # rollout alone (env-steps/s), untimed part of the report
     ses.sync()
     r0 = time.perf_counter()
-    for _ in range(max(1, args.steps // 2)):
+    for _ in range(max(1, steps // 2)):
         g.gmi_transfer(ses.gmi, ses.gmi, s0, ses.obs[ses.cur], s0.numel() * 4)
         ses.rollout(it); it += 1
     ses.sync()
-    r1 = time.perf_counter()
-    env_steps_per_s = max(1, args.steps // 2) * cfg.batch / (r1 - r0)
+    res["env_steps_per_s"] = max(1, steps // 2) * cfg.batch / (time.perf_counter() - r0)
+    ses.close()
+    return res
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    value = args.steps * cfg.batch / (t1 - t0)
-    work, flops_step = class_work(cfg, int(ses.theta.numel()), {k: v[1] for k, v in per_class.items()})
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="C4",
+                    help="C4 (default): the largest single-instance workload, the one the matrix-core target is set on")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the other workloads, the instance-split sweep and the scaled bandwidth kernels")
+    ap.add_argument("--fusion", type=int, default=None,
+                    help="fusion level of the instance (0 per-layer kernels only, 1 fused agent/rollout and trainer "
+                         "kernels); default: the library's")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (its instances are CU-masked streams of one device); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2206_08482_amd as g
+    from paper_2206_08482_amd.runner import PPOSession
+    from workloads import synthetic as syn
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+    if syn.get_config(args.config).n_agents != 1:
+        print("bench.py: the multi-instance configuration is measured by benchmarks/instances.py (its summary is in "
+              "the default run's c5_split_sweep)", file=sys.stderr)
+        return 2
+    r = run_workload(g, torch, syn, PPOSession, args.config, args.steps, args.warmup, args.fusion)
+    cfg, per_class, dominant = r["cfg"], r["per_class"], r["dominant"]
+    dom_ms, dom_launches, dom_flops, dom_bytes = r["dom_ms"], r["dom_launches"], r["dom_flops"], r["dom_bytes"]
+
+    ms_per_step = r["seconds"] * 1e3 / args.steps
+    value = args.steps * cfg.batch / r["seconds"]
+    work, flops_step = class_work(cfg, r["n_params"], {k: v[1] for k, v in per_class.items()})
     avg_ms = dom_ms / max(dom_launches, 1)
     if dom_flops > 0 or dom_bytes > 0:          # stated by the launcher for exactly the timed launches
         flops_per_launch, bytes_per_launch = dom_flops / dom_launches, dom_bytes / dom_launches
@@ -226,24 +264,31 @@ def main() -> int:
         w = work.get(dominant, {"launches": 1})       # a class without stated work (only ever dominant under a profiler)
         flops_per_launch = w.get("flops", 0.0) / max(w["launches"], 1)
         bytes_per_launch = w.get("bytes", 0.0) / max(w["launches"], 1)
-    # the roof that bounds this kernel: the larger of its matrix-core time and its HBM time at the peaks
+    # the roof: a kernel made of matrix products is judged against the matrix cores (unpadded 2 * MAC flops of its
+    # launch / its time / the dense peak of its operand type), every other kernel against HBM
     peak_flops = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
-    if flops_per_launch / (peak_flops * 1e12) >= bytes_per_launch / (PEAK_HBM_GBS * 1e9):
+    traffic = MEASURED_TRAFFIC.get((cfg.name, dominant))
+    if is_matrix_class(dominant) and flops_per_launch > 0:
         roof = {"bound": "mfma", "achieved": flops_per_launch / (avg_ms * 1e-3) / 1e12, "peak": peak_flops,
                 "unit": "TFLOP/s"}
     else:
         roof = {"bound": "hbm", "achieved": bytes_per_launch / (avg_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                 "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = MEASURED_TRAFFIC.get((cfg.name, dominant))
+    roof["traffic"] = traffic
     roof["kernel"] = dominant
     roof["avg_launch_us"] = avg_ms * 1e3
     roof["launches_timed"] = dom_launches
-    roof["tflops"] = flops_per_launch / (avg_ms * 1e-3) / 1e12
+    roof["algorithmic_flops_per_launch"] = flops_per_launch
+    # the HBM view of the same launches: the bytes the launcher calls algorithmic for its present design, and the
+    # measured traffic, each over the kernel's time and the 8 TB/s peak
     roof["algorithmic_bytes_per_launch"] = bytes_per_launch
+    roof["hbm_frac_algorithmic"] = bytes_per_launch / (avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS
+    roof["hbm_frac_measured"] = traffic / (avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if traffic else None
 
     total_ms = sum(v[0] for v in per_class.values())
     breakdown = {k: {"ms_per_step": round(v[0], 4), "launches": v[1]} for k, v in per_class.items() if v[1]}
+    whole_tflops = flops_step / (ms_per_step * 1e-3) / 1e12
     out = {
         "metric": "PPO samples/sec (rollout+update) on 1 MI355X",
         "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -254,15 +299,42 @@ def main() -> int:
                                f"minibatch {cfg.minibatch}, linear-Gaussian env, one unmasked instance",
                    "samples_per_step": cfg.batch},
         "roofline": roof,
-        "env_steps_per_s": env_steps_per_s,
-        "mlp_gemm_tflops_whole_step": flops_step / (ms_per_step * 1e-3) / 1e12,
+        "env_steps_per_s": r["env_steps_per_s"],
+        "mlp_gemm_tflops_whole_step": whole_tflops,
+        "mfma_frac_whole_step": whole_tflops / peak_flops,
         "kernel_ms_in_profiled_step": breakdown,
         "kernel_ms_sum": total_ms,
         "paper_context": "GMI-DRL reports up to 2.81x over Isaac Gym+NCCL on DGX-A100 (different hardware, env, baseline)",
     }
+    if not args.no_extras:
+        # the other single-instance workloads (fewer steps), the instance-split sweep of the multi-instance
+        # configuration and the bandwidth-bound kernels on inputs large enough for HBM to bound them
+        others = {}
+        for name in ("C2", "C3", "C4"):
+            if name == cfg.name:
+                continue
+            o = run_workload(g, torch, syn, PPOSession, name, max(5, args.steps // 2), 2, args.fusion, detail=False)
+            n = max(5, args.steps // 2)
+            others[name] = {"ms_per_step": o["seconds"] * 1e3 / n, "samples_per_s": n * o["cfg"].batch / o["seconds"],
+                            "env_steps_per_s": o["env_steps_per_s"]}
+        out["other_workloads"] = others
+        from benchmarks import instances as binst, kernels as bker
+        sw = binst.sweep("C5", steps=4, warmup=2, full=False)
+        out["c5_split_sweep"] = {
+            "workload": sw["workload"], "single_stream_ms": sw["rows"][0]["ms_per_iteration"],
+            "best": sw["best"], "best_vs_single_stream": sw["best_vs_single_stream"],
+            "rows": [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in row.items()
+                      if k in ("layout", "schedule", "hand_off", "ms_per_iteration", "vs_single_stream")}
+                     for row in sw["rows"]]}
+        bk = bker.measure(large_only=True)
+        out["bandwidth_kernels_scaled"] = {
+            "copy_kernel_GBs": bk["copy_kernel_GBs"],
+            "rows": [{"kernel": row["kernel"], "size": row["size"], "GBs": round(row["GBs"], 1),
+                      "frac_of_hbm_peak": round(row["frac_of_hbm_peak"], 4),
+                      **({"fp32_TFLOPs": round(row["fp32_TFLOPs"], 2)} if "fp32_TFLOPs" in row else {})}
+                     for row in bk["rows"]]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
-    ses.close()
     print(json.dumps(out))
     return 0
 

@@ -7,7 +7,7 @@ slabs (interleaved records).  Reports the paper's two throughput metrics of this
 second: env steps the agents serve) and TTOP (training throughput: samples per second the trainer consumes); in
 this lock-step pipeline both equal batch / iteration time.  Prints one JSON object.
 
-    python bench_channels.py [--steps K] [--warmup W]
+    python benchmarks/channels.py [--steps K] [--warmup W]
 """
 from __future__ import annotations
 
@@ -17,7 +17,7 @@ import os
 import sys
 import time
 
-ROOT = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -86,7 +86,7 @@ def main() -> int:
     for lag in (2, 4):
         rows.append(run(f"multi-channel slabs, agents {lag} rounds ahead",
                         lambda: ChannelPipeline(mode=g.CHANNELS_MULTI, capacity=(lag + 1) * n_ag, **common), lag))
-    # the layout that wins in bench_instances.py (agents on disjoint quarters of the device, trainer unmasked, the
+    # the layout that wins in benchmarks/instances.py (agents on disjoint quarters of the device, trainer unmasked, the
     # host orders the hand-offs), through channels
     probe = g.gmi_create()
     n_cu = g.gmi_cu_count(probe)

@@ -5,7 +5,7 @@ n_total / k environments and training a replica of one model on its own experien
 instance doing the same total work.  The union minibatch has the same size in every row, so all rows take
 the same number of Adam steps on the same number of samples.  Prints one JSON object.
 
-    python bench_group.py [--config C2] [--envs 16384] [--steps K] [--warmup W]
+    python benchmarks/group.py [--config C2] [--envs 16384] [--steps K] [--warmup W]
 """
 from __future__ import annotations
 
@@ -15,7 +15,7 @@ import os
 import sys
 import time
 
-ROOT = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 

@@ -12,12 +12,13 @@ import json
 import os
 import sys
 
-ROOT = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
-def main() -> int:
+def measure(copy_only=False, large_only=False):
+    """Returns the report as a dict.  large_only: only the inputs of 0.5 GB and more (the HBM-roofline evidence)."""
     import numpy as np
     import torch
 
@@ -31,10 +32,10 @@ def main() -> int:
     scratch = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
     out["copy_kernel_GBs"] = g.gmi_measure_peak(h, 1, scratch)
-    if "--copy-only" in sys.argv:
+    if copy_only:
         # calibration run for hardware counters: the copy kernel reads and writes 2^29 bytes per launch
-        print(json.dumps(out))
-        return 0
+        g.gmi_destroy(h)
+        return out
     out["mfma_loop_TFLOPs"] = g.gmi_measure_peak(h, 0, scratch)
     del scratch
 
@@ -49,7 +50,7 @@ def main() -> int:
 
     rows = []
     # GAE: T x N rewards, values, dones -> advantages, returns (25 B per sample + 4 B per env)
-    for T, N in ((16, 4096), (64, 1 << 20)):
+    for T, N in ((64, 1 << 20),) if large_only else ((16, 4096), (64, 1 << 20)):
         rb = RolloutBuffers(T, N, 1, 1, dev)
         rb.rew.normal_(); rb.val.normal_()
         lastv = torch.zeros(N, device=dev)
@@ -62,7 +63,7 @@ def main() -> int:
         g.gmi_buffer_destroy(hb)
         del rb
     # Adam on caller arrays: 16 B read + 12 B written per parameter
-    for n in (114129, 1 << 26):
+    for n in (1 << 26,) if large_only else (114129, 1 << 26):
         p, m, v, gr = (torch.zeros(n, device=dev) for _ in range(4))
         gr.normal_()
         torch.cuda.synchronize()
@@ -72,7 +73,8 @@ def main() -> int:
                      "GBs": 28.0 * n / ms / 1e6})
         del p, m, v, gr
     # env step and experience store
-    for N, O, A in ((4096, 60, 8), (1 << 20, 60, 8), (1 << 19, 108, 21), (1 << 18, 211, 20)):
+    for N, O, A in ((1 << 20, 60, 8), (1 << 19, 108, 21), (1 << 18, 211, 20)) if large_only else (
+            (4096, 60, 8), (1 << 20, 60, 8), (1 << 19, 108, 21), (1 << 18, 211, 20)):
         am = torch.eye(O, device=dev) * 0.95
         bm = torch.zeros(O, A, device=dev)
         ep = torch.zeros(N, dtype=torch.int32, device=dev)
@@ -102,7 +104,11 @@ def main() -> int:
         r["frac_of_copy_kernel"] = r["GBs"] / out["copy_kernel_GBs"]
     out["rows"] = rows
     g.gmi_destroy(h)
-    print(json.dumps(out))
+    return out
+
+
+def main() -> int:
+    print(json.dumps(measure(copy_only="--copy-only" in sys.argv)))
     return 0
 
 

@@ -6,7 +6,7 @@ profile() runs real PPO iterations (fresh reset, T-step rollout, GAE, E epochs o
 walks GMIperGPU = 10 .. 1 and num_env = 128 .. 16384 with the saturation early stop and returns the pair
 with the best projected throughput.  One JSON object on stdout.
 
-    python bench_selection.py [--config C2] [--alpha 0.1] [--iterations 3]
+    python benchmarks/selection.py [--config C2] [--alpha 0.1] [--iterations 3]
 """
 from __future__ import annotations
 
@@ -15,7 +15,7 @@ import json
 import os
 import sys
 
-ROOT = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 

@@ -76,7 +76,7 @@ ChainDims dims_of(const ModelLayout& L, int gmax = 4) {
 
 typedef int (*part_fn)(gmi_instance*, const ModelLayout&, const ChainArgs&, int, int*, double, double);
 const part_fn kParts[gmi::kChainParts] = {gmi::launch_chain_part0, gmi::launch_chain_part1, gmi::launch_chain_part2,
-                                          gmi::launch_chain_part3, gmi::launch_chain_part4, gmi::launch_chain_part5};
+                                          gmi::launch_chain_part3};
 const part_fn kFwdParts[gmi::kChainFwdParts] = {gmi::launch_chain_fwd_part0, gmi::launch_chain_fwd_part1};
 // The row-tile kernel's shapes (tile_kernel.h) come first: a model shape compiled for both takes that one.
 const part_fn kTileFns[gmi::kTileParts] = {gmi::launch_tile_part0, gmi::launch_tile_part1};

@@ -812,12 +812,11 @@ namespace gmi {
 // GMI_ERR_UNSUPPORTED otherwise.  rows == 0 only asks whether the shape matches (*tiles_out = the
 // shape's largest group, which the layout of the weight stream depends on, plus 256 for a trainer shape
 // with the bf16-copy gather).
-constexpr int kChainParts = 6;
+constexpr int kChainParts = 4;
 #define GMI_CHAIN_PART_DECL(k)                                                                              \
   int launch_chain_part##k(gmi_instance* g, const ModelLayout& L, const gmi_chain::ChainArgs& a, int rows, \
                            int* tiles_out, double flops, double bytes)
-GMI_CHAIN_PART_DECL(0); GMI_CHAIN_PART_DECL(1); GMI_CHAIN_PART_DECL(2);
-GMI_CHAIN_PART_DECL(3); GMI_CHAIN_PART_DECL(4); GMI_CHAIN_PART_DECL(5);
+GMI_CHAIN_PART_DECL(0); GMI_CHAIN_PART_DECL(1); GMI_CHAIN_PART_DECL(2); GMI_CHAIN_PART_DECL(3);
 // Defines part k for shape S.
 // Forward-only (inference) kernels exist for the shapes too large for the fused agent / rollout kernels.
 constexpr int kChainFwdParts = 2;
