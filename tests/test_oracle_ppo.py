@@ -452,6 +452,40 @@ def test_whole_iteration_on_c1_is_deterministic_and_learns_something():
 
 
 # ----------------------------------------------------------------------------- several trainer instances
+def test_rollout_bootstraps_from_the_state_after_the_last_step():
+    """Stage (i) of Section 5.1 ends with the value of the state the last interaction led to.  On an env
+    without done flags the T rounds are replayed by hand with agent_act / env_step; `rollout` must return the
+    value net's output on the state AFTER round T - 1 (not the one stored in the buffer's last slot), and the
+    advantages must depend on it."""
+    shape = ppo.ModelShape(5, 2, (7, 6))
+    theta = syn.make_model_params(5, 2, (7, 6), 4)
+    am, bm_ = syn.make_env_matrices(5, 2, 4)
+    env = ppo.EnvSpec(am, bm_, 0.05, 1.0, 0, 0, 9)          # done_period 0, threshold 0: never done
+    T, N = 6, 11
+    s0 = syn.make_initial_state(N, 5, 4)
+    buf = ppo.new_buffer(T, N, 5, 2)
+    state, ep, last_val = ppo.rollout(theta, shape, env, s0, np.zeros(N, np.uint32), buf, seed=9, iteration=2)
+    s, e = s0.astype(np.float32), np.zeros(N, np.uint32)
+    for t in range(T):
+        a, _, _, _ = ppo.agent_act(theta, shape, s, 9, 2 * T + t)
+        assert np.array_equal(buf["obs"][t], s)
+        pre = s
+        s, _, d, e = ppo.env_step(env, s, a, e, 2 * T + t)
+        assert not d.any()
+    assert np.array_equal(state, s) and np.array_equal(ep, e)
+    assert np.array_equal(last_val, ppo.value_only(theta, shape, s))
+    v_pre = ppo.value_only(theta, shape, pre)                # the state stored in the last slot
+    assert np.array_equal(v_pre, buf["val"][T - 1])
+    assert np.abs(last_val - v_pre).max() > 1e-3              # the two candidates can be told apart
+    adv1, ret1 = ppo.gae(buf["rew"], buf["val"], buf["done"], last_val, 0.99, 0.95, False)
+    adv2, _ = ppo.gae(buf["rew"], buf["val"], buf["done"], v_pre, 0.99, 0.95, False)
+    # with no done flag the bootstrap enters every advantage of an env: A_t changes by (gamma lam)^(T-1-t) gamma dv
+    dv = (last_val - v_pre).astype(np.float64)
+    for t in range(T):
+        want = (0.99 * 0.95) ** (T - 1 - t) * 0.99 * dv
+        assert np.allclose((adv1[t] - adv2[t]).astype(np.float64), want, rtol=1e-3, atol=1e-6)
+
+
 def _random_buffer(rng, T, N, O, A):
     b = ppo.new_buffer(T, N, O, A, np.float64)
     b["obs"] = rng.standard_normal((T, N, O))
