@@ -6,7 +6,7 @@ import torch
 
 from oracle import ppo as oppo
 from workloads import synthetic as syn
-from gpu_util import rel_l2
+from gpu_util import rel_l2, rel_max
 
 pytestmark = pytest.mark.gpu
 
@@ -130,6 +130,56 @@ def test_pipelined_schedule_matches_oracle_fp32(host_ordered):
         for name in ("obs", "act", "logp", "val", "rew"):
             assert rel_l2(got[name], bufs[k + 1][name]) <= 5e-5, (k, name)
         assert rel_l2(pipe.theta.cpu().numpy(), th[k + 1]) <= 2e-5, k
+    pipe.close()
+
+
+@pytest.mark.parametrize("host_ordered", [False, True])
+def test_pipelined_schedule_bf16_matches_oracle_replay(host_ordered):
+    """The multi-instance configuration's model in bf16, lag-1 schedule on masked instances, against the oracle's
+    replay of the same schedule (round k + 1 collected with the parameters after k updates).  The step size is
+    large enough for a round collected with the wrong parameter version to miss its reference by far more than
+    the bf16 band, which is asserted for the round that would show it.  The trainer's parameters: relative to
+    their own size they are the start parameters (trivial); relative to the update they follow the oracle's
+    to the extent Adam allows -- its early steps are lr * sign-like, so the ~0.5 % of weights whose bf16
+    gradient error exceeds their gradient move the other way (bound 0.25 on the step, derived from that share)."""
+    cfg = syn.get_config("C3")
+    n_agents, n_envs, horizon, minibatch = 4, 128, 4, 1024
+    shape, theta, a_mat, b_mat, thr, envs, states, hp = _setup(cfg, n_agents, n_envs, horizon, minibatch)
+    hp.lr = 2e-3
+    pipe = _pipeline(cfg, "bf16", n_agents, n_envs, horizon, minibatch, theta, a_mat, b_mat, thr, states, True,
+                     host_ordered)
+    ora = _OracleAgents(shape, envs, states, n_envs, horizon, cfg)
+    args = _train_args(cfg, minibatch)
+    args["lr"] = hp.lr
+    th = [theta]
+    m, v, kk = np.zeros_like(theta), np.zeros_like(theta), 0
+    bufs = [ora.collect(theta, 0)]
+    pipe.prologue_pipelined()
+    for k in range(3):
+        pipe.iteration_pipelined(k, **args)
+        pipe.sync_all()
+        bufs.append(ora.collect(th[k], k + 1))                   # agents still hold theta_k
+        new_th, m, v, kk, _ = oppo.ppo_update(th[k], m, v, kk, shape, bufs[k], hp, cfg.seed, k)
+        th.append(new_th)
+        got = pipe.bufs[(k + 1) % 2].to_numpy()
+        assert np.array_equal(got["done"], bufs[k + 1]["done"])
+        for name in ("obs", "act", "val", "rew"):
+            assert rel_l2(got[name], bufs[k + 1][name]) <= 2e-2, (k, name, rel_l2(got[name], bufs[k + 1][name]))
+            assert rel_max(got[name], bufs[k + 1][name]) <= 2e-2, (k, name)
+        # noise and log_std only; log_std is a trained parameter here, so it carries the trainer's bf16 error
+        assert rel_l2(got["logp"], bufs[k + 1]["logp"]) <= 1e-4
+        got_th = pipe.theta.cpu().numpy()
+        assert rel_l2(got_th, th[k + 1]) <= 2e-2, k
+        step, ref_step = got_th - theta, th[k + 1] - theta
+        assert rel_l2(step, ref_step) <= 0.25, (k, rel_l2(step, ref_step))
+        if k == 1:
+            # round 2 was collected with theta_1; a rollout under theta_0 or theta_2 is NOT what the buffer holds
+            st, ep = [s.copy() for s in ora.states], [e.copy() for e in ora.eps]
+            for wrong in (th[0], th[2]):
+                probe = _OracleAgents(shape, envs, states, n_envs, horizon, cfg)
+                probe.collect(theta, 0); probe.collect(th[0], 1)
+                assert rel_l2(got["val"], probe.collect(wrong, 2)["val"]) > 5e-2
+            ora.states, ora.eps = st, ep
     pipe.close()
 
 
