@@ -225,6 +225,20 @@ int rollout_collect(gmi_t gmi, gmi_model_t model, gmi_env_t env, gmi_buffer_t bu
 int gae_compute(gmi_t gmi, gmi_buffer_t buf, const float* last_value, float gamma, float lambda,
                 int normalize);
 
+/* gae_compute for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid it): no buffer binding is needed -- a binding owns allocations -- and the call itself
+ * allocates nothing.  Same kernels and results as gae_compute on a binding of the same arrays.
+ *  rew, val dev [T, ld] fp32, done dev [T, ld] u8, last_value dev [N]: inputs;  adv, ret dev [T, ld]: outputs
+ *  (all caller-owned; columns N..ld-1 are not touched).
+ *  The per-workgroup partial sums of the normalisation live in a fixed array of 256 KiB that the library holds on
+ *  every device it runs on until the process ends; it covers n_envs <= 4 194 304 (more: GMI_ERR_BAD_SHAPE, nothing
+ *  runs).  All calls on one device share that array: calls with normalize != 0 that overlap on one device (two
+ *  instances, or two host threads) race on it -- order them.  Asynchronous on the instance's stream like every
+ *  compute call. */
+int gae_compute_static(gmi_t gmi, int32_t horizon, int32_t n_envs, int32_t ld_envs, const float* rew,
+                       const float* val, const uint8_t* done, const float* last_value, float gamma, float lambda,
+                       int normalize, float* adv, float* ret);
+
 /* ------------------------------------------------------------------ trainer ----------------- */
 
 typedef struct {

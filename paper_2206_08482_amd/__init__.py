@@ -23,7 +23,7 @@ EXPORTS = [
     "gmi_transfer", "gmi_model_param_count", "gmi_model_shadow_bytes", "gmi_model_bind",
     "gmi_model_destroy", "gmi_model_refresh_shadow", "gmi_env_bind", "gmi_env_destroy", "env_step",
     "agent_act", "agent_value", "gmi_buffer_bind", "gmi_buffer_destroy", "collect_experience",
-    "gae_compute", "ppo_update", "ppo_evaluate", "ppo_gradient", "adam_update", "gmi_noise_fill",
+    "gae_compute", "gae_compute_static", "ppo_update", "ppo_evaluate", "ppo_gradient", "adam_update", "gmi_noise_fill",
     "gmi_permutation", "gmi_profile_enable", "gmi_profile_classes", "gmi_profile_class_name", "gmi_profile_read",
     "gmi_measure_peak", "gmi_bench_linear", "gmi_set_fusion", "rollout_collect", "gmi_profile_work", "gmi_explore", "ppo_update_group", "gmi_select_reduction",
     "gmi_har_leaders", "gmi_reduction_time", "gmi_channels_create", "gmi_channels_destroy", "gmi_channels_push",
@@ -101,6 +101,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "collect_experience": (C.c_int, [vp, vp, i32, vp, vp, vp, vp, vp, vp]),
         "rollout_collect": (C.c_int, [vp, vp, vp, vp, vp, u64, u32, u32, vp]),
         "gae_compute": (C.c_int, [vp, vp, vp, f32, f32, C.c_int]),
+        "gae_compute_static": (C.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, f32, f32, C.c_int, vp, vp]),
         "ppo_update": (C.c_int, [vp, vp, vp, C.POINTER(PPOHparams), vp]),
         "ppo_update_group": (C.c_int, [C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), i32, C.POINTER(PPOHparams), vp]),
         "ppo_evaluate": (C.c_int, [vp, vp, vp, C.POINTER(PPOHparams), vp, i32, vp]),
@@ -310,6 +311,12 @@ def rollout_collect(gmi: int, model: int, env: int, buf: int, obs, seed: int, st
 
 def gae_compute(gmi: int, buf: int, last_value, gamma: float, lam: float, normalize: bool) -> None:
     _check(_lib.gae_compute(gmi, buf, _ptr(last_value), gamma, lam, 1 if normalize else 0))
+
+
+def gae_compute_static(gmi: int, horizon: int, n_envs: int, ld_envs: int, rew, val, done, last_value, gamma: float,
+                       lam: float, normalize: bool, adv, ret) -> None:
+    _check(_lib.gae_compute_static(gmi, horizon, n_envs, ld_envs, _ptr(rew), _ptr(val), _ptr(done), _ptr(last_value),
+                                   gamma, lam, 1 if normalize else 0, _ptr(adv), _ptr(ret)))
 
 
 # ---------------------------------------------------------------- trainer

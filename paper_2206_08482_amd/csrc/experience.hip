@@ -1,4 +1,6 @@
 // Experience buffer (one array per data type, time major), its filling, and GAE.
+#include <mutex>
+
 #include "internal.h"
 
 namespace {
@@ -201,6 +203,73 @@ extern "C" int gae_compute(gmi_t g, gmi_buffer_t b, const float* last_value, flo
     int grid = (int)((total + 1023) / 1024);
     if (grid > 2048) grid = 2048;
     ps.launch(normalize_kernel, dim3(grid), dim3(256), 0, b->d, b->part, b->n_part);
+    GMI_LAUNCH_CHECK();
+  }
+  return GMI_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// gae_compute for callers that cannot allocate: no buffer binding (a binding owns device allocations), the
+// arrays as plain pointers, and the per-workgroup partial sums of the normalisation in a file-scope device array
+// instead of the binding's workspace.  Same kernels, same arithmetic, same order of additions as gae_compute.
+namespace {
+constexpr int kStaticPartMax = 16384;                     // workgroups of 256 envs: up to 4 194 304 envs per call
+static __device__ __align__(256) double scratch[2 * kStaticPartMax];      // 256 KiB on every device the library runs on
+
+constexpr int kMaxDevices = 64;
+double* g_scratch_ptr[kMaxDevices];                       // the array's address on each device (its name is only
+std::once_flag g_scratch_once[kMaxDevices];               // a host-side stand-in), looked up once per device
+hipError_t g_scratch_err[kMaxDevices];
+
+// The device array's address on `device`; looked up with that device current.
+double* scratch_on(int device, hipError_t* err) {
+  std::call_once(g_scratch_once[device], [device]() {
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e == hipSuccess && cur != device) e = hipSetDevice(device);
+    void* p = nullptr;
+    if (e == hipSuccess) e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
+    g_scratch_err[device] = e;
+    g_scratch_ptr[device] = e == hipSuccess ? static_cast<double*>(p) : nullptr;
+  });
+  *err = g_scratch_err[device];
+  return g_scratch_ptr[device];
+}
+}  // namespace
+
+extern "C" int gae_compute_static(gmi_t g, int32_t horizon, int32_t n_envs, int32_t ld_envs, const float* rew,
+                                  const float* val, const uint8_t* done, const float* last_value, float gamma,
+                                  float lambda, int normalize, float* adv, float* ret) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gae_compute_static: bad instance");
+  if (horizon < 0 || n_envs < 0 || ld_envs < n_envs)
+    GMI_FAIL(GMI_ERR_BAD_SHAPE, "gae_compute_static: need horizon, n_envs >= 0 and ld_envs >= n_envs");
+  if ((int64_t)horizon * n_envs >= (1ll << 31))
+    GMI_FAIL(GMI_ERR_BAD_SHAPE, "gae_compute_static: horizon * n_envs must be below 2^31");
+  const int n_part = (n_envs + 255) / 256;
+  if (n_part > kStaticPartMax)
+    GMI_FAIL(GMI_ERR_BAD_SHAPE, "gae_compute_static: n_envs=%d exceeds the %d envs its fixed partial-sum array covers "
+             "(use gae_compute on a buffer binding)", n_envs, 256 * kStaticPartMax);
+  if (n_envs == 0 || horizon == 0) return GMI_OK;
+  if (!rew || !val || !done || !last_value || !adv || !ret) GMI_FAIL(GMI_ERR_INVALID_ARG, "gae_compute_static: NULL pointer");
+  if (g->device < 0 || g->device >= kMaxDevices) GMI_FAIL(GMI_ERR_UNSUPPORTED, "gae_compute_static: device %d", g->device);
+  hipError_t e = hipSuccess;
+  double* part = scratch_on(g->device, &e);
+  if (!part) GMI_FAIL(GMI_ERR_HIP, "gae_compute_static: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+  gmi_buffer_desc d = {};
+  d.horizon = horizon; d.n_envs = n_envs; d.ld_envs = ld_envs; d.obs_dim = 1; d.act_dim = 1;
+  d.rew = const_cast<float*>(rew); d.val = const_cast<float*>(val); d.done = const_cast<uint8_t*>(done);
+  d.adv = adv; d.ret = ret;
+  // every workgroup of gae_kernel writes its own two partials and normalize_kernel reads exactly those: nothing
+  // of an earlier call is read, so nothing needs clearing
+  hipLaunchKernelGGL(gae_kernel, dim3(n_part), dim3(256), 0, g->stream, d, last_value, gamma, gamma * lambda,
+                     normalize ? part : nullptr);
+  GMI_LAUNCH_CHECK();
+  if (normalize) {
+    const int64_t total = (int64_t)horizon * n_envs;
+    int grid = (int)((total + 1023) / 1024);
+    if (grid > 2048) grid = 2048;
+    hipLaunchKernelGGL(normalize_kernel, dim3(grid), dim3(256), 0, g->stream, d, (const double*)part, n_part);
     GMI_LAUNCH_CHECK();
   }
   return GMI_OK;
