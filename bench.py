@@ -97,10 +97,7 @@ def class_work(cfg, n_params, launched):
         # fused kernels: all layers of both nets for a tile of rows in one launch
         "fused_agent": dict(flops=rollout_flops, bytes=T * N * 4.0 * (O + 2 * A + 2) + (T + 1) * w_bytes,
                             launches=T + 1),
-        "fused_train": dict(flops=2.0 * n_upd * MB * (mac + mac_dgrad), bytes=n_upd * MB * 2.0 * act_b,
-                            launches=n_upd),
         "fused_rollout": dict(flops=rollout_flops, bytes=exp_bytes + 8.0 * N * O + w_bytes, launches=1),
-        "reduce": dict(bytes=n_upd * (MB / 64.0) * 4.0 * (A + 8), launches=n_upd),
     }, 2.0 * (T * N * mac + N * mac_value + n_upd * MB * (2 * mac + mac_dgrad))
 
 
@@ -146,7 +143,7 @@ def cpu_baseline(cfg, budget_s=12.0):
 
 # kernel classes whose work is matrix products (judged against the matrix-core roof)
 def is_matrix_class(name):
-    return name in ("chain_train", "wgrad", "fused_agent", "fused_train", "fused_rollout") or name.startswith("linear_")
+    return name in ("chain_train", "wgrad", "fused_agent", "fused_rollout") or name.startswith("linear_")
 
 
 def run_workload(g, torch, syn, PPOSession, name, steps, warmup, fusion=None, detail=True):

@@ -17,8 +17,9 @@
  *    and frees it in the matching *_destroy; no compute call allocates.
  *  - Every compute call is asynchronous on its instance's stream.  Ordering between instances is
  *    established only by gmi_transfer(); gmi_sync() blocks the host.  The library never waits for
- *    streams it does not own: whatever the caller put into a dev buffer on another stream (an
- *    allocator's fill, a copy) must have completed before the call that touches the buffer is made.
+ *    streams it does not own unless told to: whatever the caller put into a dev buffer on another stream
+ *    (an allocator's fill, a copy) must have completed before the call that touches the buffer is made, or
+ *    gmi_wait_stream() must have ordered the instance behind that stream.
  *  - All randomness is a pure function of (seed, stream id, step, env index, element) through
  *    Philox4x32-10: counter = (env index, step, stream id, block), key = (seed low, seed high).
  *    Stream ids: 0 action noise, 1 environment noise, 2 done draw, 3 reset state, 4 shuffle.
@@ -71,15 +72,17 @@ int gmi_destroy(gmi_t gmi);
 void* gmi_stream(gmi_t gmi);
 /* Blocks the host until all work queued on the instance has finished. */
 int gmi_sync(gmi_t gmi);
+/* Makes the instance wait for everything queued so far on a stream of the caller (a hipStream_t as void*; NULL =
+ * the device's default stream): work queued on the instance after this call starts only when that work has
+ * finished.  For data the caller produces on streams of its own (an allocator's fill, a copy) -- the on-device
+ * alternative to synchronising the host before a call that touches such a buffer.  Does not block the host. */
+int gmi_wait_stream(gmi_t gmi, void* hip_stream);
 /* Number of compute units enabled for the instance (device CU count if unrestricted). */
 int gmi_cu_count(gmi_t gmi);
 const char* gmi_last_error(void);
-/* Fusion level of the instance.  0: per-layer kernels only.  1 (default): agent_act / agent_value use
- * the row-tile fused kernel (observation conversion, all layers of both nets and the sampling epilogue
- * in one launch) whenever the model fits it.  2: ppo_update also uses the row-tile fused trainer kernel
- * (gather + forward + loss + input gradients in one launch; currently slower than the per-layer
- * kernels at minibatches of tens of thousands of rows).  All levels give results within
- * the same tolerances. */
+/* enable != 0 (default): agent_act / agent_value, rollout_collect and ppo_update use the kernels that carry a tile
+ * of rows through all layers of both nets in one launch wherever the model has one; 0: one launch per layer.  Both
+ * give results within the same tolerances (tests compare each with the oracle). */
 int gmi_set_fusion(gmi_t gmi, int enable);
 
 /* Hands data from instance `src` to instance `dst` (the paper's asynchronous send / synchronous
@@ -392,40 +395,10 @@ int gmi_select_reduction(const int32_t* gmis_per_gpu, int32_t n_gpus, int32_t* s
 int gmi_har_leaders(const int32_t* gmi_ids, const int32_t* gpu_start, int32_t n_gpus, int32_t t,
                     int32_t* leaders_out);
 
-/* Time models of the three strategies (Table 3): g GPUs, t instances per GPU, m_p parameter bytes, b1 the
+/* Time models of the three strategies (Table 2): g GPUs, t instances per GPU, m_p parameter bytes, b1 the
  * inter-instance bandwidth through host memory, b2 the inter-GPU collective bandwidth (bytes/s). */
 int gmi_reduction_time(int32_t strategy, int32_t g, int32_t t, double m_p, double b1, double b2,
                        double* seconds_out);
-
-/* Built-in timer for measurement runs (the paper's profile() step of Algorithm 2 measures a trial
- * run; here the unit is one kernel class = one kernel symbol).  class_mask bit c = 1: every launch of
- * kernel class c on this instance carries a pair of HIP events on the instance's stream that receive the
- * kernel's own begin and end timestamps, so a class total is execution time without launch gaps.
- * Enabling (or passing 0 to disable) synchronises the stream and clears earlier measurements.  Event
- * pairs are created on demand, so a profiled call may allocate host-side event objects. */
-int gmi_profile_enable(gmi_t gmi, uint32_t class_mask);
-/* Number of kernel classes, and the name of class cls (NULL if out of range). */
-int gmi_profile_classes(void);
-const char* gmi_profile_class_name(int cls);
-/* Synchronises the stream and returns the summed duration (ms) and the number of bracketed
- * launches of class cls since profiling was enabled.  host: total_ms, launches. */
-int gmi_profile_read(gmi_t gmi, int cls, double* total_ms, int64_t* launches);
-/* Algorithmic work (flops; bytes of operands read and results written once) that the launchers stated
- * for the timed launches of class cls since gmi_profile_enable; 0 for classes whose launcher states
- * none (the linear-layer and weight-gradient classes state theirs).  host: flops, bytes. */
-int gmi_profile_work(gmi_t gmi, int cls, double* flops, double* bytes);
-
-/* Achievable-peak probes for measurement reports: what = 0 runs a pure bf16 matrix-core loop and
- * returns TFLOP/s, what = 1 runs a streaming copy over the two halves of `scratch` and returns GB/s
- * (bytes read + written).  Blocks until done.  scratch: dev, scratch_bytes long; result: host. */
-int gmi_measure_peak(gmi_t gmi, int what, void* scratch, size_t scratch_bytes, double* result);
-
-/* Micro-benchmark of one bf16 linear-layer product of the MLPs (Table 6 shapes) on synthetic operands
- * carved out of `scratch` (dev; zero or arbitrary finite contents): kind 0 = forward with bias + ELU,
- * 2 = input gradient, 3 = weight gradient.  rows x K -> F, K and F multiples of 32, n_nets (1 or 2)
- * problems per launch as in the real path.  us_per_launch (host) = average over reps launches. Blocks. */
-int gmi_bench_linear(gmi_t gmi, int kind, int rows, int K, int F, int n_nets, int reps, void* scratch,
-                     size_t scratch_bytes, double* us_per_launch);
 
 #ifdef __cplusplus
 }

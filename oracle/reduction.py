@@ -1,5 +1,5 @@
 """Oracle for the layout-aware gradient reduction choice (Section 4.1: Algorithm 1, the leader rule of the
-hierarchical reduction, and the time models of Table 3).
+hierarchical reduction, and the time models of Table 2).
 
 TEST INFRASTRUCTURE ONLY: imported by tests/ (and nothing in the product).  Plain Python in the paper's
 notation.  MPL is the GMI-to-GPU mapping list: MPL[p] = ids of the trainer instances on GPU p.

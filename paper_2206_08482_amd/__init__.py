@@ -20,7 +20,7 @@ STREAM_ACTION, STREAM_ENV, STREAM_DONE, STREAM_RESET, STREAM_SHUFFLE = 0, 1, 2, 
 
 EXPORTS = [
     "gmi_create", "gmi_destroy", "gmi_stream", "gmi_sync", "gmi_cu_count", "gmi_last_error",
-    "gmi_transfer", "gmi_model_param_count", "gmi_model_shadow_bytes", "gmi_model_bind",
+    "gmi_wait_stream", "gmi_transfer", "gmi_model_param_count", "gmi_model_shadow_bytes", "gmi_model_bind",
     "gmi_model_destroy", "gmi_model_refresh_shadow", "gmi_env_bind", "gmi_env_destroy", "env_step",
     "agent_act", "agent_value", "gmi_buffer_bind", "gmi_buffer_destroy", "collect_experience",
     "gae_compute", "gae_compute_static", "ppo_update", "ppo_evaluate", "ppo_gradient", "adam_update", "gmi_noise_fill",
@@ -123,6 +123,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "gmi_profile_class_name": (C.c_char_p, [C.c_int]),
         "gmi_profile_read": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]),
         "gmi_set_fusion": (C.c_int, [vp, C.c_int]),
+        "gmi_wait_stream": (C.c_int, [vp, vp]),
         "gmi_explore": (C.c_int, [PROFILE_FN, vp, ESTIMATE_FN, vp, i32, C.c_double, C.POINTER(i32), i32,
                                   C.POINTER(i32), i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_double)]),
         "gmi_profile_work": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
@@ -509,5 +510,16 @@ def gmi_bench_linear(gmi: int, kind: int, rows: int, K: int, F: int, n_nets: int
 
 
 def gmi_set_fusion(gmi: int, level: int) -> None:
-    """0: per-layer kernels; 1 (default): fused agent kernel; 2: also the fused trainer kernel."""
+    """0: one launch per layer; otherwise (default) the one-launch agent, rollout and trainer kernels where the
+    model has them."""
     _check(_lib.gmi_set_fusion(gmi, int(level)))
+
+
+def gmi_wait_stream(gmi: int, stream=None) -> None:
+    """Orders the instance behind everything queued so far on `stream` (a torch.cuda.Stream or a raw stream
+    handle; None: torch's current stream)."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    handle = getattr(stream, "cuda_stream", stream)
+    _check(_lib.gmi_wait_stream(gmi, C.c_void_p(int(handle) if handle else None)))

@@ -3,7 +3,7 @@
 #include <string.h>
 
 #include "internal.h"
-#include "rng.cuh"
+#include "rng.h"
 
 namespace gmi {
 static thread_local char g_err[512] = "";
@@ -38,7 +38,7 @@ bool ProfScope::next_events(hipEvent_t* a, hipEvent_t* b) {
 }
 static const char* kClassNames[kClsCount] = {
     "gather", "wgrad", "loss", "adam", "shadow_transpose", "env_step", "sample", "collect", "gae", "permutation",
-    "fused_agent", "fused_train", "fused_rollout", "reduce", "linear_f32", "chain_train",
+    "fused_agent", "fused_rollout", "linear_f32", "chain_train",
     "linear_big256_fwd", "linear_big256_head", "linear_big256_dgrad",
     "linear_big128_fwd", "linear_big128_head", "linear_big128_dgrad",
     "linear_t128_fwd", "linear_t128_head", "linear_t128_dgrad",
@@ -139,6 +139,10 @@ extern "C" int gmi_create(const uint32_t* cu_mask, uint32_t n_words, int device,
   g->prof_mask = 0;
   g->fusion = 1;
   hipError_t e = hipEventCreateWithFlags(&g->event, hipEventDisableTiming);
+  if (e == hipSuccess) {
+    e = hipEventCreateWithFlags(&g->wait_event, hipEventDisableTiming);
+    if (e != hipSuccess) (void)hipEventDestroy(g->event);
+  }
   if (e != hipSuccess) {
     hipStreamDestroy(stream);
     delete g;
@@ -157,6 +161,7 @@ extern "C" int gmi_destroy(gmi_t g) {
       (void)hipEventDestroy(g->prof[c].stop[i]);
     }
   (void)hipEventDestroy(g->event);
+  (void)hipEventDestroy(g->wait_event);
   (void)hipStreamDestroy(g->stream);
   g->magic = 0;
   delete g;
@@ -165,7 +170,7 @@ extern "C" int gmi_destroy(gmi_t g) {
 
 extern "C" int gmi_set_fusion(gmi_t g, int enable) {
   if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_set_fusion: bad handle");
-  g->fusion = enable < 0 ? 0 : (enable > 2 ? 2 : enable);
+  g->fusion = enable > 0 ? 1 : 0;
   return GMI_OK;
 }
 
@@ -179,6 +184,15 @@ extern "C" int gmi_cu_count(gmi_t g) {
 extern "C" int gmi_sync(gmi_t g) {
   if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_sync: bad handle");
   GMI_HIP(hipStreamSynchronize(g->stream));
+  return GMI_OK;
+}
+
+extern "C" int gmi_wait_stream(gmi_t g, void* hip_stream) {
+  if (!valid(g)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_wait_stream: bad handle");
+  hipStream_t other = static_cast<hipStream_t>(hip_stream);
+  if (other == g->stream) return GMI_OK;
+  GMI_HIP(hipEventRecord(g->wait_event, other));
+  GMI_HIP(hipStreamWaitEvent(g->stream, g->wait_event, 0));
   return GMI_OK;
 }
 

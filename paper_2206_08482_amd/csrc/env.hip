@@ -1,7 +1,7 @@
 // Environment simulator role: the seeded linear-Gaussian stand-in (Section 3 of the paper describes
 // the role: receive actions, return new states and rewards for hundreds or thousands of envs).
 #include "internal.h"
-#include "rng.cuh"
+#include "rng.h"
 
 namespace {
 

@@ -9,7 +9,7 @@
 #else
 #define GMI_RT_MARK(i) do { } while (0)
 #endif
-#include "rng.cuh"
+#include "rng.h"
 
 namespace {
 
@@ -1028,230 +1028,12 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   }
 }
 
-// ------------------------------------------------------------------------------------------------
-// Trainer: one launch per minibatch does, for a tile of R samples and one net (blockIdx.y), the gather
-// of the shuffled rows, the forward pass (activations kept for the weight gradients), the clipped-
-// surrogate / value loss on the tile, and the whole input-gradient chain.  Only the weight-gradient
-// reduction over samples and Adam remain separate launches.
-struct TrainNet {
-  FusedNet fwd;                                // W [out_pad, in_pad], bias
-  const uint16_t* wt[GMI_MAX_HIDDEN + 1];      // W^T [in_pad, out_pad]
-  uint16_t* h[GMI_MAX_HIDDEN + 1];             // global activations h[l] = input of layer l (l >= 1), [rows, in_pad]
-  uint16_t* dz[GMI_MAX_HIDDEN + 1];            // global gradients w.r.t. the output of layer l, [rows, out_pad]
-};
-struct TrainArgs {
-  TrainNet net[2];
-  const float* log_std;
-  const float *b_obs, *b_act, *b_logp, *b_adv, *b_ret;
-  const int32_t* idx;
-  uint16_t* x0;                                // global [rows, obs_pad]
-  int rows, n_envs, ld_envs, obs_dim, obs_pad, act_dim, max_h;
-  float clip, c_v;
-  float* stat_part;                            // [tiles][kStatStride + act_dim]
-};
-
-template <int R>
-__device__ __forceinline__ void tile_to_global(const uint16_t* s, int stride, uint16_t* g, int width, int r0, int rows) {
-  const int cpr = width >> 3;                  // 16-byte chunks per row
-  for (int i = threadIdx.x; i < R * cpr; i += 256) {
-    const int r = i / cpr, c = i - r * cpr;
-    if (r0 + r < rows)
-      *reinterpret_cast<uint4*>(g + (int64_t)(r0 + r) * width + c * 8) = *reinterpret_cast<const uint4*>(s + r * stride + c * 8);
-  }
-}
-template <int R>
-__device__ __forceinline__ void global_to_tile(uint16_t* s, int stride, const uint16_t* g, int width, int r0, int rows) {
-  const int cpr = width >> 3;
-  for (int i = threadIdx.x; i < R * cpr; i += 256) {
-    const int r = i / cpr, c = i - r * cpr;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (r0 + r < rows) v = *reinterpret_cast<const uint4*>(g + (int64_t)(r0 + r) * width + c * 8);
-    *reinterpret_cast<uint4*>(s + r * stride + c * 8) = v;
-  }
-}
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-  return v;
-}
-
-template <int RT>
-__global__ __launch_bounds__(256) void train_fused_kernel(TrainArgs a) {
-  constexpr int R = RT * 32;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  const int net = blockIdx.y;
-  const TrainNet& N = a.net[net];
-  const int L = N.fwd.n_layers - 1;            // hidden layers; layer L is the head
-  const int A = a.act_dim;
-  const int stride_x0 = a.obs_pad + 8, stride_h = a.max_h + 8, stride_dh = 40;
-  uint16_t* s_x0 = reinterpret_cast<uint16_t*>(smem_raw);
-  uint16_t* s_buf[3];
-  s_buf[0] = s_x0 + R * stride_x0;
-  s_buf[1] = s_buf[0] + R * stride_h;
-  s_buf[2] = s_buf[1] + R * stride_h;
-  uint16_t* s_dzh = s_buf[2] + R * stride_h;                        // [R][40] head gradient (bf16)
-  float* s_head = reinterpret_cast<float*>(s_dzh + R * stride_dh);   // [R][A] (policy) or [R] (value)
-  float* s_ex = s_head + R * A;                                      // [R][A + 3]: act, logp_old, adv, ret
-  float* s_red = s_ex + R * (A + 3);                                 // [4][A + 4] per-wave partial sums
-  float* s_bias = s_red + 4 * (A + 4);                               // this net's biases
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int r0 = blockIdx.x * R;
-  const int EW = A + 3;
-
-  stage_biases(N.fwd, s_bias, tid, 256);
-  // gather: shuffled rows of the buffer -> bf16 input tile (+ the per-sample scalars of the loss)
-  for (int i = tid; i < R * a.obs_pad; i += 256) {
-    const int r = i / a.obs_pad, k = i - r * a.obs_pad;
-    float v = 0.f;
-    if (r0 + r < a.rows && k < a.obs_dim) {
-      const int sm = a.idx[r0 + r];
-      v = a.b_obs[((int64_t)(sm / a.n_envs) * a.ld_envs + (sm % a.n_envs)) * a.obs_dim + k];
-    }
-    s_x0[r * stride_x0 + k] = (uint16_t)(pack_bf16(v, 0.f) & 0xFFFFu);
-  }
-  for (int i = tid; i < R * EW; i += 256) {
-    const int r = i / EW, j = i - r * EW;
-    float v = 0.f;
-    if (r0 + r < a.rows) {
-      const int sm = a.idx[r0 + r];
-      const int64_t slot = (int64_t)(sm / a.n_envs) * a.ld_envs + (sm % a.n_envs);
-      v = j < A ? a.b_act[slot * A + j] : (j == A ? a.b_logp[slot] : (j == A + 1 ? a.b_adv[slot] : a.b_ret[slot]));
-    }
-    s_ex[i] = v;
-  }
-  __syncthreads();
-  if (net == 0) tile_to_global<R>(s_x0, stride_x0, a.x0, a.obs_pad, r0, a.rows);
-
-  // forward: h[l+1] = ELU(h[l] W_l^T + b_l), ping-pong between s_buf[0] and s_buf[1]
-  const uint16_t* in = s_x0;
-  int stride_in = stride_x0;
-  int cur = 0;
-  for (int l = 0; l < L; ++l) {
-    fused_layer<RT, kFEpiElu>(N.fwd.w[l], s_bias + N.fwd.bias_off[l], N.fwd.in_pad[l], N.fwd.out_pad[l], in, stride_in, s_buf[cur],
-                              stride_h, nullptr, 0, 0);
-    __syncthreads();
-    tile_to_global<R>(s_buf[cur], stride_h, N.h[l + 1], N.fwd.out_pad[l], r0, a.rows);
-    in = s_buf[cur];
-    stride_in = stride_h;
-    cur ^= 1;
-  }
-  const int hl = cur ^ 1;                       // s_buf[hl] holds h[L] (if L >= 1)
-  fused_layer<RT, kFEpiHead>(N.fwd.w[L], s_bias + N.fwd.bias_off[L], N.fwd.in_pad[L], N.fwd.out_pad[L], in, stride_in, nullptr, 0,
-                             s_head, net == 0 ? A : 1, N.fwd.out_store);
-  for (int i = tid; i < R * stride_dh; i += 256) s_dzh[i] = 0;
-  for (int i = tid; i < 4 * (A + 4); i += 256) s_red[i] = 0.f;
-  __syncthreads();
-
-  // loss on the tile: one thread per sample (the first R threads)
-  const float inv_m = 1.0f / (float)a.rows;
-  float s0 = 0.f, s1 = 0.f, s2 = 0.f;            // policy: surrogate, kl, clipped;  value: squared error
-  const bool ok = tid < R && (r0 + tid) < a.rows;
-  float g_lp = 0.f;
-  if (net == 0) {
-    if (ok) {
-      float lp = 0.f;
-      for (int j = 0; j < A; ++j) {
-        const float ls = a.log_std[j];
-        const float z = (s_ex[tid * EW + j] - s_head[tid * A + j]) * expf(-ls);
-        lp += -0.5f * z * z - ls - 0.918938533204672742f;
-      }
-      const float lo = s_ex[tid * EW + A], ad = s_ex[tid * EW + A + 1];
-      const float ratio = expf(lp - lo);
-      const float u1 = ratio * ad;
-      const float u2 = fminf(fmaxf(ratio, 1.0f - a.clip), 1.0f + a.clip) * ad;
-      s0 = -fminf(u1, u2);
-      s1 = lo - lp;
-      s2 = fabsf(ratio - 1.0f) > a.clip ? 1.f : 0.f;
-      g_lp = (u1 <= u2) ? -(ad * ratio) * inv_m : 0.f;
-    }
-    if (wave == 0) {                              // whole wave: the shuffles below need all 64 lanes
-      for (int j = 0; j < A; ++j) {
-        float c = 0.f;
-        if (ok) {
-          const float inv_sigma = expf(-a.log_std[j]);
-          const float z = (s_ex[tid * EW + j] - s_head[tid * A + j]) * inv_sigma;
-          s_dzh[tid * stride_dh + j] = (uint16_t)(pack_bf16(g_lp * z * inv_sigma, 0.f) & 0xFFFFu);
-          c = g_lp * (z * z - 1.0f);
-        }
-        c = wave_sum(c);
-        if (lane == 0) s_red[wave * (A + 4) + 4 + j] = c;
-      }
-    }
-  } else if (ok) {
-    const float dv = s_head[tid] - s_ex[tid * EW + A + 2];
-    s0 = dv * dv;
-    s_dzh[tid * stride_dh] = (uint16_t)(pack_bf16(2.0f * a.c_v * dv * inv_m, 0.f) & 0xFFFFu);
-  }
-  if (wave == 0) {
-    s0 = wave_sum(s0); s1 = wave_sum(s1); s2 = wave_sum(s2);
-    if (lane == 0) { s_red[wave * (A + 4) + 0] = s0; s_red[wave * (A + 4) + 1] = s1; s_red[wave * (A + 4) + 2] = s2; }
-  }
-  __syncthreads();
-  {
-    // R <= 64: wave 0 holds all samples of the tile -> its sums are the tile's partial row
-    float* out = a.stat_part + (int64_t)blockIdx.x * (gmi::kStatStride + A);
-    if (net == 0) {
-      if (tid == 0) {
-        out[0] = s_red[0]; out[3] = s_red[1]; out[4] = s_red[2];
-        float ent = 0.f;
-        if (blockIdx.x == 0)
-          for (int j = 0; j < A; ++j) ent += a.log_std[j] + 1.418938533204672742f;
-        out[2] = ent;
-        out[5] = out[6] = out[7] = 0.f;
-      }
-      for (int j = tid; j < A; j += 256) out[gmi::kStatStride + j] = s_red[4 + j];
-    } else if (tid == 0) {
-      out[1] = s_red[0];
-    }
-  }
-  tile_to_global<R>(s_dzh, stride_dh, N.dz[L], 32, r0, a.rows);
-
-  // input-gradient chain: dz[l-1] = (dz[l] W_l) * ELU'(h[l]),  l = L .. 1
-  const uint16_t* d_in = s_dzh;
-  int stride_d = stride_dh;
-  int outb = 2;                                 // first result goes to the third buffer
-  for (int l = L; l >= 1; --l) {
-    fused_layer<RT, kFEpiEluGrad, false>(N.wt[l], nullptr, N.fwd.out_pad[l], N.fwd.in_pad[l], d_in, stride_d, s_buf[outb], stride_h,
-                                  nullptr, 0, 0, s_buf[hl], stride_h);
-    __syncthreads();
-    tile_to_global<R>(s_buf[outb], stride_h, N.dz[l - 1], N.fwd.in_pad[l], r0, a.rows);
-    if (l > 1) global_to_tile<R>(s_buf[hl], stride_h, N.h[l - 1], N.fwd.in_pad[l - 1], r0, a.rows);
-    d_in = s_buf[outb];
-    stride_d = stride_h;
-    outb = (outb == 2) ? (hl ^ 1) : 2;
-    __syncthreads();
-  }
-}
-
-// out[c] = sum over rows of part[row][c]; one workgroup per column, fixed summation order
-__global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restrict__ part, int n_rows, int width,
-                                                          float* __restrict__ out) {
-  __shared__ float sh[4];
-  const int c = blockIdx.x;
-  float s = 0.f;
-  for (int r = threadIdx.x; r < n_rows; r += 256) s += part[(int64_t)r * width + c];
-  s = wave_sum(s);
-  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
-  __syncthreads();
-  if (threadIdx.x == 0) out[c] = sh[0] + sh[1] + sh[2] + sh[3];
-}
-
 // floats of one net's LDS bias block (the two nets have the same padded widths except for the head,
 // whose padded width is at least as large for the policy net)
 size_t bias_floats(const gmi_model* m, int net) {
   size_t n = 0;
   for (int l = 0; l < m->L.n_layers; ++l) n += m->L.net[net][l].out_pad;
   return n;
-}
-
-size_t train_lds_bytes(const gmi_model* m, int R) {
-  const ModelLayout& L = m->L;
-  int max_h = 32;
-  for (int l = 0; l < L.n_hidden; ++l) max_h = L.net[0][l].out_pad > max_h ? L.net[0][l].out_pad : max_h;
-  const int A = L.act_dim;
-  return (size_t)R * (gmi::pad32(L.obs_dim) + 8) * 2 + 3 * (size_t)R * (max_h + 8) * 2 + (size_t)R * 40 * 2 +
-         ((size_t)R * A + (size_t)R * (A + 3) + 4 * (A + 4) + bias_floats(m, 0)) * 4;
 }
 
 void fill_net(const gmi_model* m, int net, FusedNet* N) {
@@ -1367,68 +1149,6 @@ int launch_agent_fused(gmi_instance* g, gmi_model* m, const float* obs, int n, u
     ps.launch(agent_fused_kernel<1>, dim3((n + 31) / 32), dim3(256), lds, a);
   }
   GMI_LAUNCH_CHECK();
-  return GMI_OK;
-}
-
-// Gather + forward + loss + input gradients of one minibatch in one launch, then the reduction of the
-// per-tile statistics.  Leaves m->x0, m->h, m->dz ready for the weight-gradient launch and the summed
-// statistics / log_std partials in row kLossBlocksMax of m->stat_part.
-int launch_train_fused(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx,
-                       int rows) {
-  if (m->L.dtype != GMI_DTYPE_BF16) return GMI_ERR_UNSUPPORTED;
-  if (m->L.weight_bytes > (1 << 20)) return GMI_ERR_UNSUPPORTED;
-  constexpr size_t kLdsMax = 160 * 1024;
-  int R = 64;
-  if (train_lds_bytes(m, R) > kLdsMax) R = 32;
-  if (train_lds_bytes(m, R) > kLdsMax) return GMI_ERR_UNSUPPORTED;
-  const int tiles = (rows + R - 1) / R;
-  if (tiles > kLossBlocksMax) return GMI_ERR_UNSUPPORTED;
-  const ModelLayout& L = m->L;
-  TrainArgs a;
-  for (int net = 0; net < 2; ++net) {
-    fill_net(m, net, &a.net[net].fwd);
-    for (int l = 0; l < L.n_layers; ++l) {
-      a.net[net].wt[l] = reinterpret_cast<const uint16_t*>(m->shadow + L.net[net][l].sh_wt);
-      a.net[net].h[l] = (uint16_t*)m->h[net][l];
-      a.net[net].dz[l] = (uint16_t*)m->dz[net][l];
-    }
-  }
-  a.log_std = reinterpret_cast<const float*>(m->shadow + L.sh_logstd);
-  a.b_obs = b->d.obs; a.b_act = b->d.act; a.b_logp = b->d.logp; a.b_adv = b->d.adv; a.b_ret = b->d.ret;
-  a.idx = idx;
-  a.x0 = (uint16_t*)m->x0;
-  a.rows = rows; a.n_envs = b->d.n_envs; a.ld_envs = b->d.ld_envs;
-  a.obs_dim = L.obs_dim; a.obs_pad = pad32(L.obs_dim); a.act_dim = L.act_dim;
-  a.max_h = 32;
-  for (int l = 0; l < L.n_hidden; ++l) a.max_h = L.net[0][l].out_pad > a.max_h ? L.net[0][l].out_pad : a.max_h;
-  a.clip = hp->clip; a.c_v = hp->c_v;
-  a.stat_part = m->stat_part;
-  const size_t lds = train_lds_bytes(m, R);
-  {
-    ProfScope ps(g, kClsFusedTrain);
-    if (R == 64) {
-      static bool attr64 = false;
-      if (!attr64) {
-        GMI_HIP(hipFuncSetAttribute((const void*)train_fused_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
-        attr64 = true;
-      }
-      ps.launch(train_fused_kernel<2>, dim3(dim3(tiles, 2)), dim3(256), lds, a);
-    } else {
-      static bool attr32 = false;
-      if (!attr32) {
-        GMI_HIP(hipFuncSetAttribute((const void*)train_fused_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax));
-        attr32 = true;
-      }
-      ps.launch(train_fused_kernel<1>, dim3(dim3(tiles, 2)), dim3(256), lds, a);
-    }
-    GMI_LAUNCH_CHECK();
-  }
-  {
-    ProfScope ps(g, kClsReduce);
-    const int width = kStatStride + L.act_dim;
-    ps.launch(reduce_rows_kernel, dim3(width), dim3(256), 0, m->stat_part, tiles, width, m->stat_part + (int64_t)kLossBlocksMax * width);
-    GMI_LAUNCH_CHECK();
-  }
   return GMI_OK;
 }
 

@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "../../include/gmidrl.h"
+#include "../../include/gmidrl_bench.h"
 
 namespace gmi {
 
@@ -66,7 +67,7 @@ namespace gmi {
 // have one -- a model uses one or the other.)
 enum KernelClass {
   kClsGather = 0, kClsWgrad, kClsLoss, kClsAdam, kClsShadowTranspose, kClsEnvStep, kClsSample,
-  kClsCollect, kClsGae, kClsPermutation, kClsFusedAgent, kClsFusedTrain, kClsFusedRollout, kClsReduce,
+  kClsCollect, kClsGae, kClsPermutation, kClsFusedAgent, kClsFusedRollout,
   kClsLinearF32, kClsChainTrain, kClsLinear, kClsCount = kClsLinear + 15
 };
 static_assert(kClsCount < 32, "class masks are 32-bit");
@@ -82,6 +83,7 @@ struct gmi_instance {
   int device;
   hipStream_t stream;
   hipEvent_t event;      // used by gmi_transfer
+  hipEvent_t wait_event; // used by gmi_wait_stream
   int cu_count;
   int fusion;            // 1: use the row-tile fused kernels where the model fits them (default)
   uint32_t prof_mask;    // bit c set: launches of kernel class c carry timing events
@@ -275,8 +277,6 @@ int forward_nets(gmi_instance* g, gmi_model* m, int rows, bool policy, bool valu
 int launch_agent_fused(gmi_instance* g, gmi_model* m, const float* obs, int n, uint64_t seed, uint32_t step,
                        uint32_t env_offset, float* act, float* logp, float* value, float* mu_out, bool do_policy);
 
-int launch_train_fused(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx,
-                       int rows);
 
 // Shuffles of epochs epoch0 .. epoch0 + n_epochs - 1 into out[e][n], one launch.
 constexpr int kPermEpochs = 8;

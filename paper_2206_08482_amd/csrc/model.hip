@@ -1,7 +1,7 @@
 // Policy / value model: parameter layout, bf16 shadow, workspace, forward driver, and the agent role's
 // action decision (Section 3 of the paper, "DRL Agent"; model shapes as in its Table 6).
 #include "internal.h"
-#include "rng.cuh"
+#include "rng.h"
 
 
 int build_layout(const gmi_model_desc* d, ModelLayout* L) {

@@ -71,7 +71,7 @@ extern "C" int gmi_explore(gmi_profile_fn profile, void* profile_user, gmi_estim
 // ---------------------------------------------------------------------------------------------------------
 // Layout-aware gradient reduction, host logic (Section 4.1 of the paper): which of the three strategies a
 // layout of trainer instances calls for (Algorithm 1), which instance leads its GPU in the cross-GPU step of
-// the hierarchical form, and the time models of Table 3.  On one GPU only the first answer ever occurs and
+// the hierarchical form, and the time models of Table 2.  On one GPU only the first answer ever occurs and
 // this build performs that reduction in memory (ppo_update_group); the functions describe layouts this build
 // does not run.
 extern "C" int gmi_select_reduction(const int32_t* gmis_per_gpu, int32_t n_gpus, int32_t* strategy_out) {

@@ -437,17 +437,11 @@ int layers_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hpar
 // Forward + loss (+ backward products) of the `rows` samples idx[0..rows) of the buffer.
 // Leaves gradient partials in m->grad_part / m->stat_part.  Returns the split count through n_split.
 int minibatch_pass(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx,
-                   int rows, bool want_grad, int* n_split_out, int* n_loss_blocks_out, bool allow_fused = true,
-                   bool obs16_ready = false) {
+                   int rows, bool want_grad, int* n_split_out, int* n_loss_blocks_out, bool obs16_ready = false) {
   const ModelLayout& L = m->L;
   const bool bf = L.dtype == GMI_DTYPE_BF16;
   int rc = GMI_ERR_UNSUPPORTED;
   bool blocks = false;
-  if (g->fusion >= 2 && want_grad && allow_fused) {
-    // row-tile fused kernel (opt-in): statistics already summed (row kLossBlocksMax of stat_part)
-    rc = gmi::launch_train_fused(g, m, b, hp, idx, rows);
-    if (rc == GMI_OK) *n_loss_blocks_out = -1;
-  }
   if (rc == GMI_ERR_UNSUPPORTED && g->fusion >= 1 && want_grad && bf) {
     // register-chained kernel (gather + forward + loss + input gradients in one launch) where this shape has one
     rc = gmi::launch_train_chain(g, m, b, hp, idx, rows, n_loss_blocks_out, obs16_ready, &blocks);
@@ -493,11 +487,6 @@ int launch_adam(gmi_instance* g, gmi_model* const* ms, int n, int n_split, int n
   for (int i = 0; i < kMaxGroup; ++i) {
     set.part[i] = i < n ? ms[i]->grad_part : nullptr;
     set.stat[i] = i < n ? ms[i]->stat_part : nullptr;
-  }
-  if (n_loss_blocks < 0) {      // fused / chained trainer: every replica's statistics are already summed into one row
-    for (int i = 0; i < n; ++i)
-      set.stat[i] = ms[i]->stat_part + (int64_t)gmi::kLossBlocksMax * (gmi::kStatStride + m->L.act_dim);
-    n_loss_blocks = 1;
   }
   const bool bf = m->L.dtype == GMI_DTYPE_BF16;
   ps.launch(adam_kernel, dim3(grid), dim3(256), 0, tab, bf ? 1 : 0, m->params, m->adam_m, m->adam_v, set, n_split,
@@ -556,7 +545,7 @@ extern "C" int ppo_update(gmi_t g, gmi_model_t m, gmi_buffer_t b, const gmi_ppo_
     }
     for (int j = 0; j < nmb; ++j) {
       int n_split = 1, nlb = 1;
-      rc = minibatch_pass(g, m, b, hp, perm + (int64_t)j * hp->minibatch, hp->minibatch, true, &n_split, &nlb, true, obs16);
+      rc = minibatch_pass(g, m, b, hp, perm + (int64_t)j * hp->minibatch, hp->minibatch, true, &n_split, &nlb, obs16);
       if (rc != GMI_OK) return rc;
       ++k;
       rc = launch_adam(g, &m, 1, n_split, nlb, hp, hp->minibatch, k,
@@ -627,7 +616,7 @@ extern "C" int ppo_update_group(const gmi_t* gs, const gmi_model_t* ms, const gm
       for (int i = 0; i < n; ++i) {
         int ns_i = 1, nlb_i = 1;
         rc = minibatch_pass(gs[i], ms[i], bs[i], hp, bs[i]->perm + perm_off + (int64_t)j * hp->minibatch, hp->minibatch, true,
-                            &ns_i, &nlb_i, false, obs16[i]);
+                            &ns_i, &nlb_i, obs16[i]);
         if (rc != GMI_OK) return rc;
         if (i == 0) { n_split = ns_i; nlb = nlb_i; }
         // replica i's partials are complete: let instance 0 see them

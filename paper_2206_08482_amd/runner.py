@@ -12,7 +12,7 @@ import torch
 from . import (DTYPE_BF16, DTYPE_F32, agent_act, agent_value, buffer_desc, collect_experience, env_desc,
                env_step, gae_compute, gmi_buffer_bind, gmi_buffer_destroy, gmi_create, gmi_destroy,
                gmi_env_bind, gmi_env_destroy, gmi_model_bind, gmi_model_destroy, gmi_model_refresh_shadow,
-               gmi_model_shadow_bytes, gmi_stream, gmi_sync, model_desc, ppo_hparams, ppo_update,
+               gmi_model_shadow_bytes, gmi_stream, gmi_sync, gmi_wait_stream, model_desc, ppo_hparams, ppo_update,
                rollout_collect, GmiError, ERR_UNSUPPORTED, ppo_update_group)
 
 
@@ -83,7 +83,7 @@ class PPOSession:
         else:
             self.shadow = replica_of.shadow
         # torch filled the arrays above on its own stream; the library works on the instance's stream
-        torch.cuda.synchronize()
+        gmi_wait_stream(self.gmi)
         self.model = gmi_model_bind(self.gmi, self.mdesc, self.theta, self.shadow, self.adam_m, self.adam_v)
         if replica_of is None:
             gmi_model_refresh_shadow(self.gmi, self.model)
@@ -105,7 +105,7 @@ class PPOSession:
         self.done = torch.zeros(n_envs, dtype=torch.uint8, device=dev)
         self.last_value = torch.zeros(n_envs, **f)
         self.fused_rollout = fused_rollout and dtype == "bf16"
-        torch.cuda.synchronize()
+        gmi_wait_stream(self.gmi)      # the fills above (torch's stream) come before anything queued on the instance
 
     # -- stage (i): experience collection
     def rollout(self, iteration: int) -> None:

@@ -6,18 +6,19 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "gmidrl.h")
+HEADERS = [os.path.join(ROOT, "include", "gmidrl.h"), os.path.join(ROOT, "include", "gmidrl_bench.h")]
 
 
-def declared_functions():
-    text = open(HEADER).read()
+def declared_functions(headers=HEADERS):
+    text = "\n".join(open(h).read() for h in headers)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"^\s*(?:const\s+)?(?:int|void\*|int64_t|char\*|const char\*)\s+\**([a-z_0-9]+)\s*\(", text, flags=re.M)
     return sorted(set(names))
 
 
 def test_header_declares_the_seven_calls_of_the_problem_statement():
-    names = declared_functions()
+    names = declared_functions(HEADERS[:1])
+    assert not any(n.startswith(("gmi_profile_", "gmi_measure_", "gmi_bench_")) for n in names)      # measurement interface: its own header
     for fn in ("gmi_create", "agent_act", "env_step", "collect_experience", "gae_compute", "ppo_update",
                "gmi_transfer"):
         assert fn in names

@@ -245,11 +245,11 @@ def _theta_and_batch(cfg, T, N, seed=1):
     ("BB", 3, 400, 1200, "bf16", "bimodal"), ("FC", 2, 300, 555, "bf16", "bimodal"),
     ("AY", 2, 512, 1024, "bf16", "bimodal"), ("HM", 2, 700, 1400, "bf16", "bimodal"),
     ("SH", 2, 600, 1111, "bf16", "bimodal")])
-@pytest.mark.parametrize("path", ["chain", "rowtile", "layers"])
+@pytest.mark.parametrize("path", ["chain", "layers"])
 def test_gradient_and_stats_match_oracle(g, inst, name, T, N, rows, dtype, ratios, path):
-    """path: which trainer kernels compute forward, loss and input gradients: "chain" the register-chained
-    kernel (one launch; the library's default for the model shapes it is compiled for), "rowtile" the
-    row-tile fused kernel (opt-in), "layers" the per-layer kernels.
+    """path: which trainer kernels compute forward, loss and input gradients: "chain" the one-launch kernels (the
+    register-chained kernel or, for the 512-wide shapes, the row-tile kernel; the library's default for the model
+    shapes they are compiled for), "layers" the per-layer kernels.
     ratios = "straddle": old/new probability ratios spread smoothly across the clip range, so some
     samples sit within rounding distance of a clip boundary.  Which side such a sample falls on is a
     yes/no decision taken in the arithmetic of the forward pass; in fp32 both sides agree, in bf16 a
@@ -257,12 +257,10 @@ def test_gradient_and_stats_match_oracle(g, inst, name, T, N, rows, dtype, ratio
     gradient by that sample's whole contribution.  ratios = "bimodal" keeps every ratio either well
     inside or well outside the clip range, so the decisions agree and the comparison measures the
     arithmetic of the products alone."""
-    if path == "rowtile" and (dtype == "f32" or name in ("C4", "SH")):
-        pytest.skip("the row-tile fused trainer kernel covers bf16 models up to 1 MB of weights")
     if path == "chain" and (dtype == "f32" or name == "C1"):
         pytest.skip("the register-chained kernel covers the bf16 benchmark shapes")
     fused = path != "layers"
-    g.gmi_set_fusion(inst, {"chain": 1, "rowtile": 2, "layers": 0}[path])
+    g.gmi_set_fusion(inst, {"chain": 1, "layers": 0}[path])
     cfg = syn.get_config(name)
     shape, theta = _theta_and_batch(cfg, T, N)
     b, rb, hb = _filled_buffer(g, inst, cfg, T, N, seed=2)
@@ -294,10 +292,10 @@ def test_gradient_and_stats_match_oracle(g, inst, name, T, N, rows, dtype, ratio
     r_stats, r_grad = oppo.ppo_loss_and_grad(theta, shape, flat["obs"][idx], flat["act"][idx], flat["logp"][idx],
                                              flat["adv"][idx], flat["ret"][idx], ohp)
     got_g, got_s = grad.cpu().numpy(), stats.cpu().numpy()
-    # evaluate = forward + loss only.  With the row-tile fused trainer the two calls run different kernels
-    # (bias added before the products there, after them in the per-layer kernels): a few bf16 activations
-    # round the other way, which moves the batch statistics by ~1e-5 of their scale (the approximate KL
-    # is a mean of small signed terms, hence the absolute floor).
+    # evaluate = forward + loss only.  With the one-launch trainer kernels the two calls run different kernels
+    # (other order of the fp32 sums, bias inside or after them): a few bf16 activations round the other way,
+    # which moves the batch statistics by ~1e-5 of their scale (the approximate KL is a mean of small signed
+    # terms, hence the absolute floor).
     assert np.allclose(got_s, stats2.cpu().numpy(), rtol=2e-3 if fused else 1e-5, atol=2e-5 if fused else 1e-7)
     assert 0.02 < r_stats[4] < 0.9                         # the clip is active for part of the batch
     tol = 2e-4 if dtype == "f32" else TOL16
@@ -539,6 +537,27 @@ def test_error_paths(g, inst):
         g.gmi_model_destroy(hm)               # double destroy
     assert ei.value.code == g.ERR_BAD_HANDLE
     g.gmi_buffer_destroy(hb)
+
+
+def test_wait_stream_orders_the_instance_behind_a_caller_stream(g, inst):
+    """Data produced on a stream of the caller, consumed by the instance with no host synchronisation between:
+    gmi_wait_stream makes the instance's copy wait for the fills queued before it."""
+    side = torch.cuda.Stream()
+    n = 1 << 26
+    dst = torch.zeros(n, device="cuda:0")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        src = torch.empty(n, device="cuda:0")
+        for k in range(8):                       # a few hundred microseconds of work on the caller's stream
+            src.fill_(float(k))
+        src.add_(1.0)
+    g.gmi_wait_stream(inst, side)
+    g.gmi_transfer(inst, inst, src, dst, n * 4)
+    g.gmi_sync(inst)
+    assert bool((dst == 8.0).all().item())
+    side.synchronize()
+    with pytest.raises(g.GmiError):
+        g.gmi_wait_stream(0, side)
 
 
 def test_masked_instances_and_transfer(g):

@@ -1,5 +1,5 @@
 """Pins of the oracle for Algorithm 1 (communication strategy selection), the leader rule and the time models
-of the three reduction strategies (Section 4.1, Table 3)."""
+of the three reduction strategies (Section 4.1, Table 2)."""
 import itertools
 
 import pytest

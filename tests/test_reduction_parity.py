@@ -1,4 +1,4 @@
-"""The library's reduction-strategy functions (Algorithm 1, leader rule, Table 3 time models) against the oracle:
+"""The library's reduction-strategy functions (Algorithm 1, leader rule, Table 2 time models) against the oracle:
 integer / control-flow work, bit-exact; the time models to the last rounding.  Host-only: runs wherever the
 library loads."""
 import itertools
