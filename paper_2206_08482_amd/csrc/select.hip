@@ -8,12 +8,54 @@
 
 namespace {
 
-// Relative change and Sat are IEEE divisions: x/0 = +-inf, 0/0 = NaN; NaN never compares below alpha.
-double ratio(double num, double den) { return num / den; }
+// One measured operating point of an instance size.
+struct Point {
+  int envs;
+  double rate, bytes;      // throughput and memory of ONE instance
+  // a point with neither throughput nor memory cannot anchor a comparison (the listing's "trackers still 0")
+  bool anchors() const { return rate != 0.0 || bytes != 0.0; }
+};
 
-double default_estimate(int gmi_per_gpu, int num_gpu, double top, void*) {
+// Throughput gained per memory spent when an instance grows from `from` to `to`, both as relative changes.
+// IEEE divisions on purpose: x/0 = +-inf, 0/0 = NaN, and a NaN is never "below alpha".
+double gain_per_memory(const Point& from, const Point& to) {
+  const double gain = (to.rate - from.rate) / from.rate;
+  const double cost = (to.bytes - from.bytes) / from.bytes;
+  return gain / cost;
+}
+
+struct Candidate {
+  int instances, envs;
+  double system_rate;
+};
+
+double whole_system(int instances, int gpus, double rate, void*) {
   // every instance of every GPU contributes its measured throughput
-  return top * (double)gmi_per_gpu * (double)num_gpu;
+  return rate * (double)instances * (double)gpus;
+}
+
+// Grows the environments of one instance size through env_grid until growth stops paying (gain per memory below
+// alpha), measuring each size with the caller's trial run; every point that still paid becomes a candidate with
+// its projected whole-system throughput.  The first measurable point only anchors the comparison.
+int scan_instance_size(int instances, const int32_t* env_grid, int n_env, gmi_profile_fn trial, void* trial_user,
+                       gmi_estimate_fn project, void* project_user, int gpus, double alpha,
+                       std::vector<Candidate>* out) {
+  Point last = {0, 0.0, 0.0};
+  for (int i = 0; i < n_env; ++i) {
+    Point now = {env_grid[i], 0.0, 0.0};
+    int ran = 0;
+    const int rc = trial(instances, now.envs, &ran, &now.rate, &now.bytes, trial_user);
+    if (rc != 0) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_explore: profile callback failed (%d) at GMIperGPU %d, num_env %d",
+                          rc, instances, now.envs);
+    if (!ran) continue;                                  // this size does not run at all (memory, hang): skip it
+    const bool comparable = last.anchors();
+    const double paid = comparable ? gain_per_memory(last, now) : 0.0;
+    last = now;
+    if (!comparable) continue;
+    if (paid < alpha) break;                             // saturated
+    out->push_back({instances, now.envs, project(instances, gpus, now.rate, project_user)});
+  }
+  return GMI_OK;
 }
 
 }  // namespace
@@ -27,44 +69,19 @@ extern "C" int gmi_explore(gmi_profile_fn profile, void* profile_user, gmi_estim
   if (num_gpu < 1) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_explore: num_gpu must be >= 1");
   if (n_gmi < 0 || n_env < 0 || (n_gmi > 0 && !gmi_per_gpu_values) || (n_env > 0 && !num_env_values))
     GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_explore: bad value lists");
-  if (!estimate) estimate = default_estimate;
-  bool have_best = false;
-  int best_env = 0, best_gmi = 0;
-  double max_top = -INFINITY;
+  std::vector<Candidate> candidates;
   for (int a = 0; a < n_gmi; ++a) {
-    const int gmi_per_gpu = gmi_per_gpu_values[a];
-    double pre_top = 0.0, pre_mem = 0.0;
-    for (int b = 0; b < n_env; ++b) {
-      const int num_env = num_env_values[b];
-      int runnable = 0;
-      double top = 0.0, mem = 0.0;
-      const int rc = profile(gmi_per_gpu, num_env, &runnable, &top, &mem, profile_user);
-      if (rc != 0) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_explore: profile callback failed (%d) at GMIperGPU %d, num_env %d",
-                            rc, gmi_per_gpu, num_env);
-      if (!runnable) continue;
-      if (pre_top == 0.0 && pre_mem == 0.0) {
-        pre_top = top;
-        pre_mem = mem;
-        continue;
-      }
-      const double r_top = ratio(top - pre_top, pre_top);
-      const double r_mem = ratio(mem - pre_mem, pre_mem);
-      const double sat = ratio(r_top, r_mem);
-      pre_top = top;
-      pre_mem = mem;
-      if (sat < alpha) break;
-      const double acc_top = estimate(gmi_per_gpu, num_gpu, top, estimate_user);
-      if (acc_top > max_top) {
-        max_top = acc_top;
-        best_env = num_env;
-        best_gmi = gmi_per_gpu;
-        have_best = true;
-      }
-    }
+    const int rc = scan_instance_size(gmi_per_gpu_values[a], num_env_values, n_env, profile, profile_user,
+                                      estimate ? estimate : whole_system, estimate_user, num_gpu, alpha, &candidates);
+    if (rc != GMI_OK) return rc;
   }
-  *num_env_out = have_best ? best_env : 0;
-  *gmi_per_gpu_out = have_best ? best_gmi : 0;
-  if (projected_out) *projected_out = have_best ? max_top : 0.0;
+  // the candidate with the highest projected throughput; of equals the one measured first; a NaN never wins
+  const Candidate* best = nullptr;
+  for (const Candidate& c : candidates)
+    if (best ? c.system_rate > best->system_rate : c.system_rate > -INFINITY) best = &c;
+  *num_env_out = best ? best->envs : 0;
+  *gmi_per_gpu_out = best ? best->instances : 0;
+  if (projected_out) *projected_out = best ? best->system_rate : 0.0;
   return GMI_OK;
 }
 
