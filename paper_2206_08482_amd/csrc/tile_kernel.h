@@ -20,12 +20,6 @@
 // for the weight-gradient kernel) - barrier.  The next layer's first weight blocks are fetched before the epilogue.
 #pragma once
 #include "chain_kernel.h"
-#ifndef TILE_X_NOSTORE
-#define TILE_X_NOSTORE 0
-#endif
-#ifndef TILE_X_NOH
-#define TILE_X_NOH 0
-#endif
 
 namespace gmi_tile {
 using namespace gmi_chain;
@@ -163,13 +157,21 @@ __device__ __forceinline__ int64_t block_word(int tr, int nks, int ks, int rt) {
 template <class S, int SEG, int T>
 __device__ __forceinline__ void fetch_h(Ctx<S>& c, const ChainArgs& a) {
   using G = Seg<S, SEG>;
-  if constexpr (G::bwd && T < G::FTW * G::RT && !TILE_X_NOH) {
+  if constexpr (G::bwd && T < G::FTW * G::RT) {
     constexpr int ta = T / G::RT, tb = T % G::RT;
     constexpr int nks = G::D.d[G::layer] / 16;
     const int ft = c.wave * G::FTW + ta;
     const uint4* p = reinterpret_cast<const uint4*>(a.h[c.net][G::layer]) + block_word(blockIdx.x, nks, 2 * ft, tb) + c.lane;
     c.hq[T % (kHPre + 1)][0] = p[0];
     c.hq[T % (kHPre + 1)][1] = p[4 * 64];
+  }
+}
+
+template <class S, int SEG, int T>
+__device__ __forceinline__ void fetch_h_first(Ctx<S>& c, const ChainArgs& a) {
+  if constexpr (T < kHPre) {
+    fetch_h<S, SEG, T>(c, a);
+    fetch_h_first<S, SEG, T + 1>(c, a);
   }
 }
 
@@ -187,7 +189,7 @@ __device__ __forceinline__ void aux_op(Ctx<S>& c, const ChainArgs& a) {
   if constexpr (I < G::RT) {
     if constexpr (KS + G::XD < G::NKS)
       c.xq[(KS + G::XD) % 3][I] = c.X[((KS + G::XD) * 4 + (G::head ? c.wave : I)) * 64 + c.lane];
-  } else if constexpr (G::store_x && !TILE_X_NOSTORE) {
+  } else if constexpr (G::store_x) {
     if constexpr (I == G::RT) {
       c.sx[KS & 1] = c.X[(KS * 4 + c.wave) * 64 + c.lane];
     } else if constexpr (KS >= 1) {
@@ -238,10 +240,7 @@ __device__ __forceinline__ void k_steps(Ctx<S>& c, const ChainArgs& a, const uin
   using G = Seg<S, SEG>;
   if constexpr (KS < G::NKS) {
     if constexpr (G::bwd && KS == G::HK) {          // the first tiles' stored activations, late enough not to hold up
-      fetch_h<S, SEG, 0>(c, a);                     // the weight fetches behind them, early enough to be there
-      fetch_h<S, SEG, 1>(c, a);
-      fetch_h<S, SEG, 2>(c, a);
-      static_assert(kHPre == 3, "three tiles ahead");
+      fetch_h_first<S, SEG, 0>(c, a);               // the weight fetches behind them, early enough to be there
     }
     k_products<S, SEG, KS, 0>(c, a, wseg);
     k_steps<S, SEG, KS + 1>(c, a, wseg);
@@ -443,7 +442,7 @@ __device__ __forceinline__ void run_segment(Ctx<S>& c, const ChainArgs& a) {
     read_x<S, SEG, 0>(c);
     if constexpr (G::XD > 1) read_x<S, SEG, 1>(c);
     k_steps<S, SEG, 0>(c, a, wseg);
-    if constexpr (G::store_x && !TILE_X_NOSTORE)
+    if constexpr (G::store_x)
       (store_x_array<S, SEG>(c, a) + block_word(blockIdx.x, G::NKS, G::NKS - 1, c.wave))[c.lane] = c.sx[(G::NKS - 1) & 1];
 #ifdef GMI_CHAIN_TIMING
     c.ts[3 * SEG + 1] = __builtin_readcyclecounter();
