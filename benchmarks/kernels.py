@@ -50,16 +50,19 @@ def measure(copy_only=False, large_only=False):
 
     rows = []
     # GAE: T x N rewards, values, dones -> advantages, returns (25 B per sample + 4 B per env)
-    for T, N in ((64, 1 << 20),) if large_only else ((16, 4096), (64, 1 << 20)):
+    for T, N in ((64, 1 << 20),) if large_only else ((16, 4096), (32, 4096), (16, 16384), (32, 16384), (64, 1 << 20)):
         rb = RolloutBuffers(T, N, 1, 1, dev)
         rb.rew.normal_(); rb.val.normal_()
         lastv = torch.zeros(N, device=dev)
         torch.cuda.synchronize()
         hb = g.gmi_buffer_bind(h, rb.desc(0, N))
         for norm, nbytes in ((False, T * N * 17.0 + 4.0 * N), (True, T * N * 25.0 + 4.0 * N)):
-            ms = timed("gae", lambda: g.gae_compute(h, hb, lastv, 0.99, 0.95, norm))
-            rows.append({"kernel": "gae" + ("+normalize" if norm else ""), "size": f"T={T} N={N}", "bytes": nbytes,
-                         "us": ms * 1e3, "GBs": nbytes / ms / 1e6})
+            for variant, vname in ((0, ""), (1, " (wavefront scan)")):      # the default serial walk, then the scan
+                g.gmi_bench_gae_variant(variant)
+                ms = timed("gae", lambda: g.gae_compute(h, hb, lastv, 0.99, 0.95, norm))
+                rows.append({"kernel": "gae" + ("+normalize" if norm else "") + vname, "size": f"T={T} N={N}",
+                             "bytes": nbytes, "us": ms * 1e3, "GBs": nbytes / ms / 1e6})
+            g.gmi_bench_gae_variant(0)
         g.gmi_buffer_destroy(hb)
         del rb
     # Adam on caller arrays: 16 B read + 12 B written per parameter

@@ -42,6 +42,11 @@ int gmi_measure_peak(gmi_t gmi, int what, void* scratch, size_t scratch_bytes, d
 int gmi_bench_linear(gmi_t gmi, int kind, int rows, int K, int F, int n_nets, int reps, void* scratch,
                      size_t scratch_bytes, double* us_per_launch);
 
+/* gae_compute has two kernels for the recurrence over the horizon: the serial walk with one lane per env (0, the
+ * default at every size) and a wavefront scan with lanes over time (1; horizons up to 64, else the serial walk
+ * runs).  Forces one of them for every later call of the process; results agree within fp32 rounding. */
+int gmi_bench_gae_variant(int variant);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,7 @@ EXPORTS = [
     "agent_act", "agent_value", "gmi_buffer_bind", "gmi_buffer_destroy", "collect_experience",
     "gae_compute", "gae_compute_static", "ppo_update", "ppo_evaluate", "ppo_gradient", "adam_update", "gmi_noise_fill",
     "gmi_permutation", "gmi_profile_enable", "gmi_profile_classes", "gmi_profile_class_name", "gmi_profile_read",
-    "gmi_measure_peak", "gmi_bench_linear", "gmi_set_fusion", "rollout_collect", "gmi_profile_work", "gmi_explore", "ppo_update_group", "gmi_select_reduction",
+    "gmi_measure_peak", "gmi_bench_linear", "gmi_bench_gae_variant", "gmi_set_fusion", "rollout_collect", "gmi_profile_work", "gmi_explore", "ppo_update_group", "gmi_select_reduction",
     "gmi_har_leaders", "gmi_reduction_time", "gmi_channels_create", "gmi_channels_destroy", "gmi_channels_push",
     "gmi_channels_pop", "gmi_channels_count", "gmi_route_least_loaded",
 ]
@@ -123,6 +123,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "gmi_profile_class_name": (C.c_char_p, [C.c_int]),
         "gmi_profile_read": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]),
         "gmi_set_fusion": (C.c_int, [vp, C.c_int]),
+        "gmi_bench_gae_variant": (C.c_int, [C.c_int]),
         "gmi_wait_stream": (C.c_int, [vp, vp]),
         "gmi_explore": (C.c_int, [PROFILE_FN, vp, ESTIMATE_FN, vp, i32, C.c_double, C.POINTER(i32), i32,
                                   C.POINTER(i32), i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_double)]),
@@ -507,6 +508,11 @@ def gmi_bench_linear(gmi: int, kind: int, rows: int, K: int, F: int, n_nets: int
     _check(_lib.gmi_bench_linear(gmi, kind, rows, K, F, n_nets, reps, _ptr(scratch),
                                  scratch.numel() * scratch.element_size(), C.byref(out)))
     return out.value
+
+
+def gmi_bench_gae_variant(variant: int) -> None:
+    """0: serial walk (default); 1: wavefront scan."""
+    _check(_lib.gmi_bench_gae_variant(int(variant)))
 
 
 def gmi_set_fusion(gmi: int, level: int) -> None:

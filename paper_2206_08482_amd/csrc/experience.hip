@@ -83,6 +83,108 @@ __global__ __launch_bounds__(256) void gae_kernel(gmi_buffer_desc d, const float
   }
 }
 
+// The same recurrence as a wavefront scan: A_t = f_t(A_{t+1}) with the affine maps f_t(x) = delta_t + c_t x,
+// c_t = gamma lambda (1 - d_t), and composition of affine maps is associative -- (c_a, d_a) o (c_b, d_b) =
+// (c_a c_b, d_a + c_a d_b) -- so the TP = 2^k >= T consecutive lanes of one env compose their suffixes in log2 TP
+// shuffle steps (Hillis-Steele, reverse direction).  A workgroup takes 64 envs: their [T, 64] slices travel through
+// LDS so that memory is touched with lanes over envs (coalesced on the time-major layout) and the scan runs with
+// lanes over time.  Horizons up to 64.  The sums are formed in another order than the serial walk's (a tree instead
+// of a chain): equal within the fp32 rounding of T terms.
+constexpr int kScanEnvs = 64;
+template <int TP>
+__global__ __launch_bounds__(256) void gae_scan_kernel(gmi_buffer_desc d, const float* __restrict__ last_value,
+                                                       float gamma, float gl, double* __restrict__ part) {
+  extern __shared__ float s_gae[];                      // [T + 1][65] values, [T][65] rewards -> advantages, [T][65] done
+  const int T = d.horizon, ldl = kScanEnvs + 1;
+  float* s_v = s_gae;
+  float* s_r = s_v + (T + 1) * ldl;
+  float* s_d = s_r + T * ldl;
+  const int e0 = blockIdx.x * kScanEnvs, tid = threadIdx.x;
+  for (int i = tid; i < T * kScanEnvs; i += 256) {
+    const int t = i / kScanEnvs, e = i % kScanEnvs;
+    const bool ok = e0 + e < d.n_envs;
+    const int64_t g = (int64_t)t * d.ld_envs + e0 + e;
+    s_v[t * ldl + e] = ok ? d.val[g] : 0.f;
+    s_r[t * ldl + e] = ok ? d.rew[g] : 0.f;
+    s_d[t * ldl + e] = ok ? (float)d.done[g] : 0.f;
+  }
+  if (tid < kScanEnvs) s_v[T * ldl + tid] = e0 + tid < d.n_envs ? last_value[e0 + tid] : 0.f;
+  __syncthreads();
+  double s1 = 0.0, s2 = 0.0;
+  for (int slot = tid; slot < kScanEnvs * TP; slot += 256) {       // TP consecutive lanes = one env's timeline
+    const int e = slot / TP, t = slot % TP;
+    const bool in = t < T;
+    float c = 1.f, a = 0.f, v = 0.f;                    // past the horizon: the identity map
+    if (in) {
+      const float nd = 1.0f - s_d[t * ldl + e];
+      v = s_v[t * ldl + e];
+      c = gl * nd;
+      a = s_r[t * ldl + e] + gamma * s_v[(t + 1) * ldl + e] * nd - v;
+    }
+#pragma unroll
+    for (int off = 1; off < TP; off <<= 1) {
+      const float cp = __shfl_down(c, off, TP), ap = __shfl_down(a, off, TP);
+      if (t + off < TP) { a = a + c * ap; c = c * cp; }
+    }
+    if (in) {
+      s_r[t * ldl + e] = a;                              // the advantage takes the reward's place
+      if (e0 + e < d.n_envs) { s1 += (double)a; s2 += (double)a * (double)a; }
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < T * kScanEnvs; i += 256) {
+    const int t = i / kScanEnvs, e = i % kScanEnvs;
+    if (e0 + e < d.n_envs) {
+      const int64_t g = (int64_t)t * d.ld_envs + e0 + e;
+      const float a = s_r[t * ldl + e];
+      d.adv[g] = a;
+      d.ret[g] = a + s_v[t * ldl + e];
+    }
+  }
+  if (part) {
+    __shared__ double sh[2][4];
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    const int w = tid >> 6;
+    if ((tid & 63) == 0) { sh[0][w] = s1; sh[1][w] = s2; }
+    __syncthreads();
+    if (tid == 0) {
+      part[2 * blockIdx.x + 0] = sh[0][0] + sh[0][1] + sh[0][2] + sh[0][3];
+      part[2 * blockIdx.x + 1] = sh[1][0] + sh[1][1] + sh[1][2] + sh[1][3];
+    }
+  }
+}
+
+// Which of the two GAE kernels a call takes: 0 the serial walk (lane per env), 1 the wavefront scan.  The serial
+// walk is the default at every size (measured: it is the faster one wherever the two differ, see the profiles);
+// the measurement interface can force either.
+int g_gae_variant = 0;
+
+// Launches the chosen GAE kernel on `stream`; returns the number of partial-sum pairs it leaves in `part`.
+template <typename Launch>
+int launch_gae(int variant, const gmi_buffer_desc& d, const float* last_value, float gamma, float gl, double* part,
+               Launch&& launch) {
+  if (variant == 1 && d.horizon <= 64) {
+    const int n_part = (d.n_envs + kScanEnvs - 1) / kScanEnvs;
+    const size_t lds = sizeof(float) * (size_t)(3 * d.horizon + 1) * (kScanEnvs + 1);
+    int tp = 1;
+    while (tp < d.horizon) tp <<= 1;
+    switch (tp) {
+      case 1: launch(gae_scan_kernel<1>, n_part, lds); break;
+      case 2: launch(gae_scan_kernel<2>, n_part, lds); break;
+      case 4: launch(gae_scan_kernel<4>, n_part, lds); break;
+      case 8: launch(gae_scan_kernel<8>, n_part, lds); break;
+      case 16: launch(gae_scan_kernel<16>, n_part, lds); break;
+      case 32: launch(gae_scan_kernel<32>, n_part, lds); break;
+      default: launch(gae_scan_kernel<64>, n_part, lds); break;
+    }
+    return n_part;
+  }
+  const int n_part = (d.n_envs + 255) / 256;
+  launch(gae_kernel, n_part, (size_t)0);
+  return n_part;
+}
+
 // A <- (A - mean) / (std + 1e-8); every workgroup re-reduces the (small) partial array in the same
 // order, so the statistics are identical everywhere and reproducible.
 __global__ __launch_bounds__(256) void normalize_kernel(gmi_buffer_desc d, const double* __restrict__ part,
@@ -131,7 +233,7 @@ extern "C" int gmi_buffer_bind(gmi_t g, const gmi_buffer_desc* d, gmi_buffer_t* 
   gmi_buffer* b = new gmi_buffer();
   b->magic = gmi::kMagicBuffer;
   b->d = *d;
-  b->n_part = (d->n_envs + 255) / 256;
+  b->n_part = (d->n_envs + kScanEnvs - 1) / kScanEnvs;      // room for either GAE kernel's partial sums
   b->part = nullptr;
   b->perm = nullptr;
   b->obs16 = nullptr;
@@ -195,14 +297,17 @@ extern "C" int gae_compute(gmi_t g, gmi_buffer_t b, const float* last_value, flo
   if (b->d.n_envs == 0 || b->d.horizon == 0) return GMI_OK;
   if (!last_value) GMI_FAIL(GMI_ERR_INVALID_ARG, "gae_compute: last_value is NULL");
   gmi::ProfScope ps(g, gmi::kClsGae);
-  ps.launch(gae_kernel, dim3(b->n_part), dim3(256), 0, b->d, last_value, gamma, gamma * lambda,
-                                               normalize ? b->part : nullptr);
+  const int n_part = launch_gae(g_gae_variant, b->d, last_value, gamma, gamma * lambda, normalize ? b->part : nullptr,
+                                [&](auto kernel, int grid, size_t lds) {
+                                  ps.launch(kernel, dim3(grid), dim3(256), lds, b->d, last_value, gamma, gamma * lambda,
+                                            normalize ? b->part : nullptr);
+                                });
   GMI_LAUNCH_CHECK();
   if (normalize) {
     const int64_t total = (int64_t)b->d.horizon * b->d.n_envs;
     int grid = (int)((total + 1023) / 1024);
     if (grid > 2048) grid = 2048;
-    ps.launch(normalize_kernel, dim3(grid), dim3(256), 0, b->d, b->part, b->n_part);
+    ps.launch(normalize_kernel, dim3(grid), dim3(256), 0, b->d, b->part, n_part);
     GMI_LAUNCH_CHECK();
   }
   return GMI_OK;
@@ -246,8 +351,8 @@ extern "C" int gae_compute_static(gmi_t g, int32_t horizon, int32_t n_envs, int3
     GMI_FAIL(GMI_ERR_BAD_SHAPE, "gae_compute_static: need horizon, n_envs >= 0 and ld_envs >= n_envs");
   if ((int64_t)horizon * n_envs >= (1ll << 31))
     GMI_FAIL(GMI_ERR_BAD_SHAPE, "gae_compute_static: horizon * n_envs must be below 2^31");
-  const int n_part = (n_envs + 255) / 256;
-  if (n_part > kStaticPartMax)
+  const int variant = g_gae_variant == 1 && horizon <= 64 ? 1 : 0;
+  if ((n_envs + (variant ? kScanEnvs : 256) - 1) / (variant ? kScanEnvs : 256) > kStaticPartMax)
     GMI_FAIL(GMI_ERR_BAD_SHAPE, "gae_compute_static: n_envs=%d exceeds the %d envs its fixed partial-sum array covers "
              "(use gae_compute on a buffer binding)", n_envs, 256 * kStaticPartMax);
   if (n_envs == 0 || horizon == 0) return GMI_OK;
@@ -262,8 +367,11 @@ extern "C" int gae_compute_static(gmi_t g, int32_t horizon, int32_t n_envs, int3
   d.adv = adv; d.ret = ret;
   // every workgroup of gae_kernel writes its own two partials and normalize_kernel reads exactly those: nothing
   // of an earlier call is read, so nothing needs clearing
-  hipLaunchKernelGGL(gae_kernel, dim3(n_part), dim3(256), 0, g->stream, d, last_value, gamma, gamma * lambda,
-                     normalize ? part : nullptr);
+  const int n_part = launch_gae(variant, d, last_value, gamma, gamma * lambda, normalize ? part : nullptr,
+                                [&](auto kernel, int grid, size_t lds) {
+                                  hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds, g->stream, d, last_value, gamma,
+                                                     gamma * lambda, normalize ? part : nullptr);
+                                });
   GMI_LAUNCH_CHECK();
   if (normalize) {
     const int64_t total = (int64_t)horizon * n_envs;
@@ -272,5 +380,13 @@ extern "C" int gae_compute_static(gmi_t g, int32_t horizon, int32_t n_envs, int3
     hipLaunchKernelGGL(normalize_kernel, dim3(grid), dim3(256), 0, g->stream, d, (const double*)part, n_part);
     GMI_LAUNCH_CHECK();
   }
+  return GMI_OK;
+}
+
+// Measurement interface: forces one of the two GAE kernels for every later gae_compute / gae_compute_static call of
+// the process (0 the serial walk, the default; 1 the wavefront scan).
+extern "C" int gmi_bench_gae_variant(int variant) {
+  if (variant != 0 && variant != 1) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_bench_gae_variant: 0 or 1");
+  g_gae_variant = variant;
   return GMI_OK;
 }

@@ -150,7 +150,10 @@ def test_collect_experience_fills_slot_t_of_a_column_slice(g, inst):
 
 @pytest.mark.parametrize("T,N,ld,normalize", [(16, 64, 64, True), (1, 1, 1, False), (32, 4096, 4096, True),
                                               (7, 1000, 1024, True), (64, 300, 300, False), (16, 70000, 70000, True)])
-def test_gae_matches_oracle(g, inst, T, N, ld, normalize):
+@pytest.mark.parametrize("variant", [0, 1])
+def test_gae_matches_oracle(g, inst, T, N, ld, normalize, variant):
+    """variant 0: the serial walk with a lane per env (the default); 1: the wavefront scan with lanes over time."""
+    g.gmi_bench_gae_variant(variant)
     b = syn.make_rollout_batch(T, N, 3, 2, seed=T + N, done_prob=0.1)
     rb, hb = _bind_buffer(g, inst, T, N, ld, 3, 2)
     rb.rew[:, :N] = dev(b["rew"])
@@ -165,6 +168,7 @@ def test_gae_matches_oracle(g, inst, T, N, ld, normalize):
     if ld > N:
         assert not rb.adv[:, N:].any().item()
     g.gmi_buffer_destroy(hb)
+    g.gmi_bench_gae_variant(0)
 
 
 # ----------------------------------------------------------------------------- agent
