@@ -366,7 +366,16 @@ int gmi_channels_push(gmi_t agent, gmi_channels_t ch, gmi_buffer_t src, const fl
 int gmi_channels_pop(gmi_t trainer, gmi_channels_t ch, int32_t n_slabs, int32_t env0, int32_t take,
                      gmi_buffer_t dst, int32_t dst_col0, float* last_value_out);
 
-/* Ring state: slabs waiting, and the totals pushed / popped so far (any pointer may be NULL).  Host only. */
+/* Discards the n_slabs oldest waiting slabs unread (host only, nothing is copied): what an agent that must not
+ * wait does when the ring is full, so that the trainer always finds the freshest experience (the asynchronous
+ * setting of Section 5.2, where serving and training run at their own rates).  The next push into such a slab
+ * first waits, on its stream, for the discarded push to finish.  GMI_ERR_UNSUPPORTED (nothing done) when fewer
+ * than n_slabs are waiting. */
+int gmi_channels_drop(gmi_channels_t ch, int32_t n_slabs);
+
+/* Ring state: slabs waiting, and the totals pushed / popped so far (any pointer may be NULL; slabs discarded =
+ * pushed - popped - waiting).  Host only.  push, pop, drop and count may be called from different host threads:
+ * the ring state is guarded by a lock (the order of slabs is the order in which pushes took that lock). */
 int gmi_channels_count(gmi_channels_t ch, int32_t* waiting, int64_t* pushed, int64_t* popped);
 
 /* The migrator's choice among several trainer instances (Section 4.2: the trainer "with the least workload"):

@@ -27,7 +27,7 @@ EXPORTS = [
     "gmi_permutation", "gmi_profile_enable", "gmi_profile_classes", "gmi_profile_class_name", "gmi_profile_read",
     "gmi_measure_peak", "gmi_bench_linear", "gmi_bench_gae_variant", "gmi_set_fusion", "rollout_collect", "gmi_profile_work", "gmi_explore", "ppo_update_group", "gmi_select_reduction",
     "gmi_har_leaders", "gmi_reduction_time", "gmi_channels_create", "gmi_channels_destroy", "gmi_channels_push",
-    "gmi_channels_pop", "gmi_channels_count", "gmi_route_least_loaded",
+    "gmi_channels_pop", "gmi_channels_drop", "gmi_channels_count", "gmi_route_least_loaded",
 ]
 
 
@@ -109,6 +109,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "gmi_channels_destroy": (C.c_int, [vp]),
         "gmi_channels_push": (C.c_int, [vp, vp, vp, vp]),
         "gmi_channels_pop": (C.c_int, [vp, vp, i32, i32, i32, vp, i32, vp]),
+        "gmi_channels_drop": (C.c_int, [vp, i32]),
         "gmi_channels_count": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]),
         "gmi_route_least_loaded": (C.c_int, [C.POINTER(i64), i32, C.POINTER(i32)]),
         "gmi_select_reduction": (C.c_int, [C.POINTER(i32), i32, C.POINTER(i32)]),
@@ -364,6 +365,10 @@ def gmi_channels_push(agent: int, ch: int, src_buffer: int, last_value) -> None:
 def gmi_channels_pop(trainer: int, ch: int, n_slabs: int, env0: int, take: int, dst_buffer: int, dst_col0: int,
                      last_value_out) -> None:
     _check(_lib.gmi_channels_pop(trainer, ch, n_slabs, env0, take, dst_buffer, dst_col0, _ptr(last_value_out)))
+
+
+def gmi_channels_drop(ch: int, n_slabs: int) -> None:
+    _check(_lib.gmi_channels_drop(ch, n_slabs))
 
 
 def gmi_channels_count(ch: int):

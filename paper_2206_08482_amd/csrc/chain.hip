@@ -80,19 +80,14 @@ const part_fn kParts[gmi::kChainParts] = {gmi::launch_chain_part0, gmi::launch_c
 const part_fn kFwdParts[gmi::kChainFwdParts] = {gmi::launch_chain_fwd_part0, gmi::launch_chain_fwd_part1};
 // The row-tile kernel's shapes (tile_kernel.h) come first: a model shape compiled for both takes that one.
 const part_fn kTileFns[gmi::kTileParts] = {gmi::launch_tile_part0, gmi::launch_tile_part1};
-bool tile_enabled() {
-  static const bool on = getenv("GMI_DISABLE_TILE") == nullptr;
-  return on;
-}
 
 // What the trainer kernel compiled for this model's shape answers to the probe: its largest group, plus 256 if it
 // can gather its rows from the bf16 copy of all observations; 0 if there is none.
 int compiled_probe(const ModelLayout& L) {
   ChainArgs none = {};
   int v = 0;
-  if (tile_enabled())
-    for (int p = 0; p < gmi::kTileParts; ++p)
-      if (kTileFns[p](nullptr, L, none, 0, &v, 0.0, 0.0) == GMI_OK) return v;
+  for (int p = 0; p < gmi::kTileParts; ++p)
+    if (kTileFns[p](nullptr, L, none, 0, &v, 0.0, 0.0) == GMI_OK) return v;
   for (int p = 0; p < gmi::kChainParts; ++p)
     if (kParts[p](nullptr, L, none, 0, &v, 0.0, 0.0) == GMI_OK) return v;
   return 0;
@@ -248,8 +243,7 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_p
   }
   rc = GMI_ERR_UNSUPPORTED;
   *blocks = false;
-  if (tile_enabled())
-    for (int p = 0; p < kTileParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = kTileFns[p](g, L, a, rows, &tiles, flops, bytes);
+  for (int p = 0; p < kTileParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = kTileFns[p](g, L, a, rows, &tiles, flops, bytes);
   if (rc == GMI_OK) *blocks = true;
   for (int p = 0; p < kChainParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = kParts[p](g, L, a, rows, &tiles, flops, bytes);
   if (rc != GMI_OK) return rc;

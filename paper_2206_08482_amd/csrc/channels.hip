@@ -10,6 +10,8 @@
 // (filled: recorded on the agent's stream, awaited by the trainer's; freed: the other way round).
 #include "internal.h"
 
+#include <mutex>
+
 struct gmi_channels {
   uint32_t magic;
   int device;
@@ -21,7 +23,8 @@ struct gmi_channels {
   int head, count;            // ring state (host)
   int64_t pushed, popped;
   std::vector<hipEvent_t> filled, freed;
-  std::vector<char> was_popped;
+  std::vector<char> was_popped, was_dropped;
+  std::mutex mu;              // the ring state above: agents and the trainer may call from threads of their own
 };
 
 namespace {
@@ -152,6 +155,7 @@ extern "C" int gmi_channels_create(const gmi_channels_desc* d, int device, gmi_c
   c->filled.resize(d->capacity);
   c->freed.resize(d->capacity);
   c->was_popped.assign(d->capacity, 0);
+  c->was_dropped.assign(d->capacity, 0);
   for (int i = 0; i < d->capacity; ++i) {
     if (hipEventCreateWithFlags(&c->filled[i], hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&c->freed[i], hipEventDisableTiming) != hipSuccess) {
@@ -183,10 +187,15 @@ extern "C" int gmi_channels_push(gmi_t g, gmi_channels_t c, gmi_buffer_t src, co
   if (b.horizon != c->d.horizon || b.n_envs != c->d.n_envs || b.obs_dim != c->d.obs_dim || b.act_dim != c->d.act_dim)
     GMI_FAIL(GMI_ERR_BAD_SHAPE, "gmi_channels_push: buffer [T %d, N %d, O %d, A %d] does not match the channels' slab [%d, %d, %d, %d]",
              b.horizon, b.n_envs, b.obs_dim, b.act_dim, c->d.horizon, c->d.n_envs, c->d.obs_dim, c->d.act_dim);
+  std::lock_guard<std::mutex> hold(c->mu);
   if (c->count >= c->d.capacity) GMI_FAIL(GMI_ERR_UNSUPPORTED, "gmi_channels_push: all %d slabs are waiting for the trainer", c->d.capacity);
   if (g->device != c->device) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_channels_push: instance and channels live on different devices");
   const int slab = (c->head + c->count) % c->d.capacity;
   if (c->was_popped[slab]) GMI_HIP(hipStreamWaitEvent(g->stream, c->freed[slab], 0));   // the trainer has read it out
+  if (c->was_dropped[slab]) {      // discarded unread: its writer (perhaps another agent's stream) must have finished
+    GMI_HIP(hipStreamWaitEvent(g->stream, c->filled[slab], 0));
+    c->was_dropped[slab] = 0;
+  }
   MoveArgs a;
   a.b = b;
   for (int i = 0; i < 8; ++i) a.s[i] = slab_ptrs(c, slab);
@@ -215,6 +224,7 @@ extern "C" int gmi_channels_pop(gmi_t g, gmi_channels_t c, int32_t n_slabs, int3
   if (!::valid(dst)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_channels_pop: bad buffer");
   if (!last_value_out) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_channels_pop: last_value_out is NULL");
   if (n_slabs < 1 || n_slabs > 8) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_channels_pop: 1 <= n_slabs <= 8 per call");
+  std::lock_guard<std::mutex> hold(c->mu);
   if (n_slabs > c->count) GMI_FAIL(GMI_ERR_UNSUPPORTED, "gmi_channels_pop: %d slabs asked for, %d waiting", n_slabs, c->count);
   if (env0 < 0 || take < 1 || env0 + take > c->d.n_envs)
     GMI_FAIL(GMI_ERR_BAD_SHAPE, "gmi_channels_pop: slice [%d, %d) outside a slab's %d envs", env0, env0 + take, c->d.n_envs);
@@ -256,8 +266,20 @@ extern "C" int gmi_channels_pop(gmi_t g, gmi_channels_t c, int32_t n_slabs, int3
   return GMI_OK;
 }
 
+extern "C" int gmi_channels_drop(gmi_channels_t c, int32_t n_slabs) {
+  if (!valid(c)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_channels_drop: bad handle");
+  if (n_slabs < 0) GMI_FAIL(GMI_ERR_INVALID_ARG, "gmi_channels_drop: n_slabs < 0");
+  std::lock_guard<std::mutex> hold(c->mu);
+  if (n_slabs > c->count) GMI_FAIL(GMI_ERR_UNSUPPORTED, "gmi_channels_drop: %d slabs to discard, %d waiting", n_slabs, c->count);
+  for (int i = 0; i < n_slabs; ++i) c->was_dropped[(c->head + i) % c->d.capacity] = 1;
+  c->head = (c->head + n_slabs) % c->d.capacity;
+  c->count -= n_slabs;
+  return GMI_OK;
+}
+
 extern "C" int gmi_channels_count(gmi_channels_t c, int32_t* waiting, int64_t* pushed, int64_t* popped) {
   if (!valid(c)) GMI_FAIL(GMI_ERR_BAD_HANDLE, "gmi_channels_count: bad handle");
+  std::lock_guard<std::mutex> hold(c->mu);
   if (waiting) *waiting = c->count;
   if (pushed) *pushed = c->pushed;
   if (popped) *popped = c->popped;
