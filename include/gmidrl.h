@@ -174,6 +174,25 @@ int agent_act(gmi_t gmi, gmi_model_t model, const float* obs, int32_t n_rows, ui
 /* value = V(obs) only: the bootstrap value of the state after the last collected step. */
 int agent_value(gmi_t gmi, gmi_model_t model, const float* obs, int32_t n_rows, float* value);
 
+/* Agents that only serve, in 8-bit floating point (the agent role of Section 3 needs the forward pass alone).
+ * A gmi_fp8_t holds, in device memory it owns, the model's weights as E4M3 (the OCP 8-bit format: 4 exponent bits,
+ * bias 7, 3 mantissa bits, largest value 448) in matrix-instruction operand order, one power-of-two scale per
+ * layer (the smallest s with max|W_l| / s <= 448), fp32 biases and log_std, and a [max_rows, act_dim] fp32 array
+ * for the means.  desc: shapes and max_rows as for gmi_model_bind (dtype is ignored); layers up to 512 wide (GMI_ERR_UNSUPPORTED beyond what fits in LDS).
+ * gmi_fp8_refresh quantises from params dev fp32 [P] (the flat parameter vector of gmi_model_bind) on the
+ * instance's stream: call it after every parameter publication the agent should see. */
+typedef struct gmi_fp8* gmi_fp8_t;
+int gmi_fp8_bind(gmi_t gmi, const gmi_model_desc* desc, gmi_fp8_t* out);
+int gmi_fp8_refresh(gmi_t gmi, gmi_fp8_t weights, const float* params);
+int gmi_fp8_destroy(gmi_fp8_t weights);
+
+/* agent_act through the fp8 weights: the observation and every hidden activation are rounded to E4M3 (nearest
+ * even, saturating at +-448, no scale), products accumulate in fp32, then scale, fp32 bias and ELU; the heads'
+ * outputs are fp32.  Noise, action and log-density exactly as agent_act.  Same arguments and layouts as agent_act;
+ * n_rows <= the binding's max_rows. */
+int agent_act_fp8(gmi_t gmi, gmi_fp8_t weights, const float* obs, int32_t n_rows, uint64_t seed, uint32_t step,
+                  uint32_t env_offset, float* act, float* logp, float* value, float* mu);
+
 /* ------------------------------------------------------------------ experience -------------- */
 
 typedef struct {

@@ -22,7 +22,7 @@ EXPORTS = [
     "gmi_create", "gmi_destroy", "gmi_stream", "gmi_sync", "gmi_cu_count", "gmi_last_error",
     "gmi_wait_stream", "gmi_transfer", "gmi_model_param_count", "gmi_model_shadow_bytes", "gmi_model_bind",
     "gmi_model_destroy", "gmi_model_refresh_shadow", "gmi_env_bind", "gmi_env_destroy", "env_step",
-    "agent_act", "agent_value", "gmi_buffer_bind", "gmi_buffer_destroy", "collect_experience",
+    "agent_act", "agent_value", "gmi_fp8_bind", "gmi_fp8_refresh", "gmi_fp8_destroy", "agent_act_fp8", "gmi_buffer_bind", "gmi_buffer_destroy", "collect_experience",
     "gae_compute", "gae_compute_static", "ppo_update", "ppo_evaluate", "ppo_gradient", "adam_update", "gmi_noise_fill",
     "gmi_permutation", "gmi_profile_enable", "gmi_profile_classes", "gmi_profile_class_name", "gmi_profile_read",
     "gmi_measure_peak", "gmi_bench_linear", "gmi_bench_gae_variant", "gmi_set_fusion", "rollout_collect", "gmi_profile_work", "gmi_explore", "ppo_update_group", "gmi_select_reduction",
@@ -96,6 +96,10 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "env_step": (C.c_int, [vp, vp, vp, vp, u32, vp, vp, vp]),
         "agent_act": (C.c_int, [vp, vp, vp, i32, u64, u32, u32, vp, vp, vp, vp]),
         "agent_value": (C.c_int, [vp, vp, vp, i32, vp]),
+        "gmi_fp8_bind": (C.c_int, [vp, C.POINTER(ModelDesc), C.POINTER(vp)]),
+        "gmi_fp8_refresh": (C.c_int, [vp, vp, vp]),
+        "gmi_fp8_destroy": (C.c_int, [vp]),
+        "agent_act_fp8": (C.c_int, [vp, vp, vp, i32, u64, u32, u32, vp, vp, vp, vp]),
         "gmi_buffer_bind": (C.c_int, [vp, C.POINTER(BufferDesc), C.POINTER(vp)]),
         "gmi_buffer_destroy": (C.c_int, [vp]),
         "collect_experience": (C.c_int, [vp, vp, i32, vp, vp, vp, vp, vp, vp]),
@@ -281,6 +285,26 @@ def agent_act(gmi: int, model: int, obs, n_rows: int, seed: int, step: int, env_
 
 def agent_value(gmi: int, model: int, obs, n_rows: int, value) -> None:
     _check(_lib.agent_value(gmi, model, _ptr(obs), n_rows, _ptr(value)))
+
+
+def gmi_fp8_bind(gmi: int, desc: ModelDesc) -> int:
+    out = C.c_void_p()
+    _check(_lib.gmi_fp8_bind(gmi, C.byref(desc), C.byref(out)))
+    return out.value
+
+
+def gmi_fp8_refresh(gmi: int, weights: int, params) -> None:
+    _check(_lib.gmi_fp8_refresh(gmi, weights, _ptr(params)))
+
+
+def gmi_fp8_destroy(weights: int) -> None:
+    _check(_lib.gmi_fp8_destroy(weights))
+
+
+def agent_act_fp8(gmi: int, weights: int, obs, n_rows: int, seed: int, step: int, env_offset: int, act, logp,
+                  value, mu=None) -> None:
+    _check(_lib.agent_act_fp8(gmi, weights, _ptr(obs), n_rows, seed, step, env_offset, _ptr(act), _ptr(logp),
+                              _ptr(value), _ptr(mu)))
 
 
 # ---------------------------------------------------------------- experience

@@ -301,6 +301,9 @@ void fill_chain_emit(const ModelLayout& L, ChainEmit* ce);
 // Forward pass of n_rows observation rows through the forward-only chained kernel: policy means into mu (NULL: value
 // net only) and values into val.  GMI_ERR_UNSUPPORTED (no message) if no such kernel is compiled for the shape.
 int launch_forward_chain(gmi_instance* g, gmi_model* m, const float* obs, int n_rows, float* mu, float* val);
+// The action decision from given means: act = mu + exp(log_std) * eps, logp, optional copy of mu (model.hip).
+int launch_sample(gmi_instance* g, const float* mu, const float* log_std, int n_rows, int act_dim, uint64_t seed,
+                  uint32_t step, uint32_t env_offset, float* act, float* logp, float* mu_out);
 // obs16_ready: b->obs16 holds the bf16 copy of the buffer's present observations (prepare_obs16).
 // *blocks = whether the hidden activations and gradients were left in the row-tile kernel's block layout.
 int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_ppo_hparams* hp, const int32_t* idx, int rows,

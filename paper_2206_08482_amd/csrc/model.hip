@@ -182,6 +182,15 @@ __global__ void sample_kernel(const float* __restrict__ mu, const float* __restr
 
 namespace gmi {
 
+int launch_sample(gmi_instance* g, const float* mu, const float* log_std, int n_rows, int act_dim, uint64_t seed,
+                  uint32_t step, uint32_t env_offset, float* act, float* logp, float* mu_out) {
+  ProfScope ps(g, kClsSample);
+  ps.launch(sample_kernel, dim3((n_rows + 127) / 128), dim3(128), 0, mu, log_std, n_rows, act_dim, (uint32_t)seed,
+            (uint32_t)(seed >> 32), step, env_offset, act, logp, mu_out);
+  GMI_LAUNCH_CHECK();
+  return GMI_OK;
+}
+
 int launch_gather(gmi_instance* g, gmi_model* m, const float* obs, int n_envs, int ld_envs,
                   const int32_t* idx, int rows, const gmi_buffer_desc* ex) {
   return launch_gather_to(g, m, obs, n_envs, ld_envs, idx, rows, ex, m->x0);
@@ -386,11 +395,7 @@ extern "C" int agent_act(gmi_t g, gmi_model_t m, const float* obs, int32_t n_row
   if (rc != GMI_OK) return rc;
   const float* log_std = m->L.dtype == GMI_DTYPE_BF16 ? reinterpret_cast<const float*>(m->shadow + m->L.sh_logstd)
                                                       : m->params + m->L.logstd_off;
-  gmi::ProfScope ps(g, gmi::kClsSample);
-  ps.launch(sample_kernel, dim3((n_rows + 127) / 128), dim3(128), 0, m->mu, log_std, n_rows, m->L.act_dim, (uint32_t)seed,
-                                                             (uint32_t)(seed >> 32), step, env_offset, act, logp, mu);
-  GMI_LAUNCH_CHECK();
-  return GMI_OK;
+  return gmi::launch_sample(g, m->mu, log_std, n_rows, m->L.act_dim, seed, step, env_offset, act, logp, mu);
 }
 
 extern "C" int agent_value(gmi_t g, gmi_model_t m, const float* obs, int32_t n_rows, float* value) {
