@@ -5,6 +5,11 @@ At the benchmark configurations GAE, Adam, the env step and the experience store
 which is below launch latency and inside the caches; this script runs the same kernels (through the same
 C-ABI entry points) on inputs of ~0.5-2 GB and prints achieved GB/s against the 8 TB/s HBM peak and against
 a plain copy kernel on the same device.  One JSON object on stdout.
+
+    python benchmarks/kernels.py [--large-only | --copy-only]
+
+--large-only: only the inputs of 0.5 GB and more; --copy-only: only the copy kernel (the calibration run for the
+hardware counters FETCH_SIZE and WRITE_SIZE).
 """
 from __future__ import annotations
 
@@ -111,7 +116,7 @@ def measure(copy_only=False, large_only=False):
 
 
 def main() -> int:
-    print(json.dumps(measure(copy_only="--copy-only" in sys.argv)))
+    print(json.dumps(measure(copy_only="--copy-only" in sys.argv, large_only="--large-only" in sys.argv)))
     return 0
 
 

@@ -293,8 +293,7 @@ int ppo_update(gmi_t gmi, gmi_model_t model, gmi_buffer_t buf, const gmi_ppo_hpa
  * backward of its slice on its own stream, instance 0 then sums all partials (fixed order), divides by n,
  * takes the Adam step and refreshes the shared shadow, and the others wait for it before their next slice.
  * stats_out dev fp32 [epochs * (T*N/minibatch), 5]: means over the instances; may be NULL.
- * host: the three handle arrays.  n = 1 is ppo_update.  At most 16 instances; the row-tile fused trainer
- * is not used here. */
+ * host: the three handle arrays.  n = 1 is ppo_update.  At most 16 instances. */
 int ppo_update_group(const gmi_t* gmis, const gmi_model_t* models, const gmi_buffer_t* bufs, int32_t n,
                      const gmi_ppo_hparams* hp, float* stats_out);
 

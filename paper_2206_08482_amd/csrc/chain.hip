@@ -97,13 +97,6 @@ bool compiled_x16(const ModelLayout& L) { return (compiled_probe(L) & 256) != 0;
 
 }  // namespace
 
-#ifdef GMI_CHAIN_TIMING
-static long long* g_chain_dbg = nullptr;
-extern "C" int gmi_chain_timing(long long* out, int n) {
-  if (!g_chain_dbg) return -1;
-  return (int)hipMemcpy(out, g_chain_dbg, (size_t)n * 8, hipMemcpyDeviceToHost);
-}
-#endif
 
 namespace gmi {
 using namespace gmi_chain;
@@ -210,12 +203,6 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_p
   a.rows = rows; a.act_dim = L.act_dim;
   a.clip = hp->clip; a.c_v = hp->c_v;
   a.stat_part = m->stat_part;
-#ifdef GMI_CHAIN_TIMING
-  static long long* dbg = nullptr;
-  if (!dbg) { GMI_HIP(hipMalloc(&dbg, 4096 * 8)); GMI_HIP(hipMemset(dbg, 0, 4096 * 8)); }
-  a.dbg = dbg;
-  g_chain_dbg = dbg;
-#endif
   int tiles = 0, rc;
   if (rows < 1 || rows > m->max_rows) return GMI_ERR_UNSUPPORTED;      // the activation arrays hold max_rows (in whole tiles)
   // algorithmic work at the logical (unpadded) widths: forward products of every layer, input-gradient products

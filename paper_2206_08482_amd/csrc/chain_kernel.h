@@ -199,9 +199,6 @@ struct ChainArgs {
   float* mu_out;                                   // [rows, act_dim] policy means
   float* val_out;                                  // [rows] values
   uint16_t* x0b;                                   // row-tile kernel: x0 in its block layout (tile_kernel.h)
-#ifdef GMI_CHAIN_TIMING
-  long long* dbg;                                  // [n_chunks + 1] clock at the start of every chunk (workgroup 0, wave 0)
-#endif
 };
 
 constexpr int kSlotBytes = 16 * 1024;              // one chunk
@@ -637,9 +634,6 @@ __device__ __forceinline__ void chain_step(Ctx<S>& c, const ChainArgs& a) {
   // even segments read xa and write xb, odd ones the other way round
   uint4* xi = (seg & 1) ? c.xb : c.xa;
   uint4* xo = (seg & 1) ? c.xa : c.xb;
-#ifdef GMI_CHAIN_TIMING
-  if (blockIdx.x == 0 && blockIdx.y == 0 && c.tid == 0) a.dbg[C] = __builtin_readcyclecounter();
-#endif
 
   issue_chunk<S, C + 1 + S::DEPTH>(c);
   if constexpr (!S::FWD && seg == NL - 2 && ci.gi == 0 && ci.first) fetch_loss_inputs<S>(c, a);

@@ -4,11 +4,6 @@
 // (Section 3 of the paper, "DRL Agent"): observation conversion, every layer of both nets, and the Gaussian
 // sampling epilogue.
 #include "internal.h"
-#ifdef GMI_ROLLOUT_TIMING
-#define GMI_RT_MARK(i) do { if (blockIdx.x == 0 && tid == 0 && t == 3) a.dbg[i] = __builtin_readcyclecounter(); } while (0)
-#else
-#define GMI_RT_MARK(i) do { } while (0)
-#endif
 #include "rng.h"
 
 namespace {
@@ -305,9 +300,6 @@ struct RolloutArgs {
   int ahead_off;
   float* b_obs; float* b_act; float* b_logp; float* b_val; float* b_rew; uint8_t* b_done;
   float* last_value;
-#ifdef GMI_ROLLOUT_TIMING
-  long long* dbg;                   // [16] clock at the phase boundaries of one step (workgroup 0, thread 0)
-#endif
 };
 
 // Simulator step for the tile: items (group of EPT envs, block of 4 state elements).  mt points at the
@@ -841,8 +833,6 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
   for (int t = 0; t <= a.T; ++t) {
     // both nets, layer by layer; after the last step only the value net (bootstrap value)
     const bool run = half == 1 || t < a.T;
-    GMI_RT_MARK(0);
-    GMI_RT_MARK(1);
     if constexpr (kStationary) {
       if constexpr (R16)
         ws_net16<WS, 0>(wreg, s_w, N, s_nb, s_x0, stride_x0, s_a, s_b, stride_h, s_head, head_stride, run, wave4, tid & 63);
@@ -877,7 +867,6 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       }
       __syncthreads();
     }
-    GMI_RT_MARK(2);
     if (t == a.T) {
       if (tid < Rv && r0 + tid < a.n) a.last_value[r0 + tid] = s_val[tid];
       break;
@@ -891,7 +880,6 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       draw_items(a, s_noise, a.step0 + (uint32_t)t, Rv, r0, npr, nba, nbo, tid, NT);
       __syncthreads();
     }
-    GMI_RT_MARK(3);
     const uint32_t step = a.step0 + (uint32_t)t;
     const int64_t slot0 = (int64_t)t * a.ld_envs + r0;
     // action = mu + exp(log_std) * eps, log-prob partials per block of 4 action elements: one thread per element;
@@ -919,7 +907,6 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       lp += __shfl_down(term, 3, 64);
       if (i == 0) s_lp[blk] = lp;
     }
-    GMI_RT_MARK(8);
     // this step's observations to the buffer, by the waves without action items
     if (tid >= obs_tid0) {
       if (a.obs_vec) {          // rows of whole 16-byte pieces on both sides: a quarter of the stores
@@ -936,7 +923,6 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
         }
       }
     }
-    GMI_RT_MARK(9);
     if (dtid >= 0 && dtid < Rv) {
       const int e = r0 + dtid;
       int d = 0;
@@ -952,9 +938,7 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       }
       s_done[dtid] = d;
     }
-    GMI_RT_MARK(10);
     __syncthreads();
-    GMI_RT_MARK(4);
     if (tid < Rv && r0 + tid < a.n) {
       float lp = 0.f;
       for (int b = 0; b < nba; ++b) lp += s_lp[tid * nba + b];
@@ -976,9 +960,7 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       if ((Rv / 4) * nbo >= 192) sim_items<4>(a, Rv, r0, step, s_in, mt_glb_ptr, s_part, s_next, s_done, s_noise, npr, nba);
       else sim_items<1>(a, Rv, r0, step, s_in, mt_glb_ptr, s_part, s_next, s_done, s_noise, npr, nba);
     }
-    GMI_RT_MARK(5);
     __syncthreads();
-    GMI_RT_MARK(6);
     // the reward on the last wave (the state update below starts with the first threads)
     const int rt = tid - (NT - 64);
     if (rt >= 0 && rt < Rv && r0 + rt < a.n) {
@@ -1016,7 +998,6 @@ __global__ __launch_bounds__(512) void rollout_fused_kernel(RolloutArgs a) {
       }
     }
     __syncthreads();
-    GMI_RT_MARK(7);
   }
   // the loop ends right after the bootstrap value; s_in still holds the final state
   for (int idx = tid; idx < Rv * O; idx += NT) {
@@ -1154,13 +1135,6 @@ int launch_agent_fused(gmi_instance* g, gmi_model* m, const float* obs, int n, u
 
 }  // namespace gmi
 
-#ifdef GMI_ROLLOUT_TIMING
-static long long* g_rollout_dbg = nullptr;
-extern "C" int gmi_rollout_timing(long long* out, int n) {
-  if (!g_rollout_dbg) return -1;
-  return (int)hipMemcpy(out, g_rollout_dbg, (size_t)n * 8, hipMemcpyDeviceToHost);
-}
-#endif
 
 extern "C" int rollout_collect(gmi_t g, gmi_model_t m, gmi_env_t env, gmi_buffer_t b, float* obs, uint64_t seed,
                                uint32_t step0, uint32_t env_offset, float* last_value) {
@@ -1216,12 +1190,6 @@ extern "C" int rollout_collect(gmi_t g, gmi_model_t m, gmi_env_t env, gmi_buffer
   a.obs_vec = (L.obs_dim % 4 == 0 && (L.obs_dim + L.act_dim) % 4 == 0 && ((uintptr_t)bd.obs & 15) == 0) ? 1 : 0;
   a.b_obs = bd.obs; a.b_act = bd.act; a.b_logp = bd.logp; a.b_val = bd.val; a.b_rew = bd.rew; a.b_done = bd.done;
   a.last_value = last_value;
-#ifdef GMI_ROLLOUT_TIMING
-  static long long* dbg = nullptr;
-  if (!dbg) { GMI_HIP(hipMalloc(&dbg, 16 * 8)); GMI_HIP(hipMemset(dbg, 0, 16 * 8)); }
-  a.dbg = dbg;
-  g_rollout_dbg = dbg;
-#endif
   size_t lds = rollout_lds_bytes(m, R, mt_lds);
   // fewer 32-env tiles than compute units: 16 envs per workgroup use twice as many of them
   const int rows_per_wg = (R == 32 && (n + 31) / 32 < g->cu_count && n > 16) ? 16 : R;

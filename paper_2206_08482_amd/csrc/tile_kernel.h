@@ -104,9 +104,6 @@ struct Ctx {
   float l_act[16], l_lo, l_ad, l_rt;
   int tid, lane, wave, s, hh;
   int row0, net;                     // first row of the workgroup's tile
-#ifdef GMI_CHAIN_TIMING
-  long long ts[32];
-#endif
 };
 
 // First weight block of wave `wave` in segment SEG: its FTW tiles are consecutive tiles of one group of the stream.
@@ -412,9 +409,6 @@ __device__ __forceinline__ void run_segment(Ctx<S>& c, const ChainArgs& a) {
   if constexpr (SEG < S::nseg()) {
     using G = Seg<S, SEG>;
     const uint4* wseg = seg_weights<S, SEG>(c);
-#ifdef GMI_CHAIN_TIMING
-    c.ts[3 * SEG] = __builtin_readcyclecounter();
-#endif
     if constexpr (!G::bwd && !G::head) {
       // the accumulators start at the bias (register i of a lane = feature 8 (i / 4) + 4 hh + i % 4 of the tile)
       constexpr int boff = S::bias_off(G::layer);
@@ -444,14 +438,8 @@ __device__ __forceinline__ void run_segment(Ctx<S>& c, const ChainArgs& a) {
     k_steps<S, SEG, 0>(c, a, wseg);
     if constexpr (G::store_x)
       (store_x_array<S, SEG>(c, a) + block_word(blockIdx.x, G::NKS, G::NKS - 1, c.wave))[c.lane] = c.sx[(G::NKS - 1) & 1];
-#ifdef GMI_CHAIN_TIMING
-    c.ts[3 * SEG + 1] = __builtin_readcyclecounter();
-#endif
     issue_first_weights<S, SEG + 1>(c);
     __syncthreads();                       // every wave is done with the layer's input
-#ifdef GMI_CHAIN_TIMING
-    c.ts[3 * SEG + 2] = __builtin_readcyclecounter();
-#endif
     // this lane's loss inputs: cold loads, issued where a long stretch of arithmetic follows and no younger load is
     // waited for (the memory counter is in order)
     if constexpr (SEG == (S::NL >= 3 ? S::NL - 3 : 0)) fetch_loss_inputs<S>(c, a);
@@ -469,9 +457,6 @@ __device__ __forceinline__ void run_segment(Ctx<S>& c, const ChainArgs& a) {
       for (int ks = 0; ks < G::F / 16; ++ks)
         (arr + block_word(blockIdx.x, G::F / 16, ks, c.wave))[c.lane] = c.X[(ks * 4 + c.wave) * 64 + c.lane];      // arrays hold whole tiles
     }
-#ifdef GMI_CHAIN_TIMING
-    if constexpr (G::last) c.ts[3 * SEG + 3] = __builtin_readcyclecounter();
-#endif
     run_segment<S, SEG + 1>(c, a);
   }
 }
@@ -495,10 +480,6 @@ __global__ __launch_bounds__(kWaves * 64) void train_tile_kernel(ChainArgs a) {
   c.s_red = s_bias + S::bias_total();
   c.scr = reinterpret_cast<char*>(smem_raw) + 65536 + c.wave * kScrBytes;
   c.wnet = reinterpret_cast<const uint4*>(a.wstream[c.net]);
-#ifdef GMI_CHAIN_TIMING
-  c.ts[30] = __builtin_readcyclecounter();
-  const long long t_real0 = __builtin_amdgcn_s_memrealtime();
-#endif
 
   issue_first_weights<S, 0>(c);
   {
@@ -589,23 +570,7 @@ __global__ __launch_bounds__(kWaves * 64) void train_tile_kernel(ChainArgs a) {
     }
   }
   __syncthreads();
-#ifdef GMI_CHAIN_TIMING
-  c.ts[31] = __builtin_readcyclecounter();
-#endif
   run_segment<S, 0>(c, a);
-#ifdef GMI_CHAIN_TIMING
-  if (blockIdx.x == gridDim.x / 2 && blockIdx.y == 0 && c.tid == 64) {
-#pragma unroll
-    for (int i = 0; i < 32; ++i) a.dbg[i] = c.ts[i];
-  }
-  if (c.tid == 0) {      // wall clock (100 MHz) and cycle counter of every workgroup's start and end
-    const int wg = blockIdx.y * gridDim.x + blockIdx.x;
-    a.dbg[64 + 4 * wg] = t_real0;
-    a.dbg[64 + 4 * wg + 1] = __builtin_amdgcn_s_memrealtime();
-    a.dbg[64 + 4 * wg + 2] = c.ts[30];
-    a.dbg[64 + 4 * wg + 3] = __builtin_readcyclecounter();
-  }
-#endif
 }
 
 template <class S>
