@@ -71,6 +71,13 @@ class Channels:
         out["last_val"] = np.concatenate([s["last_val"][env0:env0 + take] for s in slabs])
         return out
 
+    def drop(self, k: int) -> None:
+        """Discards the k oldest waiting slabs unread (an agent that must not wait for the trainer makes room this
+        way: the asynchronous setting of Section 5.2).  They count as pushed, never as popped."""
+        if k < 0 or k > len(self.fifo):
+            raise ChannelError("not enough slabs")
+        self.fifo = self.fifo[k:]
+
     def filled(self) -> int:
         return len(self.fifo)
 

@@ -84,6 +84,77 @@ def test_push_pop_matches_oracle(g, mode, T, n, O, A):
     g.gmi_destroy(agent); g.gmi_destroy(trainer)
 
 
+@pytest.mark.parametrize("mode", ["multi", "uni"])
+def test_drop_makes_room_and_the_reused_slab_holds_the_new_round(g, mode):
+    """Two agents on streams of their own fill a ring of 3; the oldest slabs are discarded unread and their places
+    refilled by the OTHER agent without any host wait in between (the refill has to wait, on the device, for the
+    discarded push): what the trainer pops is what the oracle's queue holds, bit for bit."""
+    T, n, O, A, cap = 5, 200, 33, 6, 3
+    agents = [g.gmi_create(), g.gmi_create()]
+    trainer = g.gmi_create()
+    ch = g.gmi_channels_create(T, n, O, A, cap, g.CHANNELS_MULTI if mode == "multi" else g.CHANNELS_UNI)
+    ref = och.Channels(T, n, O, A, cap)
+    srcs = [_buffers(g, a, T, n, n, O, A) for a in agents]
+    lvs = [torch.zeros(n, device="cuda") for _ in agents]
+    dst_rb, dst = _buffers(g, trainer, T, cap * n, cap * n, O, A)
+    last_out = torch.zeros(cap * n, device="cuda")
+
+    def push(i, seed, wait):
+        b = syn.make_rollout_batch(T, n, O, A, seed=seed, done_prob=0.3)
+        g.gmi_sync(agents[i])                     # the agent's buffer is free again (its last push has run)
+        _upload(srcs[i][0], b, 0)
+        lvs[i].copy_(torch.tensor(b["last_val"], device="cuda"))
+        torch.cuda.synchronize()
+        g.gmi_channels_push(agents[i], ch, srcs[i][1], lvs[i])
+        if wait:
+            g.gmi_sync(agents[i])
+        ref.push(b, b["last_val"])
+
+    push(0, 1, True); push(1, 2, True); push(0, 3, False)        # ring full: slabs 0, 1, 2
+    with pytest.raises(g.GmiError):
+        g.gmi_channels_drop(ch, 4)                               # more than are waiting
+    g.gmi_channels_drop(ch, 2); ref.drop(2)                      # slabs 0 and 1 discarded unread
+    assert g.gmi_channels_count(ch) == (1, 3, 0)
+    push(1, 4, False); push(1, 5, False)                         # refills slabs 0 and 1 from the other stream
+    assert g.gmi_channels_count(ch) == (3, 5, 0)
+    want = ref.pop(3)
+    g.gmi_channels_pop(trainer, ch, 3, 0, n, dst, 0, last_out)
+    g.gmi_sync(trainer)
+    got = dst_rb.to_numpy()
+    for t in och.TYPES:
+        assert np.array_equal(got[t], want[t]), t
+    assert np.array_equal(last_out.cpu().numpy(), want["last_val"])
+    assert g.gmi_channels_count(ch) == (0, 5, 3)
+    g.gmi_channels_drop(ch, 0)
+    # a ring of one slab: agent 0's push is discarded while it may still be running, agent 1's push into the same
+    # slab is queued at once on another stream and must wait for it on the device
+    ch1 = g.gmi_channels_create(T, n, O, A, 1, g.CHANNELS_MULTI if mode == "multi" else g.CHANNELS_UNI)
+    b0 = syn.make_rollout_batch(T, n, O, A, seed=11, done_prob=0.3)
+    b1 = syn.make_rollout_batch(T, n, O, A, seed=12, done_prob=0.3)
+    for i, b in enumerate((b0, b1)):
+        g.gmi_sync(agents[i])
+        _upload(srcs[i][0], b, 0)
+        lvs[i].copy_(torch.tensor(b["last_val"], device="cuda"))
+    torch.cuda.synchronize()
+    g.gmi_channels_push(agents[0], ch1, srcs[0][1], lvs[0])
+    g.gmi_channels_drop(ch1, 1)
+    g.gmi_channels_push(agents[1], ch1, srcs[1][1], lvs[1])
+    g.gmi_channels_pop(trainer, ch1, 1, 0, n, dst, 0, last_out)
+    g.gmi_sync(trainer)
+    got = dst_rb.to_numpy()
+    for t in och.TYPES:
+        assert np.array_equal(got[t][:, :n], b1[t]), t
+    assert np.array_equal(last_out.cpu().numpy()[:n], b1["last_val"])
+    g.gmi_channels_destroy(ch1)
+    for (_, h) in srcs:
+        g.gmi_buffer_destroy(h)
+    g.gmi_buffer_destroy(dst)
+    g.gmi_channels_destroy(ch)
+    for a in agents:
+        g.gmi_destroy(a)
+    g.gmi_destroy(trainer)
+
+
 def test_hand_off_is_ordered_by_events_not_by_the_host(g):
     """The agent refills its buffer right after the push and the trainer pops at once, with no host
     synchronisation in between: the trainer must see the pushed values (masked instances on disjoint CUs)."""

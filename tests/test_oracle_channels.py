@@ -29,6 +29,22 @@ def test_fifo_order_and_stacking_is_concatenation():
     assert (ch.pushed, ch.popped) == (3, 3)
 
 
+def test_drop_discards_the_oldest_and_keeps_the_order_of_the_rest():
+    ch = och.Channels(4, 6, 5, 3, capacity=3)
+    slabs = [slab(4, 6, 5, 3, s) for s in range(5)]
+    for b, lv in slabs[:3]:
+        ch.push(b, lv)
+    ch.drop(1)                                   # slab 0 is gone, room for one more
+    ch.push(*slabs[3])
+    out = ch.pop(3)
+    for j, src in enumerate((1, 2, 3)):
+        assert np.array_equal(out["obs"][:, 6 * j:6 * (j + 1)], slabs[src][0]["obs"])
+    assert (ch.pushed, ch.popped, ch.filled()) == (4, 3, 0)
+    ch.drop(0)
+    with pytest.raises(och.ChannelError):
+        ch.drop(1)
+
+
 def test_slices_of_one_slab_tile_it_exactly():
     """Popping the same slab content as two halves (pushed twice) gives back the two column halves: slicing
     followed by stacking is the identity."""
