@@ -21,6 +21,8 @@ if ROOT not in sys.path:
 
 
 def measure(config="C5", updates=8):
+    import torch
+
     import paper_2206_08482_amd as g
     from paper_2206_08482_amd.async_schedule import AsyncPipeline
     from paper_2206_08482_amd.instances import cu_masks
@@ -61,7 +63,6 @@ def measure(config="C5", updates=8):
                 lags += [e[1] - s[2] for s in e[2]]      # updates made since the slab's parameters were current
         r.update({"layout": label, "on_full": on_full, "mean_staleness_updates": sum(lags) / max(len(lags), 1),
                   "max_staleness_updates": max(lags) if lags else 0})
-        import torch
         r["finite"] = bool(torch.isfinite(pipe.theta).all().item())
         rows.append(r)
         pipe.close()

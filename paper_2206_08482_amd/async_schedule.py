@@ -24,10 +24,10 @@ from typing import List, Optional, Sequence
 import numpy as np
 import torch
 
-from . import (CHANNELS_MULTI, ERR_UNSUPPORTED, GmiError, agent_act, agent_value, collect_experience, dtype_code,
+from . import (CHANNELS_MULTI, agent_act, agent_act_fp8, agent_value, collect_experience, dtype_code,
                env_desc, env_step, gae_compute, gmi_buffer_bind, gmi_buffer_destroy, gmi_channels_create,
                gmi_channels_destroy, gmi_channels_drop, gmi_channels_pop, gmi_channels_push, gmi_create, gmi_destroy,
-               gmi_env_bind, gmi_env_destroy, gmi_model_bind, gmi_model_destroy, gmi_model_refresh_shadow,
+               gmi_env_bind, gmi_env_destroy, gmi_fp8_bind, gmi_fp8_destroy, gmi_fp8_refresh, gmi_model_bind, gmi_model_destroy, gmi_model_refresh_shadow,
                gmi_model_shadow_bytes, gmi_sync, gmi_transfer, model_desc, ppo_hparams, ppo_update, rollout_collect)
 from .runner import RolloutBuffers
 
@@ -43,9 +43,14 @@ class AsyncPipeline:
                  done_threshold: int, seed: int, minibatch: int, slabs_per_update: Optional[int] = None,
                  capacity: Optional[int] = None, on_full: str = "block", mode: int = CHANNELS_MULTI,
                  agent_masks: Optional[Sequence[Optional[Sequence[int]]]] = None,
-                 trainer_mask: Optional[Sequence[int]] = None, reset_each_round: bool = False):
+                 trainer_mask: Optional[Sequence[int]] = None, reset_each_round: bool = False,
+                 agent_precision: str = "model"):
         """reset_each_round: every round starts from the agent's initial state (for timing runs: the synthetic
-        dynamics are not stable over hundreds of steps)."""
+        dynamics are not stable over hundreds of steps).  agent_precision: "model" = the agents serve in the
+        trainer's arithmetic; "fp8" = they serve through agent_act_fp8 (E4M3 weights re-quantised from every
+        parameter version they take; the trainer is unchanged)."""
+        if agent_precision not in ("model", "fp8"):
+            raise ValueError(f"unknown agent_precision {agent_precision!r}")
         if on_full not in ("block", "drop_oldest"):
             raise ValueError(f"unknown on_full {on_full!r}")
         dev = torch.device("cuda:0")
@@ -62,7 +67,8 @@ class AsyncPipeline:
         self.seed = seed
         code = dtype_code(dtype)
         self.f32 = code == 0
-        self.fused_rollout = not self.f32
+        self.fp8 = agent_precision == "fp8"
+        self.fused_rollout = not self.f32 and not self.fp8
         self.trainer = gmi_create(trainer_mask)
         self.theta = torch.tensor(theta, **f)
         self.adam_m = torch.zeros_like(self.theta)
@@ -71,14 +77,16 @@ class AsyncPipeline:
         t_desc = model_desc(obs_dim, act_dim, list(hidden), code, minibatch)
         a_desc = model_desc(obs_dim, act_dim, list(hidden), code, n_envs)
         nsh = gmi_model_shadow_bytes(t_desc)
-        self.pub_bytes = nsh if nsh else self.theta.numel() * 4
+        pub_shadow = bool(nsh) and not self.fp8     # fp8 agents quantise from the fp32 parameters themselves
+        self.pub_bytes = nsh if pub_shadow else self.theta.numel() * 4
 
         def weights():      # one copy of what an agent reads: the bf16 shadow, or the fp32 parameters
-            if nsh:
+            if pub_shadow:
                 return torch.zeros(max(nsh, 256), dtype=torch.uint8, device=dev)
             return torch.tensor(theta, **f)
 
-        self.t_shadow = weights() if nsh else None
+        self.t_shadow = torch.zeros(max(nsh, 256), dtype=torch.uint8, device=dev) if nsh else None
+        self.pub_shadow = pub_shadow
         self.pub = [weights(), weights()]       # version v is published in slot v % 2
         self.channels = gmi_channels_create(horizon, n_envs, obs_dim, act_dim, self.capacity, mode)
         self.batch = RolloutBuffers(horizon, self.Ntot, obs_dim, act_dim, dev)
@@ -97,7 +105,10 @@ class AsyncPipeline:
             ag.gmi = gmi_create(agent_masks[i] if agent_masks else None)
             ag.weights = weights()
             torch.cuda.synchronize()
-            if nsh:
+            ag.model = ag.fp8 = None
+            if self.fp8:
+                ag.fp8 = gmi_fp8_bind(ag.gmi, a_desc)
+            elif nsh:
                 ag.model = gmi_model_bind(ag.gmi, a_desc, self.theta, ag.weights, None, None)
             else:
                 ag.model = gmi_model_bind(ag.gmi, a_desc, ag.weights, None, None, None)
@@ -139,7 +150,7 @@ class AsyncPipeline:
         with self.params:       # agents that chose this slot two versions ago have finished copying from it
             while self.readers[slot]:
                 self.params.wait()
-        src = self.t_shadow if self.t_shadow is not None else self.theta
+        src = self.t_shadow if self.pub_shadow else self.theta
         gmi_transfer(self.trainer, self.trainer, src, self.pub[slot], self.pub_bytes)
 
     def _take_newest(self, ag) -> int:
@@ -148,6 +159,8 @@ class AsyncPipeline:
             self.readers[v % 2] += 1
         try:
             gmi_transfer(ag.gmi, ag.gmi, self.pub[v % 2], ag.weights, self.pub_bytes)
+            if ag.fp8 is not None:
+                gmi_fp8_refresh(ag.gmi, ag.fp8, ag.weights)
             gmi_sync(ag.gmi)
         finally:
             with self.params:
@@ -166,11 +179,17 @@ class AsyncPipeline:
         for t in range(T):
             step = r * T + t
             obs, nxt = ag.obs[ag.cur], ag.obs[1 - ag.cur]
-            agent_act(ag.gmi, ag.model, obs, self.N, ag.seed, step, 0, ag.act, ag.logp, ag.value)
+            if ag.fp8 is not None:
+                agent_act_fp8(ag.gmi, ag.fp8, obs, self.N, ag.seed, step, 0, ag.act, ag.logp, ag.value)
+            else:
+                agent_act(ag.gmi, ag.model, obs, self.N, ag.seed, step, 0, ag.act, ag.logp, ag.value)
             env_step(ag.gmi, ag.env, obs, ag.act, step, nxt, ag.reward, ag.done)
             collect_experience(ag.gmi, ag.buffer, t, obs, ag.act, ag.logp, ag.value, ag.reward, ag.done)
             ag.cur = 1 - ag.cur
-        agent_value(ag.gmi, ag.model, ag.obs[ag.cur], self.N, ag.last)
+        if ag.fp8 is not None:      # the bootstrap value: the value output of one more decision (its action is unused)
+            agent_act_fp8(ag.gmi, ag.fp8, ag.obs[ag.cur], self.N, ag.seed, (r + 1) * T, 0, ag.act, ag.logp, ag.last)
+        else:
+            agent_value(ag.gmi, ag.model, ag.obs[ag.cur], self.N, ag.last)
 
     def _agent_loop(self, ag, max_rounds: Optional[int]) -> None:
         try:
@@ -277,7 +296,10 @@ class AsyncPipeline:
         for ag in self.agents:
             gmi_buffer_destroy(ag.buffer)
             gmi_env_destroy(ag.env)
-            gmi_model_destroy(ag.model)
+            if ag.model is not None:
+                gmi_model_destroy(ag.model)
+            if ag.fp8 is not None:
+                gmi_fp8_destroy(ag.fp8)
             gmi_destroy(ag.gmi)
         gmi_buffer_destroy(self.t_buffer)
         gmi_channels_destroy(self.channels)

@@ -4,6 +4,7 @@ the parameter version the trace says it was collected with, every update on the 
 import numpy as np
 import pytest
 
+from oracle import fp8model as f8
 from oracle import ppo as oppo
 from workloads import synthetic as syn
 from gpu_util import rel_l2
@@ -11,7 +12,8 @@ from gpu_util import rel_l2
 pytestmark = pytest.mark.gpu
 
 
-def _make(cfg, dtype, n_agents, n_envs, horizon, minibatch, slabs, capacity, on_full, masked=False):
+def _make(cfg, dtype, n_agents, n_envs, horizon, minibatch, slabs, capacity, on_full, masked=False,
+          agent_precision="model"):
     import paper_2206_08482_amd as g
     from paper_2206_08482_amd.async_schedule import AsyncPipeline
     from paper_2206_08482_amd.instances import cu_masks
@@ -29,13 +31,26 @@ def _make(cfg, dtype, n_agents, n_envs, horizon, minibatch, slabs, capacity, on_
                          hidden=cfg.hidden, horizon=horizon, dtype=dtype, theta=theta, a_mat=a_mat, b_mat=b_mat,
                          state0=states, noise_std=cfg.noise_std, reward_scale=cfg.reward_scale,
                          done_period=cfg.done_period, done_threshold=thr, seed=cfg.seed, minibatch=minibatch,
-                         slabs_per_update=slabs, capacity=capacity, on_full=on_full, agent_masks=agent_masks)
+                         slabs_per_update=slabs, capacity=capacity, on_full=on_full, agent_masks=agent_masks,
+                         agent_precision=agent_precision)
     envs = [oppo.EnvSpec(a_mat, b_mat, cfg.noise_std, cfg.reward_scale, cfg.done_period, thr, cfg.seed + i)
             for i in range(n_agents)]
     return pipe, theta, envs, states
 
 
-def _replay(trace, cfg, theta, envs, states, n_envs, horizon, hp):
+def _rollout_fp8(theta, shape, env, state, eps, buf, seed, r):
+    """oracle.ppo.rollout with the agent's decisions (and the bootstrap value) taken by the fp8 model."""
+    T = buf["obs"].shape[0]
+    for t in range(T):
+        step = r * T + t
+        act, logp, val, _ = f8.agent_act(theta, shape, state, seed, step)
+        nxt, rew, done, eps = oppo.env_step(env, state, act, eps, step, np.float32, 0)
+        oppo.collect_experience(buf, t, state, act, logp, val, rew, done, 0)
+        state = nxt
+    return state, eps, f8.agent_forward(theta, shape, state)[1]
+
+
+def _replay(trace, cfg, theta, envs, states, n_envs, horizon, hp, fp8=False):
     """The oracle walks the trace; returns the parameter versions and the number of rounds it collected."""
     shape = oppo.ModelShape(cfg.obs_dim, cfg.act_dim, tuple(cfg.hidden))
     th = [theta]
@@ -50,7 +65,10 @@ def _replay(trace, cfg, theta, envs, states, n_envs, horizon, hp):
             assert r == nxt[i], "an agent's rounds enter the ring in order"
             assert ver < len(th), "a round cannot use parameters that did not exist yet"
             buf = oppo.new_buffer(horizon, n_envs, cfg.obs_dim, cfg.act_dim)
-            st[i], ep[i], last = oppo.rollout(th[ver], shape, envs[i], st[i], ep[i], buf, envs[i].seed, r)
+            if fp8:
+                st[i], ep[i], last = _rollout_fp8(th[ver], shape, envs[i], st[i], ep[i], buf, envs[i].seed, r)
+            else:
+                st[i], ep[i], last = oppo.rollout(th[ver], shape, envs[i], st[i], ep[i], buf, envs[i].seed, r)
             slabs[(i, r)] = (buf, last)
             nxt[i] += 1
         elif ev[0] == "drop":
@@ -132,4 +150,35 @@ def test_async_bf16_bounded_rounds_replay():
     got = pipe.theta.cpu().numpy()
     assert rel_l2(got, th[-1]) <= 2e-2
     assert rel_l2(got - theta, th[-1] - theta) <= 0.25, rel_l2(got - theta, th[-1] - theta)
+    pipe.close()
+
+
+def test_async_fp8_agents_bf16_trainer_replay():
+    """Agents that serve in fp8 (weights re-quantised from every parameter version they take) feeding a bf16
+    trainer: the trace replayed with the oracle's fp8 agent and fp32 trainer, bounds of the bf16 trainer."""
+    cfg = syn.get_config("C3")
+    n_agents, n_envs, horizon, slabs = 2, 128, 4, 2
+    minibatch = 512
+    pipe, theta, envs, states = _make(cfg, "bf16", n_agents, n_envs, horizon, minibatch, slabs, 4, "block",
+                                      agent_precision="fp8")
+    args = dict(gamma=cfg.gamma, lam=cfg.lam, epochs=2, minibatch=minibatch, clip=cfg.clip, c_v=cfg.c_v, c_e=cfg.c_e,
+                lr=2e-3)
+    rates = pipe.run(3, max_rounds=3, **args)
+    assert rates["updates"] == 3 and rates["rounds_collected"] == 6
+    hp = oppo.PPOHyper(clip=cfg.clip, c_v=cfg.c_v, c_e=cfg.c_e, lr=2e-3, epochs=2, minibatch=minibatch)
+    th, _ = _replay(list(pipe.trace), cfg, theta, envs, states, n_envs, horizon, hp, fp8=True)
+    got = pipe.theta.cpu().numpy()
+    assert rel_l2(got, th[-1]) <= 2e-2
+    assert rel_l2(got - theta, th[-1] - theta) <= 0.25, rel_l2(got - theta, th[-1] - theta)
+    # the agents really served in fp8: the last batch's values follow the fp8 oracle, not the exact network
+    shape = oppo.ModelShape(cfg.obs_dim, cfg.act_dim, tuple(cfg.hidden))
+    batch = pipe.batch.to_numpy()
+    last_update = [e for e in pipe.trace if e[0] == "update"][-1]
+    ver = last_update[2][0][2]
+    obs0 = batch["obs"][0, :n_envs]
+    v8 = f8.agent_forward(th[ver], shape, obs0)[1]
+    vx = oppo.value_only(th[ver], shape, obs0)
+    # (the device's parameters of that version carry the bf16 trainer's band, hence 4e-2; E4M3 itself is ~8e-2 away)
+    assert rel_l2(batch["val"][0, :n_envs], v8) <= 4e-2, rel_l2(batch["val"][0, :n_envs], v8)
+    assert rel_l2(batch["val"][0, :n_envs], vx) > 5e-2, rel_l2(batch["val"][0, :n_envs], vx)
     pipe.close()
