@@ -12,7 +12,7 @@ BUILD_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libgmidrl.so")
 # the slowest compiles first (the forward-only chained kernels of the widest shapes take minutes), so that they
 # overlap all the others
-SOURCES = ["chain_f1.hip", "chain_f0.hip", "fused.hip", "mlp.hip", "chain_p1.hip", "chain_p3.hip", "chain_p0.hip", "chain_p2.hip", "tile_p0.hip", "tile_p1.hip",
+SOURCES = ["fused.hip", "mlp.hip", "chain_p1.hip", "chain_p3.hip", "chain_p0.hip", "chain_p2.hip", "tile_p0.hip", "tile_p1.hip", "tile_f0.hip", "tile_f1.hip",
            "core.hip", "env.hip", "experience.hip", "model.hip", "update.hip", "peaks.hip", "select.hip", "channels.hip", "fp8.hip", "chain.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Wno-unused-value", "-Wno-unused-result", "-fhip-fp32-correctly-rounded-divide-sqrt",

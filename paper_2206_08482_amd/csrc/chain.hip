@@ -77,9 +77,9 @@ ChainDims dims_of(const ModelLayout& L, int gmax = 4) {
 typedef int (*part_fn)(gmi_instance*, const ModelLayout&, const ChainArgs&, int, int*, double, double);
 const part_fn kParts[gmi::kChainParts] = {gmi::launch_chain_part0, gmi::launch_chain_part1, gmi::launch_chain_part2,
                                           gmi::launch_chain_part3};
-const part_fn kFwdParts[gmi::kChainFwdParts] = {gmi::launch_chain_fwd_part0, gmi::launch_chain_fwd_part1};
 // The row-tile kernel's shapes (tile_kernel.h) come first: a model shape compiled for both takes that one.
 const part_fn kTileFns[gmi::kTileParts] = {gmi::launch_tile_part0, gmi::launch_tile_part1};
+const part_fn kTileFwdFns[gmi::kTileFwdParts] = {gmi::launch_tile_fwd_part0, gmi::launch_tile_fwd_part1};
 
 // What the trainer kernel compiled for this model's shape answers to the probe: its largest group, plus 256 if it
 // can gather its rows from the bf16 copy of all observations; 0 if there is none.
@@ -238,17 +238,16 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_p
   return GMI_OK;
 }
 
-// Inference through the forward-only chained kernel (agent_act / agent_value of the models too large for the fused
+// Inference through the forward-only row-tile kernel (agent_act / agent_value of the models too large for the fused
 // agent kernel): the same stream, the same products in the same order as the trainer's forward pass.
 int launch_forward_chain(gmi_instance* g, gmi_model* m, const float* obs, int n_rows, float* mu, float* val) {
   const ModelLayout& L = m->L;
   if (L.dtype != GMI_DTYPE_BF16 || L.sh_chain_bytes == 0 || L.act_dim > 32) return GMI_ERR_UNSUPPORTED;
   if (n_rows < 1 || n_rows > m->max_rows) return GMI_ERR_UNSUPPORTED;
   ChainArgs a = {};
-  int gm_fwd = 0, rc = GMI_ERR_UNSUPPORTED;
-  for (int p = 0; p < kChainFwdParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = kFwdParts[p](nullptr, L, a, 0, &gm_fwd, 0.0, 0.0);
-  if (rc != GMI_OK) return rc;
-  if (gm_fwd != compiled_gmax(L)) return GMI_ERR_UNSUPPORTED;      // the stream is laid out for the trainer kernel's groups
+  int probe = 0, rc = GMI_ERR_UNSUPPORTED;
+  for (int p = 0; p < kTileFwdParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = kTileFwdFns[p](nullptr, L, a, 0, &probe, 0.0, 0.0);
+  if (rc != GMI_OK) return rc;      // no forward-only kernel compiled for this shape
   for (int net = 0; net < 2; ++net) {
     a.wstream[net] = m->shadow + L.sh_chain[net];
     for (int l = 0; l < L.n_layers; ++l) a.bias[net][l] = reinterpret_cast<const float*>(m->shadow + L.net[net][l].sh_b);
@@ -276,7 +275,7 @@ int launch_forward_chain(gmi_instance* g, gmi_model* m, const float* obs, int n_
   bytes += (a.x0_ready ? 2.0 : 4.0) * n_rows * L.obs_dim * (2 - a.net0) + 4.0 * n_rows * ((mu ? L.act_dim : 0) + 1);
   int tiles = 0;
   rc = GMI_ERR_UNSUPPORTED;
-  for (int p = 0; p < kChainFwdParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = kFwdParts[p](g, L, a, n_rows, &tiles, flops, bytes);
+  for (int p = 0; p < kTileFwdParts && rc == GMI_ERR_UNSUPPORTED; ++p) rc = kTileFwdFns[p](g, L, a, n_rows, &tiles, flops, bytes);
   return rc;
 }
 

@@ -98,12 +98,6 @@ __host__ __device__ constexpr int cd_nchunks(const ChainDims& D) {
   for (int s = 0; s < cd_nseg(D); ++s) n += cd_seg_chunks(D, s);
   return n;
 }
-// chunks of the forward segments alone (they come first)
-__host__ __device__ constexpr int cd_fwd_chunks(const ChainDims& D) {
-  int n = 0;
-  for (int s = 0; s < D.nl; ++s) n += cd_seg_chunks(D, s);
-  return n;
-}
 __host__ __device__ constexpr int cd_nblocks(const ChainDims& D) {
   int n = 0;
   for (int s = 0; s < cd_nseg(D); ++s) n += cd_seg_blocks(D, s);
@@ -194,7 +188,7 @@ struct ChainArgs {
   int rows, act_dim;
   float clip, c_v;
   float* stat_part;                                // [tiles][kStatStride + act_dim]
-  // inference (shapes with FWD): workgroup row y works on net net0 + y; results of the heads
+  // inference (the forward-only row-tile kernel, tile_kernel.h): workgroup row y works on net net0 + y; results of the heads
   int net0;
   float* mu_out;                                   // [rows, act_dim] policy means
   float* val_out;                                  // [rows] values
@@ -214,20 +208,18 @@ template <int NW_, int DEPTH_, int GMAX_, int DEFER_, int HFETCH_, int MODE_, in
 struct ChainShape {
   static constexpr int NW = NW_, NT = NW_ * 64, DEPTH = DEPTH_, GMAX = GMAX_;
   static constexpr bool DEFER = DEFER_ != 0;
-  static constexpr bool FWD = MODE_ == 1;     // inference: the forward segments only, nothing stored for the weight gradients,
-                                              // the head's results written out instead of the loss
   static constexpr bool X16 = MODE_ == 2;     // trainer that can also gather its rows from the bf16 copy of all observations
                                               // (x0_ready == 2; only the shapes of models with unaligned observation rows
                                               // carry that code: its mere presence cost the 400-wide shapes 8 %)
-  static_assert(MODE_ >= 0 && MODE_ <= 2, "MODE: 0 trainer, 1 forward-only, 2 trainer with the bf16-copy gather");
+  static_assert(MODE_ == 0 || MODE_ == 2, "MODE: 0 trainer, 2 trainer with the bf16-copy gather");
   static constexpr int HFETCH = HFETCH_;      // without DEFER: a group fetches its stored activations this many chunks before its end
   static_assert(GMAX_ == 4 || GMAX_ == 2, "groups of at most 4 or 2 tiles");
   static constexpr int NL = (int)sizeof...(DIMS) - 1;
   static constexpr int LPT = (16 * 64 + NT - 1) / NT;      // 16-byte pieces of a chunk per thread
   static constexpr ChainDims dims() { return ChainDims{NL, GMAX_, {DIMS...}}; }
   static constexpr int maxks() { return cd_maxdim(dims()) / 16; }
-  static constexpr int nch() { return FWD ? cd_fwd_chunks(dims()) : cd_nchunks(dims()); }
-  static constexpr int items(int gs) { return FWD ? 4 * gs : cd_items(gs); }      // no store steps in inference
+  static constexpr int nch() { return cd_nchunks(dims()); }
+  static constexpr int items(int gs) { return cd_items(gs); }
   static constexpr int bias_total() {
     int n = 0;
     for (int l = 0; l < NL; ++l) n += dims().d[l + 1];
@@ -452,24 +444,6 @@ __device__ __forceinline__ void loss_epilogue(Ctx<S>& c, const ChainArgs& a, con
   }
 }
 
-// Inference: the heads' results (accumulator + bias) of the wave's 32 samples; lane (s, hh), register i =
-// feature 8 (i / 4) + 4 hh + i % 4.
-template <class S>
-__device__ __forceinline__ void head_outputs(Ctx<S>& c, const ChainArgs& a, const floatx16& acc) {
-  constexpr int HB = S::bias_off(S::NL - 1);
-  const int row = c.row0 + c.s;
-  if (row >= a.rows) return;
-  if (c.net == 0) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int f = 8 * (i >> 2) + 4 * c.hh + (i & 3);
-      if (f < a.act_dim) a.mu_out[(int64_t)row * a.act_dim + f] = acc[i] + c.s_bias[HB + f];
-    }
-  } else if (c.hh == 0) {
-    a.val_out[row] = acc[0] + c.s_bias[HB];
-  }
-}
-
 template <class S, int C, int K, int RING>
 __device__ __forceinline__ void fetch_kstep(Ctx<S>& c) {
   if constexpr (C < S::nch()) {
@@ -532,8 +506,7 @@ __device__ __forceinline__ void item_compute(Ctx<S>& c, const ChainArgs& a) {
       v2 = elu_f(v2 + __uint_as_float(pre.z)); v3 = elu_f(v3 + __uint_as_float(pre.w));
     }
     const uint32_t w0 = pack_bf16(v0, v1), w1 = pack_bf16(v2, v3);
-    if constexpr (!S::FWD)
-      *reinterpret_cast<uint2*>(c.scr + c.s * kScrStride + (32 * t + 8 * q + 4 * c.hh) * 2) = make_uint2(w0, w1);
+    *reinterpret_cast<uint2*>(c.scr + c.s * kScrStride + (32 * t + 8 * q + 4 * c.hh) * 2) = make_uint2(w0, w1);
     uint4& x = xo[2 * (pi.tile0 + t) + q / 2];
     if constexpr (q % 2 == 0) { x.x = w0; x.y = w1; } else { x.z = w0; x.w = w1; }
   } else {
@@ -636,7 +609,7 @@ __device__ __forceinline__ void chain_step(Ctx<S>& c, const ChainArgs& a) {
   uint4* xo = (seg & 1) ? c.xa : c.xb;
 
   issue_chunk<S, C + 1 + S::DEPTH>(c);
-  if constexpr (!S::FWD && seg == NL - 2 && ci.gi == 0 && ci.first) fetch_loss_inputs<S>(c, a);
+  if constexpr (seg == NL - 2 && ci.gi == 0 && ci.first) fetch_loss_inputs<S>(c, a);
 
   // stored activations of this group's features, for ELU': fetched HFETCH chunks before the group's end
   if constexpr (!S::DEFER && bwd && (ci.last_in == (S::HFETCH < ci.group_chunks ? S::HFETCH : ci.group_chunks) - 1))
@@ -653,12 +626,8 @@ __device__ __forceinline__ void chain_step(Ctx<S>& c, const ChainArgs& a) {
   if constexpr (ci.last) {
     if constexpr (!bwd && layer == NL - 1) {
       static_assert(GS == 1, "the head is one 32-wide tile");
-      if constexpr (S::FWD) {
-        head_outputs<S>(c, a, c.acc[ci.gord & 1][0]);
-      } else {
-        fetch_next_h<S, C>(c, a);
-        loss_epilogue<S>(c, a, c.acc[ci.gord & 1][0], xo);
-      }
+      fetch_next_h<S, C>(c, a);
+      loss_epilogue<S>(c, a, c.acc[ci.gord & 1][0], xo);
     } else {
       // the stored activations go to the transposition buffer now (the previous group's items are done with it),
       // the rest of the epilogue either now or inside the next group's k steps
@@ -688,7 +657,7 @@ __global__ __launch_bounds__(S::NW * 64) void train_chain_kernel(ChainArgs a) {
   c.wave = __builtin_amdgcn_readfirstlane(c.tid >> 6);
   c.s = c.lane & 31;
   c.hh = c.lane >> 5;
-  c.net = blockIdx.y + (S::FWD ? a.net0 : 0);
+  c.net = blockIdx.y;
   c.row0 = (blockIdx.x * S::NW + c.wave) * 32;
   c.lds = reinterpret_cast<char*>(smem_raw);
   c.scr = c.lds + kSlots * kSlotBytes + c.wave * kScrBytes;
@@ -728,7 +697,7 @@ __global__ __launch_bounds__(S::NW * 64) void train_chain_kernel(ChainArgs a) {
     // in x0 for the weight-gradient kernel.  All loads unconditional (clamped addresses, selected values).
     const int row = c.row0 + c.s;
     const int rc = row < a.rows ? row : a.rows - 1;
-    const int sm = a.idx ? a.idx[rc] : rc;               // no index: rows in order (inference)
+    const int sm = a.idx ? a.idx[rc] : rc;               // no index: rows in order
     c.slot = (int64_t)(sm / a.n_envs) * a.ld_envs + (sm % a.n_envs);
     const float* orow = a.b_obs + c.slot * a.obs_dim;
     const int O = a.obs_dim;
@@ -759,7 +728,7 @@ __global__ __launch_bounds__(S::NW * 64) void train_chain_kernel(ChainArgs a) {
           v[4 * q + 2] = f < O ? t.z : 0.f; v[4 * q + 3] = f < O ? t.w : 0.f;
         }
         c.xa[ks] = make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
-        if (!S::FWD && c.net == 0) *reinterpret_cast<uint4*>(xw + 16 * ks) = c.xa[ks];      // arrays hold whole tiles
+        if (c.net == 0) *reinterpret_cast<uint4*>(xw + 16 * ks) = c.xa[ks];      // arrays hold whole tiles
       }
     }
   }
@@ -787,14 +756,14 @@ int launch_shape(gmi_instance* g, const ChainArgs& a, int rows, int* tiles_out, 
   const size_t lds = S::lds_bytes();
   const int tiles = (rows + 32 * S::NW - 1) / (32 * S::NW);
   *tiles_out = tiles;
-  if (!S::FWD && tiles > gmi::kLossBlocksMax) return GMI_ERR_UNSUPPORTED;      // one statistics row per tile
+  if (tiles > gmi::kLossBlocksMax) return GMI_ERR_UNSUPPORTED;      // one statistics row per tile
   if (!attr) {
     GMI_HIP(hipFuncSetAttribute((const void*)train_chain_kernel<S>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr = true;
   }
-  gmi::ProfScope ps(g, S::FWD ? gmi::kClsFusedAgent : gmi::kClsChainTrain);
+  gmi::ProfScope ps(g, gmi::kClsChainTrain);
   ps.work(flops, bytes);
-  ps.launch(train_chain_kernel<S>, dim3(tiles, S::FWD ? 2 - a.net0 : 2), dim3(S::NT), lds, a);
+  ps.launch(train_chain_kernel<S>, dim3(tiles, 2), dim3(S::NT), lds, a);
   GMI_LAUNCH_CHECK();
   return GMI_OK;
 }
@@ -812,20 +781,6 @@ constexpr int kChainParts = 4;
                            int* tiles_out, double flops, double bytes)
 GMI_CHAIN_PART_DECL(0); GMI_CHAIN_PART_DECL(1); GMI_CHAIN_PART_DECL(2); GMI_CHAIN_PART_DECL(3);
 // Defines part k for shape S.
-// Forward-only (inference) kernels exist for the shapes too large for the fused agent / rollout kernels.
-constexpr int kChainFwdParts = 2;
-#define GMI_CHAIN_FWD_DECL(k)                                                                              \
-  int launch_chain_fwd_part##k(gmi_instance* g, const ModelLayout& L, const gmi_chain::ChainArgs& a, int rows, \
-                               int* tiles_out, double flops, double bytes)
-GMI_CHAIN_FWD_DECL(0); GMI_CHAIN_FWD_DECL(1);
-#define GMI_CHAIN_FWD_DEFINE(k, ...)                                                              \
-  GMI_CHAIN_FWD_DECL(k) {                                                                         \
-    using S = gmi_chain::ChainShape<__VA_ARGS__>;                                                 \
-    static_assert(S::FWD, "a forward-only shape");                                                \
-    if (!gmi_chain::shape_matches<S>(L)) return GMI_ERR_UNSUPPORTED;                              \
-    if (rows == 0) { *tiles_out = S::GMAX; return GMI_OK; }                                       \
-    return gmi_chain::launch_shape<S>(g, a, rows, tiles_out, flops, bytes);                       \
-  }
 #define GMI_CHAIN_PART_DEFINE(k, ...)                                                             \
   GMI_CHAIN_PART_DECL(k) {                                                                        \
     using S = gmi_chain::ChainShape<__VA_ARGS__>;                                                 \

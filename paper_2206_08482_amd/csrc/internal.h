@@ -63,7 +63,7 @@ namespace gmi {
 //           4 linear_bf16_kernel<1,4,1,2,*> (128x64)
 //   role    0 forward hidden layer (bias + ELU)   1 forward head   2 input gradient (ELU')
 // (kClsGae covers gae_kernel and normalize_kernel, kClsLinearF32 the three fp32 epilogues, kClsFusedAgent the
-// one-launch agent forward of a model: agent_fused_kernel, or the forward-only chained kernel for the shapes that
+// one-launch agent forward of a model: agent_fused_kernel, or the forward-only row-tile kernel for the shapes that
 // have one -- a model uses one or the other.)
 enum KernelClass {
   kClsGather = 0, kClsWgrad, kClsLoss, kClsAdam, kClsShadowTranspose, kClsEnvStep, kClsSample,
@@ -298,7 +298,7 @@ struct ChainEmit {
   ChainEmitLayer l[kMaxWgradProblems];
 };
 void fill_chain_emit(const ModelLayout& L, ChainEmit* ce);
-// Forward pass of n_rows observation rows through the forward-only chained kernel: policy means into mu (NULL: value
+// Forward pass of n_rows observation rows through the forward-only row-tile kernel: policy means into mu (NULL: value
 // net only) and values into val.  GMI_ERR_UNSUPPORTED (no message) if no such kernel is compiled for the shape.
 int launch_forward_chain(gmi_instance* g, gmi_model* m, const float* obs, int n_rows, float* mu, float* val);
 // The action decision from given means: act = mu + exp(log_std) * eps, logp, optional copy of mu (model.hip).

@@ -18,6 +18,9 @@
 // A layer is: k loop (all accumulators of the layer live at once) - barrier - epilogue (bias + ELU, or x ELU' of
 // the stored activation; conversion; the results into LDS in place of the layer's input; from there they go to memory
 // for the weight-gradient kernel) - barrier.  The next layer's first weight blocks are fetched before the epilogue.
+//
+// TileShapeFwd is the same walk cut after the heads (agent_act / agent_value of these models: Section 3, "DRL Agent"):
+// nothing is stored for the weight gradients and the heads' results go out as policy means and values.
 #pragma once
 #include "chain_kernel.h"
 
@@ -31,6 +34,7 @@ constexpr int kHPre = 3;          // tiles whose stored activations are fetched 
 
 template <int... DIMS>
 struct TileShape {
+  static constexpr bool fwd = false;      // TileShapeFwd: the forward pass alone (inference)
   static constexpr int NL = (int)sizeof...(DIMS) - 1;
   static constexpr ChainDims dims() { return ChainDims{NL, 4, {DIMS...}}; }
   static constexpr int nseg() { return cd_nseg(dims()); }
@@ -62,13 +66,23 @@ struct TileShape {
   }
 };
 
+// The same shape for inference: the walk ends after the heads, nothing is stored for the weight gradients, and the
+// heads' results go out as policy means and values (the products and their order are the trainer's forward pass).
+template <int... DIMS>
+struct TileShapeFwd : TileShape<DIMS...> {
+  static constexpr bool fwd = true;
+};
+// Segments the kernel runs for shape S.
+template <class S>
+constexpr int n_run() { return S::fwd ? S::NL : S::nseg(); }
+
 template <class S, int SEG>
 struct Seg {
   static constexpr ChainDims D = S::dims();
   static constexpr int K = cd_K(D, SEG), F = cd_F(D, SEG), NKS = K / 16, NFT = F / 32;
   static constexpr bool head = SEG == S::NL - 1;
   static constexpr bool bwd = SEG >= S::NL;
-  static constexpr bool last = SEG == S::nseg() - 1;
+  static constexpr bool last = !S::fwd && SEG == S::nseg() - 1;
   static constexpr int layer = cd_layer(D, SEG);
   static constexpr int FTW = head ? 1 : NFT / kWaves;     // feature tiles per wave
   static constexpr int RT = head ? 1 : 4;                 // row tiles per wave (the head: one row tile per wave)
@@ -83,7 +97,7 @@ struct Seg {
   // fetches, and the memory counter is in order: the loop would wait for every one of them.)  Not for the first
   // segment (the gather stores its rows) nor the first input-gradient segment (the loss epilogue stores the head's).
   static constexpr int HK = NKS > 6 ? NKS - 6 : 0;        // k step at which an input-gradient segment starts to fetch ELU' inputs
-  static constexpr bool store_x = (SEG >= 1 && SEG <= S::NL - 1) || SEG > S::NL;
+  static constexpr bool store_x = !S::fwd && ((SEG >= 1 && SEG <= S::NL - 1) || SEG > S::NL);
   static_assert(head || NFT % kWaves == 0, "feature tiles divide over the waves");
   static_assert(!head || NFT == 1, "the head is one 32-wide tile");
 };
@@ -125,7 +139,7 @@ __device__ __forceinline__ void issue_weights(Ctx<S>& c, const uint4* wseg) {
 // The first DEP k steps of segment SEG (issued before the previous segment's epilogue).
 template <class S, int SEG, int KS = 0>
 __device__ __forceinline__ void issue_first_weights(Ctx<S>& c) {
-  if constexpr (SEG < S::nseg()) {
+  if constexpr (SEG < n_run<S>()) {
     if constexpr (KS < Seg<S, SEG>::DEP) {
       issue_weights<S, SEG, KS>(c, seg_weights<S, SEG>(c));
       issue_first_weights<S, SEG, KS + 1>(c);
@@ -404,9 +418,27 @@ __device__ __forceinline__ void loss_epilogue(Ctx<S>& c, const ChainArgs& a, con
   }
 }
 
+// Inference: the head's results of row tile `wave` (lane = row, register i = feature 8 (i / 4) + 4 hh + i % 4) plus
+// the head's bias go out as policy means [rows, act_dim] or as values [rows].
+template <class S>
+__device__ __forceinline__ void head_outputs(Ctx<S>& c, const ChainArgs& a, const floatx16& acc) {
+  constexpr int HB = S::bias_off(S::NL - 1);
+  const int row = c.row0 + 32 * c.wave + c.s;
+  if (row >= a.rows) return;
+  if (c.net == 0) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int f = 8 * (i / 4) + 4 * c.hh + (i % 4);
+      if (f < a.act_dim) a.mu_out[(int64_t)row * a.act_dim + f] = acc[i] + c.s_bias[HB + f];
+    }
+  } else if (c.hh == 0) {
+    a.val_out[row] = acc[0] + c.s_bias[HB];
+  }
+}
+
 template <class S, int SEG>
 __device__ __forceinline__ void run_segment(Ctx<S>& c, const ChainArgs& a) {
-  if constexpr (SEG < S::nseg()) {
+  if constexpr (SEG < n_run<S>()) {
     using G = Seg<S, SEG>;
     const uint4* wseg = seg_weights<S, SEG>(c);
     if constexpr (!G::bwd && !G::head) {
@@ -442,8 +474,10 @@ __device__ __forceinline__ void run_segment(Ctx<S>& c, const ChainArgs& a) {
     __syncthreads();                       // every wave is done with the layer's input
     // this lane's loss inputs: cold loads, issued where a long stretch of arithmetic follows and no younger load is
     // waited for (the memory counter is in order)
-    if constexpr (SEG == (S::NL >= 3 ? S::NL - 3 : 0)) fetch_loss_inputs<S>(c, a);
-    if constexpr (G::head) {
+    if constexpr (!S::fwd && SEG == (S::NL >= 3 ? S::NL - 3 : 0)) fetch_loss_inputs<S>(c, a);
+    if constexpr (G::head && S::fwd) {
+      head_outputs<S>(c, a, c.acc[0][0]);
+    } else if constexpr (G::head) {
       loss_epilogue<S>(c, a, c.acc[0][0]);
     } else {
       tile_epilogue<S, SEG, 0>(c, a);
@@ -472,7 +506,7 @@ __global__ __launch_bounds__(kWaves * 64) void train_tile_kernel(ChainArgs a) {
   c.wave = __builtin_amdgcn_readfirstlane(c.tid >> 6);
   c.s = c.lane & 31;
   c.hh = c.lane >> 5;
-  c.net = blockIdx.y;
+  c.net = S::fwd ? (int)blockIdx.y + a.net0 : (int)blockIdx.y;
   c.row0 = blockIdx.x * kRows;
   c.X = reinterpret_cast<uint4*>(smem_raw);
   float* s_bias = reinterpret_cast<float*>(smem_raw + S::x_bytes());
@@ -497,7 +531,7 @@ __global__ __launch_bounds__(kWaves * 64) void train_tile_kernel(ChainArgs a) {
     c.s_red[kWaves * 40 + c.tid] = ls;
     c.s_red[kWaves * 40 + 32 + c.tid] = c.tid < a.act_dim ? expf(-ls) : 0.f;
   }
-  {
+  if constexpr (!S::fwd) {
     // this lane's sample of the head layer (rows past the batch take the last sample; their results are dropped)
     const int row = c.row0 + 32 * c.wave + c.s;
     const int rc = row < a.rows ? row : a.rows - 1;
@@ -564,7 +598,7 @@ __global__ __launch_bounds__(kWaves * 64) void train_tile_kernel(ChainArgs a) {
         if (j < NP) {
           const int w = ((j >> 1) * 4 + (r >> 5)) * 64 + (r & 31) + 32 * (j & 1);
           c.X[w] = v[gi][it];
-          if (c.net == 0) xb[w] = v[gi][it];      // arrays hold whole tiles
+          if (!S::fwd && c.net == 0) xb[w] = v[gi][it];      // arrays hold whole tiles
         }
       }
     }
@@ -589,15 +623,15 @@ int launch_shape(gmi_instance* g, const ChainArgs& a, int rows, int* tiles_out, 
   const size_t lds = S::lds_bytes();
   const int tiles = (rows + kRows - 1) / kRows;
   *tiles_out = tiles;
-  if (tiles > gmi::kLossBlocksMax) return GMI_ERR_UNSUPPORTED;      // one statistics row per tile
+  if (!S::fwd && tiles > gmi::kLossBlocksMax) return GMI_ERR_UNSUPPORTED;      // one statistics row per tile
   if (a.x0_ready == 0 && (a.obs_dim % 4 != 0 || a.obs_dim < 4)) return GMI_ERR_UNSUPPORTED;
   if (!attr) {
     GMI_HIP(hipFuncSetAttribute((const void*)train_tile_kernel<S>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr = true;
   }
-  gmi::ProfScope ps(g, gmi::kClsChainTrain);
+  gmi::ProfScope ps(g, S::fwd ? gmi::kClsFusedAgent : gmi::kClsChainTrain);
   ps.work(flops, bytes);
-  ps.launch(train_tile_kernel<S>, dim3(tiles, 2), dim3(kWaves * 64), lds, a);
+  ps.launch(train_tile_kernel<S>, dim3(tiles, S::fwd ? 2 - a.net0 : 2), dim3(kWaves * 64), lds, a);
   GMI_LAUNCH_CHECK();
   return GMI_OK;
 }
@@ -609,10 +643,22 @@ namespace gmi {
 // parts (chain_kernel.h): GMI_ERR_UNSUPPORTED if the model has another shape; rows == 0 only asks (the answer: the
 // stream's group size 4, plus 256 for the gather from the bf16 copy of all observations).
 constexpr int kTileParts = 2;
+constexpr int kTileFwdParts = 2;
 #define GMI_TILE_PART_DECL(k)                                                                              \
   int launch_tile_part##k(gmi_instance* g, const ModelLayout& L, const gmi_chain::ChainArgs& a, int rows, \
                           int* tiles_out, double flops, double bytes)
 GMI_TILE_PART_DECL(0); GMI_TILE_PART_DECL(1);
+#define GMI_TILE_FWD_PART_DECL(k)                                                                              \
+  int launch_tile_fwd_part##k(gmi_instance* g, const ModelLayout& L, const gmi_chain::ChainArgs& a, int rows, \
+                              int* tiles_out, double flops, double bytes)
+GMI_TILE_FWD_PART_DECL(0); GMI_TILE_FWD_PART_DECL(1);
+#define GMI_TILE_FWD_PART_DEFINE(k, ...)                                                          \
+  GMI_TILE_FWD_PART_DECL(k) {                                                                     \
+    using S = gmi_tile::TileShapeFwd<__VA_ARGS__>;                                                \
+    if (!gmi_tile::shape_matches<S>(L)) return GMI_ERR_UNSUPPORTED;                               \
+    if (rows == 0) { *tiles_out = 4; return GMI_OK; }                                             \
+    return gmi_tile::launch_shape<S>(g, a, rows, tiles_out, flops, bytes);                        \
+  }
 #define GMI_TILE_PART_DEFINE(k, ...)                                                              \
   GMI_TILE_PART_DECL(k) {                                                                         \
     using S = gmi_tile::TileShape<__VA_ARGS__>;                                                   \
