@@ -234,9 +234,11 @@ int collect_experience(gmi_t gmi, gmi_buffer_t buf, int32_t t, const float* obs,
  * launch: each workgroup keeps its envs' state on chip for all T steps.
  *  obs dev [N,O]: in = obs_0, out = obs_T (updated in place); last_value dev [N] out;
  *  seed / env_offset: the agent's (as in agent_act); the simulator uses its binding's own.
- *  The env's episode_step array advances by T steps.  BF16 models only, whose (padded) bf16 weights total
- *  at most 1 MiB and whose 32-env tile fits the on-chip memory: otherwise GMI_ERR_UNSUPPORTED and nothing has run
- *  (use the per-step calls, which are the faster path for larger models). */
+ *  The env's episode_step array advances by T steps.  BF16 models only.  One launch for models whose (padded) bf16
+ *  weights total at most 1 MiB and whose 32-env tile fits the on-chip memory; larger models that have a forward-only
+ *  kernel of their own (the 512-wide shapes) and T >= 2 take two launches per step (that kernel, then one env-step
+ *  launch that also decides the actions and stores the experience; obs_t passes through slot t of the buffer);
+ *  otherwise GMI_ERR_UNSUPPORTED and nothing has run (use the per-step calls). */
 int rollout_collect(gmi_t gmi, gmi_model_t model, gmi_env_t env, gmi_buffer_t buf, float* obs,
                     uint64_t seed, uint32_t step0, uint32_t env_offset, float* last_value);
 

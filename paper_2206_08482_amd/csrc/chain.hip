@@ -238,9 +238,14 @@ int launch_train_chain(gmi_instance* g, gmi_model* m, gmi_buffer* b, const gmi_p
   return GMI_OK;
 }
 
+bool forward_chain_reads_x0(const gmi_model* m, const float* obs) {
+  return !(m->L.obs_dim % 4 == 0 && ((uintptr_t)obs & 15) == 0);
+}
+
 // Inference through the forward-only row-tile kernel (agent_act / agent_value of the models too large for the fused
 // agent kernel): the same stream, the same products in the same order as the trainer's forward pass.
-int launch_forward_chain(gmi_instance* g, gmi_model* m, const float* obs, int n_rows, float* mu, float* val) {
+int launch_forward_chain(gmi_instance* g, gmi_model* m, const float* obs, int n_rows, float* mu, float* val,
+                         bool x0_valid) {
   const ModelLayout& L = m->L;
   if (L.dtype != GMI_DTYPE_BF16 || L.sh_chain_bytes == 0 || L.act_dim > 32) return GMI_ERR_UNSUPPORTED;
   if (n_rows < 1 || n_rows > m->max_rows) return GMI_ERR_UNSUPPORTED;
@@ -257,11 +262,11 @@ int launch_forward_chain(gmi_instance* g, gmi_model* m, const float* obs, int n_
   a.idx = nullptr;
   a.b_obs = obs;
   a.n_envs = n_rows; a.ld_envs = n_rows; a.obs_dim = L.obs_dim;
-  a.x0_ready = (L.obs_dim % 4 == 0 && ((uintptr_t)obs & 15) == 0) ? 0 : 1;
+  a.x0_ready = forward_chain_reads_x0(m, obs) ? 1 : 0;
   a.rows = n_rows; a.act_dim = L.act_dim;
   a.net0 = mu ? 0 : 1;
   a.mu_out = mu; a.val_out = val;
-  if (a.x0_ready) {
+  if (a.x0_ready && !x0_valid) {
     rc = launch_gather(g, m, obs, n_rows, n_rows, nullptr, n_rows, nullptr);
     if (rc != GMI_OK) return rc;
   }

@@ -1156,6 +1156,11 @@ extern "C" int rollout_collect(gmi_t g, gmi_model_t m, gmi_env_t env, gmi_buffer
   // as for the fused agent kernel: every tile streams all weights from L2 at every step, which loses to the
   // per-layer large-tile kernels beyond ~1 MB of bf16 weights (measured on a [512,512,256,128] model with
   // 16384 envs and 16 steps: 4.1 ms in one launch against 3.3 ms step by step)
+  if (L.weight_bytes > (1 << 20)) {
+    // ... where the model has a forward-only kernel of its own, the stage is two launches per step instead
+    const int rc = gmi::rollout_stepwise(g, m, env, b, obs, seed, step0, env_offset, last_value);
+    if (rc != GMI_ERR_UNSUPPORTED) return rc;
+  }
   if (L.weight_bytes > (1 << 20))
     GMI_FAIL(GMI_ERR_UNSUPPORTED, "rollout_collect: model too large for the one-launch kernel (%lld bytes of bf16 "
              "weights, limit %d); use agent_act / env_step / collect_experience", (long long)L.weight_bytes, 1 << 20);

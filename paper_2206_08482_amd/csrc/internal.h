@@ -300,7 +300,30 @@ struct ChainEmit {
 void fill_chain_emit(const ModelLayout& L, ChainEmit* ce);
 // Forward pass of n_rows observation rows through the forward-only row-tile kernel: policy means into mu (NULL: value
 // net only) and values into val.  GMI_ERR_UNSUPPORTED (no message) if no such kernel is compiled for the shape.
-int launch_forward_chain(gmi_instance* g, gmi_model* m, const float* obs, int n_rows, float* mu, float* val);
+int launch_forward_chain(gmi_instance* g, gmi_model* m, const float* obs, int n_rows, float* mu, float* val,
+                         bool x0_valid = false);
+// Whether that kernel would read the bf16 rows m->x0 (made by the gather kernel) instead of obs itself.
+bool forward_chain_reads_x0(const gmi_model* m, const float* obs);
+// The collection stage for the models too large for the one-launch rollout kernel: per step the forward-only kernel
+// and one env-step launch that also decides the actions and stores the experience (model.hip).
+int rollout_stepwise(gmi_instance* g, gmi_model* m, gmi_env* env, gmi_buffer* b, float* obs, uint64_t seed,
+                     uint32_t step0, uint32_t env_offset, float* last_value);
+// What the collection stage of a model too large for the one-launch rollout kernel adds to an env step: the action
+// decision from the policy means of the step, the experience store of the step, the bf16 rows of the next state.
+struct StepFuse {
+  const float* mu;            // [N, A] policy means of this step
+  const float* log_std;       // [A]
+  uint32_t ak0, ak1, a_env_offset;      // the agent's Philox key and env offset (the simulator has its own)
+  float* b_obs;               // slot t of the experience arrays: obs [N, O] (NULL: the slot already holds this state),
+  float* b_act;               // act [N, A],
+  float* b_logp;              // logp [N]
+  uint16_t* x16_next;         // bf16 rows [N, o_pad] of the next state, or NULL
+  int o_pad;
+};
+// env_step's launch; fuse != NULL: act is not read (the actions are decided in the kernel), reward and done point
+// into slot t of the experience arrays.
+int launch_env_step(gmi_instance* g, gmi_env* env, const float* obs, const float* act, uint32_t step, float* next_obs,
+                    float* reward, uint8_t* done, const StepFuse* fuse);
 // The action decision from given means: act = mu + exp(log_std) * eps, logp, optional copy of mu (model.hip).
 int launch_sample(gmi_instance* g, const float* mu, const float* log_std, int n_rows, int act_dim, uint64_t seed,
                   uint32_t step, uint32_t env_offset, float* act, float* logp, float* mu_out);

@@ -191,6 +191,37 @@ int launch_sample(gmi_instance* g, const float* mu, const float* log_std, int n_
   return GMI_OK;
 }
 
+int rollout_stepwise(gmi_instance* g, gmi_model* m, gmi_env* env, gmi_buffer* b, float* obs, uint64_t seed,
+                     uint32_t step0, uint32_t env_offset, float* last_value) {
+  const ModelLayout& L = m->L;
+  const gmi_buffer_desc& bd = b->d;
+  const int n = bd.n_envs, T = bd.horizon, O = L.obs_dim, A = L.act_dim;
+  // obs_t lives in slot t of the experience arrays (step t - 1 writes its next state there), obs_T in the caller's
+  // array; with a horizon of one the step would read and write the caller's array
+  if (T < 2 || n > m->max_rows || !g->fusion) return GMI_ERR_UNSUPPORTED;
+  const int64_t ld = bd.ld_envs;
+  const int o_pad = gmi::pad32(O);
+  for (int t = 0; t < T; ++t) {
+    const float* cur = t == 0 ? obs : bd.obs + (int64_t)t * ld * O;
+    float* nxt = t == T - 1 ? obs : bd.obs + (int64_t)(t + 1) * ld * O;
+    // policy means into the model's workspace, values straight into slot t
+    int rc = launch_forward_chain(g, m, cur, n, m->mu, bd.val + t * ld, t > 0 && forward_chain_reads_x0(m, cur));
+    if (rc != GMI_OK) return rc;      // before anything has run if this model has no forward-only kernel (t == 0)
+    StepFuse fu;
+    fu.mu = m->mu;
+    fu.log_std = reinterpret_cast<const float*>(m->shadow + L.sh_logstd);
+    fu.ak0 = (uint32_t)seed; fu.ak1 = (uint32_t)(seed >> 32); fu.a_env_offset = env_offset;
+    fu.b_obs = t == 0 ? bd.obs : nullptr;
+    fu.b_act = bd.act + (int64_t)t * ld * A;
+    fu.b_logp = bd.logp + t * ld;
+    fu.x16_next = forward_chain_reads_x0(m, nxt) ? reinterpret_cast<uint16_t*>(m->x0) : nullptr;
+    fu.o_pad = o_pad;
+    rc = launch_env_step(g, env, cur, nullptr, step0 + (uint32_t)t, nxt, bd.rew + t * ld, bd.done + t * ld, &fu);
+    if (rc != GMI_OK) return rc;
+  }
+  return launch_forward_chain(g, m, obs, n, nullptr, last_value, forward_chain_reads_x0(m, obs));
+}
+
 int launch_gather(gmi_instance* g, gmi_model* m, const float* obs, int n_envs, int ld_envs,
                   const int32_t* idx, int rows, const gmi_buffer_desc* ex) {
   return launch_gather_to(g, m, obs, n_envs, ld_envs, idx, rows, ex, m->x0);
