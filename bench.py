@@ -31,8 +31,8 @@ PEAK_FP32_TFLOPS = 157.3       # vector fp32
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/hbm_traffic_C2_C4.md (counter values
 # scaled by what the same counters read for a copy kernel of known size).  Keyed by (workload, class).
 MEASURED_TRAFFIC = {
-    ("C2", "chain_train"): 209.18e6, ("C2", "wgrad"): 163.68e6, ("C2", "fused_rollout"): 36.40e6,
-    ("C4", "chain_train"): 669.46e6, ("C4", "wgrad"): 687.40e6, ("C4", "adam"): 104.91e6,
+    ("C2", "chain_train"): 209.18e6, ("C2", "wgrad"): 163.62e6, ("C2", "fused_rollout"): 36.40e6,
+    ("C4", "chain_train"): 669.47e6, ("C4", "wgrad"): 689.71e6, ("C4", "adam"): 104.91e6,
 }
 
 
