@@ -12,7 +12,7 @@ import torch
 from oracle import bf16model as bm
 from oracle import ppo as oppo
 from workloads import synthetic as syn
-from gpu_util import rel_l2, rel_max
+from gpu_util import make_session, oracle_pieces, rel_l2, rel_max
 from test_gpu_parity import _bind_buffer, _bind_model, _filled_buffer, dev, zeros, g, inst, _keep_device_inputs_alive  # noqa: F401
 
 pytestmark = pytest.mark.gpu
@@ -141,4 +141,35 @@ def test_whole_iteration_c2_at_benchmark_size(g):
     step, ref_step = ses.theta.cpu().numpy() - theta, ref["theta"] - theta
     assert np.abs(ref_step).max() > 1e-4
     assert rel_l2(ses.theta.cpu().numpy(), ref["theta"]) <= 1e-3
+    ses.close()
+
+
+@pytest.mark.parametrize("name", ["C4", "C3"])
+def test_collection_at_benchmark_size_on_sampled_envs(g, name):
+    """The collection stage of a benchmark workload at its full size (C4: 16384 envs x 16 steps through the
+    two-launches-per-step form of rollout_collect; C3: 4096 envs x 32 steps in one launch), in the launch
+    configuration bench.py times.  Envs are independent and the generator's counters carry the env index, so the
+    oracle computes blocks of 192 envs from three places of the range (first tile, a ragged middle, the last envs)
+    with env_offset = the block's first env, and every array of the buffer is compared on those columns."""
+    cfg = syn.get_config(name)
+    shape, theta, env, state0, hp = oracle_pieces(cfg)
+    ses = make_session(cfg, theta, env, state0, fused_rollout=True)
+    ses.rollout(0)
+    ses.sync()
+    assert ses.fused_rollout
+    got = ses.buf.to_numpy()
+    last = ses.last_value.cpu().numpy()
+    final = ses.state().cpu().numpy()
+    n, T, blk = cfg.n_envs, cfg.horizon, 192
+    for k0 in (0, n // 2 - 77, n - blk):
+        buf = oppo.new_buffer(T, blk, cfg.obs_dim, cfg.act_dim)
+        st, ep, lv = oppo.rollout(theta, shape, env, state0[k0:k0 + blk], np.zeros(blk, np.uint32), buf, env.seed, 0,
+                                  env_offset=k0)
+        sl = slice(k0, k0 + blk)
+        assert np.array_equal(got["done"][:, sl], buf["done"]), k0
+        for key in ("obs", "act", "val", "rew"):
+            assert rel_l2(got[key][:, sl], buf[key]) <= TOL16, (k0, key, rel_l2(got[key][:, sl], buf[key]))
+            assert rel_max(got[key][:, sl], buf[key]) <= TOL16, (k0, key, rel_max(got[key][:, sl], buf[key]))
+        assert rel_l2(got["logp"][:, sl], buf["logp"]) <= 1e-5
+        assert rel_l2(last[sl], lv) <= TOL16 and rel_l2(final[sl], st) <= TOL16
     ses.close()
