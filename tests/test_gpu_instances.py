@@ -173,7 +173,7 @@ def test_pipelined_schedule_bf16_matches_oracle_replay(host_ordered):
         step, ref_step = got_th - theta, th[k + 1] - theta
         assert rel_l2(step, ref_step) <= 0.25, (k, rel_l2(step, ref_step))
         if k == 1:
-            # round 2 was collected with theta_1; a rollout under theta_0 or theta_2 is NOT what the buffer holds
+            # collection round k + 1 = 2 used theta_1; a rollout under theta_0 or theta_2 is NOT what the buffer holds
             st, ep = [s.copy() for s in ora.states], [e.copy() for e in ora.eps]
             for wrong in (th[0], th[2]):
                 probe = _OracleAgents(shape, envs, states, n_envs, horizon, cfg)
