@@ -8,8 +8,9 @@ A "step" is one whole PPO iteration over one batch of synthetic experience: T ro
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C4] [--no-cpu-baseline] [--no-extras]
 
 The default run also reports, as extra keys of the same line, the step times of the other single-instance
-workloads, the agent/trainer CU-split sweep of the multi-instance configuration (benchmarks/instances.py) and the
-bandwidth-bound kernels on scaled inputs (benchmarks/kernels.py).
+workloads, the agent/trainer CU-split sweep of the multi-instance configuration (benchmarks/instances.py), its
+asynchronous serving / training rates (benchmarks/async_rates.py), the bandwidth-bound kernels on scaled inputs
+(benchmarks/kernels.py) and the fp8 agents against the bf16 ones (benchmarks/inference_precision.py).
 """
 from __future__ import annotations
 
@@ -226,7 +227,8 @@ def main() -> int:
                     help="C4 (default): the largest single-instance workload, the one the matrix-core target is set on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
-                    help="skip the other workloads, the instance-split sweep and the scaled bandwidth kernels")
+                    help="skip the other workloads, the instance-split sweep, the asynchronous rates, the scaled bandwidth "
+                         "kernels and the fp8 agents")
     ap.add_argument("--fusion", type=int, default=None,
                     help="fusion level of the instance (0 per-layer kernels only, 1 fused agent/rollout and trainer "
                          "kernels); default: the library's")
@@ -305,31 +307,64 @@ def main() -> int:
     }
     if not args.no_extras:
         # the other single-instance workloads (fewer steps), the instance-split sweep of the multi-instance
-        # configuration and the bandwidth-bound kernels on inputs large enough for HBM to bound them
-        others = {}
-        for name in ("C2", "C3", "C4"):
-            if name == cfg.name:
-                continue
-            o = run_workload(g, torch, syn, PPOSession, name, max(5, args.steps // 2), 2, args.fusion, detail=False)
-            n = max(5, args.steps // 2)
-            others[name] = {"ms_per_step": o["seconds"] * 1e3 / n, "samples_per_s": n * o["cfg"].batch / o["seconds"],
-                            "env_steps_per_s": o["env_steps_per_s"]}
-        out["other_workloads"] = others
-        from benchmarks import instances as binst, kernels as bker
-        sw = binst.sweep("C5", steps=4, warmup=2, full=False)
-        out["c5_split_sweep"] = {
-            "workload": sw["workload"], "single_stream_ms": sw["rows"][0]["ms_per_iteration"],
-            "best": sw["best"], "best_vs_single_stream": sw["best_vs_single_stream"],
-            "rows": [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in row.items()
-                      if k in ("layout", "schedule", "hand_off", "ms_per_iteration", "vs_single_stream")}
-                     for row in sw["rows"]]}
-        bk = bker.measure(large_only=True)
-        out["bandwidth_kernels_scaled"] = {
-            "copy_kernel_GBs": bk["copy_kernel_GBs"],
-            "rows": [{"kernel": row["kernel"], "size": row["size"], "GBs": round(row["GBs"], 1),
-                      "frac_of_hbm_peak": round(row["frac_of_hbm_peak"], 4),
-                      **({"fp32_TFLOPs": round(row["fp32_TFLOPs"], 2)} if "fp32_TFLOPs" in row else {})}
-                     for row in bk["rows"]]}
+        # configuration, its asynchronous rates, the bandwidth-bound kernels on inputs large enough for HBM to bound
+        # them, and the fp8 agents against the bf16 ones.  A failure in one of them is recorded under its key and
+        # does not cost the line.
+        def extra(key, fn):
+            try:
+                out[key] = fn()
+            except Exception as e:      # noqa: BLE001
+                out[key] = {"error": f"{type(e).__name__}: {e}"}
+
+        def others():
+            res = {}
+            for name in ("C2", "C3", "C4"):
+                if name == cfg.name:
+                    continue
+                n = max(5, args.steps // 2)
+                o = run_workload(g, torch, syn, PPOSession, name, n, 2, args.fusion, detail=False)
+                res[name] = {"ms_per_step": o["seconds"] * 1e3 / n, "samples_per_s": n * o["cfg"].batch / o["seconds"],
+                             "env_steps_per_s": o["env_steps_per_s"]}
+            return res
+
+        def split_sweep():
+            from benchmarks import instances as binst
+            sw = binst.sweep("C5", steps=4, warmup=2, full=False)
+            return {"workload": sw["workload"], "single_stream_ms": sw["rows"][0]["ms_per_iteration"],
+                    "best": sw["best"], "best_vs_single_stream": sw["best_vs_single_stream"],
+                    "rows": [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in row.items()
+                              if k in ("layout", "schedule", "hand_off", "ms_per_iteration", "vs_single_stream")}
+                             for row in sw["rows"]]}
+
+        def async_rates():
+            from benchmarks import async_rates as basy
+            r = basy.measure("C5", updates=4)
+            return {"workload": r["workload"],
+                    "rows": [{"layout": row["layout"], "pps_env_steps_per_s": round(row["pps_env_steps_per_s"]),
+                              "ttop_samples_per_s": round(row["ttop_samples_per_s"]),
+                              "slabs_discarded": row["slabs_discarded"],
+                              "mean_staleness_updates": round(row["mean_staleness_updates"], 2)} for row in r["rows"]]}
+
+        def scaled_kernels():
+            from benchmarks import kernels as bker
+            bk = bker.measure(large_only=True)
+            return {"copy_kernel_GBs": bk["copy_kernel_GBs"],
+                    "rows": [{"kernel": row["kernel"], "size": row["size"], "GBs": round(row["GBs"], 1),
+                              "frac_of_hbm_peak": round(row["frac_of_hbm_peak"], 4),
+                              **({"fp32_TFLOPs": round(row["fp32_TFLOPs"], 2)} if "fp32_TFLOPs" in row else {})}
+                             for row in bk["rows"]]}
+
+        def fp8_agents():
+            from benchmarks import inference_precision as binf
+            r = binf.measure(reps=20)
+            return [{"model": row["model"], "envs": row["envs"], "bf16_us": round(row["bf16_us"], 1),
+                     "fp8_us": round(row["fp8_us"], 1), "fp8_speedup": round(row["fp8_speedup"], 2)} for row in r["rows"]]
+
+        extra("other_workloads", others)
+        extra("c5_split_sweep", split_sweep)
+        extra("c5_async_rates", async_rates)
+        extra("bandwidth_kernels_scaled", scaled_kernels)
+        extra("fp8_agents_vs_bf16", fp8_agents)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
